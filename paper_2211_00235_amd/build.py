@@ -1,0 +1,27 @@
+"""Build the HIP library in-tree for gfx950 (hipcc cross-compiles without a GPU)."""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libpe_mi355x.so")
+SOURCES = ["pe_block.hip"]
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wno-pass-failed", "-Wno-unused-result"]
+
+
+def build(verbose=False):
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc] + FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if verbose or res.returncode:
+        lines = [l for l in (res.stdout + res.stderr).splitlines() if "packed-fp32-ops" not in l]
+        print("\n".join(lines))
+    if res.returncode:
+        raise RuntimeError("hipcc failed building %s" % LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

@@ -1,0 +1,443 @@
+// Gated multi-head attention with optional pair bias and key mask: forward and backward.
+//
+// Used four ways by the block: MSA row attention (bias from the pair representation),
+// MSA column attention (no bias, strided sequence axis), triangle attention around the
+// starting node and around the ending node (strided axes + transposed bias).
+//
+// Data layout: q, k, v and the gate pre-activation live in one tensor `qkvg` of rows
+// [4][H][d]; element (batch b, position p, which w, head h, channel c) is at
+//   qkvg + b*batch_stride + p*seq_stride + w*H*d + h*d + c.
+// The outputs o / og / do use rows [H][d] with strides batch_stride/4, seq_stride/4.
+//
+// Kernel design (gfx950): every wave owns 32 queries (or 32 keys in the dK/dV kernel) and
+// computes TRANSPOSED score tiles S^T = K Q^T with v_mfma 32x32, so that a query is a
+// lane (column) and its keys are spread over the lane's 16 accumulator elements and the
+// partner lane (lane ^ 32).  Row max / row sum then need one cross-lane exchange, the
+// per-query softmax state is one scalar per lane, and the probability tile can be fed
+// straight back as an MFMA operand (the contraction index is permuted consistently on
+// both operands; the other operand is read from a transposed LDS copy of V / K / Q / dO).
+// Online softmax over key tiles of 64; K row-major and V transposed are staged in LDS.
+#pragma once
+#include "pe_common.h"
+
+struct AttnArgs {
+  const void* qkvg; long long batch_stride, seq_stride;
+  int B, L, H, d;
+  const float* bias;                 // [H][L][L] (query, key) or nullptr
+  const float* mask; long long mask_bs, mask_ks;   // key mask value at mask[b*mask_bs + j*mask_ks]
+  void* o; void* og;                 // forward outputs (o ungated, og = sigmoid(g) * o)
+  float* lse;                        // [B][H][L]
+  float scale;                       // 1/sqrt(d)
+  // backward
+  const void* dog;                   // cotangent of og
+  void* dO;                          // scratch: cotangent of o (written by pre kernel)
+  float* D;                          // [B][H][L] rowsum(dO * o)
+  void* dqkvg;                       // same layout as qkvg
+  void* dS;                          // [B][H][L][L] storage type, written when bias != nullptr
+};
+
+template <typename T> struct AttnCfg {
+  static constexpr int VEC = Vec16<T>::N;
+  static constexpr int KT = 64;                                   // positions staged per iteration
+  static constexpr int RM = (sizeof(T) == 2) ? 40 : 36;           // row-major LDS row stride (elements), d padded <= 32
+  static constexpr int TS = KT + 4;                               // transposed LDS row stride
+};
+
+PE_DEV int round_up_i(int a, int b) { return (a + b - 1) / b * b; }
+
+// Stage `KT` rows (positions pos0..pos0+KT-1) of one [d]-vector per row into LDS, as a
+// row-major copy (stride RM, columns d..DP-1 zero filled) and/or a transposed copy
+// (rows = channel, stride TS).  Rows beyond L are zero.
+template <typename T>
+PE_DEV void attn_stage(const T* src /* at (b, 0, w, h, 0) */, long long seq_stride, int pos0, int L, int d, int DP,
+                       T* lds_rm, T* lds_t, int tid, int nthreads) {
+  typedef AttnCfg<T> C;
+  typedef typename Vec16<T>::type V;
+  const int vpr = DP / C::VEC;
+  for (int idx = tid; idx < C::KT * vpr; idx += nthreads) {
+    int row = idx / vpr, dd0 = (idx % vpr) * C::VEC;
+    V v;
+#pragma unroll
+    for (int e = 0; e < C::VEC; e++) v[e] = from_f<T>(0.0f);
+    int pos = pos0 + row;
+    if (pos < L && dd0 < d) v = *reinterpret_cast<const V*>(src + (long long)pos * seq_stride + dd0);
+    if (lds_rm) *reinterpret_cast<V*>(lds_rm + row * C::RM + dd0) = v;
+    if (lds_t) {
+#pragma unroll
+      for (int e = 0; e < C::VEC; e++) lds_t[(dd0 + e) * C::TS + row] = v[e];
+    }
+  }
+}
+
+// accumulator elements [u*KP, u*KP+KP) of a 32x32 tile as an MFMA operand fragment
+template <typename T> PE_DEV typename Mma<T>::frag acc_to_frag(const f32x16& acc, int u);
+template <> PE_DEV Mma<bf16>::frag acc_to_frag<bf16>(const f32x16& acc, int u) {
+  bf16x8 f;
+#pragma unroll
+  for (int t = 0; t < 8; t++) f[t] = (bf16)acc[u * 8 + t];
+  return f;
+}
+template <> PE_DEV Mma<float>::frag acc_to_frag<float>(const f32x16& acc, int u) { return acc[u]; }
+
+// matching fragment of the other operand from a transposed LDS tile: row pointer `rowp`
+// points at element [row = lane%32][tile_base]; contraction slots follow acc_row(g, a).
+template <typename T> PE_DEV typename Mma<T>::frag lds_tfrag(const T* rowp, int g, int u);
+template <> PE_DEV Mma<bf16>::frag lds_tfrag<bf16>(const bf16* rowp, int g, int u) {
+  bf16x4 lo = *reinterpret_cast<const bf16x4*>(rowp + 16 * u + 4 * g);
+  bf16x4 hi = *reinterpret_cast<const bf16x4*>(rowp + 16 * u + 8 + 4 * g);
+  bf16x8 f;
+  f[0] = lo[0]; f[1] = lo[1]; f[2] = lo[2]; f[3] = lo[3];
+  f[4] = hi[0]; f[5] = hi[1]; f[6] = hi[2]; f[7] = hi[3];
+  return f;
+}
+template <> PE_DEV Mma<float>::frag lds_tfrag<float>(const float* rowp, int g, int u) {
+  return rowp[8 * (u >> 2) + 4 * g + (u & 3)];
+}
+
+// operand fragment straight from global memory: row `p` (nullptr = out of range), channels
+// [kk*KSTEP + g*KP, +KP), zero beyond d
+template <typename T> PE_DEV typename Mma<T>::frag gl_frag(const T* p, int kk, int g, int d) {
+  typedef Mma<T> MM;
+  int c0 = kk * MM::KSTEP + g * MM::KP;
+  if (p == nullptr || c0 >= d) return MM::zero();
+  return MM::load(p + c0);
+}
+
+// ---------------------------------------------------------------------------
+// Forward
+// grid (ceil(L/128), H, B), 256 threads; wave w owns queries q0 = blockIdx.x*128 + 32*w
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
+  typedef AttnCfg<T> C;
+  typedef Mma<T> MM;
+  __shared__ __attribute__((aligned(16))) T lds_k[C::KT * C::RM];
+  __shared__ __attribute__((aligned(16))) T lds_vt[32 * C::TS];
+  __shared__ float lds_mask[C::KT];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int L = a.L, d = a.d, HD = a.H * a.d;
+  const int DP = round_up_i(d, MM::KSTEP);
+  const int NKK = DP / MM::KSTEP;
+  const int qi = blockIdx.x * 128 + wave * 32 + l32;       // this lane's query
+  const bool qok = qi < L;
+  const T* base = (const T*)a.qkvg + (long long)b * a.batch_stride + h * d;
+  const T* qrow = qok ? base + (long long)qi * a.seq_stride : nullptr;
+
+  constexpr int MAXKK = 32 / MM::KSTEP;   // 2 (bf16) or 16 (fp32): d <= 32
+  typename MM::frag qf[MAXKK];
+#pragma unroll
+  for (int kk = 0; kk < MAXKK; kk++)
+    if (kk < NKK) qf[kk] = gl_frag<T>(qrow, kk, g, d);
+
+  f32x16 oacc;
+#pragma unroll
+  for (int e = 0; e < 16; e++) oacc[e] = 0.0f;
+  float m_run = -INFINITY, l_run = 0.0f;
+  const float* brow = (a.bias && qok) ? a.bias + ((long long)h * L + qi) * L : nullptr;
+
+  for (int j0 = 0; j0 < L; j0 += C::KT) {
+    __syncthreads();
+    attn_stage<T>(base + HD, a.seq_stride, j0, L, d, DP, lds_k, (T*)nullptr, tid, 256);
+    attn_stage<T>(base + 2 * HD, a.seq_stride, j0, L, d, DP, (T*)nullptr, lds_vt, tid, 256);
+    if (tid < C::KT) {
+      int j = j0 + tid;
+      lds_mask[tid] = (j < L) ? a.mask[(long long)b * a.mask_bs + (long long)j * a.mask_ks] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int jt = 0; jt < C::KT / 32; jt++) {
+      if (j0 + jt * 32 >= L) break;
+      f32x16 sacc;
+#pragma unroll
+      for (int e = 0; e < 16; e++) sacc[e] = 0.0f;
+#pragma unroll
+      for (int kk = 0; kk < MAXKK; kk++)
+        if (kk < NKK) {
+          typename MM::frag kf = MM::load(lds_k + (jt * 32 + l32) * C::RM + kk * MM::KSTEP + g * MM::KP);
+          MM::mma(sacc, kf, qf[kk]);
+        }
+      // logits for (query = lane, keys = acc rows)
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        int jj = jt * 32 + acc_row(g, e);
+        float v = sacc[e] * a.scale;
+        if (brow) v += (j0 + jj < L) ? brow[j0 + jj] : 0.0f;
+        v = (lds_mask[jj] > 0.0f) ? v : -INFINITY;
+        sacc[e] = v;
+        tmax = fmaxf(tmax, v);
+      }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+      float m_new = fmaxf(m_run, tmax);
+      float m_use = (m_new == -INFINITY) ? 0.0f : m_new;
+      float corr = __expf(m_run - m_use);     // m_run = -inf -> 0
+      float psum = 0.0f;
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        float p = __expf(sacc[e] - m_use);
+        sacc[e] = p;
+        psum += p;
+      }
+      psum += __shfl_xor(psum, 32, 64);
+      l_run = l_run * corr + psum;
+      m_run = m_new;
+#pragma unroll
+      for (int e = 0; e < 16; e++) oacc[e] *= corr;
+      // O^T[dd, i] += sum_j V^T[dd, j] P^T[j, i]
+      const T* vrow = lds_vt + l32 * C::TS + jt * 32;
+#pragma unroll
+      for (int u = 0; u < 32 / MM::KSTEP; u++) {
+        typename MM::frag vf = lds_tfrag<T>(vrow, g, u);
+        typename MM::frag pf = acc_to_frag<T>(sacc, u);
+        MM::mma(oacc, vf, pf);
+      }
+    }
+  }
+  if (!qok) return;
+  float inv = (l_run > 0.0f) ? 1.0f / l_run : 0.0f;
+  if (g == 0) a.lse[((long long)b * a.H + h) * L + qi] = (l_run > 0.0f) ? (m_run + __logf(l_run)) : 0.0f;
+  const long long orow = (long long)b * (a.batch_stride / 4) + (long long)qi * (a.seq_stride / 4) + h * d;
+  T* po = (T*)a.o + orow;
+  T* pog = (T*)a.og + orow;
+  const T* pg = qrow + 3 * HD;
+#pragma unroll
+  for (int e = 0; e < 16; e++) {
+    int dd = acc_row(g, e);
+    if (dd < d) {
+      float ov = oacc[e] * inv;
+      po[dd] = from_f<T>(ov);
+      pog[dd] = from_f<T>(ov * sigmoidf_(to_f(pg[dd])));
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Backward, step 0: dO = dog * sigmoid(g); dg = dog * o * s(1-s) -> dqkvg gate slot;
+// D = sum_c dO * o.  One thread per (b, p, h).
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ void attn_bwd_pre_kernel(AttnArgs a) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  long long total = (long long)a.B * a.L * a.H;
+  if (idx >= total) return;
+  int h = idx % a.H;
+  long long t = idx / a.H;
+  int p = t % a.L;
+  int b = t / a.L;
+  const int d = a.d, HD = a.H * a.d;
+  long long qoff = (long long)b * a.batch_stride + (long long)p * a.seq_stride + 3 * HD + h * d;
+  long long ooff = (long long)b * (a.batch_stride / 4) + (long long)p * (a.seq_stride / 4) + h * d;
+  const T* pg = (const T*)a.qkvg + qoff;
+  const T* po = (const T*)a.o + ooff;
+  const T* pdog = (const T*)a.dog + ooff;
+  T* pdo = (T*)a.dO + ooff;
+  T* pdg = (T*)a.dqkvg + qoff;
+  float Dsum = 0.0f;
+  for (int c = 0; c < d; c++) {
+    float sg = sigmoidf_(to_f(pg[c]));
+    float ov = to_f(po[c]), dv = to_f(pdog[c]);
+    T dob = from_f<T>(dv * sg);
+    pdo[c] = dob;
+    pdg[c] = from_f<T>(dv * ov * sg * (1.0f - sg));
+    Dsum += to_f(dob) * ov;
+  }
+  a.D[((long long)b * a.H + h) * a.L + p] = Dsum;
+}
+
+// ---------------------------------------------------------------------------
+// Backward, dQ (+ dS for the bias gradient).  Same tiling as the forward kernel.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnArgs a) {
+  typedef AttnCfg<T> C;
+  typedef Mma<T> MM;
+  __shared__ __attribute__((aligned(16))) T lds_k[C::KT * C::RM];
+  __shared__ __attribute__((aligned(16))) T lds_kt[32 * C::TS];
+  __shared__ __attribute__((aligned(16))) T lds_v[C::KT * C::RM];
+  __shared__ float lds_mask[C::KT];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int L = a.L, d = a.d, HD = a.H * a.d;
+  const int DP = round_up_i(d, MM::KSTEP);
+  const int NKK = DP / MM::KSTEP;
+  const int qi = blockIdx.x * 128 + wave * 32 + l32;
+  const bool qok = qi < L;
+  const T* base = (const T*)a.qkvg + (long long)b * a.batch_stride + h * d;
+  const T* qrow = qok ? base + (long long)qi * a.seq_stride : nullptr;
+  const long long orow = (long long)b * (a.batch_stride / 4) + (long long)qi * (a.seq_stride / 4) + h * d;
+  const T* dorow = qok ? (const T*)a.dO + orow : nullptr;
+
+  constexpr int MAXKK = 32 / MM::KSTEP;
+  typename MM::frag qf[MAXKK], dof[MAXKK];
+#pragma unroll
+  for (int kk = 0; kk < MAXKK; kk++)
+    if (kk < NKK) {
+      qf[kk] = gl_frag<T>(qrow, kk, g, d);
+      dof[kk] = gl_frag<T>(dorow, kk, g, d);
+    }
+  const long long sidx = ((long long)b * a.H + h) * L + qi;
+  const float lse = qok ? a.lse[sidx] : 0.0f;
+  const float Di = qok ? a.D[sidx] : 0.0f;
+  const float* brow = (a.bias && qok) ? a.bias + ((long long)h * L + qi) * L : nullptr;
+  T* dsrow = (a.dS && qok) ? (T*)a.dS + (((long long)b * a.H + h) * L + qi) * L : nullptr;
+
+  f32x16 dq;
+#pragma unroll
+  for (int e = 0; e < 16; e++) dq[e] = 0.0f;
+
+  for (int j0 = 0; j0 < L; j0 += C::KT) {
+    __syncthreads();
+    attn_stage<T>(base + HD, a.seq_stride, j0, L, d, DP, lds_k, lds_kt, tid, 256);
+    attn_stage<T>(base + 2 * HD, a.seq_stride, j0, L, d, DP, lds_v, (T*)nullptr, tid, 256);
+    if (tid < C::KT) {
+      int j = j0 + tid;
+      lds_mask[tid] = (j < L) ? a.mask[(long long)b * a.mask_bs + (long long)j * a.mask_ks] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int jt = 0; jt < C::KT / 32; jt++) {
+      if (j0 + jt * 32 >= L) break;
+      f32x16 sacc, pacc;
+#pragma unroll
+      for (int e = 0; e < 16; e++) { sacc[e] = 0.0f; pacc[e] = 0.0f; }
+#pragma unroll
+      for (int kk = 0; kk < MAXKK; kk++)
+        if (kk < NKK) {
+          int off = (jt * 32 + l32) * C::RM + kk * MM::KSTEP + g * MM::KP;
+          MM::mma(sacc, MM::load(lds_k + off), qf[kk]);      // S^T = K Q^T
+          MM::mma(pacc, MM::load(lds_v + off), dof[kk]);     // dP^T = V dO^T
+        }
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        int jj = jt * 32 + acc_row(g, e);
+        float v = sacc[e] * a.scale;
+        if (brow) v += (j0 + jj < L) ? brow[j0 + jj] : 0.0f;
+        float p = (lds_mask[jj] > 0.0f) ? __expf(v - lse) : 0.0f;
+        float ds = p * (pacc[e] - Di);
+        sacc[e] = ds;
+        if (dsrow && j0 + jj < L) dsrow[j0 + jj] = from_f<T>(ds);
+      }
+      const T* krow = lds_kt + l32 * C::TS + jt * 32;
+#pragma unroll
+      for (int u = 0; u < 32 / MM::KSTEP; u++) MM::mma(dq, lds_tfrag<T>(krow, g, u), acc_to_frag<T>(sacc, u));
+    }
+  }
+  if (!qok) return;
+  T* pdq = (T*)a.dqkvg + (long long)b * a.batch_stride + (long long)qi * a.seq_stride + h * d;
+#pragma unroll
+  for (int e = 0; e < 16; e++) {
+    int dd = acc_row(g, e);
+    if (dd < d) pdq[dd] = from_f<T>(dq[e] * a.scale);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Backward, dK and dV.  Wave w owns keys k0 = blockIdx.x*128 + 32*w (a key is a lane);
+// loops over query tiles staged in LDS (row-major and transposed copies of Q and dO).
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
+  typedef AttnCfg<T> C;
+  typedef Mma<T> MM;
+  __shared__ __attribute__((aligned(16))) T lds_q[C::KT * C::RM];
+  __shared__ __attribute__((aligned(16))) T lds_qt[32 * C::TS];
+  __shared__ __attribute__((aligned(16))) T lds_do[C::KT * C::RM];
+  __shared__ __attribute__((aligned(16))) T lds_dot[32 * C::TS];
+  __shared__ float lds_lse[C::KT], lds_D[C::KT];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int L = a.L, d = a.d, HD = a.H * a.d;
+  const int DP = round_up_i(d, MM::KSTEP);
+  const int NKK = DP / MM::KSTEP;
+  const int kj = blockIdx.x * 128 + wave * 32 + l32;       // this lane's key
+  const bool kok = kj < L;
+  const T* base = (const T*)a.qkvg + (long long)b * a.batch_stride + h * d;
+  const T* krow = kok ? base + (long long)kj * a.seq_stride + HD : nullptr;
+  const T* vrow = kok ? base + (long long)kj * a.seq_stride + 2 * HD : nullptr;
+  const T* dobase = (const T*)a.dO + (long long)b * (a.batch_stride / 4) + h * d;
+
+  constexpr int MAXKK = 32 / MM::KSTEP;
+  typename MM::frag kf[MAXKK], vf[MAXKK];
+#pragma unroll
+  for (int kk = 0; kk < MAXKK; kk++)
+    if (kk < NKK) {
+      kf[kk] = gl_frag<T>(krow, kk, g, d);
+      vf[kk] = gl_frag<T>(vrow, kk, g, d);
+    }
+  const float mk = kok ? a.mask[(long long)b * a.mask_bs + (long long)kj * a.mask_ks] : 0.0f;
+  const float* bcol = (a.bias && kok) ? a.bias + (long long)h * L * L + kj : nullptr;
+
+  f32x16 dk, dv;
+#pragma unroll
+  for (int e = 0; e < 16; e++) { dk[e] = 0.0f; dv[e] = 0.0f; }
+
+  for (int i0 = 0; i0 < L; i0 += C::KT) {
+    __syncthreads();
+    attn_stage<T>(base, a.seq_stride, i0, L, d, DP, lds_q, lds_qt, tid, 256);
+    attn_stage<T>(dobase, a.seq_stride / 4, i0, L, d, DP, lds_do, lds_dot, tid, 256);
+    if (tid < C::KT) {
+      int i = i0 + tid;
+      long long sidx = ((long long)b * a.H + h) * L + i;
+      lds_lse[tid] = (i < L) ? a.lse[sidx] : 0.0f;
+      lds_D[tid] = (i < L) ? a.D[sidx] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < C::KT / 32; it++) {
+      if (i0 + it * 32 >= L) break;
+      f32x16 sacc, pacc;
+#pragma unroll
+      for (int e = 0; e < 16; e++) { sacc[e] = 0.0f; pacc[e] = 0.0f; }
+#pragma unroll
+      for (int kk = 0; kk < MAXKK; kk++)
+        if (kk < NKK) {
+          int off = (it * 32 + l32) * C::RM + kk * MM::KSTEP + g * MM::KP;
+          MM::mma(sacc, MM::load(lds_q + off), kf[kk]);      // S = Q K^T   (rows queries, col = key lane)
+          MM::mma(pacc, MM::load(lds_do + off), vf[kk]);     // dP = dO V^T
+        }
+      f32x16 pv;
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        int ii = it * 32 + acc_row(g, e);
+        int i = i0 + ii;
+        float v = sacc[e] * a.scale;
+        if (bcol && i < L) v += bcol[(long long)i * L];
+        float p = (mk > 0.0f && i < L) ? __expf(v - lds_lse[ii]) : 0.0f;
+        pv[e] = p;
+        sacc[e] = p * (pacc[e] - lds_D[ii]);
+      }
+      const T* dotrow = lds_dot + l32 * C::TS + it * 32;
+      const T* qtrow = lds_qt + l32 * C::TS + it * 32;
+#pragma unroll
+      for (int u = 0; u < 32 / MM::KSTEP; u++) {
+        MM::mma(dv, lds_tfrag<T>(dotrow, g, u), acc_to_frag<T>(pv, u));     // dV^T += dO^T P
+        MM::mma(dk, lds_tfrag<T>(qtrow, g, u), acc_to_frag<T>(sacc, u));    // dK^T += Q^T dS
+      }
+    }
+  }
+  if (!kok) return;
+  T* pdk = (T*)a.dqkvg + (long long)b * a.batch_stride + (long long)kj * a.seq_stride + HD + h * d;
+  T* pdv = pdk + HD;
+#pragma unroll
+  for (int e = 0; e < 16; e++) {
+    int dd = acc_row(g, e);
+    if (dd < d) {
+      pdk[dd] = from_f<T>(dk[e] * a.scale);
+      pdv[dd] = from_f<T>(dv[e]);
+    }
+  }
+}
+
+// dbias[h][i][j] = sum_b dS[b][h][i][j]
+template <typename T>
+__global__ void attn_dbias_reduce_kernel(const T* dS, float* dbias, int B, long long hll) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= hll) return;
+  float s = 0.0f;
+  for (int b = 0; b < B; b++) s += to_f(dS[(long long)b * hll + idx]);
+  dbias[idx] = s;
+}

@@ -1,0 +1,1199 @@
+// Parallel Evoformer block: host orchestration and the C ABI (see include/pe.h).
+//
+// The MSA branch (+ outer product mean) is enqueued on stream_msa and the pair branch on
+// stream_pair; the only cross-stream edges are the ones the paper's Branch Parallelism
+// section lists: forward, the pair branch's result is needed by the final outer-product
+// projection (which adds it); backward, the outer-product-mean backward reads the pair
+// output cotangent (an input) and the row-attention-bias gradient is added to the pair
+// branch's gradient of the input pair representation at the very end.
+#include <stdio.h>
+#include <string>
+#include <vector>
+
+#include "pe_attn.h"
+#include "pe_elem.h"
+#include "pe_gemm.h"
+#include "pe_layout.h"
+
+struct pe_handle {
+  hipEvent_t ev[6];
+  int branches;
+  int sync_debug;
+  std::string last_error;
+};
+
+// ---------------------------------------------------------------------------
+// bump allocators
+// ---------------------------------------------------------------------------
+struct Arena {
+  char* base = nullptr;
+  size_t off = 0, high = 0;
+  void* alloc(size_t bytes) {
+    size_t o = (off + 255) & ~(size_t)255;
+    off = o + bytes;
+    if (off > high) high = off;
+    return base + o;
+  }
+  size_t mark() const { return off; }
+  void release(size_t m) { off = m; }
+};
+
+struct Carver {   // fixed layouts (ctx, prepared weights); optionally records entries
+  char* base;
+  size_t off = 0;
+  std::vector<pe_ctx_entry>* rec = nullptr;
+  template <typename U> U* take(const char* name, long long count, int dtype_tag) {
+    size_t o = (off + 255) & ~(size_t)255;
+    off = o + (size_t)count * sizeof(U);
+    if (rec && name) {
+      pe_ctx_entry e;
+      memset(&e, 0, sizeof(e));
+      snprintf(e.name, sizeof(e.name), "%s", name);
+      e.offset_bytes = (long long)o;
+      e.count = count;
+      e.dtype = dtype_tag;
+      rec->push_back(e);
+    }
+    return reinterpret_cast<U*>(base + o);
+  }
+};
+
+template <typename T> struct AttnCtx { T* xhat; float* stats; T* qkvg; float* bias; float* zstats; float* lse; T* o; T* og; };
+template <typename T> struct TransCtx { T* xhat; float* stats; T* h; };
+template <typename T> struct TriMulCtx { T* zhat; float* stats; T* proj_t; T* a_t; T* b_t; T* g; T* x_t; float* stats_out; T* xhat; T* u; };
+template <typename T> struct OpmCtx { T* mhat; float* stats; T* a; T* b; float* inv_norm; T* O; };
+template <typename T> struct GlobCtx { T* qbar; T* kv; T* gate; float* p; T* o; T* og; };
+template <typename T> struct Ctx {
+  AttnCtx<T> row, col, tas, tae;
+  TransCtx<T> mt, pt;
+  TriMulCtx<T> tmo, tmi;
+  OpmCtx<T> opm;
+  T *m1, *m2, *m3, *z1, *z2, *z3, *z4, *z5;
+};
+
+template <typename T> struct AttnW { T *wt_qkvg, *wn_qkvg, *wt_o, *wn_o; };
+template <typename T> struct TransW { T *wt_1, *wn_1, *wt_2, *wn_2; };
+template <typename T> struct OpmW { T *wt_ab, *wn_ab, *wt_o, *wn_o; };
+template <typename T> struct TriMulW { T *wt_p, *wn_p, *wt_g, *wn_g, *wt_o, *wn_o; float* bias_p; };
+template <typename T> struct PrepW {
+  AttnW<T> row, col, tas, tae;
+  TransW<T> mt, pt;
+  OpmW<T> opm;
+  TriMulW<T> tmo, tmi;
+};
+
+template <typename T> constexpr int dtype_tag() { return sizeof(T) == 2 ? PE_BF16 : PE_F32; }
+
+template <typename T> static void carve_attn_ctx(Carver& cv, AttnCtx<T>& a, const char* pre, long long M, int C, int HD,
+                                                 int H, long long B, long long L, bool has_bias, long long Mz) {
+  char nm[32];
+  auto N = [&](const char* s) { snprintf(nm, sizeof(nm), "%s.%s", pre, s); return nm; };
+  a.xhat = cv.take<T>(N("xhat"), M * C, dtype_tag<T>());
+  a.stats = cv.take<float>(N("stats"), M * 2, PE_F32);
+  a.qkvg = cv.take<T>(N("qkvg"), M * 4 * HD, dtype_tag<T>());
+  a.bias = has_bias ? cv.take<float>(N("bias"), (long long)H * L * L, PE_F32) : nullptr;
+  a.zstats = has_bias ? cv.take<float>(N("zstats"), Mz * 2, PE_F32) : nullptr;
+  a.lse = cv.take<float>(N("lse"), B * H * L, PE_F32);
+  a.o = cv.take<T>(N("o"), M * HD, dtype_tag<T>());
+  a.og = cv.take<T>(N("og"), M * HD, dtype_tag<T>());
+}
+template <typename T> static void carve_trans_ctx(Carver& cv, TransCtx<T>& a, const char* pre, long long M, int C, int n) {
+  char nm[32];
+  auto N = [&](const char* s) { snprintf(nm, sizeof(nm), "%s.%s", pre, s); return nm; };
+  a.xhat = cv.take<T>(N("xhat"), M * C, dtype_tag<T>());
+  a.stats = cv.take<float>(N("stats"), M * 2, PE_F32);
+  a.h = cv.take<T>(N("h"), M * n * C, dtype_tag<T>());
+}
+template <typename T> static void carve_trimul_ctx(Carver& cv, TriMulCtx<T>& a, const char* pre, long long Mz, int cz, int ct) {
+  char nm[32];
+  auto N = [&](const char* s) { snprintf(nm, sizeof(nm), "%s.%s", pre, s); return nm; };
+  a.zhat = cv.take<T>(N("zhat"), Mz * cz, dtype_tag<T>());
+  a.stats = cv.take<float>(N("stats"), Mz * 2, PE_F32);
+  a.proj_t = cv.take<T>(N("proj_t"), Mz * 4 * ct, dtype_tag<T>());
+  a.a_t = cv.take<T>(N("a_t"), Mz * ct, dtype_tag<T>());
+  a.b_t = cv.take<T>(N("b_t"), Mz * ct, dtype_tag<T>());
+  a.g = cv.take<T>(N("g"), Mz * cz, dtype_tag<T>());
+  a.x_t = cv.take<T>(N("x_t"), Mz * ct, dtype_tag<T>());
+  a.stats_out = cv.take<float>(N("stats_out"), Mz * 2, PE_F32);
+  a.xhat = cv.take<T>(N("xhat"), Mz * ct, dtype_tag<T>());
+  a.u = cv.take<T>(N("u"), Mz * cz, dtype_tag<T>());
+}
+
+template <typename T> static size_t carve_ctx(char* base, const pe_dims& d, Ctx<T>& C, std::vector<pe_ctx_entry>* rec) {
+  Carver cv;
+  cv.base = base;
+  cv.rec = rec;
+  const long long s = d.s, r = d.r, Mm = s * r, Mz = r * r;
+  const int HDm = d.h_msa * d.d_msa, HDz = d.h_pair * d.d_pair;
+  carve_attn_ctx<T>(cv, C.row, "row", Mm, d.c_m, HDm, d.h_msa, s, r, true, Mz);
+  C.m1 = cv.take<T>("m1", Mm * d.c_m, dtype_tag<T>());
+  carve_attn_ctx<T>(cv, C.col, "col", Mm, d.c_m, HDm, d.h_msa, r, s, false, Mz);
+  C.m2 = cv.take<T>("m2", Mm * d.c_m, dtype_tag<T>());
+  carve_trans_ctx<T>(cv, C.mt, "mtrans", Mm, d.c_m, d.n_trans);
+  C.m3 = cv.take<T>("m3", Mm * d.c_m, dtype_tag<T>());
+  C.opm.mhat = cv.take<T>("opm.mhat", Mm * d.c_m, dtype_tag<T>());
+  C.opm.stats = cv.take<float>("opm.stats", Mm * 2, PE_F32);
+  C.opm.a = cv.take<T>("opm.a", 2 * Mm * d.c_opm, dtype_tag<T>());
+  C.opm.b = C.opm.a + Mm * d.c_opm;
+  C.opm.inv_norm = cv.take<float>("opm.inv_norm", Mz, PE_F32);
+  C.opm.O = cv.take<T>("opm.O", Mz * d.c_opm * d.c_opm, dtype_tag<T>());
+  carve_trimul_ctx<T>(cv, C.tmo, "tmo", Mz, d.c_z, d.c_tri);
+  C.z1 = cv.take<T>("z1", Mz * d.c_z, dtype_tag<T>());
+  carve_trimul_ctx<T>(cv, C.tmi, "tmi", Mz, d.c_z, d.c_tri);
+  C.z2 = cv.take<T>("z2", Mz * d.c_z, dtype_tag<T>());
+  carve_attn_ctx<T>(cv, C.tas, "tas", Mz, d.c_z, HDz, d.h_pair, r, r, true, Mz);
+  C.z3 = cv.take<T>("z3", Mz * d.c_z, dtype_tag<T>());
+  carve_attn_ctx<T>(cv, C.tae, "tae", Mz, d.c_z, HDz, d.h_pair, r, r, true, Mz);
+  C.z4 = cv.take<T>("z4", Mz * d.c_z, dtype_tag<T>());
+  carve_trans_ctx<T>(cv, C.pt, "ptrans", Mz, d.c_z, d.n_trans);
+  C.z5 = cv.take<T>("z5", Mz * d.c_z, dtype_tag<T>());
+  return (cv.off + 255) & ~(size_t)255;
+}
+
+// ---------------------------------------------------------------------------
+// prepared weights
+// ---------------------------------------------------------------------------
+struct PrepList {
+  std::vector<PrepDesc> t;   // storage-type destinations (offsets in elements from the T region)
+  std::vector<PrepDesc> f;   // fp32 destinations
+};
+template <typename T> struct PrepCarver {
+  T* tbase; float* fbase;
+  long long toff = 0, foff = 0;
+  PrepList* list;
+  // weight W[in][out] at params offset src -> transposed copy [out][in] placed at row block `row0` of a [*, in] matrix
+  T* region(long long count) { long long o = (toff + 127) & ~127LL; toff = o + count; return tbase + o; }
+  float* fregion(long long count) { long long o = (foff + 63) & ~63LL; foff = o + count; return fbase + o; }
+  void add(T* dst, long long src, int rows, int cols, long long ld_r, long long ld_c) {
+    PrepDesc p; p.src_off = src; p.dst_off = dst - tbase; p.rows = rows; p.cols = cols; p.ld_r = ld_r; p.ld_c = ld_c;
+    list->t.push_back(p);
+  }
+  void addf(float* dst, long long src, int n) {
+    PrepDesc p; p.src_off = src; p.dst_off = dst - fbase; p.rows = 1; p.cols = n; p.ld_r = 0; p.ld_c = 1;
+    list->f.push_back(p);
+  }
+};
+
+template <typename T> static void prep_attn(PrepCarver<T>& pc, AttnW<T>& w, const AttnP& p, int C, int HD) {
+  w.wt_qkvg = pc.region((long long)4 * HD * C);
+  w.wn_qkvg = pc.region((long long)4 * HD * C);
+  w.wt_o = pc.region((long long)HD * C);
+  w.wn_o = pc.region((long long)HD * C);
+  const long long src[4] = {p.w_q, p.w_k, p.w_v, p.w_g};
+  for (int k = 0; k < 4; k++) {
+    pc.add(w.wt_qkvg + (long long)k * HD * C, src[k], C, HD, 1, C);   // [out][in]
+    pc.add(w.wn_qkvg + (long long)k * HD, src[k], C, HD, 4 * HD, 1);  // [in][4HD]
+  }
+  pc.add(w.wt_o, p.w_o, HD, C, 1, HD);   // [C][HD]
+  pc.add(w.wn_o, p.w_o, HD, C, C, 1);    // [HD][C]
+}
+template <typename T> static void prep_trans(PrepCarver<T>& pc, TransW<T>& w, const TransP& p, int C, int n) {
+  long long nc = (long long)n * C;
+  w.wt_1 = pc.region(nc * C); w.wn_1 = pc.region(nc * C); w.wt_2 = pc.region(nc * C); w.wn_2 = pc.region(nc * C);
+  pc.add(w.wt_1, p.w1, C, (int)nc, 1, C);      // [nC][C]
+  pc.add(w.wn_1, p.w1, C, (int)nc, nc, 1);     // [C][nC]
+  pc.add(w.wt_2, p.w2, (int)nc, C, 1, nc);     // [C][nC]
+  pc.add(w.wn_2, p.w2, (int)nc, C, C, 1);      // [nC][C]
+}
+template <typename T> static void prep_trimul(PrepCarver<T>& pc, TriMulW<T>& w, const TriMulP& p, int cz, int ct) {
+  w.wt_p = pc.region((long long)4 * ct * cz); w.wn_p = pc.region((long long)4 * ct * cz);
+  w.wt_g = pc.region((long long)cz * cz); w.wn_g = pc.region((long long)cz * cz);
+  w.wt_o = pc.region((long long)cz * ct); w.wn_o = pc.region((long long)cz * ct);
+  w.bias_p = pc.fregion(4 * ct);
+  const long long src[4] = {p.w_ap, p.w_ag, p.w_bp, p.w_bg};
+  const long long bsrc[4] = {p.b_ap, p.b_ag, p.b_bp, p.b_bg};
+  for (int k = 0; k < 4; k++) {
+    pc.add(w.wt_p + (long long)k * ct * cz, src[k], cz, ct, 1, cz);   // [4ct][cz]
+    pc.add(w.wn_p + (long long)k * ct, src[k], cz, ct, 4 * ct, 1);    // [cz][4ct]
+    pc.addf(w.bias_p + k * ct, bsrc[k], ct);
+  }
+  pc.add(w.wt_g, p.w_g, cz, cz, 1, cz);
+  pc.add(w.wn_g, p.w_g, cz, cz, cz, 1);
+  pc.add(w.wt_o, p.w_o, ct, cz, 1, ct);   // [cz][ct]
+  pc.add(w.wn_o, p.w_o, ct, cz, cz, 1);   // [ct][cz]
+}
+
+// ---------------------------------------------------------------------------
+// Runner: one block, one storage type
+// ---------------------------------------------------------------------------
+template <typename T> struct Runner {
+  pe_handle* h;
+  pe_dims d;
+  ParamLayout PL;
+  bool dry = false;
+  int err = 0;
+  const float* params = nullptr;
+  float* dparams = nullptr;
+  const T* msa_in = nullptr; const T* pair_in = nullptr;
+  const float* msa_mask = nullptr; const float* pair_mask = nullptr;
+  hipStream_t sm = nullptr, sp = nullptr;
+  Ctx<T> C;
+  PrepW<T> W;
+  PrepList prep_msa, prep_pair;
+  T* prep_tbase_m = nullptr; float* prep_fbase_m = nullptr;
+  T* prep_tbase_p = nullptr; float* prep_fbase_p = nullptr;
+  Arena am, ap;
+  long long Mm, Mz;
+  int HDm, HDz;
+
+  void init(const pe_dims& dd) {
+    d = dd;
+    build_param_layout(d, PL);
+    Mm = (long long)d.s * d.r;
+    Mz = (long long)d.r * d.r;
+    HDm = d.h_msa * d.d_msa;
+    HDz = d.h_pair * d.d_pair;
+  }
+  void fail(const char* what) {
+    if (!err) {
+      err = PE_ERR_HIP;
+      hipError_t e = hipGetLastError();
+      if (h) h->last_error = std::string(what) + ": " + hipGetErrorString(e);
+    }
+  }
+  void check(const char* what) {
+    if (dry || err) return;
+    if (hipGetLastError() != hipSuccess) { fail(what); return; }
+    if (h && h->sync_debug) {
+      if (hipDeviceSynchronize() != hipSuccess) fail(what);
+    }
+  }
+
+  // ---- prepared weights: returns bytes used -------------------------------
+  size_t carve_prep(char* base) {
+    size_t off = 0;
+    auto region = [&](size_t bytes) { size_t o = (off + 255) & ~(size_t)255; off = o + bytes; return base + o; };
+    // sizes: generous upper bounds (2 copies of every weight + padding)
+    size_t tbytes = (size_t)(2 * PL.total + 128 * 64) * sizeof(T);
+    size_t fbytes = (size_t)(16 * d.c_tri + 1024) * sizeof(float);
+    prep_tbase_m = (T*)region(tbytes); prep_fbase_m = (float*)region(fbytes);
+    prep_tbase_p = (T*)region(tbytes); prep_fbase_p = (float*)region(fbytes);
+    prep_msa.t.clear(); prep_msa.f.clear(); prep_pair.t.clear(); prep_pair.f.clear();
+    PrepCarver<T> pm{prep_tbase_m, prep_fbase_m, 0, 0, &prep_msa};
+    prep_attn<T>(pm, W.row, PL.row, d.c_m, HDm);
+    if (!d.col_global) prep_attn<T>(pm, W.col, PL.col, d.c_m, HDm);
+    prep_trans<T>(pm, W.mt, PL.mtrans, d.c_m, d.n_trans);
+    {
+      int co = d.c_opm, cm = d.c_m, cz = d.c_z;
+      W.opm.wt_ab = pm.region((long long)2 * co * cm); W.opm.wn_ab = pm.region((long long)2 * co * cm);
+      W.opm.wt_o = pm.region((long long)co * co * cz); W.opm.wn_o = pm.region((long long)co * co * cz);
+      pm.add(W.opm.wt_ab, PL.opm.w_a, cm, co, 1, cm);
+      pm.add(W.opm.wt_ab + (long long)co * cm, PL.opm.w_b, cm, co, 1, cm);
+      pm.add(W.opm.wn_ab, PL.opm.w_a, cm, co, 2 * co, 1);
+      pm.add(W.opm.wn_ab + co, PL.opm.w_b, cm, co, 2 * co, 1);
+      pm.add(W.opm.wt_o, PL.opm.w_o, co * co, cz, 1, (long long)co * co);   // [cz][co*co]
+      pm.add(W.opm.wn_o, PL.opm.w_o, co * co, cz, cz, 1);                   // [co*co][cz]
+    }
+    PrepCarver<T> pp{prep_tbase_p, prep_fbase_p, 0, 0, &prep_pair};
+    prep_trimul<T>(pp, W.tmo, PL.tmo, d.c_z, d.c_tri);
+    prep_trimul<T>(pp, W.tmi, PL.tmi, d.c_z, d.c_tri);
+    prep_attn<T>(pp, W.tas, PL.tas, d.c_z, HDz);
+    prep_attn<T>(pp, W.tae, PL.tae, d.c_z, HDz);
+    prep_trans<T>(pp, W.pt, PL.ptrans, d.c_z, d.n_trans);
+    return (off + 255) & ~(size_t)255;
+  }
+  void run_prep_list(hipStream_t st, const std::vector<PrepDesc>& v, bool is_f, T* tbase, float* fbase) {
+    for (size_t i = 0; i < v.size(); i += PREP_MAX) {
+      PrepBatch pb;
+      pb.n = (int)std::min((size_t)PREP_MAX, v.size() - i);
+      for (int k = 0; k < pb.n; k++) pb.d[k] = v[i + k];
+      dim3 grid(64, pb.n);
+      if (is_f) hipLaunchKernelGGL(prep_params_kernel<float>, grid, dim3(256), 0, st, params, fbase, pb);
+      else hipLaunchKernelGGL(prep_params_kernel<T>, grid, dim3(256), 0, st, params, tbase, pb);
+      check("prep_params");
+    }
+  }
+  void run_prep(bool msa_side) {
+    if (dry) return;
+    if (msa_side) {
+      run_prep_list(sm, prep_msa.t, false, prep_tbase_m, prep_fbase_m);
+      run_prep_list(sm, prep_msa.f, true, prep_tbase_m, prep_fbase_m);
+    } else {
+      run_prep_list(sp, prep_pair.t, false, prep_tbase_p, prep_fbase_p);
+      run_prep_list(sp, prep_pair.f, true, prep_tbase_p, prep_fbase_p);
+    }
+  }
+
+  // ---- kernel wrappers -----------------------------------------------------
+  const float* P(long long off) const { return params + off; }
+
+  void k_ln_fwd(hipStream_t st, const T* x, long long g_off, long long b_off, T* y, float* stats, long long M, int Cc) {
+    if (dry || err) return;
+    int grid = (int)std::min<long long>((M + 3) / 4, 4096);
+    hipLaunchKernelGGL(ln_fwd_kernel<T>, dim3(grid), dim3(256), 0, st, x, P(g_off), P(b_off), y, stats, M, Cc, d.ln_eps);
+    check("ln_fwd");
+  }
+  void reduce_to(hipStream_t st, const float* part, int nsplit, long long stride, int rows, int cols, int nseg,
+                 const ReduceSeg* segs) {
+    if (dry || err) return;
+    ReduceArgs ra;
+    ra.part = part; ra.nsplit = nsplit; ra.stride = stride; ra.rows = rows; ra.cols = cols; ra.nseg = nseg;
+    for (int i = 0; i < nseg; i++) ra.seg[i] = segs[i];
+    ra.dst = dparams;
+    long long total = (long long)rows * cols;
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, ra);
+    check("reduce_partials");
+  }
+  void k_ln_bwd(hipStream_t st, Arena& ar, const T* dy, const T* x, const float* stats, long long g_off, long long b_off,
+                const T* gin, T* gout, long long M, int Cc) {
+    size_t mk = ar.mark();
+    int grid = (int)std::min<long long>((M + 3) / 4, LN_MAX_WG);
+    float* part = (float*)ar.alloc((size_t)grid * 2 * Cc * sizeof(float));
+    if (!dry && !err) {
+      hipLaunchKernelGGL(ln_bwd_kernel<T>, dim3(grid), dim3(256), 0, st, dy, x, stats, P(g_off), gin, gout, part, M, Cc);
+      check("ln_bwd");
+      ReduceSeg sg[2] = {{0, Cc, g_off, 0}, {Cc, Cc, b_off, 0}};
+      reduce_to(st, part, grid, 2LL * Cc, 1, 2 * Cc, 2, sg);
+    }
+    ar.release(mk);
+  }
+  void k_colsum(hipStream_t st, Arena& ar, const T* y, long long M, int N, long long ld, long long dst_off) {
+    size_t mk = ar.mark();
+    int nwg = (int)std::min<long long>(256, M);
+    long long rpw = (M + nwg - 1) / nwg;
+    nwg = (int)((M + rpw - 1) / rpw);
+    float* part = (float*)ar.alloc((size_t)nwg * N * sizeof(float));
+    if (!dry && !err) {
+      hipLaunchKernelGGL(colsum_kernel<T>, dim3(nwg), dim3(256), 0, st, y, M, N, ld, part, rpw);
+      check("colsum");
+      ReduceSeg sg[1] = {{0, N, dst_off, 0}};
+      reduce_to(st, part, nwg, N, 1, N, 1, sg);
+    }
+    ar.release(mk);
+  }
+  void gemm(hipStream_t st, const Operand& A, bool akc, const Operand& B, bool bkc, int M, int N, int K, int batch,
+            const EpiGeneric<T>& e, const char* what) {
+    if (dry || err) return;
+    GemmShape sh{M, N, K, batch, 0};
+    int rc = launch_gemm<T, EpiGeneric<T>>(st, A, akc, B, bkc, sh, e);
+    if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = std::string("gemm operand alignment: ") + what; return; }
+    check(what);
+  }
+  // dW[rows][cols] += sum_k X(row,k) * Y(col,k), K huge: split-K partials + ordered reduce into dparams
+  void gemm_dw(hipStream_t st, Arena& ar, const Operand& X, bool xkc, const Operand& Y, bool ykc, int rows, int cols,
+               long long K, int nseg, const ReduceSeg* segs, const char* what) {
+    size_t mk = ar.mark();
+    int tiles = ((rows + 127) / 128) * ((cols + 127) / 128);
+    int want = std::max(1, 768 / tiles);
+    const int BK = GemmCfg<T>::BK;
+    long long kc = (K + want - 1) / want;
+    kc = (kc + BK - 1) / BK * BK;
+    int nsplit = (int)((K + kc - 1) / kc);
+    float* part = (float*)ar.alloc((size_t)nsplit * rows * cols * sizeof(float));
+    if (!dry && !err) {
+      GemmShape sh{rows, cols, (int)K, nsplit, (int)kc};
+      EpiPartial ep{part, (long long)rows * cols, cols};
+      int rc = launch_gemm<T, EpiPartial>(st, X, xkc, Y, ykc, sh, ep);
+      if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = std::string("gemm_dw operand alignment: ") + what; }
+      else check(what);
+      reduce_to(st, part, nsplit, (long long)rows * cols, rows, cols, nseg, segs);
+    }
+    ar.release(mk);
+  }
+
+  // ---- sub-operations: forward ---------------------------------------------
+  struct AttnGeom { long long B, L, batch_stride, seq_stride, mask_bs, mask_ks; const float* mask; int bias_transposed; };
+
+  void attn_sub_fwd(hipStream_t st, Arena& ar, const AttnP& p, const AttnW<T>& w, AttnCtx<T>& c, const T* x, T* xout,
+                    long long M, int Cc, int H, int dh, const AttnGeom& g, const T* bias_src, long long bias_ln_g,
+                    long long bias_ln_b) {
+    const int HD = H * dh;
+    k_ln_fwd(st, x, p.ln_g, p.ln_b, c.xhat, c.stats, M, Cc);
+    if (c.bias && !dry && !err) {
+      int grid = (int)std::min<long long>((Mz + 3) / 4, 4096);
+      hipLaunchKernelGGL(ln_bias_fwd_kernel<T>, dim3(grid), dim3(256), 0, st, bias_src, P(bias_ln_g), P(bias_ln_b),
+                         P(p.w_bias), c.bias, c.zstats, d.r, d.c_z, H, d.ln_eps, g.bias_transposed);
+      check("ln_bias_fwd");
+    }
+    {
+      EpiGeneric<T> e = epi_plain<T>(c.qkvg, 4 * HD);
+      e.bias_n = P(p.b_g) - 3 * HD;   // only columns >= 3HD carry a bias (see bn_begin)
+      e.bn_begin = 3 * HD;
+      gemm(st, op_plain(c.xhat, Cc), true, op_plain(w.wt_qkvg, Cc), true, (int)M, 4 * HD, Cc, 1, e, "attn qkvg");
+    }
+    if (!dry && !err) {
+      AttnArgs a;
+      memset(&a, 0, sizeof(a));
+      a.qkvg = c.qkvg; a.batch_stride = g.batch_stride; a.seq_stride = g.seq_stride;
+      a.B = (int)g.B; a.L = (int)g.L; a.H = H; a.d = dh;
+      a.bias = c.bias; a.mask = g.mask; a.mask_bs = g.mask_bs; a.mask_ks = g.mask_ks;
+      a.o = c.o; a.og = c.og; a.lse = c.lse; a.scale = 1.0f / sqrtf((float)dh);
+      dim3 grid((unsigned)((g.L + 127) / 128), H, (unsigned)g.B);
+      hipLaunchKernelGGL(attn_fwd_kernel<T>, grid, dim3(256), 0, st, a);
+      check("attn_fwd");
+    }
+    {
+      EpiGeneric<T> e = epi_plain<T>(xout, Cc);
+      e.bias_n = P(p.b_o);
+      e.res = x; e.ld_res = Cc;
+      gemm(st, op_plain(c.og, HD), true, op_plain(w.wt_o, HD), true, (int)M, Cc, HD, 1, e, "attn out");
+    }
+  }
+
+  void trans_sub_fwd(hipStream_t st, const TransP& p, const TransW<T>& w, TransCtx<T>& c, const T* x, T* xout, long long M,
+                     int Cc) {
+    const int nC = d.n_trans * Cc;
+    k_ln_fwd(st, x, p.ln_g, p.ln_b, c.xhat, c.stats, M, Cc);
+    {
+      EpiGeneric<T> e = epi_plain<T>(c.h, nC);
+      e.bias_n = P(p.b1); e.act = 1;
+      gemm(st, op_plain(c.xhat, Cc), true, op_plain(w.wt_1, Cc), true, (int)M, nC, Cc, 1, e, "trans 1");
+    }
+    {
+      EpiGeneric<T> e = epi_plain<T>(xout, Cc);
+      e.bias_n = P(p.b2); e.res = x; e.ld_res = Cc;
+      gemm(st, op_plain(c.h, nC), true, op_plain(w.wt_2, nC), true, (int)M, Cc, nC, 1, e, "trans 2");
+    }
+  }
+
+  void trimul_sub_fwd(hipStream_t st, const TriMulP& p, const TriMulW<T>& w, TriMulCtx<T>& c, const T* z, T* zout,
+                      bool outgoing) {
+    const int cz = d.c_z, ct = d.c_tri, r = d.r;
+    k_ln_fwd(st, z, p.ln_in_g, p.ln_in_b, c.zhat, c.stats, Mz, cz);
+    {  // channel-major projections: proj_t[4ct][Mz] = W_p^T[4ct][cz] . zhat^T
+      EpiGeneric<T> e = epi_plain<T>(c.proj_t, Mz);
+      e.bias_m = w.bias_p;
+      gemm(st, op_plain(w.wt_p, cz), true, op_plain(c.zhat, cz), true, 4 * ct, (int)Mz, cz, 1, e, "trimul proj");
+    }
+    if (!dry && !err) {
+      long long n = (long long)ct * Mz;
+      hipLaunchKernelGGL(tm_gate_fwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, c.proj_t, pair_mask,
+                         c.a_t, c.b_t, ct, Mz);
+      check("tm_gate_fwd");
+    }
+    {  // per-channel contraction over the third residue
+      EpiGeneric<T> e = epi_plain<T>(c.x_t, r);
+      e.out_batch = Mz;
+      if (outgoing) gemm(st, op_plain(c.a_t, r, Mz), true, op_plain(c.b_t, r, Mz), true, r, r, r, ct, e, "trimul out");
+      else gemm(st, op_trans(c.a_t, r, Mz), false, op_trans(c.b_t, r, Mz), false, r, r, r, ct, e, "trimul in");
+    }
+    if (!dry && !err) {
+      size_t lds = (size_t)64 * (ct + 1) * sizeof(float);
+      hipLaunchKernelGGL(ln_cmajor_fwd_kernel<T>, dim3((unsigned)((Mz + 63) / 64)), dim3(256), lds, st, c.x_t,
+                         P(p.ln_out_g), P(p.ln_out_b), c.xhat, c.stats_out, Mz, ct, d.ln_eps);
+      check("ln_cmajor_fwd");
+    }
+    {
+      EpiGeneric<T> e = epi_plain<T>(c.g, cz);
+      e.bias_n = P(p.b_g); e.act = 2;
+      gemm(st, op_plain(c.zhat, cz), true, op_plain(w.wt_g, cz), true, (int)Mz, cz, cz, 1, e, "trimul gate");
+    }
+    {
+      EpiGeneric<T> e = epi_plain<T>(zout, cz);
+      e.bias_n = P(p.b_o);
+      e.aux = c.u; e.ld_aux = cz;
+      e.mul = c.g; e.ld_mul = cz;
+      e.res = z; e.ld_res = cz;
+      gemm(st, op_plain(c.xhat, ct), true, op_plain(w.wt_o, ct), true, (int)Mz, cz, ct, 1, e, "trimul outproj");
+    }
+  }
+
+  AttnGeom geom_row() const { return AttnGeom{d.s, d.r, (long long)d.r * 4 * HDm, 4LL * HDm, d.r, 1, msa_mask, 0}; }
+  AttnGeom geom_col() const { return AttnGeom{d.r, d.s, 4LL * HDm, (long long)d.r * 4 * HDm, 1, d.r, msa_mask, 0}; }
+  AttnGeom geom_tas() const { return AttnGeom{d.r, d.r, (long long)d.r * 4 * HDz, 4LL * HDz, d.r, 1, pair_mask, 0}; }
+  AttnGeom geom_tae() const { return AttnGeom{d.r, d.r, 4LL * HDz, (long long)d.r * 4 * HDz, 1, d.r, pair_mask, 1}; }
+
+  void fwd_msa(T* msa_out) {
+    run_prep(true);
+    attn_sub_fwd(sm, am, PL.row, W.row, C.row, msa_in, C.m1, Mm, d.c_m, d.h_msa, d.d_msa, geom_row(), pair_in,
+                 PL.row.ln_z_g, PL.row.ln_z_b);
+    attn_sub_fwd(sm, am, PL.col, W.col, C.col, C.m1, C.m2, Mm, d.c_m, d.h_msa, d.d_msa, geom_col(), nullptr, 0, 0);
+    trans_sub_fwd(sm, PL.mtrans, W.mt, C.mt, C.m2, C.m3, Mm, d.c_m);
+    if (!dry && !err && msa_out) {
+      if (hipMemcpyAsync(msa_out, C.m3, (size_t)Mm * d.c_m * sizeof(T), hipMemcpyDeviceToDevice, sm) != hipSuccess)
+        fail("copy msa_out");
+    }
+    // outer product mean, up to the projection (which needs the pair branch's result)
+    const int co = d.c_opm, r = d.r;
+    const long long Wd = (long long)r * co;
+    k_ln_fwd(sm, C.m3, PL.opm.ln_g, PL.opm.ln_b, C.opm.mhat, C.opm.stats, Mm, d.c_m);
+    for (int k = 0; k < 2; k++) {
+      EpiGeneric<T> e = epi_plain<T>(k ? C.opm.b : C.opm.a, co);
+      e.bias_n = P(k ? PL.opm.b_b : PL.opm.b_a);
+      e.rowscale = msa_mask;
+      gemm(sm, op_plain(C.opm.mhat, d.c_m), true, op_plain(W.opm.wt_ab + (long long)k * co * d.c_m, d.c_m), true, (int)Mm,
+           co, d.c_m, 1, e, "opm ab");
+    }
+    if (!dry && !err) {
+      hipLaunchKernelGGL(opm_norm_kernel, dim3((unsigned)((Mz + 255) / 256)), dim3(256), 0, sm, msa_mask, C.opm.inv_norm,
+                         d.s, r, d.opm_eps);
+      check("opm_norm");
+    }
+    {
+      EpiGeneric<T> e = epi_plain<T>(C.opm.O, Wd);
+      e.scale2d = C.opm.inv_norm; e.s2_mdiv = co; e.s2_ndiv = co; e.s2_ld = r;
+      gemm(sm, op_trans(C.opm.a, Wd), false, op_trans(C.opm.b, Wd), false, (int)Wd, (int)Wd, d.s, 1, e, "opm outer");
+    }
+  }
+  // final projection of the outer product mean; adds the pair branch's output
+  void fwd_opm_project(T* pair_out, const T* z5) {
+    const int co = d.c_opm, r = d.r;
+    const long long Wd = (long long)r * co;
+    Operand A;
+    A.ptr = C.opm.O; A.batch_stride = 0;
+    A.x_in = r; A.x_outer = (long long)co * Wd; A.x_stride = co;
+    A.k_in = co; A.k_outer = Wd; A.k_stride = 1;
+    EpiGeneric<T> e = epi_plain<T>(pair_out, d.c_z);
+    e.bias_n = P(PL.opm.b_o);
+    e.res = z5; e.ld_res = d.c_z;
+    gemm(sm, A, true, op_plain(W.opm.wt_o, (long long)co * co), true, (int)Mz, d.c_z, co * co, 1, e, "opm project");
+  }
+  void fwd_pair() {
+    run_prep(false);
+    trimul_sub_fwd(sp, PL.tmo, W.tmo, C.tmo, pair_in, C.z1, true);
+    trimul_sub_fwd(sp, PL.tmi, W.tmi, C.tmi, C.z1, C.z2, false);
+    attn_sub_fwd(sp, ap, PL.tas, W.tas, C.tas, C.z2, C.z3, Mz, d.c_z, d.h_pair, d.d_pair, geom_tas(), C.z2, PL.tas.ln_g,
+                 PL.tas.ln_b);
+    attn_sub_fwd(sp, ap, PL.tae, W.tae, C.tae, C.z3, C.z4, Mz, d.c_z, d.h_pair, d.d_pair, geom_tae(), C.z3, PL.tae.ln_g,
+                 PL.tae.ln_b);
+    trans_sub_fwd(sp, PL.ptrans, W.pt, C.pt, C.z4, C.z5, Mz, d.c_z);
+  }
+
+  // ---- sub-operations: backward --------------------------------------------
+  // g: running gradient w.r.t. the sub-op's output (and, after the call, its input) [M][C]
+  void trans_sub_bwd(hipStream_t st, Arena& ar, const TransP& p, const TransW<T>& w, const TransCtx<T>& c, const T* x, T* g,
+                     long long M, int Cc) {
+    size_t mk = ar.mark();
+    const int nC = d.n_trans * Cc;
+    T* dh = (T*)ar.alloc((size_t)M * nC * sizeof(T));
+    T* dxh = (T*)ar.alloc((size_t)M * Cc * sizeof(T));
+    k_colsum(st, ar, g, M, Cc, Cc, p.b2);
+    { ReduceSeg sg[1] = {{0, Cc, p.w2, Cc}};
+      gemm_dw(st, ar, op_trans(c.h, nC), false, op_trans(g, Cc), false, nC, Cc, M, 1, sg, "trans dW2"); }
+    { EpiGeneric<T> e = epi_plain<T>(dh, nC);
+      e.relu_mask = c.h; e.ld_rm = nC;
+      gemm(st, op_plain(g, Cc), true, op_plain(w.wn_2, Cc), true, (int)M, nC, Cc, 1, e, "trans dh"); }
+    k_colsum(st, ar, dh, M, nC, nC, p.b1);
+    { ReduceSeg sg[1] = {{0, nC, p.w1, nC}};
+      gemm_dw(st, ar, op_trans(c.xhat, Cc), false, op_trans(dh, nC), false, Cc, nC, M, 1, sg, "trans dW1"); }
+    { EpiGeneric<T> e = epi_plain<T>(dxh, Cc);
+      gemm(st, op_plain(dh, nC), true, op_plain(w.wn_1, nC), true, (int)M, Cc, nC, 1, e, "trans dxhat"); }
+    k_ln_bwd(st, ar, dxh, x, c.stats, p.ln_g, p.ln_b, g, g, M, Cc);
+    ar.release(mk);
+  }
+
+  // bias_gout: where the gradient through the pair bias goes (gin added when not null)
+  void attn_sub_bwd(hipStream_t st, Arena& ar, const AttnP& p, const AttnW<T>& w, const AttnCtx<T>& c, const T* x, T* g,
+                    long long M, int Cc, int H, int dh, const AttnGeom& gm, const T* bias_src, long long bias_ln_g,
+                    long long bias_ln_b, const T* bias_gin, T* bias_gout) {
+    size_t mk = ar.mark();
+    const int HD = H * dh;
+    T* dog = (T*)ar.alloc((size_t)M * HD * sizeof(T));
+    T* dO = (T*)ar.alloc((size_t)M * HD * sizeof(T));
+    T* dqkvg = (T*)ar.alloc((size_t)M * 4 * HD * sizeof(T));
+    float* Dv = (float*)ar.alloc((size_t)gm.B * H * gm.L * sizeof(float));
+    T* dxh = (T*)ar.alloc((size_t)M * Cc * sizeof(T));
+    T* dS = nullptr;
+    float* dbias = nullptr;
+    if (c.bias) {
+      dS = (T*)ar.alloc((size_t)gm.B * H * gm.L * gm.L * sizeof(T));
+      dbias = (float*)ar.alloc((size_t)H * gm.L * gm.L * sizeof(float));
+    }
+    k_colsum(st, ar, g, M, Cc, Cc, p.b_o);
+    { ReduceSeg sg[1] = {{0, Cc, p.w_o, Cc}};
+      gemm_dw(st, ar, op_trans(c.og, HD), false, op_trans(g, Cc), false, HD, Cc, M, 1, sg, "attn dWo"); }
+    { EpiGeneric<T> e = epi_plain<T>(dog, HD);
+      gemm(st, op_plain(g, Cc), true, op_plain(w.wn_o, Cc), true, (int)M, HD, Cc, 1, e, "attn dog"); }
+    if (!dry && !err) {
+      AttnArgs a;
+      memset(&a, 0, sizeof(a));
+      a.qkvg = c.qkvg; a.batch_stride = gm.batch_stride; a.seq_stride = gm.seq_stride;
+      a.B = (int)gm.B; a.L = (int)gm.L; a.H = H; a.d = dh;
+      a.bias = c.bias; a.mask = gm.mask; a.mask_bs = gm.mask_bs; a.mask_ks = gm.mask_ks;
+      a.o = c.o; a.og = c.og; a.lse = c.lse; a.scale = 1.0f / sqrtf((float)dh);
+      a.dog = dog; a.dO = dO; a.D = Dv; a.dqkvg = dqkvg; a.dS = dS;
+      long long tot = gm.B * gm.L * H;
+      hipLaunchKernelGGL(attn_bwd_pre_kernel<T>, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a);
+      check("attn_bwd_pre");
+      dim3 grid((unsigned)((gm.L + 127) / 128), H, (unsigned)gm.B);
+      hipLaunchKernelGGL(attn_bwd_dq_kernel<T>, grid, dim3(256), 0, st, a);
+      check("attn_bwd_dq");
+      hipLaunchKernelGGL(attn_bwd_dkv_kernel<T>, grid, dim3(256), 0, st, a);
+      check("attn_bwd_dkv");
+      if (c.bias) {
+        long long hll = (long long)H * gm.L * gm.L;
+        hipLaunchKernelGGL(attn_dbias_reduce_kernel<T>, dim3((unsigned)((hll + 255) / 256)), dim3(256), 0, st, dS, dbias,
+                           (int)gm.B, hll);
+        check("attn_dbias_reduce");
+      }
+    }
+    k_colsum(st, ar, dqkvg + 3 * HD, M, HD, 4 * HD, p.b_g);
+    { ReduceSeg sg[4] = {{0, HD, p.w_q, HD}, {HD, HD, p.w_k, HD}, {2 * HD, HD, p.w_v, HD}, {3 * HD, HD, p.w_g, HD}};
+      gemm_dw(st, ar, op_trans(c.xhat, Cc), false, op_trans(dqkvg, 4 * HD), false, Cc, 4 * HD, M, 4, sg, "attn dWqkvg"); }
+    { EpiGeneric<T> e = epi_plain<T>(dxh, Cc);
+      gemm(st, op_plain(dqkvg, 4 * HD), true, op_plain(w.wn_qkvg, 4 * HD), true, (int)M, Cc, 4 * HD, 1, e, "attn dxhat"); }
+    k_ln_bwd(st, ar, dxh, x, c.stats, p.ln_g, p.ln_b, g, g, M, Cc);
+    if (c.bias) {
+      const int cz = d.c_z;
+      int grid = (int)std::min<long long>((Mz + 3) / 4, LN_MAX_WG);
+      int plen = 2 * cz + cz * H;
+      float* part = (float*)ar.alloc((size_t)grid * plen * sizeof(float));
+      if (!dry && !err) {
+        hipLaunchKernelGGL(ln_bias_bwd_kernel<T>, dim3(grid), dim3(256), 0, st, dbias, bias_src, c.zstats, P(bias_ln_g),
+                           P(bias_ln_b), P(p.w_bias), bias_gin, bias_gout, part, d.r, cz, H, gm.bias_transposed);
+        check("ln_bias_bwd");
+        ReduceSeg sg[3] = {{0, cz, bias_ln_g, 0}, {cz, cz, bias_ln_b, 0}, {2 * cz, cz * H, p.w_bias, 0}};
+        reduce_to(st, part, grid, plen, 1, plen, 3, sg);
+      }
+    }
+    ar.release(mk);
+  }
+
+  void trimul_sub_bwd(hipStream_t st, Arena& ar, const TriMulP& p, const TriMulW<T>& w, const TriMulCtx<T>& c, const T* z,
+                      T* g, bool outgoing) {
+    size_t mk = ar.mark();
+    const int cz = d.c_z, ct = d.c_tri, r = d.r;
+    T* du = (T*)ar.alloc((size_t)Mz * cz * sizeof(T));
+    T* dgraw = (T*)ar.alloc((size_t)Mz * cz * sizeof(T));
+    T* dxh_o = (T*)ar.alloc((size_t)Mz * ct * sizeof(T));
+    T* dx_t = (T*)ar.alloc((size_t)Mz * ct * sizeof(T));
+    T* da_t = (T*)ar.alloc((size_t)Mz * ct * sizeof(T));
+    T* db_t = (T*)ar.alloc((size_t)Mz * ct * sizeof(T));
+    T* dproj_t = (T*)ar.alloc((size_t)Mz * 4 * ct * sizeof(T));
+    T* dzh = (T*)ar.alloc((size_t)Mz * cz * sizeof(T));
+    if (!dry && !err) {
+      long long n = Mz * cz;
+      hipLaunchKernelGGL(tm_out_bwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, g, c.g, c.u, du, dgraw, n);
+      check("tm_out_bwd");
+    }
+    k_colsum(st, ar, du, Mz, cz, cz, p.b_o);
+    { ReduceSeg sg[1] = {{0, cz, p.w_o, cz}};
+      gemm_dw(st, ar, op_trans(c.xhat, ct), false, op_trans(du, cz), false, ct, cz, Mz, 1, sg, "trimul dWo"); }
+    { EpiGeneric<T> e = epi_plain<T>(dxh_o, ct);
+      gemm(st, op_plain(du, cz), true, op_plain(w.wn_o, cz), true, (int)Mz, ct, cz, 1, e, "trimul dxhat_o"); }
+    {  // LayerNorm (channel-major input) backward
+      size_t mk2 = ar.mark();
+      int grid = (int)((Mz + 63) / 64);
+      float* part = (float*)ar.alloc((size_t)grid * 2 * ct * sizeof(float));
+      if (!dry && !err) {
+        size_t lds = (size_t)64 * (ct + 1) * sizeof(float);
+        hipLaunchKernelGGL(ln_cmajor_bwd_kernel<T>, dim3(grid), dim3(256), lds, st, dxh_o, c.x_t, c.stats_out,
+                           P(p.ln_out_g), dx_t, part, Mz, ct);
+        check("ln_cmajor_bwd");
+        ReduceSeg sg[2] = {{0, ct, p.ln_out_g, 0}, {ct, ct, p.ln_out_b, 0}};
+        reduce_to(st, part, grid, 2LL * ct, 1, 2 * ct, 2, sg);
+      }
+      ar.release(mk2);
+    }
+    {  // contraction backward, per channel
+      EpiGeneric<T> ea = epi_plain<T>(da_t, r); ea.out_batch = Mz;
+      EpiGeneric<T> eb = epi_plain<T>(db_t, r); eb.out_batch = Mz;
+      if (outgoing) {
+        // da[i,k] = sum_j dx[i,j] b[j,k];  db[j,k] = sum_i dx[i,j] a[i,k]
+        gemm(st, op_plain(dx_t, r, Mz), true, op_trans(c.b_t, r, Mz), false, r, r, r, ct, ea, "trimul da");
+        gemm(st, op_trans(dx_t, r, Mz), false, op_trans(c.a_t, r, Mz), false, r, r, r, ct, eb, "trimul db");
+      } else {
+        // da[k,i] = sum_j b[k,j] dx[i,j];  db[k,j] = sum_i a[k,i] dx[i,j]
+        gemm(st, op_plain(c.b_t, r, Mz), true, op_plain(dx_t, r, Mz), true, r, r, r, ct, ea, "trimul da");
+        gemm(st, op_plain(c.a_t, r, Mz), true, op_trans(dx_t, r, Mz), false, r, r, r, ct, eb, "trimul db");
+      }
+    }
+    if (!dry && !err) {
+      long long n = (long long)ct * Mz;
+      hipLaunchKernelGGL(tm_gate_bwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, c.proj_t, pair_mask,
+                         da_t, db_t, dproj_t, ct, Mz);
+      check("tm_gate_bwd");
+      // bias gradients: row sums of the channel-major projection gradients
+      const long long boff[4] = {p.b_ap, p.b_ag, p.b_bp, p.b_bg};
+      for (int k = 0; k < 4; k++) {
+        hipLaunchKernelGGL(rowsum_kernel<T>, dim3(ct), dim3(256), 0, st, dproj_t + (long long)k * ct * Mz, Mz,
+                           dparams + boff[k]);
+        check("rowsum");
+      }
+    }
+    k_colsum(st, ar, dgraw, Mz, cz, cz, p.b_g);
+    { ReduceSeg sg[4] = {{0, ct, p.w_ap, ct}, {ct, ct, p.w_ag, ct}, {2 * ct, ct, p.w_bp, ct}, {3 * ct, ct, p.w_bg, ct}};
+      gemm_dw(st, ar, op_trans(c.zhat, cz), false, op_plain(dproj_t, Mz), true, cz, 4 * ct, Mz, 4, sg, "trimul dWp"); }
+    { ReduceSeg sg[1] = {{0, cz, p.w_g, cz}};
+      gemm_dw(st, ar, op_trans(c.zhat, cz), false, op_trans(dgraw, cz), false, cz, cz, Mz, 1, sg, "trimul dWg"); }
+    { EpiGeneric<T> e = epi_plain<T>(dzh, cz);
+      gemm(st, op_trans(dproj_t, Mz), false, op_plain(w.wn_p, 4 * ct), true, (int)Mz, cz, 4 * ct, 1, e, "trimul dzhat p"); }
+    { EpiGeneric<T> e = epi_plain<T>(dzh, cz);
+      e.accumulate = 1;
+      gemm(st, op_plain(dgraw, cz), true, op_plain(w.wn_g, cz), true, (int)Mz, cz, cz, 1, e, "trimul dzhat g"); }
+    k_ln_bwd(st, ar, dzh, z, c.stats, p.ln_in_g, p.ln_in_b, g, g, Mz, cz);
+    ar.release(mk);
+  }
+
+  // MSA side backward.  gm_out receives d_msa_in; dz_bias receives the row-attention-bias
+  // term of d_pair_in.
+  void bwd_msa(const T* d_msa_out, const T* d_pair_out, T* gm, T* dz_bias) {
+    const int co = d.c_opm, r = d.r, cm = d.c_m, cz = d.c_z;
+    const long long Wd = (long long)r * co;
+    {  // outer product mean backward
+      size_t mk = am.mark();
+      T* dOs = (T*)am.alloc((size_t)Wd * Wd * sizeof(T));
+      T* dab = (T*)am.alloc((size_t)2 * Mm * co * sizeof(T));
+      T* dmh = (T*)am.alloc((size_t)Mm * cm * sizeof(T));
+      k_colsum(sm, am, d_pair_out, Mz, cz, cz, PL.opm.b_o);
+      {
+        Operand X;   // rows (p,q), contraction (i,j) over O[(i,p),(j,q)]
+        X.ptr = C.opm.O; X.batch_stride = 0;
+        X.x_in = co; X.x_outer = Wd; X.x_stride = 1;
+        X.k_in = r; X.k_outer = (long long)co * Wd; X.k_stride = co;
+        ReduceSeg sg[1] = {{0, cz, PL.opm.w_o, cz}};
+        gemm_dw(sm, am, X, false, op_trans(d_pair_out, cz), false, co * co, cz, Mz, 1, sg, "opm dWo");
+      }
+      {
+        EpiGeneric<T> e = epi_plain<T>(dOs, Wd);
+        e.om_in = r; e.om_outer = (long long)co * Wd; e.om_stride = co;
+        e.on_in = co; e.on_outer = Wd; e.on_stride = 1;
+        e.rowscale = C.opm.inv_norm;
+        gemm(sm, op_plain(d_pair_out, cz), true, op_plain(W.opm.wn_o, cz), true, (int)Mz, co * co, cz, 1, e, "opm dO");
+      }
+      {
+        EpiGeneric<T> e = epi_plain<T>(dab, Wd);
+        e.scale2d = msa_mask; e.s2_mdiv = 1; e.s2_ndiv = co; e.s2_ld = r;
+        gemm(sm, op_plain(C.opm.b, Wd), true, op_plain(dOs, Wd), true, d.s, (int)Wd, (int)Wd, 1, e, "opm da");
+        EpiGeneric<T> e2 = e;
+        e2.out = dab + Mm * co;
+        gemm(sm, op_plain(C.opm.a, Wd), true, op_trans(dOs, Wd), false, d.s, (int)Wd, (int)Wd, 1, e2, "opm db");
+      }
+      k_colsum(sm, am, dab, Mm, co, co, PL.opm.b_a);
+      k_colsum(sm, am, dab + Mm * co, Mm, co, co, PL.opm.b_b);
+      {
+        Operand Y;   // rows n = (which, c), contraction over MSA positions
+        Y.ptr = dab; Y.batch_stride = 0;
+        Y.x_in = co; Y.x_outer = Mm * co; Y.x_stride = 1;
+        Y.k_in = 1 << 30; Y.k_outer = 0; Y.k_stride = co;
+        ReduceSeg sg[2] = {{0, co, PL.opm.w_a, co}, {co, co, PL.opm.w_b, co}};
+        gemm_dw(sm, am, op_trans(C.opm.mhat, cm), false, Y, false, cm, 2 * co, Mm, 2, sg, "opm dWab");
+      }
+      {
+        Operand A;   // [Mm][2co] view of the two gradient halves
+        A.ptr = dab; A.batch_stride = 0;
+        A.x_in = 1 << 30; A.x_outer = 0; A.x_stride = co;
+        A.k_in = co; A.k_outer = Mm * co; A.k_stride = 1;
+        EpiGeneric<T> e = epi_plain<T>(dmh, cm);
+        gemm(sm, A, true, op_plain(W.opm.wn_ab, 2 * co), true, (int)Mm, cm, 2 * co, 1, e, "opm dmhat");
+      }
+      k_ln_bwd(sm, am, dmh, C.m3, C.opm.stats, PL.opm.ln_g, PL.opm.ln_b, d_msa_out, gm, Mm, cm);
+      am.release(mk);
+    }
+    trans_sub_bwd(sm, am, PL.mtrans, W.mt, C.mt, C.m2, gm, Mm, cm);
+    attn_sub_bwd(sm, am, PL.col, W.col, C.col, C.m1, gm, Mm, cm, d.h_msa, d.d_msa, geom_col(), nullptr, 0, 0, nullptr, nullptr);
+    attn_sub_bwd(sm, am, PL.row, W.row, C.row, msa_in, gm, Mm, cm, d.h_msa, d.d_msa, geom_row(), pair_in, PL.row.ln_z_g,
+                 PL.row.ln_z_b, nullptr, dz_bias);
+  }
+  void bwd_pair(const T* d_pair_out, T* gz) {
+    if (!dry && !err) {
+      if (hipMemcpyAsync(gz, d_pair_out, (size_t)Mz * d.c_z * sizeof(T), hipMemcpyDeviceToDevice, sp) != hipSuccess)
+        fail("copy gz");
+    }
+    trans_sub_bwd(sp, ap, PL.ptrans, W.pt, C.pt, C.z4, gz, Mz, d.c_z);
+    attn_sub_bwd(sp, ap, PL.tae, W.tae, C.tae, C.z3, gz, Mz, d.c_z, d.h_pair, d.d_pair, geom_tae(), C.z3, PL.tae.ln_g,
+                 PL.tae.ln_b, gz, gz);
+    attn_sub_bwd(sp, ap, PL.tas, W.tas, C.tas, C.z2, gz, Mz, d.c_z, d.h_pair, d.d_pair, geom_tas(), C.z2, PL.tas.ln_g,
+                 PL.tas.ln_b, gz, gz);
+    trimul_sub_bwd(sp, ap, PL.tmi, W.tmi, C.tmi, C.z1, gz, false);
+    trimul_sub_bwd(sp, ap, PL.tmo, W.tmo, C.tmo, pair_in, gz, true);
+  }
+};
+
+// ---------------------------------------------------------------------------
+// Plans: workspace layout = [prepared weights | MSA arena | pair arena | internal ctx]
+// ---------------------------------------------------------------------------
+struct Plan {
+  size_t prep_bytes, arena_m, arena_p, ctx_bytes;
+  size_t total(bool with_ctx) const { return prep_bytes + arena_m + arena_p + (with_ctx ? ctx_bytes : 0) + 1024; }
+};
+
+template <typename T> static Plan make_plan(const pe_dims& d) {
+  Runner<T> R;
+  R.h = nullptr;
+  R.init(d);
+  R.dry = true;
+  Plan pl;
+  pl.ctx_bytes = carve_ctx<T>(nullptr, d, R.C, nullptr);
+  pl.prep_bytes = R.carve_prep(nullptr);
+  // forward needs z5-independent scratch only from ctx; backward uses the arenas
+  R.fwd_msa(nullptr);
+  R.fwd_opm_project(nullptr, nullptr);
+  R.fwd_pair();
+  T* gm = (T*)R.am.alloc((size_t)R.Mm * d.c_m * sizeof(T));
+  T* dzb = (T*)R.am.alloc((size_t)R.Mz * d.c_z * sizeof(T));
+  R.bwd_msa(nullptr, nullptr, gm, dzb);
+  T* gz = (T*)R.ap.alloc((size_t)R.Mz * d.c_z * sizeof(T));
+  R.bwd_pair(nullptr, gz);
+  pl.arena_m = (R.am.high + 255) & ~(size_t)255;
+  pl.arena_p = (R.ap.high + 255) & ~(size_t)255;
+  return pl;
+}
+static Plan plan_for(const pe_dims& d) { return d.dtype == PE_BF16 ? make_plan<bf16>(d) : make_plan<float>(d); }
+
+template <typename T> static void setup_runner(Runner<T>& R, pe_handle* h, const pe_dims& d, const Plan& pl, char* ws,
+                                               char* ctx, hipStream_t sm, hipStream_t sp) {
+  R.h = h;
+  R.init(d);
+  R.sm = sm;
+  R.sp = sp;
+  R.carve_prep(ws);
+  R.am.base = ws + pl.prep_bytes;
+  R.ap.base = ws + pl.prep_bytes + pl.arena_m;
+  carve_ctx<T>(ctx ? ctx : ws + pl.prep_bytes + pl.arena_m + pl.arena_p, d, R.C, nullptr);
+}
+
+static bool hip_ok(pe_handle* h, hipError_t e, const char* what) {
+  if (e == hipSuccess) return true;
+  if (h) h->last_error = std::string(what) + ": " + hipGetErrorString(e);
+  return false;
+}
+
+template <typename T>
+static int block_fwd_impl(pe_handle* h, const pe_dims& d, const void* msa_in, const void* pair_in, const float* msa_mask,
+                          const float* pair_mask, const float* params, void* msa_out, void* pair_out, void* ctx,
+                          void* workspace, size_t wbytes, hipStream_t sm, hipStream_t sp) {
+  Plan pl = plan_for(d);
+  if (wbytes < pl.total(ctx == nullptr)) return PE_ERR_WORKSPACE;
+  Runner<T> R;
+  setup_runner<T>(R, h, d, pl, (char*)workspace, (char*)ctx, sm, sp);
+  R.params = params;
+  R.msa_in = (const T*)msa_in; R.pair_in = (const T*)pair_in;
+  R.msa_mask = msa_mask; R.pair_mask = pair_mask;
+  const bool two = sm != sp;
+  const bool do_m = h->branches & 1, do_p = h->branches & 2;
+  if (two) {
+    if (!hip_ok(h, hipEventRecord(h->ev[0], sm), "event record")) return PE_ERR_HIP;
+    if (!hip_ok(h, hipStreamWaitEvent(sp, h->ev[0], 0), "stream wait")) return PE_ERR_HIP;
+  }
+  if (do_p) R.fwd_pair();
+  if (do_m) R.fwd_msa((T*)msa_out);
+  if (two && do_p) {
+    if (!hip_ok(h, hipEventRecord(h->ev[1], sp), "event record")) return PE_ERR_HIP;
+    if (!hip_ok(h, hipStreamWaitEvent(sm, h->ev[1], 0), "stream wait")) return PE_ERR_HIP;
+  }
+  if (do_m && do_p) R.fwd_opm_project((T*)pair_out, R.C.z5);
+  else if (do_p && !R.err) {
+    if (!hip_ok(h, hipMemcpyAsync(pair_out, R.C.z5, (size_t)R.Mz * d.c_z * sizeof(T), hipMemcpyDeviceToDevice, sm),
+                "copy pair_out")) return PE_ERR_HIP;
+  }
+  if (two) {
+    if (!hip_ok(h, hipEventRecord(h->ev[2], sm), "event record")) return PE_ERR_HIP;
+    if (!hip_ok(h, hipStreamWaitEvent(sp, h->ev[2], 0), "stream wait")) return PE_ERR_HIP;
+  }
+  return R.err;
+}
+
+template <typename T>
+static int block_bwd_impl(pe_handle* h, const pe_dims& d, const void* msa_in, const void* pair_in, const float* msa_mask,
+                          const float* pair_mask, const float* params, const void* d_msa_out, const void* d_pair_out,
+                          void* d_msa_in, void* d_pair_in, float* d_params, const void* ctx, void* workspace,
+                          size_t wbytes, hipStream_t sm, hipStream_t sp) {
+  Plan pl = plan_for(d);
+  if (wbytes < pl.total(ctx == nullptr)) return PE_ERR_WORKSPACE;
+  const bool two = sm != sp;
+  const bool do_m = h->branches & 1, do_p = h->branches & 2;
+  Runner<T> R;
+  setup_runner<T>(R, h, d, pl, (char*)workspace, (char*)ctx, sm, sp);
+  R.params = params; R.dparams = d_params;
+  R.msa_in = (const T*)msa_in; R.pair_in = (const T*)pair_in;
+  R.msa_mask = msa_mask; R.pair_mask = pair_mask;
+  if (two) {
+    if (!hip_ok(h, hipEventRecord(h->ev[0], sm), "event record")) return PE_ERR_HIP;
+    if (!hip_ok(h, hipStreamWaitEvent(sp, h->ev[0], 0), "stream wait")) return PE_ERR_HIP;
+  }
+  if (ctx == nullptr) {   // recompute the forward into the internal ctx
+    if (do_p) R.fwd_pair();
+    if (do_m) R.fwd_msa(nullptr);
+    // the outer-product projection is not needed for the backward pass
+  } else {
+    if (do_p) R.run_prep(false);
+    if (do_m) R.run_prep(true);
+  }
+  T* dzb = (T*)R.am.alloc((size_t)R.Mz * d.c_z * sizeof(T));
+  T* gz = (T*)R.ap.alloc((size_t)R.Mz * d.c_z * sizeof(T));
+  if (do_p) R.bwd_pair((const T*)d_pair_out, gz);
+  if (do_m) R.bwd_msa((const T*)d_msa_out, (const T*)d_pair_out, (T*)d_msa_in, dzb);
+  if (two && do_m) {
+    if (!hip_ok(h, hipEventRecord(h->ev[1], sm), "event record")) return PE_ERR_HIP;
+    if (!hip_ok(h, hipStreamWaitEvent(sp, h->ev[1], 0), "stream wait")) return PE_ERR_HIP;
+  }
+  if (!R.err) {
+    long long n = R.Mz * d.c_z;
+    if (do_m && do_p) {
+      hipLaunchKernelGGL(add2_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, sp, gz, dzb, (T*)d_pair_in, n);
+      R.check("add d_pair_in");
+    } else if (do_p) {
+      if (!hip_ok(h, hipMemcpyAsync(d_pair_in, gz, (size_t)n * sizeof(T), hipMemcpyDeviceToDevice, sp), "copy")) return PE_ERR_HIP;
+    } else if (do_m) {
+      if (!hip_ok(h, hipMemcpyAsync(d_pair_in, dzb, (size_t)n * sizeof(T), hipMemcpyDeviceToDevice, sp), "copy")) return PE_ERR_HIP;
+    }
+  }
+  if (two) {
+    if (!hip_ok(h, hipEventRecord(h->ev[2], sp), "event record")) return PE_ERR_HIP;
+    if (!hip_ok(h, hipStreamWaitEvent(sm, h->ev[2], 0), "stream wait")) return PE_ERR_HIP;
+  }
+  return R.err;
+}
+
+
+// ---------------------------------------------------------------------------
+// Stack (trunk): saved block inputs + recompute in the backward pass
+// ---------------------------------------------------------------------------
+struct StackPlan {
+  size_t E;
+  size_t n_pair, n_msa, n_extra;        // bytes of one pair / msa / extra-msa tensor
+  size_t off_pair_saved, off_msa_saved, off_extra_saved, off_pp, off_block, block_bytes, total;
+};
+static size_t al256(size_t v) { return (v + 255) & ~(size_t)255; }
+static int make_stack_plan(int n_extra, const pe_dims* ex, int n_main, const pe_dims* mn, StackPlan& sp) {
+  if (n_extra < 0 || n_main < 0 || n_extra + n_main < 1) return PE_ERR_ARG;
+  if ((n_extra && !ex) || (n_main && !mn)) return PE_ERR_NULL;
+  if (n_extra && pe_check_dims(ex)) return PE_ERR_DIMS;
+  if (n_main && pe_check_dims(mn)) return PE_ERR_DIMS;
+  if (n_extra && n_main && (ex->r != mn->r || ex->c_z != mn->c_z || ex->dtype != mn->dtype)) return PE_ERR_DIMS;
+  const pe_dims* any = n_main ? mn : ex;
+  sp.E = any->dtype == PE_BF16 ? 2 : 4;
+  sp.n_pair = al256((size_t)any->r * any->r * any->c_z * sp.E);
+  sp.n_msa = n_main ? al256((size_t)mn->s * mn->r * mn->c_m * sp.E) : 0;
+  sp.n_extra = n_extra ? al256((size_t)ex->s * ex->r * ex->c_m * sp.E) : 0;
+  int nb = n_extra + n_main;
+  size_t off = 0;
+  sp.off_pair_saved = off; off += sp.n_pair * (size_t)(nb - 1);
+  sp.off_msa_saved = off; off += sp.n_msa * (size_t)(n_main > 0 ? n_main - 1 : 0);
+  sp.off_extra_saved = off; off += sp.n_extra * (size_t)n_extra;     // slot n_extra-1 = dropped final output
+  sp.off_pp = off; off += 2 * (sp.n_pair + sp.n_msa + sp.n_extra);   // ping-pong cotangents
+  sp.off_block = off;
+  size_t be = n_extra ? plan_for(*ex).total(true) : 0, bm = n_main ? plan_for(*mn).total(true) : 0;
+  sp.block_bytes = al256(be > bm ? be : bm);
+  sp.total = off + sp.block_bytes;
+  return PE_OK;
+}
+
+template <typename T>
+static int stack_impl(pe_handle* h, int n_extra, const pe_dims* ex, int n_main, const pe_dims* mn, const StackPlan& sp,
+                      const void* extra_msa_in, const void* msa_in, const void* pair_in, const float* extra_mask,
+                      const float* msa_mask, const float* pair_mask, const float* params, const void* d_msa_out,
+                      const void* d_pair_out, void* msa_out, void* pair_out, void* d_extra_msa_in, void* d_msa_in,
+                      void* d_pair_in, float* d_params, char* ws, hipStream_t sm, hipStream_t sp_) {
+  const int nb = n_extra + n_main;
+  const long long pe_n = n_extra ? pe_param_count(ex) : 0, pm_n = n_main ? pe_param_count(mn) : 0;
+  char* blockws = ws + sp.off_block;
+  auto pair_slot = [&](int b) -> char* { return ws + sp.off_pair_saved + sp.n_pair * (size_t)(b - 1); };   // input of block b>=1
+  auto x_in = [&](int b) -> const void* {
+    if (b < n_extra) return b == 0 ? extra_msa_in : (const void*)(ws + sp.off_extra_saved + sp.n_extra * (size_t)(b - 1));
+    int k = b - n_extra;
+    return k == 0 ? msa_in : (const void*)(ws + sp.off_msa_saved + sp.n_msa * (size_t)(k - 1));
+  };
+  auto z_in = [&](int b) -> const void* { return b == 0 ? pair_in : (const void*)pair_slot(b); };
+  auto poff = [&](int b) -> long long { return b < n_extra ? pe_n * b : pe_n * n_extra + pm_n * (b - n_extra); };
+  // forward
+  for (int b = 0; b < nb; b++) {
+    const bool is_e = b < n_extra;
+    const pe_dims& d = is_e ? *ex : *mn;
+    void* xo;
+    if (is_e) xo = ws + sp.off_extra_saved + sp.n_extra * (size_t)b;
+    else xo = (b == nb - 1) ? msa_out : (void*)(ws + sp.off_msa_saved + sp.n_msa * (size_t)(b - n_extra));
+    void* zo = (b == nb - 1) ? pair_out : (void*)pair_slot(b + 1);
+    int rc = block_fwd_impl<T>(h, d, x_in(b), z_in(b), is_e ? extra_mask : msa_mask, pair_mask, params + poff(b), xo, zo,
+                               nullptr, blockws, sp.block_bytes, sm, sp_);
+    if (rc) return rc;
+  }
+  // backward
+  char* pp = ws + sp.off_pp;
+  char* dz_pp[2] = {pp, pp + sp.n_pair};
+  char* dm_pp[2] = {pp + 2 * sp.n_pair, pp + 2 * sp.n_pair + sp.n_msa};
+  char* de_pp[2] = {pp + 2 * sp.n_pair + 2 * sp.n_msa, pp + 2 * sp.n_pair + 2 * sp.n_msa + sp.n_extra};
+  const void* dz = d_pair_out;
+  const void* dm = d_msa_out;
+  const void* de = nullptr;
+  if (n_extra) {
+    if (!hip_ok(h, hipMemsetAsync(de_pp[1], 0, sp.n_extra, sm), "memset")) return PE_ERR_HIP;
+    de = de_pp[1];
+  }
+  for (int b = nb - 1; b >= 0; b--) {
+    const bool is_e = b < n_extra;
+    const pe_dims& d = is_e ? *ex : *mn;
+    void* dz_in = (b == 0) ? d_pair_in : (void*)dz_pp[b & 1];
+    void* dx_in;
+    if (is_e) dx_in = (b == 0) ? d_extra_msa_in : (void*)de_pp[b & 1];
+    else dx_in = (b == n_extra) ? d_msa_in : (void*)dm_pp[b & 1];
+    int rc = block_bwd_impl<T>(h, d, x_in(b), z_in(b), is_e ? extra_mask : msa_mask, pair_mask, params + poff(b),
+                               is_e ? de : dm, dz, dx_in, dz_in, d_params + poff(b), nullptr, blockws, sp.block_bytes, sm,
+                               sp_);
+    if (rc) return rc;
+    dz = dz_in;
+    if (is_e) de = dx_in; else dm = dx_in;
+  }
+  return PE_OK;
+}
+
+// ---------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------
+static bool overlap(const void* a, size_t na, const void* b, size_t nb) {
+  const char* x = (const char*)a; const char* y = (const char*)b;
+  return x < y + nb && y < x + na;
+}
+
+extern "C" {
+
+int pe_create(pe_handle** out) {
+  if (!out) return PE_ERR_NULL;
+  pe_handle* h = new pe_handle();
+  h->branches = 3;
+  h->sync_debug = 0;
+  for (int i = 0; i < 6; i++) {
+    if (hipEventCreateWithFlags(&h->ev[i], hipEventDisableTiming) != hipSuccess) {
+      for (int j = 0; j < i; j++) (void)hipEventDestroy(h->ev[j]);
+      delete h;
+      return PE_ERR_HIP;
+    }
+  }
+  *out = h;
+  return PE_OK;
+}
+int pe_destroy(pe_handle* h) {
+  if (!h) return PE_ERR_NULL;
+  for (int i = 0; i < 6; i++) (void)hipEventDestroy(h->ev[i]);
+  delete h;
+  return PE_OK;
+}
+int pe_set_option(pe_handle* h, int option, int value) {
+  if (!h) return PE_ERR_NULL;
+  if (option == PE_OPT_BRANCHES) { if (value < 1 || value > 3) return PE_ERR_ARG; h->branches = value; return PE_OK; }
+  if (option == PE_OPT_SYNC_DEBUG) { h->sync_debug = value ? 1 : 0; return PE_OK; }
+  return PE_ERR_ARG;
+}
+int pe_check_dims(const pe_dims* d) {
+  int rc = pe_check_dims_impl(d);
+  if (rc) return rc;
+  if (d->col_global) return PE_ERR_DIMS;   // global column attention: not built yet
+  return PE_OK;
+}
+long long pe_param_count(const pe_dims* d) {
+  if (pe_check_dims_impl(d)) return -1;
+  ParamLayout L;
+  build_param_layout(*d, L);
+  return L.total;
+}
+int pe_param_table(const pe_dims* d, pe_param_entry* out, int cap) {
+  int rc = pe_check_dims_impl(d);
+  if (rc) return rc;
+  ParamLayout L;
+  build_param_layout(*d, L);
+  int n = (int)L.entries.size();
+  if (out) {
+    if (cap < n) return PE_ERR_ARG;
+    for (int i = 0; i < n; i++) out[i] = L.entries[i];
+  }
+  return n;
+}
+int pe_ctx_table(const pe_dims* d, pe_ctx_entry* out, int cap) {
+  int rc = pe_check_dims(d);
+  if (rc) return rc;
+  std::vector<pe_ctx_entry> rec;
+  if (d->dtype == PE_BF16) { Ctx<bf16> c; carve_ctx<bf16>(nullptr, *d, c, &rec); }
+  else { Ctx<float> c; carve_ctx<float>(nullptr, *d, c, &rec); }
+  int n = (int)rec.size();
+  if (out) {
+    if (cap < n) return PE_ERR_ARG;
+    for (int i = 0; i < n; i++) out[i] = rec[i];
+  }
+  return n;
+}
+size_t pe_ctx_bytes(const pe_dims* d) {
+  if (pe_check_dims(d)) return 0;
+  return plan_for(*d).ctx_bytes;
+}
+size_t pe_workspace_bytes(const pe_dims* d, int with_ctx) {
+  if (pe_check_dims(d)) return 0;
+  return plan_for(*d).total(with_ctx != 0);
+}
+
+int pe_block_fwd(pe_handle* h, const pe_dims* dims, const void* msa_in, const void* pair_in, const float* msa_mask,
+                 const float* pair_mask, const float* params, void* msa_out, void* pair_out, void* ctx, void* workspace,
+                 size_t workspace_bytes, void* stream_msa, void* stream_pair) {
+  if (!h || !dims || !msa_in || !pair_in || !msa_mask || !pair_mask || !params || !msa_out || !pair_out || !workspace)
+    return PE_ERR_NULL;
+  int rc = pe_check_dims(dims);
+  if (rc) return rc;
+  size_t E = dims->dtype == PE_BF16 ? 2 : 4;
+  size_t nm = (size_t)dims->s * dims->r * dims->c_m * E, nz = (size_t)dims->r * dims->r * dims->c_z * E;
+  if (overlap(msa_out, nm, msa_in, nm) || overlap(pair_out, nz, pair_in, nz) || overlap(msa_out, nm, pair_in, nz) ||
+      overlap(pair_out, nz, msa_in, nm) || overlap(msa_out, nm, pair_out, nz))
+    return PE_ERR_ALIAS;
+  if (((uintptr_t)workspace) % 256 || (ctx && ((uintptr_t)ctx) % 256)) return PE_ERR_ARG;
+  if (dims->dtype == PE_BF16)
+    return block_fwd_impl<bf16>(h, *dims, msa_in, pair_in, msa_mask, pair_mask, params, msa_out, pair_out, ctx, workspace,
+                                workspace_bytes, (hipStream_t)stream_msa, (hipStream_t)stream_pair);
+  return block_fwd_impl<float>(h, *dims, msa_in, pair_in, msa_mask, pair_mask, params, msa_out, pair_out, ctx, workspace,
+                               workspace_bytes, (hipStream_t)stream_msa, (hipStream_t)stream_pair);
+}
+
+int pe_block_bwd(pe_handle* h, const pe_dims* dims, const void* msa_in, const void* pair_in, const float* msa_mask,
+                 const float* pair_mask, const float* params, const void* d_msa_out, const void* d_pair_out,
+                 void* d_msa_in, void* d_pair_in, float* d_params, const void* ctx, void* workspace,
+                 size_t workspace_bytes, void* stream_msa, void* stream_pair) {
+  if (!h || !dims || !msa_in || !pair_in || !msa_mask || !pair_mask || !params || !d_msa_out || !d_pair_out ||
+      !d_msa_in || !d_pair_in || !d_params || !workspace)
+    return PE_ERR_NULL;
+  int rc = pe_check_dims(dims);
+  if (rc) return rc;
+  size_t E = dims->dtype == PE_BF16 ? 2 : 4;
+  size_t nm = (size_t)dims->s * dims->r * dims->c_m * E, nz = (size_t)dims->r * dims->r * dims->c_z * E;
+  if (overlap(d_msa_in, nm, msa_in, nm) || overlap(d_pair_in, nz, pair_in, nz) || overlap(d_msa_in, nm, d_msa_out, nm) ||
+      overlap(d_pair_in, nz, d_pair_out, nz) || overlap(d_msa_in, nm, d_pair_in, nz))
+    return PE_ERR_ALIAS;
+  if (((uintptr_t)workspace) % 256 || (ctx && ((uintptr_t)ctx) % 256)) return PE_ERR_ARG;
+  if (dims->dtype == PE_BF16)
+    return block_bwd_impl<bf16>(h, *dims, msa_in, pair_in, msa_mask, pair_mask, params, d_msa_out, d_pair_out, d_msa_in,
+                                d_pair_in, d_params, ctx, workspace, workspace_bytes, (hipStream_t)stream_msa,
+                                (hipStream_t)stream_pair);
+  return block_bwd_impl<float>(h, *dims, msa_in, pair_in, msa_mask, pair_mask, params, d_msa_out, d_pair_out, d_msa_in,
+                               d_pair_in, d_params, ctx, workspace, workspace_bytes, (hipStream_t)stream_msa,
+                               (hipStream_t)stream_pair);
+}
+
+size_t pe_stack_workspace_bytes(int n_extra, const pe_dims* extra, int n_main, const pe_dims* main_) {
+  StackPlan sp;
+  if (make_stack_plan(n_extra, extra, n_main, main_, sp)) return 0;
+  return sp.total;
+}
+
+int pe_stack_fwd_bwd(pe_handle* h, int n_extra, const pe_dims* extra, int n_main, const pe_dims* main_,
+                     const void* extra_msa_in, const void* msa_in, const void* pair_in, const float* extra_msa_mask,
+                     const float* msa_mask, const float* pair_mask, const float* params, const void* d_msa_out,
+                     const void* d_pair_out, void* msa_out, void* pair_out, void* d_extra_msa_in, void* d_msa_in,
+                     void* d_pair_in, float* d_params, void* workspace, size_t workspace_bytes, void* stream_msa,
+                     void* stream_pair) {
+  if (!h || !pair_in || !pair_mask || !params || !d_pair_out || !pair_out || !d_pair_in || !d_params || !workspace)
+    return PE_ERR_NULL;
+  StackPlan sp;
+  int rc = make_stack_plan(n_extra, extra, n_main, main_, sp);
+  if (rc) return rc;
+  if (n_extra && (!extra_msa_in || !extra_msa_mask || !d_extra_msa_in)) return PE_ERR_NULL;
+  if (n_main && (!msa_in || !msa_mask || !d_msa_out || !msa_out || !d_msa_in)) return PE_ERR_NULL;
+  if (((uintptr_t)workspace) % 256) return PE_ERR_ARG;
+  if (workspace_bytes < sp.total) return PE_ERR_WORKSPACE;
+  if (overlap(pair_out, sp.n_pair, pair_in, sp.n_pair) || overlap(d_pair_in, sp.n_pair, d_pair_out, sp.n_pair) ||
+      overlap(d_pair_in, sp.n_pair, pair_in, sp.n_pair))
+    return PE_ERR_ALIAS;
+  if (n_main && (overlap(msa_out, sp.n_msa, msa_in, sp.n_msa) || overlap(d_msa_in, sp.n_msa, d_msa_out, sp.n_msa) ||
+                 overlap(d_msa_in, sp.n_msa, msa_in, sp.n_msa)))
+    return PE_ERR_ALIAS;
+  const int dt = n_main ? main_->dtype : extra->dtype;
+  if (dt == PE_BF16)
+    return stack_impl<bf16>(h, n_extra, extra, n_main, main_, sp, extra_msa_in, msa_in, pair_in, extra_msa_mask, msa_mask,
+                            pair_mask, params, d_msa_out, d_pair_out, msa_out, pair_out, d_extra_msa_in, d_msa_in,
+                            d_pair_in, d_params, (char*)workspace, (hipStream_t)stream_msa, (hipStream_t)stream_pair);
+  return stack_impl<float>(h, n_extra, extra, n_main, main_, sp, extra_msa_in, msa_in, pair_in, extra_msa_mask, msa_mask,
+                           pair_mask, params, d_msa_out, d_pair_out, msa_out, pair_out, d_extra_msa_in, d_msa_in,
+                           d_pair_in, d_params, (char*)workspace, (hipStream_t)stream_msa, (hipStream_t)stream_pair);
+}
+
+const char* pe_strerror(int code) {
+  switch (code) {
+    case PE_OK: return "ok";
+    case PE_ERR_NULL: return "required pointer is NULL";
+    case PE_ERR_DIMS: return "unsupported dims";
+    case PE_ERR_WORKSPACE: return "workspace too small";
+    case PE_ERR_ALIAS: return "output aliases an input or another output";
+    case PE_ERR_HIP: return "HIP error (see pe_last_error)";
+    case PE_ERR_ARG: return "bad argument";
+    default: return "unknown error";
+  }
+}
+const char* pe_last_error(pe_handle* h) { return h ? h->last_error.c_str() : ""; }
+
+}  // extern "C"

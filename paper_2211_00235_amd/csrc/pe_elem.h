@@ -1,0 +1,501 @@
+// HBM-bound kernels of the block: LayerNorm (forward / backward, channel-last and
+// channel-major), the pair-bias projection fused with its LayerNorm, gating of the
+// triangle-multiplication projections, reductions for parameter gradients, parameter
+// preparation (fp32 -> storage type, transposed copies).
+//
+// Row-wise kernels give one row to one 64-lane wave: lane l holds channels
+// c = (ch*64 + l)*4 + 0..3 for ch < NCH (8- or 16-byte loads), row statistics are wave
+// reductions, per-channel parameter-gradient partial sums stay in registers over the
+// wave's rows and are written once per workgroup as fp32 partials; a second small
+// kernel reduces the partials in a fixed order (deterministic, no atomics).
+#pragma once
+#include "pe_common.h"
+
+constexpr int LN_NCH = 4;          // channels <= 64*4*LN_NCH = 1024
+constexpr int LN_MAX_WG = 512;     // workgroups (x4 waves) of the row-wise backward kernels
+
+template <typename T> PE_DEV void load4(const T* p, float (&v)[4]);
+template <> PE_DEV void load4<float>(const float* p, float (&v)[4]) {
+  f32x4 t = *reinterpret_cast<const f32x4*>(p);
+  v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+}
+template <> PE_DEV void load4<bf16>(const bf16* p, float (&v)[4]) {
+  bf16x4 t = *reinterpret_cast<const bf16x4*>(p);
+  v[0] = (float)t[0]; v[1] = (float)t[1]; v[2] = (float)t[2]; v[3] = (float)t[3];
+}
+template <typename T> PE_DEV void store4(T* p, const float (&v)[4]);
+template <> PE_DEV void store4<float>(float* p, const float (&v)[4]) {
+  f32x4 t; t[0] = v[0]; t[1] = v[1]; t[2] = v[2]; t[3] = v[3];
+  *reinterpret_cast<f32x4*>(p) = t;
+}
+template <> PE_DEV void store4<bf16>(bf16* p, const float (&v)[4]) {
+  bf16x4 t; t[0] = (bf16)v[0]; t[1] = (bf16)v[1]; t[2] = (bf16)v[2]; t[3] = (bf16)v[3];
+  *reinterpret_cast<bf16x4*>(p) = t;
+}
+
+// ---------------------------------------------------------------------------
+// LayerNorm forward, channel-last: y = (x - mu) * rstd * gamma + beta; stats = (mu, rstd)
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const T* x, const float* gamma, const float* beta, T* y,
+                                                     float* stats, long long M, int C, float eps) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float gm[LN_NCH][4], bt[LN_NCH][4];
+#pragma unroll
+  for (int ch = 0; ch < LN_NCH; ch++) {
+    int c = (ch * 64 + lane) * 4;
+#pragma unroll
+    for (int e = 0; e < 4; e++) { gm[ch][e] = (c < C) ? gamma[c + e] : 0.0f; bt[ch][e] = (c < C) ? beta[c + e] : 0.0f; }
+  }
+  for (long long row = (long long)blockIdx.x * 4 + wave; row < M; row += (long long)gridDim.x * 4) {
+    float v[LN_NCH][4];
+    float s = 0.0f;
+#pragma unroll
+    for (int ch = 0; ch < LN_NCH; ch++) {
+      int c = (ch * 64 + lane) * 4;
+      if (c < C) load4<T>(x + row * C + c, v[ch]);
+      else { v[ch][0] = v[ch][1] = v[ch][2] = v[ch][3] = 0.0f; }
+      s += v[ch][0] + v[ch][1] + v[ch][2] + v[ch][3];
+    }
+    float mu = wave_sum(s) / C;
+    float q = 0.0f;
+#pragma unroll
+    for (int ch = 0; ch < LN_NCH; ch++) {
+      int c = (ch * 64 + lane) * 4;
+      if (c < C) {
+#pragma unroll
+        for (int e = 0; e < 4; e++) { float t = v[ch][e] - mu; q += t * t; }
+      }
+    }
+    float rstd = rsqrtf(wave_sum(q) / C + eps);
+#pragma unroll
+    for (int ch = 0; ch < LN_NCH; ch++) {
+      int c = (ch * 64 + lane) * 4;
+      if (c < C) {
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; e++) o[e] = (v[ch][e] - mu) * rstd * gm[ch][e] + bt[ch][e];
+        store4<T>(y + row * C + c, o);
+      }
+    }
+    if (lane == 0) { stats[row * 2] = mu; stats[row * 2 + 1] = rstd; }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// LayerNorm backward, channel-last.
+//   dx = (dxh - mean(dxh) - xh * mean(dxh * xh)) * rstd,  dxh = dy * gamma
+//   gout = (gin ? gin : 0) + dx;  partial[wg][0:C] = sum dy*xh, partial[wg][C:2C] = sum dy
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void ln_bwd_kernel(const T* dy, const T* x, const float* stats, const float* gamma,
+                                                     const T* gin, T* gout, float* partial, long long M, int C) {
+  __shared__ float red[4][2 * 64 * 4 * LN_NCH];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float gm[LN_NCH][4], dgs[LN_NCH][4], dbs[LN_NCH][4];
+#pragma unroll
+  for (int ch = 0; ch < LN_NCH; ch++) {
+    int c = (ch * 64 + lane) * 4;
+#pragma unroll
+    for (int e = 0; e < 4; e++) { gm[ch][e] = (c < C) ? gamma[c + e] : 0.0f; dgs[ch][e] = 0.0f; dbs[ch][e] = 0.0f; }
+  }
+  for (long long row = (long long)blockIdx.x * 4 + wave; row < M; row += (long long)gridDim.x * 4) {
+    float mu = stats[row * 2], rstd = stats[row * 2 + 1];
+    float xh[LN_NCH][4], dxh[LN_NCH][4];
+    float s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+    for (int ch = 0; ch < LN_NCH; ch++) {
+      int c = (ch * 64 + lane) * 4;
+      if (c < C) {
+        float xv[4], dv[4];
+        load4<T>(x + row * C + c, xv);
+        load4<T>(dy + row * C + c, dv);
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          xh[ch][e] = (xv[e] - mu) * rstd;
+          dxh[ch][e] = dv[e] * gm[ch][e];
+          dgs[ch][e] += dv[e] * xh[ch][e];
+          dbs[ch][e] += dv[e];
+          s1 += dxh[ch][e];
+          s2 += dxh[ch][e] * xh[ch][e];
+        }
+      }
+    }
+    s1 = wave_sum(s1) / C;
+    s2 = wave_sum(s2) / C;
+#pragma unroll
+    for (int ch = 0; ch < LN_NCH; ch++) {
+      int c = (ch * 64 + lane) * 4;
+      if (c < C) {
+        float o[4];
+        if (gin) load4<T>(gin + row * C + c, o);
+        else { o[0] = o[1] = o[2] = o[3] = 0.0f; }
+#pragma unroll
+        for (int e = 0; e < 4; e++) o[e] += (dxh[ch][e] - s1 - xh[ch][e] * s2) * rstd;
+        store4<T>(gout + row * C + c, o);
+      }
+    }
+  }
+  // cross-wave reduction of the parameter-gradient partials
+#pragma unroll
+  for (int ch = 0; ch < LN_NCH; ch++)
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+      int c = (ch * 64 + lane) * 4 + e;
+      red[wave][c] = dgs[ch][e];
+      red[wave][64 * 4 * LN_NCH + c] = dbs[ch][e];
+    }
+  __syncthreads();
+  for (int c = threadIdx.x; c < C; c += 256) {
+    float a = 0.0f, b = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 4; w++) { a += red[w][c]; b += red[w][64 * 4 * LN_NCH + c]; }
+    partial[(long long)blockIdx.x * 2 * C + c] = a;
+    partial[(long long)blockIdx.x * 2 * C + C + c] = b;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// LayerNorm over channels of a CHANNEL-MAJOR tensor x_t[C][M] (triangle-multiplication
+// contraction output), producing channel-last y[M][C].  A workgroup handles 64
+// consecutive positions: thread (p = tid%64, part = tid/64) walks channels part, part+4, ..
+// (coalesced along positions), tile transposed through LDS for the channel-last store.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void ln_cmajor_fwd_kernel(const T* xt, const float* gamma, const float* beta, T* y,
+                                                            float* stats, long long M, int C, float eps) {
+  extern __shared__ float tile[];   // [64][C+1]
+  __shared__ float rs[4][64], rq[4][64];
+  const int p = threadIdx.x & 63, part = threadIdx.x >> 6;
+  const long long m0 = (long long)blockIdx.x * 64;
+  const long long m = m0 + p;
+  float s = 0.0f;
+  for (int c = part; c < C; c += 4) {
+    float v = (m < M) ? to_f(xt[(long long)c * M + m]) : 0.0f;
+    tile[p * (C + 1) + c] = v;
+    s += v;
+  }
+  rs[part][p] = s;
+  __syncthreads();
+  float mu = (rs[0][p] + rs[1][p] + rs[2][p] + rs[3][p]) / C;
+  float q = 0.0f;
+  for (int c = part; c < C; c += 4) { float t = tile[p * (C + 1) + c] - mu; q += t * t; }
+  rq[part][p] = q;
+  __syncthreads();
+  float rstd = rsqrtf((rq[0][p] + rq[1][p] + rq[2][p] + rq[3][p]) / C + eps);
+  if (part == 0 && m < M) { stats[m * 2] = mu; stats[m * 2 + 1] = rstd; }
+  // channel-last store: thread t handles channel c = t % C.. for rows
+  for (int idx = threadIdx.x; idx < 64 * C; idx += 256) {
+    int pp = idx / C, c = idx % C;
+    long long mm = m0 + pp;
+    if (mm < M) {
+      float mu2 = (rs[0][pp] + rs[1][pp] + rs[2][pp] + rs[3][pp]) / C;
+      float rstd2 = rsqrtf((rq[0][pp] + rq[1][pp] + rq[2][pp] + rq[3][pp]) / C + eps);
+      y[mm * C + c] = from_f<T>((tile[pp * (C + 1) + c] - mu2) * rstd2 * gamma[c] + beta[c]);
+    }
+  }
+}
+
+// backward: dy[M][C] channel-last, x_t[C][M] channel-major, -> dx_t[C][M]; partial[wg][2C]
+template <typename T>
+__global__ __launch_bounds__(256) void ln_cmajor_bwd_kernel(const T* dy, const T* xt, const float* stats,
+                                                            const float* gamma, T* dxt, float* partial, long long M,
+                                                            int C) {
+  extern __shared__ float tile[];   // dy tile [64][C+1]
+  __shared__ float r1[4][64], r2[4][64];
+  const int p = threadIdx.x & 63, part = threadIdx.x >> 6;
+  const long long m0 = (long long)blockIdx.x * 64;
+  const long long m = m0 + p;
+  for (int idx = threadIdx.x; idx < 64 * C; idx += 256) {
+    int pp = idx / C, c = idx % C;
+    long long mm = m0 + pp;
+    tile[pp * (C + 1) + c] = (mm < M) ? to_f(dy[mm * C + c]) : 0.0f;
+  }
+  __syncthreads();
+  float mu = (m < M) ? stats[m * 2] : 0.0f, rstd = (m < M) ? stats[m * 2 + 1] : 0.0f;
+  float s1 = 0.0f, s2 = 0.0f;
+  for (int c = part; c < C; c += 4) {
+    float xh = (m < M) ? (to_f(xt[(long long)c * M + m]) - mu) * rstd : 0.0f;
+    float dxh = tile[p * (C + 1) + c] * gamma[c];
+    s1 += dxh;
+    s2 += dxh * xh;
+  }
+  r1[part][p] = s1;
+  r2[part][p] = s2;
+  __syncthreads();
+  s1 = (r1[0][p] + r1[1][p] + r1[2][p] + r1[3][p]) / C;
+  s2 = (r2[0][p] + r2[1][p] + r2[2][p] + r2[3][p]) / C;
+  for (int c = part; c < C; c += 4) {
+    float xh = (m < M) ? (to_f(xt[(long long)c * M + m]) - mu) * rstd : 0.0f;
+    float dv = tile[p * (C + 1) + c];
+    float dxh = dv * gamma[c];
+    if (m < M) dxt[(long long)c * M + m] = from_f<T>((dxh - s1 - xh * s2) * rstd);
+    // per-channel partials over the 64 positions: wave reduction (a wave = one `part`)
+    float a = wave_sum(dv * xh), b = wave_sum(dv);
+    if (p == 0) {
+      partial[(long long)blockIdx.x * 2 * C + c] = a;
+      partial[(long long)blockIdx.x * 2 * C + C + c] = b;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Pair-bias projection fused with its LayerNorm: bias[h][i][j] = (LN(z_ij) W)_h
+// (transposed: bias[h][j][i]).  C <= 256 (one 4-channel chunk per lane).
+// ---------------------------------------------------------------------------
+constexpr int BIAS_MAXH = 8;
+template <typename T>
+__global__ __launch_bounds__(256) void ln_bias_fwd_kernel(const T* z, const float* gamma, const float* beta,
+                                                          const float* w /*[C][H]*/, float* bias, float* stats, int r,
+                                                          int C, int H, float eps, int transposed) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane * 4;
+  float gm[4], bt[4], wv[4][BIAS_MAXH];
+#pragma unroll
+  for (int e = 0; e < 4; e++) {
+    gm[e] = (c < C) ? gamma[c + e] : 0.0f;
+    bt[e] = (c < C) ? beta[c + e] : 0.0f;
+#pragma unroll
+    for (int h = 0; h < BIAS_MAXH; h++) wv[e][h] = (c < C && h < H) ? w[(c + e) * H + h] : 0.0f;
+  }
+  const long long M = (long long)r * r;
+  for (long long row = (long long)blockIdx.x * 4 + wave; row < M; row += (long long)gridDim.x * 4) {
+    float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (c < C) load4<T>(z + row * C + c, v);
+    float mu = wave_sum(v[0] + v[1] + v[2] + v[3]) / C;
+    float q = 0.0f;
+    if (c < C) {
+#pragma unroll
+      for (int e = 0; e < 4; e++) { float t = v[e] - mu; q += t * t; }
+    }
+    float rstd = rsqrtf(wave_sum(q) / C + eps);
+    float y[4];
+#pragma unroll
+    for (int e = 0; e < 4; e++) y[e] = (c < C) ? (v[e] - mu) * rstd * gm[e] + bt[e] : 0.0f;
+    int i = row / r, j = row % r;
+    long long o = transposed ? ((long long)j * r + i) : row;
+#pragma unroll
+    for (int h = 0; h < BIAS_MAXH; h++) {
+      if (h < H) {
+        float t = y[0] * wv[0][h] + y[1] * wv[1][h] + y[2] * wv[2][h] + y[3] * wv[3][h];
+        t = wave_sum(t);
+        if (lane == 0) bias[(long long)h * M + o] = t;
+      }
+    }
+    if (lane == 0) { stats[row * 2] = mu; stats[row * 2 + 1] = rstd; }
+  }
+}
+
+// backward: dy_c = sum_h dbias[h][row] W[c][h]; LayerNorm backward -> gout = gin + dz;
+// partial[wg] = [ dgamma (C) | dbeta (C) | dW (C*H) ]
+template <typename T>
+__global__ __launch_bounds__(256) void ln_bias_bwd_kernel(const float* dbias, const T* z, const float* stats,
+                                                          const float* gamma, const float* beta, const float* w,
+                                                          const T* gin, T* gout, float* partial, int r, int C, int H,
+                                                          int transposed) {
+  __shared__ float red[4][256 * (2 + BIAS_MAXH)];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane * 4;
+  float gm[4], bt[4], wv[4][BIAS_MAXH], dgs[4], dbs[4], dws[4][BIAS_MAXH];
+#pragma unroll
+  for (int e = 0; e < 4; e++) {
+    gm[e] = (c < C) ? gamma[c + e] : 0.0f;
+    bt[e] = (c < C) ? beta[c + e] : 0.0f;
+    dgs[e] = 0.0f; dbs[e] = 0.0f;
+#pragma unroll
+    for (int h = 0; h < BIAS_MAXH; h++) { wv[e][h] = (c < C && h < H) ? w[(c + e) * H + h] : 0.0f; dws[e][h] = 0.0f; }
+  }
+  const long long M = (long long)r * r;
+  for (long long row = (long long)blockIdx.x * 4 + wave; row < M; row += (long long)gridDim.x * 4) {
+    float mu = stats[row * 2], rstd = stats[row * 2 + 1];
+    int i = row / r, j = row % r;
+    long long o = transposed ? ((long long)j * r + i) : row;
+    float db[BIAS_MAXH];
+#pragma unroll
+    for (int h = 0; h < BIAS_MAXH; h++) db[h] = (h < H) ? dbias[(long long)h * M + o] : 0.0f;
+    float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (c < C) load4<T>(z + row * C + c, v);
+    float xh[4], dxh[4];
+    float s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+      xh[e] = (c < C) ? (v[e] - mu) * rstd : 0.0f;
+      float y = xh[e] * gm[e] + bt[e];
+      float dy = 0.0f;
+#pragma unroll
+      for (int h = 0; h < BIAS_MAXH; h++) { dy += db[h] * wv[e][h]; dws[e][h] += y * db[h]; }
+      dxh[e] = dy * gm[e];
+      dgs[e] += dy * xh[e];
+      dbs[e] += dy;
+      s1 += dxh[e];
+      s2 += dxh[e] * xh[e];
+    }
+    s1 = wave_sum(s1) / C;
+    s2 = wave_sum(s2) / C;
+    if (c < C) {
+      float ov[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      if (gin) load4<T>(gin + row * C + c, ov);
+#pragma unroll
+      for (int e = 0; e < 4; e++) ov[e] += (dxh[e] - s1 - xh[e] * s2) * rstd;
+      store4<T>(gout + row * C + c, ov);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 4; e++) {
+    red[wave][c + e] = dgs[e];
+    red[wave][256 + c + e] = dbs[e];
+#pragma unroll
+    for (int h = 0; h < BIAS_MAXH; h++) red[wave][512 + (c + e) * BIAS_MAXH + h] = dws[e][h];
+  }
+  __syncthreads();
+  float* pp = partial + (long long)blockIdx.x * (2 * C + C * H);
+  for (int t = threadIdx.x; t < C; t += 256) {
+    pp[t] = red[0][t] + red[1][t] + red[2][t] + red[3][t];
+    pp[C + t] = red[0][256 + t] + red[1][256 + t] + red[2][256 + t] + red[3][256 + t];
+  }
+  for (int t = threadIdx.x; t < C * H; t += 256) {
+    int cc = t / H, h = t % H;
+    int k = 512 + cc * BIAS_MAXH + h;
+    pp[2 * C + t] = red[0][k] + red[1][k] + red[2][k] + red[3][k];
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Reductions for parameter gradients
+// ---------------------------------------------------------------------------
+// dst[seg] += sum_s part[s][idx]; the [rows][cols] result is scattered by column segments
+struct ReduceSeg { int n_begin, n_count; long long dst_off; int dst_ld; };
+struct ReduceArgs {
+  const float* part; int nsplit; long long stride;   // partial s at part + s*stride
+  int rows, cols;
+  int nseg; ReduceSeg seg[5];
+  float* dst;
+};
+__global__ void reduce_partials_kernel(ReduceArgs a) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  long long total = (long long)a.rows * a.cols;
+  if (idx >= total) return;
+  int m = idx / a.cols, n = idx % a.cols;
+  float s = 0.0f;
+  for (int k = 0; k < a.nsplit; k++) s += a.part[(long long)k * a.stride + idx];
+  for (int q = 0; q < a.nseg; q++) {
+    const ReduceSeg& g = a.seg[q];
+    if (n >= g.n_begin && n < g.n_begin + g.n_count) {
+      a.dst[g.dst_off + (long long)m * g.dst_ld + (n - g.n_begin)] += s;
+      break;
+    }
+  }
+}
+
+// column sums of a channel-last tensor y[M][N] (row stride ld): partial[wg][N]
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_kernel(const T* y, long long M, int N, long long ld, float* partial,
+                                                     long long rows_per_wg) {
+  long long r0 = (long long)blockIdx.x * rows_per_wg;
+  long long r1 = r0 + rows_per_wg < M ? r0 + rows_per_wg : M;
+  for (int n = threadIdx.x; n < N; n += 256) {
+    float s = 0.0f;
+    for (long long m = r0; m < r1; m++) s += to_f(y[m * ld + n]);
+    partial[(long long)blockIdx.x * N + n] = s;
+  }
+}
+
+// row sums of a channel-major tensor yt[N][M]: dst[n] += sum_m yt[n][m]  (one workgroup per row)
+template <typename T>
+__global__ __launch_bounds__(256) void rowsum_kernel(const T* yt, long long M, float* dst) {
+  __shared__ float red[4];
+  const T* p = yt + (long long)blockIdx.x * M;
+  float s = 0.0f;
+  for (long long m = threadIdx.x; m < M; m += 256) s += to_f(p[m]);
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) dst[blockIdx.x] += red[0] + red[1] + red[2] + red[3];
+}
+
+// ---------------------------------------------------------------------------
+// Parameter preparation: dst[r*ld_r + c*ld_c] = T(src[r*cols + c])
+// ---------------------------------------------------------------------------
+struct PrepDesc { long long src_off, dst_off; int rows, cols; long long ld_r, ld_c; };
+constexpr int PREP_MAX = 32;
+struct PrepBatch { PrepDesc d[PREP_MAX]; int n; };
+template <typename T>
+__global__ void prep_params_kernel(const float* params, T* dst, PrepBatch pb) {
+  const PrepDesc& d = pb.d[blockIdx.y];
+  long long total = (long long)d.rows * d.cols;
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (long long)gridDim.x * blockDim.x) {
+    int r = idx / d.cols, c = idx % d.cols;
+    dst[d.dst_off + r * d.ld_r + c * d.ld_c] = from_f<T>(params[d.src_off + idx]);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Triangle multiplication gating (channel-major tensors [c][M]):
+//   proj_t rows: [0,ct) a-projection, [ct,2ct) a-gate, [2ct,3ct) b-projection, [3ct,4ct) b-gate
+//   a = mask * sigmoid(ag) * ap,  b likewise
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ void tm_gate_fwd_kernel(const T* proj_t, const float* mask, T* a_t, T* b_t, int ct, long long M) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long long)ct * M) return;
+  long long m = idx % M;
+  int c = idx / M;
+  float mk = mask[m];
+  float ap = to_f(proj_t[(long long)c * M + m]), ag = to_f(proj_t[(long long)(ct + c) * M + m]);
+  float bp = to_f(proj_t[(long long)(2 * ct + c) * M + m]), bg = to_f(proj_t[(long long)(3 * ct + c) * M + m]);
+  a_t[idx] = from_f<T>(mk * sigmoidf_(ag) * ap);
+  b_t[idx] = from_f<T>(mk * sigmoidf_(bg) * bp);
+}
+template <typename T>
+__global__ void tm_gate_bwd_kernel(const T* proj_t, const float* mask, const T* da_t, const T* db_t, T* dproj_t, int ct,
+                                   long long M) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long long)ct * M) return;
+  long long m = idx % M;
+  int c = idx / M;
+  float mk = mask[m];
+  float ap = to_f(proj_t[(long long)c * M + m]), sa = sigmoidf_(to_f(proj_t[(long long)(ct + c) * M + m]));
+  float bp = to_f(proj_t[(long long)(2 * ct + c) * M + m]), sb = sigmoidf_(to_f(proj_t[(long long)(3 * ct + c) * M + m]));
+  float da = to_f(da_t[idx]) * mk, db = to_f(db_t[idx]) * mk;
+  dproj_t[(long long)c * M + m] = from_f<T>(da * sa);
+  dproj_t[(long long)(ct + c) * M + m] = from_f<T>(da * ap * sa * (1.0f - sa));
+  dproj_t[(long long)(2 * ct + c) * M + m] = from_f<T>(db * sb);
+  dproj_t[(long long)(3 * ct + c) * M + m] = from_f<T>(db * bp * sb * (1.0f - sb));
+}
+// output gate backward: du = G * g, dgraw = G * u * g * (1 - g)
+template <typename T>
+__global__ void tm_out_bwd_kernel(const T* G, const T* g, const T* u, T* du, T* dgraw, long long n) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n) return;
+  float gv = to_f(g[idx]), Gv = to_f(G[idx]), uv = to_f(u[idx]);
+  du[idx] = from_f<T>(Gv * gv);
+  dgraw[idx] = from_f<T>(Gv * uv * gv * (1.0f - gv));
+}
+
+// ---------------------------------------------------------------------------
+// Outer product mean normaliser: inv_norm[i][j] = 1 / (eps + sum_s mask[s][i] mask[s][j])
+// ---------------------------------------------------------------------------
+__global__ void opm_norm_kernel(const float* mask, float* inv_norm, int s, int r, float eps) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long long)r * r) return;
+  int i = idx / r, j = idx % r;
+  float acc = 0.0f;
+  for (int t = 0; t < s; t++) acc += mask[(long long)t * r + i] * mask[(long long)t * r + j];
+  inv_norm[idx] = 1.0f / (eps + acc);
+}
+
+template <typename T>
+__global__ void add2_kernel(const T* a, const T* b, T* out, long long n) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < n) out[idx] = from_f<T>(to_f(a[idx]) + to_f(b[idx]));
+}
+// rows of y[M][N] (row stride ld) scaled by a per-row fp32 factor, in place
+template <typename T>
+__global__ void rowscale_kernel(T* y, const float* scale, long long M, int N, long long ld) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= M * N) return;
+  long long m = idx / N;
+  int n = idx % N;
+  y[m * ld + n] = from_f<T>(to_f(y[m * ld + n]) * scale[m]);
+}

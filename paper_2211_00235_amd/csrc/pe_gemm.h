@@ -1,0 +1,293 @@
+// Tiled MFMA GEMM for gfx950 used by every linear layer (forward, dX, dW), by the
+// triangle-multiplication contraction and by the outer-product-mean contractions.
+//
+//   C[b][m][n] = epilogue( sum_k A[b][m][k] * B[b][n][k] )
+//
+// Both operands are addressed as (row x, contraction k) through a two-level
+// index map, so that plain matrices, transposed matrices, channel-major tensors
+// and the [(i,p),(j,q)] outer-product layout are all reachable without copies:
+//   addr(x,k) = (x / x_in) * x_outer + (x % x_in) * x_stride
+//             + (k / k_in) * k_outer + (k % k_in) * k_stride
+// An operand is either "k-contiguous" (k_stride == 1, 16-byte loads along k) or
+// "x-contiguous" (x_stride == 1, 16-byte loads along x, transposed in registers
+// on the way into LDS).  LDS always holds k-contiguous rows, which is what the
+// 32x32 MFMA operand fragments want.
+//
+// Workgroup: 256 threads = 4 waves in a 2x2 grid; block tile 128x128; each wave
+// owns 64x64 = 2x2 MFMA tiles (64 accumulator VGPRs).  Next k-tile is prefetched
+// into registers while the current one is consumed from LDS.
+#pragma once
+#include "pe_common.h"
+
+struct Operand {
+  const void* ptr;
+  long long batch_stride;
+  int x_in; long long x_outer, x_stride;
+  int k_in; long long k_outer, k_stride;
+};
+
+static inline Operand op_plain(const void* p, long long ld /*row stride, k contiguous*/, long long batch = 0) {
+  Operand o; o.ptr = p; o.batch_stride = batch;
+  o.x_in = 1 << 30; o.x_outer = 0; o.x_stride = ld;
+  o.k_in = 1 << 30; o.k_outer = 0; o.k_stride = 1;
+  return o;
+}
+// operand stored [k][x] (x contiguous): contraction index strided by ld
+static inline Operand op_trans(const void* p, long long ld, long long batch = 0) {
+  Operand o; o.ptr = p; o.batch_stride = batch;
+  o.x_in = 1 << 30; o.x_outer = 0; o.x_stride = 1;
+  o.k_in = 1 << 30; o.k_outer = 0; o.k_stride = ld;
+  return o;
+}
+
+struct GemmShape {
+  int M, N, K, batch;
+  int k_chunk;  // > 0: split-K; batch index selects the k range [b*k_chunk, min(K,(b+1)*k_chunk))
+};
+
+// ---------------------------------------------------------------------------
+// Epilogues
+// ---------------------------------------------------------------------------
+template <typename T> struct EpiGeneric {
+  T* out; long long out_batch;
+  int om_in; long long om_outer, om_stride;
+  int on_in; long long on_outer, on_stride;
+  const float* bias_n; int bn_begin;     // v += bias_n[n] for n >= bn_begin
+  const float* bias_m;
+  float alpha;
+  int act;                       // 0 none, 1 relu, 2 sigmoid
+  const T* relu_mask; long long ld_rm;   // v *= (relu_mask[m][n] > 0)
+  T* aux; long long ld_aux;              // aux[m][n] = v (after bias/act, before mul)
+  const T* mul; long long ld_mul;        // v *= mul[m][n]
+  const float* rowscale;                 // v *= rowscale[m]
+  const float* scale2d; int s2_mdiv, s2_ndiv, s2_ld;  // v *= scale2d[(m/mdiv)*ld + n/ndiv]
+  const T* res; long long ld_res;        // v += res[m][n]
+  int accumulate;                        // v += out (read-modify-write)
+
+  PE_DEV void operator()(int b, int m, int n, float v) const {
+    v *= alpha;
+    if (bias_n && n >= bn_begin) v += bias_n[n];
+    if (bias_m) v += bias_m[m];
+    if (act == 1) v = fmaxf(v, 0.0f);
+    else if (act == 2) v = sigmoidf_(v);
+    if (relu_mask) v = (to_f(relu_mask[(long long)m * ld_rm + n]) > 0.0f) ? v : 0.0f;
+    if (aux) aux[(long long)m * ld_aux + n] = from_f<T>(v);
+    if (mul) v *= to_f(mul[(long long)m * ld_mul + n]);
+    if (rowscale) v *= rowscale[m];
+    if (scale2d) v *= scale2d[(long long)(m / s2_mdiv) * s2_ld + (n / s2_ndiv)];
+    if (res) v += to_f(res[(long long)m * ld_res + n]);
+    long long o = (long long)b * out_batch + (long long)(m / om_in) * om_outer + (long long)(m % om_in) * om_stride +
+                  (long long)(n / on_in) * on_outer + (long long)(n % on_in) * on_stride;
+    if (accumulate) v += to_f(out[o]);
+    out[o] = from_f<T>(v);
+  }
+};
+
+template <typename T> static inline EpiGeneric<T> epi_plain(void* out, long long ldc) {
+  EpiGeneric<T> e;
+  memset(&e, 0, sizeof(e));
+  e.out = (T*)out; e.out_batch = 0;
+  e.om_in = 1 << 30; e.om_outer = 0; e.om_stride = ldc;
+  e.on_in = 1 << 30; e.on_outer = 0; e.on_stride = 1;
+  e.alpha = 1.0f; e.s2_mdiv = 1; e.s2_ndiv = 1;
+  return e;
+}
+
+// fp32 partial sums of a split-K GEMM: part[b][m][n]
+struct EpiPartial {
+  float* out; long long mn; int ldn;
+  PE_DEV void operator()(int b, int m, int n, float v) const { out[(long long)b * mn + (long long)m * ldn + n] = v; }
+};
+
+// ---------------------------------------------------------------------------
+// Kernel
+// ---------------------------------------------------------------------------
+template <typename T> struct GemmCfg {
+  static constexpr int VEC = Vec16<T>::N;
+  static constexpr int BM = 128, BN = 128;
+  static constexpr int BK = 8 * VEC;        // 64 (bf16) or 32 (fp32): 128-byte rows
+  static constexpr int LDSS = BK + VEC;     // +16 bytes: conflict-free 16-byte fragment reads
+};
+
+template <typename T, bool KC>
+PE_DEV void gemm_load_tile(typename Vec16<T>::type (&regs)[4], const T* base, const Operand& op, int x0, int X, int k0,
+                           int kend, int tid) {
+  constexpr int VEC = Vec16<T>::N;
+  typedef typename Vec16<T>::type V;
+  if (KC) {
+    // thread loads 4 vectors: row = tid/8 + 32*i, k-vector kv = tid%8
+    int kv = tid & 7;
+    int k = k0 + kv * VEC;
+    long long ka = (long long)(k / op.k_in) * op.k_outer + (long long)(k % op.k_in);
+    bool kok = k < kend;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      int x = x0 + (tid >> 3) + 32 * i;
+      V v;
+#pragma unroll
+      for (int e = 0; e < VEC; e++) v[e] = from_f<T>(0.0f);
+      if (kok && x < X) {
+        long long xa = (long long)(x / op.x_in) * op.x_outer + (long long)(x % op.x_in) * op.x_stride;
+        v = *reinterpret_cast<const V*>(base + xa + ka);
+      }
+      regs[i] = v;
+    }
+  } else {
+    // micro-block: VEC rows (x) by 4 contraction steps; 4 loads of VEC elements along x
+    constexpr int XB = 128 / VEC;
+    int xb = tid % XB, kb = tid / XB;
+    int x = x0 + xb * VEC;
+    bool xok = x < X;
+    long long xa = (long long)(x / op.x_in) * op.x_outer + (long long)(x % op.x_in);
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      int k = k0 + kb * 4 + j;
+      V v;
+#pragma unroll
+      for (int e = 0; e < VEC; e++) v[e] = from_f<T>(0.0f);
+      if (xok && k < kend) {
+        long long ka = (long long)(k / op.k_in) * op.k_outer + (long long)(k % op.k_in) * op.k_stride;
+        v = *reinterpret_cast<const V*>(base + xa + ka);
+      }
+      regs[j] = v;
+    }
+  }
+}
+
+template <typename T, bool KC>
+PE_DEV void gemm_store_tile(const typename Vec16<T>::type (&regs)[4], T* lds, int tid) {
+  constexpr int VEC = Vec16<T>::N;
+  constexpr int LDSS = GemmCfg<T>::LDSS;
+  typedef typename Vec16<T>::type V;
+  if (KC) {
+    int kv = tid & 7;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      int row = (tid >> 3) + 32 * i;
+      *reinterpret_cast<V*>(lds + row * LDSS + kv * VEC) = regs[i];
+    }
+  } else {
+    constexpr int XB = 128 / VEC;
+    int xb = tid % XB, kb = tid / XB;
+    typedef T V4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+    for (int e = 0; e < VEC; e++) {
+      V4 w;
+      w[0] = regs[0][e]; w[1] = regs[1][e]; w[2] = regs[2][e]; w[3] = regs[3][e];
+      *reinterpret_cast<V4*>(lds + (xb * VEC + e) * LDSS + kb * 4) = w;
+    }
+  }
+}
+
+template <typename T, bool A_KC, bool B_KC, class Epi>
+__global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmShape sh, Epi epi) {
+  typedef GemmCfg<T> C;
+  typedef Mma<T> MM;
+  typedef typename Vec16<T>::type V;
+  __shared__ __attribute__((aligned(16))) T lds_a[C::BM * C::LDSS];
+  __shared__ __attribute__((aligned(16))) T lds_b[C::BN * C::LDSS];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int b = blockIdx.z;
+  const int m0 = blockIdx.y * C::BM, n0 = blockIdx.x * C::BN;
+
+  int kbeg = 0, kend = sh.K;
+  const T* pa = (const T*)A.ptr;
+  const T* pb = (const T*)B.ptr;
+  if (sh.k_chunk > 0) {
+    kbeg = b * sh.k_chunk;
+    kend = min(sh.K, kbeg + sh.k_chunk);
+  } else {
+    pa += (long long)b * A.batch_stride;
+    pb += (long long)b * B.batch_stride;
+  }
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; i++)
+#pragma unroll
+    for (int j = 0; j < 2; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.0f;
+
+  V ra[4], rb[4];
+  if (kbeg < kend) {
+    gemm_load_tile<T, A_KC>(ra, pa, A, m0, sh.M, kbeg, kend, tid);
+    gemm_load_tile<T, B_KC>(rb, pb, B, n0, sh.N, kbeg, kend, tid);
+  }
+  for (int k0 = kbeg; k0 < kend; k0 += C::BK) {
+    __syncthreads();  // previous tile fully consumed
+    gemm_store_tile<T, A_KC>(ra, lds_a, tid);
+    gemm_store_tile<T, B_KC>(rb, lds_b, tid);
+    __syncthreads();
+    if (k0 + C::BK < kend) {
+      gemm_load_tile<T, A_KC>(ra, pa, A, m0, sh.M, k0 + C::BK, kend, tid);
+      gemm_load_tile<T, B_KC>(rb, pb, B, n0, sh.N, k0 + C::BK, kend, tid);
+    }
+#pragma unroll
+    for (int kk = 0; kk < C::BK / MM::KSTEP; kk++) {
+      typename MM::frag af[2], bf[2];
+#pragma unroll
+      for (int t = 0; t < 2; t++) {
+        af[t] = MM::load(lds_a + (wm * 64 + t * 32 + l32) * C::LDSS + kk * MM::KSTEP + g * MM::KP);
+        bf[t] = MM::load(lds_b + (wn * 64 + t * 32 + l32) * C::LDSS + kk * MM::KSTEP + g * MM::KP);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; i++)
+#pragma unroll
+        for (int j = 0; j < 2; j++) MM::mma(acc[i][j], af[i], bf[j]);
+    }
+  }
+
+#pragma unroll
+  for (int i = 0; i < 2; i++)
+#pragma unroll
+    for (int j = 0; j < 2; j++) {
+      int n = n0 + wn * 64 + j * 32 + l32;
+#pragma unroll
+      for (int a = 0; a < 16; a++) {
+        int m = m0 + wm * 64 + i * 32 + acc_row(g, a);
+        if (m < sh.M && n < sh.N) epi(b, m, n, acc[i][j][a]);
+      }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Host launcher.  Returns 0 or a negative code when an operand violates the
+// vector-alignment rules (nothing is launched then).
+// ---------------------------------------------------------------------------
+template <typename T> static inline bool gemm_operand_ok(const Operand& o, bool kc, int X, const GemmShape& sh) {
+  const int VEC = Vec16<T>::N;
+  if (((uintptr_t)o.ptr) % 16) return false;
+  if (o.batch_stride % VEC) return false;
+  if (kc) {
+    if (o.k_stride != 1) return false;
+    if (o.k_in % VEC && o.k_in < sh.K) return false;
+    if (sh.K % VEC) return false;
+    if (o.x_outer % VEC || (o.x_stride % VEC)) return false;
+    if (o.k_outer % VEC) return false;
+    if (sh.k_chunk > 0 && sh.k_chunk % GemmCfg<T>::BK) return false;
+  } else {
+    if (o.x_stride != 1) return false;
+    if (o.x_in % VEC && o.x_in < X) return false;
+    if (X % VEC) return false;
+    if (o.x_outer % VEC || o.k_outer % VEC || o.k_stride % VEC) return false;
+  }
+  return true;
+}
+
+template <typename T, class Epi>
+static inline int launch_gemm(hipStream_t st, const Operand& A, bool a_kc, const Operand& B, bool b_kc,
+                              const GemmShape& sh, const Epi& epi) {
+  if (sh.M <= 0 || sh.N <= 0 || sh.batch <= 0) return 0;
+  if (!gemm_operand_ok<T>(A, a_kc, sh.M, sh) || !gemm_operand_ok<T>(B, b_kc, sh.N, sh)) return -1;
+  dim3 grid((sh.N + 127) / 128, (sh.M + 127) / 128, sh.batch);
+  dim3 block(256);
+  if (a_kc && b_kc) hipLaunchKernelGGL((gemm_kernel<T, true, true, Epi>), grid, block, 0, st, A, B, sh, epi);
+  else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_kernel<T, true, false, Epi>), grid, block, 0, st, A, B, sh, epi);
+  else if (!a_kc && b_kc) hipLaunchKernelGGL((gemm_kernel<T, false, true, Epi>), grid, block, 0, st, A, B, sh, epi);
+  else hipLaunchKernelGGL((gemm_kernel<T, false, false, Epi>), grid, block, 0, st, A, B, sh, epi);
+  return hipGetLastError() == hipSuccess ? 0 : -2;
+}

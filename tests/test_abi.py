@@ -1,0 +1,73 @@
+"""Host-side checks of the C ABI (no GPU): exported symbols, layouts, error codes."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2211_00235_amd as pe
+from oracle.params import param_table as oracle_table
+from pe_inputs import CONFIGS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(os.path.join(ROOT, "paper_2211_00235_amd", "libpe_mi355x.so")):
+        from paper_2211_00235_amd import build
+        build.build()
+    return pe.lib()
+
+
+def test_every_declared_symbol_is_exported(L):
+    hdr = open(os.path.join(ROOT, "include", "pe.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(pe_[a-z_]+)\s*\(", hdr))
+    assert {"pe_block_fwd", "pe_block_bwd", "pe_stack_fwd_bwd", "pe_create"} <= names
+    for n in sorted(names):
+        assert hasattr(L, n), n
+
+
+@pytest.mark.parametrize("name", list(CONFIGS))
+def test_param_table_matches_oracle_layout(L, name):
+    dims = dict(CONFIGS[name][0])
+    if dims["col_global"] and pe.check_dims(dims) != 0:
+        pytest.skip("global column attention not built")
+    ot, on = oracle_table(dims)
+    assert pe.param_count(dims) == on
+    lt = pe.param_table(dims)
+    assert len(lt) == len(ot)
+    for a, b in zip(lt, ot):
+        assert a["name"] == b["name"] and a["offset"] == b["offset"]
+        assert tuple(a["shape"]) == tuple(b["shape"]) and a["fan_in"] == b["fan_in"] and a["kind"] == b["kind"]
+
+
+def test_dims_validation(L):
+    d = dict(CONFIGS["af2_initial"][0])
+    assert pe.check_dims(d) == 0
+    for key, bad in (("c_m", 250), ("d_msa", 64), ("dtype", 7), ("s", 0), ("c_z", 512), ("h_msa", 16)):
+        dd = dict(d)
+        dd[key] = bad
+        assert pe.check_dims(dd) == -2, key
+        assert pe.workspace_bytes(dd, 1) == 0
+
+
+def test_sizes_are_consistent(L):
+    d = dict(CONFIGS["tiny"][0])
+    assert pe.workspace_bytes(d, 1) >= pe.workspace_bytes(d, 0) + pe.ctx_bytes(d)
+    tab = pe.ctx_table(d)
+    assert all(e["offset_bytes"] % 256 == 0 for e in tab)
+    end = max(e["offset_bytes"] + e["count"] * (2 if e["dtype"] == 1 else 4) for e in tab)
+    assert end <= pe.ctx_bytes(d)
+    assert pe.stack_workspace_bytes(0, None, 2, d) > pe.workspace_bytes(d, 1)
+
+
+def test_null_and_error_strings(L):
+    assert L.pe_block_fwd(None, None, None, None, None, None, None, None, None, None, None, 0, None, None) == -1
+    assert L.pe_block_bwd(None, None, None, None, None, None, None, None, None, None, None, None, None, None, 0,
+                          None, None) == -1
+    assert L.pe_stack_workspace_bytes(0, None, 0, None) == 0
+    for code in range(0, -7, -1):
+        assert len(pe.strerror(code)) > 0
+    assert pe.strerror(-3) == "workspace too small"
