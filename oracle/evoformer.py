@@ -266,17 +266,23 @@ def tri_attn_end_bwd(P, G, pre, dupd, cache, dims):
 # --------------------------------------------------------------------------
 # transition
 # --------------------------------------------------------------------------
-def transition_fwd(P, pre, x, dims):
+def transition_fwd(P, pre, x, dims, relu_on=None):
+    """LN -> Linear -> ReLU -> Linear.  `relu_on` (bool array, optional) overrides the
+    ReLU on/off decision a > 0: h = a where relu_on else 0.  It exists for parity tests
+    of reduced-precision implementations, where the sign of a pre-activation within the
+    implementation's rounding error of zero is not uniquely determined; the default
+    (None) is the plain definition."""
     xh, c_ln = ln_fwd(x, P[pre + ".ln.g"], P[pre + ".ln.b"], dims["ln_eps"])
     a = lin_fwd(xh, P[pre + ".w1"], P[pre + ".b1"])
-    h = np.maximum(a, 0.0)
-    return lin_fwd(h, P[pre + ".w2"], P[pre + ".b2"]), (c_ln, xh, a, h)
+    on = (a > 0) if relu_on is None else relu_on
+    h = np.where(on, a, 0.0)
+    return lin_fwd(h, P[pre + ".w2"], P[pre + ".b2"]), (c_ln, xh, a, h, on)
 
 
 def transition_bwd(P, G, pre, dupd, cache):
-    c_ln, xh, a, h = cache
+    c_ln, xh, a, h, on = cache
     dh, G[pre + ".w2"], G[pre + ".b2"] = lin_bwd(h, P[pre + ".w2"], dupd)
-    da = dh * (a > 0)
+    da = dh * on
     dxh, G[pre + ".w1"], G[pre + ".b1"] = lin_bwd(xh, P[pre + ".w1"], da)
     dx, G[pre + ".ln.g"], G[pre + ".ln.b"] = ln_bwd(dxh, c_ln)
     return dx
@@ -383,13 +389,15 @@ def opm_bwd(P, G, dupd, cache, dims):
 # --------------------------------------------------------------------------
 # the block
 # --------------------------------------------------------------------------
-def block_fwd(dims, params, msa, pair, msa_mask, pair_mask, want_cache=True):
+def block_fwd(dims, params, msa, pair, msa_mask, pair_mask, want_cache=True, relu_on=None):
     """Parallel Evoformer block forward (Figure 1(c); Section "Parallel
     Evoformer").  MSA branch: row attention biased by the block's INPUT pair
     representation, column attention, transition.  Pair branch: triangle
     multiplication outgoing then incoming, triangle attention starting then
     ending node, transition.  The outer product mean of the MSA branch's
-    output is added to the pair branch's output at the end."""
+    output is added to the pair branch's output at the end.
+    relu_on: optional {"mtrans": bool array, "ptrans": bool array}, see transition_fwd."""
+    relu_on = relu_on or {}
     table, _ = param_table(dims)
     P = unpack(np.asarray(params, dtype=np.float64), table)
     C = {}
@@ -400,7 +408,7 @@ def block_fwd(dims, params, msa, pair, msa_mask, pair_mask, want_cache=True):
     else:
         u, C["col"] = col_attn_fwd(P, m1, msa_mask, dims)
     m2 = m1 + u
-    u, C["mtrans"] = transition_fwd(P, "mtrans", m2, dims)
+    u, C["mtrans"] = transition_fwd(P, "mtrans", m2, dims, relu_on.get("mtrans"))
     m3 = m2 + u
     opm, C["opm"] = opm_fwd(P, m3, msa_mask, dims)
 
@@ -412,10 +420,11 @@ def block_fwd(dims, params, msa, pair, msa_mask, pair_mask, want_cache=True):
     z3 = z2 + u
     u, C["tae"] = tri_attn_end_fwd(P, "tae", z3, pair_mask, dims)
     z4 = z3 + u
-    u, C["ptrans"] = transition_fwd(P, "ptrans", z4, dims)
+    u, C["ptrans"] = transition_fwd(P, "ptrans", z4, dims, relu_on.get("ptrans"))
     z5 = z4 + u
     pair_out = z5 + opm
-    inter = dict(m1=m1, m2=m2, m3=m3, opm=opm, z1=z1, z2=z2, z3=z3, z4=z4, z5=z5)
+    inter = dict(m1=m1, m2=m2, m3=m3, opm=opm, z1=z1, z2=z2, z3=z3, z4=z4, z5=z5,
+                 mtrans_pre=C["mtrans"][2], ptrans_pre=C["ptrans"][2])
     return m3, pair_out, ((P, C) if want_cache else None), inter
 
 

@@ -109,11 +109,43 @@ template <typename T> struct GemmCfg {
   static constexpr int LDSS = BK + VEC;     // +16 bytes: conflict-free 16-byte fragment reads
 };
 
+// element-wise (unaligned) variant of one 16-byte vector load: elements e = 0..VEC-1 along k (KC) or x
 template <typename T, bool KC>
+PE_DEV typename Vec16<T>::type gemm_load_slow(const T* base, const Operand& op, int x, int X, int k, int kend) {
+  constexpr int VEC = Vec16<T>::N;
+  typename Vec16<T>::type v;
+#pragma unroll
+  for (int e = 0; e < VEC; e++) {
+    int xx = KC ? x : x + e, kk = KC ? k + e : k;
+    float f = 0.0f;
+    if (xx < X && kk < kend) {
+      long long a = (long long)(xx / op.x_in) * op.x_outer + (long long)(xx % op.x_in) * op.x_stride +
+                    (long long)(kk / op.k_in) * op.k_outer + (long long)(kk % op.k_in) * op.k_stride;
+      f = to_f(base[a]);
+    }
+    v[e] = from_f<T>(f);
+  }
+  return v;
+}
+
+template <typename T, bool KC, bool AL>
 PE_DEV void gemm_load_tile(typename Vec16<T>::type (&regs)[4], const T* base, const Operand& op, int x0, int X, int k0,
                            int kend, int tid) {
   constexpr int VEC = Vec16<T>::N;
   typedef typename Vec16<T>::type V;
+  if (!AL) {
+    if (KC) {
+      int kv = tid & 7;
+#pragma unroll
+      for (int i = 0; i < 4; i++) regs[i] = gemm_load_slow<T, true>(base, op, x0 + (tid >> 3) + 32 * i, X, k0 + kv * VEC, kend);
+    } else {
+      constexpr int XB = 128 / VEC;
+      int xb = tid % XB, kb = tid / XB;
+#pragma unroll
+      for (int j = 0; j < 4; j++) regs[j] = gemm_load_slow<T, false>(base, op, x0 + xb * VEC, X, k0 + kb * 4 + j, kend);
+    }
+    return;
+  }
   if (KC) {
     // thread loads 4 vectors: row = tid/8 + 32*i, k-vector kv = tid%8
     int kv = tid & 7;
@@ -179,7 +211,7 @@ PE_DEV void gemm_store_tile(const typename Vec16<T>::type (&regs)[4], T* lds, in
   }
 }
 
-template <typename T, bool A_KC, bool B_KC, class Epi>
+template <typename T, bool A_KC, bool B_KC, bool AL, class Epi>
 __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmShape sh, Epi epi) {
   typedef GemmCfg<T> C;
   typedef Mma<T> MM;
@@ -214,8 +246,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
 
   V ra[4], rb[4];
   if (kbeg < kend) {
-    gemm_load_tile<T, A_KC>(ra, pa, A, m0, sh.M, kbeg, kend, tid);
-    gemm_load_tile<T, B_KC>(rb, pb, B, n0, sh.N, kbeg, kend, tid);
+    gemm_load_tile<T, A_KC, AL>(ra, pa, A, m0, sh.M, kbeg, kend, tid);
+    gemm_load_tile<T, B_KC, AL>(rb, pb, B, n0, sh.N, kbeg, kend, tid);
   }
   for (int k0 = kbeg; k0 < kend; k0 += C::BK) {
     __syncthreads();  // previous tile fully consumed
@@ -223,8 +255,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
     gemm_store_tile<T, B_KC>(rb, lds_b, tid);
     __syncthreads();
     if (k0 + C::BK < kend) {
-      gemm_load_tile<T, A_KC>(ra, pa, A, m0, sh.M, k0 + C::BK, kend, tid);
-      gemm_load_tile<T, B_KC>(rb, pb, B, n0, sh.N, k0 + C::BK, kend, tid);
+      gemm_load_tile<T, A_KC, AL>(ra, pa, A, m0, sh.M, k0 + C::BK, kend, tid);
+      gemm_load_tile<T, B_KC, AL>(rb, pb, B, n0, sh.N, k0 + C::BK, kend, tid);
     }
 #pragma unroll
     for (int kk = 0; kk < C::BK / MM::KSTEP; kk++) {
@@ -278,16 +310,28 @@ template <typename T> static inline bool gemm_operand_ok(const Operand& o, bool 
   return true;
 }
 
+template <typename T, bool AL, class Epi>
+static inline void launch_gemm_al(hipStream_t st, dim3 grid, const Operand& A, bool a_kc, const Operand& B, bool b_kc,
+                                  const GemmShape& sh, const Epi& epi) {
+  dim3 block(256);
+  if (a_kc && b_kc) hipLaunchKernelGGL((gemm_kernel<T, true, true, AL, Epi>), grid, block, 0, st, A, B, sh, epi);
+  else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_kernel<T, true, false, AL, Epi>), grid, block, 0, st, A, B, sh, epi);
+  else if (!a_kc && b_kc) hipLaunchKernelGGL((gemm_kernel<T, false, true, AL, Epi>), grid, block, 0, st, A, B, sh, epi);
+  else hipLaunchKernelGGL((gemm_kernel<T, false, false, AL, Epi>), grid, block, 0, st, A, B, sh, epi);
+}
+
+// Operands that break the 16-byte vector rules (odd leading dimensions) take the
+// element-wise loader: same tiles, same arithmetic, slower loads.
 template <typename T, class Epi>
 static inline int launch_gemm(hipStream_t st, const Operand& A, bool a_kc, const Operand& B, bool b_kc,
                               const GemmShape& sh, const Epi& epi) {
   if (sh.M <= 0 || sh.N <= 0 || sh.batch <= 0) return 0;
-  if (!gemm_operand_ok<T>(A, a_kc, sh.M, sh) || !gemm_operand_ok<T>(B, b_kc, sh.N, sh)) return -1;
+  if (a_kc ? A.k_stride != 1 : A.x_stride != 1) return -1;
+  if (b_kc ? B.k_stride != 1 : B.x_stride != 1) return -1;
+  if (sh.k_chunk > 0 && sh.k_chunk % GemmCfg<T>::BK) return -1;
+  bool al = gemm_operand_ok<T>(A, a_kc, sh.M, sh) && gemm_operand_ok<T>(B, b_kc, sh.N, sh);
   dim3 grid((sh.N + 127) / 128, (sh.M + 127) / 128, sh.batch);
-  dim3 block(256);
-  if (a_kc && b_kc) hipLaunchKernelGGL((gemm_kernel<T, true, true, Epi>), grid, block, 0, st, A, B, sh, epi);
-  else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_kernel<T, true, false, Epi>), grid, block, 0, st, A, B, sh, epi);
-  else if (!a_kc && b_kc) hipLaunchKernelGGL((gemm_kernel<T, false, true, Epi>), grid, block, 0, st, A, B, sh, epi);
-  else hipLaunchKernelGGL((gemm_kernel<T, false, false, Epi>), grid, block, 0, st, A, B, sh, epi);
+  if (al) launch_gemm_al<T, true, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);
+  else launch_gemm_al<T, false, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);
   return hipGetLastError() == hipSuccess ? 0 : -2;
 }

@@ -152,3 +152,36 @@ def test_stack_gradients_fd():
     pz = args["pair"]
     idx = rng.choice(pz.size, size=20, replace=False)
     assert np.max(np.abs(_fd(f, pz, idx) - dz.reshape(-1)[idx])) / np.max(np.abs(dz)) < 1e-6
+
+
+def test_relu_override_is_consistent():
+    """With the on/off decision supplied explicitly the block is smooth in its inputs: the
+    backward must be the exact derivative of that function (finite differences with the same
+    fixed decisions), and supplying the default decisions changes nothing."""
+    dims, table, n, inp = tiny_case(seed=17)
+    msa, pair, params = inp["msa"].copy(), inp["pair"].copy(), inp["params"].copy()
+    mm, pm, wm, wz = inp["msa_mask"], inp["pair_mask"], inp["d_msa_out"], inp["d_pair_out"]
+    m0, z0, cache0, it0 = ev.block_fwd(dims, params, msa, pair, mm, pm)
+    on = {"mtrans": it0["mtrans_pre"] > 0, "ptrans": it0["ptrans_pre"] > 0}
+    m1, z1, cache1, _ = ev.block_fwd(dims, params, msa, pair, mm, pm, relu_on=on)
+    assert np.array_equal(m0, m1) and np.array_equal(z0, z1)
+    assert np.array_equal(ev.block_bwd(dims, cache0, wm, wz)[2], ev.block_bwd(dims, cache1, wm, wz)[2])
+    # flip the decisions of the pre-activations closest to zero
+    rng = np.random.default_rng(0)
+    for k in ("mtrans", "ptrans"):
+        a = it0[k + "_pre"]
+        thr = np.quantile(np.abs(a), 0.1)
+        on[k] = np.where(np.abs(a) < thr, rng.random(a.shape) < 0.5, a > 0)
+    _, _, cache, _ = ev.block_fwd(dims, params, msa, pair, mm, pm, relu_on=on)
+    dm, dz, g, _ = ev.block_bwd(dims, cache, wm, wz)
+
+    def f():
+        m, z, _, _ = ev.block_fwd(dims, params, msa, pair, mm, pm, want_cache=False, relu_on=on)
+        return float((wm * m).sum() + (wz * z).sum())
+    idx = rng.choice(params.size, size=60, replace=False)
+    num = _fd(f, params, idx)
+    assert np.max(np.abs(num - g[idx]) / (np.abs(g[idx]) + 1e-3 * np.max(np.abs(g)))) < 1e-5
+    idx = rng.choice(msa.size, size=30, replace=False)
+    assert np.max(np.abs(_fd(f, msa, idx) - dm.reshape(-1)[idx])) / np.max(np.abs(dm)) < 1e-6
+    idx = rng.choice(pair.size, size=30, replace=False)
+    assert np.max(np.abs(_fd(f, pair, idx) - dz.reshape(-1)[idx])) / np.max(np.abs(dz)) < 1e-6
