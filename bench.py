@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark: one Parallel Evoformer block forward + backward on one MI355X.
+
+A "step" is one pass of the whole hot path (pe_block_fwd with saved ctx, then
+pe_block_fwd's ctx consumed by pe_block_bwd) over one synthetic AlphaFold2
+initial-training batch (s=128, r=256, c_m=256, c_z=128, bf16 storage, fp32
+accumulate), MSA branch and pair branch on two HIP streams.  Inputs are
+resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+PAPER_MS_PER_LAYER = 32.47    # paper Table 5, PPFold DAP=1 BP=1, 1x A100 40G, fp16, same shape
+
+
+def block_fwd_flops(d):
+    """Algorithmic forward flops (2*M*N*K per contraction, masked positions counted dense)."""
+    s, r, cm, cz = d["s"], d["r"], d["c_m"], d["c_z"]
+    Mm, Mz = s * r, r * r
+    Hm, dm, Hp, dp = d["h_msa"], d["d_msa"], d["h_pair"], d["d_pair"]
+    ct, co, n = d["c_tri"], d["c_opm"], d["n_trans"]
+    f = 0.0
+    f += 2 * Mm * cm * 5 * Hm * dm + 2 * Mz * cz * Hm + 4 * s * Hm * r * r * dm          # row attention
+    f += 2 * Mm * cm * 5 * Hm * dm + 4 * r * Hm * s * s * dm                             # column attention
+    f += 4 * Mm * cm * n * cm                                                            # MSA transition
+    f += 2 * Mm * cm * 2 * co + 2 * (r * co) ** 2 * s + 2 * Mz * co * co * cz            # outer product mean
+    f += 2 * (2 * Mz * cz * (4 * ct + cz) + 2 * Mz * ct * cz + 2 * r ** 3 * ct)          # triangle multiplication x2
+    f += 2 * (2 * Mz * cz * 5 * Hp * dp + 2 * Mz * cz * Hp + 4 * r * Hp * r * r * dp)    # triangle attention x2
+    f += 4 * Mz * cz * n * cz                                                            # pair transition
+    return f
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="af2_initial")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs the one-GPU share of the path only (two HIP streams on one "
+              "MI355X); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2211_00235_amd as pe
+    from pe_inputs import dims_for, make_inputs
+    from tests.gpu_util import BlockRun     # argument marshalling helper (no oracle import)
+
+    pe.lib()                                  # fails loudly when the HIP library is not built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    dims, mask, seed = dims_for(args.workload)
+    table = pe.param_table(dims)
+    inp = make_inputs(dims, table, pe.param_count(dims), mask, seed)
+    run = BlockRun(dims, inp, two_streams=True)
+
+    def step():
+        run.fwd(use_ctx=True)
+        run.bwd(use_ctx=True)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # ---- branch overlap (a few untimed-in-the-headline iterations each) ----
+    def timed(n, fn):
+        fn()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3 / n
+    nrep = max(3, min(10, args.steps))
+    run.h.set_option(1, 1)
+    t_msa = timed(nrep, step)
+    run.h.set_option(1, 2)
+    t_pair = timed(nrep, step)
+    run.h.set_option(1, 3)
+    one = BlockRun(dims, inp, two_streams=False)
+    t_serial = timed(nrep, lambda: (one.fwd(), one.bwd()))
+    overlap = (t_msa + t_pair - ms) / min(t_msa, t_pair)
+
+    # ---- per-kernel timing with HIP events on the launching stream ----
+    one.h.set_option(3, 1)
+    for _ in range(3):
+        one.fwd()
+        one.bwd()
+    ent = one.h.timing_collect()
+    one.h.set_option(3, 0)
+    by_kernel = {}
+    for e in ent:
+        k = by_kernel.setdefault(e["kernel"], dict(ms=0.0, launches=0, flops=0.0, bytes=0.0))
+        k["ms"] += e["total_ms"] / 3
+        k["launches"] += e["launches"] // 3
+        k["flops"] += e["flops"] / 3
+        k["bytes"] += e["bytes"] / 3
+    dom_name = max(by_kernel, key=lambda k: by_kernel[k]["ms"])
+    dom = by_kernel[dom_name]
+    if dom["flops"] > 0 and (dom["flops"] / max(dom["bytes"], 1.0)) > PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9) / 4:
+        achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+        roof = dict(bound="mfma", achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                    frac=achieved / PEAK_BF16_TFLOPS, traffic=None)
+    else:
+        achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
+        roof = dict(bound="hbm", achieved=achieved, peak=PEAK_HBM_GBS, unit="GB/s", frac=achieved / PEAK_HBM_GBS,
+                    traffic=None)
+    roof.update(kernel=dom_name, launches_per_step=dom["launches"], avg_launch_us=1e3 * dom["ms"] / max(dom["launches"], 1),
+                kernel_ms_per_step=dom["ms"])
+    kernels = {k: dict(ms=round(v["ms"], 4), launches=v["launches"],
+                       tflops=round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["ms"] > 0 else 0.0,
+                       gbs=round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["ms"] > 0 else 0.0)
+               for k, v in sorted(by_kernel.items(), key=lambda kv: -kv[1]["ms"])}
+
+    flops = 3.0 * block_fwd_flops(dims)
+    out = {
+        "metric": "Parallel Evoformer block fwd+bwd ms (s=%d,r=%d)" % (dims["s"], dims["r"]),
+        "value": ms, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": ms / PAPER_MS_PER_LAYER,
+        "baseline_note": "paper Table 5: 32.47 ms per Evoformer layer fwd+bwd, PPFold on 1x A100 40G, fp16, same "
+                         "shape (other hardware: context, not the target)",
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "s": dims["s"], "r": dims["r"], "c_m": dims["c_m"], "c_z": dims["c_z"],
+                   "batch": 1, "streams": 2, "activation_ctx": "saved"},
+        "samples_per_s": 1e3 / ms,
+        "block_tflops": flops / (ms * 1e-3) / 1e12,
+        "bf16_mfma_peak_frac": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "overlap": {"t_msa_only_ms": t_msa, "t_pair_only_ms": t_pair, "t_two_streams_ms": ms,
+                    "t_one_stream_ms": t_serial, "ratio": overlap},
+        "roofline": roof,
+        "kernels_ms_per_step": kernels,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import evoformer as ev      # cpu_baseline leg only
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count()])
+        except Exception:
+            cores = os.cpu_count()
+        t = time.perf_counter()
+        ev.block_fwd_bwd(dims, inp["params"], inp["msa"], inp["pair"], inp["msa_mask"], inp["pair_mask"],
+                         inp["d_msa_out"], inp["d_pair_out"])
+        cpu_ms = (time.perf_counter() - t) * 1e3
+        out["cpu_baseline"] = {"value": cpu_ms, "unit": "ms", "cores": int(cores), "kind": "oracle",
+                               "sample": "one full fwd+bwd of the same %s block, float64 numpy" % args.workload}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

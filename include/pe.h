@@ -99,9 +99,28 @@ int pe_destroy(pe_handle* h);
  * mean), bit 1 = run the pair branch; default 3.  With a branch disabled its
  * outputs are left untouched (used to time each branch alone).
  * PE_OPT_SYNC_DEBUG: 1 = hipStreamSynchronize + error check after each
- * sub-operation (slow; for fault isolation).                                 */
-enum { PE_OPT_BRANCHES = 1, PE_OPT_SYNC_DEBUG = 2 };
+ * sub-operation (slow; for fault isolation).
+ * PE_OPT_KERNEL_TIMING: 1 = bracket every kernel launch with a pair of HIP
+ * events on the stream it is launched on; read the result with
+ * pe_timing_collect (measurement only: events add launch overhead).          */
+enum { PE_OPT_BRANCHES = 1, PE_OPT_SYNC_DEBUG = 2, PE_OPT_KERNEL_TIMING = 3 };
 int pe_set_option(pe_handle* h, int option, int value);
+
+/* Per-kernel timing since the last collect, aggregated by launch label.
+ * flops / bytes are the ALGORITHMIC work of those launches (2*M*N*K per
+ * contraction; minimal reads + writes for the memory-bound kernels).
+ * pe_timing_collect synchronises the device and returns the number of
+ * entries; with out == NULL it only reports that number, otherwise it fills
+ * out (cap >= number) and clears the records.                                */
+typedef struct pe_timing_entry {
+  char name[32];         /* launch label, e.g. "attn qkvg"                           */
+  char kernel[64];       /* kernel (template) name the label ran                     */
+  int launches;
+  double total_ms;
+  double flops;
+  double bytes;
+} pe_timing_entry;
+int pe_timing_collect(pe_handle* h, pe_timing_entry* out, int cap);
 
 /* Host-side shape queries (no GPU needed). */
 int pe_check_dims(const pe_dims* d);                                   /* PE_OK or PE_ERR_DIMS */
@@ -122,9 +141,10 @@ size_t pe_stack_workspace_bytes(int n_extra, const pe_dims* extra, int n_main, c
  *     outer-product projections are multiplied by the mask.
  *   params: fp32 flat buffer, pe_param_count elements, layout pe_param_table.
  *   msa_out, pair_out: outputs, must not alias any input.
- *   ctx: NULL, or pe_ctx_bytes bytes that receive the activations saved for
- *     pe_block_bwd.
- *   workspace: >= pe_workspace_bytes(dims, 0) bytes, 256-byte aligned.
+ *   ctx: NULL, or pe_ctx_bytes bytes (256-byte aligned) that receive the
+ *     activations saved for pe_block_bwd.
+ *   workspace: 256-byte aligned, >= pe_workspace_bytes(dims, ctx == NULL)
+ *     bytes (without a caller ctx the intermediates live in the workspace).
  *   stream_msa, stream_pair: hipStream_t (NULL = default stream).            */
 int pe_block_fwd(pe_handle* h, const pe_dims* dims,
                  const void* msa_in, const void* pair_in,

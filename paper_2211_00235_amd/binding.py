@@ -32,6 +32,11 @@ class _CtxEntry(C.Structure):
                 ("dtype", C.c_int)]
 
 
+class _TimingEntry(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("kernel", C.c_char * 64), ("launches", C.c_int), ("total_ms", C.c_double),
+                ("flops", C.c_double), ("bytes", C.c_double)]
+
+
 _lib = None
 _KINDS = {0: "weight", 1: "ln_gamma", 2: "ln_beta", 3: "bias"}
 
@@ -64,6 +69,7 @@ def lib():
     L.pe_block_bwd.argtypes = [vp, dp, vp, vp, fp, fp, fp, vp, vp, vp, vp, fp, vp, vp, C.c_size_t, vp, vp]
     L.pe_stack_fwd_bwd.argtypes = [vp, C.c_int, dp, C.c_int, dp, vp, vp, vp, fp, fp, fp, fp, vp, vp,
                                    vp, vp, vp, vp, vp, fp, vp, C.c_size_t, vp, vp]
+    L.pe_timing_collect.argtypes = [vp, C.POINTER(_TimingEntry), C.c_int]
     L.pe_strerror.argtypes = [C.c_int]
     L.pe_strerror.restype = C.c_char_p
     L.pe_last_error.argtypes = [vp]
@@ -135,6 +141,18 @@ class Handle:
         rc = lib().pe_set_option(self._h, opt, value)
         if rc:
             raise PEError(strerror(rc))
+
+    def timing_collect(self):
+        """Per-label kernel timings since the last call (PE_OPT_KERNEL_TIMING = 3 must be on)."""
+        n = lib().pe_timing_collect(self._h, None, 0)
+        if n < 0:
+            raise PEError(strerror(n))
+        arr = (_TimingEntry * max(n, 1))()
+        n = lib().pe_timing_collect(self._h, arr, n)
+        if n < 0:
+            raise PEError(strerror(n))
+        return [dict(name=e.name.decode(), kernel=e.kernel.decode(), launches=int(e.launches), total_ms=float(e.total_ms),
+                     flops=float(e.flops), bytes=float(e.bytes)) for e in arr[:n]]
 
     def last_error(self):
         return lib().pe_last_error(self._h).decode()

@@ -19,11 +19,13 @@
 // Online softmax over key tiles of 64; K row-major and V transposed are staged in LDS.
 #pragma once
 #include "pe_common.h"
+#include "pe_elem.h"
 
 struct AttnArgs {
   const void* qkvg; long long batch_stride, seq_stride;
   int B, L, H, d;
   const float* bias;                 // [H][L][L] (query, key) or nullptr
+  const float* biasT;                // the same values as [H][key][query] (read by the query-per-lane kernels)
   const float* mask; long long mask_bs, mask_ks;   // key mask value at mask[b*mask_bs + j*mask_ks]
   void* o; void* og;                 // forward outputs (o ungated, og = sigmoid(g) * o)
   float* lse;                        // [B][H][L]
@@ -33,7 +35,7 @@ struct AttnArgs {
   void* dO;                          // scratch: cotangent of o (written by pre kernel)
   float* D;                          // [B][H][L] rowsum(dO * o)
   void* dqkvg;                       // same layout as qkvg
-  void* dS;                          // [B][H][L][L] storage type, written when bias != nullptr
+  void* dS;                          // [B][H][key][query] storage type, written when bias != nullptr
 };
 
 template <typename T> struct AttnCfg {
@@ -135,7 +137,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
 #pragma unroll
   for (int e = 0; e < 16; e++) oacc[e] = 0.0f;
   float m_run = -INFINITY, l_run = 0.0f;
-  const float* brow = (a.bias && qok) ? a.bias + ((long long)h * L + qi) * L : nullptr;
+  const float* bcol = (a.biasT && qok) ? a.biasT + (long long)h * L * L + qi : nullptr;   // + key * L
 
   for (int j0 = 0; j0 < L; j0 += C::KT) {
     __syncthreads();
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
       for (int e = 0; e < 16; e++) {
         int jj = jt * 32 + acc_row(g, e);
         float v = sacc[e] * a.scale;
-        if (brow) v += (j0 + jj < L) ? brow[j0 + jj] : 0.0f;
+        if (bcol) v += (j0 + jj < L) ? bcol[(long long)(j0 + jj) * L] : 0.0f;
         v = (lds_mask[jj] > 0.0f) ? v : -INFINITY;
         sacc[e] = v;
         tmax = fmaxf(tmax, v);
@@ -218,10 +220,14 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
 // D = sum_c dO * o.  One thread per (b, p, h).
 // ---------------------------------------------------------------------------
 template <typename T>
-__global__ void attn_bwd_pre_kernel(AttnArgs a) {
-  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+__global__ __launch_bounds__(256) void attn_bwd_pre_kernel(AttnArgs a) {
+  // 8 lanes per (b, p, h): lane `sub` owns channels [4*sub, 4*sub+4)
+  long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int sub = gid & 7;
+  long long idx = gid >> 3;
   long long total = (long long)a.B * a.L * a.H;
-  if (idx >= total) return;
+  const bool ok = idx < total;
+  if (!ok) idx = total - 1;
   int h = idx % a.H;
   long long t = idx / a.H;
   int p = t % a.L;
@@ -229,21 +235,27 @@ __global__ void attn_bwd_pre_kernel(AttnArgs a) {
   const int d = a.d, HD = a.H * a.d;
   long long qoff = (long long)b * a.batch_stride + (long long)p * a.seq_stride + 3 * HD + h * d;
   long long ooff = (long long)b * (a.batch_stride / 4) + (long long)p * (a.seq_stride / 4) + h * d;
-  const T* pg = (const T*)a.qkvg + qoff;
-  const T* po = (const T*)a.o + ooff;
-  const T* pdog = (const T*)a.dog + ooff;
-  T* pdo = (T*)a.dO + ooff;
-  T* pdg = (T*)a.dqkvg + qoff;
   float Dsum = 0.0f;
-  for (int c = 0; c < d; c++) {
-    float sg = sigmoidf_(to_f(pg[c]));
-    float ov = to_f(po[c]), dv = to_f(pdog[c]);
-    T dob = from_f<T>(dv * sg);
-    pdo[c] = dob;
-    pdg[c] = from_f<T>(dv * ov * sg * (1.0f - sg));
-    Dsum += to_f(dob) * ov;
+  const int c0 = sub * 4;
+  if (ok && c0 < d) {
+    float gv[4], ov[4], dv[4], dov[4], dgv[4];
+    load4<T>((const T*)a.qkvg + qoff + c0, gv);
+    load4<T>((const T*)a.o + ooff + c0, ov);
+    load4<T>((const T*)a.dog + ooff + c0, dv);
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+      float sg = sigmoidf_(gv[e]);
+      dov[e] = to_f(from_f<T>(dv[e] * sg));
+      dgv[e] = dv[e] * ov[e] * sg * (1.0f - sg);
+      Dsum += dov[e] * ov[e];
+    }
+    store4<T>((T*)a.dO + ooff + c0, dov);
+    store4<T>((T*)a.dqkvg + qoff + c0, dgv);
   }
-  a.D[((long long)b * a.H + h) * a.L + p] = Dsum;
+  Dsum += __shfl_xor(Dsum, 4, 64);
+  Dsum += __shfl_xor(Dsum, 2, 64);
+  Dsum += __shfl_xor(Dsum, 1, 64);
+  if (ok && sub == 0) a.D[((long long)b * a.H + h) * a.L + p] = Dsum;
 }
 
 // ---------------------------------------------------------------------------
@@ -281,8 +293,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnArgs a) {
   const long long sidx = ((long long)b * a.H + h) * L + qi;
   const float lse = qok ? a.lse[sidx] : 0.0f;
   const float Di = qok ? a.D[sidx] : 0.0f;
-  const float* brow = (a.bias && qok) ? a.bias + ((long long)h * L + qi) * L : nullptr;
-  T* dsrow = (a.dS && qok) ? (T*)a.dS + (((long long)b * a.H + h) * L + qi) * L : nullptr;
+  const float* bcol = (a.biasT && qok) ? a.biasT + (long long)h * L * L + qi : nullptr;       // + key * L
+  T* dscol = (a.dS && qok) ? (T*)a.dS + ((long long)b * a.H + h) * L * L + qi : nullptr;        // + key * L
 
   f32x16 dq;
 #pragma unroll
@@ -314,11 +326,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnArgs a) {
       for (int e = 0; e < 16; e++) {
         int jj = jt * 32 + acc_row(g, e);
         float v = sacc[e] * a.scale;
-        if (brow) v += (j0 + jj < L) ? brow[j0 + jj] : 0.0f;
+        if (bcol) v += (j0 + jj < L) ? bcol[(long long)(j0 + jj) * L] : 0.0f;
         float p = (lds_mask[jj] > 0.0f) ? __expf(v - lse) : 0.0f;
         float ds = p * (pacc[e] - Di);
         sacc[e] = ds;
-        if (dsrow && j0 + jj < L) dsrow[j0 + jj] = from_f<T>(ds);
+        if (dscol && j0 + jj < L) dscol[(long long)(j0 + jj) * L] = from_f<T>(ds);
       }
       const T* krow = lds_kt + l32 * C::TS + jt * 32;
 #pragma unroll
@@ -432,7 +444,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
   }
 }
 
-// dbias[h][i][j] = sum_b dS[b][h][i][j]
+// dbiasT[h][j][i] = sum_b dS[b][h][j][i]  (elementwise over the trailing [H][L][L] block)
 template <typename T>
 __global__ void attn_dbias_reduce_kernel(const T* dS, float* dbias, int B, long long hll) {
   long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;

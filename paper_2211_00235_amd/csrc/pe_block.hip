@@ -15,10 +15,14 @@
 #include "pe_gemm.h"
 #include "pe_layout.h"
 
+struct ProfRec { const char* label; std::string kern; double flops, bytes; hipEvent_t e0, e1; };
 struct pe_handle {
   hipEvent_t ev[6];
   int branches;
   int sync_debug;
+  int timing;                       // PE_OPT_KERNEL_TIMING
+  std::vector<ProfRec> recs;        // one per timed launch since the last collect
+  std::vector<hipEvent_t> ev_pool;  // reusable timing events
   std::string last_error;
 };
 
@@ -58,7 +62,7 @@ struct Carver {   // fixed layouts (ctx, prepared weights); optionally records e
   }
 };
 
-template <typename T> struct AttnCtx { T* xhat; float* stats; T* qkvg; float* bias; float* zstats; float* lse; T* o; T* og; };
+template <typename T> struct AttnCtx { T* xhat; float* stats; T* qkvg; float* bias; float* biasT; float* zstats; float* lse; T* o; T* og; };
 template <typename T> struct TransCtx { T* xhat; float* stats; T* h; };
 template <typename T> struct TriMulCtx { T* zhat; float* stats; T* proj_t; T* a_t; T* b_t; T* g; T* x_t; float* stats_out; T* xhat; T* u; };
 template <typename T> struct OpmCtx { T* mhat; float* stats; T* a; T* b; float* inv_norm; T* O; };
@@ -92,6 +96,7 @@ template <typename T> static void carve_attn_ctx(Carver& cv, AttnCtx<T>& a, cons
   a.stats = cv.take<float>(N("stats"), M * 2, PE_F32);
   a.qkvg = cv.take<T>(N("qkvg"), M * 4 * HD, dtype_tag<T>());
   a.bias = has_bias ? cv.take<float>(N("bias"), (long long)H * L * L, PE_F32) : nullptr;
+  a.biasT = has_bias ? cv.take<float>(N("biasT"), (long long)H * L * L, PE_F32) : nullptr;
   a.zstats = has_bias ? cv.take<float>(N("zstats"), Mz * 2, PE_F32) : nullptr;
   a.lse = cv.take<float>(N("lse"), B * H * L, PE_F32);
   a.o = cv.take<T>(N("o"), M * HD, dtype_tag<T>());
@@ -259,6 +264,35 @@ template <typename T> struct Runner {
     }
   }
 
+  hipEvent_t prof_event() {
+    hipEvent_t e;
+    if (!h->ev_pool.empty()) { e = h->ev_pool.back(); h->ev_pool.pop_back(); return e; }
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+  hipEvent_t prof_e0 = nullptr;
+  void prof_begin(hipStream_t st) {
+    if (dry || err || !h || !h->timing) return;
+    prof_e0 = prof_event();
+    if (prof_e0) (void)hipEventRecord(prof_e0, st);
+  }
+  void prof_end(hipStream_t st, const char* label, const char* kern, double flops, double bytes) {
+    if (dry || err || !h || !h->timing || !prof_e0) return;
+    hipEvent_t e1 = prof_event();
+    if (e1) {
+      (void)hipEventRecord(e1, st);
+      h->recs.push_back(ProfRec{label, kern, flops, bytes, prof_e0, e1});
+    }
+    prof_e0 = nullptr;
+  }
+#define PE_LAUNCH(label, flops, bytes, st, kern, grid, block, lds, ...)     \
+  do {                                                                      \
+    prof_begin(st);                                                         \
+    hipLaunchKernelGGL(kern, grid, block, lds, st, __VA_ARGS__);            \
+    prof_end(st, label, #kern, (double)(flops), (double)(bytes));           \
+    check(label);                                                           \
+  } while (0)
+
   // ---- prepared weights: returns bytes used -------------------------------
   size_t carve_prep(char* base) {
     size_t off = 0;
@@ -320,8 +354,7 @@ template <typename T> struct Runner {
   void k_ln_fwd(hipStream_t st, const T* x, long long g_off, long long b_off, T* y, float* stats, long long M, int Cc) {
     if (dry || err) return;
     int grid = (int)std::min<long long>((M + 3) / 4, 4096);
-    hipLaunchKernelGGL(ln_fwd_kernel<T>, dim3(grid), dim3(256), 0, st, x, P(g_off), P(b_off), y, stats, M, Cc, d.ln_eps);
-    check("ln_fwd");
+    PE_LAUNCH("ln_fwd", 0, 2.0 * M * Cc * sizeof(T), st, ln_fwd_kernel<T>, dim3(grid), dim3(256), 0, x, P(g_off), P(b_off), y, stats, M, Cc, d.ln_eps);
   }
   void reduce_to(hipStream_t st, const float* part, int nsplit, long long stride, int rows, int cols, int nseg,
                  const ReduceSeg* segs) {
@@ -331,8 +364,7 @@ template <typename T> struct Runner {
     for (int i = 0; i < nseg; i++) ra.seg[i] = segs[i];
     ra.dst = dparams;
     long long total = (long long)rows * cols;
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, ra);
-    check("reduce_partials");
+    PE_LAUNCH("reduce_partials", 0, 4.0 * total * (nsplit + 2), st, reduce_partials_kernel, dim3((unsigned)((total + 63) / 64)), dim3(1024), 0, ra);
   }
   void k_ln_bwd(hipStream_t st, Arena& ar, const T* dy, const T* x, const float* stats, long long g_off, long long b_off,
                 const T* gin, T* gout, long long M, int Cc) {
@@ -340,8 +372,7 @@ template <typename T> struct Runner {
     int grid = (int)std::min<long long>((M + 3) / 4, LN_MAX_WG);
     float* part = (float*)ar.alloc((size_t)grid * 2 * Cc * sizeof(float));
     if (!dry && !err) {
-      hipLaunchKernelGGL(ln_bwd_kernel<T>, dim3(grid), dim3(256), 0, st, dy, x, stats, P(g_off), gin, gout, part, M, Cc);
-      check("ln_bwd");
+      PE_LAUNCH("ln_bwd", 0, (gin ? 4.0 : 3.0) * M * Cc * sizeof(T), st, ln_bwd_kernel<T>, dim3(grid), dim3(256), 0, dy, x, stats, P(g_off), gin, gout, part, M, Cc);
       ReduceSeg sg[2] = {{0, Cc, g_off, 0}, {Cc, Cc, b_off, 0}};
       reduce_to(st, part, grid, 2LL * Cc, 1, 2 * Cc, 2, sg);
     }
@@ -349,13 +380,12 @@ template <typename T> struct Runner {
   }
   void k_colsum(hipStream_t st, Arena& ar, const T* y, long long M, int N, long long ld, long long dst_off) {
     size_t mk = ar.mark();
-    int nwg = (int)std::min<long long>(256, M);
+    int nwg = (int)std::min<long long>(1024, (M + 31) / 32);
     long long rpw = (M + nwg - 1) / nwg;
     nwg = (int)((M + rpw - 1) / rpw);
     float* part = (float*)ar.alloc((size_t)nwg * N * sizeof(float));
     if (!dry && !err) {
-      hipLaunchKernelGGL(colsum_kernel<T>, dim3(nwg), dim3(256), 0, st, y, M, N, ld, part, rpw);
-      check("colsum");
+      PE_LAUNCH("colsum", 0, 1.0 * M * N * sizeof(T), st, colsum_kernel<T>, dim3(nwg), dim3(256), 0, y, M, N, ld, part, rpw);
       ReduceSeg sg[1] = {{0, N, dst_off, 0}};
       reduce_to(st, part, nwg, N, 1, N, 1, sg);
     }
@@ -365,7 +395,12 @@ template <typename T> struct Runner {
             const EpiGeneric<T>& e, const char* what) {
     if (dry || err) return;
     GemmShape sh{M, N, K, batch, 0};
-    int rc = launch_gemm<T, EpiGeneric<T>>(st, A, akc, B, bkc, sh, e);
+    prof_begin(st);
+    bool al = false;
+    int rc = launch_gemm<T, EpiGeneric<T>>(st, A, akc, B, bkc, sh, e, &al);
+    char kn[64];
+    snprintf(kn, sizeof(kn), "gemm_kernel<%s,%s,%s,EpiGeneric>", akc ? "kc" : "xc", bkc ? "kc" : "xc", al ? "vec" : "elem");
+    prof_end(st, what, kn, 2.0 * M * N * K * batch, ((double)M * K + (double)N * K + (double)M * N) * batch * sizeof(T));
     if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = std::string("gemm operand alignment: ") + what; return; }
     check(what);
   }
@@ -383,7 +418,12 @@ template <typename T> struct Runner {
     if (!dry && !err) {
       GemmShape sh{rows, cols, (int)K, nsplit, (int)kc};
       EpiPartial ep{part, (long long)rows * cols, cols};
-      int rc = launch_gemm<T, EpiPartial>(st, X, xkc, Y, ykc, sh, ep);
+      prof_begin(st);
+      bool al = false;
+      int rc = launch_gemm<T, EpiPartial>(st, X, xkc, Y, ykc, sh, ep, &al);
+      char kn[64];
+      snprintf(kn, sizeof(kn), "gemm_kernel<%s,%s,%s,EpiPartial>", xkc ? "kc" : "xc", ykc ? "kc" : "xc", al ? "vec" : "elem");
+      prof_end(st, what, kn, 2.0 * rows * cols * K, ((double)rows * K + (double)cols * K) * sizeof(T));
       if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = std::string("gemm_dw operand alignment: ") + what; }
       else check(what);
       reduce_to(st, part, nsplit, (long long)rows * cols, rows, cols, nseg, segs);
@@ -401,9 +441,8 @@ template <typename T> struct Runner {
     k_ln_fwd(st, x, p.ln_g, p.ln_b, c.xhat, c.stats, M, Cc);
     if (c.bias && !dry && !err) {
       int grid = (int)std::min<long long>((Mz + 3) / 4, 4096);
-      hipLaunchKernelGGL(ln_bias_fwd_kernel<T>, dim3(grid), dim3(256), 0, st, bias_src, P(bias_ln_g), P(bias_ln_b),
-                         P(p.w_bias), c.bias, c.zstats, d.r, d.c_z, H, d.ln_eps, g.bias_transposed);
-      check("ln_bias_fwd");
+      PE_LAUNCH("ln_bias_fwd", 2.0 * Mz * d.c_z * H, 1.0 * Mz * d.c_z * sizeof(T) + 4.0 * Mz * H, st, ln_bias_fwd_kernel<T>, dim3(grid), dim3(256), 0, bias_src, P(bias_ln_g), P(bias_ln_b),
+                         P(p.w_bias), c.bias, c.biasT, c.zstats, d.r, d.c_z, H, d.ln_eps, g.bias_transposed);
     }
     {
       EpiGeneric<T> e = epi_plain<T>(c.qkvg, 4 * HD);
@@ -416,11 +455,10 @@ template <typename T> struct Runner {
       memset(&a, 0, sizeof(a));
       a.qkvg = c.qkvg; a.batch_stride = g.batch_stride; a.seq_stride = g.seq_stride;
       a.B = (int)g.B; a.L = (int)g.L; a.H = H; a.d = dh;
-      a.bias = c.bias; a.mask = g.mask; a.mask_bs = g.mask_bs; a.mask_ks = g.mask_ks;
+      a.bias = c.bias; a.biasT = c.biasT; a.mask = g.mask; a.mask_bs = g.mask_bs; a.mask_ks = g.mask_ks;
       a.o = c.o; a.og = c.og; a.lse = c.lse; a.scale = 1.0f / sqrtf((float)dh);
       dim3 grid((unsigned)((g.L + 127) / 128), H, (unsigned)g.B);
-      hipLaunchKernelGGL(attn_fwd_kernel<T>, grid, dim3(256), 0, st, a);
-      check("attn_fwd");
+      PE_LAUNCH("attn_fwd", 4.0 * g.B * H * g.L * g.L * dh, (5.0 * M * HD + 1.0 * M * HD) * sizeof(T) + (c.bias ? 4.0 * H * g.L * g.L : 0.0), st, attn_fwd_kernel<T>, grid, dim3(256), 0, a);
     }
     {
       EpiGeneric<T> e = epi_plain<T>(xout, Cc);
@@ -457,9 +495,8 @@ template <typename T> struct Runner {
     }
     if (!dry && !err) {
       long long n = (long long)ct * Mz;
-      hipLaunchKernelGGL(tm_gate_fwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, c.proj_t, pair_mask,
+      PE_LAUNCH("tm_gate_fwd", 0, 6.0 * n * sizeof(T), st, tm_gate_fwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c.proj_t, pair_mask,
                          c.a_t, c.b_t, ct, Mz);
-      check("tm_gate_fwd");
     }
     {  // per-channel contraction over the third residue
       EpiGeneric<T> e = epi_plain<T>(c.x_t, r);
@@ -469,9 +506,8 @@ template <typename T> struct Runner {
     }
     if (!dry && !err) {
       size_t lds = (size_t)64 * (ct + 1) * sizeof(float);
-      hipLaunchKernelGGL(ln_cmajor_fwd_kernel<T>, dim3((unsigned)((Mz + 63) / 64)), dim3(256), lds, st, c.x_t,
+      PE_LAUNCH("ln_cmajor_fwd", 0, 2.0 * Mz * ct * sizeof(T), st, ln_cmajor_fwd_kernel<T>, dim3((unsigned)((Mz + 63) / 64)), dim3(256), lds, c.x_t,
                          P(p.ln_out_g), P(p.ln_out_b), c.xhat, c.stats_out, Mz, ct, d.ln_eps);
-      check("ln_cmajor_fwd");
     }
     {
       EpiGeneric<T> e = epi_plain<T>(c.g, cz);
@@ -515,9 +551,8 @@ template <typename T> struct Runner {
            co, d.c_m, 1, e, "opm ab");
     }
     if (!dry && !err) {
-      hipLaunchKernelGGL(opm_norm_kernel, dim3((unsigned)((Mz + 255) / 256)), dim3(256), 0, sm, msa_mask, C.opm.inv_norm,
+      PE_LAUNCH("opm_norm", 2.0 * Mz * d.s, 4.0 * (Mz + Mm), sm, opm_norm_kernel, dim3((unsigned)((Mz + 255) / 256)), dim3(256), 0, msa_mask, C.opm.inv_norm,
                          d.s, r, d.opm_eps);
-      check("opm_norm");
     }
     {
       EpiGeneric<T> e = epi_plain<T>(C.opm.O, Wd);
@@ -599,22 +634,18 @@ template <typename T> struct Runner {
       memset(&a, 0, sizeof(a));
       a.qkvg = c.qkvg; a.batch_stride = gm.batch_stride; a.seq_stride = gm.seq_stride;
       a.B = (int)gm.B; a.L = (int)gm.L; a.H = H; a.d = dh;
-      a.bias = c.bias; a.mask = gm.mask; a.mask_bs = gm.mask_bs; a.mask_ks = gm.mask_ks;
+      a.bias = c.bias; a.biasT = c.biasT; a.mask = gm.mask; a.mask_bs = gm.mask_bs; a.mask_ks = gm.mask_ks;
       a.o = c.o; a.og = c.og; a.lse = c.lse; a.scale = 1.0f / sqrtf((float)dh);
       a.dog = dog; a.dO = dO; a.D = Dv; a.dqkvg = dqkvg; a.dS = dS;
       long long tot = gm.B * gm.L * H;
-      hipLaunchKernelGGL(attn_bwd_pre_kernel<T>, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a);
-      check("attn_bwd_pre");
+      PE_LAUNCH("attn_bwd_pre", 0, 5.0 * M * HD * sizeof(T), st, attn_bwd_pre_kernel<T>, dim3((unsigned)((tot * 8 + 255) / 256)), dim3(256), 0, a);
       dim3 grid((unsigned)((gm.L + 127) / 128), H, (unsigned)gm.B);
-      hipLaunchKernelGGL(attn_bwd_dq_kernel<T>, grid, dim3(256), 0, st, a);
-      check("attn_bwd_dq");
-      hipLaunchKernelGGL(attn_bwd_dkv_kernel<T>, grid, dim3(256), 0, st, a);
-      check("attn_bwd_dkv");
+      PE_LAUNCH("attn_bwd_dq", 6.0 * gm.B * H * gm.L * gm.L * dh, 5.0 * M * HD * sizeof(T) + (c.bias ? 1.0 * gm.B * H * gm.L * gm.L * sizeof(T) : 0.0), st, attn_bwd_dq_kernel<T>, grid, dim3(256), 0, a);
+      PE_LAUNCH("attn_bwd_dkv", 8.0 * gm.B * H * gm.L * gm.L * dh, 6.0 * M * HD * sizeof(T), st, attn_bwd_dkv_kernel<T>, grid, dim3(256), 0, a);
       if (c.bias) {
         long long hll = (long long)H * gm.L * gm.L;
-        hipLaunchKernelGGL(attn_dbias_reduce_kernel<T>, dim3((unsigned)((hll + 255) / 256)), dim3(256), 0, st, dS, dbias,
+        PE_LAUNCH("attn_dbias_reduce", 0, 1.0 * gm.B * hll * sizeof(T) + 4.0 * hll, st, attn_dbias_reduce_kernel<T>, dim3((unsigned)((hll + 255) / 256)), dim3(256), 0, dS, dbias,
                            (int)gm.B, hll);
-        check("attn_dbias_reduce");
       }
     }
     k_colsum(st, ar, dqkvg + 3 * HD, M, HD, 4 * HD, p.b_g);
@@ -629,9 +660,8 @@ template <typename T> struct Runner {
       int plen = 2 * cz + cz * H;
       float* part = (float*)ar.alloc((size_t)grid * plen * sizeof(float));
       if (!dry && !err) {
-        hipLaunchKernelGGL(ln_bias_bwd_kernel<T>, dim3(grid), dim3(256), 0, st, dbias, bias_src, c.zstats, P(bias_ln_g),
-                           P(bias_ln_b), P(p.w_bias), bias_gin, bias_gout, part, d.r, cz, H, gm.bias_transposed);
-        check("ln_bias_bwd");
+        PE_LAUNCH("ln_bias_bwd", 4.0 * Mz * cz * H, (bias_gin ? 3.0 : 2.0) * Mz * cz * sizeof(T) + 4.0 * Mz * H, st, ln_bias_bwd_kernel<T>, dim3(grid), dim3(256), 0, dbias, bias_src, c.zstats, P(bias_ln_g),
+                           P(bias_ln_b), P(p.w_bias), bias_gin, bias_gout, part, d.r, cz, H, gm.bias_transposed ^ 1);
         ReduceSeg sg[3] = {{0, cz, bias_ln_g, 0}, {cz, cz, bias_ln_b, 0}, {2 * cz, cz * H, p.w_bias, 0}};
         reduce_to(st, part, grid, plen, 1, plen, 3, sg);
       }
@@ -653,8 +683,7 @@ template <typename T> struct Runner {
     T* dzh = (T*)ar.alloc((size_t)Mz * cz * sizeof(T));
     if (!dry && !err) {
       long long n = Mz * cz;
-      hipLaunchKernelGGL(tm_out_bwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, g, c.g, c.u, du, dgraw, n);
-      check("tm_out_bwd");
+      PE_LAUNCH("tm_out_bwd", 0, 5.0 * n * sizeof(T), st, tm_out_bwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, g, c.g, c.u, du, dgraw, n);
     }
     k_colsum(st, ar, du, Mz, cz, cz, p.b_o);
     { ReduceSeg sg[1] = {{0, cz, p.w_o, cz}};
@@ -667,9 +696,8 @@ template <typename T> struct Runner {
       float* part = (float*)ar.alloc((size_t)grid * 2 * ct * sizeof(float));
       if (!dry && !err) {
         size_t lds = (size_t)64 * (ct + 1) * sizeof(float);
-        hipLaunchKernelGGL(ln_cmajor_bwd_kernel<T>, dim3(grid), dim3(256), lds, st, dxh_o, c.x_t, c.stats_out,
+        PE_LAUNCH("ln_cmajor_bwd", 0, 3.0 * Mz * ct * sizeof(T), st, ln_cmajor_bwd_kernel<T>, dim3(grid), dim3(256), lds, dxh_o, c.x_t, c.stats_out,
                            P(p.ln_out_g), dx_t, part, Mz, ct);
-        check("ln_cmajor_bwd");
         ReduceSeg sg[2] = {{0, ct, p.ln_out_g, 0}, {ct, ct, p.ln_out_b, 0}};
         reduce_to(st, part, grid, 2LL * ct, 1, 2 * ct, 2, sg);
       }
@@ -690,16 +718,20 @@ template <typename T> struct Runner {
     }
     if (!dry && !err) {
       long long n = (long long)ct * Mz;
-      hipLaunchKernelGGL(tm_gate_bwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, c.proj_t, pair_mask,
+      PE_LAUNCH("tm_gate_bwd", 0, 10.0 * n * sizeof(T), st, tm_gate_bwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c.proj_t, pair_mask,
                          da_t, db_t, dproj_t, ct, Mz);
-      check("tm_gate_bwd");
-      // bias gradients: row sums of the channel-major projection gradients
-      const long long boff[4] = {p.b_ap, p.b_ag, p.b_bp, p.b_bg};
-      for (int k = 0; k < 4; k++) {
-        hipLaunchKernelGGL(rowsum_kernel<T>, dim3(ct), dim3(256), 0, st, dproj_t + (long long)k * ct * Mz, Mz,
-                           dparams + boff[k]);
-        check("rowsum");
+    }
+    {  // bias gradients: row sums of the channel-major projection gradients (two stages)
+      size_t mk2 = ar.mark();
+      const int nch = 16;
+      float* part = (float*)ar.alloc((size_t)nch * 4 * ct * sizeof(float));
+      if (!dry && !err) {
+        PE_LAUNCH("rowsum", 0, 4.0 * ct * Mz * sizeof(T), st, rowsum_kernel<T>, dim3(4 * ct, nch), dim3(256), 0, dproj_t, Mz,
+                  part, 4 * ct);
+        ReduceSeg sg[4] = {{0, ct, p.b_ap, 0}, {ct, ct, p.b_ag, 0}, {2 * ct, ct, p.b_bp, 0}, {3 * ct, ct, p.b_bg, 0}};
+        reduce_to(st, part, nch, 4LL * ct, 1, 4 * ct, 4, sg);
       }
+      ar.release(mk2);
     }
     k_colsum(st, ar, dgraw, Mz, cz, cz, p.b_g);
     { ReduceSeg sg[4] = {{0, ct, p.w_ap, ct}, {ct, ct, p.w_ag, ct}, {2 * ct, ct, p.w_bp, ct}, {3 * ct, ct, p.w_bg, ct}};
@@ -1033,6 +1065,7 @@ int pe_create(pe_handle** out) {
   pe_handle* h = new pe_handle();
   h->branches = 3;
   h->sync_debug = 0;
+  h->timing = 0;
   for (int i = 0; i < 6; i++) {
     if (hipEventCreateWithFlags(&h->ev[i], hipEventDisableTiming) != hipSuccess) {
       for (int j = 0; j < i; j++) (void)hipEventDestroy(h->ev[j]);
@@ -1046,6 +1079,8 @@ int pe_create(pe_handle** out) {
 int pe_destroy(pe_handle* h) {
   if (!h) return PE_ERR_NULL;
   for (int i = 0; i < 6; i++) (void)hipEventDestroy(h->ev[i]);
+  for (auto& r : h->recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
+  for (auto e : h->ev_pool) (void)hipEventDestroy(e);
   delete h;
   return PE_OK;
 }
@@ -1053,6 +1088,7 @@ int pe_set_option(pe_handle* h, int option, int value) {
   if (!h) return PE_ERR_NULL;
   if (option == PE_OPT_BRANCHES) { if (value < 1 || value > 3) return PE_ERR_ARG; h->branches = value; return PE_OK; }
   if (option == PE_OPT_SYNC_DEBUG) { h->sync_debug = value ? 1 : 0; return PE_OK; }
+  if (option == PE_OPT_KERNEL_TIMING) { h->timing = value ? 1 : 0; return PE_OK; }
   return PE_ERR_ARG;
 }
 int pe_check_dims(const pe_dims* d) {
@@ -1180,6 +1216,38 @@ int pe_stack_fwd_bwd(pe_handle* h, int n_extra, const pe_dims* extra, int n_main
   return stack_impl<float>(h, n_extra, extra, n_main, main_, sp, extra_msa_in, msa_in, pair_in, extra_msa_mask, msa_mask,
                            pair_mask, params, d_msa_out, d_pair_out, msa_out, pair_out, d_extra_msa_in, d_msa_in,
                            d_pair_in, d_params, (char*)workspace, (hipStream_t)stream_msa, (hipStream_t)stream_pair);
+}
+
+int pe_timing_collect(pe_handle* h, pe_timing_entry* out, int cap) {
+  if (!h) return PE_ERR_NULL;
+  if (hipDeviceSynchronize() != hipSuccess) { h->last_error = "timing: device synchronize failed"; return PE_ERR_HIP; }
+  std::vector<pe_timing_entry> agg;
+  for (auto& r : h->recs) {
+    float ms = 0.0f;
+    (void)hipEventElapsedTime(&ms, r.e0, r.e1);
+    size_t k = 0;
+    for (; k < agg.size(); k++)
+      if (!strncmp(agg[k].name, r.label, sizeof(agg[k].name) - 1) &&
+          !strncmp(agg[k].kernel, r.kern.c_str(), sizeof(agg[k].kernel) - 1)) break;
+    if (k == agg.size()) {
+      pe_timing_entry e;
+      memset(&e, 0, sizeof(e));
+      snprintf(e.name, sizeof(e.name), "%s", r.label);
+      snprintf(e.kernel, sizeof(e.kernel), "%s", r.kern.c_str());
+      agg.push_back(e);
+    }
+    agg[k].launches += 1;
+    agg[k].total_ms += ms;
+    agg[k].flops += r.flops;
+    agg[k].bytes += r.bytes;
+  }
+  int n = (int)agg.size();
+  if (!out) return n;               // query only: records are kept
+  if (cap < n) return PE_ERR_ARG;
+  for (int i = 0; i < n; i++) out[i] = agg[i];
+  for (auto& r : h->recs) { h->ev_pool.push_back(r.e0); h->ev_pool.push_back(r.e1); }
+  h->recs.clear();
+  return n;
 }
 
 const char* pe_strerror(int code) {

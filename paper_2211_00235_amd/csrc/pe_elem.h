@@ -246,8 +246,8 @@ __global__ __launch_bounds__(256) void ln_cmajor_bwd_kernel(const T* dy, const T
 constexpr int BIAS_MAXH = 8;
 template <typename T>
 __global__ __launch_bounds__(256) void ln_bias_fwd_kernel(const T* z, const float* gamma, const float* beta,
-                                                          const float* w /*[C][H]*/, float* bias, float* stats, int r,
-                                                          int C, int H, float eps, int transposed) {
+                                                          const float* w /*[C][H]*/, float* bias, float* biasT,
+                                                          float* stats, int r, int C, int H, float eps, int transposed) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = lane * 4;
   float gm[4], bt[4], wv[4][BIAS_MAXH];
@@ -274,12 +274,13 @@ __global__ __launch_bounds__(256) void ln_bias_fwd_kernel(const T* z, const floa
     for (int e = 0; e < 4; e++) y[e] = (c < C) ? (v[e] - mu) * rstd * gm[e] + bt[e] : 0.0f;
     int i = row / r, j = row % r;
     long long o = transposed ? ((long long)j * r + i) : row;
+    long long oT = transposed ? row : ((long long)j * r + i);
 #pragma unroll
     for (int h = 0; h < BIAS_MAXH; h++) {
       if (h < H) {
         float t = y[0] * wv[0][h] + y[1] * wv[1][h] + y[2] * wv[2][h] + y[3] * wv[3][h];
         t = wave_sum(t);
-        if (lane == 0) bias[(long long)h * M + o] = t;
+        if (lane == 0) { bias[(long long)h * M + o] = t; biasT[(long long)h * M + oT] = t; }
       }
     }
     if (lane == 0) { stats[row * 2] = mu; stats[row * 2 + 1] = rstd; }
@@ -371,13 +372,21 @@ struct ReduceArgs {
   int nseg; ReduceSeg seg[5];
   float* dst;
 };
-__global__ void reduce_partials_kernel(ReduceArgs a) {
-  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  long long total = (long long)a.rows * a.cols;
-  if (idx >= total) return;
-  int m = idx / a.cols, n = idx % a.cols;
+// 1024 threads = 64 outputs x 16 split lanes; fixed summation order (deterministic)
+__global__ __launch_bounds__(1024) void reduce_partials_kernel(ReduceArgs a) {
+  __shared__ float red[16][64];
+  const int x = threadIdx.x & 63, y = threadIdx.x >> 6;
+  const long long total = (long long)a.rows * a.cols;
+  const long long idx = (long long)blockIdx.x * 64 + x;
   float s = 0.0f;
-  for (int k = 0; k < a.nsplit; k++) s += a.part[(long long)k * a.stride + idx];
+  if (idx < total)
+    for (int k = y; k < a.nsplit; k += 16) s += a.part[(long long)k * a.stride + idx];
+  red[y][x] = s;
+  __syncthreads();
+  if (y != 0 || idx >= total) return;
+#pragma unroll
+  for (int k = 1; k < 16; k++) s += red[k][x];
+  int m = idx / a.cols, n = idx % a.cols;
   for (int q = 0; q < a.nseg; q++) {
     const ReduceSeg& g = a.seg[q];
     if (n >= g.n_begin && n < g.n_begin + g.n_count) {
@@ -387,30 +396,70 @@ __global__ void reduce_partials_kernel(ReduceArgs a) {
   }
 }
 
-// column sums of a channel-last tensor y[M][N] (row stride ld): partial[wg][N]
+// column sums of a channel-last tensor y[M][N] (row stride ld): partial[wg][N].
+// Thread = (column group of 4, row lane); 8/16-byte loads, LDS reduction over row lanes.
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T* y, long long M, int N, long long ld, float* partial,
                                                      long long rows_per_wg) {
-  long long r0 = (long long)blockIdx.x * rows_per_wg;
-  long long r1 = r0 + rows_per_wg < M ? r0 + rows_per_wg : M;
-  for (int n = threadIdx.x; n < N; n += 256) {
-    float s = 0.0f;
-    for (long long m = r0; m < r1; m++) s += to_f(y[m * ld + n]);
-    partial[(long long)blockIdx.x * N + n] = s;
+  __shared__ float red[256][4];
+  const long long r0 = (long long)blockIdx.x * rows_per_wg;
+  const long long r1 = r0 + rows_per_wg < M ? r0 + rows_per_wg : M;
+  const int ncg = N / 4;
+  const int tid = threadIdx.x;
+  if (ncg >= 256) {
+    for (int cg = tid; cg < ncg; cg += 256) {
+      float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      for (long long m = r0; m < r1; m++) {
+        float v[4];
+        load4<T>(y + m * ld + cg * 4, v);
+        s[0] += v[0]; s[1] += v[1]; s[2] += v[2]; s[3] += v[3];
+      }
+      store4<float>(partial + (long long)blockIdx.x * N + cg * 4, s);
+    }
+    return;
+  }
+  const int RL = 256 / ncg;
+  const int cg = tid % ncg, rl = tid / ncg;
+  float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  if (rl < RL)
+    for (long long m = r0 + rl; m < r1; m += RL) {
+      float v[4];
+      load4<T>(y + m * ld + cg * 4, v);
+      s[0] += v[0]; s[1] += v[1]; s[2] += v[2]; s[3] += v[3];
+    }
+  red[tid][0] = s[0]; red[tid][1] = s[1]; red[tid][2] = s[2]; red[tid][3] = s[3];
+  __syncthreads();
+  if (rl == 0) {
+    for (int k = 1; k < RL; k++) {
+      s[0] += red[k * ncg + cg][0]; s[1] += red[k * ncg + cg][1];
+      s[2] += red[k * ncg + cg][2]; s[3] += red[k * ncg + cg][3];
+    }
+    store4<float>(partial + (long long)blockIdx.x * N + cg * 4, s);
   }
 }
 
-// row sums of a channel-major tensor yt[N][M]: dst[n] += sum_m yt[n][m]  (one workgroup per row)
+// row sums of a channel-major tensor yt[rows][M]: partial[chunk][row] (grid = rows x chunks)
 template <typename T>
-__global__ __launch_bounds__(256) void rowsum_kernel(const T* yt, long long M, float* dst) {
+__global__ __launch_bounds__(256) void rowsum_kernel(const T* yt, long long M, float* partial, int nrows) {
   __shared__ float red[4];
+  const long long per = ((M + gridDim.y - 1) / gridDim.y + 3) / 4 * 4;
+  const long long m0 = (long long)blockIdx.y * per;
+  const long long m1 = m0 + per < M ? m0 + per : M;
   const T* p = yt + (long long)blockIdx.x * M;
   float s = 0.0f;
-  for (long long m = threadIdx.x; m < M; m += 256) s += to_f(p[m]);
+  if ((M & 3) == 0) {
+    for (long long m = m0 + threadIdx.x * 4; m < m1; m += 1024) {
+      float v[4];
+      load4<T>(p + m, v);
+      s += v[0] + v[1] + v[2] + v[3];
+    }
+  } else {
+    for (long long m = m0 + threadIdx.x; m < m1; m += 256) s += to_f(p[m]);
+  }
   s = wave_sum(s);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
   __syncthreads();
-  if (threadIdx.x == 0) dst[blockIdx.x] += red[0] + red[1] + red[2] + red[3];
+  if (threadIdx.x == 0) partial[(long long)blockIdx.y * nrows + blockIdx.x] = red[0] + red[1] + red[2] + red[3];
 }
 
 // ---------------------------------------------------------------------------

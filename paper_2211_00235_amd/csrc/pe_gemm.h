@@ -64,7 +64,25 @@ template <typename T> struct EpiGeneric {
   const T* res; long long ld_res;        // v += res[m][n]
   int accumulate;                        // v += out (read-modify-write)
 
-  PE_DEV void operator()(int b, int m, int n, float v) const {
+  // Per-row and per-column parts of the addressing are computed once per row / column.
+  struct Row { long long o; long long s2; };
+  struct Col { long long o; int s2; };
+  PE_DEV Row row(int b, int m) const {
+    Row r;
+    r.o = (long long)b * out_batch +
+          ((om_in >= (1 << 30)) ? (long long)m * om_stride
+                                : (long long)(m / om_in) * om_outer + (long long)(m % om_in) * om_stride);
+    r.s2 = scale2d ? (long long)(m / s2_mdiv) * s2_ld : 0;
+    return r;
+  }
+  PE_DEV Col col(int n) const {
+    Col c;
+    c.o = (on_in >= (1 << 30)) ? (long long)n * on_stride
+                               : (long long)(n / on_in) * on_outer + (long long)(n % on_in) * on_stride;
+    c.s2 = scale2d ? n / s2_ndiv : 0;
+    return c;
+  }
+  PE_DEV void operator()(int m, int n, const Row& r, const Col& c, float v) const {
     v *= alpha;
     if (bias_n && n >= bn_begin) v += bias_n[n];
     if (bias_m) v += bias_m[m];
@@ -74,10 +92,9 @@ template <typename T> struct EpiGeneric {
     if (aux) aux[(long long)m * ld_aux + n] = from_f<T>(v);
     if (mul) v *= to_f(mul[(long long)m * ld_mul + n]);
     if (rowscale) v *= rowscale[m];
-    if (scale2d) v *= scale2d[(long long)(m / s2_mdiv) * s2_ld + (n / s2_ndiv)];
+    if (scale2d) v *= scale2d[r.s2 + c.s2];
     if (res) v += to_f(res[(long long)m * ld_res + n]);
-    long long o = (long long)b * out_batch + (long long)(m / om_in) * om_outer + (long long)(m % om_in) * om_stride +
-                  (long long)(n / on_in) * on_outer + (long long)(n % on_in) * on_stride;
+    long long o = r.o + c.o;
     if (accumulate) v += to_f(out[o]);
     out[o] = from_f<T>(v);
   }
@@ -96,7 +113,11 @@ template <typename T> static inline EpiGeneric<T> epi_plain(void* out, long long
 // fp32 partial sums of a split-K GEMM: part[b][m][n]
 struct EpiPartial {
   float* out; long long mn; int ldn;
-  PE_DEV void operator()(int b, int m, int n, float v) const { out[(long long)b * mn + (long long)m * ldn + n] = v; }
+  struct Row { long long o; };
+  struct Col { long long o; };
+  PE_DEV Row row(int b, int m) const { return Row{(long long)b * mn + (long long)m * ldn}; }
+  PE_DEV Col col(int n) const { return Col{(long long)n}; }
+  PE_DEV void operator()(int, int, const Row& r, const Col& c, float v) const { out[r.o + c.o] = v; }
 };
 
 // ---------------------------------------------------------------------------
@@ -128,59 +149,78 @@ PE_DEV typename Vec16<T>::type gemm_load_slow(const T* base, const Operand& op, 
   return v;
 }
 
+// Per-thread row part of the tile addressing, computed once before the k loop.
+template <typename T, bool KC> struct RowAddr {
+  long long a[KC ? 4 : 1];
+  bool ok[KC ? 4 : 1];
+  int x[KC ? 4 : 1];
+  PE_DEV void init(const Operand& op, int x0, int X, int tid) {
+    constexpr int VEC = Vec16<T>::N;
+    if (KC) {
+#pragma unroll
+      for (int i = 0; i < (KC ? 4 : 1); i++) {
+        int xx = x0 + (tid >> 3) + 32 * i;
+        x[i] = xx;
+        ok[i] = xx < X;
+        int xc = ok[i] ? xx : 0;
+        a[i] = (op.x_in >= (1 << 30)) ? (long long)xc * op.x_stride
+                                      : (long long)(xc / op.x_in) * op.x_outer + (long long)(xc % op.x_in) * op.x_stride;
+      }
+    } else {
+      constexpr int XB = 128 / VEC;
+      int xx = x0 + (tid % XB) * VEC;
+      x[0] = xx;
+      ok[0] = xx < X;
+      int xc = ok[0] ? xx : 0;
+      a[0] = (op.x_in >= (1 << 30)) ? (long long)xc : (long long)(xc / op.x_in) * op.x_outer + (long long)(xc % op.x_in);
+    }
+  }
+};
+PE_DEV long long gemm_kaddr(const Operand& op, int k) {
+  return (op.k_in >= (1 << 30)) ? (long long)k * op.k_stride
+                                : (long long)(k / op.k_in) * op.k_outer + (long long)(k % op.k_in) * op.k_stride;
+}
+
 template <typename T, bool KC, bool AL>
-PE_DEV void gemm_load_tile(typename Vec16<T>::type (&regs)[4], const T* base, const Operand& op, int x0, int X, int k0,
-                           int kend, int tid) {
+PE_DEV void gemm_load_tile(typename Vec16<T>::type (&regs)[4], const T* base, const Operand& op, const RowAddr<T, KC>& ra,
+                           int X, int k0, int kend, int tid) {
   constexpr int VEC = Vec16<T>::N;
   typedef typename Vec16<T>::type V;
   if (!AL) {
     if (KC) {
       int kv = tid & 7;
 #pragma unroll
-      for (int i = 0; i < 4; i++) regs[i] = gemm_load_slow<T, true>(base, op, x0 + (tid >> 3) + 32 * i, X, k0 + kv * VEC, kend);
+      for (int i = 0; i < 4; i++) regs[i] = gemm_load_slow<T, true>(base, op, ra.x[i], X, k0 + kv * VEC, kend);
     } else {
-      constexpr int XB = 128 / VEC;
-      int xb = tid % XB, kb = tid / XB;
+      int kb = tid / (128 / VEC);
 #pragma unroll
-      for (int j = 0; j < 4; j++) regs[j] = gemm_load_slow<T, false>(base, op, x0 + xb * VEC, X, k0 + kb * 4 + j, kend);
+      for (int j = 0; j < 4; j++) regs[j] = gemm_load_slow<T, false>(base, op, ra.x[0], X, k0 + kb * 4 + j, kend);
     }
     return;
   }
   if (KC) {
     // thread loads 4 vectors: row = tid/8 + 32*i, k-vector kv = tid%8
-    int kv = tid & 7;
-    int k = k0 + kv * VEC;
-    long long ka = (long long)(k / op.k_in) * op.k_outer + (long long)(k % op.k_in);
+    int k = k0 + (tid & 7) * VEC;
+    long long ka = gemm_kaddr(op, k);
     bool kok = k < kend;
 #pragma unroll
     for (int i = 0; i < 4; i++) {
-      int x = x0 + (tid >> 3) + 32 * i;
       V v;
 #pragma unroll
       for (int e = 0; e < VEC; e++) v[e] = from_f<T>(0.0f);
-      if (kok && x < X) {
-        long long xa = (long long)(x / op.x_in) * op.x_outer + (long long)(x % op.x_in) * op.x_stride;
-        v = *reinterpret_cast<const V*>(base + xa + ka);
-      }
+      if (kok && ra.ok[i]) v = *reinterpret_cast<const V*>(base + ra.a[i] + ka);
       regs[i] = v;
     }
   } else {
     // micro-block: VEC rows (x) by 4 contraction steps; 4 loads of VEC elements along x
-    constexpr int XB = 128 / VEC;
-    int xb = tid % XB, kb = tid / XB;
-    int x = x0 + xb * VEC;
-    bool xok = x < X;
-    long long xa = (long long)(x / op.x_in) * op.x_outer + (long long)(x % op.x_in);
+    int kb = tid / (128 / VEC);
 #pragma unroll
     for (int j = 0; j < 4; j++) {
       int k = k0 + kb * 4 + j;
       V v;
 #pragma unroll
       for (int e = 0; e < VEC; e++) v[e] = from_f<T>(0.0f);
-      if (xok && k < kend) {
-        long long ka = (long long)(k / op.k_in) * op.k_outer + (long long)(k % op.k_in) * op.k_stride;
-        v = *reinterpret_cast<const V*>(base + xa + ka);
-      }
+      if (ra.ok[0] && k < kend) v = *reinterpret_cast<const V*>(base + ra.a[0] + gemm_kaddr(op, k));
       regs[j] = v;
     }
   }
@@ -245,9 +285,13 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.0f;
 
   V ra[4], rb[4];
+  RowAddr<T, A_KC> rowa;
+  RowAddr<T, B_KC> rowb;
+  rowa.init(A, m0, sh.M, tid);
+  rowb.init(B, n0, sh.N, tid);
   if (kbeg < kend) {
-    gemm_load_tile<T, A_KC, AL>(ra, pa, A, m0, sh.M, kbeg, kend, tid);
-    gemm_load_tile<T, B_KC, AL>(rb, pb, B, n0, sh.N, kbeg, kend, tid);
+    gemm_load_tile<T, A_KC, AL>(ra, pa, A, rowa, sh.M, kbeg, kend, tid);
+    gemm_load_tile<T, B_KC, AL>(rb, pb, B, rowb, sh.N, kbeg, kend, tid);
   }
   for (int k0 = kbeg; k0 < kend; k0 += C::BK) {
     __syncthreads();  // previous tile fully consumed
@@ -255,8 +299,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
     gemm_store_tile<T, B_KC>(rb, lds_b, tid);
     __syncthreads();
     if (k0 + C::BK < kend) {
-      gemm_load_tile<T, A_KC, AL>(ra, pa, A, m0, sh.M, k0 + C::BK, kend, tid);
-      gemm_load_tile<T, B_KC, AL>(rb, pb, B, n0, sh.N, k0 + C::BK, kend, tid);
+      gemm_load_tile<T, A_KC, AL>(ra, pa, A, rowa, sh.M, k0 + C::BK, kend, tid);
+      gemm_load_tile<T, B_KC, AL>(rb, pb, B, rowb, sh.N, k0 + C::BK, kend, tid);
     }
 #pragma unroll
     for (int kk = 0; kk < C::BK / MM::KSTEP; kk++) {
@@ -273,15 +317,23 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
     }
   }
 
+  typename Epi::Col cols[2];
+  int ncol[2];
+#pragma unroll
+  for (int j = 0; j < 2; j++) {
+    ncol[j] = n0 + wn * 64 + j * 32 + l32;
+    cols[j] = epi.col(ncol[j] < sh.N ? ncol[j] : 0);
+  }
 #pragma unroll
   for (int i = 0; i < 2; i++)
 #pragma unroll
-    for (int j = 0; j < 2; j++) {
-      int n = n0 + wn * 64 + j * 32 + l32;
+    for (int a = 0; a < 16; a++) {
+      int m = m0 + wm * 64 + i * 32 + acc_row(g, a);
+      if (m < sh.M) {
+        typename Epi::Row r = epi.row(b, m);
 #pragma unroll
-      for (int a = 0; a < 16; a++) {
-        int m = m0 + wm * 64 + i * 32 + acc_row(g, a);
-        if (m < sh.M && n < sh.N) epi(b, m, n, acc[i][j][a]);
+        for (int j = 0; j < 2; j++)
+          if (ncol[j] < sh.N) epi(m, ncol[j], r, cols[j], acc[i][j][a]);
       }
     }
 }
@@ -324,12 +376,13 @@ static inline void launch_gemm_al(hipStream_t st, dim3 grid, const Operand& A, b
 // element-wise loader: same tiles, same arithmetic, slower loads.
 template <typename T, class Epi>
 static inline int launch_gemm(hipStream_t st, const Operand& A, bool a_kc, const Operand& B, bool b_kc,
-                              const GemmShape& sh, const Epi& epi) {
+                              const GemmShape& sh, const Epi& epi, bool* used_vec = nullptr) {
   if (sh.M <= 0 || sh.N <= 0 || sh.batch <= 0) return 0;
   if (a_kc ? A.k_stride != 1 : A.x_stride != 1) return -1;
   if (b_kc ? B.k_stride != 1 : B.x_stride != 1) return -1;
   if (sh.k_chunk > 0 && sh.k_chunk % GemmCfg<T>::BK) return -1;
   bool al = gemm_operand_ok<T>(A, a_kc, sh.M, sh) && gemm_operand_ok<T>(B, b_kc, sh.N, sh);
+  if (used_vec) *used_vec = al;
   dim3 grid((sh.N + 127) / 128, (sh.M + 127) / 128, sh.batch);
   if (al) launch_gemm_al<T, true, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);
   else launch_gemm_al<T, false, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);
