@@ -47,6 +47,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="af2_initial")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--detail", action="store_true", help="also print the per-launch-label timing table to stderr")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the one-GPU share of the path only (two HIP streams on one "
@@ -106,6 +107,11 @@ def main():
         one.bwd()
     ent = one.h.timing_collect()
     one.h.set_option(3, 0)
+    if args.detail:
+        for e in sorted(ent, key=lambda e: -e["total_ms"]):
+            print("%-22s %-44s n=%3d  %8.1f us/launch  %7.1f TFLOP/s  %7.1f GB/s" % (
+                e["name"], e["kernel"], e["launches"] // 3, 1e3 * e["total_ms"] / e["launches"],
+                e["flops"] / (e["total_ms"] * 1e-3) / 1e12, e["bytes"] / (e["total_ms"] * 1e-3) / 1e9), file=sys.stderr)
     by_kernel = {}
     for e in ent:
         k = by_kernel.setdefault(e["kernel"], dict(ms=0.0, launches=0, flops=0.0, bytes=0.0))

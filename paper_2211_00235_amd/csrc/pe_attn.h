@@ -105,6 +105,22 @@ template <typename T> PE_DEV typename Mma<T>::frag gl_frag(const T* p, int kk, i
   return MM::load(p + c0);
 }
 
+// Softmax is evaluated in the base-2 domain: t = s * (scale * log2 e) + bias * log2 e, p = 2^(t - m).
+// biasT is stored pre-multiplied by log2 e.  Key masks are applied as an additive 0 / -inf
+// term read from LDS four keys at a time.  All 16 bias loads of a tile are issued before the
+// score MFMAs (clamped addresses, no branches), so their latency overlaps the matrix work.
+#define PE_LOG2E 1.4426950408889634f
+#define PE_LN2 0.6931471805599453f
+
+// bias values of one 32x32 tile for this lane's query: element e <-> key row acc_row(g, e)
+PE_DEV void attn_load_bias16(const float* bcol, int L, int key0 /* first key of the tile + 4g */, float (&bv)[16]) {
+#pragma unroll
+  for (int e = 0; e < 16; e++) {
+    int key = min(key0 + 8 * (e >> 2) + (e & 3), L - 1);
+    bv[e] = bcol[key * L];
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Forward
 // grid (ceil(L/128), H, B), 256 threads; wave w owns queries q0 = blockIdx.x*128 + 32*w
@@ -115,7 +131,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
   typedef Mma<T> MM;
   __shared__ __attribute__((aligned(16))) T lds_k[C::KT * C::RM];
   __shared__ __attribute__((aligned(16))) T lds_vt[32 * C::TS];
-  __shared__ float lds_mask[C::KT];
+  __shared__ __attribute__((aligned(16))) float lds_madd[C::KT];   // 0 for a valid key, -inf for a masked one
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
   const int h = blockIdx.y, b = blockIdx.z;
@@ -137,7 +153,9 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
 #pragma unroll
   for (int e = 0; e < 16; e++) oacc[e] = 0.0f;
   float m_run = -INFINITY, l_run = 0.0f;
-  const float* bcol = (a.biasT && qok) ? a.biasT + (long long)h * L * L + qi : nullptr;   // + key * L
+  const bool has_bias = a.biasT != nullptr;
+  const float* bcol = has_bias ? a.biasT + (long long)h * L * L + min(qi, L - 1) : nullptr;   // + key * L
+  const float c1 = a.scale * PE_LOG2E;
 
   for (int j0 = 0; j0 < L; j0 += C::KT) {
     __syncthreads();
@@ -145,12 +163,15 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
     attn_stage<T>(base + 2 * HD, a.seq_stride, j0, L, d, DP, (T*)nullptr, lds_vt, tid, 256);
     if (tid < C::KT) {
       int j = j0 + tid;
-      lds_mask[tid] = (j < L) ? a.mask[(long long)b * a.mask_bs + (long long)j * a.mask_ks] : 0.0f;
+      float mk = (j < L) ? a.mask[(long long)b * a.mask_bs + (long long)j * a.mask_ks] : 0.0f;
+      lds_madd[tid] = (mk > 0.0f) ? 0.0f : -INFINITY;
     }
     __syncthreads();
 #pragma unroll
     for (int jt = 0; jt < C::KT / 32; jt++) {
       if (j0 + jt * 32 >= L) break;
+      float bv[16];
+      if (has_bias) attn_load_bias16(bcol, L, j0 + jt * 32 + 4 * g, bv);
       f32x16 sacc;
 #pragma unroll
       for (int e = 0; e < 16; e++) sacc[e] = 0.0f;
@@ -160,25 +181,28 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
           typename MM::frag kf = MM::load(lds_k + (jt * 32 + l32) * C::RM + kk * MM::KSTEP + g * MM::KP);
           MM::mma(sacc, kf, qf[kk]);
         }
-      // logits for (query = lane, keys = acc rows)
+      // logits (base-2 domain) for (query = lane, keys = acc rows)
       float tmax = -INFINITY;
 #pragma unroll
-      for (int e = 0; e < 16; e++) {
-        int jj = jt * 32 + acc_row(g, e);
-        float v = sacc[e] * a.scale;
-        if (bcol) v += (j0 + jj < L) ? bcol[(long long)(j0 + jj) * L] : 0.0f;
-        v = (lds_mask[jj] > 0.0f) ? v : -INFINITY;
-        sacc[e] = v;
-        tmax = fmaxf(tmax, v);
+      for (int q4 = 0; q4 < 4; q4++) {
+        f32x4 ma = *reinterpret_cast<const f32x4*>(lds_madd + jt * 32 + 8 * q4 + 4 * g);
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+          int e = q4 * 4 + r;
+          float v = has_bias ? fmaf(sacc[e], c1, bv[e]) : sacc[e] * c1;
+          v += ma[r];
+          sacc[e] = v;
+          tmax = fmaxf(tmax, v);
+        }
       }
       tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
       float m_new = fmaxf(m_run, tmax);
       float m_use = (m_new == -INFINITY) ? 0.0f : m_new;
-      float corr = __expf(m_run - m_use);     // m_run = -inf -> 0
+      float corr = exp2f(m_run - m_use);     // m_run = -inf -> 0
       float psum = 0.0f;
 #pragma unroll
       for (int e = 0; e < 16; e++) {
-        float p = __expf(sacc[e] - m_use);
+        float p = exp2f(sacc[e] - m_use);
         sacc[e] = p;
         psum += p;
       }
@@ -199,18 +223,24 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
   }
   if (!qok) return;
   float inv = (l_run > 0.0f) ? 1.0f / l_run : 0.0f;
-  if (g == 0) a.lse[((long long)b * a.H + h) * L + qi] = (l_run > 0.0f) ? (m_run + __logf(l_run)) : 0.0f;
+  if (g == 0) a.lse[((long long)b * a.H + h) * L + qi] = (l_run > 0.0f) ? (m_run + log2f(l_run)) * PE_LN2 : 0.0f;
   const long long orow = (long long)b * (a.batch_stride / 4) + (long long)qi * (a.seq_stride / 4) + h * d;
   T* po = (T*)a.o + orow;
   T* pog = (T*)a.og + orow;
   const T* pg = qrow + 3 * HD;
 #pragma unroll
-  for (int e = 0; e < 16; e++) {
-    int dd = acc_row(g, e);
+  for (int q4 = 0; q4 < 4; q4++) {
+    int dd = 8 * q4 + 4 * g;
     if (dd < d) {
-      float ov = oacc[e] * inv;
-      po[dd] = from_f<T>(ov);
-      pog[dd] = from_f<T>(ov * sigmoidf_(to_f(pg[dd])));
+      float gv[4], ov[4], ogv[4];
+      load4<T>(pg + dd, gv);
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        ov[r] = oacc[q4 * 4 + r] * inv;
+        ogv[r] = ov[r] * sigmoidf_(gv[r]);
+      }
+      store4<T>(po + dd, ov);
+      store4<T>(pog + dd, ogv);
     }
   }
 }
@@ -268,7 +298,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) T lds_k[C::KT * C::RM];
   __shared__ __attribute__((aligned(16))) T lds_kt[32 * C::TS];
   __shared__ __attribute__((aligned(16))) T lds_v[C::KT * C::RM];
-  __shared__ float lds_mask[C::KT];
+  __shared__ __attribute__((aligned(16))) float lds_madd[C::KT];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
   const int h = blockIdx.y, b = blockIdx.z;
@@ -291,10 +321,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnArgs a) {
       dof[kk] = gl_frag<T>(dorow, kk, g, d);
     }
   const long long sidx = ((long long)b * a.H + h) * L + qi;
-  const float lse = qok ? a.lse[sidx] : 0.0f;
+  const float lse2 = qok ? a.lse[sidx] * PE_LOG2E : 0.0f;
   const float Di = qok ? a.D[sidx] : 0.0f;
-  const float* bcol = (a.biasT && qok) ? a.biasT + (long long)h * L * L + qi : nullptr;       // + key * L
-  T* dscol = (a.dS && qok) ? (T*)a.dS + ((long long)b * a.H + h) * L * L + qi : nullptr;        // + key * L
+  const bool has_bias = a.biasT != nullptr;
+  const float* bcol = has_bias ? a.biasT + (long long)h * L * L + min(qi, L - 1) : nullptr;      // + key * L
+  T* dscol = (a.dS && qok) ? (T*)a.dS + ((long long)b * a.H + h) * L * L + qi : nullptr;         // + key * L
+  const float c1 = a.scale * PE_LOG2E;
 
   f32x16 dq;
 #pragma unroll
@@ -306,12 +338,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnArgs a) {
     attn_stage<T>(base + 2 * HD, a.seq_stride, j0, L, d, DP, lds_v, (T*)nullptr, tid, 256);
     if (tid < C::KT) {
       int j = j0 + tid;
-      lds_mask[tid] = (j < L) ? a.mask[(long long)b * a.mask_bs + (long long)j * a.mask_ks] : 0.0f;
+      float mk = (j < L) ? a.mask[(long long)b * a.mask_bs + (long long)j * a.mask_ks] : 0.0f;
+      lds_madd[tid] = (mk > 0.0f) ? 0.0f : -INFINITY;
     }
     __syncthreads();
 #pragma unroll
     for (int jt = 0; jt < C::KT / 32; jt++) {
-      if (j0 + jt * 32 >= L) break;
+      const int kt0 = j0 + jt * 32;
+      if (kt0 >= L) break;
+      float bv[16];
+      if (has_bias) attn_load_bias16(bcol, L, kt0 + 4 * g, bv);
       f32x16 sacc, pacc;
 #pragma unroll
       for (int e = 0; e < 16; e++) { sacc[e] = 0.0f; pacc[e] = 0.0f; }
@@ -323,14 +359,23 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnArgs a) {
           MM::mma(pacc, MM::load(lds_v + off), dof[kk]);     // dP^T = V dO^T
         }
 #pragma unroll
-      for (int e = 0; e < 16; e++) {
-        int jj = jt * 32 + acc_row(g, e);
-        float v = sacc[e] * a.scale;
-        if (bcol) v += (j0 + jj < L) ? bcol[(long long)(j0 + jj) * L] : 0.0f;
-        float p = (lds_mask[jj] > 0.0f) ? __expf(v - lse) : 0.0f;
-        float ds = p * (pacc[e] - Di);
-        sacc[e] = ds;
-        if (dscol && j0 + jj < L) dscol[(long long)(j0 + jj) * L] = from_f<T>(ds);
+      for (int q4 = 0; q4 < 4; q4++) {
+        f32x4 ma = *reinterpret_cast<const f32x4*>(lds_madd + jt * 32 + 8 * q4 + 4 * g);
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+          int e = q4 * 4 + r;
+          float t = has_bias ? fmaf(sacc[e], c1, bv[e]) : sacc[e] * c1;
+          float p = exp2f(t + ma[r] - lse2);
+          sacc[e] = p * (pacc[e] - Di);
+        }
+      }
+      if (dscol) {
+        const bool full = kt0 + 32 <= L;
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          int key = kt0 + acc_row(g, e);
+          if (full || key < L) dscol[(long long)key * L] = from_f<T>(sacc[e]);
+        }
       }
       const T* krow = lds_kt + l32 * C::TS + jt * 32;
 #pragma unroll
@@ -340,9 +385,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnArgs a) {
   if (!qok) return;
   T* pdq = (T*)a.dqkvg + (long long)b * a.batch_stride + (long long)qi * a.seq_stride + h * d;
 #pragma unroll
-  for (int e = 0; e < 16; e++) {
-    int dd = acc_row(g, e);
-    if (dd < d) pdq[dd] = from_f<T>(dq[e] * a.scale);
+  for (int q4 = 0; q4 < 4; q4++) {
+    int dd = 8 * q4 + 4 * g;
+    if (dd < d) {
+      float v[4];
+#pragma unroll
+      for (int r = 0; r < 4; r++) v[r] = dq[q4 * 4 + r] * a.scale;
+      store4<T>(pdq + dd, v);
+    }
   }
 }
 
@@ -358,7 +408,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) T lds_qt[32 * C::TS];
   __shared__ __attribute__((aligned(16))) T lds_do[C::KT * C::RM];
   __shared__ __attribute__((aligned(16))) T lds_dot[32 * C::TS];
-  __shared__ float lds_lse[C::KT], lds_D[C::KT];
+  __shared__ __attribute__((aligned(16))) float lds_lse[C::KT];   // base-2 log-sum-exp, +inf beyond L
+  __shared__ __attribute__((aligned(16))) float lds_D[C::KT];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
   const int h = blockIdx.y, b = blockIdx.z;
@@ -381,7 +432,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
       vf[kk] = gl_frag<T>(vrow, kk, g, d);
     }
   const float mk = kok ? a.mask[(long long)b * a.mask_bs + (long long)kj * a.mask_ks] : 0.0f;
-  const float* bcol = (a.bias && kok) ? a.bias + (long long)h * L * L + kj : nullptr;
+  const float madd = (mk > 0.0f) ? 0.0f : -INFINITY;
+  const bool has_bias = a.bias != nullptr;
+  const float* bcol = has_bias ? a.bias + (long long)h * L * L + min(kj, L - 1) : nullptr;   // + query * L
+  const float c1 = a.scale * PE_LOG2E;
 
   f32x16 dk, dv;
 #pragma unroll
@@ -394,13 +448,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
     if (tid < C::KT) {
       int i = i0 + tid;
       long long sidx = ((long long)b * a.H + h) * L + i;
-      lds_lse[tid] = (i < L) ? a.lse[sidx] : 0.0f;
+      lds_lse[tid] = (i < L) ? a.lse[sidx] * PE_LOG2E : INFINITY;
       lds_D[tid] = (i < L) ? a.D[sidx] : 0.0f;
     }
     __syncthreads();
 #pragma unroll
     for (int it = 0; it < C::KT / 32; it++) {
       if (i0 + it * 32 >= L) break;
+      float bv[16];
+      if (has_bias) attn_load_bias16(bcol, L, i0 + it * 32 + 4 * g, bv);
       f32x16 sacc, pacc;
 #pragma unroll
       for (int e = 0; e < 16; e++) { sacc[e] = 0.0f; pacc[e] = 0.0f; }
@@ -413,14 +469,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
         }
       f32x16 pv;
 #pragma unroll
-      for (int e = 0; e < 16; e++) {
-        int ii = it * 32 + acc_row(g, e);
-        int i = i0 + ii;
-        float v = sacc[e] * a.scale;
-        if (bcol && i < L) v += bcol[(long long)i * L];
-        float p = (mk > 0.0f && i < L) ? __expf(v - lds_lse[ii]) : 0.0f;
-        pv[e] = p;
-        sacc[e] = p * (pacc[e] - lds_D[ii]);
+      for (int q4 = 0; q4 < 4; q4++) {
+        f32x4 ls = *reinterpret_cast<const f32x4*>(lds_lse + it * 32 + 8 * q4 + 4 * g);
+        f32x4 Dr = *reinterpret_cast<const f32x4*>(lds_D + it * 32 + 8 * q4 + 4 * g);
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+          int e = q4 * 4 + r;
+          float t = sacc[e] * c1;
+          if (has_bias) t = fmaf(bv[e], PE_LOG2E, t);
+          float p = exp2f(t + madd - ls[r]);
+          pv[e] = p;
+          sacc[e] = p * (pacc[e] - Dr[r]);
+        }
       }
       const T* dotrow = lds_dot + l32 * C::TS + it * 32;
       const T* qtrow = lds_qt + l32 * C::TS + it * 32;
@@ -435,21 +495,50 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
   T* pdk = (T*)a.dqkvg + (long long)b * a.batch_stride + (long long)kj * a.seq_stride + HD + h * d;
   T* pdv = pdk + HD;
 #pragma unroll
-  for (int e = 0; e < 16; e++) {
-    int dd = acc_row(g, e);
+  for (int q4 = 0; q4 < 4; q4++) {
+    int dd = 8 * q4 + 4 * g;
     if (dd < d) {
-      pdk[dd] = from_f<T>(dk[e] * a.scale);
-      pdv[dd] = from_f<T>(dv[e]);
+      float v1[4], v2[4];
+#pragma unroll
+      for (int r = 0; r < 4; r++) { v1[r] = dk[q4 * 4 + r] * a.scale; v2[r] = dv[q4 * 4 + r]; }
+      store4<T>(pdk + dd, v1);
+      store4<T>(pdv + dd, v2);
     }
   }
 }
 
 // dbiasT[h][j][i] = sum_b dS[b][h][j][i]  (elementwise over the trailing [H][L][L] block)
+// 256 threads = 64 groups of 4 consecutive outputs x 4 batch lanes; 8- / 16-byte loads
 template <typename T>
-__global__ void attn_dbias_reduce_kernel(const T* dS, float* dbias, int B, long long hll) {
-  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= hll) return;
-  float s = 0.0f;
-  for (int b = 0; b < B; b++) s += to_f(dS[(long long)b * hll + idx]);
-  dbias[idx] = s;
+__global__ __launch_bounds__(256) void attn_dbias_reduce_kernel(const T* dS, float* dbias, int B, long long hll) {
+  __shared__ float red[256][4];
+  const int x = threadIdx.x & 63, y = threadIdx.x >> 6;
+  const long long idx = ((long long)blockIdx.x * 64 + x) * 4;
+  float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  if (idx < hll) {
+    if ((hll & 3) == 0) {
+      for (int b = y; b < B; b += 16) {      // 4 independent loads in flight
+        float v[4][4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+          int bb = b + 4 * u;
+          if (bb < B) load4<T>(dS + (long long)bb * hll + idx, v[u]);
+          else { v[u][0] = v[u][1] = v[u][2] = v[u][3] = 0.0f; }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; e++) s[e] += (v[0][e] + v[1][e]) + (v[2][e] + v[3][e]);
+      }
+    } else {
+      for (int b = y; b < B; b += 4)
+        for (int e = 0; e < 4; e++)
+          if (idx + e < hll) s[e] += to_f(dS[(long long)b * hll + idx + e]);
+    }
+  }
+  red[threadIdx.x][0] = s[0]; red[threadIdx.x][1] = s[1]; red[threadIdx.x][2] = s[2]; red[threadIdx.x][3] = s[3];
+  __syncthreads();
+  if (y != 0 || idx >= hll) return;
+  for (int k = 1; k < 4; k++)
+    for (int e = 0; e < 4; e++) s[e] += red[k * 64 + x][e];
+  for (int e = 0; e < 4; e++)
+    if (idx + e < hll) dbias[idx + e] = s[e];
 }

@@ -364,7 +364,9 @@ template <typename T> struct Runner {
     for (int i = 0; i < nseg; i++) ra.seg[i] = segs[i];
     ra.dst = dparams;
     long long total = (long long)rows * cols;
-    PE_LAUNCH("reduce_partials", 0, 4.0 * total * (nsplit + 2), st, reduce_partials_kernel, dim3((unsigned)((total + 63) / 64)), dim3(1024), 0, ra);
+    ra.ylanes = nsplit >= 256 ? 64 : (nsplit >= 64 ? 16 : (nsplit >= 16 && total < 65536 ? 4 : 1));
+    const int X = 256 / ra.ylanes;
+    PE_LAUNCH("reduce_partials", 0, 4.0 * total * (nsplit + 2), st, reduce_partials_kernel, dim3((unsigned)((total + X - 1) / X)), dim3(256), 0, ra);
   }
   void k_ln_bwd(hipStream_t st, Arena& ar, const T* dy, const T* x, const float* stats, long long g_off, long long b_off,
                 const T* gin, T* gout, long long M, int Cc) {
@@ -409,7 +411,7 @@ template <typename T> struct Runner {
                long long K, int nseg, const ReduceSeg* segs, const char* what) {
     size_t mk = ar.mark();
     int tiles = ((rows + 127) / 128) * ((cols + 127) / 128);
-    int want = std::max(1, 768 / tiles);
+    int want = std::max(1, 512 / tiles);
     const int BK = GemmCfg<T>::BK;
     long long kc = (K + want - 1) / want;
     kc = (kc + BK - 1) / BK * BK;
@@ -432,7 +434,8 @@ template <typename T> struct Runner {
   }
 
   // ---- sub-operations: forward ---------------------------------------------
-  struct AttnGeom { long long B, L, batch_stride, seq_stride, mask_bs, mask_ks; const float* mask; int bias_transposed; };
+  struct AttnGeom { long long B, L, batch_stride, seq_stride, mask_bs, mask_ks; const float* mask; int bias_transposed;
+                    const char *l_fwd, *l_dq, *l_dkv; };
 
   void attn_sub_fwd(hipStream_t st, Arena& ar, const AttnP& p, const AttnW<T>& w, AttnCtx<T>& c, const T* x, T* xout,
                     long long M, int Cc, int H, int dh, const AttnGeom& g, const T* bias_src, long long bias_ln_g,
@@ -458,7 +461,7 @@ template <typename T> struct Runner {
       a.bias = c.bias; a.biasT = c.biasT; a.mask = g.mask; a.mask_bs = g.mask_bs; a.mask_ks = g.mask_ks;
       a.o = c.o; a.og = c.og; a.lse = c.lse; a.scale = 1.0f / sqrtf((float)dh);
       dim3 grid((unsigned)((g.L + 127) / 128), H, (unsigned)g.B);
-      PE_LAUNCH("attn_fwd", 4.0 * g.B * H * g.L * g.L * dh, (5.0 * M * HD + 1.0 * M * HD) * sizeof(T) + (c.bias ? 4.0 * H * g.L * g.L : 0.0), st, attn_fwd_kernel<T>, grid, dim3(256), 0, a);
+      PE_LAUNCH(g.l_fwd, 4.0 * g.B * H * g.L * g.L * dh, (5.0 * M * HD + 1.0 * M * HD) * sizeof(T) + (c.bias ? 4.0 * H * g.L * g.L : 0.0), st, attn_fwd_kernel<T>, grid, dim3(256), 0, a);
     }
     {
       EpiGeneric<T> e = epi_plain<T>(xout, Cc);
@@ -524,10 +527,14 @@ template <typename T> struct Runner {
     }
   }
 
-  AttnGeom geom_row() const { return AttnGeom{d.s, d.r, (long long)d.r * 4 * HDm, 4LL * HDm, d.r, 1, msa_mask, 0}; }
-  AttnGeom geom_col() const { return AttnGeom{d.r, d.s, 4LL * HDm, (long long)d.r * 4 * HDm, 1, d.r, msa_mask, 0}; }
-  AttnGeom geom_tas() const { return AttnGeom{d.r, d.r, (long long)d.r * 4 * HDz, 4LL * HDz, d.r, 1, pair_mask, 0}; }
-  AttnGeom geom_tae() const { return AttnGeom{d.r, d.r, 4LL * HDz, (long long)d.r * 4 * HDz, 1, d.r, pair_mask, 1}; }
+  AttnGeom geom_row() const { return AttnGeom{d.s, d.r, (long long)d.r * 4 * HDm, 4LL * HDm, d.r, 1, msa_mask, 0,
+                                               "attn_fwd row", "attn_dq row", "attn_dkv row"}; }
+  AttnGeom geom_col() const { return AttnGeom{d.r, d.s, 4LL * HDm, (long long)d.r * 4 * HDm, 1, d.r, msa_mask, 0,
+                                               "attn_fwd col", "attn_dq col", "attn_dkv col"}; }
+  AttnGeom geom_tas() const { return AttnGeom{d.r, d.r, (long long)d.r * 4 * HDz, 4LL * HDz, d.r, 1, pair_mask, 0,
+                                               "attn_fwd tas", "attn_dq tas", "attn_dkv tas"}; }
+  AttnGeom geom_tae() const { return AttnGeom{d.r, d.r, 4LL * HDz, (long long)d.r * 4 * HDz, 1, d.r, pair_mask, 1,
+                                               "attn_fwd tae", "attn_dq tae", "attn_dkv tae"}; }
 
   void fwd_msa(T* msa_out) {
     run_prep(true);
@@ -640,8 +647,8 @@ template <typename T> struct Runner {
       long long tot = gm.B * gm.L * H;
       PE_LAUNCH("attn_bwd_pre", 0, 5.0 * M * HD * sizeof(T), st, attn_bwd_pre_kernel<T>, dim3((unsigned)((tot * 8 + 255) / 256)), dim3(256), 0, a);
       dim3 grid((unsigned)((gm.L + 127) / 128), H, (unsigned)gm.B);
-      PE_LAUNCH("attn_bwd_dq", 6.0 * gm.B * H * gm.L * gm.L * dh, 5.0 * M * HD * sizeof(T) + (c.bias ? 1.0 * gm.B * H * gm.L * gm.L * sizeof(T) : 0.0), st, attn_bwd_dq_kernel<T>, grid, dim3(256), 0, a);
-      PE_LAUNCH("attn_bwd_dkv", 8.0 * gm.B * H * gm.L * gm.L * dh, 6.0 * M * HD * sizeof(T), st, attn_bwd_dkv_kernel<T>, grid, dim3(256), 0, a);
+      PE_LAUNCH(gm.l_dq, 6.0 * gm.B * H * gm.L * gm.L * dh, 5.0 * M * HD * sizeof(T) + (c.bias ? 1.0 * gm.B * H * gm.L * gm.L * sizeof(T) : 0.0), st, attn_bwd_dq_kernel<T>, grid, dim3(256), 0, a);
+      PE_LAUNCH(gm.l_dkv, 8.0 * gm.B * H * gm.L * gm.L * dh, 6.0 * M * HD * sizeof(T), st, attn_bwd_dkv_kernel<T>, grid, dim3(256), 0, a);
       if (c.bias) {
         long long hll = (long long)H * gm.L * gm.L;
         PE_LAUNCH("attn_dbias_reduce", 0, 1.0 * gm.B * hll * sizeof(T) + 4.0 * hll, st, attn_dbias_reduce_kernel<T>, dim3((unsigned)((hll + 255) / 256)), dim3(256), 0, dS, dbias,

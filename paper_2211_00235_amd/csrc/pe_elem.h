@@ -12,7 +12,7 @@
 #include "pe_common.h"
 
 constexpr int LN_NCH = 4;          // channels <= 64*4*LN_NCH = 1024
-constexpr int LN_MAX_WG = 512;     // workgroups (x4 waves) of the row-wise backward kernels
+constexpr int LN_MAX_WG = 2048;    // workgroups (x4 waves) of the row-wise backward kernels
 
 template <typename T> PE_DEV void load4(const T* p, float (&v)[4]);
 template <> PE_DEV void load4<float>(const float* p, float (&v)[4]) {
@@ -241,7 +241,8 @@ __global__ __launch_bounds__(256) void ln_cmajor_bwd_kernel(const T* dy, const T
 
 // ---------------------------------------------------------------------------
 // Pair-bias projection fused with its LayerNorm: bias[h][i][j] = (LN(z_ij) W)_h
-// (transposed: bias[h][j][i]).  C <= 256 (one 4-channel chunk per lane).
+// (transposed: bias[h][j][i]); biasT holds the other orientation multiplied by log2(e),
+// the form the base-2 softmax of the query-per-lane attention kernels reads.  C <= 256 (one 4-channel chunk per lane).
 // ---------------------------------------------------------------------------
 constexpr int BIAS_MAXH = 8;
 template <typename T>
@@ -280,7 +281,7 @@ __global__ __launch_bounds__(256) void ln_bias_fwd_kernel(const T* z, const floa
       if (h < H) {
         float t = y[0] * wv[0][h] + y[1] * wv[1][h] + y[2] * wv[2][h] + y[3] * wv[3][h];
         t = wave_sum(t);
-        if (lane == 0) { bias[(long long)h * M + o] = t; biasT[(long long)h * M + oT] = t; }
+        if (lane == 0) { bias[(long long)h * M + o] = t; biasT[(long long)h * M + oT] = t * 1.4426950408889634f; }
       }
     }
     if (lane == 0) { stats[row * 2] = mu; stats[row * 2 + 1] = rstd; }
@@ -371,21 +372,36 @@ struct ReduceArgs {
   int rows, cols;
   int nseg; ReduceSeg seg[5];
   float* dst;
+  int ylanes;
 };
-// 1024 threads = 64 outputs x 16 split lanes; fixed summation order (deterministic)
-__global__ __launch_bounds__(1024) void reduce_partials_kernel(ReduceArgs a) {
-  __shared__ float red[16][64];
-  const int x = threadIdx.x & 63, y = threadIdx.x >> 6;
+// 256 threads = X outputs x Y split lanes (Y = a.ylanes in {1, 4, 16, 64}, X = 256 / Y); fixed
+// summation order (deterministic)
+__global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceArgs a) {
+  __shared__ float red[256];
+  const int Y = a.ylanes, X = 256 / Y;
+  const int x = threadIdx.x % X, y = threadIdx.x / X;
   const long long total = (long long)a.rows * a.cols;
-  const long long idx = (long long)blockIdx.x * 64 + x;
+  const long long idx = (long long)blockIdx.x * X + x;
   float s = 0.0f;
-  if (idx < total)
-    for (int k = y; k < a.nsplit; k += 16) s += a.part[(long long)k * a.stride + idx];
-  red[y][x] = s;
-  __syncthreads();
-  if (y != 0 || idx >= total) return;
+  if (idx < total) {
+    // 8 independent loads in flight per thread; the sum order is still a fixed function of (nsplit, Y)
+    for (int k = y; k < a.nsplit; k += 8 * Y) {
+      float v[8];
 #pragma unroll
-  for (int k = 1; k < 16; k++) s += red[k][x];
+      for (int u = 0; u < 8; u++) {
+        int kk = k + u * Y;
+        v[u] = (kk < a.nsplit) ? a.part[(long long)kk * a.stride + idx] : 0.0f;
+      }
+      s += ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+    }
+  }
+  if (Y > 1) {
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (y != 0) return;
+    for (int k = 1; k < Y; k++) s += red[k * X + x];
+  }
+  if (idx >= total) return;
   int m = idx / a.cols, n = idx % a.cols;
   for (int q = 0; q < a.nseg; q++) {
     const ReduceSeg& g = a.seg[q];

@@ -45,6 +45,33 @@ struct GemmShape {
   int k_chunk;  // > 0: split-K; batch index selects the k range [b*k_chunk, min(K,(b+1)*k_chunk))
 };
 
+// 8 consecutive storage elements <-> 8 floats (one or two 16-byte accesses)
+template <typename T> PE_DEV void load8(const T* p, float (&v)[8]);
+template <> PE_DEV void load8<bf16>(const bf16* p, float (&v)[8]) {
+  bf16x8 t = *reinterpret_cast<const bf16x8*>(p);
+#pragma unroll
+  for (int e = 0; e < 8; e++) v[e] = (float)t[e];
+}
+template <> PE_DEV void load8<float>(const float* p, float (&v)[8]) {
+  f32x4 a = *reinterpret_cast<const f32x4*>(p), b = *reinterpret_cast<const f32x4*>(p + 4);
+#pragma unroll
+  for (int e = 0; e < 4; e++) { v[e] = a[e]; v[4 + e] = b[e]; }
+}
+template <typename T> PE_DEV void store8(T* p, const float (&v)[8]);
+template <> PE_DEV void store8<bf16>(bf16* p, const float (&v)[8]) {
+  bf16x8 t;
+#pragma unroll
+  for (int e = 0; e < 8; e++) t[e] = (bf16)v[e];
+  *reinterpret_cast<bf16x8*>(p) = t;
+}
+template <> PE_DEV void store8<float>(float* p, const float (&v)[8]) {
+  f32x4 a, b;
+#pragma unroll
+  for (int e = 0; e < 4; e++) { a[e] = v[e]; b[e] = v[4 + e]; }
+  *reinterpret_cast<f32x4*>(p) = a;
+  *reinterpret_cast<f32x4*>(p + 4) = b;
+}
+
 // ---------------------------------------------------------------------------
 // Epilogues
 // ---------------------------------------------------------------------------
@@ -98,6 +125,74 @@ template <typename T> struct EpiGeneric {
     if (accumulate) v += to_f(out[o]);
     out[o] = from_f<T>(v);
   }
+  // 8 consecutive columns n..n+7 of row m at once (host checked vec_ok)
+  PE_DEV void vec8(int b, int m, int n, float (&v)[8]) const {
+    Row r = row(b, m);
+    Col c = col(n);
+    if (bias_n && n >= bn_begin) {
+#pragma unroll
+      for (int e = 0; e < 8; e++) v[e] = fmaf(v[e], alpha, bias_n[n + e]);
+    } else if (alpha != 1.0f) {
+#pragma unroll
+      for (int e = 0; e < 8; e++) v[e] *= alpha;
+    }
+    if (bias_m) {
+      float bm = bias_m[m];
+#pragma unroll
+      for (int e = 0; e < 8; e++) v[e] += bm;
+    }
+    if (act == 1) {
+#pragma unroll
+      for (int e = 0; e < 8; e++) v[e] = fmaxf(v[e], 0.0f);
+    } else if (act == 2) {
+#pragma unroll
+      for (int e = 0; e < 8; e++) v[e] = sigmoidf_(v[e]);
+    }
+    float t[8];
+    if (relu_mask) {
+      load8<T>(relu_mask + (long long)m * ld_rm + n, t);
+#pragma unroll
+      for (int e = 0; e < 8; e++) v[e] = (t[e] > 0.0f) ? v[e] : 0.0f;
+    }
+    if (aux) store8<T>(aux + (long long)m * ld_aux + n, v);
+    if (mul) {
+      load8<T>(mul + (long long)m * ld_mul + n, t);
+#pragma unroll
+      for (int e = 0; e < 8; e++) v[e] *= t[e];
+    }
+    float sc = rowscale ? rowscale[m] : 1.0f;
+    if (scale2d) sc *= scale2d[r.s2 + c.s2];
+    if (rowscale || scale2d) {
+#pragma unroll
+      for (int e = 0; e < 8; e++) v[e] *= sc;
+    }
+    if (res) {
+      load8<T>(res + (long long)m * ld_res + n, t);
+#pragma unroll
+      for (int e = 0; e < 8; e++) v[e] += t[e];
+    }
+    T* po = out + r.o + c.o;
+    if (accumulate) {
+      load8<T>(po, t);
+#pragma unroll
+      for (int e = 0; e < 8; e++) v[e] += t[e];
+    }
+    store8<T>(po, v);
+  }
+  bool vec_ok(int N) const {
+    auto a8 = [](long long x) { return x % 8 == 0; };
+    auto p16 = [](const void* p) { return ((uintptr_t)p) % 16 == 0; };
+    if (N % 8) return false;
+    if (on_stride != 1 || !(on_in >= (1 << 30) || on_in % 8 == 0) || !a8(on_outer)) return false;
+    if (!a8(om_stride) || !a8(om_outer) || !a8(out_batch) || !p16(out)) return false;
+    if (bias_n && bn_begin % 8) return false;
+    if (relu_mask && (!a8(ld_rm) || !p16(relu_mask))) return false;
+    if (aux && (!a8(ld_aux) || !p16(aux))) return false;
+    if (mul && (!a8(ld_mul) || !p16(mul))) return false;
+    if (res && (!a8(ld_res) || !p16(res))) return false;
+    if (scale2d && s2_ndiv % 8) return false;
+    return true;
+  }
 };
 
 template <typename T> static inline EpiGeneric<T> epi_plain(void* out, long long ldc) {
@@ -118,6 +213,10 @@ struct EpiPartial {
   PE_DEV Row row(int b, int m) const { return Row{(long long)b * mn + (long long)m * ldn}; }
   PE_DEV Col col(int n) const { return Col{(long long)n}; }
   PE_DEV void operator()(int, int, const Row& r, const Col& c, float v) const { out[r.o + c.o] = v; }
+  PE_DEV void vec8(int b, int m, int n, float (&v)[8]) const {
+    store8<float>(out + (long long)b * mn + (long long)m * ldn + n, v);
+  }
+  bool vec_ok(int N) const { return N % 8 == 0 && ldn % 8 == 0 && mn % 8 == 0 && ((uintptr_t)out) % 16 == 0; }
 };
 
 // ---------------------------------------------------------------------------
@@ -251,13 +350,14 @@ PE_DEV void gemm_store_tile(const typename Vec16<T>::type (&regs)[4], T* lds, in
   }
 }
 
-template <typename T, bool A_KC, bool B_KC, bool AL, class Epi>
+template <typename T, bool A_KC, bool B_KC, bool AL, bool VE, class Epi>
 __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmShape sh, Epi epi) {
   typedef GemmCfg<T> C;
   typedef Mma<T> MM;
   typedef typename Vec16<T>::type V;
-  __shared__ __attribute__((aligned(16))) T lds_a[C::BM * C::LDSS];
-  __shared__ __attribute__((aligned(16))) T lds_b[C::BN * C::LDSS];
+  __shared__ __attribute__((aligned(16))) T lds_all[(C::BM + C::BN) * C::LDSS];   // 36 KB
+  T* lds_a = lds_all;
+  T* lds_b = lds_all + C::BM * C::LDSS;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
@@ -317,6 +417,42 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
     }
   }
 
+  if (VE) {
+    // Coalesced epilogue: the fp32 tile goes through LDS 64 rows at a time, then every thread
+    // handles 8 consecutive columns of one row (16-byte loads / stores of every epilogue operand).
+    constexpr int SS = C::BN + 4;
+    static_assert(64 * SS * sizeof(float) <= (C::BM + C::BN) * C::LDSS * sizeof(T), "stage tile must fit");
+    float* stage = reinterpret_cast<float*>(lds_all);
+#pragma unroll
+    for (int pass = 0; pass < 2; pass++) {
+      __syncthreads();
+      if (wm == pass) {
+#pragma unroll
+        for (int i = 0; i < 2; i++)
+#pragma unroll
+          for (int j = 0; j < 2; j++)
+#pragma unroll
+            for (int a = 0; a < 16; a++)
+              stage[(i * 32 + acc_row(g, a)) * SS + wn * 64 + j * 32 + l32] = acc[i][j][a];
+      }
+      __syncthreads();
+#pragma unroll
+      for (int it = 0; it < 4; it++) {
+        int v = tid + it * 256;
+        int row = v >> 4, c8 = (v & 15) * 8;
+        int m = m0 + pass * 64 + row, n = n0 + c8;
+        if (m < sh.M && n < sh.N) {
+          float vals[8];
+          f32x4 lo = *reinterpret_cast<const f32x4*>(stage + row * SS + c8);
+          f32x4 hi = *reinterpret_cast<const f32x4*>(stage + row * SS + c8 + 4);
+#pragma unroll
+          for (int e = 0; e < 4; e++) { vals[e] = lo[e]; vals[4 + e] = hi[e]; }
+          epi.vec8(b, m, n, vals);
+        }
+      }
+    }
+    return;
+  }
   typename Epi::Col cols[2];
   int ncol[2];
 #pragma unroll
@@ -362,18 +498,18 @@ template <typename T> static inline bool gemm_operand_ok(const Operand& o, bool 
   return true;
 }
 
-template <typename T, bool AL, class Epi>
+template <typename T, bool AL, bool VE, class Epi>
 static inline void launch_gemm_al(hipStream_t st, dim3 grid, const Operand& A, bool a_kc, const Operand& B, bool b_kc,
                                   const GemmShape& sh, const Epi& epi) {
   dim3 block(256);
-  if (a_kc && b_kc) hipLaunchKernelGGL((gemm_kernel<T, true, true, AL, Epi>), grid, block, 0, st, A, B, sh, epi);
-  else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_kernel<T, true, false, AL, Epi>), grid, block, 0, st, A, B, sh, epi);
-  else if (!a_kc && b_kc) hipLaunchKernelGGL((gemm_kernel<T, false, true, AL, Epi>), grid, block, 0, st, A, B, sh, epi);
-  else hipLaunchKernelGGL((gemm_kernel<T, false, false, AL, Epi>), grid, block, 0, st, A, B, sh, epi);
+  if (a_kc && b_kc) hipLaunchKernelGGL((gemm_kernel<T, true, true, AL, VE, Epi>), grid, block, 0, st, A, B, sh, epi);
+  else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_kernel<T, true, false, AL, VE, Epi>), grid, block, 0, st, A, B, sh, epi);
+  else if (!a_kc && b_kc) hipLaunchKernelGGL((gemm_kernel<T, false, true, AL, VE, Epi>), grid, block, 0, st, A, B, sh, epi);
+  else hipLaunchKernelGGL((gemm_kernel<T, false, false, AL, VE, Epi>), grid, block, 0, st, A, B, sh, epi);
 }
 
 // Operands that break the 16-byte vector rules (odd leading dimensions) take the
-// element-wise loader: same tiles, same arithmetic, slower loads.
+// element-wise loader and the per-element epilogue: same tiles, same arithmetic, slower.
 template <typename T, class Epi>
 static inline int launch_gemm(hipStream_t st, const Operand& A, bool a_kc, const Operand& B, bool b_kc,
                               const GemmShape& sh, const Epi& epi, bool* used_vec = nullptr) {
@@ -382,9 +518,11 @@ static inline int launch_gemm(hipStream_t st, const Operand& A, bool a_kc, const
   if (b_kc ? B.k_stride != 1 : B.x_stride != 1) return -1;
   if (sh.k_chunk > 0 && sh.k_chunk % GemmCfg<T>::BK) return -1;
   bool al = gemm_operand_ok<T>(A, a_kc, sh.M, sh) && gemm_operand_ok<T>(B, b_kc, sh.N, sh);
-  if (used_vec) *used_vec = al;
+  bool ve = al && epi.vec_ok(sh.N);
+  if (used_vec) *used_vec = ve;
   dim3 grid((sh.N + 127) / 128, (sh.M + 127) / 128, sh.batch);
-  if (al) launch_gemm_al<T, true, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);
-  else launch_gemm_al<T, false, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);
+  if (ve) launch_gemm_al<T, true, true, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);
+  else if (al) launch_gemm_al<T, true, false, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);
+  else launch_gemm_al<T, false, false, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);
   return hipGetLastError() == hipSuccess ? 0 : -2;
 }
