@@ -411,7 +411,7 @@ template <typename T> struct Runner {
                long long K, int nseg, const ReduceSeg* segs, const char* what) {
     size_t mk = ar.mark();
     int tiles = ((rows + 127) / 128) * ((cols + 127) / 128);
-    int want = std::max(1, 512 / tiles);
+    int want = std::max(1, 256 / tiles);
     const int BK = GemmCfg<T>::BK;
     long long kc = (K + want - 1) / want;
     kc = (kc + BK - 1) / BK * BK;

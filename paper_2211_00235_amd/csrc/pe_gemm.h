@@ -227,6 +227,10 @@ template <typename T> struct GemmCfg {
   static constexpr int BM = 128, BN = 128;
   static constexpr int BK = 8 * VEC;        // 64 (bf16) or 32 (fp32): 128-byte rows
   static constexpr int LDSS = BK + VEC;     // +16 bytes: conflict-free 16-byte fragment reads
+  // LDS element offset of (row, 16-byte chunk c of the row, element w inside the chunk).  The chunk
+  // index is XOR-swizzled with the row's 8-row group so that the transposing store of x-contiguous
+  // operands (8 rows apart per lane) does not hit one bank pair 16 times.
+  static PE_DEV int off(int row, int c, int w) { return row * LDSS + ((c ^ ((row >> 3) & 7)) * VEC) + w; }
 };
 
 // element-wise (unaligned) variant of one 16-byte vector load: elements e = 0..VEC-1 along k (KC) or x
@@ -335,7 +339,7 @@ PE_DEV void gemm_store_tile(const typename Vec16<T>::type (&regs)[4], T* lds, in
 #pragma unroll
     for (int i = 0; i < 4; i++) {
       int row = (tid >> 3) + 32 * i;
-      *reinterpret_cast<V*>(lds + row * LDSS + kv * VEC) = regs[i];
+      *reinterpret_cast<V*>(lds + GemmCfg<T>::off(row, kv, 0)) = regs[i];
     }
   } else {
     constexpr int XB = 128 / VEC;
@@ -345,7 +349,7 @@ PE_DEV void gemm_store_tile(const typename Vec16<T>::type (&regs)[4], T* lds, in
     for (int e = 0; e < VEC; e++) {
       V4 w;
       w[0] = regs[0][e]; w[1] = regs[1][e]; w[2] = regs[2][e]; w[3] = regs[3][e];
-      *reinterpret_cast<V4*>(lds + (xb * VEC + e) * LDSS + kb * 4) = w;
+      *reinterpret_cast<V4*>(lds + GemmCfg<T>::off(xb * VEC + e, (kb * 4) / VEC, (kb * 4) % VEC)) = w;
     }
   }
 }
@@ -407,8 +411,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
       typename MM::frag af[2], bf[2];
 #pragma unroll
       for (int t = 0; t < 2; t++) {
-        af[t] = MM::load(lds_a + (wm * 64 + t * 32 + l32) * C::LDSS + kk * MM::KSTEP + g * MM::KP);
-        bf[t] = MM::load(lds_b + (wn * 64 + t * 32 + l32) * C::LDSS + kk * MM::KSTEP + g * MM::KP);
+        const int eo = kk * MM::KSTEP + g * MM::KP;
+        af[t] = MM::load(lds_a + C::off(wm * 64 + t * 32 + l32, eo / C::VEC, eo % C::VEC));
+        bf[t] = MM::load(lds_b + C::off(wn * 64 + t * 32 + l32, eo / C::VEC, eo % C::VEC));
       }
 #pragma unroll
       for (int i = 0; i < 2; i++)
