@@ -356,6 +356,10 @@ template <typename T> struct Runner {
     int grid = (int)std::min<long long>((M + 3) / 4, 4096);
     PE_LAUNCH("ln_fwd", 0, 2.0 * M * Cc * sizeof(T), st, ln_fwd_kernel<T>, dim3(grid), dim3(256), 0, x, P(g_off), P(b_off), y, stats, M, Cc, d.ln_eps);
   }
+  // Reductions of fp32 partials into d_params are queued and launched several per kernel
+  // (flush_reduces).  Partial buffers stay allocated until the enclosing sub-operation
+  // releases its arena frame, which every sub-operation does after flushing.
+  std::vector<ReduceArgs> pending;
   void reduce_to(hipStream_t st, const float* part, int nsplit, long long stride, int rows, int cols, int nseg,
                  const ReduceSeg* segs) {
     if (dry || err) return;
@@ -365,12 +369,31 @@ template <typename T> struct Runner {
     ra.dst = dparams;
     long long total = (long long)rows * cols;
     ra.ylanes = nsplit >= 256 ? 64 : (nsplit >= 64 ? 16 : (nsplit >= 16 && total < 65536 ? 4 : 1));
-    const int X = 256 / ra.ylanes;
-    PE_LAUNCH("reduce_partials", 0, 4.0 * total * (nsplit + 2), st, reduce_partials_kernel, dim3((unsigned)((total + X - 1) / X)), dim3(256), 0, ra);
+    pending.push_back(ra);
+    (void)st;
+  }
+  void flush_reduces(hipStream_t st) {
+    if (dry || err) { pending.clear(); return; }
+    for (size_t i = 0; i < pending.size(); i += REDUCE_BATCH) {
+      ReduceBatch rb;
+      rb.n = (int)std::min((size_t)REDUCE_BATCH, pending.size() - i);
+      long long maxblocks = 1;
+      double bytes = 0;
+      for (int k = 0; k < REDUCE_BATCH; k++) {
+        rb.a[k] = pending[i + (k < rb.n ? k : 0)];
+        if (k < rb.n) {
+          long long total = (long long)rb.a[k].rows * rb.a[k].cols;
+          int X = 256 / rb.a[k].ylanes;
+          maxblocks = std::max(maxblocks, (total + X - 1) / X);
+          bytes += 4.0 * total * (rb.a[k].nsplit + 2);
+        }
+      }
+      PE_LAUNCH("reduce_partials", 0, bytes, st, reduce_partials_kernel, dim3((unsigned)maxblocks, rb.n), dim3(256), 0, rb);
+    }
+    pending.clear();
   }
   void k_ln_bwd(hipStream_t st, Arena& ar, const T* dy, const T* x, const float* stats, long long g_off, long long b_off,
                 const T* gin, T* gout, long long M, int Cc) {
-    size_t mk = ar.mark();
     int grid = (int)std::min<long long>((M + 3) / 4, LN_MAX_WG);
     float* part = (float*)ar.alloc((size_t)grid * 2 * Cc * sizeof(float));
     if (!dry && !err) {
@@ -378,10 +401,8 @@ template <typename T> struct Runner {
       ReduceSeg sg[2] = {{0, Cc, g_off, 0}, {Cc, Cc, b_off, 0}};
       reduce_to(st, part, grid, 2LL * Cc, 1, 2 * Cc, 2, sg);
     }
-    ar.release(mk);
   }
   void k_colsum(hipStream_t st, Arena& ar, const T* y, long long M, int N, long long ld, long long dst_off) {
-    size_t mk = ar.mark();
     int nwg = (int)std::min<long long>(1024, (M + 31) / 32);
     long long rpw = (M + nwg - 1) / nwg;
     nwg = (int)((M + rpw - 1) / rpw);
@@ -391,10 +412,35 @@ template <typename T> struct Runner {
       ReduceSeg sg[1] = {{0, N, dst_off, 0}};
       reduce_to(st, part, nwg, N, 1, N, 1, sg);
     }
-    ar.release(mk);
   }
   void gemm(hipStream_t st, const Operand& A, bool akc, const Operand& B, bool bkc, int M, int N, int K, int batch,
-            const EpiGeneric<T>& e, const char* what) {
+            const EpiGeneric<T>& e, const char* what, Arena* split_arena = nullptr) {
+    // A grid too small to fill the chip with a long contraction: split K, fp32 partials,
+    // fixed-order finish kernel that applies the epilogue.
+    const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
+    const int BK = GemmCfg<T>::BK;
+    if (split_arena && batch == 1 && tiles <= 96 && K >= 16 * BK && N % 8 == 0) {
+      int want = std::max(2, 256 / tiles);
+      long long kc = ((K + want - 1) / want + BK - 1) / BK * BK;
+      int nsplit = (int)((K + kc - 1) / kc);
+      float* part = (float*)split_arena->alloc((size_t)nsplit * M * N * sizeof(float));
+      if (dry || err) return;
+      if (!e.vec_ok(N)) { err = PE_ERR_DIMS; if (h) h->last_error = std::string("split-K epilogue alignment: ") + what; return; }
+      GemmShape sh{M, N, K, nsplit, (int)kc};
+      EpiPartial ep{part, (long long)M * N, N};
+      prof_begin(st);
+      bool al = false;
+      int rc = launch_gemm<T, EpiPartial>(st, A, akc, B, bkc, sh, ep, &al);
+      char kn[64];
+      snprintf(kn, sizeof(kn), "gemm_kernel<%s,%s,%s,EpiPartial>", akc ? "kc" : "xc", bkc ? "kc" : "xc", al ? "vec" : "elem");
+      prof_end(st, what, kn, 2.0 * M * N * K, ((double)M * K + (double)N * K) * sizeof(T));
+      if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = std::string("gemm operand alignment: ") + what; return; }
+      check(what);
+      long long nv = (long long)M * (N / 8);
+      PE_LAUNCH("gemm_finish", 0, 4.0 * nsplit * M * N, st, gemm_finish_kernel<T>, dim3((unsigned)((nv + 255) / 256)), dim3(256), 0,
+                part, nsplit, M, N, e);
+      return;
+    }
     if (dry || err) return;
     GemmShape sh{M, N, K, batch, 0};
     prof_begin(st);
@@ -409,7 +455,6 @@ template <typename T> struct Runner {
   // dW[rows][cols] += sum_k X(row,k) * Y(col,k), K huge: split-K partials + ordered reduce into dparams
   void gemm_dw(hipStream_t st, Arena& ar, const Operand& X, bool xkc, const Operand& Y, bool ykc, int rows, int cols,
                long long K, int nseg, const ReduceSeg* segs, const char* what) {
-    size_t mk = ar.mark();
     int tiles = ((rows + 127) / 128) * ((cols + 127) / 128);
     int want = std::max(1, 256 / tiles);
     const int BK = GemmCfg<T>::BK;
@@ -430,7 +475,6 @@ template <typename T> struct Runner {
       else check(what);
       reduce_to(st, part, nsplit, (long long)rows * cols, rows, cols, nseg, segs);
     }
-    ar.release(mk);
   }
 
   // ---- sub-operations: forward ---------------------------------------------
@@ -611,6 +655,7 @@ template <typename T> struct Runner {
     { EpiGeneric<T> e = epi_plain<T>(dxh, Cc);
       gemm(st, op_plain(dh, nC), true, op_plain(w.wn_1, nC), true, (int)M, Cc, nC, 1, e, "trans dxhat"); }
     k_ln_bwd(st, ar, dxh, x, c.stats, p.ln_g, p.ln_b, g, g, M, Cc);
+    flush_reduces(st);
     ar.release(mk);
   }
 
@@ -661,6 +706,7 @@ template <typename T> struct Runner {
     { EpiGeneric<T> e = epi_plain<T>(dxh, Cc);
       gemm(st, op_plain(dqkvg, 4 * HD), true, op_plain(w.wn_qkvg, 4 * HD), true, (int)M, Cc, 4 * HD, 1, e, "attn dxhat"); }
     k_ln_bwd(st, ar, dxh, x, c.stats, p.ln_g, p.ln_b, g, g, M, Cc);
+    flush_reduces(st);   // the bias path below adds to the same LayerNorm parameters: separate launch
     if (c.bias) {
       const int cz = d.c_z;
       int grid = (int)std::min<long long>((Mz + 3) / 4, LN_MAX_WG);
@@ -672,6 +718,7 @@ template <typename T> struct Runner {
         ReduceSeg sg[3] = {{0, cz, bias_ln_g, 0}, {cz, cz, bias_ln_b, 0}, {2 * cz, cz * H, p.w_bias, 0}};
         reduce_to(st, part, grid, plen, 1, plen, 3, sg);
       }
+      flush_reduces(st);
     }
     ar.release(mk);
   }
@@ -698,7 +745,6 @@ template <typename T> struct Runner {
     { EpiGeneric<T> e = epi_plain<T>(dxh_o, ct);
       gemm(st, op_plain(du, cz), true, op_plain(w.wn_o, cz), true, (int)Mz, ct, cz, 1, e, "trimul dxhat_o"); }
     {  // LayerNorm (channel-major input) backward
-      size_t mk2 = ar.mark();
       int grid = (int)((Mz + 63) / 64);
       float* part = (float*)ar.alloc((size_t)grid * 2 * ct * sizeof(float));
       if (!dry && !err) {
@@ -708,7 +754,6 @@ template <typename T> struct Runner {
         ReduceSeg sg[2] = {{0, ct, p.ln_out_g, 0}, {ct, ct, p.ln_out_b, 0}};
         reduce_to(st, part, grid, 2LL * ct, 1, 2 * ct, 2, sg);
       }
-      ar.release(mk2);
     }
     {  // contraction backward, per channel
       EpiGeneric<T> ea = epi_plain<T>(da_t, r); ea.out_batch = Mz;
@@ -729,7 +774,6 @@ template <typename T> struct Runner {
                          da_t, db_t, dproj_t, ct, Mz);
     }
     {  // bias gradients: row sums of the channel-major projection gradients (two stages)
-      size_t mk2 = ar.mark();
       const int nch = 16;
       float* part = (float*)ar.alloc((size_t)nch * 4 * ct * sizeof(float));
       if (!dry && !err) {
@@ -738,7 +782,6 @@ template <typename T> struct Runner {
         ReduceSeg sg[4] = {{0, ct, p.b_ap, 0}, {ct, ct, p.b_ag, 0}, {2 * ct, ct, p.b_bp, 0}, {3 * ct, ct, p.b_bg, 0}};
         reduce_to(st, part, nch, 4LL * ct, 1, 4 * ct, 4, sg);
       }
-      ar.release(mk2);
     }
     k_colsum(st, ar, dgraw, Mz, cz, cz, p.b_g);
     { ReduceSeg sg[4] = {{0, ct, p.w_ap, ct}, {ct, ct, p.w_ag, ct}, {2 * ct, ct, p.w_bp, ct}, {3 * ct, ct, p.w_bg, ct}};
@@ -751,6 +794,7 @@ template <typename T> struct Runner {
       e.accumulate = 1;
       gemm(st, op_plain(dgraw, cz), true, op_plain(w.wn_g, cz), true, (int)Mz, cz, cz, 1, e, "trimul dzhat g"); }
     k_ln_bwd(st, ar, dzh, z, c.stats, p.ln_in_g, p.ln_in_b, g, g, Mz, cz);
+    flush_reduces(st);
     ar.release(mk);
   }
 
@@ -783,10 +827,10 @@ template <typename T> struct Runner {
       {
         EpiGeneric<T> e = epi_plain<T>(dab, Wd);
         e.scale2d = msa_mask; e.s2_mdiv = 1; e.s2_ndiv = co; e.s2_ld = r;
-        gemm(sm, op_plain(C.opm.b, Wd), true, op_plain(dOs, Wd), true, d.s, (int)Wd, (int)Wd, 1, e, "opm da");
+        gemm(sm, op_plain(C.opm.b, Wd), true, op_plain(dOs, Wd), true, d.s, (int)Wd, (int)Wd, 1, e, "opm da", &am);
         EpiGeneric<T> e2 = e;
         e2.out = dab + Mm * co;
-        gemm(sm, op_plain(C.opm.a, Wd), true, op_trans(dOs, Wd), false, d.s, (int)Wd, (int)Wd, 1, e2, "opm db");
+        gemm(sm, op_plain(C.opm.a, Wd), true, op_trans(dOs, Wd), false, d.s, (int)Wd, (int)Wd, 1, e2, "opm db", &am);
       }
       k_colsum(sm, am, dab, Mm, co, co, PL.opm.b_a);
       k_colsum(sm, am, dab + Mm * co, Mm, co, co, PL.opm.b_b);
@@ -807,6 +851,7 @@ template <typename T> struct Runner {
         gemm(sm, A, true, op_plain(W.opm.wn_ab, 2 * co), true, (int)Mm, cm, 2 * co, 1, e, "opm dmhat");
       }
       k_ln_bwd(sm, am, dmh, C.m3, C.opm.stats, PL.opm.ln_g, PL.opm.ln_b, d_msa_out, gm, Mm, cm);
+      flush_reduces(sm);
       am.release(mk);
     }
     trans_sub_bwd(sm, am, PL.mtrans, W.mt, C.mt, C.m2, gm, Mm, cm);

@@ -375,12 +375,17 @@ struct ReduceArgs {
   int ylanes;
 };
 // 256 threads = X outputs x Y split lanes (Y = a.ylanes in {1, 4, 16, 64}, X = 256 / Y); fixed
-// summation order (deterministic)
-__global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceArgs a) {
+// summation order (deterministic).  Up to REDUCE_BATCH independent reductions per launch
+// (blockIdx.y selects one); their destinations must not overlap.
+constexpr int REDUCE_BATCH = 8;
+struct ReduceBatch { ReduceArgs a[REDUCE_BATCH]; int n; };
+__global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceBatch rb) {
   __shared__ float red[256];
+  const ReduceArgs& a = rb.a[blockIdx.y];
   const int Y = a.ylanes, X = 256 / Y;
-  const int x = threadIdx.x % X, y = threadIdx.x / X;
   const long long total = (long long)a.rows * a.cols;
+  if ((long long)blockIdx.x * X >= total) return;
+  const int x = threadIdx.x % X, y = threadIdx.x / X;
   const long long idx = (long long)blockIdx.x * X + x;
   float s = 0.0f;
   if (idx < total) {

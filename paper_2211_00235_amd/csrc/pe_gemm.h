@@ -479,6 +479,25 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
     }
 }
 
+// Second stage of a split-K GEMM with a full epilogue: sums the fp32 partials part[s][m][n]
+// in a fixed order and applies the epilogue to 8 consecutive columns per thread.
+template <typename T>
+__global__ __launch_bounds__(256) void gemm_finish_kernel(const float* part, int nsplit, int M, int N, EpiGeneric<T> epi) {
+  const long long v = (long long)blockIdx.x * 256 + threadIdx.x;
+  const int n8 = N / 8;
+  if (v >= (long long)M * n8) return;
+  const int m = v / n8, n = (v % n8) * 8;
+  const long long mn = (long long)M * N;
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int s = 0; s < nsplit; s++) {
+    float t[8];
+    load8<float>(part + s * mn + (long long)m * N + n, t);
+#pragma unroll
+    for (int e = 0; e < 8; e++) acc[e] += t[e];
+  }
+  epi.vec8(0, m, n, acc);
+}
+
 // ---------------------------------------------------------------------------
 // Host launcher.  Returns 0 or a negative code when an operand violates the
 // vector-alignment rules (nothing is launched then).
