@@ -12,6 +12,7 @@
 
 #include "pe_attn.h"
 #include "pe_elem.h"
+#include "pe_gcol.h"
 #include "pe_gemm.h"
 #include "pe_layout.h"
 
@@ -66,12 +67,13 @@ template <typename T> struct AttnCtx { T* xhat; float* stats; T* qkvg; float* bi
 template <typename T> struct TransCtx { T* xhat; float* stats; T* h; };
 template <typename T> struct TriMulCtx { T* zhat; float* stats; T* proj_t; T* a_t; T* b_t; T* g; T* x_t; float* stats_out; T* xhat; T* u; };
 template <typename T> struct OpmCtx { T* mhat; float* stats; T* a; T* b; float* inv_norm; T* O; };
-template <typename T> struct GlobCtx { T* qbar; T* kv; T* gate; float* p; T* o; T* og; };
+template <typename T> struct GlobCtx { T* xhat; float* stats; T* proj; float* qbar; float* den; float* p; float* o; T* og; };
 template <typename T> struct Ctx {
   AttnCtx<T> row, col, tas, tae;
   TransCtx<T> mt, pt;
   TriMulCtx<T> tmo, tmi;
   OpmCtx<T> opm;
+  GlobCtx<T> gcol;
   T *m1, *m2, *m3, *z1, *z2, *z3, *z4, *z5;
 };
 
@@ -79,11 +81,13 @@ template <typename T> struct AttnW { T *wt_qkvg, *wn_qkvg, *wt_o, *wn_o; };
 template <typename T> struct TransW { T *wt_1, *wn_1, *wt_2, *wn_2; };
 template <typename T> struct OpmW { T *wt_ab, *wn_ab, *wt_o, *wn_o; };
 template <typename T> struct TriMulW { T *wt_p, *wn_p, *wt_g, *wn_g, *wt_o, *wn_o; float* bias_p; };
+template <typename T> struct GlobW { T *wt_proj, *wn_proj, *wt_o, *wn_o; };
 template <typename T> struct PrepW {
   AttnW<T> row, col, tas, tae;
   TransW<T> mt, pt;
   OpmW<T> opm;
   TriMulW<T> tmo, tmi;
+  GlobW<T> gcol;
 };
 
 template <typename T> constexpr int dtype_tag() { return sizeof(T) == 2 ? PE_BF16 : PE_F32; }
@@ -132,7 +136,20 @@ template <typename T> static size_t carve_ctx(char* base, const pe_dims& d, Ctx<
   const int HDm = d.h_msa * d.d_msa, HDz = d.h_pair * d.d_pair;
   carve_attn_ctx<T>(cv, C.row, "row", Mm, d.c_m, HDm, d.h_msa, s, r, true, Mz);
   C.m1 = cv.take<T>("m1", Mm * d.c_m, dtype_tag<T>());
-  carve_attn_ctx<T>(cv, C.col, "col", Mm, d.c_m, HDm, d.h_msa, r, s, false, Mz);
+  if (d.col_global) {
+    const long long Wg = 2LL * HDm + 2 * d.d_msa;
+    C.gcol.xhat = cv.take<T>("col.xhat", Mm * d.c_m, dtype_tag<T>());
+    C.gcol.stats = cv.take<float>("col.stats", Mm * 2, PE_F32);
+    C.gcol.proj = cv.take<T>("col.proj", Mm * Wg, dtype_tag<T>());
+    C.gcol.qbar = cv.take<float>("col.qbar", r * HDm, PE_F32);
+    C.gcol.den = cv.take<float>("col.den", r, PE_F32);
+    C.gcol.p = cv.take<float>("col.p", r * d.h_msa * s, PE_F32);
+    C.gcol.o = cv.take<float>("col.o", r * HDm, PE_F32);
+    C.gcol.og = cv.take<T>("col.og", Mm * HDm, dtype_tag<T>());
+    memset(&C.col, 0, sizeof(C.col));
+  } else {
+    carve_attn_ctx<T>(cv, C.col, "col", Mm, d.c_m, HDm, d.h_msa, r, s, false, Mz);
+  }
   C.m2 = cv.take<T>("m2", Mm * d.c_m, dtype_tag<T>());
   carve_trans_ctx<T>(cv, C.mt, "mtrans", Mm, d.c_m, d.n_trans);
   C.m3 = cv.take<T>("m3", Mm * d.c_m, dtype_tag<T>());
@@ -306,6 +323,19 @@ template <typename T> struct Runner {
     PrepCarver<T> pm{prep_tbase_m, prep_fbase_m, 0, 0, &prep_msa};
     prep_attn<T>(pm, W.row, PL.row, d.c_m, HDm);
     if (!d.col_global) prep_attn<T>(pm, W.col, PL.col, d.c_m, HDm);
+    else {
+      const int C_ = d.c_m, dd = d.d_msa, Wg = 2 * HDm + 2 * dd;
+      W.gcol.wt_proj = pm.region((long long)Wg * C_); W.gcol.wn_proj = pm.region((long long)Wg * C_);
+      W.gcol.wt_o = pm.region((long long)HDm * C_); W.gcol.wn_o = pm.region((long long)HDm * C_);
+      const long long src[4] = {PL.col.w_q, PL.col.w_k, PL.col.w_v, PL.col.w_g};
+      const int wd[4] = {HDm, dd, dd, HDm}, c0[4] = {0, HDm, HDm + dd, HDm + 2 * dd};
+      for (int k = 0; k < 4; k++) {
+        pm.add(W.gcol.wt_proj + (long long)c0[k] * C_, src[k], C_, wd[k], 1, C_);   // [Wg][C]
+        pm.add(W.gcol.wn_proj + c0[k], src[k], C_, wd[k], Wg, 1);                    // [C][Wg]
+      }
+      pm.add(W.gcol.wt_o, PL.col.w_o, HDm, C_, 1, HDm);
+      pm.add(W.gcol.wn_o, PL.col.w_o, HDm, C_, C_, 1);
+    }
     prep_trans<T>(pm, W.mt, PL.mtrans, d.c_m, d.n_trans);
     {
       int co = d.c_opm, cm = d.c_m, cz = d.c_z;
@@ -515,6 +545,74 @@ template <typename T> struct Runner {
     }
   }
 
+  // ---- global column attention (extra-MSA blocks) ---------------------------
+  GcolArgs gcol_args(const GlobCtx<T>& c) const {
+    GcolArgs a;
+    memset(&a, 0, sizeof(a));
+    a.proj = c.proj; a.mask = msa_mask; a.qbar = c.qbar; a.den = c.den; a.p = c.p; a.o = c.o; a.og = c.og;
+    a.s = d.s; a.r = d.r; a.H = d.h_msa; a.d = d.d_msa; a.scale = 1.0f / sqrtf((float)d.d_msa);
+    return a;
+  }
+  void gcol_sub_fwd(hipStream_t st, const T* x, T* xout) {
+    const AttnP& p = PL.col;
+    GlobCtx<T>& c = C.gcol;
+    const int Cc = d.c_m, HD = HDm, dd = d.d_msa, Wg = 2 * HD + 2 * dd;
+    k_ln_fwd(st, x, p.ln_g, p.ln_b, c.xhat, c.stats, Mm, Cc);
+    {
+      EpiGeneric<T> e = epi_plain<T>(c.proj, Wg);
+      e.bias_n = P(p.b_g) - (HD + 2 * dd);
+      e.bn_begin = HD + 2 * dd;
+      gemm(st, op_plain(c.xhat, Cc), true, op_plain(W.gcol.wt_proj, Cc), true, (int)Mm, Wg, Cc, 1, e, "gcol proj");
+    }
+    if (!dry && !err) {
+      GcolArgs a = gcol_args(c);
+      const double pb = (double)Mm * Wg * sizeof(T);
+      PE_LAUNCH("gcol_qmean", 0, (double)Mm * HD * sizeof(T), st, gcol_qmean_kernel<T>, dim3(d.r), dim3(256), 0, a);
+      PE_LAUNCH("gcol_attn_fwd", 6.0 * Mm * HD, 3.0 * Mm * 2 * dd * sizeof(T), st, gcol_attn_fwd_kernel<T>, dim3(d.r), dim3(256), 0, a);
+      long long n = Mm * HD;
+      PE_LAUNCH("gcol_gate_fwd", 0, 2.0 * n * sizeof(T), st, gcol_gate_fwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, a);
+      (void)pb;
+    }
+    {
+      EpiGeneric<T> e = epi_plain<T>(xout, Cc);
+      e.bias_n = P(p.b_o);
+      e.res = x; e.ld_res = Cc;
+      gemm(st, op_plain(c.og, HD), true, op_plain(W.gcol.wt_o, HD), true, (int)Mm, Cc, HD, 1, e, "gcol out");
+    }
+  }
+  void gcol_sub_bwd(hipStream_t st, Arena& ar, const T* x, T* g) {
+    const AttnP& p = PL.col;
+    const GlobCtx<T>& c = C.gcol;
+    size_t mk = ar.mark();
+    const int Cc = d.c_m, HD = HDm, dd = d.d_msa, Wg = 2 * HD + 2 * dd;
+    T* dog = (T*)ar.alloc((size_t)Mm * HD * sizeof(T));
+    T* dproj = (T*)ar.alloc((size_t)Mm * Wg * sizeof(T));
+    float* dO = (float*)ar.alloc((size_t)d.r * HD * sizeof(float));
+    float* dqbar = (float*)ar.alloc((size_t)d.r * HD * sizeof(float));
+    T* dxh = (T*)ar.alloc((size_t)Mm * Cc * sizeof(T));
+    k_colsum(st, ar, g, Mm, Cc, Cc, p.b_o);
+    { ReduceSeg sg[1] = {{0, Cc, p.w_o, Cc}};
+      gemm_dw(st, ar, op_trans(c.og, HD), false, op_trans(g, Cc), false, HD, Cc, Mm, 1, sg, "gcol dWo"); }
+    { EpiGeneric<T> e = epi_plain<T>(dog, HD);
+      gemm(st, op_plain(g, Cc), true, op_plain(W.gcol.wn_o, Cc), true, (int)Mm, HD, Cc, 1, e, "gcol dog"); }
+    if (!dry && !err) {
+      GcolArgs a = gcol_args(c);
+      a.dproj = dproj; a.dog = dog; a.dO = dO; a.dqbar = dqbar;
+      long long n = Mm * HD;
+      PE_LAUNCH("gcol_gate_bwd", 0, 3.0 * n * sizeof(T), st, gcol_gate_bwd_kernel<T>, dim3(d.r), dim3(256), 0, a);
+      PE_LAUNCH("gcol_attn_bwd", 12.0 * Mm * HD, 4.0 * Mm * 2 * dd * sizeof(T), st, gcol_attn_bwd_kernel<T>, dim3(d.r), dim3(256), 0, a);
+      PE_LAUNCH("gcol_dq", 0, 1.0 * n * sizeof(T), st, gcol_dq_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, a);
+    }
+    k_colsum(st, ar, dproj + HD + 2 * dd, Mm, HD, Wg, p.b_g);
+    { ReduceSeg sg[4] = {{0, HD, p.w_q, HD}, {HD, dd, p.w_k, dd}, {HD + dd, dd, p.w_v, dd}, {HD + 2 * dd, HD, p.w_g, HD}};
+      gemm_dw(st, ar, op_trans(c.xhat, Cc), false, op_trans(dproj, Wg), false, Cc, Wg, Mm, 4, sg, "gcol dWproj"); }
+    { EpiGeneric<T> e = epi_plain<T>(dxh, Cc);
+      gemm(st, op_plain(dproj, Wg), true, op_plain(W.gcol.wn_proj, Wg), true, (int)Mm, Cc, Wg, 1, e, "gcol dxhat"); }
+    k_ln_bwd(st, ar, dxh, x, c.stats, p.ln_g, p.ln_b, g, g, Mm, Cc);
+    flush_reduces(st);
+    ar.release(mk);
+  }
+
   void trans_sub_fwd(hipStream_t st, const TransP& p, const TransW<T>& w, TransCtx<T>& c, const T* x, T* xout, long long M,
                      int Cc) {
     const int nC = d.n_trans * Cc;
@@ -584,7 +682,8 @@ template <typename T> struct Runner {
     run_prep(true);
     attn_sub_fwd(sm, am, PL.row, W.row, C.row, msa_in, C.m1, Mm, d.c_m, d.h_msa, d.d_msa, geom_row(), pair_in,
                  PL.row.ln_z_g, PL.row.ln_z_b);
-    attn_sub_fwd(sm, am, PL.col, W.col, C.col, C.m1, C.m2, Mm, d.c_m, d.h_msa, d.d_msa, geom_col(), nullptr, 0, 0);
+    if (d.col_global) gcol_sub_fwd(sm, C.m1, C.m2);
+    else attn_sub_fwd(sm, am, PL.col, W.col, C.col, C.m1, C.m2, Mm, d.c_m, d.h_msa, d.d_msa, geom_col(), nullptr, 0, 0);
     trans_sub_fwd(sm, PL.mtrans, W.mt, C.mt, C.m2, C.m3, Mm, d.c_m);
     if (!dry && !err && msa_out) {
       if (hipMemcpyAsync(msa_out, C.m3, (size_t)Mm * d.c_m * sizeof(T), hipMemcpyDeviceToDevice, sm) != hipSuccess)
@@ -855,7 +954,8 @@ template <typename T> struct Runner {
       am.release(mk);
     }
     trans_sub_bwd(sm, am, PL.mtrans, W.mt, C.mt, C.m2, gm, Mm, cm);
-    attn_sub_bwd(sm, am, PL.col, W.col, C.col, C.m1, gm, Mm, cm, d.h_msa, d.d_msa, geom_col(), nullptr, 0, 0, nullptr, nullptr);
+    if (d.col_global) gcol_sub_bwd(sm, am, C.m1, gm);
+    else attn_sub_bwd(sm, am, PL.col, W.col, C.col, C.m1, gm, Mm, cm, d.h_msa, d.d_msa, geom_col(), nullptr, 0, 0, nullptr, nullptr);
     attn_sub_bwd(sm, am, PL.row, W.row, C.row, msa_in, gm, Mm, cm, d.h_msa, d.d_msa, geom_row(), pair_in, PL.row.ln_z_g,
                  PL.row.ln_z_b, nullptr, dz_bias);
   }
@@ -1146,7 +1246,7 @@ int pe_set_option(pe_handle* h, int option, int value) {
 int pe_check_dims(const pe_dims* d) {
   int rc = pe_check_dims_impl(d);
   if (rc) return rc;
-  if (d->col_global) return PE_ERR_DIMS;   // global column attention: not built yet
+  if (d->col_global && (d->d_msa > GC_MAXD || d->h_msa > GC_MAXH)) return PE_ERR_DIMS;   // global variant: d <= 8, H <= 8
   return PE_OK;
 }
 long long pe_param_count(const pe_dims* d) {

@@ -83,3 +83,56 @@ def test_recompute_and_single_stream_match():
     for other in outs[1:]:
         for a, b in zip(outs[0], other):
             assert torch.equal(a, b)
+
+
+@pytest.mark.slow
+def test_af2_finetune_bf16():
+    """Config 4: fine-tuning shape (s=512, r=384), bf16 path, every output element."""
+    dims, table, inp = _case("af2_finetune")
+    _assert(*check_case(dims, table, inp)[:3])
+
+
+def test_masked_edge_cases():
+    """All MSA rows of one residue column masked except one, a fully masked residue (column
+    attention sees no valid key there), and an all-ones mask."""
+    for recipe in (("none", 0), ("last_residues", 15)):
+        dims, table, inp = _case("tiny", dtype=0)
+        table, n = param_table(dims)
+        inp = make_inputs(dims, table, n, recipe, 21)
+        _assert(*check_case(dims, table, inp)[:3])
+
+
+def test_bad_arguments_return_errors():
+    import torch
+    import paper_2211_00235_amd as pe
+    from tests.gpu_util import BlockRun
+    dims, table, inp = _case("tiny")
+    run = BlockRun(dims, inp)
+    with pytest.raises(pe.PEError, match="aliases"):
+        pe.block_fwd(run.h, dims, run.msa, run.pair, run.msa_mask, run.pair_mask, run.params, run.msa, run.pair_out,
+                     run.ctx, run.ws)
+    small = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    with pytest.raises(pe.PEError, match="workspace too small"):
+        pe.block_fwd(run.h, dims, run.msa, run.pair, run.msa_mask, run.pair_mask, run.params, run.msa_out,
+                     run.pair_out, run.ctx, small)
+    bad = dict(dims, c_m=30)
+    with pytest.raises(pe.PEError, match="unsupported dims"):
+        pe.block_fwd(run.h, bad, run.msa, run.pair, run.msa_mask, run.pair_mask, run.params, run.msa_out,
+                     run.pair_out, run.ctx, run.ws)
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_global_column_attention_small(dtype):
+    """Extra-MSA block variant (global column attention) at a small ragged shape."""
+    dims, table, inp = _case("tiny", dtype=dtype, s=70, r=45, c_m=32, h_msa=4, d_msa=8, col_global=1)
+    table, n = param_table(dims)
+    inp = make_inputs(dims, table, n, ("random_rows", 0.1), 31)
+    errs, worst, tol, _ = check_case(dims, table, inp)
+    _assert(errs, worst, SMALL_BF16_TOL if dtype == 1 else tol)
+
+
+@pytest.mark.slow
+def test_extra_msa_bf16():
+    """Config 3: extra-MSA-stack block (s=1024, r=256, c_m=64, global column attention), bf16."""
+    dims, table, inp = _case("extra_msa")
+    _assert(*check_case(dims, table, inp)[:3])

@@ -1,0 +1,141 @@
+"""GPU tests of pe_stack_fwd_bwd: against the oracle (fp32) and against chained single-block calls."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2211_00235_amd as pe
+from oracle import evoformer as ev
+from oracle.params import param_table
+from pe_inputs import make_inputs, dims_for
+from tests.gpu_util import to_dev, to_np, rel_err, tdtype
+
+pytestmark = pytest.mark.gpu
+
+
+def _stack_inputs(dims, n_blocks, seed, mask):
+    table, n = param_table(dims)
+    inp = make_inputs(dims, table, n, mask, seed, n_blocks=n_blocks)
+    return table, n, inp
+
+
+def _run_stack(dims, n_main, inp, two_streams=True):
+    dt, f32 = tdtype(dims), torch.float32
+    h = pe.Handle()
+    msa, pair = to_dev(inp["msa"], dt), to_dev(inp["pair"], dt)
+    mm, pm = to_dev(inp["msa_mask"], f32), to_dev(inp["pair_mask"], f32)
+    params = to_dev(inp["params"], f32)
+    dmo, dzo = to_dev(inp["d_msa_out"], dt), to_dev(inp["d_pair_out"], dt)
+    mo, zo, dmi, dzi = (torch.empty_like(t) for t in (msa, pair, msa, pair))
+    dpar = torch.zeros_like(params)
+    ws = torch.empty(pe.stack_workspace_bytes(0, None, n_main, dims), dtype=torch.uint8, device="cuda")
+    sm = torch.cuda.Stream() if two_streams else torch.cuda.current_stream()
+    sp = torch.cuda.Stream() if two_streams else sm
+    torch.cuda.synchronize()
+    pe.stack_fwd_bwd(h, 0, None, n_main, dims, None, msa, pair, None, mm, pm, params, dmo, dzo, mo, zo, None, dmi, dzi,
+                     dpar, ws, sm, sp)
+    torch.cuda.synchronize()
+    return mo, zo, dmi, dzi, dpar
+
+
+def test_stack_fp32_matches_oracle():
+    """Two tiny fp32 blocks: outputs, input cotangents and all parameter gradients at 1e-4."""
+    dims, mask, seed = dims_for("tiny")
+    table, n, inp = _stack_inputs(dims, 2, 11, mask)
+    mo, zo, dmi, dzi, dpar = _run_stack(dims, 2, inp)
+    r = ev.stack_fwd_bwd(0, None, 2, dims, inp["params"], None, inp["msa"], inp["pair"], None, inp["msa_mask"],
+                         inp["pair_mask"], inp["d_msa_out"], inp["d_pair_out"])
+    msa_o, pair_o, _, dm, dz, g = r
+    assert rel_err(to_np(mo), msa_o) < 1e-4 and rel_err(to_np(zo), pair_o) < 1e-4
+    assert rel_err(to_np(dmi), dm) < 1e-4 and rel_err(to_np(dzi), dz) < 1e-4
+    gg = to_np(dpar)
+    for b in range(2):
+        for e in table:
+            k = int(np.prod(e["shape"]))
+            sl = slice(b * n + e["offset"], b * n + e["offset"] + k)
+            den = max(np.max(np.abs(g[sl])), 1e-3 * np.max(np.abs(g)))
+            assert np.max(np.abs(gg[sl] - g[sl])) / den < 1e-4, (b, e["name"])
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_stack_equals_chained_blocks(dtype):
+    """The stack (saved block inputs + recompute) is bit-identical to calling pe_block_fwd for every
+    block and then pe_block_bwd in reverse order; this carries the block-level parity to any depth."""
+    dims, mask, seed = dims_for("tiny")
+    dims.update(dtype=dtype, s=16, r=40)
+    nb = 3
+    table, n, inp = _stack_inputs(dims, nb, 12, ("last_residues", 4))
+    mo, zo, dmi, dzi, dpar = _run_stack(dims, nb, inp)
+    dt, f32 = tdtype(dims), torch.float32
+    h = pe.Handle()
+    mm, pm = to_dev(inp["msa_mask"], f32), to_dev(inp["pair_mask"], f32)
+    params = to_dev(inp["params"], f32)
+    xs, zs = [to_dev(inp["msa"], dt)], [to_dev(inp["pair"], dt)]
+    ws = torch.empty(pe.workspace_bytes(dims, 1), dtype=torch.uint8, device="cuda")
+    for b in range(nb):
+        xo, zo2 = torch.empty_like(xs[0]), torch.empty_like(zs[0])
+        pe.block_fwd(h, dims, xs[b], zs[b], mm, pm, params[b * n:(b + 1) * n], xo, zo2, None, ws)
+        xs.append(xo)
+        zs.append(zo2)
+    dm, dz = to_dev(inp["d_msa_out"], dt), to_dev(inp["d_pair_out"], dt)
+    dpar2 = torch.zeros_like(params)
+    for b in reversed(range(nb)):
+        dmi2, dzi2 = torch.empty_like(dm), torch.empty_like(dz)
+        pe.block_bwd(h, dims, xs[b], zs[b], mm, pm, params[b * n:(b + 1) * n], dm, dz, dmi2, dzi2,
+                     dpar2[b * n:(b + 1) * n], None, ws)
+        dm, dz = dmi2, dzi2
+    torch.cuda.synchronize()
+    assert torch.equal(mo, xs[-1]) and torch.equal(zo, zs[-1])
+    assert torch.equal(dmi, dm) and torch.equal(dzi, dz) and torch.equal(dpar, dpar2)
+
+
+def test_stack_argument_errors():
+    dims, mask, seed = dims_for("tiny")
+    table, n, inp = _stack_inputs(dims, 1, 1, mask)
+    h = pe.Handle()
+    t = to_dev(inp["pair"], torch.float32)
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    with pytest.raises(pe.PEError, match="workspace too small"):
+        m = to_dev(inp["msa"], torch.float32)
+        pe.stack_fwd_bwd(h, 0, None, 1, dims, None, m, t, None, to_dev(inp["msa_mask"], torch.float32),
+                         to_dev(inp["pair_mask"], torch.float32), to_dev(inp["params"], torch.float32), m, t,
+                         torch.empty_like(m), torch.empty_like(t), None, torch.empty_like(m), torch.empty_like(t),
+                         torch.zeros(n, device="cuda"), small)
+
+
+def test_stack_extra_then_main_fp32_matches_oracle():
+    """One extra-MSA block (global column attention, its own s and c_m) followed by one main block:
+    the pair representation chains through both, the extra-MSA representation is dropped."""
+    dims_m, mask, seed = dims_for("tiny")
+    dims_e = dict(dims_m, s=24, c_m=16, col_global=1)
+    te, ne = param_table(dims_e)
+    tm, nm = param_table(dims_m)
+    ie = make_inputs(dims_e, te, ne, ("random_rows", 0.1), 41)
+    im = make_inputs(dims_m, tm, nm, mask, 42)
+    params = np.concatenate([ie["params"], im["params"]])
+    f32 = torch.float32
+    h = pe.Handle()
+    dev = lambda a: to_dev(a, f32)
+    ex, msa, pair = dev(ie["msa"]), dev(im["msa"]), dev(im["pair"])
+    exm, mm, pm = dev(ie["msa_mask"]), dev(im["msa_mask"]), dev(im["pair_mask"])
+    par = dev(params)
+    dmo, dzo = dev(im["d_msa_out"]), dev(im["d_pair_out"])
+    mo, zo, dex, dmi, dzi = (torch.empty_like(t) for t in (msa, pair, ex, msa, pair))
+    dpar = torch.zeros_like(par)
+    ws = torch.empty(pe.stack_workspace_bytes(1, dims_e, 1, dims_m), dtype=torch.uint8, device="cuda")
+    sm, sp = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    pe.stack_fwd_bwd(h, 1, dims_e, 1, dims_m, ex, msa, pair, exm, mm, pm, par, dmo, dzo, mo, zo, dex, dmi, dzi, dpar,
+                     ws, sm, sp)
+    torch.cuda.synchronize()
+    r = ev.stack_fwd_bwd(1, dims_e, 1, dims_m, params, ie["msa"], im["msa"], im["pair"], ie["msa_mask"],
+                         im["msa_mask"], im["pair_mask"], im["d_msa_out"], im["d_pair_out"])
+    msa_o, pair_o, de, dm, dz, g = r
+    for got, ref in ((mo, msa_o), (zo, pair_o), (dex, de), (dmi, dm), (dzi, dz)):
+        assert rel_err(to_np(got), ref) < 1e-4
+    gg = to_np(dpar)
+    for off, table in ((0, te), (ne, tm)):
+        for e in table:
+            k = int(np.prod(e["shape"]))
+            sl = slice(off + e["offset"], off + e["offset"] + k)
+            den = max(np.max(np.abs(g[sl])), 1e-3 * np.max(np.abs(g)))
+            assert np.max(np.abs(gg[sl] - g[sl])) / den < 1e-4, e["name"]
