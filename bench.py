@@ -40,6 +40,50 @@ def block_fwd_flops(d):
     return f
 
 
+def bench_trunk(args, torch, pe):
+    """Config 5: 4 extra-MSA blocks then 48 main blocks, per-block recompute, two streams."""
+    from pe_inputs import dims_for, make_inputs
+    from tests.gpu_util import to_dev
+    de, me, _ = dims_for("extra_msa")
+    dm, mmk, _ = dims_for("af2_initial")
+    ne, nm = 4, 48
+    te, tm = pe.param_table(de), pe.param_table(dm)
+    ie = make_inputs(de, te, pe.param_count(de), me, 4, n_blocks=ne)
+    im = make_inputs(dm, tm, pe.param_count(dm), mmk, 5, n_blocks=nm)
+    bf, f32 = torch.bfloat16, torch.float32
+    ex, msa, pair = to_dev(ie["msa"], bf), to_dev(im["msa"], bf), to_dev(im["pair"], bf)
+    exm, mm, pm = to_dev(ie["msa_mask"], f32), to_dev(im["msa_mask"], f32), to_dev(im["pair_mask"], f32)
+    par = torch.cat([to_dev(ie["params"], f32), to_dev(im["params"], f32)])
+    dmo, dzo = to_dev(im["d_msa_out"], bf), to_dev(im["d_pair_out"], bf)
+    mo, zo, dex, dmi, dzi = (torch.empty_like(t) for t in (msa, pair, ex, msa, pair))
+    dpar = torch.zeros_like(par)
+    ws = torch.empty(pe.stack_workspace_bytes(ne, de, nm, dm), dtype=torch.uint8, device="cuda")
+    h = pe.Handle()
+    sm, sp = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def step():
+        pe.stack_fwd_bwd(h, ne, de, nm, dm, ex, msa, pair, exm, mm, pm, par, dmo, dzo, mo, zo, dex, dmi, dzi, dpar,
+                         ws, sm, sp)
+    steps, warm = max(1, min(args.steps, 5)), max(1, min(args.warmup, 2))
+    for _ in range(warm):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    flops = 3.0 * (ne * block_fwd_flops(de) + nm * block_fwd_flops(dm))
+    print(json.dumps({
+        "metric": "Parallel Evoformer trunk (4 extra + 48 main blocks) fwd+bwd ms", "value": ms, "unit": "ms",
+        "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": ms, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "trunk", "n_extra": ne, "n_main": nm, "recompute": "per block", "streams": 2},
+        "counted_tflops": flops / (ms * 1e-3) / 1e12,
+        "bf16_mfma_peak_frac": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "finite_outputs": bool(torch.isfinite(zo.float()).all().item() and torch.isfinite(dpar).all().item())}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -63,6 +107,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
+    if args.workload == "trunk":
+        return bench_trunk(args, torch, pe)
     dims, mask, seed = dims_for(args.workload)
     table = pe.param_table(dims)
     inp = make_inputs(dims, table, pe.param_count(dims), mask, seed)
