@@ -381,10 +381,28 @@ template <typename T> struct Runner {
   // ---- kernel wrappers -----------------------------------------------------
   const float* P(long long off) const { return params + off; }
 
+  static int ln_lpr(int Cc) {   // lanes per row of the fast LayerNorm kernels, 0 = generic kernel
+    for (int l = 2; l <= 64; l <<= 1)
+      if (Cc == 8 * l) return l;
+    return 0;
+  }
   void k_ln_fwd(hipStream_t st, const T* x, long long g_off, long long b_off, T* y, float* stats, long long M, int Cc) {
     if (dry || err) return;
+    const int lpr = ln_lpr(Cc);
+    const double bytes = 2.0 * M * Cc * sizeof(T);
+    if (lpr) {
+      const int rpw = 64 / lpr;
+      int grid = (int)std::min<long long>((M + 4 * rpw - 1) / (4 * rpw), 8192);
+#define PE_LN_FWD(L) PE_LAUNCH("ln_fwd", 0, bytes, st, (ln_fwd_fast_kernel<T, L>), dim3(grid), dim3(256), 0, x, P(g_off), P(b_off), y, stats, M, d.ln_eps)
+      switch (lpr) {
+        case 2: PE_LN_FWD(2); break;   case 4: PE_LN_FWD(4); break;   case 8: PE_LN_FWD(8); break;
+        case 16: PE_LN_FWD(16); break; case 32: PE_LN_FWD(32); break; default: PE_LN_FWD(64); break;
+      }
+#undef PE_LN_FWD
+      return;
+    }
     int grid = (int)std::min<long long>((M + 3) / 4, 4096);
-    PE_LAUNCH("ln_fwd", 0, 2.0 * M * Cc * sizeof(T), st, ln_fwd_kernel<T>, dim3(grid), dim3(256), 0, x, P(g_off), P(b_off), y, stats, M, Cc, d.ln_eps);
+    PE_LAUNCH("ln_fwd", 0, bytes, st, ln_fwd_kernel<T>, dim3(grid), dim3(256), 0, x, P(g_off), P(b_off), y, stats, M, Cc, d.ln_eps);
   }
   // Reductions of fp32 partials into d_params are queued and launched several per kernel
   // (flush_reduces).  Partial buffers stay allocated until the enclosing sub-operation
@@ -424,10 +442,22 @@ template <typename T> struct Runner {
   }
   void k_ln_bwd(hipStream_t st, Arena& ar, const T* dy, const T* x, const float* stats, long long g_off, long long b_off,
                 const T* gin, T* gout, long long M, int Cc) {
-    int grid = (int)std::min<long long>((M + 3) / 4, LN_MAX_WG);
+    const int lpr = ln_lpr(Cc);
+    const int rpw = lpr ? 64 / lpr : 1;
+    int grid = (int)std::min<long long>((M + 4 * rpw - 1) / (4 * rpw), LN_MAX_WG);
     float* part = (float*)ar.alloc((size_t)grid * 2 * Cc * sizeof(float));
     if (!dry && !err) {
-      PE_LAUNCH("ln_bwd", 0, (gin ? 4.0 : 3.0) * M * Cc * sizeof(T), st, ln_bwd_kernel<T>, dim3(grid), dim3(256), 0, dy, x, stats, P(g_off), gin, gout, part, M, Cc);
+      const double bytes = (gin ? 4.0 : 3.0) * M * Cc * sizeof(T);
+      if (lpr) {
+#define PE_LN_BWD(L) PE_LAUNCH("ln_bwd", 0, bytes, st, (ln_bwd_fast_kernel<T, L>), dim3(grid), dim3(256), 0, dy, x, stats, P(g_off), gin, gout, part, M)
+        switch (lpr) {
+          case 2: PE_LN_BWD(2); break;   case 4: PE_LN_BWD(4); break;   case 8: PE_LN_BWD(8); break;
+          case 16: PE_LN_BWD(16); break; case 32: PE_LN_BWD(32); break; default: PE_LN_BWD(64); break;
+        }
+#undef PE_LN_BWD
+      } else {
+        PE_LAUNCH("ln_bwd", 0, bytes, st, ln_bwd_kernel<T>, dim3(grid), dim3(256), 0, dy, x, stats, P(g_off), gin, gout, part, M, Cc);
+      }
       ReduceSeg sg[2] = {{0, Cc, g_off, 0}, {Cc, Cc, b_off, 0}};
       reduce_to(st, part, grid, 2LL * Cc, 1, 2 * Cc, 2, sg);
     }
@@ -517,9 +547,22 @@ template <typename T> struct Runner {
     const int HD = H * dh;
     k_ln_fwd(st, x, p.ln_g, p.ln_b, c.xhat, c.stats, M, Cc);
     if (c.bias && !dry && !err) {
-      int grid = (int)std::min<long long>((Mz + 3) / 4, 4096);
-      PE_LAUNCH("ln_bias_fwd", 2.0 * Mz * d.c_z * H, 1.0 * Mz * d.c_z * sizeof(T) + 4.0 * Mz * H, st, ln_bias_fwd_kernel<T>, dim3(grid), dim3(256), 0, bias_src, P(bias_ln_g), P(bias_ln_b),
-                         P(p.w_bias), c.bias, c.biasT, c.zstats, d.r, d.c_z, H, d.ln_eps, g.bias_transposed);
+      const int lpr = ln_lpr(d.c_z);
+      const double fl = 2.0 * Mz * d.c_z * H, by = 1.0 * Mz * d.c_z * sizeof(T) + 8.0 * Mz * H;
+      if (lpr && lpr <= 32) {
+        const int rpw = 64 / lpr;
+        int grid = (int)std::min<long long>((Mz + 4 * rpw - 1) / (4 * rpw), 1024);   // long loops amortise the weight preload
+#define PE_LNB_FWD(L) PE_LAUNCH("ln_bias_fwd", fl, by, st, (ln_bias_fwd_fast_kernel<T, L>), dim3(grid), dim3(256), 0, bias_src, P(bias_ln_g), P(bias_ln_b), P(p.w_bias), c.bias, c.biasT, c.zstats, d.r, H, d.ln_eps, g.bias_transposed)
+        switch (lpr) {
+          case 2: PE_LNB_FWD(2); break; case 4: PE_LNB_FWD(4); break; case 8: PE_LNB_FWD(8); break;
+          case 16: PE_LNB_FWD(16); break; default: PE_LNB_FWD(32); break;
+        }
+#undef PE_LNB_FWD
+      } else {
+        int grid = (int)std::min<long long>((Mz + 3) / 4, 4096);
+        PE_LAUNCH("ln_bias_fwd", fl, by, st, ln_bias_fwd_kernel<T>, dim3(grid), dim3(256), 0, bias_src, P(bias_ln_g), P(bias_ln_b),
+                  P(p.w_bias), c.bias, c.biasT, c.zstats, d.r, d.c_z, H, d.ln_eps, g.bias_transposed);
+      }
     }
     {
       EpiGeneric<T> e = epi_plain<T>(c.qkvg, 4 * HD);
@@ -808,12 +851,24 @@ template <typename T> struct Runner {
     flush_reduces(st);   // the bias path below adds to the same LayerNorm parameters: separate launch
     if (c.bias) {
       const int cz = d.c_z;
-      int grid = (int)std::min<long long>((Mz + 3) / 4, LN_MAX_WG);
+      const int lpr = (ln_lpr(cz) && ln_lpr(cz) <= 32) ? ln_lpr(cz) : 0;
+      const int rpw = lpr ? 64 / lpr : 1;
+      int grid = (int)std::min<long long>((Mz + 4 * rpw - 1) / (4 * rpw), 1024);
       int plen = 2 * cz + cz * H;
       float* part = (float*)ar.alloc((size_t)grid * plen * sizeof(float));
       if (!dry && !err) {
-        PE_LAUNCH("ln_bias_bwd", 4.0 * Mz * cz * H, (bias_gin ? 3.0 : 2.0) * Mz * cz * sizeof(T) + 4.0 * Mz * H, st, ln_bias_bwd_kernel<T>, dim3(grid), dim3(256), 0, dbias, bias_src, c.zstats, P(bias_ln_g),
-                           P(bias_ln_b), P(p.w_bias), bias_gin, bias_gout, part, d.r, cz, H, gm.bias_transposed ^ 1);
+        const double fl = 4.0 * Mz * cz * H, by = (bias_gin ? 3.0 : 2.0) * Mz * cz * sizeof(T) + 4.0 * Mz * H;
+        if (lpr) {
+#define PE_LNB_BWD(L) PE_LAUNCH("ln_bias_bwd", fl, by, st, (ln_bias_bwd_fast_kernel<T, L>), dim3(grid), dim3(256), 0, dbias, bias_src, c.zstats, P(bias_ln_g), P(bias_ln_b), P(p.w_bias), bias_gin, bias_gout, part, d.r, H, gm.bias_transposed ^ 1)
+          switch (lpr) {
+            case 2: PE_LNB_BWD(2); break; case 4: PE_LNB_BWD(4); break; case 8: PE_LNB_BWD(8); break;
+            case 16: PE_LNB_BWD(16); break; default: PE_LNB_BWD(32); break;
+          }
+#undef PE_LNB_BWD
+        } else {
+          PE_LAUNCH("ln_bias_bwd", fl, by, st, ln_bias_bwd_kernel<T>, dim3(grid), dim3(256), 0, dbias, bias_src, c.zstats,
+                    P(bias_ln_g), P(bias_ln_b), P(p.w_bias), bias_gin, bias_gout, part, d.r, cz, H, gm.bias_transposed ^ 1);
+        }
         ReduceSeg sg[3] = {{0, cz, bias_ln_g, 0}, {cz, cz, bias_ln_b, 0}, {2 * cz, cz * H, p.w_bias, 0}};
         reduce_to(st, part, grid, plen, 1, plen, 3, sg);
       }

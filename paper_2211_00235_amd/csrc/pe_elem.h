@@ -156,6 +156,140 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* dy, const T* x, co
 }
 
 // ---------------------------------------------------------------------------
+// Fast LayerNorm path for C = 8 * LPR channels (LPR = lanes per row, a power of two <= 64):
+// a wave handles 64 / LPR rows at once, every lane owns 8 consecutive channels (one 16-byte
+// load for bf16), row statistics are reductions over LPR lanes.  Twice to eight times more
+// bytes in flight per wave than the generic kernels above, which stay as the fallback.
+// ---------------------------------------------------------------------------
+template <typename T> PE_DEV void ld8(const T* p, float (&v)[8]) {
+  float a[4], b[4];
+  load4<T>(p, a);
+  load4<T>(p + 4, b);
+#pragma unroll
+  for (int e = 0; e < 4; e++) { v[e] = a[e]; v[4 + e] = b[e]; }
+}
+template <> PE_DEV void ld8<bf16>(const bf16* p, float (&v)[8]) {
+  bf16x8 t = *reinterpret_cast<const bf16x8*>(p);
+#pragma unroll
+  for (int e = 0; e < 8; e++) v[e] = (float)t[e];
+}
+template <typename T> PE_DEV void st8(T* p, const float (&v)[8]) {
+  float a[4] = {v[0], v[1], v[2], v[3]}, b[4] = {v[4], v[5], v[6], v[7]};
+  store4<T>(p, a);
+  store4<T>(p + 4, b);
+}
+template <> PE_DEV void st8<bf16>(bf16* p, const float (&v)[8]) {
+  bf16x8 t;
+#pragma unroll
+  for (int e = 0; e < 8; e++) t[e] = (bf16)v[e];
+  *reinterpret_cast<bf16x8*>(p) = t;
+}
+template <int LPR> PE_DEV float group_sum(float v) {
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+template <typename T, int LPR>
+__global__ __launch_bounds__(256) void ln_fwd_fast_kernel(const T* x, const float* gamma, const float* beta, T* y,
+                                                          float* stats, long long M, float eps) {
+  constexpr int C = 8 * LPR, RPW = 64 / LPR;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPR, rw = lane / LPR, c0 = sub * 8;
+  float gm[8], bt[8];
+#pragma unroll
+  for (int e = 0; e < 8; e++) { gm[e] = gamma[c0 + e]; bt[e] = beta[c0 + e]; }
+  const long long stride = (long long)gridDim.x * 4 * RPW;
+  for (long long row = ((long long)blockIdx.x * 4 + wave) * RPW + rw; row < M + rw; row += stride) {
+    const bool ok = row < M;          // row - rw < M for the whole wave: shuffles stay convergent
+    float v[8];
+    if (ok) ld8<T>(x + row * C + c0, v);
+    else {
+#pragma unroll
+      for (int e = 0; e < 8; e++) v[e] = 0.0f;
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; e++) s += v[e];
+    float mu = group_sum<LPR>(s) * (1.0f / C);
+    float q = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; e++) { float t = v[e] - mu; q += t * t; }
+    float rstd = rsqrtf(group_sum<LPR>(q) * (1.0f / C) + eps);
+    if (ok) {
+      float o[8];
+#pragma unroll
+      for (int e = 0; e < 8; e++) o[e] = (v[e] - mu) * rstd * gm[e] + bt[e];
+      st8<T>(y + row * C + c0, o);
+      if (sub == 0) { stats[row * 2] = mu; stats[row * 2 + 1] = rstd; }
+    }
+  }
+}
+
+template <typename T, int LPR>
+__global__ __launch_bounds__(256) void ln_bwd_fast_kernel(const T* dy, const T* x, const float* stats, const float* gamma,
+                                                          const T* gin, T* gout, float* partial, long long M) {
+  constexpr int C = 8 * LPR, RPW = 64 / LPR;
+  __shared__ float red[4][2 * C];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPR, rw = lane / LPR, c0 = sub * 8;
+  float gm[8], dgs[8], dbs[8];
+#pragma unroll
+  for (int e = 0; e < 8; e++) { gm[e] = gamma[c0 + e]; dgs[e] = 0.0f; dbs[e] = 0.0f; }
+  const long long stride = (long long)gridDim.x * 4 * RPW;
+  for (long long row = ((long long)blockIdx.x * 4 + wave) * RPW + rw; row < M + rw; row += stride) {
+    const bool ok = row < M;
+    float xv[8], dv[8], xh[8], dxh[8];
+    float mu = 0.0f, rstd = 0.0f;
+    if (ok) {
+      ld8<T>(x + row * C + c0, xv);
+      ld8<T>(dy + row * C + c0, dv);
+      mu = stats[row * 2];
+      rstd = stats[row * 2 + 1];
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; e++) { xv[e] = 0.0f; dv[e] = 0.0f; }
+    }
+    float s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      xh[e] = (xv[e] - mu) * rstd;
+      dxh[e] = dv[e] * gm[e];
+      dgs[e] += dv[e] * xh[e];
+      dbs[e] += dv[e];
+      s1 += dxh[e];
+      s2 += dxh[e] * xh[e];
+    }
+    s1 = group_sum<LPR>(s1) * (1.0f / C);
+    s2 = group_sum<LPR>(s2) * (1.0f / C);
+    if (ok) {
+      float o[8];
+      if (gin) ld8<T>(gin + row * C + c0, o);
+      else {
+#pragma unroll
+        for (int e = 0; e < 8; e++) o[e] = 0.0f;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; e++) o[e] += (dxh[e] - s1 - xh[e] * s2) * rstd;
+      st8<T>(gout + row * C + c0, o);
+    }
+  }
+  // rows of a wave hold the same channels in lanes sub, sub + LPR, ...: fold them, then fold the waves
+#pragma unroll
+  for (int e = 0; e < 8; e++) {
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1) { dgs[e] += __shfl_xor(dgs[e], o, 64); dbs[e] += __shfl_xor(dbs[e], o, 64); }
+  }
+  if (rw == 0) {
+#pragma unroll
+    for (int e = 0; e < 8; e++) { red[wave][c0 + e] = dgs[e]; red[wave][C + c0 + e] = dbs[e]; }
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < 2 * C; c += 256)
+    partial[(long long)blockIdx.x * 2 * C + c] = red[0][c] + red[1][c] + red[2][c] + red[3][c];
+}
+
+// ---------------------------------------------------------------------------
 // LayerNorm over channels of a CHANNEL-MAJOR tensor x_t[C][M] (triangle-multiplication
 // contraction output), producing channel-last y[M][C].  A workgroup handles 64
 // consecutive positions: thread (p = tid%64, part = tid/64) walks channels part, part+4, ..
@@ -358,6 +492,153 @@ __global__ __launch_bounds__(256) void ln_bias_bwd_kernel(const float* dbias, co
   for (int t = threadIdx.x; t < C * H; t += 256) {
     int cc = t / H, h = t % H;
     int k = 512 + cc * BIAS_MAXH + h;
+    pp[2 * C + t] = red[0][k] + red[1][k] + red[2][k] + red[3][k];
+  }
+}
+
+// Fast variants for C = 8 * LPR (LPR <= 32): 64 / LPR rows per wave, 8 channels per lane.
+template <typename T, int LPR>
+__global__ __launch_bounds__(256) void ln_bias_fwd_fast_kernel(const T* z, const float* gamma, const float* beta,
+                                                               const float* w, float* bias, float* biasT, float* stats,
+                                                               int r, int H, float eps, int transposed) {
+  constexpr int C = 8 * LPR, RPW = 64 / LPR;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPR, rw = lane / LPR, c0 = sub * 8;
+  float gm[8], bt[8], wv[8][BIAS_MAXH];
+#pragma unroll
+  for (int e = 0; e < 8; e++) {
+    gm[e] = gamma[c0 + e];
+    bt[e] = beta[c0 + e];
+#pragma unroll
+    for (int h = 0; h < BIAS_MAXH; h++) wv[e][h] = (h < H) ? w[(c0 + e) * H + h] : 0.0f;
+  }
+  const long long M = (long long)r * r;
+  const long long stride = (long long)gridDim.x * 4 * RPW;
+  for (long long row = ((long long)blockIdx.x * 4 + wave) * RPW + rw; row < M + rw; row += stride) {
+    const bool ok = row < M;
+    float v[8];
+    if (ok) ld8<T>(z + row * C + c0, v);
+    else {
+#pragma unroll
+      for (int e = 0; e < 8; e++) v[e] = 0.0f;
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; e++) s += v[e];
+    float mu = group_sum<LPR>(s) * (1.0f / C);
+    float q = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; e++) { float t = v[e] - mu; q += t * t; }
+    float rstd = rsqrtf(group_sum<LPR>(q) * (1.0f / C) + eps);
+    float y[8];
+#pragma unroll
+    for (int e = 0; e < 8; e++) y[e] = (v[e] - mu) * rstd * gm[e] + bt[e];
+    const long long rr = ok ? row : 0;
+    const int i = rr / r, j = rr % r;
+    const long long o = transposed ? ((long long)j * r + i) : rr;
+    const long long oT = transposed ? rr : ((long long)j * r + i);
+#pragma unroll
+    for (int h = 0; h < BIAS_MAXH; h++) {
+      if (h < H) {
+        float t = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; e++) t += y[e] * wv[e][h];
+        t = group_sum<LPR>(t);
+        if (ok && sub == 0) { bias[(long long)h * M + o] = t; biasT[(long long)h * M + oT] = t * 1.4426950408889634f; }
+      }
+    }
+    if (ok && sub == 0) { stats[row * 2] = mu; stats[row * 2 + 1] = rstd; }
+  }
+}
+
+template <typename T, int LPR>
+__global__ __launch_bounds__(256) void ln_bias_bwd_fast_kernel(const float* dbias, const T* z, const float* stats,
+                                                               const float* gamma, const float* beta, const float* w,
+                                                               const T* gin, T* gout, float* partial, int r, int H,
+                                                               int transposed) {
+  constexpr int C = 8 * LPR, RPW = 64 / LPR;
+  __shared__ float red[4][C * (2 + BIAS_MAXH)];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPR, rw = lane / LPR, c0 = sub * 8;
+  float gm[8], bt[8], wv[8][BIAS_MAXH], dgs[8], dbs[8], dws[8][BIAS_MAXH];
+#pragma unroll
+  for (int e = 0; e < 8; e++) {
+    gm[e] = gamma[c0 + e];
+    bt[e] = beta[c0 + e];
+    dgs[e] = 0.0f; dbs[e] = 0.0f;
+#pragma unroll
+    for (int h = 0; h < BIAS_MAXH; h++) { wv[e][h] = (h < H) ? w[(c0 + e) * H + h] : 0.0f; dws[e][h] = 0.0f; }
+  }
+  const long long M = (long long)r * r;
+  const long long stride = (long long)gridDim.x * 4 * RPW;
+  for (long long row = ((long long)blockIdx.x * 4 + wave) * RPW + rw; row < M + rw; row += stride) {
+    const bool ok = row < M;
+    const long long rr = ok ? row : 0;
+    const int i = rr / r, j = rr % r;
+    const long long o = transposed ? ((long long)j * r + i) : rr;
+    float db[BIAS_MAXH];
+#pragma unroll
+    for (int h = 0; h < BIAS_MAXH; h++) db[h] = (ok && h < H) ? dbias[(long long)h * M + o] : 0.0f;
+    float v[8];
+    float mu = 0.0f, rstd = 0.0f;
+    if (ok) { ld8<T>(z + row * C + c0, v); mu = stats[row * 2]; rstd = stats[row * 2 + 1]; }
+    else {
+#pragma unroll
+      for (int e = 0; e < 8; e++) v[e] = 0.0f;
+    }
+    float xh[8], dxh[8];
+    float s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      xh[e] = (v[e] - mu) * rstd;
+      float y = xh[e] * gm[e] + bt[e];
+      float dy = 0.0f;
+#pragma unroll
+      for (int h = 0; h < BIAS_MAXH; h++) { dy += db[h] * wv[e][h]; dws[e][h] += y * db[h]; }
+      dxh[e] = dy * gm[e];
+      dgs[e] += dy * xh[e];
+      dbs[e] += dy;
+      s1 += dxh[e];
+      s2 += dxh[e] * xh[e];
+    }
+    s1 = group_sum<LPR>(s1) * (1.0f / C);
+    s2 = group_sum<LPR>(s2) * (1.0f / C);
+    if (ok) {
+      float ov[8];
+      if (gin) ld8<T>(gin + row * C + c0, ov);
+      else {
+#pragma unroll
+        for (int e = 0; e < 8; e++) ov[e] = 0.0f;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; e++) ov[e] += (dxh[e] - s1 - xh[e] * s2) * rstd;
+      st8<T>(gout + row * C + c0, ov);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; e++) {
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1) {
+      dgs[e] += __shfl_xor(dgs[e], o, 64);
+      dbs[e] += __shfl_xor(dbs[e], o, 64);
+#pragma unroll
+      for (int h = 0; h < BIAS_MAXH; h++) dws[e][h] += __shfl_xor(dws[e][h], o, 64);
+    }
+  }
+  if (rw == 0) {
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      red[wave][c0 + e] = dgs[e];
+      red[wave][C + c0 + e] = dbs[e];
+#pragma unroll
+      for (int h = 0; h < BIAS_MAXH; h++) red[wave][2 * C + (c0 + e) * BIAS_MAXH + h] = dws[e][h];
+    }
+  }
+  __syncthreads();
+  float* pp = partial + (long long)blockIdx.x * (2 * C + C * H);
+  for (int t = threadIdx.x; t < 2 * C; t += 256) pp[t] = red[0][t] + red[1][t] + red[2][t] + red[3][t];
+  for (int t = threadIdx.x; t < C * H; t += 256) {
+    int k = 2 * C + (t / H) * BIAS_MAXH + (t % H);
     pp[2 * C + t] = red[0][k] + red[1][k] + red[2][k] + red[3][k];
   }
 }
