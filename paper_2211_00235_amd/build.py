@@ -8,6 +8,7 @@ LIB = os.path.join(HERE, "libpe_mi355x.so")
 SOURCES = ["pe_block.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-mfma-vgpr-form",      # MFMA accumulators in VGPRs: no AGPR<->VGPR copies around the softmax
          "-Wno-pass-failed", "-Wno-unused-result"]
 
 

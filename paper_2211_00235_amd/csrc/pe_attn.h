@@ -111,6 +111,8 @@ template <typename T> PE_DEV typename Mma<T>::frag gl_frag(const T* p, int kk, i
 // score MFMAs (clamped addresses, no branches), so their latency overlaps the matrix work.
 #define PE_LOG2E 1.4426950408889634f
 #define PE_LN2 0.6931471805599453f
+// raw v_exp_f32 (2^x; results below the normal range flush to zero, which is what softmax wants)
+PE_DEV float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // bias values of one 32x32 tile for this lane's query: element e <-> key row acc_row(g, e)
 PE_DEV void attn_load_bias16(const float* bcol, int L, int key0 /* first key of the tile + 4g */, float (&bv)[16]) {
@@ -125,7 +127,7 @@ PE_DEV void attn_load_bias16(const float* bcol, int L, int key0 /* first key of 
 // Forward
 // grid (ceil(L/128), H, B), 256 threads; wave w owns queries q0 = blockIdx.x*128 + 32*w
 // ---------------------------------------------------------------------------
-template <typename T>
+template <typename T, bool HAS_BIAS>
 __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
   typedef AttnCfg<T> C;
   typedef Mma<T> MM;
@@ -153,7 +155,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
 #pragma unroll
   for (int e = 0; e < 16; e++) oacc[e] = 0.0f;
   float m_run = -INFINITY, l_run = 0.0f;
-  const bool has_bias = a.biasT != nullptr;
+  constexpr bool has_bias = HAS_BIAS;
   const float* bcol = has_bias ? a.biasT + (long long)h * L * L + min(qi, L - 1) : nullptr;   // + key * L
   const float c1 = a.scale * PE_LOG2E;
 
@@ -198,11 +200,11 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
       tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
       float m_new = fmaxf(m_run, tmax);
       float m_use = (m_new == -INFINITY) ? 0.0f : m_new;
-      float corr = exp2f(m_run - m_use);     // m_run = -inf -> 0
+      float corr = fast_exp2(m_run - m_use);     // m_run = -inf -> 0
       float psum = 0.0f;
 #pragma unroll
       for (int e = 0; e < 16; e++) {
-        float p = exp2f(sacc[e] - m_use);
+        float p = fast_exp2(sacc[e] - m_use);
         sacc[e] = p;
         psum += p;
       }
@@ -291,7 +293,7 @@ __global__ __launch_bounds__(256) void attn_bwd_pre_kernel(AttnArgs a) {
 // ---------------------------------------------------------------------------
 // Backward, dQ (+ dS for the bias gradient).  Same tiling as the forward kernel.
 // ---------------------------------------------------------------------------
-template <typename T>
+template <typename T, bool HAS_BIAS>
 __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnArgs a) {
   typedef AttnCfg<T> C;
   typedef Mma<T> MM;
@@ -323,7 +325,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnArgs a) {
   const long long sidx = ((long long)b * a.H + h) * L + qi;
   const float lse2 = qok ? a.lse[sidx] * PE_LOG2E : 0.0f;
   const float Di = qok ? a.D[sidx] : 0.0f;
-  const bool has_bias = a.biasT != nullptr;
+  constexpr bool has_bias = HAS_BIAS;
   const float* bcol = has_bias ? a.biasT + (long long)h * L * L + min(qi, L - 1) : nullptr;      // + key * L
   T* dscol = (a.dS && qok) ? (T*)a.dS + ((long long)b * a.H + h) * L * L + qi : nullptr;         // + key * L
   const float c1 = a.scale * PE_LOG2E;
@@ -365,7 +367,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnArgs a) {
         for (int r = 0; r < 4; r++) {
           int e = q4 * 4 + r;
           float t = has_bias ? fmaf(sacc[e], c1, bv[e]) : sacc[e] * c1;
-          float p = exp2f(t + ma[r] - lse2);
+          float p = fast_exp2(t + ma[r] - lse2);
           sacc[e] = p * (pacc[e] - Di);
         }
       }
@@ -400,7 +402,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnArgs a) {
 // Backward, dK and dV.  Wave w owns keys k0 = blockIdx.x*128 + 32*w (a key is a lane);
 // loops over query tiles staged in LDS (row-major and transposed copies of Q and dO).
 // ---------------------------------------------------------------------------
-template <typename T>
+template <typename T, bool HAS_BIAS>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
   typedef AttnCfg<T> C;
   typedef Mma<T> MM;
@@ -433,7 +435,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
     }
   const float mk = kok ? a.mask[(long long)b * a.mask_bs + (long long)kj * a.mask_ks] : 0.0f;
   const float madd = (mk > 0.0f) ? 0.0f : -INFINITY;
-  const bool has_bias = a.bias != nullptr;
+  constexpr bool has_bias = HAS_BIAS;
   const float* bcol = has_bias ? a.bias + (long long)h * L * L + min(kj, L - 1) : nullptr;   // + query * L
   const float c1 = a.scale * PE_LOG2E;
 
@@ -477,7 +479,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
           int e = q4 * 4 + r;
           float t = sacc[e] * c1;
           if (has_bias) t = fmaf(bv[e], PE_LOG2E, t);
-          float p = exp2f(t + madd - ls[r]);
+          float p = fast_exp2(t + madd - ls[r]);
           pv[e] = p;
           sacc[e] = p * (pacc[e] - Dr[r]);
         }
