@@ -17,6 +17,7 @@
 // owns 64x64 = 2x2 MFMA tiles (64 accumulator VGPRs).  Next k-tile is prefetched
 // into registers while the current one is consumed from LDS.
 #pragma once
+#include <string.h>
 #include "pe_common.h"
 
 struct Operand {
@@ -366,8 +367,14 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
   const int wm = wave >> 1, wn = wave & 1;
-  const int b = blockIdx.z;
-  const int m0 = blockIdx.y * C::BM, n0 = blockIdx.x * C::BN;
+  // XCD-aware mapping: workgroup w runs on XCD w % 8; all column tiles of one (batch, m-tile)
+  // unit go to the same XCD so that its L2 serves the shared A rows.
+  const int NTm = (sh.M + C::BM - 1) / C::BM, NTn = (sh.N + C::BN - 1) / C::BN;
+  const int xcd = blockIdx.x & 7, jq = blockIdx.x >> 3;
+  const int unit = xcd + 8 * (jq / NTn);
+  if (unit >= NTm * sh.batch) return;
+  const int b = unit / NTm;
+  const int m0 = (unit % NTm) * C::BM, n0 = (jq % NTn) * C::BN;
 
   int kbeg = 0, kend = sh.K;
   const T* pa = (const T*)A.ptr;
@@ -544,7 +551,8 @@ static inline int launch_gemm(hipStream_t st, const Operand& A, bool a_kc, const
   bool al = gemm_operand_ok<T>(A, a_kc, sh.M, sh) && gemm_operand_ok<T>(B, b_kc, sh.N, sh);
   bool ve = al && epi.vec_ok(sh.N);
   if (used_vec) *used_vec = ve;
-  dim3 grid((sh.N + 127) / 128, (sh.M + 127) / 128, sh.batch);
+  const int NTm_ = (sh.M + 127) / 128, NTn_ = (sh.N + 127) / 128;
+  dim3 grid((unsigned)(8 * ((NTm_ * sh.batch + 7) / 8) * NTn_));
   if (ve) launch_gemm_al<T, true, true, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);
   else if (al) launch_gemm_al<T, true, false, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);
   else launch_gemm_al<T, false, false, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);

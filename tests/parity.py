@@ -57,6 +57,7 @@ def check_case(dims, table, inp, two_streams=True, use_ctx=True, verbose=False):
     errs["pair_out"] = rel_err(to_np(run.pair_out), z)
     if not use_ctx:
         run.ctx.zero_()
+        run.sync()
     run.bwd(use_ctx=use_ctx)
     run.sync()
     errs["d_msa_in"] = rel_err(to_np(run.d_msa_in), dm)

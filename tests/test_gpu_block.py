@@ -76,7 +76,9 @@ def test_recompute_and_single_stream_match():
         run = BlockRun(dims, inp, two_streams=two)
         run.fwd()
         if not use_ctx:
+            run.sync()          # zero_() runs on torch's stream, the forward on the run's own streams
             run.ctx.zero_()
+            run.sync()
         run.bwd(use_ctx=use_ctx)
         run.sync()
         outs.append([t.clone() for t in (run.msa_out, run.pair_out, run.d_msa_in, run.d_pair_in, run.d_params)])
