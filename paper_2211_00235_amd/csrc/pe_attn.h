@@ -4,10 +4,14 @@
 // MSA column attention (no bias, strided sequence axis), triangle attention around the
 // starting node and around the ending node (strided axes + transposed bias).
 //
-// Data layout: q, k, v and the gate pre-activation live in one tensor `qkvg` of rows
-// [4][H][d]; element (batch b, position p, which w, head h, channel c) is at
-//   qkvg + b*batch_stride + p*seq_stride + w*H*d + h*d + c.
-// The outputs o / og / do use rows [H][d] with strides batch_stride/4, seq_stride/4.
+// Data layout: HEAD-MAJOR.  q, k, v and the gate pre-activation live in one tensor `qkvg` of
+// 4*H planes [B*L][d]; element (which w, head h, batch b, position p, channel c) is at
+//   qkvg + (w*H + h)*plane + (b*L + p)*d + c,      plane = B*L*d.
+// o / og / dO / dog are H planes of the same shape.  A head's K, V, Q tile is therefore one
+// contiguous run of memory (64 positions x 64 bytes at d = 32) whatever axis the attention runs
+// along; the producing / consuming GEMMs reach this layout through their two-level index maps.
+// (With channel-last [B*L][4*H*d] rows a head's 64-byte slice sits alone in its 128-byte line:
+// measured HBM fetch of the forward kernel was 2.5x its algorithmic bytes.)
 //
 // Kernel design (gfx950): every wave owns 32 queries (or 32 keys in the dK/dV kernel) and
 // computes TRANSPOSED score tiles S^T = K Q^T with v_mfma 32x32, so that a query is a
@@ -22,7 +26,7 @@
 #include "pe_elem.h"
 
 struct AttnArgs {
-  const void* qkvg; long long batch_stride, seq_stride;
+  const void* qkvg; long long plane;    // plane = B*L*d elements
   int B, L, H, d;
   const float* bias;                 // [H][L][L] (query, key) or nullptr
   const float* biasT;                // the same values as [H][key][query] (read by the query-per-lane kernels)
@@ -51,7 +55,7 @@ PE_DEV int round_up_i(int a, int b) { return (a + b - 1) / b * b; }
 // row-major copy (stride RM, columns d..DP-1 zero filled) and/or a transposed copy
 // (rows = channel, stride TS).  Rows beyond L are zero.
 template <typename T>
-PE_DEV void attn_stage(const T* src /* at (b, 0, w, h, 0) */, long long seq_stride, int pos0, int L, int d, int DP,
+PE_DEV void attn_stage(const T* src /* at (w, h, b, position 0, 0) */, int seq_stride, int pos0, int L, int d, int DP,
                        T* lds_rm, T* lds_t, int tid, int nthreads) {
   typedef AttnCfg<T> C;
   typedef typename Vec16<T>::type V;
@@ -62,7 +66,7 @@ PE_DEV void attn_stage(const T* src /* at (b, 0, w, h, 0) */, long long seq_stri
 #pragma unroll
     for (int e = 0; e < C::VEC; e++) v[e] = from_f<T>(0.0f);
     int pos = pos0 + row;
-    if (pos < L && dd0 < d) v = *reinterpret_cast<const V*>(src + (long long)pos * seq_stride + dd0);
+    if (pos < L && dd0 < d) v = *reinterpret_cast<const V*>(src + pos * seq_stride + dd0);
     if (lds_rm) *reinterpret_cast<V*>(lds_rm + row * C::RM + dd0) = v;
     if (lds_t) {
 #pragma unroll
@@ -142,8 +146,9 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
   const int NKK = DP / MM::KSTEP;
   const int qi = blockIdx.x * 128 + wave * 32 + l32;       // this lane's query
   const bool qok = qi < L;
-  const T* base = (const T*)a.qkvg + (long long)b * a.batch_stride + h * d;
-  const T* qrow = qok ? base + (long long)qi * a.seq_stride : nullptr;
+  const long long HP = (long long)a.H * a.plane;            // distance between the q, k, v, gate groups
+  const T* base = (const T*)a.qkvg + h * a.plane + (long long)b * L * d;
+  const T* qrow = qok ? base + qi * d : nullptr;
 
   constexpr int MAXKK = 32 / MM::KSTEP;   // 2 (bf16) or 16 (fp32): d <= 32
   typename MM::frag qf[MAXKK];
@@ -161,8 +166,8 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
 
   for (int j0 = 0; j0 < L; j0 += C::KT) {
     __syncthreads();
-    attn_stage<T>(base + HD, a.seq_stride, j0, L, d, DP, lds_k, (T*)nullptr, tid, 256);
-    attn_stage<T>(base + 2 * HD, a.seq_stride, j0, L, d, DP, (T*)nullptr, lds_vt, tid, 256);
+    attn_stage<T>(base + HP, d, j0, L, d, DP, lds_k, (T*)nullptr, tid, 256);
+    attn_stage<T>(base + 2 * HP, d, j0, L, d, DP, (T*)nullptr, lds_vt, tid, 256);
     if (tid < C::KT) {
       int j = j0 + tid;
       float mk = (j < L) ? a.mask[(long long)b * a.mask_bs + (long long)j * a.mask_ks] : 0.0f;
@@ -226,10 +231,10 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
   if (!qok) return;
   float inv = (l_run > 0.0f) ? 1.0f / l_run : 0.0f;
   if (g == 0) a.lse[((long long)b * a.H + h) * L + qi] = (l_run > 0.0f) ? (m_run + log2f(l_run)) * PE_LN2 : 0.0f;
-  const long long orow = (long long)b * (a.batch_stride / 4) + (long long)qi * (a.seq_stride / 4) + h * d;
+  const long long orow = h * a.plane + ((long long)b * L + qi) * d;
   T* po = (T*)a.o + orow;
   T* pog = (T*)a.og + orow;
-  const T* pg = qrow + 3 * HD;
+  const T* pg = qrow + 3 * HP;
 #pragma unroll
   for (int q4 = 0; q4 < 4; q4++) {
     int dd = 8 * q4 + 4 * g;
@@ -253,20 +258,21 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
 // ---------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void attn_bwd_pre_kernel(AttnArgs a) {
-  // 8 lanes per (b, p, h): lane `sub` owns channels [4*sub, 4*sub+4)
+  // 8 lanes per (h, b, p): lane `sub` owns channels [4*sub, 4*sub+4); consecutive groups walk
+  // consecutive positions of one head plane (contiguous memory)
   long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   const int sub = gid & 7;
   long long idx = gid >> 3;
-  long long total = (long long)a.B * a.L * a.H;
+  const long long M = (long long)a.B * a.L;
+  long long total = M * a.H;
   const bool ok = idx < total;
   if (!ok) idx = total - 1;
-  int h = idx % a.H;
-  long long t = idx / a.H;
-  int p = t % a.L;
-  int b = t / a.L;
-  const int d = a.d, HD = a.H * a.d;
-  long long qoff = (long long)b * a.batch_stride + (long long)p * a.seq_stride + 3 * HD + h * d;
-  long long ooff = (long long)b * (a.batch_stride / 4) + (long long)p * (a.seq_stride / 4) + h * d;
+  const int h = idx / M;
+  const long long plin = idx % M;
+  const int b = plin / a.L, p = plin % a.L;
+  const int d = a.d;
+  long long qoff = (3LL * a.H + h) * a.plane + plin * d;
+  long long ooff = h * a.plane + plin * d;
   float Dsum = 0.0f;
   const int c0 = sub * 4;
   if (ok && c0 < d) {
@@ -309,9 +315,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnArgs a) {
   const int NKK = DP / MM::KSTEP;
   const int qi = blockIdx.x * 128 + wave * 32 + l32;
   const bool qok = qi < L;
-  const T* base = (const T*)a.qkvg + (long long)b * a.batch_stride + h * d;
-  const T* qrow = qok ? base + (long long)qi * a.seq_stride : nullptr;
-  const long long orow = (long long)b * (a.batch_stride / 4) + (long long)qi * (a.seq_stride / 4) + h * d;
+  const long long HP = (long long)a.H * a.plane;
+  const T* base = (const T*)a.qkvg + h * a.plane + (long long)b * L * d;
+  const T* qrow = qok ? base + qi * d : nullptr;
+  const long long orow = h * a.plane + ((long long)b * L + qi) * d;
   const T* dorow = qok ? (const T*)a.dO + orow : nullptr;
 
   constexpr int MAXKK = 32 / MM::KSTEP;
@@ -336,8 +343,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnArgs a) {
 
   for (int j0 = 0; j0 < L; j0 += C::KT) {
     __syncthreads();
-    attn_stage<T>(base + HD, a.seq_stride, j0, L, d, DP, lds_k, lds_kt, tid, 256);
-    attn_stage<T>(base + 2 * HD, a.seq_stride, j0, L, d, DP, lds_v, (T*)nullptr, tid, 256);
+    attn_stage<T>(base + HP, d, j0, L, d, DP, lds_k, lds_kt, tid, 256);
+    attn_stage<T>(base + 2 * HP, d, j0, L, d, DP, lds_v, (T*)nullptr, tid, 256);
     if (tid < C::KT) {
       int j = j0 + tid;
       float mk = (j < L) ? a.mask[(long long)b * a.mask_bs + (long long)j * a.mask_ks] : 0.0f;
@@ -385,7 +392,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnArgs a) {
     }
   }
   if (!qok) return;
-  T* pdq = (T*)a.dqkvg + (long long)b * a.batch_stride + (long long)qi * a.seq_stride + h * d;
+  T* pdq = (T*)a.dqkvg + orow;
 #pragma unroll
   for (int q4 = 0; q4 < 4; q4++) {
     int dd = 8 * q4 + 4 * g;
@@ -420,10 +427,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
   const int NKK = DP / MM::KSTEP;
   const int kj = blockIdx.x * 128 + wave * 32 + l32;       // this lane's key
   const bool kok = kj < L;
-  const T* base = (const T*)a.qkvg + (long long)b * a.batch_stride + h * d;
-  const T* krow = kok ? base + (long long)kj * a.seq_stride + HD : nullptr;
-  const T* vrow = kok ? base + (long long)kj * a.seq_stride + 2 * HD : nullptr;
-  const T* dobase = (const T*)a.dO + (long long)b * (a.batch_stride / 4) + h * d;
+  const long long HP = (long long)a.H * a.plane;
+  const T* base = (const T*)a.qkvg + h * a.plane + (long long)b * L * d;
+  const T* krow = kok ? base + HP + kj * d : nullptr;
+  const T* vrow = kok ? base + 2 * HP + kj * d : nullptr;
+  const T* dobase = (const T*)a.dO + h * a.plane + (long long)b * L * d;
 
   constexpr int MAXKK = 32 / MM::KSTEP;
   typename MM::frag kf[MAXKK], vf[MAXKK];
@@ -445,8 +453,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
 
   for (int i0 = 0; i0 < L; i0 += C::KT) {
     __syncthreads();
-    attn_stage<T>(base, a.seq_stride, i0, L, d, DP, lds_q, lds_qt, tid, 256);
-    attn_stage<T>(dobase, a.seq_stride / 4, i0, L, d, DP, lds_do, lds_dot, tid, 256);
+    attn_stage<T>(base, d, i0, L, d, DP, lds_q, lds_qt, tid, 256);
+    attn_stage<T>(dobase, d, i0, L, d, DP, lds_do, lds_dot, tid, 256);
     if (tid < C::KT) {
       int i = i0 + tid;
       long long sidx = ((long long)b * a.H + h) * L + i;
@@ -494,8 +502,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
     }
   }
   if (!kok) return;
-  T* pdk = (T*)a.dqkvg + (long long)b * a.batch_stride + (long long)kj * a.seq_stride + HD + h * d;
-  T* pdv = pdk + HD;
+  T* pdk = (T*)a.dqkvg + HP + h * a.plane + ((long long)b * L + kj) * d;
+  T* pdv = pdk + HP;
 #pragma unroll
   for (int q4 = 0; q4 < 4; q4++) {
     int dd = 8 * q4 + 4 * g;

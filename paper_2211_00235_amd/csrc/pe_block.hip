@@ -462,13 +462,17 @@ template <typename T> struct Runner {
       reduce_to(st, part, grid, 2LL * Cc, 1, 2 * Cc, 2, sg);
     }
   }
-  void k_colsum(hipStream_t st, Arena& ar, const T* y, long long M, int N, long long ld, long long dst_off) {
+  // column sums of y[M][N]; column n lives at (n / n_in) * n_outer + n % n_in (+ m * ld): plain
+  // matrices use n_in = N, head-major tensors n_in = head dim, n_outer = plane
+  void k_colsum(hipStream_t st, Arena& ar, const T* y, long long M, int N, long long ld, long long dst_off, int n_in = 0,
+                long long n_outer = 0) {
+    if (n_in == 0) n_in = N;
     int nwg = (int)std::min<long long>(1024, (M + 31) / 32);
     long long rpw = (M + nwg - 1) / nwg;
     nwg = (int)((M + rpw - 1) / rpw);
     float* part = (float*)ar.alloc((size_t)nwg * N * sizeof(float));
     if (!dry && !err) {
-      PE_LAUNCH("colsum", 0, 1.0 * M * N * sizeof(T), st, colsum_kernel<T>, dim3(nwg), dim3(256), 0, y, M, N, ld, part, rpw);
+      PE_LAUNCH("colsum", 0, 1.0 * M * N * sizeof(T), st, colsum_kernel<T>, dim3(nwg), dim3(256), 0, y, M, N, ld, part, rpw, n_in, n_outer);
       ReduceSeg sg[1] = {{0, N, dst_off, 0}};
       reduce_to(st, part, nwg, N, 1, N, 1, sg);
     }
@@ -538,8 +542,32 @@ template <typename T> struct Runner {
   }
 
   // ---- sub-operations: forward ---------------------------------------------
-  struct AttnGeom { long long B, L, batch_stride, seq_stride, mask_bs, mask_ks; const float* mask; int bias_transposed;
+  // tr = 0: GEMM row m is already the head-plane position b*L + p (row attention, starting node);
+  // tr = 1: m = p*B' + b with B' = inner (the attention runs along the slow axis: column attention,
+  // ending node), so the plane position is (m % inner)*L + m / inner.
+  struct AttnGeom { long long B, L; int tr; long long inner, mask_bs, mask_ks; const float* mask; int bias_transposed;
                     const char *l_fwd, *l_dq, *l_dkv; };
+  // head-major addressing of the per-head tensors through the GEMM index maps (dh = head dim)
+  static void plane_rows(const AttnGeom& g, int dh, int& in, long long& outer, long long& stride) {
+    if (g.tr) { in = (int)g.inner; outer = dh; stride = g.L * dh; }
+    else { in = 1 << 30; outer = 0; stride = dh; }
+  }
+  Operand op_heads_rows(const void* ptr, const AttnGeom& g, int dh, long long plane) const {   // rows = positions, k = (head, c)
+    Operand o; o.ptr = ptr; o.batch_stride = 0;
+    plane_rows(g, dh, o.x_in, o.x_outer, o.x_stride);
+    o.k_in = dh; o.k_outer = plane; o.k_stride = 1;
+    return o;
+  }
+  Operand op_heads_cols(const void* ptr, const AttnGeom& g, int dh, long long plane) const {   // rows = (head, c), k = positions
+    Operand o; o.ptr = ptr; o.batch_stride = 0;
+    o.x_in = dh; o.x_outer = plane; o.x_stride = 1;
+    plane_rows(g, dh, o.k_in, o.k_outer, o.k_stride);
+    return o;
+  }
+  void epi_heads(EpiGeneric<T>& e, const AttnGeom& g, int dh, long long plane) const {
+    plane_rows(g, dh, e.om_in, e.om_outer, e.om_stride);
+    e.on_in = dh; e.on_outer = plane; e.on_stride = 1;
+  }
 
   void attn_sub_fwd(hipStream_t st, Arena& ar, const AttnP& p, const AttnW<T>& w, AttnCtx<T>& c, const T* x, T* xout,
                     long long M, int Cc, int H, int dh, const AttnGeom& g, const T* bias_src, long long bias_ln_g,
@@ -566,6 +594,7 @@ template <typename T> struct Runner {
     }
     {
       EpiGeneric<T> e = epi_plain<T>(c.qkvg, 4 * HD);
+      epi_heads(e, g, dh, M * dh);
       e.bias_n = P(p.b_g) - 3 * HD;   // only columns >= 3HD carry a bias (see bn_begin)
       e.bn_begin = 3 * HD;
       gemm(st, op_plain(c.xhat, Cc), true, op_plain(w.wt_qkvg, Cc), true, (int)M, 4 * HD, Cc, 1, e, "attn qkvg");
@@ -573,7 +602,7 @@ template <typename T> struct Runner {
     if (!dry && !err) {
       AttnArgs a;
       memset(&a, 0, sizeof(a));
-      a.qkvg = c.qkvg; a.batch_stride = g.batch_stride; a.seq_stride = g.seq_stride;
+      a.qkvg = c.qkvg; a.plane = M * dh;
       a.B = (int)g.B; a.L = (int)g.L; a.H = H; a.d = dh;
       a.bias = c.bias; a.biasT = c.biasT; a.mask = g.mask; a.mask_bs = g.mask_bs; a.mask_ks = g.mask_ks;
       a.o = c.o; a.og = c.og; a.lse = c.lse; a.scale = 1.0f / sqrtf((float)dh);
@@ -585,7 +614,7 @@ template <typename T> struct Runner {
       EpiGeneric<T> e = epi_plain<T>(xout, Cc);
       e.bias_n = P(p.b_o);
       e.res = x; e.ld_res = Cc;
-      gemm(st, op_plain(c.og, HD), true, op_plain(w.wt_o, HD), true, (int)M, Cc, HD, 1, e, "attn out");
+      gemm(st, op_heads_rows(c.og, g, dh, M * dh), true, op_plain(w.wt_o, HD), true, (int)M, Cc, HD, 1, e, "attn out");
     }
   }
 
@@ -713,13 +742,13 @@ template <typename T> struct Runner {
     }
   }
 
-  AttnGeom geom_row() const { return AttnGeom{d.s, d.r, (long long)d.r * 4 * HDm, 4LL * HDm, d.r, 1, msa_mask, 0,
+  AttnGeom geom_row() const { return AttnGeom{d.s, d.r, 0, 0, d.r, 1, msa_mask, 0,
                                                "attn_fwd row", "attn_dq row", "attn_dkv row"}; }
-  AttnGeom geom_col() const { return AttnGeom{d.r, d.s, 4LL * HDm, (long long)d.r * 4 * HDm, 1, d.r, msa_mask, 0,
+  AttnGeom geom_col() const { return AttnGeom{d.r, d.s, 1, d.r, 1, d.r, msa_mask, 0,
                                                "attn_fwd col", "attn_dq col", "attn_dkv col"}; }
-  AttnGeom geom_tas() const { return AttnGeom{d.r, d.r, (long long)d.r * 4 * HDz, 4LL * HDz, d.r, 1, pair_mask, 0,
+  AttnGeom geom_tas() const { return AttnGeom{d.r, d.r, 0, 0, d.r, 1, pair_mask, 0,
                                                "attn_fwd tas", "attn_dq tas", "attn_dkv tas"}; }
-  AttnGeom geom_tae() const { return AttnGeom{d.r, d.r, 4LL * HDz, (long long)d.r * 4 * HDz, 1, d.r, pair_mask, 1,
+  AttnGeom geom_tae() const { return AttnGeom{d.r, d.r, 1, d.r, 1, d.r, pair_mask, 1,
                                                "attn_fwd tae", "attn_dq tae", "attn_dkv tae"}; }
 
   void fwd_msa(T* msa_out) {
@@ -821,13 +850,14 @@ template <typename T> struct Runner {
     }
     k_colsum(st, ar, g, M, Cc, Cc, p.b_o);
     { ReduceSeg sg[1] = {{0, Cc, p.w_o, Cc}};
-      gemm_dw(st, ar, op_trans(c.og, HD), false, op_trans(g, Cc), false, HD, Cc, M, 1, sg, "attn dWo"); }
+      gemm_dw(st, ar, op_heads_cols(c.og, gm, dh, M * dh), false, op_trans(g, Cc), false, HD, Cc, M, 1, sg, "attn dWo"); }
     { EpiGeneric<T> e = epi_plain<T>(dog, HD);
+      epi_heads(e, gm, dh, M * dh);
       gemm(st, op_plain(g, Cc), true, op_plain(w.wn_o, Cc), true, (int)M, HD, Cc, 1, e, "attn dog"); }
     if (!dry && !err) {
       AttnArgs a;
       memset(&a, 0, sizeof(a));
-      a.qkvg = c.qkvg; a.batch_stride = gm.batch_stride; a.seq_stride = gm.seq_stride;
+      a.qkvg = c.qkvg; a.plane = M * dh;
       a.B = (int)gm.B; a.L = (int)gm.L; a.H = H; a.d = dh;
       a.bias = c.bias; a.biasT = c.biasT; a.mask = gm.mask; a.mask_bs = gm.mask_bs; a.mask_ks = gm.mask_ks;
       a.o = c.o; a.og = c.og; a.lse = c.lse; a.scale = 1.0f / sqrtf((float)dh);
@@ -845,11 +875,11 @@ template <typename T> struct Runner {
                            (int)gm.B, hll);
       }
     }
-    k_colsum(st, ar, dqkvg + 3 * HD, M, HD, 4 * HD, p.b_g);
+    k_colsum(st, ar, dqkvg + 3LL * H * M * dh, M, HD, dh, p.b_g, dh, M * dh);   // gate planes [H][M][d]
     { ReduceSeg sg[4] = {{0, HD, p.w_q, HD}, {HD, HD, p.w_k, HD}, {2 * HD, HD, p.w_v, HD}, {3 * HD, HD, p.w_g, HD}};
-      gemm_dw(st, ar, op_trans(c.xhat, Cc), false, op_trans(dqkvg, 4 * HD), false, Cc, 4 * HD, M, 4, sg, "attn dWqkvg"); }
+      gemm_dw(st, ar, op_trans(c.xhat, Cc), false, op_heads_cols(dqkvg, gm, dh, M * dh), false, Cc, 4 * HD, M, 4, sg, "attn dWqkvg"); }
     { EpiGeneric<T> e = epi_plain<T>(dxh, Cc);
-      gemm(st, op_plain(dqkvg, 4 * HD), true, op_plain(w.wn_qkvg, 4 * HD), true, (int)M, Cc, 4 * HD, 1, e, "attn dxhat"); }
+      gemm(st, op_heads_rows(dqkvg, gm, dh, M * dh), true, op_plain(w.wn_qkvg, 4 * HD), true, (int)M, Cc, 4 * HD, 1, e, "attn dxhat"); }
     k_ln_bwd(st, ar, dxh, x, c.stats, p.ln_g, p.ln_b, g, g, M, Cc);
     flush_reduces(st);   // the bias path below adds to the same LayerNorm parameters: separate launch
     if (c.bias) {

@@ -702,7 +702,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceBatch rb) {
 // Thread = (column group of 4, row lane); 8/16-byte loads, LDS reduction over row lanes.
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T* y, long long M, int N, long long ld, float* partial,
-                                                     long long rows_per_wg) {
+                                                     long long rows_per_wg, int n_in, long long n_outer) {
   __shared__ float red[256][4];
   const long long r0 = (long long)blockIdx.x * rows_per_wg;
   const long long r1 = r0 + rows_per_wg < M ? r0 + rows_per_wg : M;
@@ -713,7 +713,7 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* y, long long M, in
       float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
       for (long long m = r0; m < r1; m++) {
         float v[4];
-        load4<T>(y + m * ld + cg * 4, v);
+        load4<T>(y + m * ld + (long long)((cg * 4) / n_in) * n_outer + (cg * 4) % n_in, v);
         s[0] += v[0]; s[1] += v[1]; s[2] += v[2]; s[3] += v[3];
       }
       store4<float>(partial + (long long)blockIdx.x * N + cg * 4, s);
@@ -723,10 +723,11 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* y, long long M, in
   const int RL = 256 / ncg;
   const int cg = tid % ncg, rl = tid / ncg;
   float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  const long long coff = (long long)((cg * 4) / n_in) * n_outer + (cg * 4) % n_in;
   if (rl < RL)
     for (long long m = r0 + rl; m < r1; m += RL) {
       float v[4];
-      load4<T>(y + m * ld + cg * 4, v);
+      load4<T>(y + m * ld + coff, v);
       s[0] += v[0]; s[1] += v[1]; s[2] += v[2]; s[3] += v[3];
     }
   red[tid][0] = s[0]; red[tid][1] = s[1]; red[tid][2] = s[2]; red[tid][3] = s[3];
