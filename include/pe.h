@@ -90,8 +90,8 @@ typedef struct pe_ctx_entry {
   int dtype;
 } pe_ctx_entry;
 
-/* Handle: owns a few hipEvents used to fork/join the two streams.  Host
- * state only.  Not thread safe; use one handle per host thread.              */
+/* Handle: owns a few hipEvents used to fork/join the streams and two side
+ * streams (default priority).  Host state only.  Not thread safe; use one handle per host thread.              */
 int pe_create(pe_handle** h);
 int pe_destroy(pe_handle* h);
 
@@ -102,8 +102,13 @@ int pe_destroy(pe_handle* h);
  * sub-operation (slow; for fault isolation).
  * PE_OPT_KERNEL_TIMING: 1 = bracket every kernel launch with a pair of HIP
  * events on the stream it is launched on; read the result with
- * pe_timing_collect (measurement only: events add launch overhead).          */
-enum { PE_OPT_BRANCHES = 1, PE_OPT_SYNC_DEBUG = 2, PE_OPT_KERNEL_TIMING = 3 };
+ * pe_timing_collect (measurement only: events add launch overhead).
+ * PE_OPT_SIDE_STREAMS (default 0): 1 = the backward pass runs parameter-
+ * gradient kernels (dW GEMMs, bias sums, partial reductions) on one library-
+ * owned side stream per branch, forked from / joined to the caller's streams
+ * with events; results are bit-identical.  Measured slower on MI355X (each
+ * cross-stream event wait costs more than the overlap wins), hence off.      */
+enum { PE_OPT_BRANCHES = 1, PE_OPT_SYNC_DEBUG = 2, PE_OPT_KERNEL_TIMING = 3, PE_OPT_SIDE_STREAMS = 4 };
 int pe_set_option(pe_handle* h, int option, int value);
 
 /* Per-kernel timing since the last collect, aggregated by launch label.

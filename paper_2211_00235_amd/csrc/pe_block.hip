@@ -22,6 +22,10 @@ struct pe_handle {
   int branches;
   int sync_debug;
   int timing;                       // PE_OPT_KERNEL_TIMING
+  int side_streams;                 // PE_OPT_SIDE_STREAMS
+  hipStream_t side[2];              // side stream of the MSA branch / of the pair branch
+  hipEvent_t side_ev[32];           // ring of fork/join events
+  int side_ev_next;
   std::vector<ProfRec> recs;        // one per timed launch since the last collect
   std::vector<hipEvent_t> ev_pool;  // reusable timing events
   std::string last_error;
@@ -404,6 +408,28 @@ template <typename T> struct Runner {
     int grid = (int)std::min<long long>((M + 3) / 4, 4096);
     PE_LAUNCH("ln_fwd", 0, bytes, st, ln_fwd_kernel<T>, dim3(grid), dim3(256), 0, x, P(g_off), P(b_off), y, stats, M, Cc, d.ln_eps);
   }
+  // Side streams: parameter-gradient work (dW GEMMs, bias column sums, partial reductions) is off
+  // the critical path of the backward pass and its kernels have small grids, so it runs on a
+  // second stream per branch, forked from / joined to the branch's stream with events.  A join
+  // happens before any buffer the side stream reads is overwritten or released.
+  bool side_dirty[2] = {false, false};
+  int side_idx(hipStream_t st) const { return (st == sp && sp != sm) ? 1 : 0; }
+  bool side_on() const { return !dry && h && h->side_streams; }
+  hipStream_t side_of(hipStream_t st) { return side_on() ? h->side[side_idx(st)] : st; }
+  hipEvent_t next_side_event() { hipEvent_t e = h->side_ev[h->side_ev_next]; h->side_ev_next = (h->side_ev_next + 1) & 31; return e; }
+  void fork_side(hipStream_t st) {      // side stream waits for everything queued on st so far
+    if (!side_on() || err) return;
+    hipEvent_t e = next_side_event();
+    if (hipEventRecord(e, st) != hipSuccess || hipStreamWaitEvent(h->side[side_idx(st)], e, 0) != hipSuccess) fail("fork_side");
+    side_dirty[side_idx(st)] = true;
+  }
+  void join_side(hipStream_t st) {      // st waits for the side stream
+    if (!side_on() || err || !side_dirty[side_idx(st)]) return;
+    hipEvent_t e = next_side_event();
+    if (hipEventRecord(e, h->side[side_idx(st)]) != hipSuccess || hipStreamWaitEvent(st, e, 0) != hipSuccess) fail("join_side");
+    side_dirty[side_idx(st)] = false;
+  }
+
   // Reductions of fp32 partials into d_params are queued and launched several per kernel
   // (flush_reduces).  Partial buffers stay allocated until the enclosing sub-operation
   // releases its arena frame, which every sub-operation does after flushing.
@@ -420,8 +446,10 @@ template <typename T> struct Runner {
     pending.push_back(ra);
     (void)st;
   }
-  void flush_reduces(hipStream_t st) {
+  void flush_reduces(hipStream_t main_st) {
     if (dry || err) { pending.clear(); return; }
+    fork_side(main_st);
+    hipStream_t st = side_of(main_st);
     for (size_t i = 0; i < pending.size(); i += REDUCE_BATCH) {
       ReduceBatch rb;
       rb.n = (int)std::min((size_t)REDUCE_BATCH, pending.size() - i);
@@ -439,6 +467,7 @@ template <typename T> struct Runner {
       PE_LAUNCH("reduce_partials", 0, bytes, st, reduce_partials_kernel, dim3((unsigned)maxblocks, rb.n), dim3(256), 0, rb);
     }
     pending.clear();
+    join_side(main_st);
   }
   void k_ln_bwd(hipStream_t st, Arena& ar, const T* dy, const T* x, const float* stats, long long g_off, long long b_off,
                 const T* gin, T* gout, long long M, int Cc) {
@@ -447,6 +476,7 @@ template <typename T> struct Runner {
     int grid = (int)std::min<long long>((M + 4 * rpw - 1) / (4 * rpw), LN_MAX_WG);
     float* part = (float*)ar.alloc((size_t)grid * 2 * Cc * sizeof(float));
     if (!dry && !err) {
+      join_side(st);   // gout may alias a buffer the side stream is still reading
       const double bytes = (gin ? 4.0 : 3.0) * M * Cc * sizeof(T);
       if (lpr) {
 #define PE_LN_BWD(L) PE_LAUNCH("ln_bwd", 0, bytes, st, (ln_bwd_fast_kernel<T, L>), dim3(grid), dim3(256), 0, dy, x, stats, P(g_off), gin, gout, part, M)
@@ -472,6 +502,8 @@ template <typename T> struct Runner {
     nwg = (int)((M + rpw - 1) / rpw);
     float* part = (float*)ar.alloc((size_t)nwg * N * sizeof(float));
     if (!dry && !err) {
+      fork_side(st);
+      st = side_of(st);
       PE_LAUNCH("colsum", 0, 1.0 * M * N * sizeof(T), st, colsum_kernel<T>, dim3(nwg), dim3(256), 0, y, M, N, ld, part, rpw, n_in, n_outer);
       ReduceSeg sg[1] = {{0, N, dst_off, 0}};
       reduce_to(st, part, nwg, N, 1, N, 1, sg);
@@ -527,6 +559,8 @@ template <typename T> struct Runner {
     int nsplit = (int)((K + kc - 1) / kc);
     float* part = (float*)ar.alloc((size_t)nsplit * rows * cols * sizeof(float));
     if (!dry && !err) {
+      fork_side(st);
+      st = side_of(st);
       GemmShape sh{rows, cols, (int)K, nsplit, (int)kc};
       EpiPartial ep{part, (long long)rows * cols, cols};
       prof_begin(st);
@@ -964,7 +998,9 @@ template <typename T> struct Runner {
       const int nch = 16;
       float* part = (float*)ar.alloc((size_t)nch * 4 * ct * sizeof(float));
       if (!dry && !err) {
-        PE_LAUNCH("rowsum", 0, 4.0 * ct * Mz * sizeof(T), st, rowsum_kernel<T>, dim3(4 * ct, nch), dim3(256), 0, dproj_t, Mz,
+        fork_side(st);
+        hipStream_t sst = side_of(st);
+        PE_LAUNCH("rowsum", 0, 4.0 * ct * Mz * sizeof(T), sst, rowsum_kernel<T>, dim3(4 * ct, nch), dim3(256), 0, dproj_t, Mz,
                   part, 4 * ct);
         ReduceSeg sg[4] = {{0, ct, p.b_ap, 0}, {ct, ct, p.b_ag, 0}, {2 * ct, ct, p.b_bp, 0}, {3 * ct, ct, p.b_bg, 0}};
         reduce_to(st, part, nch, 4LL * ct, 1, 4 * ct, 4, sg);
@@ -1300,12 +1336,18 @@ static bool overlap(const void* a, size_t na, const void* b, size_t nb) {
 
 extern "C" {
 
+int pe_destroy(pe_handle* h);
+
 int pe_create(pe_handle** out) {
   if (!out) return PE_ERR_NULL;
   pe_handle* h = new pe_handle();
   h->branches = 3;
   h->sync_debug = 0;
   h->timing = 0;
+  h->side_streams = 0;
+  h->side[0] = h->side[1] = nullptr;
+  h->side_ev_next = 0;
+  for (int i = 0; i < 32; i++) h->side_ev[i] = nullptr;
   for (int i = 0; i < 6; i++) {
     if (hipEventCreateWithFlags(&h->ev[i], hipEventDisableTiming) != hipSuccess) {
       for (int j = 0; j < i; j++) (void)hipEventDestroy(h->ev[j]);
@@ -1313,6 +1355,10 @@ int pe_create(pe_handle** out) {
       return PE_ERR_HIP;
     }
   }
+  for (int i = 0; i < 2; i++)
+    if (hipStreamCreateWithFlags(&h->side[i], hipStreamNonBlocking) != hipSuccess) { pe_destroy(h); return PE_ERR_HIP; }
+  for (int i = 0; i < 32; i++)
+    if (hipEventCreateWithFlags(&h->side_ev[i], hipEventDisableTiming) != hipSuccess) { pe_destroy(h); return PE_ERR_HIP; }
   *out = h;
   return PE_OK;
 }
@@ -1321,6 +1367,8 @@ int pe_destroy(pe_handle* h) {
   for (int i = 0; i < 6; i++) (void)hipEventDestroy(h->ev[i]);
   for (auto& r : h->recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
   for (auto e : h->ev_pool) (void)hipEventDestroy(e);
+  for (int i = 0; i < 2; i++) if (h->side[i]) (void)hipStreamDestroy(h->side[i]);
+  for (int i = 0; i < 32; i++) if (h->side_ev[i]) (void)hipEventDestroy(h->side_ev[i]);
   delete h;
   return PE_OK;
 }
@@ -1329,6 +1377,7 @@ int pe_set_option(pe_handle* h, int option, int value) {
   if (option == PE_OPT_BRANCHES) { if (value < 1 || value > 3) return PE_ERR_ARG; h->branches = value; return PE_OK; }
   if (option == PE_OPT_SYNC_DEBUG) { h->sync_debug = value ? 1 : 0; return PE_OK; }
   if (option == PE_OPT_KERNEL_TIMING) { h->timing = value ? 1 : 0; return PE_OK; }
+  if (option == PE_OPT_SIDE_STREAMS) { h->side_streams = value ? 1 : 0; return PE_OK; }
   return PE_ERR_ARG;
 }
 int pe_check_dims(const pe_dims* d) {
