@@ -1355,10 +1355,6 @@ int pe_create(pe_handle** out) {
       return PE_ERR_HIP;
     }
   }
-  for (int i = 0; i < 2; i++)
-    if (hipStreamCreateWithFlags(&h->side[i], hipStreamNonBlocking) != hipSuccess) { pe_destroy(h); return PE_ERR_HIP; }
-  for (int i = 0; i < 32; i++)
-    if (hipEventCreateWithFlags(&h->side_ev[i], hipEventDisableTiming) != hipSuccess) { pe_destroy(h); return PE_ERR_HIP; }
   *out = h;
   return PE_OK;
 }
@@ -1377,7 +1373,18 @@ int pe_set_option(pe_handle* h, int option, int value) {
   if (option == PE_OPT_BRANCHES) { if (value < 1 || value > 3) return PE_ERR_ARG; h->branches = value; return PE_OK; }
   if (option == PE_OPT_SYNC_DEBUG) { h->sync_debug = value ? 1 : 0; return PE_OK; }
   if (option == PE_OPT_KERNEL_TIMING) { h->timing = value ? 1 : 0; return PE_OK; }
-  if (option == PE_OPT_SIDE_STREAMS) { h->side_streams = value ? 1 : 0; return PE_OK; }
+  if (option == PE_OPT_SIDE_STREAMS) {
+    // Created on first use only: every extra stream competes for the process's few hardware
+    // queues (4 by default), and two streams that share a queue serialise.
+    if (value && !h->side[0]) {
+      for (int i = 0; i < 2; i++)
+        if (hipStreamCreateWithFlags(&h->side[i], hipStreamNonBlocking) != hipSuccess) return PE_ERR_HIP;
+      for (int i = 0; i < 32; i++)
+        if (hipEventCreateWithFlags(&h->side_ev[i], hipEventDisableTiming) != hipSuccess) return PE_ERR_HIP;
+    }
+    h->side_streams = value ? 1 : 0;
+    return PE_OK;
+  }
   return PE_ERR_ARG;
 }
 int pe_check_dims(const pe_dims* d) {
