@@ -613,12 +613,20 @@ template <typename T> struct Runner {
       const double fl = 2.0 * Mz * d.c_z * H, by = 1.0 * Mz * d.c_z * sizeof(T) + 8.0 * Mz * H;
       if (lpr && lpr <= 32) {
         const int rpw = 64 / lpr;
-        int grid = (int)std::min<long long>((Mz + 4 * rpw - 1) / (4 * rpw), 1024);   // long loops amortise the weight preload
-#define PE_LNB_FWD(L) PE_LAUNCH("ln_bias_fwd", fl, by, st, (ln_bias_fwd_fast_kernel<T, L>), dim3(grid), dim3(256), 0, bias_src, P(bias_ln_g), P(bias_ln_b), P(p.w_bias), c.bias, c.biasT, c.zstats, d.r, H, d.ln_eps, g.bias_transposed)
+        int grid = (int)std::min<long long>((Mz + 4 * rpw - 1) / (4 * rpw), 8192);
+        // direct (row-order) orientation first, the other one by a tiled transpose
+        float* direct = g.bias_transposed ? c.biasT : c.bias;
+        float* other = g.bias_transposed ? c.bias : c.biasT;
+        const float dscale = g.bias_transposed ? 1.4426950408889634f : 1.0f;
+        const float oscale = g.bias_transposed ? 0.6931471805599453f : 1.4426950408889634f;
+#define PE_LNB_FWD(L, HH) PE_LAUNCH("ln_bias_fwd", fl, by, st, (ln_bias_fwd_fast_kernel<T, L, HH>), dim3(grid), dim3(256), 0, bias_src, P(bias_ln_g), P(bias_ln_b), P(p.w_bias), direct, dscale, c.zstats, d.r, H, d.ln_eps)
+#define PE_LNB_FWD_H(L) do { if (H <= 4) PE_LNB_FWD(L, 4); else PE_LNB_FWD(L, 8); } while (0)
         switch (lpr) {
-          case 2: PE_LNB_FWD(2); break; case 4: PE_LNB_FWD(4); break; case 8: PE_LNB_FWD(8); break;
-          case 16: PE_LNB_FWD(16); break; default: PE_LNB_FWD(32); break;
+          case 2: PE_LNB_FWD_H(2); break; case 4: PE_LNB_FWD_H(4); break; case 8: PE_LNB_FWD_H(8); break;
+          case 16: PE_LNB_FWD_H(16); break; default: PE_LNB_FWD_H(32); break;
         }
+        PE_LAUNCH("bias_transpose", 0, 8.0 * H * Mz, st, bias_transpose_kernel, dim3((d.r + 31) / 32, (d.r + 31) / 32, H), dim3(256), 0, direct, other, d.r, oscale);
+#undef PE_LNB_FWD_H
 #undef PE_LNB_FWD
       } else {
         int grid = (int)std::min<long long>((Mz + 3) / 4, 4096);
@@ -758,8 +766,12 @@ template <typename T> struct Runner {
     }
     if (!dry && !err) {
       size_t lds = (size_t)64 * (ct + 1) * sizeof(float);
-      PE_LAUNCH("ln_cmajor_fwd", 0, 2.0 * Mz * ct * sizeof(T), st, ln_cmajor_fwd_kernel<T>, dim3((unsigned)((Mz + 63) / 64)), dim3(256), lds, c.x_t,
-                         P(p.ln_out_g), P(p.ln_out_b), c.xhat, c.stats_out, Mz, ct, d.ln_eps);
+      if (Mz % 4 == 0 && ct % 8 == 0)
+        PE_LAUNCH("ln_cmajor_fwd", 0, 2.0 * Mz * ct * sizeof(T), st, ln_cmajor_fwd_fast_kernel<T>, dim3((unsigned)((Mz + 63) / 64)), dim3(256), lds, c.x_t,
+                  P(p.ln_out_g), P(p.ln_out_b), c.xhat, c.stats_out, Mz, ct, d.ln_eps);
+      else
+        PE_LAUNCH("ln_cmajor_fwd", 0, 2.0 * Mz * ct * sizeof(T), st, ln_cmajor_fwd_kernel<T>, dim3((unsigned)((Mz + 63) / 64)), dim3(256), lds, c.x_t,
+                  P(p.ln_out_g), P(p.ln_out_b), c.xhat, c.stats_out, Mz, ct, d.ln_eps);
     }
     {
       EpiGeneric<T> e = epi_plain<T>(c.g, cz);
@@ -923,14 +935,20 @@ template <typename T> struct Runner {
       int grid = (int)std::min<long long>((Mz + 4 * rpw - 1) / (4 * rpw), 1024);
       int plen = 2 * cz + cz * H;
       float* part = (float*)ar.alloc((size_t)grid * plen * sizeof(float));
+      // dbias is [h][key][query]; bring it to pair-row order when the bias rows are the queries
+      const bool flip = lpr && !gm.bias_transposed;
+      float* dbias_rows = flip ? (float*)ar.alloc((size_t)H * Mz * sizeof(float)) : dbias;
       if (!dry && !err) {
         const double fl = 4.0 * Mz * cz * H, by = (bias_gin ? 3.0 : 2.0) * Mz * cz * sizeof(T) + 4.0 * Mz * H;
         if (lpr) {
-#define PE_LNB_BWD(L) PE_LAUNCH("ln_bias_bwd", fl, by, st, (ln_bias_bwd_fast_kernel<T, L>), dim3(grid), dim3(256), 0, dbias, bias_src, c.zstats, P(bias_ln_g), P(bias_ln_b), P(p.w_bias), bias_gin, bias_gout, part, d.r, H, gm.bias_transposed ^ 1)
+          if (flip) PE_LAUNCH("bias_transpose", 0, 8.0 * H * Mz, st, bias_transpose_kernel, dim3((d.r + 31) / 32, (d.r + 31) / 32, H), dim3(256), 0, dbias, dbias_rows, d.r, 1.0f);
+#define PE_LNB_BWD(L, HH) PE_LAUNCH("ln_bias_bwd", fl, by, st, (ln_bias_bwd_fast_kernel<T, L, HH>), dim3(grid), dim3(256), 0, dbias_rows, bias_src, c.zstats, P(bias_ln_g), P(bias_ln_b), P(p.w_bias), bias_gin, bias_gout, part, d.r, H)
+#define PE_LNB_BWD_H(L) do { if (H <= 4) PE_LNB_BWD(L, 4); else PE_LNB_BWD(L, 8); } while (0)
           switch (lpr) {
-            case 2: PE_LNB_BWD(2); break; case 4: PE_LNB_BWD(4); break; case 8: PE_LNB_BWD(8); break;
-            case 16: PE_LNB_BWD(16); break; default: PE_LNB_BWD(32); break;
+            case 2: PE_LNB_BWD_H(2); break; case 4: PE_LNB_BWD_H(4); break; case 8: PE_LNB_BWD_H(8); break;
+            case 16: PE_LNB_BWD_H(16); break; default: PE_LNB_BWD_H(32); break;
           }
+#undef PE_LNB_BWD_H
 #undef PE_LNB_BWD
         } else {
           PE_LAUNCH("ln_bias_bwd", fl, by, st, ln_bias_bwd_kernel<T>, dim3(grid), dim3(256), 0, dbias, bias_src, c.zstats,
@@ -970,8 +988,12 @@ template <typename T> struct Runner {
       float* part = (float*)ar.alloc((size_t)grid * 2 * ct * sizeof(float));
       if (!dry && !err) {
         size_t lds = (size_t)64 * (ct + 1) * sizeof(float);
-        PE_LAUNCH("ln_cmajor_bwd", 0, 3.0 * Mz * ct * sizeof(T), st, ln_cmajor_bwd_kernel<T>, dim3(grid), dim3(256), lds, dxh_o, c.x_t, c.stats_out,
-                           P(p.ln_out_g), dx_t, part, Mz, ct);
+        if (Mz % 4 == 0 && ct % 8 == 0)
+          PE_LAUNCH("ln_cmajor_bwd", 0, 3.0 * Mz * ct * sizeof(T), st, ln_cmajor_bwd_fast_kernel<T>, dim3(grid), dim3(256), lds, dxh_o, c.x_t, c.stats_out,
+                    P(p.ln_out_g), dx_t, part, Mz, ct);
+        else
+          PE_LAUNCH("ln_cmajor_bwd", 0, 3.0 * Mz * ct * sizeof(T), st, ln_cmajor_bwd_kernel<T>, dim3(grid), dim3(256), lds, dxh_o, c.x_t, c.stats_out,
+                    P(p.ln_out_g), dx_t, part, Mz, ct);
         ReduceSeg sg[2] = {{0, ct, p.ln_out_g, 0}, {ct, ct, p.ln_out_b, 0}};
         reduce_to(st, part, grid, 2LL * ct, 1, 2 * ct, 2, sg);
       }

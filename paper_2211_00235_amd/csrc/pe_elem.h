@@ -373,6 +373,146 @@ __global__ __launch_bounds__(256) void ln_cmajor_bwd_kernel(const T* dy, const T
   }
 }
 
+// Fast forms for M % 4 == 0 and C % 8 == 0: thread (pl = tid%16, cl = tid/16) moves 4
+// consecutive positions of channel cl, cl+16, .. per load (8 / 16 bytes per lane, 128 / 256
+// bytes per 16 lanes); the channel-last side moves 8 channels per lane.
+template <typename T>
+__global__ __launch_bounds__(256) void ln_cmajor_fwd_fast_kernel(const T* xt, const float* gamma, const float* beta,
+                                                                 T* y, float* stats, long long M, int C, float eps) {
+  extern __shared__ float tile[];   // [64][C+1]
+  __shared__ float rs[16][65], smu[64], srstd[64];
+  const int pl = threadIdx.x & 15, cl = threadIdx.x >> 4, ld = C + 1;
+  const long long m0 = (long long)blockIdx.x * 64, mb = m0 + 4 * pl;
+  const bool ok = mb < M;
+  float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  for (int c = cl; c < C; c += 16) {
+    float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (ok) load4<T>(xt + (long long)c * M + mb, v);
+#pragma unroll
+    for (int k = 0; k < 4; k++) { tile[(4 * pl + k) * ld + c] = v[k]; s[k] += v[k]; }
+  }
+#pragma unroll
+  for (int k = 0; k < 4; k++) rs[cl][4 * pl + k] = s[k];
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    float t = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 16; k++) t += rs[k][threadIdx.x];
+    smu[threadIdx.x] = t / C;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 4; k++) s[k] = 0.0f;
+  for (int c = cl; c < C; c += 16) {
+#pragma unroll
+    for (int k = 0; k < 4; k++) { float t = tile[(4 * pl + k) * ld + c] - smu[4 * pl + k]; s[k] += t * t; }
+  }
+#pragma unroll
+  for (int k = 0; k < 4; k++) rs[cl][4 * pl + k] = s[k];
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    float t = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 16; k++) t += rs[k][threadIdx.x];
+    float rstd = rsqrtf(t / C + eps);
+    srstd[threadIdx.x] = rstd;
+    long long m = m0 + threadIdx.x;
+    if (m < M) { stats[m * 2] = smu[threadIdx.x]; stats[m * 2 + 1] = rstd; }
+  }
+  __syncthreads();
+  const int C8 = C >> 3;
+  for (int idx = threadIdx.x; idx < 64 * C8; idx += 256) {
+    const int pp = idx / C8, c0 = (idx - pp * C8) * 8;
+    const long long mm = m0 + pp;
+    if (mm < M) {
+      const float mu = smu[pp], rstd = srstd[pp];
+      float o[8];
+#pragma unroll
+      for (int e = 0; e < 8; e++) o[e] = (tile[pp * ld + c0 + e] - mu) * rstd * gamma[c0 + e] + beta[c0 + e];
+      st8<T>(y + mm * C + c0, o);
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void ln_cmajor_bwd_fast_kernel(const T* dy, const T* xt, const float* stats,
+                                                                 const float* gamma, T* dxt, float* partial,
+                                                                 long long M, int C) {
+  extern __shared__ float tile[];   // dy tile [64][C+1]
+  __shared__ float r1[16][65], r2[16][65], t1[64], t2[64];
+  const int pl = threadIdx.x & 15, cl = threadIdx.x >> 4, ld = C + 1;
+  const long long m0 = (long long)blockIdx.x * 64, mb = m0 + 4 * pl;
+  const bool ok = mb < M;
+  const int C8 = C >> 3;
+  for (int idx = threadIdx.x; idx < 64 * C8; idx += 256) {
+    const int pp = idx / C8, c0 = (idx - pp * C8) * 8;
+    const long long mm = m0 + pp;
+    float v[8];
+    if (mm < M) ld8<T>(dy + mm * C + c0, v);
+    else {
+#pragma unroll
+      for (int e = 0; e < 8; e++) v[e] = 0.0f;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; e++) tile[pp * ld + c0 + e] = v[e];
+  }
+  float mu[4], rstd[4];
+#pragma unroll
+  for (int k = 0; k < 4; k++) {
+    mu[k] = ok ? stats[(mb + k) * 2] : 0.0f;
+    rstd[k] = ok ? stats[(mb + k) * 2 + 1] : 0.0f;
+  }
+  __syncthreads();
+  float s1[4] = {0.0f, 0.0f, 0.0f, 0.0f}, s2[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  for (int c = cl; c < C; c += 16) {
+    float x[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (ok) load4<T>(xt + (long long)c * M + mb, x);
+    const float g = gamma[c];
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+      float xh = (x[k] - mu[k]) * rstd[k];
+      float dxh = tile[(4 * pl + k) * ld + c] * g;
+      s1[k] += dxh;
+      s2[k] += dxh * xh;
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < 4; k++) { r1[cl][4 * pl + k] = s1[k]; r2[cl][4 * pl + k] = s2[k]; }
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    float a = 0.0f, b = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 16; k++) { a += r1[k][threadIdx.x]; b += r2[k][threadIdx.x]; }
+    t1[threadIdx.x] = a / C;
+    t2[threadIdx.x] = b / C;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 4; k++) { s1[k] = t1[4 * pl + k]; s2[k] = t2[4 * pl + k]; }
+  for (int c = cl; c < C; c += 16) {
+    float x[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (ok) load4<T>(xt + (long long)c * M + mb, x);
+    const float g = gamma[c];
+    float o[4], a = 0.0f, b = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+      float xh = (x[k] - mu[k]) * rstd[k];
+      float dv = tile[(4 * pl + k) * ld + c];
+      o[k] = (dv * g - s1[k] - xh * s2[k]) * rstd[k];
+      a += dv * xh;
+      b += dv;
+    }
+    if (ok) store4<T>(dxt + (long long)c * M + mb, o);
+    // per-channel partials over the 64 positions: the 16 lanes sharing cl
+    a = group_sum<16>(a);
+    b = group_sum<16>(b);
+    if (pl == 0) {
+      partial[(long long)blockIdx.x * 2 * C + c] = a;
+      partial[(long long)blockIdx.x * 2 * C + C + c] = b;
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Pair-bias projection fused with its LayerNorm: bias[h][i][j] = (LN(z_ij) W)_h
 // (transposed: bias[h][j][i]); biasT holds the other orientation multiplied by log2(e),
@@ -497,21 +637,36 @@ __global__ __launch_bounds__(256) void ln_bias_bwd_kernel(const float* dbias, co
 }
 
 // Fast variants for C = 8 * LPR (LPR <= 32): 64 / LPR rows per wave, 8 channels per lane.
-template <typename T, int LPR>
+// w (and the per-lane slices of it) go through LDS: sw[sub] holds the 8 x HH weights of lane
+// group `sub`, rows padded by 4 floats so that the 16-byte reads of neighbouring lanes hit
+// different banks.  HH = 4 or 8 is the compile-time head count (H <= HH).
+template <int LPR, int HH>
+PE_DEV void bias_stage_w(const float* w, int H, float (*sw)[8 * HH + 4], int sub, float (&wv)[8][HH]) {
+  for (int idx = threadIdx.x; idx < 8 * LPR * HH; idx += 256) {
+    const int c = idx / HH, h = idx % HH;
+    sw[c >> 3][(c & 7) * HH + h] = (h < H) ? w[c * H + h] : 0.0f;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < 8; e++)
+#pragma unroll
+    for (int h = 0; h < HH; h++) wv[e][h] = sw[sub][e * HH + h];
+}
+
+template <typename T, int LPR, int HH>
 __global__ __launch_bounds__(256) void ln_bias_fwd_fast_kernel(const T* z, const float* gamma, const float* beta,
-                                                               const float* w, float* bias, float* biasT, float* stats,
-                                                               int r, int H, float eps, int transposed) {
+                                                               const float* w, float* direct, float direct_scale,
+                                                               float* stats, int r, int H, float eps) {
+  // writes direct[h][row] = (LN(z_row) W)_h * direct_scale in row order (coalesced); the other
+  // orientation is produced by bias_transpose_kernel
   constexpr int C = 8 * LPR, RPW = 64 / LPR;
+  __shared__ float sw[LPR][8 * HH + 4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane % LPR, rw = lane / LPR, c0 = sub * 8;
-  float gm[8], bt[8], wv[8][BIAS_MAXH];
+  float gm[8], bt[8], wv[8][HH];
 #pragma unroll
-  for (int e = 0; e < 8; e++) {
-    gm[e] = gamma[c0 + e];
-    bt[e] = beta[c0 + e];
-#pragma unroll
-    for (int h = 0; h < BIAS_MAXH; h++) wv[e][h] = (h < H) ? w[(c0 + e) * H + h] : 0.0f;
-  }
+  for (int e = 0; e < 8; e++) { gm[e] = gamma[c0 + e]; bt[e] = beta[c0 + e]; }
+  bias_stage_w<LPR, HH>(w, H, sw, sub, wv);
   const long long M = (long long)r * r;
   const long long stride = (long long)gridDim.x * 4 * RPW;
   for (long long row = ((long long)blockIdx.x * 4 + wave) * RPW + rw; row < M + rw; row += stride) {
@@ -533,52 +688,62 @@ __global__ __launch_bounds__(256) void ln_bias_fwd_fast_kernel(const T* z, const
     float y[8];
 #pragma unroll
     for (int e = 0; e < 8; e++) y[e] = (v[e] - mu) * rstd * gm[e] + bt[e];
-    const long long rr = ok ? row : 0;
-    const int i = rr / r, j = rr % r;
-    const long long o = transposed ? ((long long)j * r + i) : rr;
-    const long long oT = transposed ? rr : ((long long)j * r + i);
 #pragma unroll
-    for (int h = 0; h < BIAS_MAXH; h++) {
-      if (h < H) {
-        float t = 0.0f;
+    for (int h = 0; h < HH; h++) {
+      float t = 0.0f;
 #pragma unroll
-        for (int e = 0; e < 8; e++) t += y[e] * wv[e][h];
-        t = group_sum<LPR>(t);
-        if (ok && sub == 0) { bias[(long long)h * M + o] = t; biasT[(long long)h * M + oT] = t * 1.4426950408889634f; }
-      }
+      for (int e = 0; e < 8; e++) t += y[e] * wv[e][h];
+      t = group_sum<LPR>(t);
+      if (ok && sub == 0 && h < H) direct[(long long)h * M + row] = t * direct_scale;
     }
     if (ok && sub == 0) { stats[row * 2] = mu; stats[row * 2 + 1] = rstd; }
   }
 }
 
-template <typename T, int LPR>
-__global__ __launch_bounds__(256) void ln_bias_bwd_fast_kernel(const float* dbias, const T* z, const float* stats,
-                                                               const float* gamma, const float* beta, const float* w,
-                                                               const T* gin, T* gout, float* partial, int r, int H,
-                                                               int transposed) {
+// dst[h][j][i] = src[h][i][j] * f for H matrices of r x r (32 x 32 tiles through LDS)
+__global__ __launch_bounds__(256) void bias_transpose_kernel(const float* src, float* dst, int r, float f) {
+  __shared__ float tile[32][33];
+  const int h = blockIdx.z, i0 = blockIdx.y * 32, j0 = blockIdx.x * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const long long base = (long long)h * r * r;
+  for (int k = ty; k < 32; k += 8) {
+    int i = i0 + k, j = j0 + tx;
+    tile[k][tx] = (i < r && j < r) ? src[base + (long long)i * r + j] : 0.0f;
+  }
+  __syncthreads();
+  for (int k = ty; k < 32; k += 8) {
+    int j = j0 + k, i = i0 + tx;
+    if (i < r && j < r) dst[base + (long long)j * r + i] = tile[tx][k] * f;
+  }
+}
+
+template <typename T, int LPR, int HH>
+__global__ __launch_bounds__(256) void ln_bias_bwd_fast_kernel(const float* dbias /*[H][M], pair-row order*/, const T* z,
+                                                               const float* stats, const float* gamma,
+                                                               const float* beta, const float* w, const T* gin, T* gout,
+                                                               float* partial, int r, int H) {
   constexpr int C = 8 * LPR, RPW = 64 / LPR;
-  __shared__ float red[4][C * (2 + BIAS_MAXH)];
+  __shared__ float red[4][C * (2 + HH)];
+  __shared__ float sw[LPR][8 * HH + 4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane % LPR, rw = lane / LPR, c0 = sub * 8;
-  float gm[8], bt[8], wv[8][BIAS_MAXH], dgs[8], dbs[8], dws[8][BIAS_MAXH];
+  float gm[8], bt[8], wv[8][HH], dgs[8], dbs[8], dws[8][HH];
 #pragma unroll
   for (int e = 0; e < 8; e++) {
     gm[e] = gamma[c0 + e];
     bt[e] = beta[c0 + e];
     dgs[e] = 0.0f; dbs[e] = 0.0f;
 #pragma unroll
-    for (int h = 0; h < BIAS_MAXH; h++) { wv[e][h] = (h < H) ? w[(c0 + e) * H + h] : 0.0f; dws[e][h] = 0.0f; }
+    for (int h = 0; h < HH; h++) dws[e][h] = 0.0f;
   }
+  bias_stage_w<LPR, HH>(w, H, sw, sub, wv);
   const long long M = (long long)r * r;
   const long long stride = (long long)gridDim.x * 4 * RPW;
   for (long long row = ((long long)blockIdx.x * 4 + wave) * RPW + rw; row < M + rw; row += stride) {
     const bool ok = row < M;
-    const long long rr = ok ? row : 0;
-    const int i = rr / r, j = rr % r;
-    const long long o = transposed ? ((long long)j * r + i) : rr;
-    float db[BIAS_MAXH];
+    float db[HH];
 #pragma unroll
-    for (int h = 0; h < BIAS_MAXH; h++) db[h] = (ok && h < H) ? dbias[(long long)h * M + o] : 0.0f;
+    for (int h = 0; h < HH; h++) db[h] = (ok && h < H) ? dbias[(long long)h * M + row] : 0.0f;
     float v[8];
     float mu = 0.0f, rstd = 0.0f;
     if (ok) { ld8<T>(z + row * C + c0, v); mu = stats[row * 2]; rstd = stats[row * 2 + 1]; }
@@ -594,7 +759,7 @@ __global__ __launch_bounds__(256) void ln_bias_bwd_fast_kernel(const float* dbia
       float y = xh[e] * gm[e] + bt[e];
       float dy = 0.0f;
 #pragma unroll
-      for (int h = 0; h < BIAS_MAXH; h++) { dy += db[h] * wv[e][h]; dws[e][h] += y * db[h]; }
+      for (int h = 0; h < HH; h++) { dy += db[h] * wv[e][h]; dws[e][h] += y * db[h]; }
       dxh[e] = dy * gm[e];
       dgs[e] += dy * xh[e];
       dbs[e] += dy;
@@ -622,7 +787,7 @@ __global__ __launch_bounds__(256) void ln_bias_bwd_fast_kernel(const float* dbia
       dgs[e] += __shfl_xor(dgs[e], o, 64);
       dbs[e] += __shfl_xor(dbs[e], o, 64);
 #pragma unroll
-      for (int h = 0; h < BIAS_MAXH; h++) dws[e][h] += __shfl_xor(dws[e][h], o, 64);
+      for (int h = 0; h < HH; h++) dws[e][h] += __shfl_xor(dws[e][h], o, 64);
     }
   }
   if (rw == 0) {
@@ -631,14 +796,14 @@ __global__ __launch_bounds__(256) void ln_bias_bwd_fast_kernel(const float* dbia
       red[wave][c0 + e] = dgs[e];
       red[wave][C + c0 + e] = dbs[e];
 #pragma unroll
-      for (int h = 0; h < BIAS_MAXH; h++) red[wave][2 * C + (c0 + e) * BIAS_MAXH + h] = dws[e][h];
+      for (int h = 0; h < HH; h++) red[wave][2 * C + (c0 + e) * HH + h] = dws[e][h];
     }
   }
   __syncthreads();
   float* pp = partial + (long long)blockIdx.x * (2 * C + C * H);
   for (int t = threadIdx.x; t < 2 * C; t += 256) pp[t] = red[0][t] + red[1][t] + red[2][t] + red[3][t];
   for (int t = threadIdx.x; t < C * H; t += 256) {
-    int k = 2 * C + (t / H) * BIAS_MAXH + (t % H);
+    int k = 2 * C + (t / H) * HH + (t % H);
     pp[2 * C + t] = red[0][k] + red[1][k] + red[2][k] + red[3][k];
   }
 }
