@@ -44,6 +44,7 @@ static inline Operand op_trans(const void* p, long long ld, long long batch = 0)
 struct GemmShape {
   int M, N, K, batch;
   int k_chunk;  // > 0: split-K; batch index selects the k range [b*k_chunk, min(K,(b+1)*k_chunk))
+  int unit_n;   // block mapping: 0 = an XCD owns (batch, m-tile) units, 1 = (batch, n-tile) units (set by the launcher)
 };
 
 // 8 consecutive storage elements <-> 8 floats (one or two 16-byte accesses)
@@ -367,14 +368,18 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
   const int wm = wave >> 1, wn = wave & 1;
-  // XCD-aware mapping: workgroup w runs on XCD w % 8; all column tiles of one (batch, m-tile)
-  // unit go to the same XCD so that its L2 serves the shared A rows.
+  // XCD-aware mapping: workgroup w runs on XCD w % 8.  All column tiles of one (batch, m-tile)
+  // unit go to the same XCD so that its L2 serves the shared A rows; when there are too few
+  // such units to balance 8 XCDs the roles of m and n are swapped (unit_n).
   const int NTm = (sh.M + C::BM - 1) / C::BM, NTn = (sh.N + C::BN - 1) / C::BN;
   const int xcd = blockIdx.x & 7, jq = blockIdx.x >> 3;
-  const int unit = xcd + 8 * (jq / NTn);
-  if (unit >= NTm * sh.batch) return;
-  const int b = unit / NTm;
-  const int m0 = (unit % NTm) * C::BM, n0 = (jq % NTn) * C::BN;
+  const int NTu = sh.unit_n ? NTn : NTm, NTi = sh.unit_n ? NTm : NTn;
+  const int unit = xcd + 8 * (jq / NTi);
+  if (unit >= NTu * sh.batch) return;
+  const int b = unit / NTu;
+  const int tu = (unit % NTu) * C::BM, ti = (jq % NTi) * C::BM;
+  static_assert(C::BM == C::BN, "square block tile");
+  const int m0 = sh.unit_n ? ti : tu, n0 = sh.unit_n ? tu : ti;
 
   int kbeg = 0, kend = sh.K;
   const T* pa = (const T*)A.ptr;
@@ -543,7 +548,8 @@ static inline void launch_gemm_al(hipStream_t st, dim3 grid, const Operand& A, b
 // element-wise loader and the per-element epilogue: same tiles, same arithmetic, slower.
 template <typename T, class Epi>
 static inline int launch_gemm(hipStream_t st, const Operand& A, bool a_kc, const Operand& B, bool b_kc,
-                              const GemmShape& sh, const Epi& epi, bool* used_vec = nullptr) {
+                              const GemmShape& shape, const Epi& epi, bool* used_vec = nullptr) {
+  GemmShape sh = shape;
   if (sh.M <= 0 || sh.N <= 0 || sh.batch <= 0) return 0;
   if (a_kc ? A.k_stride != 1 : A.x_stride != 1) return -1;
   if (b_kc ? B.k_stride != 1 : B.x_stride != 1) return -1;
@@ -552,7 +558,11 @@ static inline int launch_gemm(hipStream_t st, const Operand& A, bool a_kc, const
   bool ve = al && epi.vec_ok(sh.N);
   if (used_vec) *used_vec = ve;
   const int NTm_ = (sh.M + 127) / 128, NTn_ = (sh.N + 127) / 128;
-  dim3 grid((unsigned)(8 * ((NTm_ * sh.batch + 7) / 8) * NTn_));
+  // units over m-tiles unless units over n-tiles leave fewer idle slots on the 8 XCDs
+  const long long um = (long long)NTm_ * sh.batch, un = (long long)NTn_ * sh.batch;
+  const long long gm_ = 8 * ((um + 7) / 8) * NTn_, gn_ = 8 * ((un + 7) / 8) * NTm_;
+  sh.unit_n = gn_ < gm_ ? 1 : 0;
+  dim3 grid((unsigned)(sh.unit_n ? gn_ : gm_));
   if (ve) launch_gemm_al<T, true, true, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);
   else if (al) launch_gemm_al<T, true, false, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);
   else launch_gemm_al<T, false, false, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);
