@@ -492,23 +492,6 @@ template <typename T> struct Runner {
       reduce_to(st, part, grid, 2LL * Cc, 1, 2 * Cc, 2, sg);
     }
   }
-  // column sums of y[M][N]; column n lives at (n / n_in) * n_outer + n % n_in (+ m * ld): plain
-  // matrices use n_in = N, head-major tensors n_in = head dim, n_outer = plane
-  void k_colsum(hipStream_t st, Arena& ar, const T* y, long long M, int N, long long ld, long long dst_off, int n_in = 0,
-                long long n_outer = 0) {
-    if (n_in == 0) n_in = N;
-    int nwg = (int)std::min<long long>(1024, (M + 31) / 32);
-    long long rpw = (M + nwg - 1) / nwg;
-    nwg = (int)((M + rpw - 1) / rpw);
-    float* part = (float*)ar.alloc((size_t)nwg * N * sizeof(float));
-    if (!dry && !err) {
-      fork_side(st);
-      st = side_of(st);
-      PE_LAUNCH("colsum", 0, 1.0 * M * N * sizeof(T), st, colsum_kernel<T>, dim3(nwg), dim3(256), 0, y, M, N, ld, part, rpw, n_in, n_outer);
-      ReduceSeg sg[1] = {{0, N, dst_off, 0}};
-      reduce_to(st, part, nwg, N, 1, N, 1, sg);
-    }
-  }
   void gemm(hipStream_t st, const Operand& A, bool akc, const Operand& B, bool bkc, int M, int N, int K, int batch,
             const EpiGeneric<T>& e, const char* what, Arena* split_arena = nullptr) {
     // A grid too small to fill the chip with a long contraction: split K, fp32 partials,
@@ -549,8 +532,9 @@ template <typename T> struct Runner {
     check(what);
   }
   // dW[rows][cols] += sum_k X(row,k) * Y(col,k), K huge: split-K partials + ordered reduce into dparams
+  // ncs > 0: additionally dparams[cs[i].dst_off + j] += sum_k Y(cs[i].n_begin + j, k) (bias gradients)
   void gemm_dw(hipStream_t st, Arena& ar, const Operand& X, bool xkc, const Operand& Y, bool ykc, int rows, int cols,
-               long long K, int nseg, const ReduceSeg* segs, const char* what) {
+               long long K, int nseg, const ReduceSeg* segs, const char* what, int ncs = 0, const ReduceSeg* cs = nullptr) {
     int tiles = ((rows + 127) / 128) * ((cols + 127) / 128);
     int want = std::max(1, 256 / tiles);
     const int BK = GemmCfg<T>::BK;
@@ -558,11 +542,12 @@ template <typename T> struct Runner {
     kc = (kc + BK - 1) / BK * BK;
     int nsplit = (int)((K + kc - 1) / kc);
     float* part = (float*)ar.alloc((size_t)nsplit * rows * cols * sizeof(float));
+    float* cs_part = ncs ? (float*)ar.alloc((size_t)nsplit * cols * sizeof(float)) : nullptr;
     if (!dry && !err) {
       fork_side(st);
       st = side_of(st);
       GemmShape sh{rows, cols, (int)K, nsplit, (int)kc};
-      EpiPartial ep{part, (long long)rows * cols, cols};
+      EpiPartial ep{part, (long long)rows * cols, cols, cs_part};
       prof_begin(st);
       bool al = false;
       int rc = launch_gemm<T, EpiPartial>(st, X, xkc, Y, ykc, sh, ep, &al);
@@ -572,6 +557,7 @@ template <typename T> struct Runner {
       if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = std::string("gemm_dw operand alignment: ") + what; }
       else check(what);
       reduce_to(st, part, nsplit, (long long)rows * cols, rows, cols, nseg, segs);
+      if (ncs) reduce_to(st, cs_part, nsplit, cols, 1, cols, ncs, cs);
     }
   }
 
@@ -705,9 +691,8 @@ template <typename T> struct Runner {
     float* dO = (float*)ar.alloc((size_t)d.r * HD * sizeof(float));
     float* dqbar = (float*)ar.alloc((size_t)d.r * HD * sizeof(float));
     T* dxh = (T*)ar.alloc((size_t)Mm * Cc * sizeof(T));
-    k_colsum(st, ar, g, Mm, Cc, Cc, p.b_o);
-    { ReduceSeg sg[1] = {{0, Cc, p.w_o, Cc}};
-      gemm_dw(st, ar, op_trans(c.og, HD), false, op_trans(g, Cc), false, HD, Cc, Mm, 1, sg, "gcol dWo"); }
+    { ReduceSeg sg[1] = {{0, Cc, p.w_o, Cc}}, cb = {0, Cc, p.b_o, 0};
+      gemm_dw(st, ar, op_trans(c.og, HD), false, op_trans(g, Cc), false, HD, Cc, Mm, 1, sg, "gcol dWo", 1, &cb); }
     { EpiGeneric<T> e = epi_plain<T>(dog, HD);
       gemm(st, op_plain(g, Cc), true, op_plain(W.gcol.wn_o, Cc), true, (int)Mm, HD, Cc, 1, e, "gcol dog"); }
     if (!dry && !err) {
@@ -718,9 +703,9 @@ template <typename T> struct Runner {
       PE_LAUNCH("gcol_attn_bwd", 12.0 * Mm * HD, 4.0 * Mm * 2 * dd * sizeof(T), st, gcol_attn_bwd_kernel<T>, dim3(d.r), dim3(256), 0, a);
       PE_LAUNCH("gcol_dq", 0, 1.0 * n * sizeof(T), st, gcol_dq_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, a);
     }
-    k_colsum(st, ar, dproj + HD + 2 * dd, Mm, HD, Wg, p.b_g);
     { ReduceSeg sg[4] = {{0, HD, p.w_q, HD}, {HD, dd, p.w_k, dd}, {HD + dd, dd, p.w_v, dd}, {HD + 2 * dd, HD, p.w_g, HD}};
-      gemm_dw(st, ar, op_trans(c.xhat, Cc), false, op_trans(dproj, Wg), false, Cc, Wg, Mm, 4, sg, "gcol dWproj"); }
+      ReduceSeg cb = {HD + 2 * dd, HD, p.b_g, 0};
+      gemm_dw(st, ar, op_trans(c.xhat, Cc), false, op_trans(dproj, Wg), false, Cc, Wg, Mm, 4, sg, "gcol dWproj", 1, &cb); }
     { EpiGeneric<T> e = epi_plain<T>(dxh, Cc);
       gemm(st, op_plain(dproj, Wg), true, op_plain(W.gcol.wn_proj, Wg), true, (int)Mm, Cc, Wg, 1, e, "gcol dxhat"); }
     k_ln_bwd(st, ar, dxh, x, c.stats, p.ln_g, p.ln_b, g, g, Mm, Cc);
@@ -861,15 +846,13 @@ template <typename T> struct Runner {
     const int nC = d.n_trans * Cc;
     T* dh = (T*)ar.alloc((size_t)M * nC * sizeof(T));
     T* dxh = (T*)ar.alloc((size_t)M * Cc * sizeof(T));
-    k_colsum(st, ar, g, M, Cc, Cc, p.b2);
-    { ReduceSeg sg[1] = {{0, Cc, p.w2, Cc}};
-      gemm_dw(st, ar, op_trans(c.h, nC), false, op_trans(g, Cc), false, nC, Cc, M, 1, sg, "trans dW2"); }
+    { ReduceSeg sg[1] = {{0, Cc, p.w2, Cc}}, cb = {0, Cc, p.b2, 0};
+      gemm_dw(st, ar, op_trans(c.h, nC), false, op_trans(g, Cc), false, nC, Cc, M, 1, sg, "trans dW2", 1, &cb); }
     { EpiGeneric<T> e = epi_plain<T>(dh, nC);
       e.relu_mask = c.h; e.ld_rm = nC;
       gemm(st, op_plain(g, Cc), true, op_plain(w.wn_2, Cc), true, (int)M, nC, Cc, 1, e, "trans dh"); }
-    k_colsum(st, ar, dh, M, nC, nC, p.b1);
-    { ReduceSeg sg[1] = {{0, nC, p.w1, nC}};
-      gemm_dw(st, ar, op_trans(c.xhat, Cc), false, op_trans(dh, nC), false, Cc, nC, M, 1, sg, "trans dW1"); }
+    { ReduceSeg sg[1] = {{0, nC, p.w1, nC}}, cb = {0, nC, p.b1, 0};
+      gemm_dw(st, ar, op_trans(c.xhat, Cc), false, op_trans(dh, nC), false, Cc, nC, M, 1, sg, "trans dW1", 1, &cb); }
     { EpiGeneric<T> e = epi_plain<T>(dxh, Cc);
       gemm(st, op_plain(dh, nC), true, op_plain(w.wn_1, nC), true, (int)M, Cc, nC, 1, e, "trans dxhat"); }
     k_ln_bwd(st, ar, dxh, x, c.stats, p.ln_g, p.ln_b, g, g, M, Cc);
@@ -894,9 +877,8 @@ template <typename T> struct Runner {
       dS = (T*)ar.alloc((size_t)gm.B * H * gm.L * gm.L * sizeof(T));
       dbias = (float*)ar.alloc((size_t)H * gm.L * gm.L * sizeof(float));
     }
-    k_colsum(st, ar, g, M, Cc, Cc, p.b_o);
-    { ReduceSeg sg[1] = {{0, Cc, p.w_o, Cc}};
-      gemm_dw(st, ar, op_heads_cols(c.og, gm, dh, M * dh), false, op_trans(g, Cc), false, HD, Cc, M, 1, sg, "attn dWo"); }
+    { ReduceSeg sg[1] = {{0, Cc, p.w_o, Cc}}, cb = {0, Cc, p.b_o, 0};
+      gemm_dw(st, ar, op_heads_cols(c.og, gm, dh, M * dh), false, op_trans(g, Cc), false, HD, Cc, M, 1, sg, "attn dWo", 1, &cb); }
     { EpiGeneric<T> e = epi_plain<T>(dog, HD);
       epi_heads(e, gm, dh, M * dh);
       gemm(st, op_plain(g, Cc), true, op_plain(w.wn_o, Cc), true, (int)M, HD, Cc, 1, e, "attn dog"); }
@@ -921,9 +903,9 @@ template <typename T> struct Runner {
                            (int)gm.B, hll);
       }
     }
-    k_colsum(st, ar, dqkvg + 3LL * H * M * dh, M, HD, dh, p.b_g, dh, M * dh);   // gate planes [H][M][d]
     { ReduceSeg sg[4] = {{0, HD, p.w_q, HD}, {HD, HD, p.w_k, HD}, {2 * HD, HD, p.w_v, HD}, {3 * HD, HD, p.w_g, HD}};
-      gemm_dw(st, ar, op_trans(c.xhat, Cc), false, op_heads_cols(dqkvg, gm, dh, M * dh), false, Cc, 4 * HD, M, 4, sg, "attn dWqkvg"); }
+      ReduceSeg cb = {3 * HD, HD, p.b_g, 0};
+      gemm_dw(st, ar, op_trans(c.xhat, Cc), false, op_heads_cols(dqkvg, gm, dh, M * dh), false, Cc, 4 * HD, M, 4, sg, "attn dWqkvg", 1, &cb); }
     { EpiGeneric<T> e = epi_plain<T>(dxh, Cc);
       gemm(st, op_heads_rows(dqkvg, gm, dh, M * dh), true, op_plain(w.wn_qkvg, 4 * HD), true, (int)M, Cc, 4 * HD, 1, e, "attn dxhat"); }
     k_ln_bwd(st, ar, dxh, x, c.stats, p.ln_g, p.ln_b, g, g, M, Cc);
@@ -978,9 +960,8 @@ template <typename T> struct Runner {
       long long n = Mz * cz;
       PE_LAUNCH("tm_out_bwd", 0, 5.0 * n * sizeof(T), st, tm_out_bwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, g, c.g, c.u, du, dgraw, n);
     }
-    k_colsum(st, ar, du, Mz, cz, cz, p.b_o);
-    { ReduceSeg sg[1] = {{0, cz, p.w_o, cz}};
-      gemm_dw(st, ar, op_trans(c.xhat, ct), false, op_trans(du, cz), false, ct, cz, Mz, 1, sg, "trimul dWo"); }
+    { ReduceSeg sg[1] = {{0, cz, p.w_o, cz}}, cb = {0, cz, p.b_o, 0};
+      gemm_dw(st, ar, op_trans(c.xhat, ct), false, op_trans(du, cz), false, ct, cz, Mz, 1, sg, "trimul dWo", 1, &cb); }
     { EpiGeneric<T> e = epi_plain<T>(dxh_o, ct);
       gemm(st, op_plain(du, cz), true, op_plain(w.wn_o, cz), true, (int)Mz, ct, cz, 1, e, "trimul dxhat_o"); }
     {  // LayerNorm (channel-major input) backward
@@ -1016,23 +997,11 @@ template <typename T> struct Runner {
       PE_LAUNCH("tm_gate_bwd", 0, 10.0 * n * sizeof(T), st, tm_gate_bwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c.proj_t, pair_mask,
                          da_t, db_t, dproj_t, ct, Mz);
     }
-    {  // bias gradients: row sums of the channel-major projection gradients (two stages)
-      const int nch = 16;
-      float* part = (float*)ar.alloc((size_t)nch * 4 * ct * sizeof(float));
-      if (!dry && !err) {
-        fork_side(st);
-        hipStream_t sst = side_of(st);
-        PE_LAUNCH("rowsum", 0, 4.0 * ct * Mz * sizeof(T), sst, rowsum_kernel<T>, dim3(4 * ct, nch), dim3(256), 0, dproj_t, Mz,
-                  part, 4 * ct);
-        ReduceSeg sg[4] = {{0, ct, p.b_ap, 0}, {ct, ct, p.b_ag, 0}, {2 * ct, ct, p.b_bp, 0}, {3 * ct, ct, p.b_bg, 0}};
-        reduce_to(st, part, nch, 4LL * ct, 1, 4 * ct, 4, sg);
-      }
-    }
-    k_colsum(st, ar, dgraw, Mz, cz, cz, p.b_g);
     { ReduceSeg sg[4] = {{0, ct, p.w_ap, ct}, {ct, ct, p.w_ag, ct}, {2 * ct, ct, p.w_bp, ct}, {3 * ct, ct, p.w_bg, ct}};
-      gemm_dw(st, ar, op_trans(c.zhat, cz), false, op_plain(dproj_t, Mz), true, cz, 4 * ct, Mz, 4, sg, "trimul dWp"); }
-    { ReduceSeg sg[1] = {{0, cz, p.w_g, cz}};
-      gemm_dw(st, ar, op_trans(c.zhat, cz), false, op_trans(dgraw, cz), false, cz, cz, Mz, 1, sg, "trimul dWg"); }
+      ReduceSeg cb[4] = {{0, ct, p.b_ap, 0}, {ct, ct, p.b_ag, 0}, {2 * ct, ct, p.b_bp, 0}, {3 * ct, ct, p.b_bg, 0}};
+      gemm_dw(st, ar, op_trans(c.zhat, cz), false, op_plain(dproj_t, Mz), true, cz, 4 * ct, Mz, 4, sg, "trimul dWp", 4, cb); }
+    { ReduceSeg sg[1] = {{0, cz, p.w_g, cz}}, cb = {0, cz, p.b_g, 0};
+      gemm_dw(st, ar, op_trans(c.zhat, cz), false, op_trans(dgraw, cz), false, cz, cz, Mz, 1, sg, "trimul dWg", 1, &cb); }
     { EpiGeneric<T> e = epi_plain<T>(dzh, cz);
       gemm(st, op_trans(dproj_t, Mz), false, op_plain(w.wn_p, 4 * ct), true, (int)Mz, cz, 4 * ct, 1, e, "trimul dzhat p"); }
     { EpiGeneric<T> e = epi_plain<T>(dzh, cz);
@@ -1053,14 +1022,13 @@ template <typename T> struct Runner {
       T* dOs = (T*)am.alloc((size_t)Wd * Wd * sizeof(T));
       T* dab = (T*)am.alloc((size_t)2 * Mm * co * sizeof(T));
       T* dmh = (T*)am.alloc((size_t)Mm * cm * sizeof(T));
-      k_colsum(sm, am, d_pair_out, Mz, cz, cz, PL.opm.b_o);
       {
         Operand X;   // rows (p,q), contraction (i,j) over O[(i,p),(j,q)]
         X.ptr = C.opm.O; X.batch_stride = 0;
         X.x_in = co; X.x_outer = Wd; X.x_stride = 1;
         X.k_in = r; X.k_outer = (long long)co * Wd; X.k_stride = co;
-        ReduceSeg sg[1] = {{0, cz, PL.opm.w_o, cz}};
-        gemm_dw(sm, am, X, false, op_trans(d_pair_out, cz), false, co * co, cz, Mz, 1, sg, "opm dWo");
+        ReduceSeg sg[1] = {{0, cz, PL.opm.w_o, cz}}, cb = {0, cz, PL.opm.b_o, 0};
+        gemm_dw(sm, am, X, false, op_trans(d_pair_out, cz), false, co * co, cz, Mz, 1, sg, "opm dWo", 1, &cb);
       }
       {
         EpiGeneric<T> e = epi_plain<T>(dOs, Wd);
@@ -1077,15 +1045,14 @@ template <typename T> struct Runner {
         e2.out = dab + Mm * co;
         gemm(sm, op_plain(C.opm.a, Wd), true, op_trans(dOs, Wd), false, d.s, (int)Wd, (int)Wd, 1, e2, "opm db", &am);
       }
-      k_colsum(sm, am, dab, Mm, co, co, PL.opm.b_a);
-      k_colsum(sm, am, dab + Mm * co, Mm, co, co, PL.opm.b_b);
       {
         Operand Y;   // rows n = (which, c), contraction over MSA positions
         Y.ptr = dab; Y.batch_stride = 0;
         Y.x_in = co; Y.x_outer = Mm * co; Y.x_stride = 1;
         Y.k_in = 1 << 30; Y.k_outer = 0; Y.k_stride = co;
         ReduceSeg sg[2] = {{0, co, PL.opm.w_a, co}, {co, co, PL.opm.w_b, co}};
-        gemm_dw(sm, am, op_trans(C.opm.mhat, cm), false, Y, false, cm, 2 * co, Mm, 2, sg, "opm dWab");
+        ReduceSeg cb[2] = {{0, co, PL.opm.b_a, 0}, {co, co, PL.opm.b_b, 0}};
+        gemm_dw(sm, am, op_trans(C.opm.mhat, cm), false, Y, false, cm, 2 * co, Mm, 2, sg, "opm dWab", 2, cb);
       }
       {
         Operand A;   // [Mm][2co] view of the two gradient halves

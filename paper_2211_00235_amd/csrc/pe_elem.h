@@ -863,73 +863,6 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceBatch rb) {
   }
 }
 
-// column sums of a channel-last tensor y[M][N] (row stride ld): partial[wg][N].
-// Thread = (column group of 4, row lane); 8/16-byte loads, LDS reduction over row lanes.
-template <typename T>
-__global__ __launch_bounds__(256) void colsum_kernel(const T* y, long long M, int N, long long ld, float* partial,
-                                                     long long rows_per_wg, int n_in, long long n_outer) {
-  __shared__ float red[256][4];
-  const long long r0 = (long long)blockIdx.x * rows_per_wg;
-  const long long r1 = r0 + rows_per_wg < M ? r0 + rows_per_wg : M;
-  const int ncg = N / 4;
-  const int tid = threadIdx.x;
-  if (ncg >= 256) {
-    for (int cg = tid; cg < ncg; cg += 256) {
-      float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-      for (long long m = r0; m < r1; m++) {
-        float v[4];
-        load4<T>(y + m * ld + (long long)((cg * 4) / n_in) * n_outer + (cg * 4) % n_in, v);
-        s[0] += v[0]; s[1] += v[1]; s[2] += v[2]; s[3] += v[3];
-      }
-      store4<float>(partial + (long long)blockIdx.x * N + cg * 4, s);
-    }
-    return;
-  }
-  const int RL = 256 / ncg;
-  const int cg = tid % ncg, rl = tid / ncg;
-  float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-  const long long coff = (long long)((cg * 4) / n_in) * n_outer + (cg * 4) % n_in;
-  if (rl < RL)
-    for (long long m = r0 + rl; m < r1; m += RL) {
-      float v[4];
-      load4<T>(y + m * ld + coff, v);
-      s[0] += v[0]; s[1] += v[1]; s[2] += v[2]; s[3] += v[3];
-    }
-  red[tid][0] = s[0]; red[tid][1] = s[1]; red[tid][2] = s[2]; red[tid][3] = s[3];
-  __syncthreads();
-  if (rl == 0) {
-    for (int k = 1; k < RL; k++) {
-      s[0] += red[k * ncg + cg][0]; s[1] += red[k * ncg + cg][1];
-      s[2] += red[k * ncg + cg][2]; s[3] += red[k * ncg + cg][3];
-    }
-    store4<float>(partial + (long long)blockIdx.x * N + cg * 4, s);
-  }
-}
-
-// row sums of a channel-major tensor yt[rows][M]: partial[chunk][row] (grid = rows x chunks)
-template <typename T>
-__global__ __launch_bounds__(256) void rowsum_kernel(const T* yt, long long M, float* partial, int nrows) {
-  __shared__ float red[4];
-  const long long per = ((M + gridDim.y - 1) / gridDim.y + 3) / 4 * 4;
-  const long long m0 = (long long)blockIdx.y * per;
-  const long long m1 = m0 + per < M ? m0 + per : M;
-  const T* p = yt + (long long)blockIdx.x * M;
-  float s = 0.0f;
-  if ((M & 3) == 0) {
-    for (long long m = m0 + threadIdx.x * 4; m < m1; m += 1024) {
-      float v[4];
-      load4<T>(p + m, v);
-      s += v[0] + v[1] + v[2] + v[3];
-    }
-  } else {
-    for (long long m = m0 + threadIdx.x; m < m1; m += 256) s += to_f(p[m]);
-  }
-  s = wave_sum(s);
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
-  __syncthreads();
-  if (threadIdx.x == 0) partial[(long long)blockIdx.y * nrows + blockIdx.x] = red[0] + red[1] + red[2] + red[3];
-}
-
 // ---------------------------------------------------------------------------
 // Parameter preparation: dst[r*ld_r + c*ld_c] = T(src[r*cols + c])
 // ---------------------------------------------------------------------------
@@ -997,8 +930,16 @@ __global__ void opm_norm_kernel(const float* mask, float* inv_norm, int s, int r
   long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (long long)r * r) return;
   int i = idx / r, j = idx % r;
-  float acc = 0.0f;
-  for (int t = 0; t < s; t++) acc += mask[(long long)t * r + i] * mask[(long long)t * r + j];
+  float acc = 0.0f;   // 0/1 products: any summation order gives the same (exact) count
+  int t = 0;
+  for (; t + 8 <= s; t += 8) {
+    float a[8], b[8];
+#pragma unroll
+    for (int u = 0; u < 8; u++) { a[u] = mask[(long long)(t + u) * r + i]; b[u] = mask[(long long)(t + u) * r + j]; }
+#pragma unroll
+    for (int u = 0; u < 8; u++) acc += a[u] * b[u];
+  }
+  for (; t < s; t++) acc += mask[(long long)t * r + i] * mask[(long long)t * r + j];
   inv_norm[idx] = 1.0f / (eps + acc);
 }
 

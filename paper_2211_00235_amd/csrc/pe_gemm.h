@@ -78,6 +78,7 @@ template <> PE_DEV void store8<float>(float* p, const float (&v)[8]) {
 // Epilogues
 // ---------------------------------------------------------------------------
 template <typename T> struct EpiGeneric {
+  static constexpr bool HAS_COLSUM = false;
   T* out; long long out_batch;
   int om_in; long long om_outer, om_stride;
   int on_in; long long on_outer, on_stride;
@@ -209,7 +210,9 @@ template <typename T> static inline EpiGeneric<T> epi_plain(void* out, long long
 
 // fp32 partial sums of a split-K GEMM: part[b][m][n]
 struct EpiPartial {
+  static constexpr bool HAS_COLSUM = true;
   float* out; long long mn; int ldn;
+  float* colsum;   // nullable: [batch][N] sums over k of the B operand (bias gradients ride on the dW GEMM)
   struct Row { long long o; };
   struct Col { long long o; };
   PE_DEV Row row(int b, int m) const { return Row{(long long)b * mn + (long long)m * ldn}; }
@@ -399,6 +402,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
     for (int j = 0; j < 2; j++)
 #pragma unroll
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.0f;
+  // column sums of B: for every (batch, n-tile) one of the m-tile workgroups adds up its B tiles
+  bool do_cs = false;
+  float cs = 0.0f;
+  if constexpr (Epi::HAS_COLSUM) do_cs = epi.colsum != nullptr && tid < C::BN && (m0 / C::BM) == (n0 / C::BN + b) % NTm;
 
   V ra[4], rb[4];
   RowAddr<T, A_KC> rowa;
@@ -418,6 +425,16 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
       gemm_load_tile<T, A_KC, AL>(ra, pa, A, rowa, sh.M, k0 + C::BK, kend, tid);
       gemm_load_tile<T, B_KC, AL>(rb, pb, B, rowb, sh.N, k0 + C::BK, kend, tid);
     }
+    if constexpr (Epi::HAS_COLSUM) {
+      if (do_cs) {
+#pragma unroll
+        for (int ch = 0; ch < C::BK / C::VEC; ch++) {
+          V v = *reinterpret_cast<const V*>(lds_b + C::off(tid, ch, 0));
+#pragma unroll
+          for (int e = 0; e < C::VEC; e++) cs += to_f(v[e]);
+        }
+      }
+    }
 #pragma unroll
     for (int kk = 0; kk < C::BK / MM::KSTEP; kk++) {
       typename MM::frag af[2], bf[2];
@@ -434,6 +451,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
     }
   }
 
+  if constexpr (Epi::HAS_COLSUM) {
+    if (do_cs && n0 + tid < sh.N) epi.colsum[(long long)b * sh.N + n0 + tid] = cs;
+  }
   if (VE) {
     // Coalesced epilogue: the fp32 tile goes through LDS 64 rows at a time, then every thread
     // handles 8 consecutive columns of one row (16-byte loads / stores of every epilogue operand).
