@@ -443,6 +443,9 @@ template <typename T> struct Runner {
     ra.dst = dparams;
     long long total = (long long)rows * cols;
     ra.ylanes = nsplit >= 256 ? 64 : (nsplit >= 64 ? 16 : (nsplit >= 16 && total < 65536 ? 4 : 1));
+    bool v4 = total >= 4096 && cols % 4 == 0 && stride % 4 == 0 && ((uintptr_t)part) % 16 == 0;
+    for (int i = 0; i < nseg; i++) v4 = v4 && segs[i].n_begin % 4 == 0 && segs[i].n_count % 4 == 0;
+    ra.vec = v4 ? 4 : 1;
     pending.push_back(ra);
     (void)st;
   }
@@ -459,7 +462,7 @@ template <typename T> struct Runner {
         rb.a[k] = pending[i + (k < rb.n ? k : 0)];
         if (k < rb.n) {
           long long total = (long long)rb.a[k].rows * rb.a[k].cols;
-          int X = 256 / rb.a[k].ylanes;
+          int X = 256 / rb.a[k].ylanes * rb.a[k].vec;
           maxblocks = std::max(maxblocks, (total + X - 1) / X);
           bytes += 4.0 * total * (rb.a[k].nsplit + 2);
         }

@@ -819,6 +819,7 @@ struct ReduceArgs {
   int nseg; ReduceSeg seg[5];
   float* dst;
   int ylanes;
+  int vec;   // 1 or 4 outputs per thread
 };
 // 256 threads = X outputs x Y split lanes (Y = a.ylanes in {1, 4, 16, 64}, X = 256 / Y); fixed
 // summation order (deterministic).  Up to REDUCE_BATCH independent reductions per launch
@@ -826,38 +827,57 @@ struct ReduceArgs {
 constexpr int REDUCE_BATCH = 8;
 struct ReduceBatch { ReduceArgs a[REDUCE_BATCH]; int n; };
 __global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceBatch rb) {
-  __shared__ float red[256];
+  __shared__ float red[256][4];
   const ReduceArgs& a = rb.a[blockIdx.y];
-  const int Y = a.ylanes, X = 256 / Y;
+  const int Y = a.ylanes, X = 256 / Y, V = a.vec;   // V = 4: every thread owns 4 consecutive outputs (16-byte loads)
   const long long total = (long long)a.rows * a.cols;
-  if ((long long)blockIdx.x * X >= total) return;
+  if ((long long)blockIdx.x * X * V >= total) return;
   const int x = threadIdx.x % X, y = threadIdx.x / X;
-  const long long idx = (long long)blockIdx.x * X + x;
-  float s = 0.0f;
+  const long long idx = ((long long)blockIdx.x * X + x) * V;
+  float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
   if (idx < total) {
-    // 8 independent loads in flight per thread; the sum order is still a fixed function of (nsplit, Y)
-    for (int k = y; k < a.nsplit; k += 8 * Y) {
-      float v[8];
+    // several independent loads in flight per thread; the sum order is a fixed function of (nsplit, Y, V)
+    if (V == 4) {
+      for (int k = y; k < a.nsplit; k += 4 * Y) {
+        f32x4 v[4];
 #pragma unroll
-      for (int u = 0; u < 8; u++) {
-        int kk = k + u * Y;
-        v[u] = (kk < a.nsplit) ? a.part[(long long)kk * a.stride + idx] : 0.0f;
+        for (int u = 0; u < 4; u++) {
+          int kk = k + u * Y;
+          if (kk < a.nsplit) v[u] = *reinterpret_cast<const f32x4*>(a.part + (long long)kk * a.stride + idx);
+          else v[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        }
+#pragma unroll
+        for (int e = 0; e < 4; e++) s[e] += (v[0][e] + v[1][e]) + (v[2][e] + v[3][e]);
       }
-      s += ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+    } else {
+      for (int k = y; k < a.nsplit; k += 8 * Y) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+          int kk = k + u * Y;
+          v[u] = (kk < a.nsplit) ? a.part[(long long)kk * a.stride + idx] : 0.0f;
+        }
+        s[0] += ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+      }
     }
   }
   if (Y > 1) {
-    red[threadIdx.x] = s;
+#pragma unroll
+    for (int e = 0; e < 4; e++) red[threadIdx.x][e] = s[e];
     __syncthreads();
     if (y != 0) return;
-    for (int k = 1; k < Y; k++) s += red[k * X + x];
+    for (int k = 1; k < Y; k++)
+#pragma unroll
+      for (int e = 0; e < 4; e++) s[e] += red[k * X + x][e];
   }
   if (idx >= total) return;
-  int m = idx / a.cols, n = idx % a.cols;
+  // a 4-group never straddles a row or a segment (the host checks the multiples of 4)
+  const int m = idx / a.cols, n = idx % a.cols;
   for (int q = 0; q < a.nseg; q++) {
     const ReduceSeg& g = a.seg[q];
     if (n >= g.n_begin && n < g.n_begin + g.n_count) {
-      a.dst[g.dst_off + (long long)m * g.dst_ld + (n - g.n_begin)] += s;
+      float* dst = a.dst + g.dst_off + (long long)m * g.dst_ld + (n - g.n_begin);
+      for (int e = 0; e < V; e++) dst[e] += s[e];
       break;
     }
   }
