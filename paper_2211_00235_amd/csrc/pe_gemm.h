@@ -77,6 +77,12 @@ template <> PE_DEV void store8<float>(float* p, const float (&v)[8]) {
 // ---------------------------------------------------------------------------
 // Epilogues
 // ---------------------------------------------------------------------------
+// Compile-time feature sets of the vector epilogue: a kernel instantiated with mask F keeps the
+// code (and the run-time checks) of the features in F only; EF_ALL is the fully general kernel.
+enum : int { EF_BIASN = 1, EF_BIASM = 2, EF_ACT = 4, EF_RELUMASK = 8, EF_AUX = 16, EF_MUL = 32, EF_ROWSCALE = 64,
+             EF_SCALE2D = 128, EF_RES = 256, EF_ACC = 512, EF_OM2 = 1024, EF_ON2 = 2048, EF_ALPHA = 4096,
+             EF_ALL = 8191 };
+
 template <typename T> struct EpiGeneric {
   static constexpr bool HAS_COLSUM = false;
   T* out; long long out_batch;
@@ -128,54 +134,88 @@ template <typename T> struct EpiGeneric {
     if (accumulate) v += to_f(out[o]);
     out[o] = from_f<T>(v);
   }
-  // 8 consecutive columns n..n+7 of row m at once (host checked vec_ok)
-  PE_DEV void vec8(int b, int m, int n, float (&v)[8]) const {
-    Row r = row(b, m);
-    Col c = col(n);
-    if (bias_n && n >= bn_begin) {
+  // Vector epilogue: 8 consecutive columns n..n+7 of row m at once (host checked vec_ok).  The
+  // column part (offset, bias values) is the same for every row a thread handles: ColV.
+  int features() const {
+    int f = 0;
+    if (bias_n) f |= EF_BIASN;
+    if (bias_m) f |= EF_BIASM;
+    if (act) f |= EF_ACT;
+    if (relu_mask) f |= EF_RELUMASK;
+    if (aux) f |= EF_AUX;
+    if (mul) f |= EF_MUL;
+    if (rowscale) f |= EF_ROWSCALE;
+    if (scale2d) f |= EF_SCALE2D;
+    if (res) f |= EF_RES;
+    if (accumulate) f |= EF_ACC;
+    if (om_in < (1 << 30)) f |= EF_OM2;
+    if (on_in < (1 << 30)) f |= EF_ON2;
+    if (alpha != 1.0f) f |= EF_ALPHA;
+    return f;
+  }
+  struct ColV { long long o; int s2; float bn[8]; };
+  template <int F> PE_DEV void colv(int n, ColV& c) const {
+    c.o = ((F & EF_ON2) && on_in < (1 << 30))
+              ? (long long)((unsigned)n / (unsigned)on_in) * on_outer + (long long)((unsigned)n % (unsigned)on_in) * on_stride
+              : (long long)n * on_stride;
+    c.s2 = ((F & EF_SCALE2D) && scale2d) ? n / s2_ndiv : 0;
+    const bool hb = (F & EF_BIASN) && bias_n && n >= bn_begin;
 #pragma unroll
-      for (int e = 0; e < 8; e++) v[e] = fmaf(v[e], alpha, bias_n[n + e]);
-    } else if (alpha != 1.0f) {
+    for (int e = 0; e < 8; e++) c.bn[e] = hb ? bias_n[n + e] : 0.0f;
+  }
+  template <int F> PE_DEV void vec8(int b, int m, int n, const ColV& c, float (&v)[8]) const {
+    long long ro = (long long)b * out_batch;
+    if ((F & EF_OM2) && om_in < (1 << 30))
+      ro += (long long)((unsigned)m / (unsigned)om_in) * om_outer + (long long)((unsigned)m % (unsigned)om_in) * om_stride;
+    else
+      ro += (long long)m * om_stride;
+    if ((F & EF_ALPHA) && alpha != 1.0f) {
 #pragma unroll
       for (int e = 0; e < 8; e++) v[e] *= alpha;
     }
-    if (bias_m) {
+    if (F & EF_BIASN) {
+#pragma unroll
+      for (int e = 0; e < 8; e++) v[e] += c.bn[e];
+    }
+    if ((F & EF_BIASM) && bias_m) {
       float bm = bias_m[m];
 #pragma unroll
       for (int e = 0; e < 8; e++) v[e] += bm;
     }
-    if (act == 1) {
+    if (F & EF_ACT) {
+      if (act == 1) {
 #pragma unroll
-      for (int e = 0; e < 8; e++) v[e] = fmaxf(v[e], 0.0f);
-    } else if (act == 2) {
+        for (int e = 0; e < 8; e++) v[e] = fmaxf(v[e], 0.0f);
+      } else if (act == 2) {
 #pragma unroll
-      for (int e = 0; e < 8; e++) v[e] = sigmoidf_(v[e]);
+        for (int e = 0; e < 8; e++) v[e] = sigmoidf_(v[e]);
+      }
     }
     float t[8];
-    if (relu_mask) {
+    if ((F & EF_RELUMASK) && relu_mask) {
       load8<T>(relu_mask + (long long)m * ld_rm + n, t);
 #pragma unroll
       for (int e = 0; e < 8; e++) v[e] = (t[e] > 0.0f) ? v[e] : 0.0f;
     }
-    if (aux) store8<T>(aux + (long long)m * ld_aux + n, v);
-    if (mul) {
+    if ((F & EF_AUX) && aux) store8<T>(aux + (long long)m * ld_aux + n, v);
+    if ((F & EF_MUL) && mul) {
       load8<T>(mul + (long long)m * ld_mul + n, t);
 #pragma unroll
       for (int e = 0; e < 8; e++) v[e] *= t[e];
     }
-    float sc = rowscale ? rowscale[m] : 1.0f;
-    if (scale2d) sc *= scale2d[r.s2 + c.s2];
-    if (rowscale || scale2d) {
+    if (F & (EF_ROWSCALE | EF_SCALE2D)) {
+      float sc = ((F & EF_ROWSCALE) && rowscale) ? rowscale[m] : 1.0f;
+      if ((F & EF_SCALE2D) && scale2d) sc *= scale2d[(long long)(m / s2_mdiv) * s2_ld + c.s2];
 #pragma unroll
       for (int e = 0; e < 8; e++) v[e] *= sc;
     }
-    if (res) {
+    if ((F & EF_RES) && res) {
       load8<T>(res + (long long)m * ld_res + n, t);
 #pragma unroll
       for (int e = 0; e < 8; e++) v[e] += t[e];
     }
-    T* po = out + r.o + c.o;
-    if (accumulate) {
+    T* po = out + ro + c.o;
+    if ((F & EF_ACC) && accumulate) {
       load8<T>(po, t);
 #pragma unroll
       for (int e = 0; e < 8; e++) v[e] += t[e];
@@ -218,7 +258,10 @@ struct EpiPartial {
   PE_DEV Row row(int b, int m) const { return Row{(long long)b * mn + (long long)m * ldn}; }
   PE_DEV Col col(int n) const { return Col{(long long)n}; }
   PE_DEV void operator()(int, int, const Row& r, const Col& c, float v) const { out[r.o + c.o] = v; }
-  PE_DEV void vec8(int b, int m, int n, float (&v)[8]) const {
+  struct ColV {};
+  int features() const { return 0; }
+  template <int F> PE_DEV void colv(int, ColV&) const {}
+  template <int F> PE_DEV void vec8(int b, int m, int n, const ColV&, float (&v)[8]) const {
     store8<float>(out + (long long)b * mn + (long long)m * ldn + n, v);
   }
   bool vec_ok(int N) const { return N % 8 == 0 && ldn % 8 == 0 && mn % 8 == 0 && ((uintptr_t)out) % 16 == 0; }
@@ -272,7 +315,8 @@ template <typename T, bool KC> struct RowAddr {
         ok[i] = xx < X;
         int xc = ok[i] ? xx : 0;
         a[i] = (op.x_in >= (1 << 30)) ? (long long)xc * op.x_stride
-                                      : (long long)(xc / op.x_in) * op.x_outer + (long long)(xc % op.x_in) * op.x_stride;
+                                      : (long long)((unsigned)xc / (unsigned)op.x_in) * op.x_outer +
+                                            (long long)((unsigned)xc % (unsigned)op.x_in) * op.x_stride;
       }
     } else {
       constexpr int XB = 128 / VEC;
@@ -280,13 +324,16 @@ template <typename T, bool KC> struct RowAddr {
       x[0] = xx;
       ok[0] = xx < X;
       int xc = ok[0] ? xx : 0;
-      a[0] = (op.x_in >= (1 << 30)) ? (long long)xc : (long long)(xc / op.x_in) * op.x_outer + (long long)(xc % op.x_in);
+      a[0] = (op.x_in >= (1 << 30)) ? (long long)xc
+                                    : (long long)((unsigned)xc / (unsigned)op.x_in) * op.x_outer +
+                                          (long long)((unsigned)xc % (unsigned)op.x_in);
     }
   }
 };
 PE_DEV long long gemm_kaddr(const Operand& op, int k) {
   return (op.k_in >= (1 << 30)) ? (long long)k * op.k_stride
-                                : (long long)(k / op.k_in) * op.k_outer + (long long)(k % op.k_in) * op.k_stride;
+                                : (long long)((unsigned)k / (unsigned)op.k_in) * op.k_outer +
+                                      (long long)((unsigned)k % (unsigned)op.k_in) * op.k_stride;
 }
 
 template <typename T, bool KC, bool AL>
@@ -359,7 +406,7 @@ PE_DEV void gemm_store_tile(const typename Vec16<T>::type (&regs)[4], T* lds, in
   }
 }
 
-template <typename T, bool A_KC, bool B_KC, bool AL, bool VE, class Epi>
+template <typename T, bool A_KC, bool B_KC, bool AL, bool VE, class Epi, int F = EF_ALL>
 __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmShape sh, Epi epi) {
   typedef GemmCfg<T> C;
   typedef Mma<T> MM;
@@ -460,6 +507,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
     constexpr int SS = C::BN + 4;
     static_assert(64 * SS * sizeof(float) <= (C::BM + C::BN) * C::LDSS * sizeof(T), "stage tile must fit");
     float* stage = reinterpret_cast<float*>(lds_all);
+    const int c8 = (tid & 15) * 8, n = n0 + c8;
+    typename Epi::ColV cv;
+    if (n < sh.N) epi.template colv<F>(n, cv);
 #pragma unroll
     for (int pass = 0; pass < 2; pass++) {
       __syncthreads();
@@ -475,16 +525,15 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
       __syncthreads();
 #pragma unroll
       for (int it = 0; it < 4; it++) {
-        int v = tid + it * 256;
-        int row = v >> 4, c8 = (v & 15) * 8;
-        int m = m0 + pass * 64 + row, n = n0 + c8;
+        const int row = (tid >> 4) + it * 16;
+        const int m = m0 + pass * 64 + row;
         if (m < sh.M && n < sh.N) {
           float vals[8];
           f32x4 lo = *reinterpret_cast<const f32x4*>(stage + row * SS + c8);
           f32x4 hi = *reinterpret_cast<const f32x4*>(stage + row * SS + c8 + 4);
 #pragma unroll
           for (int e = 0; e < 4; e++) { vals[e] = lo[e]; vals[4 + e] = hi[e]; }
-          epi.vec8(b, m, n, vals);
+          epi.template vec8<F>(b, m, n, cv, vals);
         }
       }
     }
@@ -527,7 +576,9 @@ __global__ __launch_bounds__(256) void gemm_finish_kernel(const float* part, int
 #pragma unroll
     for (int e = 0; e < 8; e++) acc[e] += t[e];
   }
-  epi.vec8(0, m, n, acc);
+  typename EpiGeneric<T>::ColV cv;
+  epi.template colv<EF_ALL>(n, cv);
+  epi.template vec8<EF_ALL>(0, m, n, cv, acc);
 }
 
 // ---------------------------------------------------------------------------
@@ -554,10 +605,35 @@ template <typename T> static inline bool gemm_operand_ok(const Operand& o, bool 
   return true;
 }
 
+// Feature sets with a kernel of their own (k-contiguous operands, vector epilogue): a launch takes
+// the first one that covers what its epilogue uses, else the general kernel.
+template <typename T, class Epi>
+static inline bool launch_gemm_spec(hipStream_t st, dim3 grid, const Operand& A, const Operand& B, const GemmShape& sh,
+                                    const Epi& epi) {
+  if constexpr (Epi::HAS_COLSUM) return false;   // split-K partials: one kernel
+  const int f = epi.features();
+  dim3 block(256);
+#define PE_GEMM_SPEC(S)                                                                                     \
+  if ((f & ~(S)) == 0) {                                                                                    \
+    hipLaunchKernelGGL((gemm_kernel<T, true, true, true, true, Epi, (S)>), grid, block, 0, st, A, B, sh, epi); \
+    return true;                                                                                            \
+  }
+  PE_GEMM_SPEC(0)
+  PE_GEMM_SPEC(EF_BIASN)
+  PE_GEMM_SPEC(EF_BIASN | EF_RES)
+  PE_GEMM_SPEC(EF_BIASN | EF_ACT)
+  PE_GEMM_SPEC(EF_RELUMASK)
+  PE_GEMM_SPEC(EF_OM2 | EF_ON2 | EF_BIASN)
+  PE_GEMM_SPEC(EF_ACC | EF_BIASM)
+#undef PE_GEMM_SPEC
+  return false;
+}
+
 template <typename T, bool AL, bool VE, class Epi>
 static inline void launch_gemm_al(hipStream_t st, dim3 grid, const Operand& A, bool a_kc, const Operand& B, bool b_kc,
                                   const GemmShape& sh, const Epi& epi) {
   dim3 block(256);
+  if (AL && VE && a_kc && b_kc && launch_gemm_spec<T, Epi>(st, grid, A, B, sh, epi)) return;
   if (a_kc && b_kc) hipLaunchKernelGGL((gemm_kernel<T, true, true, AL, VE, Epi>), grid, block, 0, st, A, B, sh, epi);
   else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_kernel<T, true, false, AL, VE, Epi>), grid, block, 0, st, A, B, sh, epi);
   else if (!a_kc && b_kc) hipLaunchKernelGGL((gemm_kernel<T, false, true, AL, VE, Epi>), grid, block, 0, st, A, B, sh, epi);
