@@ -502,40 +502,43 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
     if (do_cs && n0 + tid < sh.N) epi.colsum[(long long)b * sh.N + n0 + tid] = cs;
   }
   if (VE) {
-    // Coalesced epilogue: the fp32 tile goes through LDS 64 rows at a time, then every thread
-    // handles 8 consecutive columns of one row (16-byte loads / stores of every epilogue operand).
-    constexpr int SS = C::BN + 4;
-    static_assert(64 * SS * sizeof(float) <= (C::BM + C::BN) * C::LDSS * sizeof(T), "stage tile must fit");
-    float* stage = reinterpret_cast<float*>(lds_all);
-    const int c8 = (tid & 15) * 8, n = n0 + c8;
+    // Coalesced epilogue without workgroup barriers: every wave passes its own 64x64 accumulator
+    // tile through a private LDS region, 32 rows at a time, and then handles 8 consecutive
+    // columns of one row per lane (16-byte loads / stores of every epilogue operand).  LDS
+    // operations of one wave execute in order, so the wave only needs the compiler to keep
+    // the write and read phases apart.
+    constexpr int WS = 64 + 4;
+    static_assert(4 * 32 * WS * sizeof(float) <= (C::BM + C::BN) * C::LDSS * sizeof(T), "stage tiles must fit");
+    float* stage = reinterpret_cast<float*>(lds_all) + wave * 32 * WS;
+    const int c8 = (lane & 7) * 8, n = n0 + wn * 64 + c8;
     typename Epi::ColV cv;
     if (n < sh.N) epi.template colv<F>(n, cv);
+    __syncthreads();   // all waves are done with the operand tiles
 #pragma unroll
-    for (int pass = 0; pass < 2; pass++) {
-      __syncthreads();
-      if (wm == pass) {
+    for (int i = 0; i < 2; i++) {
 #pragma unroll
-        for (int i = 0; i < 2; i++)
+      for (int j = 0; j < 2; j++)
 #pragma unroll
-          for (int j = 0; j < 2; j++)
-#pragma unroll
-            for (int a = 0; a < 16; a++)
-              stage[(i * 32 + acc_row(g, a)) * SS + wn * 64 + j * 32 + l32] = acc[i][j][a];
-      }
-      __syncthreads();
+        for (int a = 0; a < 16; a++) stage[acc_row(g, a) * WS + j * 32 + l32] = acc[i][j][a];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
       for (int it = 0; it < 4; it++) {
-        const int row = (tid >> 4) + it * 16;
-        const int m = m0 + pass * 64 + row;
+        const int row = (lane >> 3) + it * 8;
+        const int m = m0 + wm * 64 + i * 32 + row;
         if (m < sh.M && n < sh.N) {
           float vals[8];
-          f32x4 lo = *reinterpret_cast<const f32x4*>(stage + row * SS + c8);
-          f32x4 hi = *reinterpret_cast<const f32x4*>(stage + row * SS + c8 + 4);
+          f32x4 lo = *reinterpret_cast<const f32x4*>(stage + row * WS + c8);
+          f32x4 hi = *reinterpret_cast<const f32x4*>(stage + row * WS + c8 + 4);
 #pragma unroll
           for (int e = 0; e < 4; e++) { vals[e] = lo[e]; vals[4 + e] = hi[e]; }
           epi.template vec8<F>(b, m, n, cv, vals);
         }
       }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
     return;
   }
