@@ -108,6 +108,9 @@ def main():
     ap.add_argument("--workload", default="af2_initial")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="also print the per-launch-label timing table to stderr")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run three 256 MiB device-to-device copies (known traffic: the scale of the "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters is read off them)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the one-GPU share of the path only (two HIP streams on one "
@@ -123,6 +126,14 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
+    if args.copy_calibration:
+        x = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
+        y = torch.empty_like(x)
+        for _ in range(3):
+            y.copy_(x)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_each_way": 256 << 20, "copies": 3}))
+        return
     if args.workload == "trunk":
         return bench_trunk(args, torch, pe)
     dims, mask, seed = dims_for(args.workload)

@@ -132,7 +132,7 @@ int pe_check_dims(const pe_dims* d);                                   /* PE_OK 
 long long pe_param_count(const pe_dims* d);                            /* fp32 elements / block */
 int pe_param_table(const pe_dims* d, pe_param_entry* out, int cap);    /* returns #entries      */
 int pe_ctx_table(const pe_dims* d, pe_ctx_entry* out, int cap);        /* returns #entries      */
-size_t pe_ctx_bytes(const pe_dims* d);                                 /* saved activations     */
+size_t pe_ctx_bytes(const pe_dims* d);                                 /* saved activations + prepared weights */
 /* Scratch needed by pe_block_fwd / pe_block_bwd.  with_ctx != 0 adds room for
  * an internal ctx (needed when ctx == NULL is passed to pe_block_bwd).       */
 size_t pe_workspace_bytes(const pe_dims* d, int with_ctx);
@@ -147,7 +147,9 @@ size_t pe_stack_workspace_bytes(int n_extra, const pe_dims* extra, int n_main, c
  *   params: fp32 flat buffer, pe_param_count elements, layout pe_param_table.
  *   msa_out, pair_out: outputs, must not alias any input.
  *   ctx: NULL, or pe_ctx_bytes bytes (256-byte aligned) that receive the
- *     activations saved for pe_block_bwd.
+ *     activations saved for pe_block_bwd and the storage-type (transposed and
+ *     plain) copies of the weights the kernels read.  pe_block_bwd with this
+ *     ctx uses those copies: params must be unchanged between the two calls.
  *   workspace: 256-byte aligned, >= pe_workspace_bytes(dims, ctx == NULL)
  *     bytes (without a caller ctx the intermediates live in the workspace).
  *   stream_msa, stream_pair: hipStream_t (NULL = default stream).            */

@@ -1091,11 +1091,14 @@ template <typename T> struct Runner {
 };
 
 // ---------------------------------------------------------------------------
-// Plans: workspace layout = [prepared weights | MSA arena | pair arena | internal ctx]
+// Plans: workspace layout = [MSA arena | pair arena | internal ctx]; a ctx (the caller's or the
+// internal one) = [saved activations | prepared weights], so that a backward pass that gets the
+// forward's ctx does not convert the parameters again
 // ---------------------------------------------------------------------------
 struct Plan {
   size_t prep_bytes, arena_m, arena_p, ctx_bytes;
-  size_t total(bool with_ctx) const { return prep_bytes + arena_m + arena_p + (with_ctx ? ctx_bytes : 0) + 1024; }
+  size_t ctx_total() const { return ctx_bytes + prep_bytes; }
+  size_t total(bool with_ctx) const { return arena_m + arena_p + (with_ctx ? ctx_total() : 0) + 1024; }
 };
 
 template <typename T> static Plan make_plan(const pe_dims& d) {
@@ -1127,10 +1130,11 @@ template <typename T> static void setup_runner(Runner<T>& R, pe_handle* h, const
   R.init(d);
   R.sm = sm;
   R.sp = sp;
-  R.carve_prep(ws);
-  R.am.base = ws + pl.prep_bytes;
-  R.ap.base = ws + pl.prep_bytes + pl.arena_m;
-  carve_ctx<T>(ctx ? ctx : ws + pl.prep_bytes + pl.arena_m + pl.arena_p, d, R.C, nullptr);
+  R.am.base = ws;
+  R.ap.base = ws + pl.arena_m;
+  char* cbase = ctx ? ctx : ws + pl.arena_m + pl.arena_p;
+  carve_ctx<T>(cbase, d, R.C, nullptr);
+  R.carve_prep(cbase + pl.ctx_bytes);
 }
 
 static bool hip_ok(pe_handle* h, hipError_t e, const char* what) {
@@ -1196,10 +1200,7 @@ static int block_bwd_impl(pe_handle* h, const pe_dims& d, const void* msa_in, co
     if (do_p) R.fwd_pair();
     if (do_m) R.fwd_msa(nullptr);
     // the outer-product projection is not needed for the backward pass
-  } else {
-    if (do_p) R.run_prep(false);
-    if (do_m) R.run_prep(true);
-  }
+  }   // else: the prepared weights are part of ctx
   T* dzb = (T*)R.am.alloc((size_t)R.Mz * d.c_z * sizeof(T));
   T* gz = (T*)R.ap.alloc((size_t)R.Mz * d.c_z * sizeof(T));
   if (do_p) R.bwd_pair((const T*)d_pair_out, gz);
@@ -1418,7 +1419,7 @@ int pe_ctx_table(const pe_dims* d, pe_ctx_entry* out, int cap) {
 }
 size_t pe_ctx_bytes(const pe_dims* d) {
   if (pe_check_dims(d)) return 0;
-  return plan_for(*d).ctx_bytes;
+  return plan_for(*d).ctx_total();
 }
 size_t pe_workspace_bytes(const pe_dims* d, int with_ctx) {
   if (pe_check_dims(d)) return 0;

@@ -890,13 +890,35 @@ struct PrepDesc { long long src_off, dst_off; int rows, cols; long long ld_r, ld
 constexpr int PREP_MAX = 32;
 struct PrepBatch { PrepDesc d[PREP_MAX]; int n; };
 template <typename T>
-__global__ void prep_params_kernel(const float* params, T* dst, PrepBatch pb) {
+__global__ __launch_bounds__(256) void prep_params_kernel(const float* params, T* dst, PrepBatch pb) {
+  // 32 x 32 tiles; a transposed destination (ld_r == 1) goes through LDS so that reads and
+  // writes both run along the contiguous index
+  __shared__ float tile[32][33];
   const PrepDesc& d = pb.d[blockIdx.y];
-  long long total = (long long)d.rows * d.cols;
-  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
-       idx += (long long)gridDim.x * blockDim.x) {
-    int r = idx / d.cols, c = idx % d.cols;
-    dst[d.dst_off + r * d.ld_r + c * d.ld_c] = from_f<T>(params[d.src_off + idx]);
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int ntr = (d.rows + 31) / 32, ntc = (d.cols + 31) / 32;
+  const bool transposed = d.ld_r == 1 && d.ld_c != 1;
+  const float* src = params + d.src_off;
+  T* out = dst + d.dst_off;
+  for (int t = blockIdx.x; t < ntr * ntc; t += gridDim.x) {
+    const int r0 = (t / ntc) * 32, c0 = (t % ntc) * 32;
+    if (transposed) {
+      for (int k = ty; k < 32; k += 8) {
+        const int r = r0 + k, c = c0 + tx;
+        tile[k][tx] = (r < d.rows && c < d.cols) ? src[(long long)r * d.cols + c] : 0.0f;
+      }
+      __syncthreads();
+      for (int k = ty; k < 32; k += 8) {
+        const int c = c0 + k, r = r0 + tx;
+        if (r < d.rows && c < d.cols) out[r + c * d.ld_c] = from_f<T>(tile[tx][k]);
+      }
+      __syncthreads();
+    } else {
+      for (int k = ty; k < 32; k += 8) {
+        const int r = r0 + k, c = c0 + tx;
+        if (r < d.rows && c < d.cols) out[r * d.ld_r + c * d.ld_c] = from_f<T>(src[(long long)r * d.cols + c]);
+      }
+    }
   }
 }
 
