@@ -222,9 +222,9 @@ def main():
         "metric": "Parallel Evoformer block fwd+bwd ms (s=%d,r=%d)" % (dims["s"], dims["r"]),
         "value": ms, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "ms_median": ms_median, "higher_is_better": False, "scaling": "weak",
-        "vs_baseline": ms / PAPER_MS_PER_LAYER,
-        "baseline_note": "paper Table 5: 32.47 ms per Evoformer layer fwd+bwd, PPFold on 1x A100 40G, fp16, same "
-                         "shape (other hardware: context, not the target)",
+        "vs_baseline": ms / PAPER_MS_PER_LAYER if args.workload == "af2_initial" else None,
+        "baseline_note": "paper Table 5: 32.47 ms per Evoformer layer fwd+bwd, PPFold on 1x A100 40G, fp16, at the "
+                         "af2_initial shape (other hardware: context, not the target)",
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "s": dims["s"], "r": dims["r"], "c_m": dims["c_m"], "c_z": dims["c_z"],
                    "batch": 1, "streams": 2, "activation_ctx": "saved"},
@@ -237,7 +237,9 @@ def main():
         "kernels_ms_per_step": kernels,
     }
 
-    if not args.no_cpu_baseline:
+    if args.workload == "extra_msa_finetune":
+        out["cpu_baseline"] = None      # 6e9 float64 logits per attention: beyond the host's memory
+    elif not args.no_cpu_baseline:
         from oracle import evoformer as ev      # cpu_baseline leg only
         try:
             from threadpoolctl import threadpool_info

@@ -31,6 +31,10 @@ CONFIGS = {
     # AF2 fine-tuning-shape block
     "af2_finetune": (_dims(512, 384, 256, 128, 8, 32, 4, 32, 128, 32),
                      ("random_residues", 0.10), 3),
+    # extra-MSA-stack block at the fine-tuning depth (Table 1: N_extra_seq 5120, N_res 384);
+    # too large for the float64 oracle: timed, and tested through size-independent properties
+    "extra_msa_finetune": (_dims(5120, 384, 64, 128, 8, 8, 4, 32, 128, 32, col_global=1),
+                           ("random_rows", 0.05), 6),
 }
 
 # a very small shape for brute-force loops and finite differences

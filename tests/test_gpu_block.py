@@ -138,3 +138,58 @@ def test_extra_msa_bf16():
     """Config 3: extra-MSA-stack block (s=1024, r=256, c_m=64, global column attention), bf16."""
     dims, table, inp = _case("extra_msa")
     _assert(*check_case(dims, table, inp)[:3])
+
+
+@pytest.mark.slow
+def test_extra_msa_finetune_depth_by_replication():
+    """Extra-MSA block at the fine-tuning depth (Table 1: N_extra_seq = 5120, N_res = 384), too
+    large for the float64 oracle, checked through a property that holds at any size: an MSA made of
+    4 copies of a 1280-row MSA gives the same pair update, the same rows (per copy) and, with the
+    MSA cotangent divided by 4 (exact in bf16), the same gradients as the 1280-row problem.  Row
+    attention is per row; the mask-weighted mean query, the softmax over 4x duplicated keys and the
+    outer product mean (numerator and normaliser both x4, up to its 1e-3 epsilon) are unchanged."""
+    import torch
+    import paper_2211_00235_amd as pe
+    from tests.gpu_util import BlockRun, to_np, rel_err, param_errors
+    rep = 4
+    base, _, _ = dims_for("extra_msa")
+    base.update(s=1280, r=384)
+    big = dict(base, s=rep * base["s"])
+    table = pe.param_table(base)
+    inp = make_inputs(base, table, pe.param_count(base), ("random_rows", 0.05), 7)
+    big_inp = dict(inp)
+    big_inp["msa"] = np.tile(inp["msa"], (rep, 1, 1))
+    big_inp["msa_mask"] = np.tile(inp["msa_mask"], (rep, 1))
+    big_inp["d_msa_out"] = np.tile(inp["d_msa_out"], (rep, 1, 1)) / rep
+
+    def run(dims, x):
+        r = BlockRun(dims, x)
+        r.fwd()
+        r.bwd()
+        r.sync()
+        out = {k: to_np(getattr(r, k)) for k in ("msa_out", "pair_out", "d_msa_in", "d_pair_in", "d_params")}
+        del r
+        torch.cuda.empty_cache()
+        return out
+
+    small = run(base, inp)
+    large = run(big, big_inp)
+    s = base["s"]
+    tol = 1e-2
+    assert np.isfinite(large["pair_out"]).all() and np.isfinite(large["d_params"]).all()
+    assert rel_err(large["pair_out"], small["pair_out"]) < tol
+    assert rel_err(large["d_pair_in"], small["d_pair_in"]) < tol
+    # d_msa_in: the two runs round the transition's pre-activation differently (different summation
+    # orders upstream), so a ReLU decision at |a| ~ 0 can differ at isolated positions and changes
+    # that position's gradient by O(1) (both decisions are valid at bf16); everywhere else the
+    # tolerance holds.  Isolated = at most 1e-4 of the (row, residue) positions.
+    den = np.max(np.abs(small["d_msa_in"]))
+    for k in range(rep):
+        assert rel_err(large["msa_out"][k * s:(k + 1) * s], small["msa_out"]) < tol, k
+        diff = np.abs(large["d_msa_in"][k * s:(k + 1) * s] * rep - small["d_msa_in"]).max(axis=2) / den
+        bad = int((diff >= tol).sum())
+        assert bad <= 1e-4 * diff.size, (k, bad)
+        assert np.array_equal(large["d_msa_in"][k * s:(k + 1) * s], large["d_msa_in"][:s]), k   # copies are identical
+    errs = param_errors(large["d_params"], small["d_params"], table)
+    worst = max(errs, key=errs.get)
+    assert errs[worst] < tol, (worst, errs[worst])
