@@ -389,19 +389,8 @@ def opm_bwd(P, G, dupd, cache, dims):
 # --------------------------------------------------------------------------
 # the block
 # --------------------------------------------------------------------------
-def block_fwd(dims, params, msa, pair, msa_mask, pair_mask, want_cache=True, relu_on=None):
-    """Parallel Evoformer block forward (Figure 1(c); Section "Parallel
-    Evoformer").  MSA branch: row attention biased by the block's INPUT pair
-    representation, column attention, transition.  Pair branch: triangle
-    multiplication outgoing then incoming, triangle attention starting then
-    ending node, transition.  The outer product mean of the MSA branch's
-    output is added to the pair branch's output at the end.
-    relu_on: optional {"mtrans": bool array, "ptrans": bool array}, see transition_fwd."""
-    relu_on = relu_on or {}
-    table, _ = param_table(dims)
-    P = unpack(np.asarray(params, dtype=np.float64), table)
-    C = {}
-    u, C["row"] = row_attn_fwd(P, msa, pair, msa_mask, dims)
+def _msa_stack_fwd(P, C, dims, msa, bias_pair, msa_mask, relu_on):
+    u, C["row"] = row_attn_fwd(P, msa, bias_pair, msa_mask, dims)
     m1 = msa + u
     if dims["col_global"]:
         u, C["col"] = col_global_attn_fwd(P, m1, msa_mask, dims)
@@ -409,11 +398,12 @@ def block_fwd(dims, params, msa, pair, msa_mask, pair_mask, want_cache=True, rel
         u, C["col"] = col_attn_fwd(P, m1, msa_mask, dims)
     m2 = m1 + u
     u, C["mtrans"] = transition_fwd(P, "mtrans", m2, dims, relu_on.get("mtrans"))
-    m3 = m2 + u
-    opm, C["opm"] = opm_fwd(P, m3, msa_mask, dims)
+    return m1, m2, m2 + u
 
-    u, C["tmo"] = tri_mul_fwd(P, "tmo", pair, pair_mask, dims, True)
-    z1 = pair + u
+
+def _pair_stack_fwd(P, C, dims, z0, pair_mask, relu_on):
+    u, C["tmo"] = tri_mul_fwd(P, "tmo", z0, pair_mask, dims, True)
+    z1 = z0 + u
     u, C["tmi"] = tri_mul_fwd(P, "tmi", z1, pair_mask, dims, False)
     z2 = z1 + u
     u, C["tas"] = tri_attn_start_fwd(P, "tas", z2, pair_mask, dims)
@@ -421,38 +411,87 @@ def block_fwd(dims, params, msa, pair, msa_mask, pair_mask, want_cache=True, rel
     u, C["tae"] = tri_attn_end_fwd(P, "tae", z3, pair_mask, dims)
     z4 = z3 + u
     u, C["ptrans"] = transition_fwd(P, "ptrans", z4, dims, relu_on.get("ptrans"))
-    z5 = z4 + u
-    pair_out = z5 + opm
-    inter = dict(m1=m1, m2=m2, m3=m3, opm=opm, z1=z1, z2=z2, z3=z3, z4=z4, z5=z5,
+    return z1, z2, z3, z4, z4 + u
+
+
+def block_fwd(dims, params, msa, pair, msa_mask, pair_mask, want_cache=True, relu_on=None):
+    """Evoformer block forward, the three orderings of Figure 1 selected by
+    dims["variant"] (default 0).  MSA stack: row attention biased by a pair
+    representation, column attention, transition.  Pair stack: triangle
+    multiplication outgoing then incoming, triangle attention starting then
+    ending node, transition.  They differ in where the outer product mean sits:
+      0  Parallel Evoformer, Figure 1(c), Section "Parallel Evoformer": both stacks
+         read the block's inputs; the outer product mean of the MSA stack's OUTPUT
+         is added to the pair stack's output at the end.
+      1  AlphaFold2, Figure 1(a): the outer product mean of the MSA stack's output
+         is added to the pair representation BEFORE the pair stack (serial).
+      2  AlphaFold-Multimer, Figure 1(b): the outer product mean of the block's
+         INPUT MSA representation is added to the pair representation at the start;
+         the MSA stack (its row-attention bias) and the pair stack both read that sum.
+    relu_on: optional {"mtrans": bool array, "ptrans": bool array}, see transition_fwd."""
+    relu_on = relu_on or {}
+    variant = dims.get("variant", 0)
+    table, _ = param_table(dims)
+    P = unpack(np.asarray(params, dtype=np.float64), table)
+    C = {}
+    if variant == 2:
+        opm, C["opm"] = opm_fwd(P, msa, msa_mask, dims)
+        z0 = pair + opm
+        m1, m2, m3 = _msa_stack_fwd(P, C, dims, msa, z0, msa_mask, relu_on)
+    else:
+        m1, m2, m3 = _msa_stack_fwd(P, C, dims, msa, pair, msa_mask, relu_on)
+        opm, C["opm"] = opm_fwd(P, m3, msa_mask, dims)
+        z0 = pair + opm if variant == 1 else pair
+    z1, z2, z3, z4, z5 = _pair_stack_fwd(P, C, dims, z0, pair_mask, relu_on)
+    pair_out = z5 + opm if variant == 0 else z5
+    inter = dict(m1=m1, m2=m2, m3=m3, opm=opm, z0=z0, z1=z1, z2=z2, z3=z3, z4=z4, z5=z5,
                  mtrans_pre=C["mtrans"][2], ptrans_pre=C["ptrans"][2])
     return m3, pair_out, ((P, C) if want_cache else None), inter
 
 
-def block_bwd(dims, cache, d_msa_out, d_pair_out):
-    """Backward of the block.  As Section "Branch Parallelism" states, the
-    cotangent of the block's pair output feeds both the pair branch and the
-    outer product mean, and the gradient of the input pair representation is
-    the sum of the pair branch's term and the row-attention-bias term."""
-    P, C = cache
-    table, n = param_table(dims)
-    G = {}
-    # MSA side: msa_out = m3; opm reads m3
-    dm = d_msa_out + opm_bwd(P, G, d_pair_out, C["opm"], dims)
+def _msa_stack_bwd(P, G, C, dims, dm):
     dm = dm + transition_bwd(P, G, "mtrans", dm, C["mtrans"])
     if dims["col_global"]:
         dm = dm + col_global_attn_bwd(P, G, dm, C["col"], dims)
     else:
         dm = dm + col_attn_bwd(P, G, dm, C["col"], dims)
     d_row, dz_bias = row_attn_bwd(P, G, dm, C["row"], dims)
-    dm = dm + d_row
-    # pair side
-    dz = d_pair_out
+    return dm + d_row, dz_bias
+
+
+def _pair_stack_bwd(P, G, C, dims, dz):
     dz = dz + transition_bwd(P, G, "ptrans", dz, C["ptrans"])
     dz = dz + tri_attn_end_bwd(P, G, "tae", dz, C["tae"], dims)
     dz = dz + tri_attn_start_bwd(P, G, "tas", dz, C["tas"], dims)
     dz = dz + tri_mul_bwd(P, G, "tmi", dz, C["tmi"], False)
-    dz = dz + tri_mul_bwd(P, G, "tmo", dz, C["tmo"], True)
-    d_pair_in = dz + dz_bias
+    return dz + tri_mul_bwd(P, G, "tmo", dz, C["tmo"], True)
+
+
+def block_bwd(dims, cache, d_msa_out, d_pair_out):
+    """Backward of the block.  Variant 0: as Section "Branch Parallelism" states,
+    the cotangent of the block's pair output feeds both the pair stack and the
+    outer product mean, and the gradient of the input pair representation is
+    the sum of the pair stack's term and the row-attention-bias term.  Variants
+    1 and 2 follow from the chain rule on their forward orderings."""
+    P, C = cache
+    variant = dims.get("variant", 0)
+    table, n = param_table(dims)
+    G = {}
+    if variant == 0:
+        dm = d_msa_out + opm_bwd(P, G, d_pair_out, C["opm"], dims)
+        dm, dz_bias = _msa_stack_bwd(P, G, C, dims, dm)
+        dz = _pair_stack_bwd(P, G, C, dims, d_pair_out)
+        d_pair_in = dz + dz_bias
+    elif variant == 1:
+        dz = _pair_stack_bwd(P, G, C, dims, d_pair_out)          # w.r.t. pair_in + opm
+        dm = d_msa_out + opm_bwd(P, G, dz, C["opm"], dims)
+        dm, dz_bias = _msa_stack_bwd(P, G, C, dims, dm)
+        d_pair_in = dz + dz_bias
+    else:
+        dz = _pair_stack_bwd(P, G, C, dims, d_pair_out)          # pair stack's share of d(pair_in + opm)
+        dm, dz_bias = _msa_stack_bwd(P, G, C, dims, d_msa_out)   # bias was read from pair_in + opm
+        d_pair_in = dz + dz_bias
+        dm = dm + opm_bwd(P, G, d_pair_in, C["opm"], dims)       # opm read the block's input MSA
     gflat = np.zeros(n)
     for e in table:
         k = int(np.prod(e["shape"]))

@@ -10,11 +10,12 @@ _F32, _BF16 = 0, 1
 
 
 def _dims(s, r, c_m, c_z, h_msa, d_msa, h_pair, d_pair, c_tri, c_opm,
-          n_trans=4, col_global=0, dtype=_BF16):
+          n_trans=4, col_global=0, dtype=_BF16, variant=0):
+    # variant: 0 Parallel Evoformer (Figure 1(c)), 1 AlphaFold2 (1(a)), 2 AlphaFold-Multimer (1(b))
     return dict(s=s, r=r, c_m=c_m, c_z=c_z, h_msa=h_msa, d_msa=d_msa,
                 h_pair=h_pair, d_pair=d_pair, c_tri=c_tri, c_opm=c_opm,
                 n_trans=n_trans, col_global=col_global, dtype=dtype,
-                ln_eps=1e-5, opm_eps=1e-3)
+                ln_eps=1e-5, opm_eps=1e-3, variant=variant)
 
 
 # name -> (dims, mask recipe, seed)

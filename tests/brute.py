@@ -216,18 +216,31 @@ def opm(P, m, msa_mask, c_o, eps, eps_o):
     return linear(O, P["opm.w_o"], P["opm.b_o"])
 
 
-def block(dims, P, msa, pair, msa_mask, pair_mask):
+def block(dims, P, msa, pair, msa_mask, pair_mask, variant=0):
+    """variant 0: outer product mean of the MSA stack's output added at the end (Figure 1(c));
+    1: added to the pair input before the pair stack (Figure 1(a)); 2: outer product mean of the
+    INPUT MSA added first, both stacks read the sum (Figure 1(b))."""
     eps = dims["ln_eps"]
     Hm, dm, Hp, dp = dims["h_msa"], dims["d_msa"], dims["h_pair"], dims["d_pair"]
-    m1 = msa + row_attn(P, msa, pair, msa_mask, Hm, dm, eps)
+    o_in = opm(P, msa, msa_mask, dims["c_opm"], eps, dims["opm_eps"]) if variant == 2 else None
+    bias_pair = pair + o_in if variant == 2 else pair
+    m1 = msa + row_attn(P, msa, bias_pair, msa_mask, Hm, dm, eps)
     if dims["col_global"]:
         m2 = m1 + col_global_attn(P, m1, msa_mask, Hm, dm, eps)
     else:
         m2 = m1 + col_attn(P, m1, msa_mask, Hm, dm, eps)
     m3 = m2 + transition(P, "mtrans", m2, eps)
-    z1 = pair + tri_mul(P, "tmo", pair, pair_mask, eps, True)
+    if variant == 0:
+        z0 = pair
+    elif variant == 1:
+        z0 = pair + opm(P, m3, msa_mask, dims["c_opm"], eps, dims["opm_eps"])
+    else:
+        z0 = bias_pair
+    z1 = z0 + tri_mul(P, "tmo", z0, pair_mask, eps, True)
     z2 = z1 + tri_mul(P, "tmi", z1, pair_mask, eps, False)
     z3 = z2 + tri_attn(P, "tas", z2, pair_mask, Hp, dp, eps, False)
     z4 = z3 + tri_attn(P, "tae", z3, pair_mask, Hp, dp, eps, True)
     z5 = z4 + transition(P, "ptrans", z4, eps)
-    return m3, z5 + opm(P, m3, msa_mask, dims["c_opm"], eps, dims["opm_eps"])
+    if variant == 0:
+        return m3, z5 + opm(P, m3, msa_mask, dims["c_opm"], eps, dims["opm_eps"])
+    return m3, z5

@@ -84,12 +84,14 @@ def test_opm(case):
     assert np.max(np.abs(u - ref)) < TOL
 
 
+@pytest.mark.parametrize("variant", [0, 1, 2])
 @pytest.mark.parametrize("col_global", [0, 1])
-def test_whole_block(col_global):
-    dims, table, n, inp = tiny_case(seed=5, col_global=col_global)
+def test_whole_block(col_global, variant):
+    """All three orderings of Figure 1 against the scalar-loop composition."""
+    dims, table, n, inp = tiny_case(seed=5, col_global=col_global, variant=variant)
     P = P_of(inp, table)
     mm, pm = _mixed_masks(inp, dims["s"], dims["r"])
     m, z, _, _ = ev.block_fwd(dims, inp["params"], inp["msa"], inp["pair"], mm, pm)
-    mr, zr = brute.block(dims, P, inp["msa"], inp["pair"], mm, pm)
+    mr, zr = brute.block(dims, P, inp["msa"], inp["pair"], mm, pm, variant=variant)
     assert np.max(np.abs(m - mr)) < 1e-11
     assert np.max(np.abs(z - zr)) < 1e-11

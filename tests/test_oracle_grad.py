@@ -26,9 +26,10 @@ def _fd(f, x, idx, h=1e-6):
     return out
 
 
+@pytest.mark.parametrize("variant", [0, 1, 2])
 @pytest.mark.parametrize("col_global", [0, 1])
-def test_block_gradients_fd(col_global):
-    dims, table, n, inp = tiny_case(seed=7, col_global=col_global, mask=("last_residues", 1))
+def test_block_gradients_fd(col_global, variant):
+    dims, table, n, inp = tiny_case(seed=7, col_global=col_global, mask=("last_residues", 1), variant=variant)
     msa, pair, params = inp["msa"].copy(), inp["pair"].copy(), inp["params"].copy()
     mm, pm = inp["msa_mask"].copy(), inp["pair_mask"].copy()
     mm[1, 0] = 0.0

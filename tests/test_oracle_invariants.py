@@ -128,6 +128,41 @@ def test_zero_output_projections_give_identity():
     assert np.array_equal(m, inp["msa"]) and np.array_equal(z, inp["pair"])
 
 
+def test_block_orderings_differ_only_through_the_outer_product_mean():
+    """Figure 1: the three blocks are the same stacks with the outer product mean in different
+    places.  With its output projection zeroed they coincide; with it active the AlphaFold2
+    ordering is the Parallel block's pair stack applied to pair + opm(msa_out), and the Multimer
+    ordering is the Parallel block applied to the pair input pair + opm(msa_in) with the final
+    outer-product term left out."""
+    dims, table, n, inp = tiny_case(seed=12)
+    p0 = inp["params"].copy()
+    for e in table:
+        if e["name"] in ("opm.w_o", "opm.b_o"):
+            k = int(np.prod(e["shape"]))
+            p0[e["offset"]:e["offset"] + k] = 0.0
+    outs = [_blk(dict(dims, variant=v), inp, params=p0)[:2] for v in (0, 1, 2)]
+    for m, z in outs[1:]:
+        assert np.array_equal(m, outs[0][0]) and np.array_equal(z, outs[0][1])
+    m0, z0, _, i0 = _blk(dims, inp)
+    # AlphaFold2 ordering from Parallel pieces
+    _, _, _, ia = _blk(dims, inp, pair=inp["pair"] + i0["opm"])
+    m1, z1, _, _ = _blk(dict(dims, variant=1), inp)
+    assert np.array_equal(m1, m0) and np.allclose(z1, ia["z5"], atol=1e-12)
+    assert not np.allclose(z1, z0, atol=1e-3)
+    # Multimer ordering from Parallel pieces: opm(msa_in) from a block whose MSA stack is the identity
+    pid = inp["params"].copy()
+    for e in table:
+        if e["name"] in ("row.w_o", "row.b_o", "col.w_o", "col.b_o", "mtrans.w2", "mtrans.b2"):
+            k = int(np.prod(e["shape"]))
+            pid[e["offset"]:e["offset"] + k] = 0.0
+    _, _, _, iid = _blk(dims, inp, params=pid)
+    assert np.array_equal(iid["m3"], inp["msa"])
+    mb, _, _, ib = _blk(dims, inp, pair=inp["pair"] + iid["opm"])
+    m2, z2, _, _ = _blk(dict(dims, variant=2), inp)
+    assert np.allclose(m2, mb, atol=1e-12) and np.allclose(z2, ib["z5"], atol=1e-12)
+    assert not np.allclose(m2, m0, atol=1e-3)
+
+
 @pytest.mark.parametrize("col_global", [0, 1])
 def test_residue_permutation_equivariance(col_global):
     dims, table, n, inp = tiny_case(seed=7, col_global=col_global, mask=("last_residues", 1))
