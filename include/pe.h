@@ -41,6 +41,17 @@ extern "C" {
 
 enum { PE_F32 = 0, PE_BF16 = 1 };
 
+/* Block orderings of Figure 1.  The sub-operations and parameters are the same; only the place of
+ * the outer product mean differs.
+ *   PE_VARIANT_PARALLEL (c): both stacks read the block's inputs, the outer product mean of the
+ *     MSA stack's output is added to the pair stack's output (the two stacks overlap on two streams).
+ *   PE_VARIANT_AF2 (a): the outer product mean of the MSA stack's output is added to the pair
+ *     representation before the pair stack (serial; row attention is biased by the block's input).
+ *   PE_VARIANT_MULTIMER (b): the outer product mean of the block's input MSA representation is
+ *     added to the pair representation first; row attention's bias and the pair stack read that
+ *     sum (the stacks overlap after the outer product mean).                                     */
+enum { PE_VARIANT_PARALLEL = 0, PE_VARIANT_AF2 = 1, PE_VARIANT_MULTIMER = 2 };
+
 enum {
   PE_OK = 0,
   PE_ERR_NULL = -1,      /* a required pointer is NULL                               */
@@ -53,7 +64,8 @@ enum {
 
 /* Shape of one block.  Requirements checked by pe_check_dims:
  *   s,r >= 1; c_m, c_z, h*d, c_tri, c_opm, n_trans*c multiples of 8;
- *   d_msa, d_pair in [2, 32] and even; every channel count <= 1024.        */
+ *   d_msa, d_pair in [2, 32] and even; every channel count <= 1024;
+ *   variant one of PE_VARIANT_*.                                            */
 typedef struct pe_dims {
   int s, r, c_m, c_z;    /* msa[s,r,c_m], pair[r,r,c_z]                              */
   int h_msa, d_msa;      /* MSA attention heads x head dim                           */
@@ -64,6 +76,7 @@ typedef struct pe_dims {
   int dtype;             /* PE_F32 | PE_BF16: storage of activations and cotangents  */
   float ln_eps;          /* LayerNorm epsilon (1e-5)                                 */
   float opm_eps;         /* outer-product-mean normaliser epsilon (1e-3)             */
+  int variant;           /* where the outer product mean sits (Figure 1): PE_VARIANT_* */
 } pe_dims;
 
 typedef struct pe_handle pe_handle;
@@ -97,7 +110,9 @@ int pe_destroy(pe_handle* h);
 
 /* Options.  PE_OPT_BRANCHES: bit 0 = run the MSA branch (+ outer product
  * mean), bit 1 = run the pair branch; default 3.  With a branch disabled its
- * outputs are left untouched (used to time each branch alone).
+ * outputs are left untouched (used to time each branch alone; only
+ * PE_VARIANT_PARALLEL has independent branches, the other variants return
+ * PE_ERR_ARG unless both bits are set).
  * PE_OPT_SYNC_DEBUG: 1 = hipStreamSynchronize + error check after each
  * sub-operation (slow; for fault isolation).
  * PE_OPT_KERNEL_TIMING: 1 = bracket every kernel launch with a pair of HIP

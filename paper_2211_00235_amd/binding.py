@@ -15,11 +15,11 @@ class PEDims(C.Structure):
     _fields_ = [("s", C.c_int), ("r", C.c_int), ("c_m", C.c_int), ("c_z", C.c_int),
                 ("h_msa", C.c_int), ("d_msa", C.c_int), ("h_pair", C.c_int), ("d_pair", C.c_int),
                 ("c_tri", C.c_int), ("c_opm", C.c_int), ("n_trans", C.c_int), ("col_global", C.c_int),
-                ("dtype", C.c_int), ("ln_eps", C.c_float), ("opm_eps", C.c_float)]
+                ("dtype", C.c_int), ("ln_eps", C.c_float), ("opm_eps", C.c_float), ("variant", C.c_int)]
 
     @classmethod
     def from_dict(cls, d):
-        return cls(**{k: d[k] for k, _ in cls._fields_})
+        return cls(**{k: d.get(k, 0) if k == "variant" else d[k] for k, _ in cls._fields_})
 
 
 class _ParamEntry(C.Structure):

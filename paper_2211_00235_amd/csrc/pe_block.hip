@@ -78,7 +78,7 @@ template <typename T> struct Ctx {
   TriMulCtx<T> tmo, tmi;
   OpmCtx<T> opm;
   GlobCtx<T> gcol;
-  T *m1, *m2, *m3, *z1, *z2, *z3, *z4, *z5;
+  T *m1, *m2, *m3, *z0, *z1, *z2, *z3, *z4, *z5;   // z0 = pair input + outer product mean (variants 1, 2)
 };
 
 template <typename T> struct AttnW { T *wt_qkvg, *wn_qkvg, *wt_o, *wn_o; };
@@ -164,6 +164,7 @@ template <typename T> static size_t carve_ctx(char* base, const pe_dims& d, Ctx<
   C.opm.inv_norm = cv.take<float>("opm.inv_norm", Mz, PE_F32);
   C.opm.O = cv.take<T>("opm.O", Mz * d.c_opm * d.c_opm, dtype_tag<T>());
   carve_trimul_ctx<T>(cv, C.tmo, "tmo", Mz, d.c_z, d.c_tri);
+  C.z0 = d.variant != PE_VARIANT_PARALLEL ? cv.take<T>("z0", Mz * d.c_z, dtype_tag<T>()) : nullptr;
   C.z1 = cv.take<T>("z1", Mz * d.c_z, dtype_tag<T>());
   carve_trimul_ctx<T>(cv, C.tmi, "tmi", Mz, d.c_z, d.c_tri);
   C.z2 = cv.take<T>("z2", Mz * d.c_z, dtype_tag<T>());
@@ -785,9 +786,9 @@ template <typename T> struct Runner {
   AttnGeom geom_tae() const { return AttnGeom{d.r, d.r, 1, d.r, 1, d.r, pair_mask, 1,
                                                "attn_fwd tae", "attn_dq tae", "attn_dkv tae"}; }
 
-  void fwd_msa(T* msa_out) {
-    run_prep(true);
-    attn_sub_fwd(sm, am, PL.row, W.row, C.row, msa_in, C.m1, Mm, d.c_m, d.h_msa, d.d_msa, geom_row(), pair_in,
+  // MSA stack: row attention (bias read from bias_pair), column attention, transition
+  void fwd_msa_stack(const T* bias_pair, T* msa_out) {
+    attn_sub_fwd(sm, am, PL.row, W.row, C.row, msa_in, C.m1, Mm, d.c_m, d.h_msa, d.d_msa, geom_row(), bias_pair,
                  PL.row.ln_z_g, PL.row.ln_z_b);
     if (d.col_global) gcol_sub_fwd(sm, C.m1, C.m2);
     else attn_sub_fwd(sm, am, PL.col, W.col, C.col, C.m1, C.m2, Mm, d.c_m, d.h_msa, d.d_msa, geom_col(), nullptr, 0, 0);
@@ -796,10 +797,12 @@ template <typename T> struct Runner {
       if (hipMemcpyAsync(msa_out, C.m3, (size_t)Mm * d.c_m * sizeof(T), hipMemcpyDeviceToDevice, sm) != hipSuccess)
         fail("copy msa_out");
     }
-    // outer product mean, up to the projection (which needs the pair branch's result)
+  }
+  // outer product mean of x, up to its output projection
+  void fwd_opm_outer(const T* x) {
     const int co = d.c_opm, r = d.r;
     const long long Wd = (long long)r * co;
-    k_ln_fwd(sm, C.m3, PL.opm.ln_g, PL.opm.ln_b, C.opm.mhat, C.opm.stats, Mm, d.c_m);
+    k_ln_fwd(sm, x, PL.opm.ln_g, PL.opm.ln_b, C.opm.mhat, C.opm.stats, Mm, d.c_m);
     for (int k = 0; k < 2; k++) {
       EpiGeneric<T> e = epi_plain<T>(k ? C.opm.b : C.opm.a, co);
       e.bias_n = P(k ? PL.opm.b_b : PL.opm.b_a);
@@ -817,7 +820,14 @@ template <typename T> struct Runner {
       gemm(sm, op_trans(C.opm.a, Wd), false, op_trans(C.opm.b, Wd), false, (int)Wd, (int)Wd, d.s, 1, e, "opm outer");
     }
   }
-  // final projection of the outer product mean; adds the pair branch's output
+  // Parallel block, MSA branch: the stack, then the outer product mean of its output up to the
+  // projection (which needs the pair branch's result)
+  void fwd_msa(T* msa_out) {
+    run_prep(true);
+    fwd_msa_stack(pair_in, msa_out);
+    fwd_opm_outer(C.m3);
+  }
+  // output projection of the outer product mean, added to z5 (a pair representation)
   void fwd_opm_project(T* pair_out, const T* z5) {
     const int co = d.c_opm, r = d.r;
     const long long Wd = (long long)r * co;
@@ -832,13 +842,16 @@ template <typename T> struct Runner {
   }
   void fwd_pair() {
     run_prep(false);
-    trimul_sub_fwd(sp, PL.tmo, W.tmo, C.tmo, pair_in, C.z1, true);
+    fwd_pair_stack(pair_in, C.z5);
+  }
+  void fwd_pair_stack(const T* z_in, T* z_out) {
+    trimul_sub_fwd(sp, PL.tmo, W.tmo, C.tmo, z_in, C.z1, true);
     trimul_sub_fwd(sp, PL.tmi, W.tmi, C.tmi, C.z1, C.z2, false);
     attn_sub_fwd(sp, ap, PL.tas, W.tas, C.tas, C.z2, C.z3, Mz, d.c_z, d.h_pair, d.d_pair, geom_tas(), C.z2, PL.tas.ln_g,
                  PL.tas.ln_b);
     attn_sub_fwd(sp, ap, PL.tae, W.tae, C.tae, C.z3, C.z4, Mz, d.c_z, d.h_pair, d.d_pair, geom_tae(), C.z3, PL.tae.ln_g,
                  PL.tae.ln_b);
-    trans_sub_fwd(sp, PL.ptrans, W.pt, C.pt, C.z4, C.z5, Mz, d.c_z);
+    trans_sub_fwd(sp, PL.ptrans, W.pt, C.pt, C.z4, z_out, Mz, d.c_z);
   }
 
   // ---- sub-operations: backward --------------------------------------------
@@ -1018,9 +1031,15 @@ template <typename T> struct Runner {
   // MSA side backward.  gm_out receives d_msa_in; dz_bias receives the row-attention-bias
   // term of d_pair_in.
   void bwd_msa(const T* d_msa_out, const T* d_pair_out, T* gm, T* dz_bias) {
+    bwd_opm(d_pair_out, C.m3, d_msa_out, gm);
+    bwd_msa_stack(gm, pair_in, dz_bias);
+  }
+  // outer product mean backward: dz = cotangent of its output, x = the MSA tensor it read;
+  // gout = gin + gradient w.r.t. x
+  void bwd_opm(const T* d_pair_out, const T* x, const T* gin, T* gout) {
     const int co = d.c_opm, r = d.r, cm = d.c_m, cz = d.c_z;
     const long long Wd = (long long)r * co;
-    {  // outer product mean backward
+    {
       size_t mk = am.mark();
       T* dOs = (T*)am.alloc((size_t)Wd * Wd * sizeof(T));
       T* dab = (T*)am.alloc((size_t)2 * Mm * co * sizeof(T));
@@ -1065,17 +1084,22 @@ template <typename T> struct Runner {
         EpiGeneric<T> e = epi_plain<T>(dmh, cm);
         gemm(sm, A, true, op_plain(W.opm.wn_ab, 2 * co), true, (int)Mm, cm, 2 * co, 1, e, "opm dmhat");
       }
-      k_ln_bwd(sm, am, dmh, C.m3, C.opm.stats, PL.opm.ln_g, PL.opm.ln_b, d_msa_out, gm, Mm, cm);
+      k_ln_bwd(sm, am, dmh, x, C.opm.stats, PL.opm.ln_g, PL.opm.ln_b, gin, gout, Mm, cm);
       flush_reduces(sm);
       am.release(mk);
     }
+  }
+  // MSA stack backward, in place on gm; dz_bias receives the gradient through the row-attention bias
+  void bwd_msa_stack(T* gm, const T* bias_pair, T* dz_bias) {
+    const int cm = d.c_m;
     trans_sub_bwd(sm, am, PL.mtrans, W.mt, C.mt, C.m2, gm, Mm, cm);
     if (d.col_global) gcol_sub_bwd(sm, am, C.m1, gm);
     else attn_sub_bwd(sm, am, PL.col, W.col, C.col, C.m1, gm, Mm, cm, d.h_msa, d.d_msa, geom_col(), nullptr, 0, 0, nullptr, nullptr);
-    attn_sub_bwd(sm, am, PL.row, W.row, C.row, msa_in, gm, Mm, cm, d.h_msa, d.d_msa, geom_row(), pair_in, PL.row.ln_z_g,
+    attn_sub_bwd(sm, am, PL.row, W.row, C.row, msa_in, gm, Mm, cm, d.h_msa, d.d_msa, geom_row(), bias_pair, PL.row.ln_z_g,
                  PL.row.ln_z_b, nullptr, dz_bias);
   }
-  void bwd_pair(const T* d_pair_out, T* gz) {
+  void bwd_pair(const T* d_pair_out, T* gz) { bwd_pair_stack(d_pair_out, gz, pair_in); }
+  void bwd_pair_stack(const T* d_pair_out, T* gz, const T* z_in) {
     if (!dry && !err) {
       if (hipMemcpyAsync(gz, d_pair_out, (size_t)Mz * d.c_z * sizeof(T), hipMemcpyDeviceToDevice, sp) != hipSuccess)
         fail("copy gz");
@@ -1086,7 +1110,7 @@ template <typename T> struct Runner {
     attn_sub_bwd(sp, ap, PL.tas, W.tas, C.tas, C.z2, gz, Mz, d.c_z, d.h_pair, d.d_pair, geom_tas(), C.z2, PL.tas.ln_g,
                  PL.tas.ln_b, gz, gz);
     trimul_sub_bwd(sp, ap, PL.tmi, W.tmi, C.tmi, C.z1, gz, false);
-    trimul_sub_bwd(sp, ap, PL.tmo, W.tmo, C.tmo, pair_in, gz, true);
+    trimul_sub_bwd(sp, ap, PL.tmo, W.tmo, C.tmo, z_in, gz, true);
   }
 };
 
@@ -1143,39 +1167,71 @@ static bool hip_ok(pe_handle* h, hipError_t e, const char* what) {
   return false;
 }
 
+// `to` waits for everything queued on `from` so far
+static bool ev_link(pe_handle* h, int e, hipStream_t from, hipStream_t to) {
+  if (from == to) return true;
+  return hip_ok(h, hipEventRecord(h->ev[e], from), "event record") && hip_ok(h, hipStreamWaitEvent(to, h->ev[e], 0), "stream wait");
+}
+
+// Forward schedule of one block (Figure 1).  At entry stream_pair has been forked from stream_msa.
+// msa_out / pair_out may be null (recompute inside the backward pass: only ctx is needed).  On
+// return every forward kernel is ordered before later work on BOTH streams.
+template <typename T>
+static int run_forward(Runner<T>& R, pe_handle* h, const pe_dims& d, T* msa_out, T* pair_out) {
+  hipStream_t sm = R.sm, sp = R.sp;
+  const bool do_m = h->branches & 1, do_p = h->branches & 2;
+  if (d.variant == PE_VARIANT_PARALLEL) {
+    if (do_p) R.fwd_pair();
+    if (do_m) R.fwd_msa(msa_out);
+    if (do_p && !ev_link(h, 1, sp, sm)) return PE_ERR_HIP;
+    if (pair_out) {
+      if (do_m && do_p) R.fwd_opm_project(pair_out, R.C.z5);
+      else if (do_p && !R.err) {
+        if (!hip_ok(h, hipMemcpyAsync(pair_out, R.C.z5, (size_t)R.Mz * d.c_z * sizeof(T), hipMemcpyDeviceToDevice, sm),
+                    "copy pair_out")) return PE_ERR_HIP;
+      }
+    }
+    if (!ev_link(h, 2, sm, sp)) return PE_ERR_HIP;
+    return R.err;
+  }
+  R.run_prep(true);
+  R.run_prep(false);
+  T* z_out = pair_out ? pair_out : R.C.z5;
+  if (d.variant == PE_VARIANT_AF2) {
+    // MSA stack -> outer product mean of its output added to the pair input -> pair stack
+    R.fwd_msa_stack(R.pair_in, msa_out);
+    R.fwd_opm_outer(R.C.m3);
+    R.fwd_opm_project(R.C.z0, R.pair_in);
+    if (!ev_link(h, 1, sm, sp)) return PE_ERR_HIP;
+    R.fwd_pair_stack(R.C.z0, z_out);
+    if (!ev_link(h, 2, sp, sm)) return PE_ERR_HIP;
+  } else {
+    // outer product mean of the input MSA added to the pair input, then the two stacks side by side
+    R.fwd_opm_outer(R.msa_in);
+    R.fwd_opm_project(R.C.z0, R.pair_in);
+    if (!ev_link(h, 1, sm, sp)) return PE_ERR_HIP;
+    R.fwd_msa_stack(R.C.z0, msa_out);
+    R.fwd_pair_stack(R.C.z0, z_out);
+    if (!ev_link(h, 2, sp, sm)) return PE_ERR_HIP;
+    if (!ev_link(h, 3, sm, sp)) return PE_ERR_HIP;
+  }
+  return R.err;
+}
+
 template <typename T>
 static int block_fwd_impl(pe_handle* h, const pe_dims& d, const void* msa_in, const void* pair_in, const float* msa_mask,
                           const float* pair_mask, const float* params, void* msa_out, void* pair_out, void* ctx,
                           void* workspace, size_t wbytes, hipStream_t sm, hipStream_t sp) {
   Plan pl = plan_for(d);
   if (wbytes < pl.total(ctx == nullptr)) return PE_ERR_WORKSPACE;
+  if (d.variant != PE_VARIANT_PARALLEL && h->branches != 3) return PE_ERR_ARG;
   Runner<T> R;
   setup_runner<T>(R, h, d, pl, (char*)workspace, (char*)ctx, sm, sp);
   R.params = params;
   R.msa_in = (const T*)msa_in; R.pair_in = (const T*)pair_in;
   R.msa_mask = msa_mask; R.pair_mask = pair_mask;
-  const bool two = sm != sp;
-  const bool do_m = h->branches & 1, do_p = h->branches & 2;
-  if (two) {
-    if (!hip_ok(h, hipEventRecord(h->ev[0], sm), "event record")) return PE_ERR_HIP;
-    if (!hip_ok(h, hipStreamWaitEvent(sp, h->ev[0], 0), "stream wait")) return PE_ERR_HIP;
-  }
-  if (do_p) R.fwd_pair();
-  if (do_m) R.fwd_msa((T*)msa_out);
-  if (two && do_p) {
-    if (!hip_ok(h, hipEventRecord(h->ev[1], sp), "event record")) return PE_ERR_HIP;
-    if (!hip_ok(h, hipStreamWaitEvent(sm, h->ev[1], 0), "stream wait")) return PE_ERR_HIP;
-  }
-  if (do_m && do_p) R.fwd_opm_project((T*)pair_out, R.C.z5);
-  else if (do_p && !R.err) {
-    if (!hip_ok(h, hipMemcpyAsync(pair_out, R.C.z5, (size_t)R.Mz * d.c_z * sizeof(T), hipMemcpyDeviceToDevice, sm),
-                "copy pair_out")) return PE_ERR_HIP;
-  }
-  if (two) {
-    if (!hip_ok(h, hipEventRecord(h->ev[2], sm), "event record")) return PE_ERR_HIP;
-    if (!hip_ok(h, hipStreamWaitEvent(sp, h->ev[2], 0), "stream wait")) return PE_ERR_HIP;
-  }
-  return R.err;
+  if (!ev_link(h, 0, sm, sp)) return PE_ERR_HIP;
+  return run_forward<T>(R, h, d, (T*)msa_out, (T*)pair_out);
 }
 
 template <typename T>
@@ -1185,45 +1241,69 @@ static int block_bwd_impl(pe_handle* h, const pe_dims& d, const void* msa_in, co
                           size_t wbytes, hipStream_t sm, hipStream_t sp) {
   Plan pl = plan_for(d);
   if (wbytes < pl.total(ctx == nullptr)) return PE_ERR_WORKSPACE;
-  const bool two = sm != sp;
+  if (d.variant != PE_VARIANT_PARALLEL && h->branches != 3) return PE_ERR_ARG;
   const bool do_m = h->branches & 1, do_p = h->branches & 2;
   Runner<T> R;
   setup_runner<T>(R, h, d, pl, (char*)workspace, (char*)ctx, sm, sp);
   R.params = params; R.dparams = d_params;
   R.msa_in = (const T*)msa_in; R.pair_in = (const T*)pair_in;
   R.msa_mask = msa_mask; R.pair_mask = pair_mask;
-  if (two) {
-    if (!hip_ok(h, hipEventRecord(h->ev[0], sm), "event record")) return PE_ERR_HIP;
-    if (!hip_ok(h, hipStreamWaitEvent(sp, h->ev[0], 0), "stream wait")) return PE_ERR_HIP;
-  }
-  if (ctx == nullptr) {   // recompute the forward into the internal ctx
-    if (do_p) R.fwd_pair();
-    if (do_m) R.fwd_msa(nullptr);
-    // the outer-product projection is not needed for the backward pass
-  }   // else: the prepared weights are part of ctx
-  T* dzb = (T*)R.am.alloc((size_t)R.Mz * d.c_z * sizeof(T));
-  T* gz = (T*)R.ap.alloc((size_t)R.Mz * d.c_z * sizeof(T));
-  if (do_p) R.bwd_pair((const T*)d_pair_out, gz);
-  if (do_m) R.bwd_msa((const T*)d_msa_out, (const T*)d_pair_out, (T*)d_msa_in, dzb);
-  if (two && do_m) {
-    if (!hip_ok(h, hipEventRecord(h->ev[1], sm), "event record")) return PE_ERR_HIP;
-    if (!hip_ok(h, hipStreamWaitEvent(sp, h->ev[1], 0), "stream wait")) return PE_ERR_HIP;
-  }
-  if (!R.err) {
-    long long n = R.Mz * d.c_z;
-    if (do_m && do_p) {
-      hipLaunchKernelGGL(add2_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, sp, gz, dzb, (T*)d_pair_in, n);
-      R.check("add d_pair_in");
-    } else if (do_p) {
-      if (!hip_ok(h, hipMemcpyAsync(d_pair_in, gz, (size_t)n * sizeof(T), hipMemcpyDeviceToDevice, sp), "copy")) return PE_ERR_HIP;
-    } else if (do_m) {
-      if (!hip_ok(h, hipMemcpyAsync(d_pair_in, dzb, (size_t)n * sizeof(T), hipMemcpyDeviceToDevice, sp), "copy")) return PE_ERR_HIP;
+  if (!ev_link(h, 0, sm, sp)) return PE_ERR_HIP;
+  if (ctx == nullptr) {   // recompute the forward into the internal ctx (else: ctx also holds the prepared weights)
+    if (d.variant == PE_VARIANT_PARALLEL) {
+      if (do_p) R.fwd_pair();
+      if (do_m) R.fwd_msa(nullptr);   // the outer-product projection is not needed for the backward pass
+    } else {
+      int rc = run_forward<T>(R, h, d, nullptr, nullptr);
+      if (rc) return rc;
     }
   }
-  if (two) {
-    if (!hip_ok(h, hipEventRecord(h->ev[2], sp), "event record")) return PE_ERR_HIP;
-    if (!hip_ok(h, hipStreamWaitEvent(sm, h->ev[2], 0), "stream wait")) return PE_ERR_HIP;
+  const long long n = R.Mz * d.c_z;
+  T* dzb = (T*)R.am.alloc((size_t)n * sizeof(T));
+  T* gz = (T*)R.ap.alloc((size_t)n * sizeof(T));
+  T* gm = (T*)d_msa_in;
+  if (d.variant == PE_VARIANT_PARALLEL) {
+    if (do_p) R.bwd_pair((const T*)d_pair_out, gz);
+    if (do_m) R.bwd_msa((const T*)d_msa_out, (const T*)d_pair_out, gm, dzb);
+    if (do_m && !ev_link(h, 1, sm, sp)) return PE_ERR_HIP;
+    if (!R.err) {
+      if (do_m && do_p) {
+        hipLaunchKernelGGL(add2_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, sp, gz, dzb, (T*)d_pair_in, n);
+        R.check("add d_pair_in");
+      } else if (do_p) {
+        if (!hip_ok(h, hipMemcpyAsync(d_pair_in, gz, (size_t)n * sizeof(T), hipMemcpyDeviceToDevice, sp), "copy")) return PE_ERR_HIP;
+      } else if (do_m) {
+        if (!hip_ok(h, hipMemcpyAsync(d_pair_in, dzb, (size_t)n * sizeof(T), hipMemcpyDeviceToDevice, sp), "copy")) return PE_ERR_HIP;
+      }
+    }
+    if (!ev_link(h, 2, sp, sm)) return PE_ERR_HIP;
+    return R.err;
   }
+  if (d.variant == PE_VARIANT_AF2) {
+    // pair stack -> outer product mean (cotangent = the pair stack's input gradient) -> MSA stack
+    R.bwd_pair_stack((const T*)d_pair_out, gz, R.C.z0);
+    if (!ev_link(h, 1, sp, sm)) return PE_ERR_HIP;
+    R.bwd_opm(gz, R.C.m3, (const T*)d_msa_out, gm);
+    R.bwd_msa_stack(gm, R.pair_in, dzb);
+    if (!R.err) {
+      hipLaunchKernelGGL(add2_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, sm, gz, dzb, (T*)d_pair_in, n);
+      R.check("add d_pair_in");
+    }
+  } else {
+    // both stacks side by side; their two gradients w.r.t. (pair input + outer product mean) are
+    // summed, and that sum is also the cotangent of the outer product mean of the input MSA
+    if (!R.err && !hip_ok(h, hipMemcpyAsync(gm, d_msa_out, (size_t)R.Mm * d.c_m * sizeof(T), hipMemcpyDeviceToDevice, sm), "copy"))
+      return PE_ERR_HIP;
+    R.bwd_msa_stack(gm, R.C.z0, dzb);
+    R.bwd_pair_stack((const T*)d_pair_out, gz, R.C.z0);
+    if (!ev_link(h, 1, sp, sm)) return PE_ERR_HIP;
+    if (!R.err) {
+      hipLaunchKernelGGL(add2_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, sm, gz, dzb, (T*)d_pair_in, n);
+      R.check("add d_pair_in");
+    }
+    R.bwd_opm((const T*)d_pair_in, R.msa_in, gm, gm);
+  }
+  if (!ev_link(h, 2, sm, sp)) return PE_ERR_HIP;
   return R.err;
 }
 

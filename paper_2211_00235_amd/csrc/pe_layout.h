@@ -33,6 +33,7 @@ inline int pe_check_dims_impl(const pe_dims* d) {
   if ((long long)d->n_trans * d->c_m > 4096 || (long long)d->n_trans * d->c_z > 4096) return PE_ERR_DIMS;
   if (d->d_msa % 8 || d->d_msa > 32 || d->d_pair % 8 || d->d_pair > 32) return PE_ERR_DIMS;
   if (d->col_global != 0 && d->col_global != 1) return PE_ERR_DIMS;
+  if (d->variant < PE_VARIANT_PARALLEL || d->variant > PE_VARIANT_MULTIMER) return PE_ERR_DIMS;
   if (!(d->ln_eps > 0.0f) || !(d->opm_eps > 0.0f)) return PE_ERR_DIMS;
   if ((long long)d->r * d->r * 4 * d->h_pair * d->d_pair >= (1LL << 40)) return PE_ERR_DIMS;
   return PE_OK;

@@ -51,7 +51,10 @@ def check_case(dims, table, inp, two_streams=True, use_ctx=True, verbose=False):
     m, z, cache, inter = ev.block_fwd(*args, relu_on=on)
     dm, dz, g, _ = ev.block_bwd(dims, cache, inp["d_msa_out"], inp["d_pair_out"])
     errs = {}
-    for k in ("m1", "m2", "m3", "z1", "z2", "z3", "z4", "z5"):
+    # saved residual-stream values; with the outer product mean in front of the pair stack (orderings
+    # (a) and (b) of Figure 1) z0 = pair input + outer product mean is saved and z5 is the output itself
+    keys = ("m1", "m2", "m3", "z1", "z2", "z3", "z4") + (("z0",) if dims.get("variant", 0) else ("z5",))
+    for k in keys:
         errs["ctx." + k] = rel_err(run.ctx_entry(k).reshape(inter[k].shape), inter[k])
     errs["msa_out"] = rel_err(to_np(run.msa_out), m)
     errs["pair_out"] = rel_err(to_np(run.pair_out), z)

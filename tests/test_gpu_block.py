@@ -52,6 +52,27 @@ def test_ragged_shapes(dtype):
     _assert(errs, worst, SMALL_BF16_TOL if dtype == 1 else tol)
 
 
+@pytest.mark.parametrize("use_ctx", [True, False])
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("variant", [1, 2])
+def test_block_orderings_small(variant, dtype, use_ctx):
+    """The AlphaFold2 (Figure 1(a)) and Multimer (Figure 1(b)) orderings of the same sub-operations,
+    ragged shape, fp32 and bf16, with saved activations and with the forward recomputed."""
+    dims, table, inp = _case("tiny", dtype=dtype, s=37, r=150, c_m=64, c_z=32, h_msa=2, d_msa=16, h_pair=4,
+                             d_pair=8, c_tri=24, c_opm=16, n_trans=2, variant=variant)
+    table, n = param_table(dims)
+    inp = make_inputs(dims, table, n, ("random_residues", 0.07), 5)
+    errs, worst, tol, _ = check_case(dims, table, inp, use_ctx=use_ctx)
+    _assert(errs, worst, SMALL_BF16_TOL if dtype == 1 else tol)
+
+
+@pytest.mark.parametrize("variant", [1, 2])
+def test_block_orderings_af2_initial_bf16(variant):
+    """The other two orderings at the benchmark shape, bf16, every output element."""
+    dims, table, inp = _case("af2_initial", variant=variant)
+    _assert(*check_case(dims, table, inp)[:3])
+
+
 def test_af2_initial_bf16():
     """Config 2: the benchmark workload at full size, bf16 path, every output element."""
     dims, table, inp = _case("af2_initial")
