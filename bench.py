@@ -57,8 +57,11 @@ def bench_trunk(args, torch, pe):
     dmo, dzo = to_dev(im["d_msa_out"], bf), to_dev(im["d_pair_out"], bf)
     mo, zo, dex, dmi, dzi = (torch.empty_like(t) for t in (msa, pair, ex, msa, pair))
     dpar = torch.zeros_like(par)
-    ws = torch.empty(pe.stack_workspace_bytes(ne, de, nm, dm), dtype=torch.uint8, device="cuda")
+    keep = not args.recompute
+    ws = torch.empty(pe.stack_workspace_bytes(ne, de, nm, dm, keep=keep), dtype=torch.uint8, device="cuda")
     h = pe.Handle()
+    if keep:
+        h.set_option(5, 1)      # PE_OPT_STACK_KEEP_CTX: 288 GB hold every block's activations
     sm, sp = torch.cuda.Stream(), torch.cuda.Stream()
 
     def step():
@@ -78,7 +81,9 @@ def bench_trunk(args, torch, pe):
         "metric": "Parallel Evoformer trunk (4 extra + 48 main blocks) fwd+bwd ms", "value": ms, "unit": "ms",
         "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": ms, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "trunk", "n_extra": ne, "n_main": nm, "recompute": "per block", "streams": 2},
+        "config": {"workload": "trunk", "n_extra": ne, "n_main": nm, "streams": 2,
+                   "recompute": "none (every block's activations kept)" if keep else "per block",
+                   "workspace_gib": round(ws.numel() / 2 ** 30, 1)},
         "counted_tflops": flops / (ms * 1e-3) / 1e12,
         "bf16_mfma_peak_frac": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "finite_outputs": bool(torch.isfinite(zo.float()).all().item() and torch.isfinite(dpar).all().item())}))
@@ -108,6 +113,9 @@ def main():
     ap.add_argument("--workload", default="af2_initial")
     ap.add_argument("--variant", type=int, default=0, choices=[0, 1, 2],
                     help="block ordering of Figure 1: 0 Parallel Evoformer (the headline), 1 AlphaFold2, 2 Multimer")
+    ap.add_argument("--recompute", action="store_true",
+                    help="trunk workload: save block inputs only and recompute each block's forward in the backward "
+                         "pass (the paper's memory-saving setting) instead of keeping every block's activations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="also print the per-launch-label timing table to stderr")
     ap.add_argument("--copy-calibration", action="store_true",

@@ -122,8 +122,14 @@ int pe_destroy(pe_handle* h);
  * gradient kernels (dW GEMMs, bias sums, partial reductions) on one library-
  * owned side stream per branch, forked from / joined to the caller's streams
  * with events; results are bit-identical.  Measured slower on MI355X (each
- * cross-stream event wait costs more than the overlap wins), hence off.      */
-enum { PE_OPT_BRANCHES = 1, PE_OPT_SYNC_DEBUG = 2, PE_OPT_KERNEL_TIMING = 3, PE_OPT_SIDE_STREAMS = 4 };
+ * cross-stream event wait costs more than the overlap wins), hence off.
+ * PE_OPT_STACK_KEEP_CTX (default 0): 1 = pe_stack_fwd_bwd keeps every block's
+ * saved activations (pe_stack_workspace_bytes_keep bytes of workspace: about
+ * 1.3 GiB per main block at s=128, r=256, which 288 GB of HBM hold for the whole
+ * trunk) and recomputes nothing; results are bit-identical to the default,
+ * which saves block inputs only and recomputes each block's forward.         */
+enum { PE_OPT_BRANCHES = 1, PE_OPT_SYNC_DEBUG = 2, PE_OPT_KERNEL_TIMING = 3, PE_OPT_SIDE_STREAMS = 4,
+       PE_OPT_STACK_KEEP_CTX = 5 };
 int pe_set_option(pe_handle* h, int option, int value);
 
 /* Per-kernel timing since the last collect, aggregated by launch label.
@@ -153,6 +159,8 @@ size_t pe_ctx_bytes(const pe_dims* d);                                 /* saved 
 size_t pe_workspace_bytes(const pe_dims* d, int with_ctx);
 /* Scratch needed by pe_stack_fwd_bwd (saved block inputs + one block's needs). */
 size_t pe_stack_workspace_bytes(int n_extra, const pe_dims* extra, int n_main, const pe_dims* main_);
+/* The same with PE_OPT_STACK_KEEP_CTX set (every block's ctx kept, no recompute). */
+size_t pe_stack_workspace_bytes_keep(int n_extra, const pe_dims* extra, int n_main, const pe_dims* main_);
 
 /* Forward of one Parallel Evoformer block (Figure 1(c)).
  *   msa_in [s,r,c_m], pair_in [r,r,c_z]: inputs (dtype per dims), read only.
@@ -203,7 +211,8 @@ int pe_block_bwd(pe_handle* h, const pe_dims* dims,
  * made of Evoformer blocks, 52 = 4 + 48.  Only the pair representation flows
  * from the extra blocks into the main blocks; the extra-MSA representation is
  * dropped (its output cotangent is zero).  Block inputs are saved in the
- * forward pass and each block's forward is recomputed in the backward pass.
+ * forward pass and each block's forward is recomputed in the backward pass
+ * (with PE_OPT_STACK_KEEP_CTX every block's activations are kept instead).
  *   params / d_params: the blocks' flat buffers back to back, extra first.
  *   msa_out, pair_out: final representations.  d_msa_out, d_pair_out: their
  *   cotangents.  d_extra_msa_in, d_msa_in, d_pair_in: overwritten.

@@ -65,6 +65,8 @@ def lib():
     L.pe_workspace_bytes.restype = C.c_size_t
     L.pe_stack_workspace_bytes.argtypes = [C.c_int, dp, C.c_int, dp]
     L.pe_stack_workspace_bytes.restype = C.c_size_t
+    L.pe_stack_workspace_bytes_keep.argtypes = [C.c_int, dp, C.c_int, dp]
+    L.pe_stack_workspace_bytes_keep.restype = C.c_size_t
     L.pe_block_fwd.argtypes = [vp, dp, vp, vp, fp, fp, fp, vp, vp, vp, vp, C.c_size_t, vp, vp]
     L.pe_block_bwd.argtypes = [vp, dp, vp, vp, fp, fp, fp, vp, vp, vp, vp, fp, vp, vp, C.c_size_t, vp, vp]
     L.pe_stack_fwd_bwd.argtypes = [vp, C.c_int, dp, C.c_int, dp, vp, vp, vp, fp, fp, fp, fp, vp, vp,
@@ -124,10 +126,11 @@ def workspace_bytes(d, with_ctx):
     return int(lib().pe_workspace_bytes(C.byref(_dims(d)), int(with_ctx)))
 
 
-def stack_workspace_bytes(n_extra, extra, n_main, main):
+def stack_workspace_bytes(n_extra, extra, n_main, main, keep=False):
     e = C.byref(_dims(extra)) if extra is not None else None
     m = C.byref(_dims(main)) if main is not None else None
-    return int(lib().pe_stack_workspace_bytes(n_extra, e, n_main, m))
+    f = lib().pe_stack_workspace_bytes_keep if keep else lib().pe_stack_workspace_bytes
+    return int(f(n_extra, e, n_main, m))
 
 
 class Handle:

@@ -23,6 +23,7 @@ struct pe_handle {
   int sync_debug;
   int timing;                       // PE_OPT_KERNEL_TIMING
   int side_streams;                 // PE_OPT_SIDE_STREAMS
+  int stack_keep;                   // PE_OPT_STACK_KEEP_CTX
   hipStream_t side[2];              // side stream of the MSA branch / of the pair branch
   hipEvent_t side_ev[32];           // ring of fork/join events
   int side_ev_next;
@@ -1315,9 +1316,11 @@ struct StackPlan {
   size_t E;
   size_t n_pair, n_msa, n_extra;        // bytes of one pair / msa / extra-msa tensor
   size_t off_pair_saved, off_msa_saved, off_extra_saved, off_pp, off_block, block_bytes, total;
+  bool keep;                            // every block's ctx is kept: nothing is recomputed
+  size_t off_ctx, ctx_e, ctx_m;         // kept ctx slots: n_extra of ctx_e bytes, then n_main of ctx_m bytes
 };
 static size_t al256(size_t v) { return (v + 255) & ~(size_t)255; }
-static int make_stack_plan(int n_extra, const pe_dims* ex, int n_main, const pe_dims* mn, StackPlan& sp) {
+static int make_stack_plan(int n_extra, const pe_dims* ex, int n_main, const pe_dims* mn, bool keep, StackPlan& sp) {
   if (n_extra < 0 || n_main < 0 || n_extra + n_main < 1) return PE_ERR_ARG;
   if ((n_extra && !ex) || (n_main && !mn)) return PE_ERR_NULL;
   if (n_extra && pe_check_dims(ex)) return PE_ERR_DIMS;
@@ -1334,8 +1337,14 @@ static int make_stack_plan(int n_extra, const pe_dims* ex, int n_main, const pe_
   sp.off_msa_saved = off; off += sp.n_msa * (size_t)(n_main > 0 ? n_main - 1 : 0);
   sp.off_extra_saved = off; off += sp.n_extra * (size_t)n_extra;     // slot n_extra-1 = dropped final output
   sp.off_pp = off; off += 2 * (sp.n_pair + sp.n_msa + sp.n_extra);   // ping-pong cotangents
+  sp.keep = keep;
+  Plan pe_ = n_extra ? plan_for(*ex) : Plan{0, 0, 0, 0}, pm_ = n_main ? plan_for(*mn) : Plan{0, 0, 0, 0};
+  sp.ctx_e = al256(pe_.ctx_total());
+  sp.ctx_m = al256(pm_.ctx_total());
+  sp.off_ctx = off;
+  if (keep) off += sp.ctx_e * (size_t)n_extra + sp.ctx_m * (size_t)n_main;
   sp.off_block = off;
-  size_t be = n_extra ? plan_for(*ex).total(true) : 0, bm = n_main ? plan_for(*mn).total(true) : 0;
+  size_t be = n_extra ? pe_.total(!keep) : 0, bm = n_main ? pm_.total(!keep) : 0;
   sp.block_bytes = al256(be > bm ? be : bm);
   sp.total = off + sp.block_bytes;
   return PE_OK;
@@ -1358,6 +1367,10 @@ static int stack_impl(pe_handle* h, int n_extra, const pe_dims* ex, int n_main, 
   };
   auto z_in = [&](int b) -> const void* { return b == 0 ? pair_in : (const void*)pair_slot(b); };
   auto poff = [&](int b) -> long long { return b < n_extra ? pe_n * b : pe_n * n_extra + pm_n * (b - n_extra); };
+  auto ctx_of = [&](int b) -> char* {
+    if (!sp.keep) return nullptr;
+    return ws + sp.off_ctx + (b < n_extra ? sp.ctx_e * (size_t)b : sp.ctx_e * (size_t)n_extra + sp.ctx_m * (size_t)(b - n_extra));
+  };
   // forward
   for (int b = 0; b < nb; b++) {
     const bool is_e = b < n_extra;
@@ -1367,7 +1380,7 @@ static int stack_impl(pe_handle* h, int n_extra, const pe_dims* ex, int n_main, 
     else xo = (b == nb - 1) ? msa_out : (void*)(ws + sp.off_msa_saved + sp.n_msa * (size_t)(b - n_extra));
     void* zo = (b == nb - 1) ? pair_out : (void*)pair_slot(b + 1);
     int rc = block_fwd_impl<T>(h, d, x_in(b), z_in(b), is_e ? extra_mask : msa_mask, pair_mask, params + poff(b), xo, zo,
-                               nullptr, blockws, sp.block_bytes, sm, sp_);
+                               ctx_of(b), blockws, sp.block_bytes, sm, sp_);
     if (rc) return rc;
   }
   // backward
@@ -1390,7 +1403,7 @@ static int stack_impl(pe_handle* h, int n_extra, const pe_dims* ex, int n_main, 
     if (is_e) dx_in = (b == 0) ? d_extra_msa_in : (void*)de_pp[b & 1];
     else dx_in = (b == n_extra) ? d_msa_in : (void*)dm_pp[b & 1];
     int rc = block_bwd_impl<T>(h, d, x_in(b), z_in(b), is_e ? extra_mask : msa_mask, pair_mask, params + poff(b),
-                               is_e ? de : dm, dz, dx_in, dz_in, d_params + poff(b), nullptr, blockws, sp.block_bytes, sm,
+                               is_e ? de : dm, dz, dx_in, dz_in, d_params + poff(b), ctx_of(b), blockws, sp.block_bytes, sm,
                                sp_);
     if (rc) return rc;
     dz = dz_in;
@@ -1418,6 +1431,7 @@ int pe_create(pe_handle** out) {
   h->sync_debug = 0;
   h->timing = 0;
   h->side_streams = 0;
+  h->stack_keep = 0;
   h->side[0] = h->side[1] = nullptr;
   h->side_ev_next = 0;
   for (int i = 0; i < 32; i++) h->side_ev[i] = nullptr;
@@ -1446,6 +1460,7 @@ int pe_set_option(pe_handle* h, int option, int value) {
   if (option == PE_OPT_BRANCHES) { if (value < 1 || value > 3) return PE_ERR_ARG; h->branches = value; return PE_OK; }
   if (option == PE_OPT_SYNC_DEBUG) { h->sync_debug = value ? 1 : 0; return PE_OK; }
   if (option == PE_OPT_KERNEL_TIMING) { h->timing = value ? 1 : 0; return PE_OK; }
+  if (option == PE_OPT_STACK_KEEP_CTX) { h->stack_keep = value ? 1 : 0; return PE_OK; }
   if (option == PE_OPT_SIDE_STREAMS) {
     // Created on first use only: every extra stream competes for the process's few hardware
     // queues (4 by default), and two streams that share a queue serialise.
@@ -1552,7 +1567,12 @@ int pe_block_bwd(pe_handle* h, const pe_dims* dims, const void* msa_in, const vo
 
 size_t pe_stack_workspace_bytes(int n_extra, const pe_dims* extra, int n_main, const pe_dims* main_) {
   StackPlan sp;
-  if (make_stack_plan(n_extra, extra, n_main, main_, sp)) return 0;
+  if (make_stack_plan(n_extra, extra, n_main, main_, false, sp)) return 0;
+  return sp.total;
+}
+size_t pe_stack_workspace_bytes_keep(int n_extra, const pe_dims* extra, int n_main, const pe_dims* main_) {
+  StackPlan sp;
+  if (make_stack_plan(n_extra, extra, n_main, main_, true, sp)) return 0;
   return sp.total;
 }
 
@@ -1565,7 +1585,7 @@ int pe_stack_fwd_bwd(pe_handle* h, int n_extra, const pe_dims* extra, int n_main
   if (!h || !pair_in || !pair_mask || !params || !d_pair_out || !pair_out || !d_pair_in || !d_params || !workspace)
     return PE_ERR_NULL;
   StackPlan sp;
-  int rc = make_stack_plan(n_extra, extra, n_main, main_, sp);
+  int rc = make_stack_plan(n_extra, extra, n_main, main_, h->stack_keep != 0, sp);
   if (rc) return rc;
   if (n_extra && (!extra_msa_in || !extra_msa_mask || !d_extra_msa_in)) return PE_ERR_NULL;
   if (n_main && (!msa_in || !msa_mask || !d_msa_out || !msa_out || !d_msa_in)) return PE_ERR_NULL;

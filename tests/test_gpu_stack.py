@@ -18,16 +18,18 @@ def _stack_inputs(dims, n_blocks, seed, mask):
     return table, n, inp
 
 
-def _run_stack(dims, n_main, inp, two_streams=True):
+def _run_stack(dims, n_main, inp, two_streams=True, keep=False):
     dt, f32 = tdtype(dims), torch.float32
     h = pe.Handle()
+    if keep:
+        h.set_option(5, 1)      # PE_OPT_STACK_KEEP_CTX
     msa, pair = to_dev(inp["msa"], dt), to_dev(inp["pair"], dt)
     mm, pm = to_dev(inp["msa_mask"], f32), to_dev(inp["pair_mask"], f32)
     params = to_dev(inp["params"], f32)
     dmo, dzo = to_dev(inp["d_msa_out"], dt), to_dev(inp["d_pair_out"], dt)
     mo, zo, dmi, dzi = (torch.empty_like(t) for t in (msa, pair, msa, pair))
     dpar = torch.zeros_like(params)
-    ws = torch.empty(pe.stack_workspace_bytes(0, None, n_main, dims), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(pe.stack_workspace_bytes(0, None, n_main, dims, keep=keep), dtype=torch.uint8, device="cuda")
     sm = torch.cuda.Stream() if two_streams else torch.cuda.current_stream()
     sp = torch.cuda.Stream() if two_streams else sm
     torch.cuda.synchronize()
@@ -56,15 +58,17 @@ def test_stack_fp32_matches_oracle():
             assert np.max(np.abs(gg[sl] - g[sl])) / den < 1e-4, (b, e["name"])
 
 
+@pytest.mark.parametrize("keep", [False, True])
 @pytest.mark.parametrize("dtype", [0, 1])
-def test_stack_equals_chained_blocks(dtype):
-    """The stack (saved block inputs + recompute) is bit-identical to calling pe_block_fwd for every
-    block and then pe_block_bwd in reverse order; this carries the block-level parity to any depth."""
+def test_stack_equals_chained_blocks(dtype, keep):
+    """The stack (saved block inputs + recompute, or every block's activations kept) is bit-identical
+    to calling pe_block_fwd for every block and then pe_block_bwd in reverse order; this carries the
+    block-level parity to any depth."""
     dims, mask, seed = dims_for("tiny")
     dims.update(dtype=dtype, s=16, r=40)
     nb = 3
     table, n, inp = _stack_inputs(dims, nb, 12, ("last_residues", 4))
-    mo, zo, dmi, dzi, dpar = _run_stack(dims, nb, inp)
+    mo, zo, dmi, dzi, dpar = _run_stack(dims, nb, inp, keep=keep)
     dt, f32 = tdtype(dims), torch.float32
     h = pe.Handle()
     mm, pm = to_dev(inp["msa_mask"], f32), to_dev(inp["pair_mask"], f32)
