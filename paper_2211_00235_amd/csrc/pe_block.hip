@@ -444,9 +444,12 @@ template <typename T> struct Runner {
     for (int i = 0; i < nseg; i++) ra.seg[i] = segs[i];
     ra.dst = dparams;
     long long total = (long long)rows * cols;
-    ra.ylanes = nsplit >= 256 ? 64 : (nsplit >= 64 ? 16 : (nsplit >= 16 && total < 65536 ? 4 : 1));
+    // split lanes per output so that a thread has at most ~4 partial loads (all in flight at once)
+    ra.ylanes = nsplit > 64 ? 64 : (nsplit > 16 ? 16 : (nsplit > 4 ? 4 : 1));
     bool v4 = total >= 4096 && cols % 4 == 0 && stride % 4 == 0 && ((uintptr_t)part) % 16 == 0;
-    for (int i = 0; i < nseg; i++) v4 = v4 && segs[i].n_begin % 4 == 0 && segs[i].n_count % 4 == 0;
+    v4 = v4 && ((uintptr_t)dparams) % 16 == 0;
+    for (int i = 0; i < nseg; i++)
+      v4 = v4 && segs[i].n_begin % 4 == 0 && segs[i].n_count % 4 == 0 && segs[i].dst_off % 4 == 0 && segs[i].dst_ld % 4 == 0;
     ra.vec = v4 ? 4 : 1;
     pending.push_back(ra);
     (void)st;
@@ -458,18 +461,20 @@ template <typename T> struct Runner {
     for (size_t i = 0; i < pending.size(); i += REDUCE_BATCH) {
       ReduceBatch rb;
       rb.n = (int)std::min((size_t)REDUCE_BATCH, pending.size() - i);
-      long long maxblocks = 1;
+      long long nblocks = 0;
       double bytes = 0;
       for (int k = 0; k < REDUCE_BATCH; k++) {
         rb.a[k] = pending[i + (k < rb.n ? k : 0)];
+        rb.first[k] = (int)nblocks;
         if (k < rb.n) {
           long long total = (long long)rb.a[k].rows * rb.a[k].cols;
           int X = 256 / rb.a[k].ylanes * rb.a[k].vec;
-          maxblocks = std::max(maxblocks, (total + X - 1) / X);
+          nblocks += (total + X - 1) / X;
           bytes += 4.0 * total * (rb.a[k].nsplit + 2);
         }
       }
-      PE_LAUNCH("reduce_partials", 0, bytes, st, reduce_partials_kernel, dim3((unsigned)maxblocks, rb.n), dim3(256), 0, rb);
+      rb.first[REDUCE_BATCH] = (int)nblocks;
+      PE_LAUNCH("reduce_partials", 0, bytes, st, reduce_partials_kernel, dim3((unsigned)nblocks), dim3(256), 0, rb);
     }
     pending.clear();
     join_side(main_st);

@@ -825,15 +825,21 @@ struct ReduceArgs {
 // summation order (deterministic).  Up to REDUCE_BATCH independent reductions per launch
 // (blockIdx.y selects one); their destinations must not overlap.
 constexpr int REDUCE_BATCH = 8;
-struct ReduceBatch { ReduceArgs a[REDUCE_BATCH]; int n; };
+// first[k] = first workgroup of reduction k (first[n] = grid size): every workgroup has work
+struct ReduceBatch { ReduceArgs a[REDUCE_BATCH]; int first[REDUCE_BATCH + 1]; int n; };
 __global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceBatch rb) {
   __shared__ float red[256][4];
-  const ReduceArgs& a = rb.a[blockIdx.y];
+  int which = 0;
+#pragma unroll
+  for (int k = 1; k < REDUCE_BATCH; k++)
+    if (k < rb.n && (int)blockIdx.x >= rb.first[k]) which = k;
+  const ReduceArgs& a = rb.a[which];
+  const int blk = blockIdx.x - rb.first[which];
   const int Y = a.ylanes, X = 256 / Y, V = a.vec;   // V = 4: every thread owns 4 consecutive outputs (16-byte loads)
   const long long total = (long long)a.rows * a.cols;
-  if ((long long)blockIdx.x * X * V >= total) return;
+  if ((long long)blk * X * V >= total) return;
   const int x = threadIdx.x % X, y = threadIdx.x / X;
-  const long long idx = ((long long)blockIdx.x * X + x) * V;
+  const long long idx = ((long long)blk * X + x) * V;
   float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
   if (idx < total) {
     // several independent loads in flight per thread; the sum order is a fixed function of (nsplit, Y, V)
@@ -877,7 +883,14 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceBatch rb) {
     const ReduceSeg& g = a.seg[q];
     if (n >= g.n_begin && n < g.n_begin + g.n_count) {
       float* dst = a.dst + g.dst_off + (long long)m * g.dst_ld + (n - g.n_begin);
-      for (int e = 0; e < V; e++) dst[e] += s[e];
+      if (V == 4) {   // host checked: 16-byte aligned destination groups
+        f32x4 t = *reinterpret_cast<f32x4*>(dst);
+#pragma unroll
+        for (int e = 0; e < 4; e++) t[e] += s[e];
+        *reinterpret_cast<f32x4*>(dst) = t;
+      } else {
+        dst[0] += s[0];
+      }
       break;
     }
   }
