@@ -125,6 +125,16 @@ def test_masked_edge_cases():
         _assert(*check_case(dims, table, inp)[:3])
 
 
+@pytest.mark.parametrize("s,r", [(1, 1), (1, 9), (9, 1), (2, 130)])
+def test_degenerate_sizes(s, r):
+    """A single sequence, a single residue, both, and a 2-row MSA over more than one tile of
+    residues: every contraction and softmax collapses to length 1 somewhere (fp32 path)."""
+    dims, table, inp = _case("tiny", dtype=0, s=s, r=r)
+    table, n = param_table(dims)
+    inp = make_inputs(dims, table, n, ("none", 0), 23)
+    _assert(*check_case(dims, table, inp)[:3])
+
+
 def test_bad_arguments_return_errors():
     import torch
     import paper_2211_00235_amd as pe
