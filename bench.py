@@ -214,14 +214,18 @@ def main():
         k["bytes"] += e["bytes"] / 3
     dom_name = max(by_kernel, key=lambda k: by_kernel[k]["ms"])
     dom = by_kernel[dom_name]
-    if dom["flops"] > 0 and (dom["flops"] / max(dom["bytes"], 1.0)) > PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9) / 4:
-        achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
-        roof = dict(bound="mfma", achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                    frac=achieved / PEAK_BF16_TFLOPS, traffic=None)
-    else:
-        achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
-        roof = dict(bound="hbm", achieved=achieved, peak=PEAK_HBM_GBS, unit="GB/s", frac=achieved / PEAK_HBM_GBS,
+    # roofline model: the kernel's algorithmic intensity against the ridge (peak flops / peak bandwidth)
+    # decides which roof bounds it; a contraction below the ridge is bound by HBM, not by the MFMA peak
+    intensity = dom["flops"] / max(dom["bytes"], 1.0)
+    ridge = PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    tflops = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+    gbs = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
+    if dom["flops"] > 0 and intensity >= ridge:
+        roof = dict(bound="mfma", achieved=tflops, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=tflops / PEAK_BF16_TFLOPS,
                     traffic=None)
+    else:
+        roof = dict(bound="hbm", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s", frac=gbs / PEAK_HBM_GBS, traffic=None)
+    roof.update(flop_per_byte=intensity, ridge_flop_per_byte=ridge, tflops=tflops, mfma_peak_frac=tflops / PEAK_BF16_TFLOPS)
     roof["traffic"] = profiled_traffic(dom_name) if args.workload == "af2_initial" else None
     roof.update(kernel=dom_name, launches_per_step=dom["launches"], avg_launch_us=1e3 * dom["ms"] / max(dom["launches"], 1),
                 kernel_ms_per_step=dom["ms"])
