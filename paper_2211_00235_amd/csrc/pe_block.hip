@@ -792,17 +792,27 @@ template <typename T> struct Runner {
   AttnGeom geom_tae() const { return AttnGeom{d.r, d.r, 1, d.r, 1, d.r, pair_mask, 1,
                                                "attn_fwd tae", "attn_dq tae", "attn_dkv tae"}; }
 
-  // MSA stack: row attention (bias read from bias_pair), column attention, transition
-  void fwd_msa_stack(const T* bias_pair, T* msa_out) {
-    attn_sub_fwd(sm, am, PL.row, W.row, C.row, msa_in, C.m1, Mm, d.c_m, d.h_msa, d.d_msa, geom_row(), bias_pair,
-                 PL.row.ln_z_g, PL.row.ln_z_b);
-    if (d.col_global) gcol_sub_fwd(sm, C.m1, C.m2);
-    else attn_sub_fwd(sm, am, PL.col, W.col, C.col, C.m1, C.m2, Mm, d.c_m, d.h_msa, d.d_msa, geom_col(), nullptr, 0, 0);
-    trans_sub_fwd(sm, PL.mtrans, W.mt, C.mt, C.m2, C.m3, Mm, d.c_m);
-    if (!dry && !err && msa_out) {
-      if (hipMemcpyAsync(msa_out, C.m3, (size_t)Mm * d.c_m * sizeof(T), hipMemcpyDeviceToDevice, sm) != hipSuccess)
-        fail("copy msa_out");
+  // MSA stack: row attention (bias read from bias_pair), column attention, transition.  Steps can
+  // be enqueued one at a time so that the host alternates between the two streams (a stream whose
+  // kernels are enqueued late starts late: the host needs ~10 us per launch).
+  static constexpr int MSA_STEPS = 3, PAIR_STEPS = 5;
+  void fwd_msa_step(int i, const T* bias_pair, T* msa_out) {
+    if (i == 0) {
+      attn_sub_fwd(sm, am, PL.row, W.row, C.row, msa_in, C.m1, Mm, d.c_m, d.h_msa, d.d_msa, geom_row(), bias_pair,
+                   PL.row.ln_z_g, PL.row.ln_z_b);
+    } else if (i == 1) {
+      if (d.col_global) gcol_sub_fwd(sm, C.m1, C.m2);
+      else attn_sub_fwd(sm, am, PL.col, W.col, C.col, C.m1, C.m2, Mm, d.c_m, d.h_msa, d.d_msa, geom_col(), nullptr, 0, 0);
+    } else {
+      trans_sub_fwd(sm, PL.mtrans, W.mt, C.mt, C.m2, C.m3, Mm, d.c_m);
+      if (!dry && !err && msa_out) {
+        if (hipMemcpyAsync(msa_out, C.m3, (size_t)Mm * d.c_m * sizeof(T), hipMemcpyDeviceToDevice, sm) != hipSuccess)
+          fail("copy msa_out");
+      }
     }
+  }
+  void fwd_msa_stack(const T* bias_pair, T* msa_out) {
+    for (int i = 0; i < MSA_STEPS; i++) fwd_msa_step(i, bias_pair, msa_out);
   }
   // outer product mean of x, up to its output projection
   void fwd_opm_outer(const T* x) {
@@ -850,14 +860,19 @@ template <typename T> struct Runner {
     run_prep(false);
     fwd_pair_stack(pair_in, C.z5);
   }
+  void fwd_pair_step(int i, const T* z_in, T* z_out) {
+    switch (i) {
+      case 0: trimul_sub_fwd(sp, PL.tmo, W.tmo, C.tmo, z_in, C.z1, true); break;
+      case 1: trimul_sub_fwd(sp, PL.tmi, W.tmi, C.tmi, C.z1, C.z2, false); break;
+      case 2: attn_sub_fwd(sp, ap, PL.tas, W.tas, C.tas, C.z2, C.z3, Mz, d.c_z, d.h_pair, d.d_pair, geom_tas(), C.z2,
+                           PL.tas.ln_g, PL.tas.ln_b); break;
+      case 3: attn_sub_fwd(sp, ap, PL.tae, W.tae, C.tae, C.z3, C.z4, Mz, d.c_z, d.h_pair, d.d_pair, geom_tae(), C.z3,
+                           PL.tae.ln_g, PL.tae.ln_b); break;
+      default: trans_sub_fwd(sp, PL.ptrans, W.pt, C.pt, C.z4, z_out, Mz, d.c_z); break;
+    }
+  }
   void fwd_pair_stack(const T* z_in, T* z_out) {
-    trimul_sub_fwd(sp, PL.tmo, W.tmo, C.tmo, z_in, C.z1, true);
-    trimul_sub_fwd(sp, PL.tmi, W.tmi, C.tmi, C.z1, C.z2, false);
-    attn_sub_fwd(sp, ap, PL.tas, W.tas, C.tas, C.z2, C.z3, Mz, d.c_z, d.h_pair, d.d_pair, geom_tas(), C.z2, PL.tas.ln_g,
-                 PL.tas.ln_b);
-    attn_sub_fwd(sp, ap, PL.tae, W.tae, C.tae, C.z3, C.z4, Mz, d.c_z, d.h_pair, d.d_pair, geom_tae(), C.z3, PL.tae.ln_g,
-                 PL.tae.ln_b);
-    trans_sub_fwd(sp, PL.ptrans, W.pt, C.pt, C.z4, z_out, Mz, d.c_z);
+    for (int i = 0; i < PAIR_STEPS; i++) fwd_pair_step(i, z_in, z_out);
   }
 
   // ---- sub-operations: backward --------------------------------------------
@@ -1096,27 +1111,57 @@ template <typename T> struct Runner {
     }
   }
   // MSA stack backward, in place on gm; dz_bias receives the gradient through the row-attention bias
-  void bwd_msa_stack(T* gm, const T* bias_pair, T* dz_bias) {
+  void bwd_msa_step(int i, T* gm, const T* bias_pair, T* dz_bias) {
     const int cm = d.c_m;
-    trans_sub_bwd(sm, am, PL.mtrans, W.mt, C.mt, C.m2, gm, Mm, cm);
-    if (d.col_global) gcol_sub_bwd(sm, am, C.m1, gm);
-    else attn_sub_bwd(sm, am, PL.col, W.col, C.col, C.m1, gm, Mm, cm, d.h_msa, d.d_msa, geom_col(), nullptr, 0, 0, nullptr, nullptr);
-    attn_sub_bwd(sm, am, PL.row, W.row, C.row, msa_in, gm, Mm, cm, d.h_msa, d.d_msa, geom_row(), bias_pair, PL.row.ln_z_g,
-                 PL.row.ln_z_b, nullptr, dz_bias);
+    if (i == 0) {
+      trans_sub_bwd(sm, am, PL.mtrans, W.mt, C.mt, C.m2, gm, Mm, cm);
+    } else if (i == 1) {
+      if (d.col_global) gcol_sub_bwd(sm, am, C.m1, gm);
+      else attn_sub_bwd(sm, am, PL.col, W.col, C.col, C.m1, gm, Mm, cm, d.h_msa, d.d_msa, geom_col(), nullptr, 0, 0, nullptr, nullptr);
+    } else {
+      attn_sub_bwd(sm, am, PL.row, W.row, C.row, msa_in, gm, Mm, cm, d.h_msa, d.d_msa, geom_row(), bias_pair, PL.row.ln_z_g,
+                   PL.row.ln_z_b, nullptr, dz_bias);
+    }
+  }
+  void bwd_msa_stack(T* gm, const T* bias_pair, T* dz_bias) {
+    for (int i = 0; i < MSA_STEPS; i++) bwd_msa_step(i, gm, bias_pair, dz_bias);
   }
   void bwd_pair(const T* d_pair_out, T* gz) { bwd_pair_stack(d_pair_out, gz, pair_in); }
-  void bwd_pair_stack(const T* d_pair_out, T* gz, const T* z_in) {
-    if (!dry && !err) {
-      if (hipMemcpyAsync(gz, d_pair_out, (size_t)Mz * d.c_z * sizeof(T), hipMemcpyDeviceToDevice, sp) != hipSuccess)
-        fail("copy gz");
+  void bwd_pair_step(int i, const T* d_pair_out, T* gz, const T* z_in) {
+    switch (i) {
+      case 0:
+        if (!dry && !err) {
+          if (hipMemcpyAsync(gz, d_pair_out, (size_t)Mz * d.c_z * sizeof(T), hipMemcpyDeviceToDevice, sp) != hipSuccess)
+            fail("copy gz");
+        }
+        trans_sub_bwd(sp, ap, PL.ptrans, W.pt, C.pt, C.z4, gz, Mz, d.c_z);
+        break;
+      case 1: attn_sub_bwd(sp, ap, PL.tae, W.tae, C.tae, C.z3, gz, Mz, d.c_z, d.h_pair, d.d_pair, geom_tae(), C.z3,
+                           PL.tae.ln_g, PL.tae.ln_b, gz, gz); break;
+      case 2: attn_sub_bwd(sp, ap, PL.tas, W.tas, C.tas, C.z2, gz, Mz, d.c_z, d.h_pair, d.d_pair, geom_tas(), C.z2,
+                           PL.tas.ln_g, PL.tas.ln_b, gz, gz); break;
+      case 3: trimul_sub_bwd(sp, ap, PL.tmi, W.tmi, C.tmi, C.z1, gz, false); break;
+      default: trimul_sub_bwd(sp, ap, PL.tmo, W.tmo, C.tmo, z_in, gz, true); break;
     }
-    trans_sub_bwd(sp, ap, PL.ptrans, W.pt, C.pt, C.z4, gz, Mz, d.c_z);
-    attn_sub_bwd(sp, ap, PL.tae, W.tae, C.tae, C.z3, gz, Mz, d.c_z, d.h_pair, d.d_pair, geom_tae(), C.z3, PL.tae.ln_g,
-                 PL.tae.ln_b, gz, gz);
-    attn_sub_bwd(sp, ap, PL.tas, W.tas, C.tas, C.z2, gz, Mz, d.c_z, d.h_pair, d.d_pair, geom_tas(), C.z2, PL.tas.ln_g,
-                 PL.tas.ln_b, gz, gz);
-    trimul_sub_bwd(sp, ap, PL.tmi, W.tmi, C.tmi, C.z1, gz, false);
-    trimul_sub_bwd(sp, ap, PL.tmo, W.tmo, C.tmo, z_in, gz, true);
+  }
+  void bwd_pair_stack(const T* d_pair_out, T* gz, const T* z_in) {
+    for (int i = 0; i < PAIR_STEPS; i++) bwd_pair_step(i, d_pair_out, gz, z_in);
+  }
+
+  // The two stacks side by side, enqueued alternately (pair first: it is the longer one).
+  // with_opm: the outer product mean of the MSA stack's output follows the stack on stream_msa.
+  void fwd_stacks(bool do_m, bool do_p, const T* bias_pair, const T* z_in, T* msa_out, T* z_out, bool with_opm) {
+    for (int i = 0; i < PAIR_STEPS; i++) {
+      if (do_p) fwd_pair_step(i, z_in, z_out);
+      if (do_m && i < MSA_STEPS) fwd_msa_step(i, bias_pair, msa_out);
+      if (do_m && i == MSA_STEPS && with_opm) fwd_opm_outer(C.m3);
+    }
+  }
+  void bwd_stacks(bool do_m, bool do_p, const T* d_pair_out, T* gz, const T* z_in, T* gm, const T* bias_pair, T* dz_bias) {
+    for (int i = 0; i < PAIR_STEPS; i++) {
+      if (do_p) bwd_pair_step(i, d_pair_out, gz, z_in);
+      if (do_m && i < MSA_STEPS) bwd_msa_step(i, gm, bias_pair, dz_bias);
+    }
   }
 };
 
@@ -1187,8 +1232,9 @@ static int run_forward(Runner<T>& R, pe_handle* h, const pe_dims& d, T* msa_out,
   hipStream_t sm = R.sm, sp = R.sp;
   const bool do_m = h->branches & 1, do_p = h->branches & 2;
   if (d.variant == PE_VARIANT_PARALLEL) {
-    if (do_p) R.fwd_pair();
-    if (do_m) R.fwd_msa(msa_out);
+    if (do_p) R.run_prep(false);
+    if (do_m) R.run_prep(true);
+    R.fwd_stacks(do_m, do_p, R.pair_in, R.pair_in, msa_out, R.C.z5, true);
     if (do_p && !ev_link(h, 1, sp, sm)) return PE_ERR_HIP;
     if (pair_out) {
       if (do_m && do_p) R.fwd_opm_project(pair_out, R.C.z5);
@@ -1216,8 +1262,7 @@ static int run_forward(Runner<T>& R, pe_handle* h, const pe_dims& d, T* msa_out,
     R.fwd_opm_outer(R.msa_in);
     R.fwd_opm_project(R.C.z0, R.pair_in);
     if (!ev_link(h, 1, sm, sp)) return PE_ERR_HIP;
-    R.fwd_msa_stack(R.C.z0, msa_out);
-    R.fwd_pair_stack(R.C.z0, z_out);
+    R.fwd_stacks(true, true, R.C.z0, R.C.z0, msa_out, z_out, false);
     if (!ev_link(h, 2, sp, sm)) return PE_ERR_HIP;
     if (!ev_link(h, 3, sm, sp)) return PE_ERR_HIP;
   }
@@ -1257,8 +1302,9 @@ static int block_bwd_impl(pe_handle* h, const pe_dims& d, const void* msa_in, co
   if (!ev_link(h, 0, sm, sp)) return PE_ERR_HIP;
   if (ctx == nullptr) {   // recompute the forward into the internal ctx (else: ctx also holds the prepared weights)
     if (d.variant == PE_VARIANT_PARALLEL) {
-      if (do_p) R.fwd_pair();
-      if (do_m) R.fwd_msa(nullptr);   // the outer-product projection is not needed for the backward pass
+      if (do_p) R.run_prep(false);
+      if (do_m) R.run_prep(true);
+      R.fwd_stacks(do_m, do_p, R.pair_in, R.pair_in, nullptr, R.C.z5, true);   // the projection is not needed here
     } else {
       int rc = run_forward<T>(R, h, d, nullptr, nullptr);
       if (rc) return rc;
@@ -1269,8 +1315,12 @@ static int block_bwd_impl(pe_handle* h, const pe_dims& d, const void* msa_in, co
   T* gz = (T*)R.ap.alloc((size_t)n * sizeof(T));
   T* gm = (T*)d_msa_in;
   if (d.variant == PE_VARIANT_PARALLEL) {
-    if (do_p) R.bwd_pair((const T*)d_pair_out, gz);
-    if (do_m) R.bwd_msa((const T*)d_msa_out, (const T*)d_pair_out, gm, dzb);
+    if (do_p) R.bwd_pair_step(0, (const T*)d_pair_out, gz, R.pair_in);
+    if (do_m) R.bwd_opm((const T*)d_pair_out, R.C.m3, (const T*)d_msa_out, gm);
+    for (int i = 1; i < Runner<T>::PAIR_STEPS; i++) {
+      if (do_p) R.bwd_pair_step(i, (const T*)d_pair_out, gz, R.pair_in);
+      if (do_m && i - 1 < Runner<T>::MSA_STEPS) R.bwd_msa_step(i - 1, gm, R.pair_in, dzb);
+    }
     if (do_m && !ev_link(h, 1, sm, sp)) return PE_ERR_HIP;
     if (!R.err) {
       if (do_m && do_p) {
@@ -1300,8 +1350,7 @@ static int block_bwd_impl(pe_handle* h, const pe_dims& d, const void* msa_in, co
     // summed, and that sum is also the cotangent of the outer product mean of the input MSA
     if (!R.err && !hip_ok(h, hipMemcpyAsync(gm, d_msa_out, (size_t)R.Mm * d.c_m * sizeof(T), hipMemcpyDeviceToDevice, sm), "copy"))
       return PE_ERR_HIP;
-    R.bwd_msa_stack(gm, R.C.z0, dzb);
-    R.bwd_pair_stack((const T*)d_pair_out, gz, R.C.z0);
+    R.bwd_stacks(true, true, (const T*)d_pair_out, gz, R.C.z0, gm, R.C.z0, dzb);
     if (!ev_link(h, 1, sp, sm)) return PE_ERR_HIP;
     if (!R.err) {
       hipLaunchKernelGGL(add2_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, sm, gz, dzb, (T*)d_pair_in, n);
