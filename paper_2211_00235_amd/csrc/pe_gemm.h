@@ -628,6 +628,9 @@ static inline bool launch_gemm_spec(hipStream_t st, dim3 grid, const Operand& A,
   PE_GEMM_SPEC(EF_RELUMASK)
   PE_GEMM_SPEC(EF_OM2 | EF_ON2 | EF_BIASN)
   PE_GEMM_SPEC(EF_ACC | EF_BIASM)
+  PE_GEMM_SPEC(EF_BIASN | EF_ROWSCALE)
+  PE_GEMM_SPEC(EF_BIASN | EF_AUX | EF_MUL | EF_RES)
+  PE_GEMM_SPEC(EF_OM2 | EF_ON2 | EF_ROWSCALE)
 #undef PE_GEMM_SPEC
   return false;
 }
