@@ -533,10 +533,11 @@ template <typename T> struct Runner {
     if (dry || err) return;
     GemmShape sh{M, N, K, batch, 0};
     prof_begin(st);
-    bool al = false;
-    int rc = launch_gemm<T, EpiGeneric<T>>(st, A, akc, B, bkc, sh, e, &al);
+    bool al = false, narrow = false;
+    int rc = launch_gemm<T, EpiGeneric<T>>(st, A, akc, B, bkc, sh, e, &al, &narrow);
     char kn[64];
-    snprintf(kn, sizeof(kn), "gemm_kernel<%s,%s,%s,EpiGeneric>", akc ? "kc" : "xc", bkc ? "kc" : "xc", al ? "vec" : "elem");
+    if (narrow) snprintf(kn, sizeof(kn), "gemm64_kernel<EpiGeneric>");
+    else snprintf(kn, sizeof(kn), "gemm_kernel<%s,%s,%s,EpiGeneric>", akc ? "kc" : "xc", bkc ? "kc" : "xc", al ? "vec" : "elem");
     prof_end(st, what, kn, 2.0 * M * N * K * batch, ((double)M * K + (double)N * K + (double)M * N) * batch * sizeof(T));
     if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = std::string("gemm operand alignment: ") + what; return; }
     check(what);

@@ -608,6 +608,140 @@ template <typename T> static inline bool gemm_operand_ok(const Operand& o, bool 
   return true;
 }
 
+// ---------------------------------------------------------------------------
+// Narrow-output variant (N <= 128, k-contiguous aligned operands, vector epilogue, no batch):
+// 64 x 128 block tile, wave w owns all 64 rows of columns [32w, 32w+32).  A 128-row tile would
+// give such a GEMM only M/128 workgroups (2 per CU at M = 65536), too few to overlap one
+// workgroup's loads with another's arithmetic and stores; this one doubles them and needs ~100
+// registers.
+// ---------------------------------------------------------------------------
+template <typename T, class Epi, int F>
+__global__ __launch_bounds__(256) void gemm64_kernel(Operand A, Operand B, GemmShape sh, Epi epi) {
+  typedef GemmCfg<T> C;
+  typedef Mma<T> MM;
+  typedef typename Vec16<T>::type V;
+  constexpr int BM = 64;
+  __shared__ __attribute__((aligned(16))) T lds_all[(BM + C::BN) * C::LDSS];   // 27 KB
+  T* lds_a = lds_all;
+  T* lds_b = lds_all + BM * C::LDSS;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int m0 = blockIdx.x * BM;
+  const T* pa = (const T*)A.ptr;
+  const T* pb = (const T*)B.ptr;
+
+  f32x16 acc[2];
+#pragma unroll
+  for (int i = 0; i < 2; i++)
+#pragma unroll
+    for (int e = 0; e < 16; e++) acc[i][e] = 0.0f;
+
+  // per-thread addressing: k-vector kv = tid % 8, rows tid / 8 + 32 i (2 rows of A, 4 of B)
+  const int kv = tid & 7;
+  long long aa[2];
+  bool aok[2];
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+    const int m = m0 + (tid >> 3) + 32 * i;
+    aok[i] = m < sh.M;
+    const int mc = aok[i] ? m : 0;
+    aa[i] = (A.x_in >= (1 << 30)) ? (long long)mc * A.x_stride
+                                  : (long long)((unsigned)mc / (unsigned)A.x_in) * A.x_outer +
+                                        (long long)((unsigned)mc % (unsigned)A.x_in) * A.x_stride;
+  }
+  RowAddr<T, true> rowb;
+  rowb.init(B, 0, sh.N, tid);
+  V ra[2], rb[4];
+  auto load_a = [&](int k0) {
+    const int k = k0 + kv * C::VEC;
+    const long long ka = gemm_kaddr(A, k);
+#pragma unroll
+    for (int i = 0; i < 2; i++) {
+      V v;
+#pragma unroll
+      for (int e = 0; e < C::VEC; e++) v[e] = from_f<T>(0.0f);
+      if (k < sh.K && aok[i]) v = *reinterpret_cast<const V*>(pa + aa[i] + ka);
+      ra[i] = v;
+    }
+  };
+  load_a(0);
+  gemm_load_tile<T, true, true>(rb, pb, B, rowb, sh.N, 0, sh.K, tid);
+  for (int k0 = 0; k0 < sh.K; k0 += C::BK) {
+    __syncthreads();  // previous tile fully consumed
+#pragma unroll
+    for (int i = 0; i < 2; i++) *reinterpret_cast<V*>(lds_a + C::off((tid >> 3) + 32 * i, kv, 0)) = ra[i];
+    gemm_store_tile<T, true>(rb, lds_b, tid);
+    __syncthreads();
+    if (k0 + C::BK < sh.K) {
+      load_a(k0 + C::BK);
+      gemm_load_tile<T, true, true>(rb, pb, B, rowb, sh.N, k0 + C::BK, sh.K, tid);
+    }
+#pragma unroll
+    for (int kk = 0; kk < C::BK / MM::KSTEP; kk++) {
+      const int eo = kk * MM::KSTEP + g * MM::KP;
+      typename MM::frag bf = MM::load(lds_b + C::off(wave * 32 + l32, eo / C::VEC, eo % C::VEC));
+#pragma unroll
+      for (int t = 0; t < 2; t++)
+        MM::mma(acc[t], MM::load(lds_a + C::off(t * 32 + l32, eo / C::VEC, eo % C::VEC)), bf);
+    }
+  }
+
+  // wave-private staging of the 32 x 32 sub-tiles, then 8 consecutive columns per lane
+  constexpr int WS = 32 + 4;
+  static_assert(4 * 32 * WS * sizeof(float) <= (BM + C::BN) * C::LDSS * sizeof(T), "stage tiles must fit");
+  float* stage = reinterpret_cast<float*>(lds_all) + wave * 32 * WS;
+  const int c8 = (lane & 3) * 8, n = wave * 32 + c8;
+  typename Epi::ColV cv;
+  if (n < sh.N) epi.template colv<F>(n, cv);
+  __syncthreads();   // all waves are done with the operand tiles
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+#pragma unroll
+    for (int a = 0; a < 16; a++) stage[acc_row(g, a) * WS + l32] = acc[i][a];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int it = 0; it < 2; it++) {
+      const int row = (lane >> 2) + it * 16;
+      const int m = m0 + i * 32 + row;
+      if (m < sh.M && n < sh.N) {
+        float vals[8];
+        f32x4 lo = *reinterpret_cast<const f32x4*>(stage + row * WS + c8);
+        f32x4 hi = *reinterpret_cast<const f32x4*>(stage + row * WS + c8 + 4);
+#pragma unroll
+        for (int e = 0; e < 4; e++) { vals[e] = lo[e]; vals[4 + e] = hi[e]; }
+        epi.template vec8<F>(0, m, n, cv, vals);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+}
+
+// the narrow-output kernel for the feature sets that occur with N <= 128 (else: not taken)
+template <typename T, class Epi>
+static inline bool launch_gemm64(hipStream_t st, const Operand& A, const Operand& B, const GemmShape& sh, const Epi& epi) {
+  if constexpr (Epi::HAS_COLSUM) return false;
+  const int f = epi.features();
+  dim3 grid((unsigned)((sh.M + 63) / 64)), block(256);
+#define PE_GEMM64_SPEC(S)                                                                         \
+  if ((f & ~(S)) == 0) {                                                                          \
+    hipLaunchKernelGGL((gemm64_kernel<T, Epi, (S)>), grid, block, 0, st, A, B, sh, epi);           \
+    return true;                                                                                  \
+  }
+  PE_GEMM64_SPEC(0)
+  PE_GEMM64_SPEC(EF_BIASN | EF_RES)
+  PE_GEMM64_SPEC(EF_BIASN | EF_ACT)
+  PE_GEMM64_SPEC(EF_ACC | EF_BIASM)
+  PE_GEMM64_SPEC(EF_OM2 | EF_ON2 | EF_BIASN)
+  PE_GEMM64_SPEC(EF_BIASN | EF_AUX | EF_MUL | EF_RES)
+  PE_GEMM64_SPEC(EF_BIASN | EF_ROWSCALE)
+#undef PE_GEMM64_SPEC
+  return false;
+}
+
 // Feature sets with a kernel of their own (k-contiguous operands, vector epilogue): a launch takes
 // the first one that covers what its epilogue uses, else the general kernel.
 template <typename T, class Epi>
@@ -650,7 +784,7 @@ static inline void launch_gemm_al(hipStream_t st, dim3 grid, const Operand& A, b
 // element-wise loader and the per-element epilogue: same tiles, same arithmetic, slower.
 template <typename T, class Epi>
 static inline int launch_gemm(hipStream_t st, const Operand& A, bool a_kc, const Operand& B, bool b_kc,
-                              const GemmShape& shape, const Epi& epi, bool* used_vec = nullptr) {
+                              const GemmShape& shape, const Epi& epi, bool* used_vec = nullptr, bool* used_narrow = nullptr) {
   GemmShape sh = shape;
   if (sh.M <= 0 || sh.N <= 0 || sh.batch <= 0) return 0;
   if (a_kc ? A.k_stride != 1 : A.x_stride != 1) return -1;
@@ -665,6 +799,13 @@ static inline int launch_gemm(hipStream_t st, const Operand& A, bool a_kc, const
   const long long gm_ = 8 * ((um + 7) / 8) * NTn_, gn_ = 8 * ((un + 7) / 8) * NTm_;
   sh.unit_n = gn_ < gm_ ? 1 : 0;
   dim3 grid((unsigned)(sh.unit_n ? gn_ : gm_));
+  // narrow outputs of tall GEMMs: 64-row tiles (twice the workgroups)
+  const bool narrow = ve && a_kc && b_kc && sh.batch == 1 && sh.k_chunk == 0 && sh.N <= 128 && sh.M >= 128 * 256;
+  if (used_narrow) *used_narrow = false;
+  if (narrow && launch_gemm64<T, Epi>(st, A, B, sh, epi)) {
+    if (used_narrow) *used_narrow = true;
+    return hipGetLastError() == hipSuccess ? 0 : -2;
+  }
   if (ve) launch_gemm_al<T, true, true, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);
   else if (al) launch_gemm_al<T, true, false, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);
   else launch_gemm_al<T, false, false, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);
