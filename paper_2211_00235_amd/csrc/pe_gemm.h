@@ -723,7 +723,9 @@ __global__ __launch_bounds__(256) void gemm64_kernel(Operand A, Operand B, GemmS
 // the narrow-output kernel for the feature sets that occur with N <= 128 (else: not taken)
 template <typename T, class Epi>
 static inline bool launch_gemm64(hipStream_t st, const Operand& A, const Operand& B, const GemmShape& sh, const Epi& epi) {
-  if constexpr (Epi::HAS_COLSUM) return false;
+  if constexpr (Epi::HAS_COLSUM) {
+    return false;   // split-K partials: not for this kernel (and no instantiations for that epilogue)
+  } else {
   const int f = epi.features();
   dim3 grid((unsigned)((sh.M + 63) / 64)), block(256);
 #define PE_GEMM64_SPEC(S)                                                                         \
@@ -740,6 +742,7 @@ static inline bool launch_gemm64(hipStream_t st, const Operand& A, const Operand
   PE_GEMM64_SPEC(EF_BIASN | EF_ROWSCALE)
 #undef PE_GEMM64_SPEC
   return false;
+  }
 }
 
 // Feature sets with a kernel of their own (k-contiguous operands, vector epilogue): a launch takes
@@ -747,7 +750,9 @@ static inline bool launch_gemm64(hipStream_t st, const Operand& A, const Operand
 template <typename T, class Epi>
 static inline bool launch_gemm_spec(hipStream_t st, dim3 grid, const Operand& A, const Operand& B, const GemmShape& sh,
                                     const Epi& epi) {
-  if constexpr (Epi::HAS_COLSUM) return false;   // split-K partials: one kernel
+  if constexpr (Epi::HAS_COLSUM) {
+    return false;   // split-K partials: one kernel
+  } else {
   const int f = epi.features();
   dim3 block(256);
 #define PE_GEMM_SPEC(S)                                                                                     \
@@ -767,6 +772,7 @@ static inline bool launch_gemm_spec(hipStream_t st, dim3 grid, const Operand& A,
   PE_GEMM_SPEC(EF_OM2 | EF_ON2 | EF_ROWSCALE)
 #undef PE_GEMM_SPEC
   return false;
+  }
 }
 
 template <typename T, bool AL, bool VE, class Epi>
