@@ -44,7 +44,10 @@ def test_param_table_matches_oracle_layout(L, name):
 def test_dims_validation(L):
     d = dict(CONFIGS["af2_initial"][0])
     assert pe.check_dims(d) == 0
-    for key, bad in (("c_m", 250), ("d_msa", 64), ("dtype", 7), ("s", 0), ("c_z", 512), ("h_msa", 16)):
+    for v in (1, 2):
+        assert pe.check_dims(dict(d, variant=v)) == 0
+    for key, bad in (("c_m", 250), ("d_msa", 64), ("dtype", 7), ("s", 0), ("c_z", 512), ("h_msa", 16), ("variant", 3),
+                     ("variant", -1)):
         dd = dict(d)
         dd[key] = bad
         assert pe.check_dims(dd) == -2, key
@@ -59,6 +62,12 @@ def test_sizes_are_consistent(L):
     end = max(e["offset_bytes"] + e["count"] * (2 if e["dtype"] == 1 else 4) for e in tab)
     assert end <= pe.ctx_bytes(d)
     assert pe.stack_workspace_bytes(0, None, 2, d) > pe.workspace_bytes(d, 1)
+    # keeping every block's ctx: room for n ctx slots instead of one internal ctx
+    keep = pe.stack_workspace_bytes(0, None, 3, d, keep=True)
+    assert keep >= pe.stack_workspace_bytes(0, None, 3, d) + 2 * pe.ctx_bytes(d) - 4096
+    # the orderings with the outer product mean in front save one more pair tensor (z0)
+    assert pe.ctx_bytes(dict(d, variant=1)) > pe.ctx_bytes(d)
+    assert pe.param_count(dict(d, variant=2)) == pe.param_count(d)
 
 
 def test_null_and_error_strings(L):
