@@ -762,9 +762,12 @@ template <typename T> struct Runner {
     }
     if (!dry && !err) {
       size_t lds = (size_t)64 * (ct + 1) * sizeof(float);
-      if (Mz % 4 == 0 && ct % 8 == 0)
-        PE_LAUNCH("ln_cmajor_fwd", 0, 2.0 * Mz * ct * sizeof(T), st, ln_cmajor_fwd_fast_kernel<T>, dim3((unsigned)((Mz + 63) / 64)), dim3(256), lds, c.x_t,
-                  P(p.ln_out_g), P(p.ln_out_b), c.xhat, c.stats_out, Mz, ct, d.ln_eps);
+#define PE_LNC_FWD(N) PE_LAUNCH("ln_cmajor_fwd", 0, 2.0 * Mz * ct * sizeof(T), st, (ln_cmajor_fwd_fast_kernel<T, N>), dim3((unsigned)((Mz + 63) / 64)), dim3(256), lds, c.x_t, P(p.ln_out_g), P(p.ln_out_b), c.xhat, c.stats_out, Mz, ct, d.ln_eps)
+      if (Mz % 4 == 0 && ct % 8 == 0) {
+        const int nit = (ct + 15) / 16;   // c_tri <= 192
+        if (nit <= 2) PE_LNC_FWD(2); else if (nit <= 4) PE_LNC_FWD(4); else if (nit <= 8) PE_LNC_FWD(8); else PE_LNC_FWD(12);
+      }
+#undef PE_LNC_FWD
       else
         PE_LAUNCH("ln_cmajor_fwd", 0, 2.0 * Mz * ct * sizeof(T), st, ln_cmajor_fwd_kernel<T>, dim3((unsigned)((Mz + 63) / 64)), dim3(256), lds, c.x_t,
                   P(p.ln_out_g), P(p.ln_out_b), c.xhat, c.stats_out, Mz, ct, d.ln_eps);
@@ -1007,9 +1010,12 @@ template <typename T> struct Runner {
       float* part = (float*)ar.alloc((size_t)grid * 2 * ct * sizeof(float));
       if (!dry && !err) {
         size_t lds = (size_t)64 * (ct + 1) * sizeof(float);
-        if (Mz % 4 == 0 && ct % 8 == 0)
-          PE_LAUNCH("ln_cmajor_bwd", 0, 3.0 * Mz * ct * sizeof(T), st, ln_cmajor_bwd_fast_kernel<T>, dim3(grid), dim3(256), lds, dxh_o, c.x_t, c.stats_out,
-                    P(p.ln_out_g), dx_t, part, Mz, ct);
+#define PE_LNC_BWD(N) PE_LAUNCH("ln_cmajor_bwd", 0, 3.0 * Mz * ct * sizeof(T), st, (ln_cmajor_bwd_fast_kernel<T, N>), dim3(grid), dim3(256), lds, dxh_o, c.x_t, c.stats_out, P(p.ln_out_g), dx_t, part, Mz, ct)
+        if (Mz % 4 == 0 && ct % 8 == 0) {
+          const int nit = (ct + 15) / 16;   // c_tri <= 192
+          if (nit <= 2) PE_LNC_BWD(2); else if (nit <= 4) PE_LNC_BWD(4); else if (nit <= 8) PE_LNC_BWD(8); else PE_LNC_BWD(12);
+        }
+#undef PE_LNC_BWD
         else
           PE_LAUNCH("ln_cmajor_bwd", 0, 3.0 * Mz * ct * sizeof(T), st, ln_cmajor_bwd_kernel<T>, dim3(grid), dim3(256), lds, dxh_o, c.x_t, c.stats_out,
                     P(p.ln_out_g), dx_t, part, Mz, ct);

@@ -376,7 +376,10 @@ __global__ __launch_bounds__(256) void ln_cmajor_bwd_kernel(const T* dy, const T
 // Fast forms for M % 4 == 0 and C % 8 == 0: thread (pl = tid%16, cl = tid/16) moves 4
 // consecutive positions of channel cl, cl+16, .. per load (8 / 16 bytes per lane, 128 / 256
 // bytes per 16 lanes); the channel-last side moves 8 channels per lane.
-template <typename T>
+// NIT = ceil(C / 16), the number of channels a thread walks, as a compile-time constant: the loops
+// are unrolled, all of a thread's loads are issued before the first use (a loop with a run-time
+// trip count waits for memory once per channel) and the backward pass keeps x in registers.
+template <typename T, int NIT>
 __global__ __launch_bounds__(256) void ln_cmajor_fwd_fast_kernel(const T* xt, const float* gamma, const float* beta,
                                                                  T* y, float* stats, long long M, int C, float eps) {
   extern __shared__ float tile[];   // [64][C+1]
@@ -385,11 +388,21 @@ __global__ __launch_bounds__(256) void ln_cmajor_fwd_fast_kernel(const T* xt, co
   const long long m0 = (long long)blockIdx.x * 64, mb = m0 + 4 * pl;
   const bool ok = mb < M;
   float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-  for (int c = cl; c < C; c += 16) {
-    float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    if (ok) load4<T>(xt + (long long)c * M + mb, v);
+  float xv[NIT][4];
 #pragma unroll
-    for (int k = 0; k < 4; k++) { tile[(4 * pl + k) * ld + c] = v[k]; s[k] += v[k]; }
+  for (int it = 0; it < NIT; it++) {
+    const int c = cl + 16 * it;
+#pragma unroll
+    for (int k = 0; k < 4; k++) xv[it][k] = 0.0f;
+    if (ok && c < C) load4<T>(xt + (long long)c * M + mb, xv[it]);
+  }
+#pragma unroll
+  for (int it = 0; it < NIT; it++) {
+    const int c = cl + 16 * it;
+    if (c < C) {
+#pragma unroll
+      for (int k = 0; k < 4; k++) { tile[(4 * pl + k) * ld + c] = xv[it][k]; s[k] += xv[it][k]; }
+    }
   }
 #pragma unroll
   for (int k = 0; k < 4; k++) rs[cl][4 * pl + k] = s[k];
@@ -403,9 +416,13 @@ __global__ __launch_bounds__(256) void ln_cmajor_fwd_fast_kernel(const T* xt, co
   __syncthreads();
 #pragma unroll
   for (int k = 0; k < 4; k++) s[k] = 0.0f;
-  for (int c = cl; c < C; c += 16) {
 #pragma unroll
-    for (int k = 0; k < 4; k++) { float t = tile[(4 * pl + k) * ld + c] - smu[4 * pl + k]; s[k] += t * t; }
+  for (int it = 0; it < NIT; it++) {
+    const int c = cl + 16 * it;
+    if (c < C) {
+#pragma unroll
+      for (int k = 0; k < 4; k++) { float t = xv[it][k] - smu[4 * pl + k]; s[k] += t * t; }
+    }
   }
 #pragma unroll
   for (int k = 0; k < 4; k++) rs[cl][4 * pl + k] = s[k];
@@ -434,7 +451,7 @@ __global__ __launch_bounds__(256) void ln_cmajor_fwd_fast_kernel(const T* xt, co
   }
 }
 
-template <typename T>
+template <typename T, int NIT>
 __global__ __launch_bounds__(256) void ln_cmajor_bwd_fast_kernel(const T* dy, const T* xt, const float* stats,
                                                                  const float* gamma, T* dxt, float* partial,
                                                                  long long M, int C) {
@@ -444,6 +461,22 @@ __global__ __launch_bounds__(256) void ln_cmajor_bwd_fast_kernel(const T* dy, co
   const long long m0 = (long long)blockIdx.x * 64, mb = m0 + 4 * pl;
   const bool ok = mb < M;
   const int C8 = C >> 3;
+  // x of this thread's channels (kept for both passes) and the LayerNorm statistics
+  float xv[NIT][4], gv[NIT];
+#pragma unroll
+  for (int it = 0; it < NIT; it++) {
+    const int c = cl + 16 * it;
+#pragma unroll
+    for (int k = 0; k < 4; k++) xv[it][k] = 0.0f;
+    if (ok && c < C) load4<T>(xt + (long long)c * M + mb, xv[it]);
+    gv[it] = c < C ? gamma[c] : 0.0f;
+  }
+  float mu[4], rstd[4];
+#pragma unroll
+  for (int k = 0; k < 4; k++) {
+    mu[k] = ok ? stats[(mb + k) * 2] : 0.0f;
+    rstd[k] = ok ? stats[(mb + k) * 2 + 1] : 0.0f;
+  }
   for (int idx = threadIdx.x; idx < 64 * C8; idx += 256) {
     const int pp = idx / C8, c0 = (idx - pp * C8) * 8;
     const long long mm = m0 + pp;
@@ -456,24 +489,19 @@ __global__ __launch_bounds__(256) void ln_cmajor_bwd_fast_kernel(const T* dy, co
 #pragma unroll
     for (int e = 0; e < 8; e++) tile[pp * ld + c0 + e] = v[e];
   }
-  float mu[4], rstd[4];
-#pragma unroll
-  for (int k = 0; k < 4; k++) {
-    mu[k] = ok ? stats[(mb + k) * 2] : 0.0f;
-    rstd[k] = ok ? stats[(mb + k) * 2 + 1] : 0.0f;
-  }
   __syncthreads();
   float s1[4] = {0.0f, 0.0f, 0.0f, 0.0f}, s2[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-  for (int c = cl; c < C; c += 16) {
-    float x[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    if (ok) load4<T>(xt + (long long)c * M + mb, x);
-    const float g = gamma[c];
+  float dv[NIT][4];
+#pragma unroll
+  for (int it = 0; it < NIT; it++) {
+    const int c = cl + 16 * it;
 #pragma unroll
     for (int k = 0; k < 4; k++) {
-      float xh = (x[k] - mu[k]) * rstd[k];
-      float dxh = tile[(4 * pl + k) * ld + c] * g;
+      xv[it][k] = (xv[it][k] - mu[k]) * rstd[k];          // x-hat from here on
+      dv[it][k] = c < C ? tile[(4 * pl + k) * ld + c] : 0.0f;
+      float dxh = dv[it][k] * gv[it];
       s1[k] += dxh;
-      s2[k] += dxh * xh;
+      s2[k] += dxh * xv[it][k];
     }
   }
 #pragma unroll
@@ -489,24 +517,21 @@ __global__ __launch_bounds__(256) void ln_cmajor_bwd_fast_kernel(const T* dy, co
   __syncthreads();
 #pragma unroll
   for (int k = 0; k < 4; k++) { s1[k] = t1[4 * pl + k]; s2[k] = t2[4 * pl + k]; }
-  for (int c = cl; c < C; c += 16) {
-    float x[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    if (ok) load4<T>(xt + (long long)c * M + mb, x);
-    const float g = gamma[c];
+#pragma unroll
+  for (int it = 0; it < NIT; it++) {
+    const int c = cl + 16 * it;
     float o[4], a = 0.0f, b = 0.0f;
 #pragma unroll
     for (int k = 0; k < 4; k++) {
-      float xh = (x[k] - mu[k]) * rstd[k];
-      float dv = tile[(4 * pl + k) * ld + c];
-      o[k] = (dv * g - s1[k] - xh * s2[k]) * rstd[k];
-      a += dv * xh;
-      b += dv;
+      o[k] = (dv[it][k] * gv[it] - s1[k] - xv[it][k] * s2[k]) * rstd[k];
+      a += dv[it][k] * xv[it][k];
+      b += dv[it][k];
     }
-    if (ok) store4<T>(dxt + (long long)c * M + mb, o);
+    if (ok && c < C) store4<T>(dxt + (long long)c * M + mb, o);
     // per-channel partials over the 64 positions: the 16 lanes sharing cl
     a = group_sum<16>(a);
     b = group_sum<16>(b);
-    if (pl == 0) {
+    if (pl == 0 && c < C) {
       partial[(long long)blockIdx.x * 2 * C + c] = a;
       partial[(long long)blockIdx.x * 2 * C + C + c] = b;
     }
