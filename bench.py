@@ -220,6 +220,14 @@ def main():
         step()
     ent2 = run.h.timing_collect()
     run.h.set_option(3, 0)
+    if args.detail:
+        alone = {(e["name"], e["kernel"]): e["total_ms"] / max(e["launches"], 1) for e in ent}
+        print("-- two streams (us/launch, ratio to the same launch alone) --", file=sys.stderr)
+        for e in sorted(ent2, key=lambda e: -e["total_ms"])[:40]:
+            us = 1e3 * e["total_ms"] / e["launches"]
+            a = 1e3 * alone.get((e["name"], e["kernel"]), 0.0)
+            print("%-22s %-44s n=%3d  %8.1f us/launch  x%.2f" % (e["name"], e["kernel"], e["launches"] // 5, us,
+                                                                   us / a if a else 0.0), file=sys.stderr)
     two = {}
     for e in ent2:
         k = two.setdefault(e["kernel"], dict(ms=0.0, launches=0, flops=0.0, bytes=0.0))
