@@ -116,6 +116,8 @@ def main():
     ap.add_argument("--recompute", action="store_true",
                     help="trunk workload: save block inputs only and recompute each block's forward in the backward "
                          "pass (the paper's memory-saving setting) instead of keeping every block's activations")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step (both streams) into a HIP graph once and time graph replays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="also print the per-launch-label timing table to stderr")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -156,6 +158,17 @@ def main():
         run.fwd(use_ctx=True)
         run.bwd(use_ctx=True)
 
+    eager_step = step
+    if args.graph:
+        eager_step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=run.sm):
+            eager_step()
+
+        def step():
+            with torch.cuda.stream(run.sm):
+                graph.replay()
     for _ in range(args.warmup):
         step()
     # one event per step boundary on the MSA stream (both streams are joined at every return, so
@@ -185,9 +198,9 @@ def main():
     t_msa = t_pair = overlap = None
     if args.variant == 0:       # only the Parallel block has two independent branches to time alone
         run.h.set_option(1, 1)
-        t_msa = timed(nrep, step)
+        t_msa = timed(nrep, eager_step)
         run.h.set_option(1, 2)
-        t_pair = timed(nrep, step)
+        t_pair = timed(nrep, eager_step)
         run.h.set_option(1, 3)
         overlap = (t_msa + t_pair - ms) / min(t_msa, t_pair)
     one = BlockRun(dims, inp, two_streams=False)
@@ -217,7 +230,7 @@ def main():
     # this command); kernels_ms_per_step above is the one-stream view of every kernel alone
     run.h.set_option(3, 1)
     for _ in range(5):
-        step()
+        eager_step()
     ent2 = run.h.timing_collect()
     run.h.set_option(3, 0)
     if args.detail:
@@ -269,7 +282,7 @@ def main():
                          "af2_initial shape (other hardware: context, not the target)",
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "s": dims["s"], "r": dims["r"], "c_m": dims["c_m"], "c_z": dims["c_z"],
-                   "batch": 1, "streams": 2, "activation_ctx": "saved",
+                   "batch": 1, "streams": 2, "activation_ctx": "saved", "launch": "hip graph replay" if args.graph else "eager",
                    "block_ordering": ["parallel", "alphafold2", "multimer"][args.variant]},
         "samples_per_s": 1e3 / ms,
         "block_tflops": flops / (ms * 1e-3) / 1e12,

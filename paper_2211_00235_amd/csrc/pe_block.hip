@@ -1453,7 +1453,10 @@ static int stack_impl(pe_handle* h, int n_extra, const pe_dims* ex, int n_main, 
   const void* dm = d_msa_out;
   const void* de = nullptr;
   if (n_extra) {
-    if (!hip_ok(h, hipMemsetAsync(de_pp[1], 0, sp.n_extra, sm), "memset")) return PE_ERR_HIP;
+    // a fill kernel, not hipMemsetAsync: the call may be captured into a HIP graph by the caller
+    hipLaunchKernelGGL(zero_bytes16_kernel, dim3((unsigned)((sp.n_extra / 16 + 255) / 256)), dim3(256), 0, sm,
+                       (uint4*)de_pp[1], (long long)(sp.n_extra / 16));
+    if (!hip_ok(h, hipGetLastError(), "zero fill")) return PE_ERR_HIP;
     de = de_pp[1];
   }
   for (int b = nb - 1; b >= 0; b--) {

@@ -1023,6 +1023,11 @@ __global__ void opm_norm_kernel(const float* mask, float* inv_norm, int s, int r
   inv_norm[idx] = 1.0f / (eps + acc);
 }
 
+// zero n 16-byte words (buffers are 256-byte multiples)
+__global__ void zero_bytes16_kernel(uint4* p, long long n) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < n) p[idx] = make_uint4(0u, 0u, 0u, 0u);
+}
 template <typename T>
 __global__ void add2_kernel(const T* a, const T* b, T* out, long long n) {
   long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
