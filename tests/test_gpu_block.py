@@ -85,7 +85,8 @@ def test_af2_initial_fp32():
 
 
 def test_recompute_and_single_stream_match():
-    """Backward with ctx == NULL (internal recompute) and with both branches on one stream give
+    """Backward with ctx == NULL (internal recompute), both branches on one stream, and the
+    parameter-gradient kernels on library-owned side streams (PE_OPT_SIDE_STREAMS) give
     bit-identical results to the two-stream, saved-ctx run."""
     import torch
     from tests.gpu_util import BlockRun
@@ -93,8 +94,11 @@ def test_recompute_and_single_stream_match():
     table, n = param_table(dims)
     inp = make_inputs(dims, table, n, ("last_residues", 5), 9)
     outs = []
-    for two, use_ctx in ((True, True), (False, True), (True, False)):
+    for two, use_ctx, side in ((True, True, False), (False, True, False), (True, False, False), (True, True, True),
+                               (True, False, True)):
         run = BlockRun(dims, inp, two_streams=two)
+        if side:
+            run.h.set_option(4, 1)
         run.fwd()
         if not use_ctx:
             run.sync()          # zero_() runs on torch's stream, the forward on the run's own streams
