@@ -103,8 +103,13 @@ typedef struct pe_ctx_entry {
   int dtype;
 } pe_ctx_entry;
 
-/* Handle: owns a few hipEvents used to fork/join the streams and two side
- * streams (default priority).  Host state only.  Not thread safe; use one handle per host thread.              */
+/* Handle: owns a few hipEvents used to fork/join the streams and, once
+ * PE_OPT_SIDE_STREAMS has been set, two side streams (default priority).
+ * Host state only.  Not thread safe: one handle per host thread; calls on one
+ * handle must not overlap.  The compute calls may be captured into a HIP
+ * graph by the caller (they allocate nothing, never synchronise the host and
+ * record no memset nodes); keep PE_OPT_KERNEL_TIMING and PE_OPT_SYNC_DEBUG off
+ * while capturing.                                                            */
 int pe_create(pe_handle** h);
 int pe_destroy(pe_handle* h);
 
