@@ -11,6 +11,7 @@
 #include "pe_elem.h"
 
 constexpr int GC_MAXH = 8, GC_MAXD = 8;
+constexpr int GC_UR = 32;   // sequence positions in flight per thread in the latency-bound reductions over s
 
 struct GcolArgs {
   const void* proj; void* dproj;    // [s][r][Wg] storage type
@@ -26,6 +27,13 @@ struct GcolArgs {
   int s, r, H, d;
   float scale;
 };
+
+// d (<= 8) consecutive channels of one (sequence, residue) row -> float[8] (zero beyond d)
+template <typename T> PE_DEV void gc_load_row(const T* p, int d, float (&v)[GC_MAXD]) {
+  if (d == GC_MAXD) { ld8<T>(p, v); return; }   // 16 / 32 bytes, aligned: row offsets are multiples of 8 channels
+#pragma unroll
+  for (int c = 0; c < GC_MAXD; c++) v[c] = c < d ? to_f(p[c]) : 0.0f;
+}
 
 PE_DEV float block_reduce_sum(float v, float* red /*[4]*/) {
   v = wave_sum(v);
@@ -51,10 +59,17 @@ __global__ __launch_bounds__(256) void gcol_qmean_kernel(GcolArgs a) {
   const T* q = (const T*)a.proj + (long long)i * Wg + hd;
   float acc = 0.0f, msum = 0.0f;
   if (sl < SL)
-    for (int t = sl; t < a.s; t += SL) {
-      float mk = a.mask[(long long)t * a.r + i];
-      acc += mk * to_f(q[(long long)t * a.r * Wg]);
-      msum += mk;
+    for (int t0 = sl; t0 < a.s; t0 += GC_UR * SL) {   // GC_UR independent loads in flight per thread
+      float mk[GC_UR], qv[GC_UR];
+#pragma unroll
+      for (int u = 0; u < GC_UR; u++) {
+        const int t = t0 + u * SL;
+        const bool ok = t < a.s;
+        mk[u] = ok ? a.mask[(long long)t * a.r + i] : 0.0f;
+        qv[u] = ok ? to_f(q[(long long)t * a.r * Wg]) : 0.0f;
+      }
+#pragma unroll
+      for (int u = 0; u < GC_UR; u++) { acc += mk[u] * qv[u]; msum += mk[u]; }
     }
   red[threadIdx.x] = acc;
   redm[threadIdx.x] = msum;
@@ -67,67 +82,123 @@ __global__ __launch_bounds__(256) void gcol_qmean_kernel(GcolArgs a) {
   }
 }
 
-// softmax over the sequence axis and weighted value sum; grid = r, block = 256
+// softmax over the sequence axis and weighted value sum; grid = r, block = 256.
+// Every pass walks the sequence axis 4 positions per thread at a time: the 4 (k, v) rows and
+// masks are loaded first (one 16-byte load per row when d = 8), then used; all per-head arrays
+// have compile-time bounds (H <= 8, d <= 8 with guards) and live in registers.
+constexpr int GC_U = 4;
 template <typename T>
 __global__ __launch_bounds__(256) void gcol_attn_fwd_kernel(GcolArgs a) {
   __shared__ float qb[GC_MAXH * GC_MAXD], red[4], ored[4][GC_MAXH * GC_MAXD];
   const int i = blockIdx.x, H = a.H, d = a.d, HD = H * d, Wg = 2 * HD + 2 * d;
-  if (threadIdx.x < HD) qb[threadIdx.x] = a.qbar[(long long)i * HD + threadIdx.x];
+  if (threadIdx.x < GC_MAXH * GC_MAXD) {
+    const int h = threadIdx.x / GC_MAXD, c = threadIdx.x % GC_MAXD;
+    qb[threadIdx.x] = (h < H && c < d) ? a.qbar[(long long)i * HD + h * d + c] * a.scale : 0.0f;   // scaled query, padded
+  }
   __syncthreads();
+  float q[GC_MAXH][GC_MAXD];
+#pragma unroll
+  for (int h = 0; h < GC_MAXH; h++)
+#pragma unroll
+    for (int c = 0; c < GC_MAXD; c++) q[h][c] = qb[h * GC_MAXD + c];
   const T* kbase = (const T*)a.proj + (long long)i * Wg + HD;
   const long long tstride = (long long)a.r * Wg;
   float mx[GC_MAXH], sm[GC_MAXH];
 #pragma unroll
   for (int h = 0; h < GC_MAXH; h++) { mx[h] = -INFINITY; sm[h] = 0.0f; }
   // pass 1: max over valid keys
-  for (int t = threadIdx.x; t < a.s; t += 256) {
-    if (a.mask[(long long)t * a.r + i] > 0.0f) {
-      float kv[GC_MAXD];
-      for (int c = 0; c < d; c++) kv[c] = to_f(kbase[t * tstride + c]);
-      for (int h = 0; h < H; h++) {
-        float l = 0.0f;
-        for (int c = 0; c < d; c++) l += qb[h * d + c] * kv[c];
-        mx[h] = fmaxf(mx[h], l * a.scale);
-      }
+  for (int t0 = threadIdx.x; t0 < a.s; t0 += 256 * GC_U) {
+    float kv[GC_U][GC_MAXD], mk[GC_U];
+#pragma unroll
+    for (int u = 0; u < GC_U; u++) {
+      const int t = t0 + 256 * u;
+      const bool ok = t < a.s;
+      mk[u] = ok ? a.mask[(long long)t * a.r + i] : 0.0f;
+      gc_load_row<T>(kbase + (ok ? t : 0) * tstride, d, kv[u]);
     }
+#pragma unroll
+    for (int u = 0; u < GC_U; u++)
+      if (mk[u] > 0.0f) {
+#pragma unroll
+        for (int h = 0; h < GC_MAXH; h++) {
+          float l = 0.0f;
+#pragma unroll
+          for (int c = 0; c < GC_MAXD; c++) l += q[h][c] * kv[u][c];
+          mx[h] = fmaxf(mx[h], l);
+        }
+      }
   }
-  for (int h = 0; h < H; h++) {
+#pragma unroll
+  for (int h = 0; h < GC_MAXH; h++) {
     mx[h] = block_reduce_max(mx[h], red);
     if (mx[h] == -INFINITY) mx[h] = 0.0f;
   }
   // pass 2: sum of exponentials
-  for (int t = threadIdx.x; t < a.s; t += 256) {
-    if (a.mask[(long long)t * a.r + i] > 0.0f) {
-      float kv[GC_MAXD];
-      for (int c = 0; c < d; c++) kv[c] = to_f(kbase[t * tstride + c]);
-      for (int h = 0; h < H; h++) {
-        float l = 0.0f;
-        for (int c = 0; c < d; c++) l += qb[h * d + c] * kv[c];
-        sm[h] += __expf(l * a.scale - mx[h]);
+  for (int t0 = threadIdx.x; t0 < a.s; t0 += 256 * GC_U) {
+    float kv[GC_U][GC_MAXD], mk[GC_U];
+#pragma unroll
+    for (int u = 0; u < GC_U; u++) {
+      const int t = t0 + 256 * u;
+      const bool ok = t < a.s;
+      mk[u] = ok ? a.mask[(long long)t * a.r + i] : 0.0f;
+      gc_load_row<T>(kbase + (ok ? t : 0) * tstride, d, kv[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < GC_U; u++)
+      if (mk[u] > 0.0f) {
+#pragma unroll
+        for (int h = 0; h < GC_MAXH; h++) {
+          float l = 0.0f;
+#pragma unroll
+          for (int c = 0; c < GC_MAXD; c++) l += q[h][c] * kv[u][c];
+          sm[h] += __expf(l - mx[h]);
+        }
+      }
+  }
+#pragma unroll
+  for (int h = 0; h < GC_MAXH; h++) sm[h] = block_reduce_sum(sm[h], red);
+  // pass 3: weights and output
+  float oacc[GC_MAXH][GC_MAXD];
+#pragma unroll
+  for (int h = 0; h < GC_MAXH; h++)
+#pragma unroll
+    for (int c = 0; c < GC_MAXD; c++) oacc[h][c] = 0.0f;
+  for (int t0 = threadIdx.x; t0 < a.s; t0 += 256 * GC_U) {
+    float kv[GC_U][GC_MAXD], vv[GC_U][GC_MAXD], mk[GC_U];
+#pragma unroll
+    for (int u = 0; u < GC_U; u++) {
+      const int t = t0 + 256 * u;
+      const bool ok = t < a.s;
+      mk[u] = ok ? a.mask[(long long)t * a.r + i] : 0.0f;
+      const T* row = kbase + (ok ? t : 0) * tstride;
+      gc_load_row<T>(row, d, kv[u]);
+      gc_load_row<T>(row + d, d, vv[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < GC_U; u++) {
+      const int t = t0 + 256 * u;
+      if (t < a.s) {
+#pragma unroll
+        for (int h = 0; h < GC_MAXH; h++) {
+          if (h < H) {
+            float l = 0.0f;
+#pragma unroll
+            for (int c = 0; c < GC_MAXD; c++) l += q[h][c] * kv[u][c];
+            float pw = (mk[u] > 0.0f && sm[h] > 0.0f) ? __expf(l - mx[h]) / sm[h] : 0.0f;
+            a.p[((long long)i * H + h) * a.s + t] = pw;
+#pragma unroll
+            for (int c = 0; c < GC_MAXD; c++) oacc[h][c] += pw * vv[u][c];
+          }
+        }
       }
     }
   }
-  for (int h = 0; h < H; h++) sm[h] = block_reduce_sum(sm[h], red);
-  // pass 3: weights and output
-  float oacc[GC_MAXH * GC_MAXD];
-#pragma unroll
-  for (int e = 0; e < GC_MAXH * GC_MAXD; e++) oacc[e] = 0.0f;
-  for (int t = threadIdx.x; t < a.s; t += 256) {
-    bool valid = a.mask[(long long)t * a.r + i] > 0.0f;
-    float kv[GC_MAXD], vv[GC_MAXD];
-    for (int c = 0; c < d; c++) { kv[c] = to_f(kbase[t * tstride + c]); vv[c] = to_f(kbase[t * tstride + d + c]); }
-    for (int h = 0; h < H; h++) {
-      float l = 0.0f;
-      for (int c = 0; c < d; c++) l += qb[h * d + c] * kv[c];
-      float pw = (valid && sm[h] > 0.0f) ? __expf(l * a.scale - mx[h]) / sm[h] : 0.0f;
-      a.p[((long long)i * H + h) * a.s + t] = pw;
-      for (int c = 0; c < d; c++) oacc[h * GC_MAXD + c] += pw * vv[c];
-    }
-  }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int h = 0; h < H; h++)
-    for (int c = 0; c < d; c++) {
-      float v = wave_sum(oacc[h * GC_MAXD + c]);
+#pragma unroll
+  for (int h = 0; h < GC_MAXH; h++)
+#pragma unroll
+    for (int c = 0; c < GC_MAXD; c++) {
+      float v = wave_sum(oacc[h][c]);
       if (lane == 0) ored[wave][h * GC_MAXD + c] = v;
     }
   __syncthreads();
@@ -160,13 +231,26 @@ __global__ __launch_bounds__(256) void gcol_gate_bwd_kernel(GcolArgs a) {
   const float ov = a.o[(long long)i * HD + hd];
   float acc = 0.0f;
   if (sl < SL)
-    for (int t = sl; t < a.s; t += SL) {
-      long long pos = (long long)t * a.r + i;
-      float g = to_f(((const T*)a.proj)[pos * Wg + HD + 2 * a.d + hd]);
-      float sg = sigmoidf_(g);
-      float dv = to_f(((const T*)a.dog)[pos * HD + hd]);
-      acc += dv * sg;
-      ((T*)a.dproj)[pos * Wg + HD + 2 * a.d + hd] = from_f<T>(dv * ov * sg * (1.0f - sg));
+    for (int t0 = sl; t0 < a.s; t0 += GC_UR * SL) {   // loads of GC_UR sequence positions first, then the arithmetic
+      float gv[GC_UR], dv[GC_UR];
+#pragma unroll
+      for (int u = 0; u < GC_UR; u++) {
+        const int t = t0 + u * SL;
+        const bool ok = t < a.s;
+        const long long pos = (long long)(ok ? t : 0) * a.r + i;
+        gv[u] = to_f(((const T*)a.proj)[pos * Wg + HD + 2 * a.d + hd]);
+        dv[u] = ok ? to_f(((const T*)a.dog)[pos * HD + hd]) : 0.0f;
+      }
+#pragma unroll
+      for (int u = 0; u < GC_UR; u++) {
+        const int t = t0 + u * SL;
+        if (t < a.s) {
+          const long long pos = (long long)t * a.r + i;
+          float sg = sigmoidf_(gv[u]);
+          acc += dv[u] * sg;
+          ((T*)a.dproj)[pos * Wg + HD + 2 * a.d + hd] = from_f<T>(dv[u] * ov * sg * (1.0f - sg));
+        }
+      }
     }
   red[threadIdx.x] = acc;
   __syncthreads();
@@ -176,62 +260,110 @@ __global__ __launch_bounds__(256) void gcol_gate_bwd_kernel(GcolArgs a) {
   }
 }
 
-// softmax backward per residue: dk, dv -> dproj; dqbar.  grid = r, block = 256
+// softmax backward per residue: dk, dv -> dproj; dqbar.  grid = r, block = 256; same batching
+// and register-resident per-head arrays as the forward kernel
 template <typename T>
 __global__ __launch_bounds__(256) void gcol_attn_bwd_kernel(GcolArgs a) {
   __shared__ float qb[GC_MAXH * GC_MAXD], dob[GC_MAXH * GC_MAXD], red[4], qred[4][GC_MAXH * GC_MAXD];
   const int i = blockIdx.x, H = a.H, d = a.d, HD = H * d, Wg = 2 * HD + 2 * d;
-  if (threadIdx.x < HD) {
-    qb[threadIdx.x] = a.qbar[(long long)i * HD + threadIdx.x];
-    dob[threadIdx.x] = a.dO[(long long)i * HD + threadIdx.x];
+  if (threadIdx.x < GC_MAXH * GC_MAXD) {
+    const int h = threadIdx.x / GC_MAXD, c = threadIdx.x % GC_MAXD;
+    const bool in = h < H && c < d;
+    qb[threadIdx.x] = in ? a.qbar[(long long)i * HD + h * d + c] : 0.0f;
+    dob[threadIdx.x] = in ? a.dO[(long long)i * HD + h * d + c] : 0.0f;
   }
   __syncthreads();
+  float q[GC_MAXH][GC_MAXD], dov[GC_MAXH][GC_MAXD];
+#pragma unroll
+  for (int h = 0; h < GC_MAXH; h++)
+#pragma unroll
+    for (int c = 0; c < GC_MAXD; c++) { q[h][c] = qb[h * GC_MAXD + c]; dov[h][c] = dob[h * GC_MAXD + c]; }
   const T* kbase = (const T*)a.proj + (long long)i * Wg + HD;
   T* dkbase = (T*)a.dproj + (long long)i * Wg + HD;
   const long long tstride = (long long)a.r * Wg;
   float D[GC_MAXH];
 #pragma unroll
   for (int h = 0; h < GC_MAXH; h++) D[h] = 0.0f;
-  for (int t = threadIdx.x; t < a.s; t += 256) {
-    float vv[GC_MAXD];
-    for (int c = 0; c < d; c++) vv[c] = to_f(kbase[t * tstride + d + c]);
-    for (int h = 0; h < H; h++) {
-      float dp = 0.0f;
-      for (int c = 0; c < d; c++) dp += dob[h * d + c] * vv[c];
-      D[h] += a.p[((long long)i * H + h) * a.s + t] * dp;
-    }
-  }
-  for (int h = 0; h < H; h++) D[h] = block_reduce_sum(D[h], red);
-  float dq[GC_MAXH * GC_MAXD];
+  for (int t0 = threadIdx.x; t0 < a.s; t0 += 256 * GC_U) {
+    float vv[GC_U][GC_MAXD], pw[GC_U][GC_MAXH];
 #pragma unroll
-  for (int e = 0; e < GC_MAXH * GC_MAXD; e++) dq[e] = 0.0f;
-  for (int t = threadIdx.x; t < a.s; t += 256) {
-    float kv[GC_MAXD], vv[GC_MAXD], dk[GC_MAXD], dv[GC_MAXD];
-    for (int c = 0; c < d; c++) {
-      kv[c] = to_f(kbase[t * tstride + c]);
-      vv[c] = to_f(kbase[t * tstride + d + c]);
-      dk[c] = 0.0f; dv[c] = 0.0f;
+    for (int u = 0; u < GC_U; u++) {
+      const int t = t0 + 256 * u;
+      const bool ok = t < a.s;
+      gc_load_row<T>(kbase + (ok ? t : 0) * tstride + d, d, vv[u]);
+#pragma unroll
+      for (int h = 0; h < GC_MAXH; h++) pw[u][h] = (ok && h < H) ? a.p[((long long)i * H + h) * a.s + t] : 0.0f;
     }
-    for (int h = 0; h < H; h++) {
-      float pw = a.p[((long long)i * H + h) * a.s + t];
-      float dp = 0.0f;
-      for (int c = 0; c < d; c++) dp += dob[h * d + c] * vv[c];
-      float dl = pw * (dp - D[h]);
-      for (int c = 0; c < d; c++) {
-        dq[h * GC_MAXD + c] += dl * kv[c];
-        dk[c] += dl * qb[h * d + c];
-        dv[c] += pw * dob[h * d + c];
+#pragma unroll
+    for (int u = 0; u < GC_U; u++)
+#pragma unroll
+      for (int h = 0; h < GC_MAXH; h++) {
+        float dp = 0.0f;
+#pragma unroll
+        for (int c = 0; c < GC_MAXD; c++) dp += dov[h][c] * vv[u][c];
+        D[h] += pw[u][h] * dp;
       }
+  }
+#pragma unroll
+  for (int h = 0; h < GC_MAXH; h++) D[h] = block_reduce_sum(D[h], red);
+  float dq[GC_MAXH][GC_MAXD];
+#pragma unroll
+  for (int h = 0; h < GC_MAXH; h++)
+#pragma unroll
+    for (int c = 0; c < GC_MAXD; c++) dq[h][c] = 0.0f;
+  for (int t0 = threadIdx.x; t0 < a.s; t0 += 256 * GC_U) {
+    float kv[GC_U][GC_MAXD], vv[GC_U][GC_MAXD], pw[GC_U][GC_MAXH];
+#pragma unroll
+    for (int u = 0; u < GC_U; u++) {
+      const int t = t0 + 256 * u;
+      const bool ok = t < a.s;
+      const T* row = kbase + (ok ? t : 0) * tstride;
+      gc_load_row<T>(row, d, kv[u]);
+      gc_load_row<T>(row + d, d, vv[u]);
+#pragma unroll
+      for (int h = 0; h < GC_MAXH; h++) pw[u][h] = (ok && h < H) ? a.p[((long long)i * H + h) * a.s + t] : 0.0f;
     }
-    for (int c = 0; c < d; c++) {
-      dkbase[t * tstride + c] = from_f<T>(dk[c] * a.scale);
-      dkbase[t * tstride + d + c] = from_f<T>(dv[c]);
+#pragma unroll
+    for (int u = 0; u < GC_U; u++) {
+      const int t = t0 + 256 * u;
+      if (t < a.s) {
+        float dk[GC_MAXD], dv[GC_MAXD];
+#pragma unroll
+        for (int c = 0; c < GC_MAXD; c++) { dk[c] = 0.0f; dv[c] = 0.0f; }
+#pragma unroll
+        for (int h = 0; h < GC_MAXH; h++) {
+          float dp = 0.0f;
+#pragma unroll
+          for (int c = 0; c < GC_MAXD; c++) dp += dov[h][c] * vv[u][c];
+          const float dl = pw[u][h] * (dp - D[h]);
+#pragma unroll
+          for (int c = 0; c < GC_MAXD; c++) {
+            dq[h][c] += dl * kv[u][c];
+            dk[c] += dl * q[h][c];
+            dv[c] += pw[u][h] * dov[h][c];
+          }
+        }
+        T* orow = dkbase + t * tstride;
+        if (d == GC_MAXD) {
+          float o1[8], o2[8];
+#pragma unroll
+          for (int c = 0; c < GC_MAXD; c++) { o1[c] = dk[c] * a.scale; o2[c] = dv[c]; }
+          st8<T>(orow, o1);
+          st8<T>(orow + d, o2);
+        } else {
+#pragma unroll
+          for (int c = 0; c < GC_MAXD; c++)
+            if (c < d) { orow[c] = from_f<T>(dk[c] * a.scale); orow[d + c] = from_f<T>(dv[c]); }
+        }
+      }
     }
   }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int h = 0; h < H; h++)
-    for (int c = 0; c < d; c++) {
-      float v = wave_sum(dq[h * GC_MAXD + c]);
+#pragma unroll
+  for (int h = 0; h < GC_MAXH; h++)
+#pragma unroll
+    for (int c = 0; c < GC_MAXD; c++) {
+      float v = wave_sum(dq[h][c]);
       if (lane == 0) qred[wave][h * GC_MAXD + c] = v;
     }
   __syncthreads();
