@@ -241,12 +241,37 @@ def test_dpair_in_decomposition():
     assert np.allclose(parts0["dz_bias"] + parts1["dz_bias"], parts["dz_bias"], atol=1e-12)
 
 
+def _paper_settings():
+    import os
+    out = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "paper_settings.txt")):
+        line = line.split("#")[0].split()
+        if len(line) == 2:
+            out[line[0]] = float(line[1])
+    return out
+
+
+def test_workload_shapes_are_the_papers():
+    """The benchmark and test workloads carry the shapes the paper prints (Table 1, caption of Table 5)."""
+    from pe_inputs import dims_for
+    g = _paper_settings()
+    ini, ext, fin, exf = (dims_for(k)[0] for k in ("af2_initial", "extra_msa", "af2_finetune", "extra_msa_finetune"))
+    assert (ini["r"], ini["s"], ext["s"]) == (g["initial_training.N_res"], g["initial_training.N_seq"],
+                                             g["initial_training.N_extra_seq"])
+    assert (fin["r"], fin["s"], exf["s"], exf["r"]) == (g["fine_tuning.N_res"], g["fine_tuning.N_seq"],
+                                                       g["fine_tuning.N_extra_seq"], g["fine_tuning.N_res"])
+    assert (ini["h_msa"], ini["s"], ini["r"], ini["c_m"], ini["c_z"]) == (g["table5.head"], g["table5.N_seq"],
+                                                                         g["table5.N_res"], g["table5.C_m"], g["table5.C_z"])
+    assert ext["r"] == ini["r"] and ext["c_z"] == ini["c_z"]
+
+
 def test_param_count_matches_published_structure():
-    """52-block trunk (4 extra + 48 main) parameter count is of the order of the
+    """The trunk (48 main + 4 extra-MSA blocks, Section "Parallel Evoformer") holds most of the
     93 M parameters the paper quotes for the whole model (Introduction)."""
     from pe_inputs import dims_for
+    g = _paper_settings()
     n_main = param_table(dims_for("af2_initial")[0])[1]
     n_extra = param_table(dims_for("extra_msa")[0])[1]
-    total = 48 * n_main + 4 * n_extra
+    total = int(g["trunk.main_blocks"]) * n_main + int(g["trunk.extra_blocks"]) * n_extra
     assert total == 90_642_944
-    assert 0.9 * 93e6 < total < 93e6
+    assert 0.9 * g["model.parameters"] < total < g["model.parameters"]
