@@ -118,12 +118,30 @@ template <typename T> PE_DEV typename Mma<T>::frag gl_frag(const T* p, int kk, i
 // raw v_exp_f32 (2^x; results below the normal range flush to zero, which is what softmax wants)
 PE_DEV float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// bias values of one 32x32 tile for this lane's query: element e <-> key row acc_row(g, e)
-PE_DEV void attn_load_bias16(const float* bcol, int L, int key0 /* first key of the tile + 4g */, float (&bv)[16]) {
+// bias values of one 32x32 tile for this lane's column `col` (clamped to L-1 by the caller) of the plane
+// `ub` (uniform over the wave): element e <-> row t0 + acc_row(g, e).
+// Clamped form: rows beyond L-1 read row L-1, no branches.
+PE_DEV void attn_load_bias16(const float* ub, int L, int t0, int g, int col, float (&bv)[16]) {
+  const float* bcol = ub + col;
 #pragma unroll
   for (int e = 0; e < 16; e++) {
-    int key = min(key0 + 8 * (e >> 2) + (e & 3), L - 1);
-    bv[e] = bcol[key * L];
+    int row = min(t0 + 4 * g + 8 * (e >> 2) + (e & 3), L - 1);
+    bv[e] = bcol[row * L];
+  }
+}
+// Split form: for a full tile the address is a wave-uniform row base (scalar arithmetic) plus one per-lane
+// byte offset that is the same for every tile.  Measured faster in the dq kernel only (where the dS stores
+// use the same split), slower in the forward and dkv kernels, which keep the clamped form.
+PE_DEV void attn_load_bias16_split(const float* ub, int L, int t0, int g, int col, float (&bv)[16]) {
+  if (t0 + 32 <= L) {
+    const unsigned boff = (unsigned)(4 * g * L + col) * 4u;
+#pragma unroll
+    for (int e = 0; e < 16; e++) {
+      const char* urow = (const char*)(ub + (long long)(t0 + 8 * (e >> 2) + (e & 3)) * L);
+      bv[e] = *(const float*)(urow + boff);
+    }
+  } else {
+    attn_load_bias16(ub, L, t0, g, col, bv);
   }
 }
 
@@ -161,7 +179,8 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
   for (int e = 0; e < 16; e++) oacc[e] = 0.0f;
   float m_run = -INFINITY, l_run = 0.0f;
   constexpr bool has_bias = HAS_BIAS;
-  const float* bcol = has_bias ? a.biasT + (long long)h * L * L + min(qi, L - 1) : nullptr;   // + key * L
+  const float* bplane = has_bias ? a.biasT + (long long)h * L * L : nullptr;   // [key][query]
+  const int bcolq = min(qi, L - 1);
   const float c1 = a.scale * PE_LOG2E;
 
   for (int j0 = 0; j0 < L; j0 += C::KT) {
@@ -178,7 +197,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
     for (int jt = 0; jt < C::KT / 32; jt++) {
       if (j0 + jt * 32 >= L) break;
       float bv[16];
-      if (has_bias) attn_load_bias16(bcol, L, j0 + jt * 32 + 4 * g, bv);
+      if (has_bias) attn_load_bias16(bplane, L, j0 + jt * 32, g, bcolq, bv);
       f32x16 sacc;
 #pragma unroll
       for (int e = 0; e < 16; e++) sacc[e] = 0.0f;
@@ -333,8 +352,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnArgs a) {
   const float lse2 = qok ? a.lse[sidx] * PE_LOG2E : 0.0f;
   const float Di = qok ? a.D[sidx] : 0.0f;
   constexpr bool has_bias = HAS_BIAS;
-  const float* bcol = has_bias ? a.biasT + (long long)h * L * L + min(qi, L - 1) : nullptr;      // + key * L
-  T* dscol = (a.dS && qok) ? (T*)a.dS + ((long long)b * a.H + h) * L * L + qi : nullptr;         // + key * L
+  const float* bplane = has_bias ? a.biasT + (long long)h * L * L : nullptr;   // [key][query]
+  const int bcolq = min(qi, L - 1);
+  // dS^T plane [key][query] of this (b, h); a lane's element offset within a tile row group is tile-invariant
+  T* dsplane = a.dS ? (T*)a.dS + ((long long)b * a.H + h) * L * L : nullptr;
+  const unsigned dsoff = (unsigned)(4 * g * L + qi) * (unsigned)sizeof(T);
   const float c1 = a.scale * PE_LOG2E;
 
   f32x16 dq;
@@ -356,7 +378,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnArgs a) {
       const int kt0 = j0 + jt * 32;
       if (kt0 >= L) break;
       float bv[16];
-      if (has_bias) attn_load_bias16(bcol, L, kt0 + 4 * g, bv);
+      if (has_bias) attn_load_bias16_split(bplane, L, kt0, g, bcolq, bv);
       f32x16 sacc, pacc;
 #pragma unroll
       for (int e = 0; e < 16; e++) { sacc[e] = 0.0f; pacc[e] = 0.0f; }
@@ -378,12 +400,19 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnArgs a) {
           sacc[e] = p * (pacc[e] - Di);
         }
       }
-      if (dscol) {
-        const bool full = kt0 + 32 <= L;
+      if (dsplane && qok) {
+        if (kt0 + 32 <= L) {
 #pragma unroll
-        for (int e = 0; e < 16; e++) {
-          int key = kt0 + acc_row(g, e);
-          if (full || key < L) dscol[(long long)key * L] = from_f<T>(sacc[e]);
+          for (int e = 0; e < 16; e++) {
+            char* urow = (char*)(dsplane + (long long)(kt0 + 8 * (e >> 2) + (e & 3)) * L);   // wave-uniform
+            *(T*)(urow + dsoff) = from_f<T>(sacc[e]);
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 16; e++) {
+            int key = kt0 + acc_row(g, e);
+            if (key < L) dsplane[(long long)key * L + qi] = from_f<T>(sacc[e]);
+          }
         }
       }
       const T* krow = lds_kt + l32 * C::TS + jt * 32;
@@ -444,7 +473,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
   const float mk = kok ? a.mask[(long long)b * a.mask_bs + (long long)kj * a.mask_ks] : 0.0f;
   const float madd = (mk > 0.0f) ? 0.0f : -INFINITY;
   constexpr bool has_bias = HAS_BIAS;
-  const float* bcol = has_bias ? a.bias + (long long)h * L * L + min(kj, L - 1) : nullptr;   // + query * L
+  const float* bplane = has_bias ? a.bias + (long long)h * L * L : nullptr;   // [query][key]
+  const int bcolk = min(kj, L - 1);
   const float c1 = a.scale * PE_LOG2E;
 
   f32x16 dk, dv;
@@ -466,7 +496,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
     for (int it = 0; it < C::KT / 32; it++) {
       if (i0 + it * 32 >= L) break;
       float bv[16];
-      if (has_bias) attn_load_bias16(bcol, L, i0 + it * 32 + 4 * g, bv);
+      if (has_bias) attn_load_bias16(bplane, L, i0 + it * 32, g, bcolk, bv);
       f32x16 sacc, pacc;
 #pragma unroll
       for (int e = 0; e < 16; e++) { sacc[e] = 0.0f; pacc[e] = 0.0f; }
