@@ -92,6 +92,36 @@ def test_stack_equals_chained_blocks(dtype, keep):
     assert torch.equal(dmi, dm) and torch.equal(dzi, dz) and torch.equal(dpar, dpar2)
 
 
+def test_stack_bf16_error_against_oracle_by_depth(capsys):
+    """bf16 main blocks (channel widths of the AF2 initial-training block, s 16, r 40) stacked 1..16 deep against
+    the float64 oracle of the same stack.  The per-block tolerance is bound by the block tests and carried to
+    any depth by the chained-blocks identity above; this one reports how the rounding of the bf16 residual
+    stream accumulates (relative L2 error: forward outputs, input cotangents, parameter gradients) and bounds
+    it by sqrt(depth) growth.  ReLU decisions are not matched here, so the backward figures include the
+    O(1) gradient differences at the few pre-activations that round to the other side of zero."""
+    dims, _, _ = dims_for("af2_initial")
+    dims.update(s=16, r=40)
+    table, n = param_table(dims)
+    l2 = lambda a, b: float(np.linalg.norm(a - b) / np.linalg.norm(b))
+    rows = []
+    for depth in (1, 2, 4, 8, 16):
+        inp = make_inputs(dims, table, n, ("last_residues", 4), 100, n_blocks=depth)
+        msa_o, pair_o, _, dm, dz, g = ev.stack_fwd_bwd(0, None, depth, dims, inp["params"], None, inp["msa"], inp["pair"],
+                                                       None, inp["msa_mask"], inp["pair_mask"], inp["d_msa_out"],
+                                                       inp["d_pair_out"])
+        mo, zo, dmi, dzi, dpar = _run_stack(dims, depth, inp)
+        fwd = max(l2(to_np(mo), msa_o), l2(to_np(zo), pair_o))
+        bwd = max(l2(to_np(dmi), dm), l2(to_np(dzi), dz))
+        gp = l2(to_np(dpar), g)
+        rows.append((depth, fwd, bwd, gp))
+        assert fwd < 1e-2 * np.sqrt(depth), rows
+        assert bwd < 5e-2 * np.sqrt(depth) and gp < 5e-2 * np.sqrt(depth), rows
+    with capsys.disabled():
+        print("\n  depth  fwd rel-L2  bwd rel-L2  dparams rel-L2")
+        for r in rows:
+            print("  %5d  %.3e   %.3e   %.3e" % r)
+
+
 def test_stack_argument_errors():
     dims, mask, seed = dims_for("tiny")
     table, n, inp = _stack_inputs(dims, 1, 1, mask)
