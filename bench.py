@@ -77,6 +77,20 @@ def bench_trunk(args, torch, pe):
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / steps
     flops = 3.0 * (ne * block_fwd_flops(de) + nm * block_fwd_flops(dm))
+    cpu = None
+    if not args.no_cpu_baseline:
+        # bounded sample: one block of each kind through the float64 oracle, scaled to the trunk's depth
+        from oracle import evoformer as ev      # cpu_baseline leg only
+        t_kind = []
+        for d_, i_, n_ in ((de, ie, pe.param_count(de)), (dm, im, pe.param_count(dm))):
+            t = time.perf_counter()
+            dmo_ = i_["d_msa_out"] if d_ is dm else np.zeros_like(i_["msa"])
+            ev.block_fwd_bwd(d_, i_["params"][:n_], i_["msa"], im["pair"], i_["msa_mask"], im["pair_mask"], dmo_,
+                             im["d_pair_out"])
+            t_kind.append((time.perf_counter() - t) * 1e3)
+        cpu = {"value": ne * t_kind[0] + nm * t_kind[1], "unit": "ms", "cores": os.cpu_count(), "kind": "oracle",
+               "sample": "one extra-MSA block (%.0f ms) and one main block (%.0f ms) fwd+bwd in float64 numpy, "
+                         "scaled to 4 + 48 blocks (no recompute)" % (t_kind[0], t_kind[1])}
     print(json.dumps({
         "metric": "Parallel Evoformer trunk (4 extra + 48 main blocks) fwd+bwd ms", "value": ms, "unit": "ms",
         "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": ms, "higher_is_better": False, "scaling": "weak",
@@ -86,7 +100,8 @@ def bench_trunk(args, torch, pe):
                    "workspace_gib": round(ws.numel() / 2 ** 30, 1)},
         "counted_tflops": flops / (ms * 1e-3) / 1e12,
         "bf16_mfma_peak_frac": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-        "finite_outputs": bool(torch.isfinite(zo.float()).all().item() and torch.isfinite(dpar).all().item())}))
+        "finite_outputs": bool(torch.isfinite(zo.float()).all().item() and torch.isfinite(dpar).all().item()),
+        "cpu_baseline": cpu}))
 
 
 def profiled_traffic(kernel):
@@ -306,8 +321,15 @@ def main():
         ev.block_fwd_bwd(dims, inp["params"], inp["msa"], inp["pair"], inp["msa_mask"], inp["pair_mask"],
                          inp["d_msa_out"], inp["d_pair_out"])
         cpu_ms = (time.perf_counter() - t) * 1e3
+        model = ""
+        try:
+            with open("/proc/cpuinfo") as f:
+                model = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), "")
+        except OSError:
+            pass
         out["cpu_baseline"] = {"value": cpu_ms, "unit": "ms", "cores": int(cores), "kind": "oracle",
-                               "sample": "one full fwd+bwd of the same %s block, float64 numpy" % args.workload}
+                               "sample": "one full fwd+bwd of the same %s block, float64 numpy" % args.workload,
+                               "os_cpu_count": os.cpu_count(), "blas_threads": int(cores), "cpu_model": model}
     print(json.dumps(out))
 
 
