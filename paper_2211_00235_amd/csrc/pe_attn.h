@@ -75,6 +75,46 @@ PE_DEV void attn_stage(const T* src /* at (w, h, b, position 0, 0) */, int seq_s
   }
 }
 
+// The same staging in two halves, so that the global loads of the next tile can be in flight while
+// the current one is being used: `load` fills up to two 16-byte vectors per thread (zero beyond L / d),
+// `store` writes them to the row-major and / or transposed LDS copies.
+template <typename T> struct AttnStageRegs { typename Vec16<T>::type v[2]; };
+template <typename T>
+PE_DEV void attn_stage_load(const T* src, int seq_stride, int pos0, int L, int d, int DP, AttnStageRegs<T>& r, int tid) {
+  typedef AttnCfg<T> C;
+  typedef typename Vec16<T>::type V;
+  const int vpr = DP / C::VEC;
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+    const int idx = tid + i * 256;
+    V v;
+#pragma unroll
+    for (int e = 0; e < C::VEC; e++) v[e] = from_f<T>(0.0f);
+    const int row = idx / vpr, dd0 = (idx % vpr) * C::VEC;
+    const int pos = pos0 + row;
+    if (idx < C::KT * vpr && pos < L && dd0 < d) v = *reinterpret_cast<const V*>(src + pos * seq_stride + dd0);
+    r.v[i] = v;
+  }
+}
+template <typename T>
+PE_DEV void attn_stage_store(const AttnStageRegs<T>& r, int DP, T* lds_rm, T* lds_t, int tid) {
+  typedef AttnCfg<T> C;
+  typedef typename Vec16<T>::type V;
+  const int vpr = DP / C::VEC;
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+    const int idx = tid + i * 256;
+    if (idx < C::KT * vpr) {
+      const int row = idx / vpr, dd0 = (idx % vpr) * C::VEC;
+      if (lds_rm) *reinterpret_cast<V*>(lds_rm + row * C::RM + dd0) = r.v[i];
+      if (lds_t) {
+#pragma unroll
+        for (int e = 0; e < C::VEC; e++) lds_t[(dd0 + e) * C::TS + row] = r.v[i][e];
+      }
+    }
+  }
+}
+
 // accumulator elements [u*KP, u*KP+KP) of a 32x32 tile as an MFMA operand fragment
 template <typename T> PE_DEV typename Mma<T>::frag acc_to_frag(const f32x16& acc, int u);
 template <> PE_DEV Mma<bf16>::frag acc_to_frag<bf16>(const f32x16& acc, int u) {
@@ -183,21 +223,29 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
   const int bcolq = min(qi, L - 1);
   const float c1 = a.scale * PE_LOG2E;
 
+  // K, V and the key mask of the next 64 keys are loaded into registers while the current ones are used
+  AttnStageRegs<T> rk, rv;
+  float mk = 0.0f;
+  auto prefetch = [&](int j0) {
+    attn_stage_load<T>(base + HP, d, j0, L, d, DP, rk, tid);
+    attn_stage_load<T>(base + 2 * HP, d, j0, L, d, DP, rv, tid);
+    const int j = j0 + tid;
+    mk = (tid < C::KT && j < L) ? a.mask[(long long)b * a.mask_bs + (long long)j * a.mask_ks] : 0.0f;
+  };
+  prefetch(0);
   for (int j0 = 0; j0 < L; j0 += C::KT) {
     __syncthreads();
-    attn_stage<T>(base + HP, d, j0, L, d, DP, lds_k, (T*)nullptr, tid, 256);
-    attn_stage<T>(base + 2 * HP, d, j0, L, d, DP, (T*)nullptr, lds_vt, tid, 256);
-    if (tid < C::KT) {
-      int j = j0 + tid;
-      float mk = (j < L) ? a.mask[(long long)b * a.mask_bs + (long long)j * a.mask_ks] : 0.0f;
-      lds_madd[tid] = (mk > 0.0f) ? 0.0f : -INFINITY;
-    }
+    attn_stage_store<T>(rk, DP, lds_k, (T*)nullptr, tid);
+    attn_stage_store<T>(rv, DP, (T*)nullptr, lds_vt, tid);
+    if (tid < C::KT) lds_madd[tid] = (mk > 0.0f) ? 0.0f : -INFINITY;
     __syncthreads();
 #pragma unroll
     for (int jt = 0; jt < C::KT / 32; jt++) {
       if (j0 + jt * 32 >= L) break;
       float bv[16];
       if (has_bias) attn_load_bias16(bplane, L, j0 + jt * 32, g, bcolq, bv);
+      // issued after the first tile's bias loads, so that waiting for those does not wait for these
+      if (jt == 0 && j0 + C::KT < L) prefetch(j0 + C::KT);
       f32x16 sacc;
 #pragma unroll
       for (int e = 0; e < 16; e++) sacc[e] = 0.0f;
