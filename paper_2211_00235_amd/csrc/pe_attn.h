@@ -42,6 +42,27 @@ struct AttnArgs {
   void* dS;                          // [B][H][key][query] storage type, written when bias != nullptr
 };
 
+// XCD-aware decode of the 1-D grid of the three tile kernels: workgroup w runs on XCD w % 8, and all
+// 128-position tiles of one (batch, head) unit go to the same XCD, so that its L2 serves the K / V
+// (Q / dO in the dK/dV kernel) reads of the unit's second and later tiles; heads cycle fastest over the
+// units, so an XCD also sees only H / 8 (or one) of the bias planes.
+struct AttnWg { int tile, h, b; bool ok; };
+PE_DEV AttnWg attn_decode_wg(const AttnArgs& a) {
+  const int nt = (a.L + 127) / 128;
+  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+  const int u = (j / nt) * 8 + xcd;
+  AttnWg r;
+  r.tile = j % nt;
+  r.ok = u < a.B * a.H;
+  r.h = u % a.H;
+  r.b = u / a.H;
+  return r;
+}
+static inline unsigned attn_grid_size(long long B, int H, long long L) {
+  const long long nt = (L + 127) / 128, units = B * H;
+  return (unsigned)(8 * ((units + 7) / 8) * nt);
+}
+
 template <typename T> struct AttnCfg {
   static constexpr int VEC = Vec16<T>::N;
   static constexpr int KT = 64;                                   // positions staged per iteration
@@ -187,7 +208,7 @@ PE_DEV void attn_load_bias16_split(const float* ub, int L, int t0, int g, int co
 
 // ---------------------------------------------------------------------------
 // Forward
-// grid (ceil(L/128), H, B), 256 threads; wave w owns queries q0 = blockIdx.x*128 + 32*w
+// grid attn_grid_size(B, H, L), 256 threads; wave w owns queries q0 = tile*128 + 32*w
 // ---------------------------------------------------------------------------
 template <typename T, bool HAS_BIAS>
 __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
@@ -198,11 +219,13 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) float lds_madd[C::KT];   // 0 for a valid key, -inf for a masked one
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
-  const int h = blockIdx.y, b = blockIdx.z;
+  const AttnWg wg = attn_decode_wg(a);
+  if (!wg.ok) return;
+  const int h = wg.h, b = wg.b;
   const int L = a.L, d = a.d, HD = a.H * a.d;
   const int DP = round_up_i(d, MM::KSTEP);
   const int NKK = DP / MM::KSTEP;
-  const int qi = blockIdx.x * 128 + wave * 32 + l32;       // this lane's query
+  const int qi = wg.tile * 128 + wave * 32 + l32;       // this lane's query
   const bool qok = qi < L;
   const long long HP = (long long)a.H * a.plane;            // distance between the q, k, v, gate groups
   const T* base = (const T*)a.qkvg + h * a.plane + (long long)b * L * d;
@@ -378,11 +401,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   __shared__ __attribute__((aligned(16))) float lds_madd[C::KT];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
-  const int h = blockIdx.y, b = blockIdx.z;
+  const AttnWg wg = attn_decode_wg(a);
+  if (!wg.ok) return;
+  const int h = wg.h, b = wg.b;
   const int L = a.L, d = a.d, HD = a.H * a.d;
   const int DP = round_up_i(d, MM::KSTEP);
   const int NKK = DP / MM::KSTEP;
-  const int qi = blockIdx.x * 128 + wave * 32 + l32;
+  const int qi = wg.tile * 128 + wave * 32 + l32;
   const bool qok = qi < L;
   const long long HP = (long long)a.H * a.plane;
   const T* base = (const T*)a.qkvg + h * a.plane + (long long)b * L * d;
@@ -485,7 +510,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 }
 
 // ---------------------------------------------------------------------------
-// Backward, dK and dV.  Wave w owns keys k0 = blockIdx.x*128 + 32*w (a key is a lane);
+// Backward, dK and dV.  Wave w owns keys k0 = tile*128 + 32*w (a key is a lane);
 // loops over query tiles staged in LDS (row-major and transposed copies of Q and dO).
 // ---------------------------------------------------------------------------
 template <typename T, bool HAS_BIAS>
@@ -500,11 +525,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) float lds_D[C::KT];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
-  const int h = blockIdx.y, b = blockIdx.z;
+  const AttnWg wg = attn_decode_wg(a);
+  if (!wg.ok) return;
+  const int h = wg.h, b = wg.b;
   const int L = a.L, d = a.d, HD = a.H * a.d;
   const int DP = round_up_i(d, MM::KSTEP);
   const int NKK = DP / MM::KSTEP;
-  const int kj = blockIdx.x * 128 + wave * 32 + l32;       // this lane's key
+  const int kj = wg.tile * 128 + wave * 32 + l32;       // this lane's key
   const bool kok = kj < L;
   const long long HP = (long long)a.H * a.plane;
   const T* base = (const T*)a.qkvg + h * a.plane + (long long)b * L * d;

@@ -645,7 +645,7 @@ template <typename T> struct Runner {
       a.B = (int)g.B; a.L = (int)g.L; a.H = H; a.d = dh;
       a.bias = c.bias; a.biasT = c.biasT; a.mask = g.mask; a.mask_bs = g.mask_bs; a.mask_ks = g.mask_ks;
       a.o = c.o; a.og = c.og; a.lse = c.lse; a.scale = 1.0f / sqrtf((float)dh);
-      dim3 grid((unsigned)((g.L + 127) / 128), H, (unsigned)g.B);
+      dim3 grid(attn_grid_size(g.B, H, g.L));
       if (c.bias) PE_LAUNCH(g.l_fwd, 4.0 * g.B * H * g.L * g.L * dh, (5.0 * M * HD + 1.0 * M * HD) * sizeof(T) + (c.bias ? 4.0 * H * g.L * g.L : 0.0), st, (attn_fwd_kernel<T, true>), grid, dim3(256), 0, a);
       else PE_LAUNCH(g.l_fwd, 4.0 * g.B * H * g.L * g.L * dh, (5.0 * M * HD + 1.0 * M * HD) * sizeof(T) + (c.bias ? 4.0 * H * g.L * g.L : 0.0), st, (attn_fwd_kernel<T, false>), grid, dim3(256), 0, a);
     }
@@ -933,7 +933,7 @@ template <typename T> struct Runner {
       a.dog = dog; a.dO = dO; a.D = Dv; a.dqkvg = dqkvg; a.dS = dS;
       long long tot = gm.B * gm.L * H;
       PE_LAUNCH("attn_bwd_pre", 0, 5.0 * M * HD * sizeof(T), st, attn_bwd_pre_kernel<T>, dim3((unsigned)((tot * 8 + 255) / 256)), dim3(256), 0, a);
-      dim3 grid((unsigned)((gm.L + 127) / 128), H, (unsigned)gm.B);
+      dim3 grid(attn_grid_size(gm.B, H, gm.L));
       if (c.bias) PE_LAUNCH(gm.l_dq, 6.0 * gm.B * H * gm.L * gm.L * dh, 5.0 * M * HD * sizeof(T) + (c.bias ? 1.0 * gm.B * H * gm.L * gm.L * sizeof(T) : 0.0), st, (attn_bwd_dq_kernel<T, true>), grid, dim3(256), 0, a);
       else PE_LAUNCH(gm.l_dq, 6.0 * gm.B * H * gm.L * gm.L * dh, 5.0 * M * HD * sizeof(T) + (c.bias ? 1.0 * gm.B * H * gm.L * gm.L * sizeof(T) : 0.0), st, (attn_bwd_dq_kernel<T, false>), grid, dim3(256), 0, a);
       if (c.bias) PE_LAUNCH(gm.l_dkv, 8.0 * gm.B * H * gm.L * gm.L * dh, 6.0 * M * HD * sizeof(T), st, (attn_bwd_dkv_kernel<T, true>), grid, dim3(256), 0, a);
