@@ -846,7 +846,7 @@ struct ReduceArgs {
   int ylanes;
   int vec;   // 1 or 4 outputs per thread
 };
-// 256 threads = X outputs x Y split lanes (Y = a.ylanes in {1, 4, 16, 64}, X = 256 / Y); fixed
+// 256 threads = X outputs x Y split lanes (Y = a.ylanes in {1, 4, 16}, X = 256 / Y); fixed
 // summation order (deterministic).  Up to REDUCE_BATCH independent reductions per launch
 // (blockIdx.y selects one); their destinations must not overlap.
 constexpr int REDUCE_BATCH = 8;
