@@ -122,6 +122,58 @@ def test_stack_bf16_error_against_oracle_by_depth(capsys):
             print("  %5d  %.3e   %.3e   %.3e" % r)
 
 
+@pytest.mark.parametrize("keep", [False, True])
+def test_stack_hip_graph_capture_and_replay(keep):
+    """The whole stack call (here 1 extra-MSA + 3 main blocks, forward and backward, both streams) is
+    captured into one HIP graph; replays, with eager work of another case in between, reproduce the
+    eager result bit for bit."""
+    dims_m, mask, _ = dims_for("tiny")
+    dims_m.update(dtype=1, s=16, r=40)
+    dims_e = dict(dims_m, s=24, c_m=16, col_global=1)
+    te, ne = param_table(dims_e)
+    tm, nm = param_table(dims_m)
+    nb = 3
+    ie = make_inputs(dims_e, te, ne, ("random_rows", 0.1), 51)
+    im = make_inputs(dims_m, tm, nm, ("last_residues", 4), 52, n_blocks=nb)
+    bf, f32 = torch.bfloat16, torch.float32
+    par = to_dev(np.concatenate([ie["params"], im["params"]]), f32)
+    ex, msa, pair = to_dev(ie["msa"], bf), to_dev(im["msa"], bf), to_dev(im["pair"], bf)
+    exm, mm, pm = to_dev(ie["msa_mask"], f32), to_dev(im["msa_mask"], f32), to_dev(im["pair_mask"], f32)
+    dmo, dzo = to_dev(im["d_msa_out"], bf), to_dev(im["d_pair_out"], bf)
+    mo, zo, dex, dmi, dzi = (torch.empty_like(t) for t in (msa, pair, ex, msa, pair))
+    dpar = torch.zeros_like(par)
+    h = pe.Handle()
+    if keep:
+        h.set_option(5, 1)      # PE_OPT_STACK_KEEP_CTX
+    ws = torch.empty(pe.stack_workspace_bytes(1, dims_e, nb, dims_m, keep=keep), dtype=torch.uint8, device="cuda")
+    sm, sp = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = (mo, zo, dex, dmi, dzi, dpar)
+
+    def call():
+        pe.stack_fwd_bwd(h, 1, dims_e, nb, dims_m, ex, msa, pair, exm, mm, pm, par, dmo, dzo, mo, zo, dex, dmi, dzi,
+                         dpar, ws, sm, sp)
+    torch.cuda.synchronize()
+    call()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in outs]
+    dpar.zero_()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=sm):
+        call()
+    other = torch.randn(1 << 20, device="cuda")
+    for rep in range(3):
+        for t in outs:
+            t.zero_()
+        ws.zero_()
+        other = other * 1.0001 + 1.0     # unrelated eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (t, r) in enumerate(zip(outs, ref)):
+            assert torch.equal(t, r), (rep, i)
+
+
 def test_stack_argument_errors():
     dims, mask, seed = dims_for("tiny")
     table, n, inp = _stack_inputs(dims, 1, 1, mask)
