@@ -174,6 +174,72 @@ def test_stack_hip_graph_capture_and_replay(keep):
             assert torch.equal(t, r), (rep, i)
 
 
+def test_trunk_full_size_equals_chained_blocks():
+    """The trunk the bench times (4 extra-MSA blocks at s 1024 then 48 main blocks at s 128, r 256, bf16, every
+    block's activations kept: 69 GiB of workspace, offsets beyond 32 bits) is bit-identical to chaining
+    pe_block_fwd over the 52 blocks and pe_block_bwd (recompute) back over them.  With the block-level parity
+    at these shapes this carries the oracle comparison to the full-size trunk, which the float64 oracle
+    itself cannot run in test time."""
+    de, me, _ = dims_for("extra_msa")
+    dm, mmk, _ = dims_for("af2_initial")
+    ne, nm = 4, 48
+    te, n_e = param_table(de)
+    tm, n_m = param_table(dm)
+    ie = make_inputs(de, te, n_e, me, 4, n_blocks=ne)
+    im = make_inputs(dm, tm, n_m, mmk, 5, n_blocks=nm)
+    bf, f32 = torch.bfloat16, torch.float32
+    ex, msa, pair = to_dev(ie["msa"], bf), to_dev(im["msa"], bf), to_dev(im["pair"], bf)
+    exm, mm, pm = to_dev(ie["msa_mask"], f32), to_dev(im["msa_mask"], f32), to_dev(im["pair_mask"], f32)
+    par = torch.cat([to_dev(ie["params"], f32), to_dev(im["params"], f32)])
+    dmo, dzo = to_dev(im["d_msa_out"], bf), to_dev(im["d_pair_out"], bf)
+    mo, zo, dex, dmi, dzi = (torch.empty_like(t) for t in (msa, pair, ex, msa, pair))
+    dpar = torch.zeros_like(par)
+    h = pe.Handle()
+    h.set_option(5, 1)      # PE_OPT_STACK_KEEP_CTX
+    ws = torch.empty(pe.stack_workspace_bytes(ne, de, nm, dm, keep=True), dtype=torch.uint8, device="cuda")
+    assert ws.numel() > (1 << 32)
+    sm, sp = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    pe.stack_fwd_bwd(h, ne, de, nm, dm, ex, msa, pair, exm, mm, pm, par, dmo, dzo, mo, zo, dex, dmi, dzi, dpar, ws, sm, sp)
+    torch.cuda.synchronize()
+    del ws
+    torch.cuda.empty_cache()
+
+    h2 = pe.Handle()
+    wsb = torch.empty(max(pe.workspace_bytes(de, 1), pe.workspace_bytes(dm, 1)), dtype=torch.uint8, device="cuda")
+    off = lambda b: b * n_e if b < ne else ne * n_e + (b - ne) * n_m
+    xs_e, xs_m, zs = [ex], [msa], [pair]
+    for b in range(ne + nm):
+        is_e = b < ne
+        d_, x, mk = (de, xs_e[-1], exm) if is_e else (dm, xs_m[-1], mm)
+        n_ = n_e if is_e else n_m
+        xo, z2 = torch.empty_like(x), torch.empty_like(pair)
+        pe.block_fwd(h2, d_, x, zs[-1], mk, pm, par[off(b):off(b) + n_], xo, z2, None, wsb, sm, sp)
+        (xs_e if is_e else xs_m).append(xo)
+        zs.append(z2)
+    torch.cuda.synchronize()
+    assert torch.equal(mo, xs_m[-1]) and torch.equal(zo, zs[-1])
+    dpar2 = torch.zeros_like(par)
+    g_m, g_e, g_z = dmo, torch.zeros_like(ex), dzo
+    for b in reversed(range(ne + nm)):
+        is_e = b < ne
+        d_, mk, n_ = (de, exm, n_e) if is_e else (dm, mm, n_m)
+        x = xs_e[b] if is_e else xs_m[b - ne]
+        gx_in = g_e if is_e else g_m
+        gx, gz = torch.empty_like(x), torch.empty_like(pair)
+        pe.block_bwd(h2, d_, x, zs[b], mk, pm, par[off(b):off(b) + n_], gx_in, g_z, gx, gz,
+                     dpar2[off(b):off(b) + n_], None, wsb, sm, sp)
+        if is_e:
+            g_e = gx
+        else:
+            g_m = gx
+        g_z = gz
+    torch.cuda.synchronize()
+    assert torch.equal(dmi, g_m) and torch.equal(dex, g_e) and torch.equal(dzi, g_z)
+    assert torch.equal(dpar, dpar2)
+    assert bool(torch.isfinite(dpar).all()) and bool(torch.isfinite(zo.float()).all())
+
+
 def test_stack_argument_errors():
     dims, mask, seed = dims_for("tiny")
     table, n, inp = _stack_inputs(dims, 1, 1, mask)
