@@ -883,22 +883,24 @@ template <typename T> struct Runner {
 
   // ---- sub-operations: backward --------------------------------------------
   // g: running gradient w.r.t. the sub-op's output (and, after the call, its input) [M][C]
+  // g = gin + (gradient through the transition); gin defaults to g (in place)
   void trans_sub_bwd(hipStream_t st, Arena& ar, const TransP& p, const TransW<T>& w, const TransCtx<T>& c, const T* x, T* g,
-                     long long M, int Cc) {
+                     long long M, int Cc, const T* gin = nullptr) {
+    if (!gin) gin = g;
     size_t mk = ar.mark();
     const int nC = d.n_trans * Cc;
     T* dh = (T*)ar.alloc((size_t)M * nC * sizeof(T));
     T* dxh = (T*)ar.alloc((size_t)M * Cc * sizeof(T));
     { ReduceSeg sg[1] = {{0, Cc, p.w2, Cc}}, cb = {0, Cc, p.b2, 0};
-      gemm_dw(st, ar, op_trans(c.h, nC), false, op_trans(g, Cc), false, nC, Cc, M, 1, sg, "trans dW2", 1, &cb); }
+      gemm_dw(st, ar, op_trans(c.h, nC), false, op_trans(gin, Cc), false, nC, Cc, M, 1, sg, "trans dW2", 1, &cb); }
     { EpiGeneric<T> e = epi_plain<T>(dh, nC);
       e.relu_mask = c.h; e.ld_rm = nC;
-      gemm(st, op_plain(g, Cc), true, op_plain(w.wn_2, Cc), true, (int)M, nC, Cc, 1, e, "trans dh"); }
+      gemm(st, op_plain(gin, Cc), true, op_plain(w.wn_2, Cc), true, (int)M, nC, Cc, 1, e, "trans dh"); }
     { ReduceSeg sg[1] = {{0, nC, p.w1, nC}}, cb = {0, nC, p.b1, 0};
       gemm_dw(st, ar, op_trans(c.xhat, Cc), false, op_trans(dh, nC), false, Cc, nC, M, 1, sg, "trans dW1", 1, &cb); }
     { EpiGeneric<T> e = epi_plain<T>(dxh, Cc);
       gemm(st, op_plain(dh, nC), true, op_plain(w.wn_1, nC), true, (int)M, Cc, nC, 1, e, "trans dxhat"); }
-    k_ln_bwd(st, ar, dxh, x, c.stats, p.ln_g, p.ln_b, g, g, M, Cc);
+    k_ln_bwd(st, ar, dxh, x, c.stats, p.ln_g, p.ln_b, gin, g, M, Cc);
     flush_reduces(st);
     ar.release(mk);
   }
@@ -1139,11 +1141,8 @@ template <typename T> struct Runner {
   void bwd_pair_step(int i, const T* d_pair_out, T* gz, const T* z_in) {
     switch (i) {
       case 0:
-        if (!dry && !err) {
-          if (hipMemcpyAsync(gz, d_pair_out, (size_t)Mz * d.c_z * sizeof(T), hipMemcpyDeviceToDevice, sp) != hipSuccess)
-            fail("copy gz");
-        }
-        trans_sub_bwd(sp, ap, PL.ptrans, W.pt, C.pt, C.z4, gz, Mz, d.c_z);
+        // the running pair gradient gz starts as the output cotangent: read in place, no copy
+        trans_sub_bwd(sp, ap, PL.ptrans, W.pt, C.pt, C.z4, gz, Mz, d.c_z, d_pair_out);
         break;
       case 1: attn_sub_bwd(sp, ap, PL.tae, W.tae, C.tae, C.z3, gz, Mz, d.c_z, d.h_pair, d.d_pair, geom_tae(), C.z3,
                            PL.tae.ln_g, PL.tae.ln_b, gz, gz); break;
