@@ -924,9 +924,31 @@ template <typename T> struct Runner {
     }
     { ReduceSeg sg[1] = {{0, Cc, p.w_o, Cc}}, cb = {0, Cc, p.b_o, 0};
       gemm_dw(st, ar, op_heads_cols(c.og, gm, dh, M * dh), false, op_trans(g, Cc), false, HD, Cc, M, 1, sg, "attn dWo", 1, &cb); }
-    { EpiGeneric<T> e = epi_plain<T>(dog, HD);
+    // dog = g W_o^T; its epilogue turns dog into dO, the gate gradient and D (no dog tensor, no pass of its
+    // own) whenever the vector epilogue applies
+    bool pre_fused = false;
+    {
+      EpiAttnPre<T> ep;
+      ep.gate = c.qkvg + 3LL * H * M * dh; ep.o = c.o; ep.dO = dO; ep.dgate = dqkvg + 3LL * H * M * dh; ep.D = Dv;
+      ep.plane = M * dh; ep.H = H; ep.dh = dh; ep.L = (int)gm.L; ep.tr = gm.tr; ep.inner = (int)gm.inner;
+      const Operand A = op_plain(g, Cc), B = op_plain(w.wn_o, Cc);
+      GemmShape sh{(int)M, HD, Cc, 1, 0};
+      pre_fused = ep.vec_ok(HD) && gemm_operand_ok<T>(A, true, (int)M, sh) && gemm_operand_ok<T>(B, true, HD, sh);
+      if (pre_fused && !dry && !err) {
+        prof_begin(st);
+        bool al = false, narrow = false;
+        int rc = launch_gemm<T, EpiAttnPre<T>>(st, A, true, B, true, sh, ep, &al, &narrow);
+        prof_end(st, "attn dog+pre", narrow ? "gemm64_kernel<EpiAttnPre>" : "gemm_kernel<kc,kc,vec,EpiAttnPre>", 2.0 * M * HD * Cc,
+                 ((double)M * Cc + (double)HD * Cc + 4.0 * M * HD) * sizeof(T));
+        if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = "gemm operand alignment: attn dog"; }
+        else check("attn dog+pre");
+      }
+    }
+    if (!pre_fused) {
+      EpiGeneric<T> e = epi_plain<T>(dog, HD);
       epi_heads(e, gm, dh, M * dh);
-      gemm(st, op_plain(g, Cc), true, op_plain(w.wn_o, Cc), true, (int)M, HD, Cc, 1, e, "attn dog"); }
+      gemm(st, op_plain(g, Cc), true, op_plain(w.wn_o, Cc), true, (int)M, HD, Cc, 1, e, "attn dog");
+    }
     if (!dry && !err) {
       AttnArgs a;
       memset(&a, 0, sizeof(a));
@@ -936,7 +958,8 @@ template <typename T> struct Runner {
       a.o = c.o; a.og = c.og; a.lse = c.lse; a.scale = 1.0f / sqrtf((float)dh);
       a.dog = dog; a.dO = dO; a.D = Dv; a.dqkvg = dqkvg; a.dS = dS;
       long long tot = gm.B * gm.L * H;
-      PE_LAUNCH("attn_bwd_pre", 0, 5.0 * M * HD * sizeof(T), st, attn_bwd_pre_kernel<T>, dim3((unsigned)((tot * 8 + 255) / 256)), dim3(256), 0, a);
+      if (!pre_fused)
+        PE_LAUNCH("attn_bwd_pre", 0, 5.0 * M * HD * sizeof(T), st, attn_bwd_pre_kernel<T>, dim3((unsigned)((tot * 8 + 255) / 256)), dim3(256), 0, a);
       dim3 grid(attn_grid_size(gm.B, H, gm.L));
       if (c.bias) PE_LAUNCH(gm.l_dq, 6.0 * gm.B * H * gm.L * gm.L * dh, 5.0 * M * HD * sizeof(T) + (c.bias ? 1.0 * gm.B * H * gm.L * gm.L * sizeof(T) : 0.0), st, (attn_bwd_dq_kernel<T, true>), grid, dim3(256), 0, a);
       else PE_LAUNCH(gm.l_dq, 6.0 * gm.B * H * gm.L * gm.L * dh, 5.0 * M * HD * sizeof(T) + (c.bias ? 1.0 * gm.B * H * gm.L * gm.L * sizeof(T) : 0.0), st, (attn_bwd_dq_kernel<T, false>), grid, dim3(256), 0, a);

@@ -270,6 +270,61 @@ struct EpiPartial {
 // ---------------------------------------------------------------------------
 // Kernel
 // ---------------------------------------------------------------------------
+// Epilogue of the GEMM that produces the cotangent of the gated attention output (dog = dY W_o^T): instead
+// of storing dog it finishes the attention backward's first step on the tile, for head-major tensors
+// (element (h, position, c) at h*plane + position*dh + c):
+//   dO = dog * sigmoid(g)  (stored),  dg = dog * o * s(1-s) -> gate slot of dqkvg,  D[b][h][p] = sum_c dO * o.
+// Vector epilogue only (a lane holds 8 consecutive channels of one head; the dh/8 lanes of a head are
+// neighbours and always active together); the host falls back to a plain GEMM + a pass of its own otherwise.
+template <typename T> struct EpiAttnPre {
+  static constexpr bool HAS_COLSUM = false;
+  const T* gate;       // gate pre-activation plane group: qkvg + 3*H*plane
+  const T* o;
+  T* dO;
+  T* dgate;            // dqkvg + 3*H*plane
+  float* D;            // [B][H][L]
+  long long plane;
+  int H, dh, L;
+  int tr, inner;       // tr = 1: GEMM row m = p*inner + b (else m = b*L + p)
+  struct Row { long long o; };
+  struct Col { long long o; };
+  PE_DEV Row row(int, int) const { return Row{0}; }
+  PE_DEV Col col(int) const { return Col{0}; }
+  PE_DEV void operator()(int, int, const Row&, const Col&, float) const {}   // element-wise path: never launched
+  int features() const { return 0; }
+  bool vec_ok(int N) const {
+    return N % 8 == 0 && dh % 8 == 0 && (dh == 8 || dh == 16 || dh == 32) && plane % 8 == 0 &&
+           ((uintptr_t)gate) % 16 == 0 && ((uintptr_t)o) % 16 == 0 && ((uintptr_t)dO) % 16 == 0 && ((uintptr_t)dgate) % 16 == 0;
+  }
+  struct ColV { int h, c; };
+  template <int F> PE_DEV void colv(int n, ColV& cv) const {
+    cv.h = (int)((unsigned)n / (unsigned)dh);
+    cv.c = (int)((unsigned)n % (unsigned)dh);
+  }
+  template <int F> PE_DEV void vec8(int, int m, int, const ColV& cv, float (&v)[8]) const {
+    int b, pp;
+    if (tr) { pp = (int)((unsigned)m / (unsigned)inner); b = (int)((unsigned)m % (unsigned)inner); }
+    else { b = (int)((unsigned)m / (unsigned)L); pp = (int)((unsigned)m % (unsigned)L); }
+    const long long idx = (long long)cv.h * plane + ((long long)b * L + pp) * dh + cv.c;
+    float gv[8], ov[8], dov[8], dgv[8];
+    load8<T>(gate + idx, gv);
+    load8<T>(o + idx, ov);
+    float Dsum = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      const float sg = sigmoidf_(gv[e]);
+      dov[e] = to_f(from_f<T>(v[e] * sg));
+      dgv[e] = v[e] * ov[e] * sg * (1.0f - sg);
+      Dsum += dov[e] * ov[e];
+    }
+    store8<T>(dO + idx, dov);
+    store8<T>(dgate + idx, dgv);
+    if (dh >= 16) Dsum += __shfl_xor(Dsum, 1, 64);
+    if (dh >= 32) Dsum += __shfl_xor(Dsum, 2, 64);
+    if (cv.c == 0) D[((long long)b * H + cv.h) * L + pp] = Dsum;
+  }
+};
+
 template <typename T> struct GemmCfg {
   static constexpr int VEC = Vec16<T>::N;
   static constexpr int BM = 128, BN = 128;

@@ -52,6 +52,18 @@ def test_ragged_shapes(dtype):
     _assert(errs, worst, SMALL_BF16_TOL if dtype == 1 else tol)
 
 
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_head_dim_24(dtype):
+    """Head dimension 24 (three 8-channel groups per head): the attention kernels pad the contraction, and the
+    backward takes the separate pre-pass instead of the fused GEMM epilogue, which wants 8, 16 or 32."""
+    dims, table, inp = _case("tiny", dtype=dtype, s=20, r=72, c_m=64, c_z=32, h_msa=2, d_msa=24, h_pair=2,
+                             d_pair=24, c_tri=16, c_opm=8, n_trans=2)
+    table, n = param_table(dims)
+    inp = make_inputs(dims, table, n, ("random_residues", 0.1), 9)
+    errs, worst, tol, _ = check_case(dims, table, inp)
+    _assert(errs, worst, SMALL_BF16_TOL if dtype == 1 else tol)
+
+
 @pytest.mark.parametrize("use_ctx", [True, False])
 @pytest.mark.parametrize("dtype", [0, 1])
 @pytest.mark.parametrize("variant", [1, 2])
