@@ -510,6 +510,151 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 }
 
 // ---------------------------------------------------------------------------
+// Backward, dQ for TWO batch rows per workgroup (biased attention only).  Waves 0-3 work on batch row
+// 2u, waves 4-7 on row 2u+1 of the same head and query tile, each group exactly as attn_bwd_dq_kernel
+// with its own LDS tiles.  The bias gradient is a sum over the batch axis, so the two groups add their
+// dS tiles before the write: the upper group passes each 32x32 tile through LDS (two buffers, one
+// workgroup barrier per tile), the lower group adds its own and stores dS^T[u][h][key][query].  That
+// halves the dS traffic and the input of the reduction that follows.  With an odd B the last
+// workgroup's upper group runs on row B-1 again and contributes nothing.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) void attn_bwd_dq2_kernel(AttnArgs a) {
+  typedef AttnCfg<T> C;
+  typedef Mma<T> MM;
+  __shared__ __attribute__((aligned(16))) T lds_k2[2][C::KT * C::RM];
+  __shared__ __attribute__((aligned(16))) T lds_kt2[2][32 * C::TS];
+  __shared__ __attribute__((aligned(16))) T lds_v2[2][C::KT * C::RM];
+  __shared__ __attribute__((aligned(16))) float lds_madd2[2][C::KT];
+  __shared__ __attribute__((aligned(16))) float lds_x[2][4][16][64];   // [buffer][wave of the upper group][element][lane]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave8 = tid >> 6, l32 = lane & 31, g = lane >> 5;
+  const int grp = wave8 >> 2, wave = wave8 & 3, tg = tid & 255;
+  // XCD-aware decode as in attn_decode_wg, over (pair of batch rows, head) units
+  const int nt = (a.L + 127) / 128, Bp = (a.B + 1) / 2;
+  const int xcd = blockIdx.x & 7, jq = blockIdx.x >> 3;
+  const int u = (jq / nt) * 8 + xcd;
+  if (u >= Bp * a.H) return;
+  const int tile = jq % nt, h = u % a.H, bp = u / a.H;
+  const bool bvalid = 2 * bp + grp < a.B;
+  const int b = bvalid ? 2 * bp + grp : a.B - 1;
+  T* lds_k = lds_k2[grp];
+  T* lds_kt = lds_kt2[grp];
+  T* lds_v = lds_v2[grp];
+  float* lds_madd = lds_madd2[grp];
+
+  const int L = a.L, d = a.d;
+  const int DP = round_up_i(d, MM::KSTEP);
+  const int NKK = DP / MM::KSTEP;
+  const int qi = tile * 128 + wave * 32 + l32;
+  const bool qok = qi < L;
+  const long long HP = (long long)a.H * a.plane;
+  const T* base = (const T*)a.qkvg + h * a.plane + (long long)b * L * d;
+  const T* qrow = qok ? base + qi * d : nullptr;
+  const long long orow = h * a.plane + ((long long)b * L + qi) * d;
+  const T* dorow = qok ? (const T*)a.dO + orow : nullptr;
+
+  constexpr int MAXKK = 32 / MM::KSTEP;
+  typename MM::frag qf[MAXKK], dof[MAXKK];
+#pragma unroll
+  for (int kk = 0; kk < MAXKK; kk++)
+    if (kk < NKK) {
+      qf[kk] = gl_frag<T>(qrow, kk, g, d);
+      dof[kk] = gl_frag<T>(dorow, kk, g, d);
+    }
+  const long long sidx = ((long long)b * a.H + h) * L + qi;
+  const float lse2 = qok ? a.lse[sidx] * PE_LOG2E : 0.0f;
+  const float Di = qok ? a.D[sidx] : 0.0f;
+  const float* bplane = a.biasT + (long long)h * L * L;   // [key][query]
+  const int bcolq = min(qi, L - 1);
+  T* dsplane = (T*)a.dS + ((long long)bp * a.H + h) * L * L;   // summed pair of rows
+  const unsigned dsoff = (unsigned)(4 * g * L + qi) * (unsigned)sizeof(T);
+  const float c1 = a.scale * PE_LOG2E;
+
+  f32x16 dq;
+#pragma unroll
+  for (int e = 0; e < 16; e++) dq[e] = 0.0f;
+
+  int xb = 0;   // exchange buffer of the current tile
+  for (int j0 = 0; j0 < L; j0 += C::KT) {
+    __syncthreads();
+    attn_stage<T>(base + HP, d, j0, L, d, DP, lds_k, lds_kt, tg, 256);
+    attn_stage<T>(base + 2 * HP, d, j0, L, d, DP, lds_v, (T*)nullptr, tg, 256);
+    if (tg < C::KT) {
+      int j = j0 + tg;
+      float mk = (j < L) ? a.mask[(long long)b * a.mask_bs + (long long)j * a.mask_ks] : 0.0f;
+      lds_madd[tg] = (mk > 0.0f) ? 0.0f : -INFINITY;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int jt = 0; jt < C::KT / 32; jt++) {
+      const int kt0 = j0 + jt * 32;
+      if (kt0 >= L) break;   // uniform over the workgroup
+      float bv[16];
+      attn_load_bias16_split(bplane, L, kt0, g, bcolq, bv);
+      f32x16 sacc, pacc;
+#pragma unroll
+      for (int e = 0; e < 16; e++) { sacc[e] = 0.0f; pacc[e] = 0.0f; }
+#pragma unroll
+      for (int kk = 0; kk < MAXKK; kk++)
+        if (kk < NKK) {
+          int off = (jt * 32 + l32) * C::RM + kk * MM::KSTEP + g * MM::KP;
+          MM::mma(sacc, MM::load(lds_k + off), qf[kk]);      // S^T = K Q^T
+          MM::mma(pacc, MM::load(lds_v + off), dof[kk]);     // dP^T = V dO^T
+        }
+#pragma unroll
+      for (int q4 = 0; q4 < 4; q4++) {
+        f32x4 ma = *reinterpret_cast<const f32x4*>(lds_madd + jt * 32 + 8 * q4 + 4 * g);
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+          int e = q4 * 4 + r;
+          float t = fmaf(sacc[e], c1, bv[e]);
+          float p = fast_exp2(t + ma[r] - lse2);
+          sacc[e] = p * (pacc[e] - Di);
+        }
+      }
+      // the upper group hands its dS tile over; the lower group adds its own and writes the sum
+      if (grp == 1) {
+#pragma unroll
+        for (int e = 0; e < 16; e++) lds_x[xb][wave][e][lane] = bvalid ? sacc[e] : 0.0f;
+      }
+      __syncthreads();
+      if (grp == 0 && qok) {
+        if (kt0 + 32 <= L) {
+#pragma unroll
+          for (int e = 0; e < 16; e++) {
+            char* urow = (char*)(dsplane + (long long)(kt0 + 8 * (e >> 2) + (e & 3)) * L);   // wave-uniform
+            *(T*)(urow + dsoff) = from_f<T>(sacc[e] + lds_x[xb][wave][e][lane]);
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 16; e++) {
+            int key = kt0 + acc_row(g, e);
+            if (key < L) dsplane[(long long)key * L + qi] = from_f<T>(sacc[e] + lds_x[xb][wave][e][lane]);
+          }
+        }
+      }
+      xb ^= 1;
+      const T* krow = lds_kt + l32 * C::TS + jt * 32;
+#pragma unroll
+      for (int uu = 0; uu < 32 / MM::KSTEP; uu++) MM::mma(dq, lds_tfrag<T>(krow, g, uu), acc_to_frag<T>(sacc, uu));
+    }
+  }
+  if (!qok || !bvalid) return;
+  T* pdq = (T*)a.dqkvg + orow;
+#pragma unroll
+  for (int q4 = 0; q4 < 4; q4++) {
+    int dd = 8 * q4 + 4 * g;
+    if (dd < d) {
+      float v[4];
+#pragma unroll
+      for (int r = 0; r < 4; r++) v[r] = dq[q4 * 4 + r] * a.scale;
+      store4<T>(pdq + dd, v);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Backward, dK and dV.  Wave w owns keys k0 = tile*128 + 32*w (a key is a lane);
 // loops over query tiles staged in LDS (row-major and transposed copies of Q and dO).
 // ---------------------------------------------------------------------------

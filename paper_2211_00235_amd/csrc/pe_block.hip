@@ -961,14 +961,16 @@ template <typename T> struct Runner {
       if (!pre_fused)
         PE_LAUNCH("attn_bwd_pre", 0, 5.0 * M * HD * sizeof(T), st, attn_bwd_pre_kernel<T>, dim3((unsigned)((tot * 8 + 255) / 256)), dim3(256), 0, a);
       dim3 grid(attn_grid_size(gm.B, H, gm.L));
-      if (c.bias) PE_LAUNCH(gm.l_dq, 6.0 * gm.B * H * gm.L * gm.L * dh, 5.0 * M * HD * sizeof(T) + (c.bias ? 1.0 * gm.B * H * gm.L * gm.L * sizeof(T) : 0.0), st, (attn_bwd_dq_kernel<T, true>), grid, dim3(256), 0, a);
+      // biased attention: two batch rows per workgroup, their dS tiles summed before the write
+      const long long Bds = c.bias ? (gm.B + 1) / 2 : gm.B;
+      if (c.bias) PE_LAUNCH(gm.l_dq, 6.0 * gm.B * H * gm.L * gm.L * dh, 5.0 * M * HD * sizeof(T) + 1.0 * Bds * H * gm.L * gm.L * sizeof(T), st, (attn_bwd_dq2_kernel<T>), dim3(attn_grid_size(Bds, H, gm.L)), dim3(512), 0, a);
       else PE_LAUNCH(gm.l_dq, 6.0 * gm.B * H * gm.L * gm.L * dh, 5.0 * M * HD * sizeof(T) + (c.bias ? 1.0 * gm.B * H * gm.L * gm.L * sizeof(T) : 0.0), st, (attn_bwd_dq_kernel<T, false>), grid, dim3(256), 0, a);
       if (c.bias) PE_LAUNCH(gm.l_dkv, 8.0 * gm.B * H * gm.L * gm.L * dh, 6.0 * M * HD * sizeof(T), st, (attn_bwd_dkv_kernel<T, true>), grid, dim3(256), 0, a);
       else PE_LAUNCH(gm.l_dkv, 8.0 * gm.B * H * gm.L * gm.L * dh, 6.0 * M * HD * sizeof(T), st, (attn_bwd_dkv_kernel<T, false>), grid, dim3(256), 0, a);
       if (c.bias) {
         long long hll = (long long)H * gm.L * gm.L;
-        PE_LAUNCH("attn_dbias_reduce", 0, 1.0 * gm.B * hll * sizeof(T) + 4.0 * hll, st, attn_dbias_reduce_kernel<T>, dim3((unsigned)((hll + 255) / 256)), dim3(256), 0, dS, dbias,
-                           (int)gm.B, hll);
+        PE_LAUNCH("attn_dbias_reduce", 0, 1.0 * Bds * hll * sizeof(T) + 4.0 * hll, st, attn_dbias_reduce_kernel<T>, dim3((unsigned)((hll + 255) / 256)), dim3(256), 0, dS, dbias,
+                           (int)Bds, hll);
       }
     }
     { ReduceSeg sg[4] = {{0, HD, p.w_q, HD}, {HD, HD, p.w_k, HD}, {2 * HD, HD, p.w_v, HD}, {3 * HD, HD, p.w_g, HD}};
