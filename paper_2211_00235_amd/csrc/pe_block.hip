@@ -414,6 +414,8 @@ template <typename T> struct Runner {
   // the critical path of the backward pass and its kernels have small grids, so it runs on a
   // second stream per branch, forked from / joined to the branch's stream with events.  A join
   // happens before any buffer the side stream reads is overwritten or released.
+  // true when no other branch's kernels run beside this call's: both branches on one stream, or one branch only
+  bool alone() const { return sm == sp || (h && h->branches != 3); }
   bool side_dirty[2] = {false, false};
   int side_idx(hipStream_t st) const { return (st == sp && sp != sm) ? 1 : 0; }
   bool side_on() const { return !dry && h && h->side_streams; }
@@ -520,10 +522,11 @@ template <typename T> struct Runner {
       GemmShape sh{M, N, K, nsplit, (int)kc};
       EpiPartial ep{part, (long long)M * N, N};
       prof_begin(st);
-      bool al = false;
-      int rc = launch_gemm<T, EpiPartial>(st, A, akc, B, bkc, sh, ep, &al);
+      bool al = false, dwx = false;
+      int rc = launch_gemm<T, EpiPartial>(st, A, akc, B, bkc, sh, ep, &al, &dwx, alone());
       char kn[64];
-      snprintf(kn, sizeof(kn), "gemm_kernel<%s,%s,%s,EpiPartial>", akc ? "kc" : "xc", bkc ? "kc" : "xc", al ? "vec" : "elem");
+      if (dwx) snprintf(kn, sizeof(kn), "gemm_dwx_kernel<%d>", DWX_GROUPS);
+      else snprintf(kn, sizeof(kn), "gemm_kernel<%s,%s,%s,EpiPartial>", akc ? "kc" : "xc", bkc ? "kc" : "xc", al ? "vec" : "elem");
       prof_end(st, what, kn, 2.0 * M * N * K, ((double)M * K + (double)N * K) * sizeof(T));
       if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = std::string("gemm operand alignment: ") + what; return; }
       check(what);
@@ -562,10 +565,11 @@ template <typename T> struct Runner {
       GemmShape sh{rows, cols, (int)K, nsplit, (int)kc};
       EpiPartial ep{part, (long long)rows * cols, cols, cs_part};
       prof_begin(st);
-      bool al = false;
-      int rc = launch_gemm<T, EpiPartial>(st, X, xkc, Y, ykc, sh, ep, &al);
+      bool al = false, dwx = false;
+      int rc = launch_gemm<T, EpiPartial>(st, X, xkc, Y, ykc, sh, ep, &al, &dwx, alone());
       char kn[64];
-      snprintf(kn, sizeof(kn), "gemm_kernel<%s,%s,%s,EpiPartial>", xkc ? "kc" : "xc", ykc ? "kc" : "xc", al ? "vec" : "elem");
+      if (dwx) snprintf(kn, sizeof(kn), "gemm_dwx_kernel<%d>", DWX_GROUPS);
+      else snprintf(kn, sizeof(kn), "gemm_kernel<%s,%s,%s,EpiPartial>", xkc ? "kc" : "xc", ykc ? "kc" : "xc", al ? "vec" : "elem");
       prof_end(st, what, kn, 2.0 * rows * cols * K, ((double)rows * K + (double)cols * K) * sizeof(T));
       if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = std::string("gemm_dw operand alignment: ") + what; }
       else check(what);

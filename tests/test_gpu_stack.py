@@ -75,17 +75,23 @@ def test_stack_equals_chained_blocks(dtype, keep):
     params = to_dev(inp["params"], f32)
     xs, zs = [to_dev(inp["msa"], dt)], [to_dev(inp["pair"], dt)]
     ws = torch.empty(pe.workspace_bytes(dims, 1), dtype=torch.uint8, device="cuda")
+    # two streams, as in the stack run: a call that has the chip to itself (one stream) sums its bf16
+    # parameter gradients in another order
+    sm, sp = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = [(torch.empty_like(xs[0]), torch.empty_like(zs[0])) for _ in range(nb)]
+    dm, dz = to_dev(inp["d_msa_out"], dt), to_dev(inp["d_pair_out"], dt)
+    grads = [(torch.empty_like(dm), torch.empty_like(dz)) for _ in range(nb)]
+    dpar2 = torch.zeros_like(params)
+    torch.cuda.synchronize()
     for b in range(nb):
-        xo, zo2 = torch.empty_like(xs[0]), torch.empty_like(zs[0])
-        pe.block_fwd(h, dims, xs[b], zs[b], mm, pm, params[b * n:(b + 1) * n], xo, zo2, None, ws)
+        xo, zo2 = outs[b]
+        pe.block_fwd(h, dims, xs[b], zs[b], mm, pm, params[b * n:(b + 1) * n], xo, zo2, None, ws, sm, sp)
         xs.append(xo)
         zs.append(zo2)
-    dm, dz = to_dev(inp["d_msa_out"], dt), to_dev(inp["d_pair_out"], dt)
-    dpar2 = torch.zeros_like(params)
     for b in reversed(range(nb)):
-        dmi2, dzi2 = torch.empty_like(dm), torch.empty_like(dz)
+        dmi2, dzi2 = grads[b]
         pe.block_bwd(h, dims, xs[b], zs[b], mm, pm, params[b * n:(b + 1) * n], dm, dz, dmi2, dzi2,
-                     dpar2[b * n:(b + 1) * n], None, ws)
+                     dpar2[b * n:(b + 1) * n], None, ws, sm, sp)
         dm, dz = dmi2, dzi2
     torch.cuda.synchronize()
     assert torch.equal(mo, xs[-1]) and torch.equal(zo, zs[-1])
