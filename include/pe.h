@@ -27,6 +27,13 @@
  *    to stream_msa); at return both streams are joined, so outputs may be
  *    consumed on either stream.  stream_msa == stream_pair is allowed and
  *    serialises the branches.
+ *  - Results are deterministic: no atomics, every reduction in a fixed order.
+ *    A call that has the device to itself (stream_msa == stream_pair, or one
+ *    branch selected with PE_OPT_BRANCHES) takes a parameter-gradient kernel
+ *    that sums the contraction index in another fixed order than the
+ *    two-stream call does: outputs and input cotangents are bit-identical
+ *    between the two modes, bf16-path parameter gradients agree to fp32
+ *    rounding.
  *  - Return value 0 = PE_OK, negative = error (see pe_strerror).  Arguments
  *    are validated before anything is launched.
  */
