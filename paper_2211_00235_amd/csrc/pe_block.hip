@@ -244,6 +244,15 @@ template <typename T> static void prep_trimul(PrepCarver<T>& pc, TriMulW<T>& w, 
 // ---------------------------------------------------------------------------
 // Runner: one block, one storage type
 // ---------------------------------------------------------------------------
+// out = a + b, element-wise; 8 elements per thread when the size and the pointers allow 16-byte accesses
+template <typename T> static void launch_add2(hipStream_t st, const T* a, const T* b, T* out, long long n) {
+  auto al = [](const void* q) { return ((uintptr_t)q) % 16 == 0; };
+  if (n % 8 == 0 && al(a) && al(b) && al(out))
+    hipLaunchKernelGGL(add2x8_kernel<T>, dim3((unsigned)((n / 8 + 255) / 256)), dim3(256), 0, st, a, b, out, n);
+  else
+    hipLaunchKernelGGL(add2_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a, b, out, n);
+}
+
 template <typename T> struct Runner {
   pe_handle* h;
   pe_dims d;
@@ -415,6 +424,7 @@ template <typename T> struct Runner {
   // second stream per branch, forked from / joined to the branch's stream with events.  A join
   // happens before any buffer the side stream reads is overwritten or released.
   // true when no other branch's kernels run beside this call's: both branches on one stream, or one branch only
+  static bool al16(const void* q) { return ((uintptr_t)q) % 16 == 0; }
   bool alone() const { return sm == sp || (h && h->branches != 3); }
   bool side_dirty[2] = {false, false};
   int side_idx(hipStream_t st) const { return (st == sp && sp != sm) ? 1 : 0; }
@@ -757,8 +767,12 @@ template <typename T> struct Runner {
     }
     if (!dry && !err) {
       long long n = (long long)ct * Mz;
-      PE_LAUNCH("tm_gate_fwd", 0, 6.0 * n * sizeof(T), st, tm_gate_fwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c.proj_t, pair_mask,
-                         c.a_t, c.b_t, ct, Mz);
+      if (Mz % 8 == 0 && al16(c.proj_t) && al16(pair_mask) && al16(c.a_t) && al16(c.b_t))
+        PE_LAUNCH("tm_gate_fwd", 0, 6.0 * n * sizeof(T), st, tm_gate_fwd8_kernel<T>, dim3((unsigned)((n / 8 + 255) / 256)), dim3(256), 0, c.proj_t,
+                  pair_mask, c.a_t, c.b_t, ct, Mz);
+      else
+        PE_LAUNCH("tm_gate_fwd", 0, 6.0 * n * sizeof(T), st, tm_gate_fwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c.proj_t, pair_mask,
+                  c.a_t, c.b_t, ct, Mz);
     }
     {  // per-channel contraction over the third residue
       EpiGeneric<T> e = epi_plain<T>(c.x_t, r);
@@ -1032,7 +1046,10 @@ template <typename T> struct Runner {
     T* dzh = (T*)ar.alloc((size_t)Mz * cz * sizeof(T));
     if (!dry && !err) {
       long long n = Mz * cz;
-      PE_LAUNCH("tm_out_bwd", 0, 5.0 * n * sizeof(T), st, tm_out_bwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, g, c.g, c.u, du, dgraw, n);
+      if (n % 8 == 0 && al16(g) && al16(c.g) && al16(c.u) && al16(du) && al16(dgraw))
+        PE_LAUNCH("tm_out_bwd", 0, 5.0 * n * sizeof(T), st, tm_out_bwd8_kernel<T>, dim3((unsigned)((n / 8 + 255) / 256)), dim3(256), 0, g, c.g, c.u, du, dgraw, n);
+      else
+        PE_LAUNCH("tm_out_bwd", 0, 5.0 * n * sizeof(T), st, tm_out_bwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, g, c.g, c.u, du, dgraw, n);
     }
     { ReduceSeg sg[1] = {{0, cz, p.w_o, cz}}, cb = {0, cz, p.b_o, 0};
       gemm_dw(st, ar, op_trans(c.xhat, ct), false, op_trans(du, cz), false, ct, cz, Mz, 1, sg, "trimul dWo", 1, &cb); }
@@ -1071,8 +1088,12 @@ template <typename T> struct Runner {
     }
     if (!dry && !err) {
       long long n = (long long)ct * Mz;
-      PE_LAUNCH("tm_gate_bwd", 0, 10.0 * n * sizeof(T), st, tm_gate_bwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c.proj_t, pair_mask,
-                         da_t, db_t, dproj_t, ct, Mz);
+      if (Mz % 8 == 0 && al16(c.proj_t) && al16(pair_mask) && al16(da_t) && al16(db_t) && al16(dproj_t))
+        PE_LAUNCH("tm_gate_bwd", 0, 10.0 * n * sizeof(T), st, tm_gate_bwd8_kernel<T>, dim3((unsigned)((n / 8 + 255) / 256)), dim3(256), 0, c.proj_t,
+                  pair_mask, da_t, db_t, dproj_t, ct, Mz);
+      else
+        PE_LAUNCH("tm_gate_bwd", 0, 10.0 * n * sizeof(T), st, tm_gate_bwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c.proj_t, pair_mask,
+                  da_t, db_t, dproj_t, ct, Mz);
     }
     { ReduceSeg sg[4] = {{0, ct, p.w_ap, ct}, {ct, ct, p.w_ag, ct}, {2 * ct, ct, p.w_bp, ct}, {3 * ct, ct, p.w_bg, ct}};
       ReduceSeg cb[4] = {{0, ct, p.b_ap, 0}, {ct, ct, p.b_ag, 0}, {2 * ct, ct, p.b_bp, 0}, {3 * ct, ct, p.b_bg, 0}};
@@ -1361,7 +1382,7 @@ static int block_bwd_impl(pe_handle* h, const pe_dims& d, const void* msa_in, co
     if (do_m && !ev_link(h, 1, sm, sp)) return PE_ERR_HIP;
     if (!R.err) {
       if (do_m && do_p) {
-        hipLaunchKernelGGL(add2_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, sp, gz, dzb, (T*)d_pair_in, n);
+        launch_add2<T>(sp, gz, dzb, (T*)d_pair_in, n);
         R.check("add d_pair_in");
       } else if (do_p) {
         if (!hip_ok(h, hipMemcpyAsync(d_pair_in, gz, (size_t)n * sizeof(T), hipMemcpyDeviceToDevice, sp), "copy")) return PE_ERR_HIP;
@@ -1379,7 +1400,7 @@ static int block_bwd_impl(pe_handle* h, const pe_dims& d, const void* msa_in, co
     R.bwd_opm(gz, R.C.m3, (const T*)d_msa_out, gm);
     R.bwd_msa_stack(gm, R.pair_in, dzb);
     if (!R.err) {
-      hipLaunchKernelGGL(add2_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, sm, gz, dzb, (T*)d_pair_in, n);
+      launch_add2<T>(sm, gz, dzb, (T*)d_pair_in, n);
       R.check("add d_pair_in");
     }
   } else {
@@ -1390,7 +1411,7 @@ static int block_bwd_impl(pe_handle* h, const pe_dims& d, const void* msa_in, co
     R.bwd_stacks(true, true, (const T*)d_pair_out, gz, R.C.z0, gm, R.C.z0, dzb);
     if (!ev_link(h, 1, sp, sm)) return PE_ERR_HIP;
     if (!R.err) {
-      hipLaunchKernelGGL(add2_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, sm, gz, dzb, (T*)d_pair_in, n);
+      launch_add2<T>(sm, gz, dzb, (T*)d_pair_in, n);
       R.check("add d_pair_in");
     }
     R.bwd_opm((const T*)d_pair_in, R.msa_in, gm, gm);

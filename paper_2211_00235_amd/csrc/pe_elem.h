@@ -1003,6 +1003,85 @@ __global__ void tm_out_bwd_kernel(const T* G, const T* g, const T* u, T* du, T* 
   dgraw[idx] = from_f<T>(Gv * uv * gv * (1.0f - gv));
 }
 
+// The same three kernels and the two-operand add with 8 consecutive elements per thread (16-byte
+// accesses for bf16); the host takes them when the row length (M, or n) is a multiple of 8 and the
+// buffers are 16-byte aligned: an eighth of the waves for the same bytes.
+template <typename T>
+__global__ __launch_bounds__(256) void tm_gate_fwd8_kernel(const T* proj_t, const float* mask, T* a_t, T* b_t, int ct, long long M) {
+  const long long idx = ((long long)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (idx >= (long long)ct * M) return;
+  const long long m = idx % M;
+  const int c = idx / M;
+  float mk[8], ap[8], ag[8], bp[8], bg[8], a[8], b[8];
+  ld8<float>(mask + m, mk);
+  ld8<T>(proj_t + (long long)c * M + m, ap);
+  ld8<T>(proj_t + (long long)(ct + c) * M + m, ag);
+  ld8<T>(proj_t + (long long)(2 * ct + c) * M + m, bp);
+  ld8<T>(proj_t + (long long)(3 * ct + c) * M + m, bg);
+#pragma unroll
+  for (int e = 0; e < 8; e++) {
+    a[e] = mk[e] * sigmoidf_(ag[e]) * ap[e];
+    b[e] = mk[e] * sigmoidf_(bg[e]) * bp[e];
+  }
+  st8<T>(a_t + idx, a);
+  st8<T>(b_t + idx, b);
+}
+template <typename T>
+__global__ __launch_bounds__(256) void tm_gate_bwd8_kernel(const T* proj_t, const float* mask, const T* da_t, const T* db_t, T* dproj_t,
+                                                           int ct, long long M) {
+  const long long idx = ((long long)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (idx >= (long long)ct * M) return;
+  const long long m = idx % M;
+  const int c = idx / M;
+  float mk[8], ap[8], sa[8], bp[8], sb[8], da[8], db[8], o0[8], o1[8], o2[8], o3[8];
+  ld8<float>(mask + m, mk);
+  ld8<T>(proj_t + (long long)c * M + m, ap);
+  ld8<T>(proj_t + (long long)(ct + c) * M + m, sa);
+  ld8<T>(proj_t + (long long)(2 * ct + c) * M + m, bp);
+  ld8<T>(proj_t + (long long)(3 * ct + c) * M + m, sb);
+  ld8<T>(da_t + idx, da);
+  ld8<T>(db_t + idx, db);
+#pragma unroll
+  for (int e = 0; e < 8; e++) {
+    const float s_a = sigmoidf_(sa[e]), s_b = sigmoidf_(sb[e]);
+    const float d_a = da[e] * mk[e], d_b = db[e] * mk[e];
+    o0[e] = d_a * s_a;
+    o1[e] = d_a * ap[e] * s_a * (1.0f - s_a);
+    o2[e] = d_b * s_b;
+    o3[e] = d_b * bp[e] * s_b * (1.0f - s_b);
+  }
+  st8<T>(dproj_t + (long long)c * M + m, o0);
+  st8<T>(dproj_t + (long long)(ct + c) * M + m, o1);
+  st8<T>(dproj_t + (long long)(2 * ct + c) * M + m, o2);
+  st8<T>(dproj_t + (long long)(3 * ct + c) * M + m, o3);
+}
+template <typename T>
+__global__ __launch_bounds__(256) void tm_out_bwd8_kernel(const T* G, const T* g, const T* u, T* du, T* dgraw, long long n) {
+  const long long idx = ((long long)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (idx >= n) return;
+  float gv[8], Gv[8], uv[8], o0[8], o1[8];
+  ld8<T>(g + idx, gv);
+  ld8<T>(G + idx, Gv);
+  ld8<T>(u + idx, uv);
+#pragma unroll
+  for (int e = 0; e < 8; e++) {
+    o0[e] = Gv[e] * gv[e];
+    o1[e] = Gv[e] * uv[e] * gv[e] * (1.0f - gv[e]);
+  }
+  st8<T>(du + idx, o0);
+  st8<T>(dgraw + idx, o1);
+}
+template <typename T>
+__global__ __launch_bounds__(256) void add2x8_kernel(const T* a, const T* b, T* out, long long n) {
+  const long long idx = ((long long)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (idx >= n) return;
+  float x[8], y[8];
+  ld8<T>(a + idx, x);
+  ld8<T>(b + idx, y);
+#pragma unroll
+  for (int e = 0; e < 8; e++) x[e] += y[e];
+  st8<T>(out + idx, x);
+}
 // ---------------------------------------------------------------------------
 // Outer product mean normaliser: inv_norm[i][j] = 1 / (eps + sum_s mask[s][i] mask[s][j])
 // ---------------------------------------------------------------------------
