@@ -456,10 +456,10 @@ template <typename T> struct Runner {
     for (int i = 0; i < nseg; i++) ra.seg[i] = segs[i];
     ra.dst = dparams;
     long long total = (long long)rows * cols;
-    // split lanes per output: at most 16, so that a workgroup reads at least 256 contiguous bytes of every
-    // partial (with 64 lanes the 64-byte runs fetched twice the bytes they used; measured -0.6 % on the
-    // two-stream step although the kernel alone is 4 % slower with the longer per-thread loops)
-    ra.ylanes = nsplit > 16 ? 16 : (nsplit > 4 ? 4 : 1);
+    // split lanes per output: 4 up to 256 splits (a wave then reads 1 KB runs of every partial, each thread
+    // up to 64 splits with eight loads in flight), 16 beyond.  Measured on the two-stream step: 64 lanes
+    // (64-byte runs, twice the bytes fetched) -> 16 lanes -0.6 %, 16 -> 4 lanes for 17..256 splits -0.5 %.
+    ra.ylanes = nsplit > 256 ? 16 : (nsplit > 4 ? 4 : 1);
     bool v4 = total >= 4096 && cols % 4 == 0 && stride % 4 == 0 && ((uintptr_t)part) % 16 == 0;
     v4 = v4 && ((uintptr_t)dparams) % 16 == 0;
     for (int i = 0; i < nseg; i++)

@@ -869,7 +869,19 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceBatch rb) {
   if (idx < total) {
     // several independent loads in flight per thread; the sum order is a fixed function of (nsplit, Y, V)
     if (V == 4) {
-      for (int k = y; k < a.nsplit; k += 4 * Y) {
+      int k = y;
+      for (; k + 4 * Y < a.nsplit; k += 8 * Y) {   // more than four splits left for this lane: eight loads in flight
+        f32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+          int kk = k + u * Y;
+          if (kk < a.nsplit) v[u] = *reinterpret_cast<const f32x4*>(a.part + (long long)kk * a.stride + idx);
+          else v[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        }
+#pragma unroll
+        for (int e = 0; e < 4; e++) s[e] += ((v[0][e] + v[1][e]) + (v[2][e] + v[3][e])) + ((v[4][e] + v[5][e]) + (v[6][e] + v[7][e]));
+      }
+      for (; k < a.nsplit; k += 4 * Y) {
         f32x4 v[4];
 #pragma unroll
         for (int u = 0; u < 4; u++) {
