@@ -407,7 +407,7 @@ template <typename T> struct Runner {
     const double bytes = 2.0 * M * Cc * sizeof(T);
     if (lpr) {
       const int rpw = 64 / lpr;
-      int grid = (int)std::min<long long>((M + 4 * rpw - 1) / (4 * rpw), 8192);
+      int grid = (int)std::min<long long>((M + 8 * rpw - 1) / (8 * rpw), 8192);   // a workgroup takes 8 rpw rows per iteration
 #define PE_LN_FWD(L) PE_LAUNCH("ln_fwd", 0, bytes, st, (ln_fwd_fast_kernel<T, L>), dim3(grid), dim3(256), 0, x, P(g_off), P(b_off), y, stats, M, d.ln_eps)
       switch (lpr) {
         case 2: PE_LN_FWD(2); break;   case 4: PE_LN_FWD(4); break;   case 8: PE_LN_FWD(8); break;

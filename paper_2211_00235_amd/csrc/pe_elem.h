@@ -199,29 +199,40 @@ __global__ __launch_bounds__(256) void ln_fwd_fast_kernel(const T* x, const floa
   float gm[8], bt[8];
 #pragma unroll
   for (int e = 0; e < 8; e++) { gm[e] = gamma[c0 + e]; bt[e] = beta[c0 + e]; }
-  const long long stride = (long long)gridDim.x * 4 * RPW;
-  for (long long row = ((long long)blockIdx.x * 4 + wave) * RPW + rw; row < M + rw; row += stride) {
-    const bool ok = row < M;          // row - rw < M for the whole wave: shuffles stay convergent
-    float v[8];
-    if (ok) ld8<T>(x + row * C + c0, v);
-    else {
+  // two row groups per wave and iteration (rows r and r + RPW): both loads are issued before the first
+  // reduction starts, which doubles the bytes a wave has in flight
+  const long long stride = (long long)gridDim.x * 8 * RPW;
+  for (long long row = ((long long)blockIdx.x * 4 + wave) * 2 * RPW + rw; row < M + rw; row += stride) {
+    // row - rw < M for the whole wave: shuffles stay convergent
+    long long rr[2] = {row, row + RPW};
+    bool ok[2];
+    float v[2][8];
 #pragma unroll
-      for (int e = 0; e < 8; e++) v[e] = 0.0f;
+    for (int u = 0; u < 2; u++) {
+      ok[u] = rr[u] < M;
+      if (ok[u]) ld8<T>(x + rr[u] * C + c0, v[u]);
+      else {
+#pragma unroll
+        for (int e = 0; e < 8; e++) v[u][e] = 0.0f;
+      }
     }
-    float s = 0.0f;
 #pragma unroll
-    for (int e = 0; e < 8; e++) s += v[e];
-    float mu = group_sum<LPR>(s) * (1.0f / C);
-    float q = 0.0f;
+    for (int u = 0; u < 2; u++) {
+      float s = 0.0f;
 #pragma unroll
-    for (int e = 0; e < 8; e++) { float t = v[e] - mu; q += t * t; }
-    float rstd = rsqrtf(group_sum<LPR>(q) * (1.0f / C) + eps);
-    if (ok) {
-      float o[8];
+      for (int e = 0; e < 8; e++) s += v[u][e];
+      float mu = group_sum<LPR>(s) * (1.0f / C);
+      float q = 0.0f;
 #pragma unroll
-      for (int e = 0; e < 8; e++) o[e] = (v[e] - mu) * rstd * gm[e] + bt[e];
-      st8<T>(y + row * C + c0, o);
-      if (sub == 0) { stats[row * 2] = mu; stats[row * 2 + 1] = rstd; }
+      for (int e = 0; e < 8; e++) { float t = v[u][e] - mu; q += t * t; }
+      float rstd = rsqrtf(group_sum<LPR>(q) * (1.0f / C) + eps);
+      if (ok[u]) {
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 8; e++) o[e] = (v[u][e] - mu) * rstd * gm[e] + bt[e];
+        st8<T>(y + rr[u] * C + c0, o);
+        if (sub == 0) { stats[rr[u] * 2] = mu; stats[rr[u] * 2 + 1] = rstd; }
+      }
     }
   }
 }
