@@ -250,10 +250,18 @@ def main():
     run.h.set_option(3, 0)
     if args.detail:
         alone = {(e["name"], e["kernel"]): e["total_ms"] / max(e["launches"], 1) for e in ent}
+        # a launch that takes another kernel when it runs alone (parameter gradients): match by label only
+        alone_by_name = {}
+        for e in ent:
+            a = alone_by_name.setdefault(e["name"], [0.0, 0])
+            a[0] += e["total_ms"]
+            a[1] += e["launches"]
         print("-- two streams (us/launch, ratio to the same launch alone) --", file=sys.stderr)
         for e in sorted(ent2, key=lambda e: -e["total_ms"])[:40]:
             us = 1e3 * e["total_ms"] / e["launches"]
             a = 1e3 * alone.get((e["name"], e["kernel"]), 0.0)
+            if not a and e["name"] in alone_by_name:
+                a = 1e3 * alone_by_name[e["name"]][0] / max(alone_by_name[e["name"]][1], 1)
             print("%-22s %-44s n=%3d  %8.1f us/launch  x%.2f" % (e["name"], e["kernel"], e["launches"] // 5, us,
                                                                    us / a if a else 0.0), file=sys.stderr)
     two = {}
