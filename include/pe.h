@@ -28,8 +28,9 @@
  *    consumed on either stream.  stream_msa == stream_pair is allowed and
  *    serialises the branches.
  *  - Results are deterministic: no atomics, every reduction in a fixed order.
- *    A call that has the device to itself (stream_msa == stream_pair, or one
- *    branch selected with PE_OPT_BRANCHES) takes a parameter-gradient kernel
+ *    A call that has the device to itself (stream_msa == stream_pair, one
+ *    branch selected with PE_OPT_BRANCHES, or PE_VARIANT_AF2, whose data flow
+ *    is serial) takes a parameter-gradient kernel
  *    that sums the contraction index in another fixed order than the
  *    two-stream call does: outputs and input cotangents are bit-identical
  *    between the two modes, bf16-path parameter gradients agree to fp32

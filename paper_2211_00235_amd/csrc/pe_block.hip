@@ -423,9 +423,10 @@ template <typename T> struct Runner {
   // the critical path of the backward pass and its kernels have small grids, so it runs on a
   // second stream per branch, forked from / joined to the branch's stream with events.  A join
   // happens before any buffer the side stream reads is overwritten or released.
-  // true when no other branch's kernels run beside this call's: both branches on one stream, or one branch only
   static bool al16(const void* q) { return ((uintptr_t)q) % 16 == 0; }
-  bool alone() const { return sm == sp || (h && h->branches != 3); }
+  // true when no other branch's kernels run beside this call's: both branches on one stream, one branch only,
+  // or the AlphaFold2 ordering (MSA stack, outer product mean, pair stack: serial by its data flow)
+  bool alone() const { return sm == sp || (h && h->branches != 3) || d.variant == PE_VARIANT_AF2; }
   bool side_dirty[2] = {false, false};
   int side_idx(hipStream_t st) const { return (st == sp && sp != sm) ? 1 : 0; }
   bool side_on() const { return !dry && h && h->side_streams; }
