@@ -331,10 +331,16 @@ template <typename T> struct GemmCfg {
   static constexpr int BM = 128, BN = 128;
   static constexpr int BK = 8 * VEC;        // 64 (bf16) or 32 (fp32): 128-byte rows
   static constexpr int LDSS = BK + VEC;     // +16 bytes: conflict-free 16-byte fragment reads
-  // LDS element offset of (row, 16-byte chunk c of the row, element w inside the chunk).  The chunk
-  // index is XOR-swizzled with the row's 8-row group so that the transposing store of x-contiguous
-  // operands (8 rows apart per lane) does not hit one bank pair 16 times.
-  static PE_DEV int off(int row, int c, int w) { return row * LDSS + ((c ^ ((row >> 3) & 7)) * VEC) + w; }
+  // LDS element offset of (row, 16-byte chunk c of the row, element w inside the chunk).  For a tile
+  // filled by the transposing store of an x-contiguous operand (SW = true) the chunk index is
+  // XOR-swizzled with the row's 8-row group, so that this store (8 rows apart per lane) does not hit
+  // one bank pair 16 times.  A tile of a k-contiguous operand is stored row by row and keeps the plain
+  // layout, in which the 16 rows that a fragment read touches at once fall on 16 different bank
+  // groups (row stride 144 bytes); with the swizzle rows 8..15 would land on the groups of rows 0..7
+  // (counters: 45 % of the LDS cycles of the k-contiguous GEMMs were bank-conflict cycles).
+  template <bool SW> static PE_DEV int off(int row, int c, int w) {
+    return SW ? row * LDSS + ((c ^ ((row >> 3) & 7)) * VEC) + w : row * LDSS + c * VEC + w;
+  }
 };
 
 // element-wise (unaligned) variant of one 16-byte vector load: elements e = 0..VEC-1 along k (KC) or x
@@ -447,7 +453,7 @@ PE_DEV void gemm_store_tile(const typename Vec16<T>::type (&regs)[4], T* lds, in
 #pragma unroll
     for (int i = 0; i < 4; i++) {
       int row = (tid >> 3) + 32 * i;
-      *reinterpret_cast<V*>(lds + GemmCfg<T>::off(row, kv, 0)) = regs[i];
+      *reinterpret_cast<V*>(lds + GemmCfg<T>::template off<false>(row, kv, 0)) = regs[i];
     }
   } else {
     constexpr int XB = 128 / VEC;
@@ -457,7 +463,7 @@ PE_DEV void gemm_store_tile(const typename Vec16<T>::type (&regs)[4], T* lds, in
     for (int e = 0; e < VEC; e++) {
       V4 w;
       w[0] = regs[0][e]; w[1] = regs[1][e]; w[2] = regs[2][e]; w[3] = regs[3][e];
-      *reinterpret_cast<V4*>(lds + GemmCfg<T>::off(xb * VEC + e, (kb * 4) / VEC, (kb * 4) % VEC)) = w;
+      *reinterpret_cast<V4*>(lds + GemmCfg<T>::template off<true>(xb * VEC + e, (kb * 4) / VEC, (kb * 4) % VEC)) = w;
     }
   }
 }
@@ -532,7 +538,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
       if (do_cs) {
 #pragma unroll
         for (int ch = 0; ch < C::BK / C::VEC; ch++) {
-          V v = *reinterpret_cast<const V*>(lds_b + C::off(tid, ch, 0));
+          V v = *reinterpret_cast<const V*>(lds_b + C::template off<!B_KC>(tid, ch, 0));
 #pragma unroll
           for (int e = 0; e < C::VEC; e++) cs += to_f(v[e]);
         }
@@ -544,8 +550,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
 #pragma unroll
       for (int t = 0; t < 2; t++) {
         const int eo = kk * MM::KSTEP + g * MM::KP;
-        af[t] = MM::load(lds_a + C::off(wm * 64 + t * 32 + l32, eo / C::VEC, eo % C::VEC));
-        bf[t] = MM::load(lds_b + C::off(wn * 64 + t * 32 + l32, eo / C::VEC, eo % C::VEC));
+        af[t] = MM::load(lds_a + C::template off<!A_KC>(wm * 64 + t * 32 + l32, eo / C::VEC, eo % C::VEC));
+        bf[t] = MM::load(lds_b + C::template off<!B_KC>(wn * 64 + t * 32 + l32, eo / C::VEC, eo % C::VEC));
       }
 #pragma unroll
       for (int i = 0; i < 2; i++)
@@ -725,7 +731,7 @@ __global__ __launch_bounds__(256) void gemm64_kernel(Operand A, Operand B, GemmS
   for (int k0 = 0; k0 < sh.K; k0 += C::BK) {
     __syncthreads();  // previous tile fully consumed
 #pragma unroll
-    for (int i = 0; i < 2; i++) *reinterpret_cast<V*>(lds_a + C::off((tid >> 3) + 32 * i, kv, 0)) = ra[i];
+    for (int i = 0; i < 2; i++) *reinterpret_cast<V*>(lds_a + C::template off<false>((tid >> 3) + 32 * i, kv, 0)) = ra[i];
     gemm_store_tile<T, true>(rb, lds_b, tid);
     __syncthreads();
     if (k0 + C::BK < sh.K) {
@@ -735,10 +741,10 @@ __global__ __launch_bounds__(256) void gemm64_kernel(Operand A, Operand B, GemmS
 #pragma unroll
     for (int kk = 0; kk < C::BK / MM::KSTEP; kk++) {
       const int eo = kk * MM::KSTEP + g * MM::KP;
-      typename MM::frag bf = MM::load(lds_b + C::off(wave * 32 + l32, eo / C::VEC, eo % C::VEC));
+      typename MM::frag bf = MM::load(lds_b + C::template off<false>(wave * 32 + l32, eo / C::VEC, eo % C::VEC));
 #pragma unroll
       for (int t = 0; t < 2; t++)
-        MM::mma(acc[t], MM::load(lds_a + C::off(t * 32 + l32, eo / C::VEC, eo % C::VEC)), bf);
+        MM::mma(acc[t], MM::load(lds_a + C::template off<false>(t * 32 + l32, eo / C::VEC, eo % C::VEC)), bf);
     }
   }
 
