@@ -988,8 +988,12 @@ template <typename T> struct Runner {
       else PE_LAUNCH(gm.l_dkv, 8.0 * gm.B * H * gm.L * gm.L * dh, 6.0 * M * HD * sizeof(T), st, (attn_bwd_dkv_kernel<T, false>), grid, dim3(256), 0, a);
       if (c.bias) {
         long long hll = (long long)H * gm.L * gm.L;
-        PE_LAUNCH("attn_dbias_reduce", 0, 1.0 * Bds * hll * sizeof(T) + 4.0 * hll, st, attn_dbias_reduce_kernel<T>, dim3((unsigned)((hll + 255) / 256)), dim3(256), 0, dS, dbias,
-                           (int)Bds, hll);
+        if (hll % 8 == 0 && al16(dS) && al16(dbias))
+          PE_LAUNCH("attn_dbias_reduce", 0, 1.0 * Bds * hll * sizeof(T) + 4.0 * hll, st, attn_dbias_reduce8_kernel<T>, dim3((unsigned)((hll / 8 + 63) / 64)), dim3(256), 0,
+                    dS, dbias, (int)Bds, hll);
+        else
+          PE_LAUNCH("attn_dbias_reduce", 0, 1.0 * Bds * hll * sizeof(T) + 4.0 * hll, st, attn_dbias_reduce_kernel<T>, dim3((unsigned)((hll + 255) / 256)), dim3(256), 0, dS, dbias,
+                    (int)Bds, hll);
       }
     }
     { ReduceSeg sg[4] = {{0, HD, p.w_q, HD}, {HD, HD, p.w_k, HD}, {2 * HD, HD, p.w_v, HD}, {3 * HD, HD, p.w_g, HD}};
