@@ -917,10 +917,12 @@ __global__ __launch_bounds__(256 * KG) void gemm_dwx_kernel(Operand A, Operand B
       union { uint32_t u[4]; bf16x8 v; } a0, a1, b0, b1;
 #pragma unroll
       for (int j = 0; j < 4; j++) {
-        a0.u[j] = (wa[2 * j] & 0xffffu) | (wa[2 * j + 1] << 16);
-        a1.u[j] = (wa[2 * j] >> 16) | (wa[2 * j + 1] & 0xffff0000u);
-        b0.u[j] = (wb[2 * j] & 0xffffu) | (wb[2 * j + 1] << 16);
-        b1.u[j] = (wb[2 * j] >> 16) | (wb[2 * j + 1] & 0xffff0000u);
+        // byte permute of {first operand, second operand}: selectors 0..3 take bytes of the second, 4..7 of the
+        // first: low halves (rows 2l) -> 0x05040100, high halves (rows 2l + 1) -> 0x07060302
+        a0.u[j] = __builtin_amdgcn_perm(wa[2 * j + 1], wa[2 * j], 0x05040100u);
+        a1.u[j] = __builtin_amdgcn_perm(wa[2 * j + 1], wa[2 * j], 0x07060302u);
+        b0.u[j] = __builtin_amdgcn_perm(wb[2 * j + 1], wb[2 * j], 0x05040100u);
+        b1.u[j] = __builtin_amdgcn_perm(wb[2 * j + 1], wb[2 * j], 0x07060302u);
       }
       acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0.v, b0.v, acc[0][0], 0, 0, 0);
       acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0.v, b1.v, acc[0][1], 0, 0, 0);
