@@ -1055,6 +1055,23 @@ static inline void launch_gemm_al(hipStream_t st, dim3 grid, const Operand& A, b
                                   const GemmShape& sh, const Epi& epi) {
   dim3 block(256);
   if (AL && VE && a_kc && b_kc && launch_gemm_spec<T, Epi>(st, grid, A, B, sh, epi)) return;
+  if constexpr (AL && VE && std::is_same<Epi, EpiGeneric<T>>::value) {
+    // the other operand layouts occur with two feature sets only (the triangle contractions: none; the
+    // outer product: the 2-D scale): lean kernels for those
+    const int f = epi.features();
+#define PE_GEMM_SPEC_L(S)                                                                                              \
+    if ((f & ~(S)) == 0) {                                                                                             \
+      if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_kernel<T, true, false, true, true, Epi, (S)>), grid, block, 0, st, A, B, sh, epi);       \
+      else if (!a_kc && b_kc) hipLaunchKernelGGL((gemm_kernel<T, false, true, true, true, Epi, (S)>), grid, block, 0, st, A, B, sh, epi);  \
+      else hipLaunchKernelGGL((gemm_kernel<T, false, false, true, true, Epi, (S)>), grid, block, 0, st, A, B, sh, epi);                    \
+      return;                                                                                                          \
+    }
+    if (!(a_kc && b_kc)) {
+      PE_GEMM_SPEC_L(0)
+      PE_GEMM_SPEC_L(EF_SCALE2D)
+    }
+#undef PE_GEMM_SPEC_L
+  }
   if (a_kc && b_kc) hipLaunchKernelGGL((gemm_kernel<T, true, true, AL, VE, Epi>), grid, block, 0, st, A, B, sh, epi);
   else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_kernel<T, true, false, AL, VE, Epi>), grid, block, 0, st, A, B, sh, epi);
   else if (!a_kc && b_kc) hipLaunchKernelGGL((gemm_kernel<T, false, true, AL, VE, Epi>), grid, block, 0, st, A, B, sh, epi);
