@@ -24,7 +24,9 @@ template <typename T> struct Vec16;
 template <> struct Vec16<bf16> { static constexpr int N = 8; typedef bf16x8 type; };
 template <> struct Vec16<float> { static constexpr int N = 4; typedef f32x4 type; };
 
-PE_DEV float sigmoidf_(float x) { return 1.0f / (1.0f + __expf(-x)); }
+// 1 / (1 + 2^(-x log2 e)) with the hardware exponential and reciprocal (about 1 ulp each): four instructions;
+// the correctly rounded division alone is a ten-instruction sequence.  2^(+large) = inf gives exactly 0.
+PE_DEV float sigmoidf_(float x) { return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(x * -1.4426950408889634f)); }
 
 // ---------------------------------------------------------------------------
 // MFMA policy.  One 32x32 output tile per wave-instruction.
