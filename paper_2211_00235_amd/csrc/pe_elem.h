@@ -877,6 +877,25 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceBatch rb) {
   const int x = threadIdx.x % X, y = threadIdx.x / X;
   const long long idx = ((long long)blk * X + x) * V;
   float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  // the lane that will write the result fetches the destination's current value first, so that this load is
+  // in flight together with the partials instead of after the workgroup's barrier
+  float* dst = nullptr;
+  f32x4 cur = {0.0f, 0.0f, 0.0f, 0.0f};
+  if (y == 0 && idx < total) {
+    // a 4-group never straddles a row or a segment (the host checks the multiples of 4)
+    const int m = idx / a.cols, n = idx % a.cols;
+    for (int q = 0; q < a.nseg; q++) {
+      const ReduceSeg& g = a.seg[q];
+      if (n >= g.n_begin && n < g.n_begin + g.n_count) {
+        dst = a.dst + g.dst_off + (long long)m * g.dst_ld + (n - g.n_begin);
+        break;
+      }
+    }
+    if (dst) {
+      if (V == 4) cur = *reinterpret_cast<const f32x4*>(dst);   // host checked: 16-byte aligned destination groups
+      else cur[0] = dst[0];
+    }
+  }
   if (idx < total) {
     // several independent loads in flight per thread; the sum order is a fixed function of (nsplit, Y, V)
     if (V == 4) {
@@ -924,23 +943,13 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceBatch rb) {
 #pragma unroll
       for (int e = 0; e < 4; e++) s[e] += red[k * X + x][e];
   }
-  if (idx >= total) return;
-  // a 4-group never straddles a row or a segment (the host checks the multiples of 4)
-  const int m = idx / a.cols, n = idx % a.cols;
-  for (int q = 0; q < a.nseg; q++) {
-    const ReduceSeg& g = a.seg[q];
-    if (n >= g.n_begin && n < g.n_begin + g.n_count) {
-      float* dst = a.dst + g.dst_off + (long long)m * g.dst_ld + (n - g.n_begin);
-      if (V == 4) {   // host checked: 16-byte aligned destination groups
-        f32x4 t = *reinterpret_cast<f32x4*>(dst);
+  if (idx >= total || !dst) return;
+  if (V == 4) {
 #pragma unroll
-        for (int e = 0; e < 4; e++) t[e] += s[e];
-        *reinterpret_cast<f32x4*>(dst) = t;
-      } else {
-        dst[0] += s[0];
-      }
-      break;
-    }
+    for (int e = 0; e < 4; e++) cur[e] += s[e];
+    *reinterpret_cast<f32x4*>(dst) = cur;
+  } else {
+    dst[0] = cur[0] + s[0];
   }
 }
 
