@@ -426,6 +426,8 @@ template <typename T> struct Runner {
   static bool al16(const void* q) { return ((uintptr_t)q) % 16 == 0; }
   // true when no other branch's kernels run beside this call's: both branches on one stream, one branch only,
   // or the AlphaFold2 ordering (MSA stack, outer product mean, pair stack: serial by its data flow)
+  // wave groups of the parameter-gradient GEMM: two when the call has the chip to itself, one beside another branch
+  int dw_groups() const { return alone() ? 2 : 1; }
   bool alone() const { return sm == sp || (h && h->branches != 3) || d.variant == PE_VARIANT_AF2; }
   bool side_dirty[2] = {false, false};
   int side_idx(hipStream_t st) const { return (st == sp && sp != sm) ? 1 : 0; }
@@ -534,9 +536,9 @@ template <typename T> struct Runner {
       EpiPartial ep{part, (long long)M * N, N};
       prof_begin(st);
       bool al = false, dwx = false;
-      int rc = launch_gemm<T, EpiPartial>(st, A, akc, B, bkc, sh, ep, &al, &dwx, alone());
+      int rc = launch_gemm<T, EpiPartial>(st, A, akc, B, bkc, sh, ep, &al, &dwx, dw_groups());
       char kn[64];
-      if (dwx) snprintf(kn, sizeof(kn), "gemm_dwx_kernel<%d>", DWX_GROUPS);
+      if (dwx) snprintf(kn, sizeof(kn), "gemm_dwx_kernel<%d>", dw_groups());
       else snprintf(kn, sizeof(kn), "gemm_kernel<%s,%s,%s,EpiPartial>", akc ? "kc" : "xc", bkc ? "kc" : "xc", al ? "vec" : "elem");
       prof_end(st, what, kn, 2.0 * M * N * K, ((double)M * K + (double)N * K) * sizeof(T));
       if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = std::string("gemm operand alignment: ") + what; return; }
@@ -577,9 +579,9 @@ template <typename T> struct Runner {
       EpiPartial ep{part, (long long)rows * cols, cols, cs_part};
       prof_begin(st);
       bool al = false, dwx = false;
-      int rc = launch_gemm<T, EpiPartial>(st, X, xkc, Y, ykc, sh, ep, &al, &dwx, alone());
+      int rc = launch_gemm<T, EpiPartial>(st, X, xkc, Y, ykc, sh, ep, &al, &dwx, dw_groups());
       char kn[64];
-      if (dwx) snprintf(kn, sizeof(kn), "gemm_dwx_kernel<%d>", DWX_GROUPS);
+      if (dwx) snprintf(kn, sizeof(kn), "gemm_dwx_kernel<%d>", dw_groups());
       else snprintf(kn, sizeof(kn), "gemm_kernel<%s,%s,%s,EpiPartial>", xkc ? "kc" : "xc", ykc ? "kc" : "xc", al ? "vec" : "elem");
       prof_end(st, what, kn, 2.0 * rows * cols * K, ((double)rows * K + (double)cols * K) * sizeof(T));
       if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = std::string("gemm_dw operand alignment: ") + what; }

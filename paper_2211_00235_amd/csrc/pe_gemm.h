@@ -985,13 +985,15 @@ __global__ __launch_bounds__(256 * KG) void gemm_dwx_kernel(Operand A, Operand B
 // Two wave groups: measured 15 - 27 % faster than one on the block's parameter-gradient shapes when the
 // kernel has the chip to itself; three are no faster (and need more than 64 KB of LDS), four spill at
 // 128 registers.  Next to another branch's kernels on a second stream the extra resident waves cost
-// more than they win (the step is 1.3 % slower), so the caller asks for this kernel only when nothing
-// else runs beside it.
+// more than they win (the step is 1.3 % slower), so the caller asks for two groups only when nothing
+// else runs beside the call and for one group otherwise (0.4 % faster there than the register-transposing
+// kernel: no bank conflicts, fewer instructions).
 constexpr int DWX_GROUPS = 2;
-static inline int launch_dwx(hipStream_t st, dim3 grid, const Operand& A, const Operand& B, const GemmShape& sh, const EpiPartial& epi) {
+static inline int launch_dwx(hipStream_t st, dim3 grid, int groups, const Operand& A, const Operand& B, const GemmShape& sh, const EpiPartial& epi) {
   constexpr unsigned bytes = DWX_GROUPS * 32768u;
   static_assert(bytes <= 65536u, "more dynamic LDS than the default limit: raise hipFuncAttributeMaxDynamicSharedMemorySize first");
-  hipLaunchKernelGGL((gemm_dwx_kernel<DWX_GROUPS>), grid, dim3(256 * DWX_GROUPS), bytes, st, A, B, sh, epi);
+  if (groups == 1) hipLaunchKernelGGL((gemm_dwx_kernel<1>), grid, dim3(256), 32768u, st, A, B, sh, epi);
+  else hipLaunchKernelGGL((gemm_dwx_kernel<DWX_GROUPS>), grid, dim3(256 * DWX_GROUPS), bytes, st, A, B, sh, epi);
   return hipGetLastError() == hipSuccess ? 0 : -2;
 }
 
@@ -1083,7 +1085,7 @@ static inline void launch_gemm_al(hipStream_t st, dim3 grid, const Operand& A, b
 template <typename T, class Epi>
 static inline int launch_gemm(hipStream_t st, const Operand& A, bool a_kc, const Operand& B, bool b_kc,
                               const GemmShape& shape, const Epi& epi, bool* used_vec = nullptr, bool* used_narrow = nullptr,
-                              bool wave_groups = false) {
+                              int wave_groups = 0) {
   GemmShape sh = shape;
   if (sh.M <= 0 || sh.N <= 0 || sh.batch <= 0) return 0;
   if (a_kc ? A.k_stride != 1 : A.x_stride != 1) return -1;
@@ -1106,11 +1108,11 @@ static inline int launch_gemm(hipStream_t st, const Operand& A, bool a_kc, const
     return hipGetLastError() == hipSuccess ? 0 : -2;
   }
   if constexpr (std::is_same<Epi, EpiPartial>::value && std::is_same<T, bf16>::value) {
-    // parameter gradients from two x-contiguous operands, on request: the kernel with two wave groups
-    // (*used_narrow reports that it was taken)
+    // parameter gradients from two x-contiguous operands: the kernel that keeps the tiles in memory order,
+    // with wave_groups (1 or 2) wave groups (*used_narrow reports that it was taken)
     if (wave_groups && ve && !a_kc && !b_kc) {
       if (used_narrow) *used_narrow = true;
-      return launch_dwx(st, grid, A, B, sh, epi);
+      return launch_dwx(st, grid, wave_groups, A, B, sh, epi);
     }
   }
   if (ve) launch_gemm_al<T, true, true, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);
