@@ -108,6 +108,26 @@ def test_ragged_shapes_one_stream_bf16():
     _assert(errs, worst, SMALL_BF16_TOL)
 
 
+@pytest.mark.parametrize("two_streams", [True, False])
+def test_random_small_shapes_fp32(two_streams):
+    """Six seeded random draws of every size parameter (sequences 3..69, residues 8..200, channel widths, head
+    counts and dimensions, hidden sizes, block ordering), fp32 path at 1e-4, with the branches on two streams and
+    on one (the call that runs alone takes other parameter-gradient kernels)."""
+    rng = np.random.default_rng(123)
+    for i in range(6):
+        dims, _, _ = dims_for("tiny")
+        dims.update(dtype=0, s=int(rng.integers(3, 70)), r=int(rng.choice([8, 24, 40, 72, 136, 200])),
+                    c_m=int(rng.choice([32, 64, 128])), c_z=int(rng.choice([16, 32, 64, 128])),
+                    h_msa=int(rng.choice([1, 2, 4])), d_msa=int(rng.choice([8, 16, 32])),
+                    h_pair=int(rng.choice([1, 2, 4])), d_pair=int(rng.choice([8, 16, 32])),
+                    c_tri=int(rng.choice([8, 16, 24, 64])), c_opm=int(rng.choice([8, 16, 32])),
+                    n_trans=int(rng.choice([2, 4])), variant=int(rng.choice([0, 0, 1, 2])))
+        table, n = param_table(dims)
+        inp = make_inputs(dims, table, n, ("random_residues", 0.1), 100 + i)
+        errs, worst, tol, _ = check_case(dims, table, inp, two_streams=two_streams)
+        assert errs[worst] <= tol, "draw %d %s: worst %s = %.3e" % (i, dims, worst, errs[worst])
+
+
 def test_af2_initial_fp32():
     dims, table, inp = _case("af2_initial", dtype=0)
     _assert(*check_case(dims, table, inp)[:3])
