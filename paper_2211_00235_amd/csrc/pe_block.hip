@@ -269,7 +269,8 @@ template <typename T> struct Runner {
   PrepList prep_msa, prep_pair;
   T* prep_tbase_m = nullptr; float* prep_fbase_m = nullptr;
   T* prep_tbase_p = nullptr; float* prep_fbase_p = nullptr;
-  Arena am, ap;
+  Arena am, ap;   // work arenas of the two branches (stack discipline, one frame per sub-operation)
+  Arena pm, pp;   // partial sums of the parameter gradients: kept until the end of the backward pass
   long long Mm, Mz;
   int HDm, HDz;
 
@@ -447,11 +448,20 @@ template <typename T> struct Runner {
     side_dirty[side_idx(st)] = false;
   }
 
-  // Reductions of fp32 partials into d_params are queued and launched several per kernel
-  // (flush_reduces).  Partial buffers stay allocated until the enclosing sub-operation
-  // releases its arena frame, which every sub-operation does after flushing.
-  std::vector<ReduceArgs> pending;
-  void reduce_to(hipStream_t st, const float* part, int nsplit, long long stride, int rows, int cols, int nseg,
+  // Reductions of fp32 partials into d_params are queued per branch and launched at the end of the
+  // backward pass, REDUCE_BATCH per kernel (flush_all): one launch then reads 100 MB and more, while the
+  // two or three reductions of a single sub-operation are a launch too small to get near the memory
+  // rate.  The partial buffers therefore come from arenas of their own (pm, pp), which are only reset by
+  // flush_all.  Two reductions of one sub-operation that add to the same parameters (the z LayerNorm of a
+  // biased attention gets one from the q/k/v path and one from the bias path) go into different phases,
+  // which are launched one after the other.
+  std::vector<ReduceArgs> pend[2][2];
+  int phase[2] = {0, 0};
+  int bidx(const Arena& ar) const { return &ar == &ap ? 1 : 0; }
+  Arena& part_arena(const Arena& ar) { return &ar == &ap ? pp : pm; }
+  void next_phase(const Arena& ar) { phase[bidx(ar)] = 1; }
+  void end_subop(const Arena& ar) { phase[bidx(ar)] = 0; }
+  void reduce_to(const Arena& ar, const float* part, int nsplit, long long stride, int rows, int cols, int nseg,
                  const ReduceSeg* segs) {
     if (dry || err) return;
     ReduceArgs ra;
@@ -468,32 +478,39 @@ template <typename T> struct Runner {
     for (int i = 0; i < nseg; i++)
       v4 = v4 && segs[i].n_begin % 4 == 0 && segs[i].n_count % 4 == 0 && segs[i].dst_off % 4 == 0 && segs[i].dst_ld % 4 == 0;
     ra.vec = v4 ? 4 : 1;
-    pending.push_back(ra);
-    (void)st;
+    pend[bidx(ar)][phase[bidx(ar)]].push_back(ra);
   }
-  void flush_reduces(hipStream_t main_st) {
-    if (dry || err) { pending.clear(); return; }
+  // launches every queued reduction of the branch that works in `ar` on that branch's stream and
+  // releases the branch's partial buffers
+  void flush_all(const Arena& ar, hipStream_t main_st) {
+    const int bi = bidx(ar);
+    part_arena(ar).release(0);
+    if (dry || err) { pend[bi][0].clear(); pend[bi][1].clear(); phase[bi] = 0; return; }
     fork_side(main_st);
     hipStream_t st = side_of(main_st);
-    for (size_t i = 0; i < pending.size(); i += REDUCE_BATCH) {
-      ReduceBatch rb;
-      rb.n = (int)std::min((size_t)REDUCE_BATCH, pending.size() - i);
-      long long nblocks = 0;
-      double bytes = 0;
-      for (int k = 0; k < REDUCE_BATCH; k++) {
-        rb.a[k] = pending[i + (k < rb.n ? k : 0)];
-        rb.first[k] = (int)nblocks;
-        if (k < rb.n) {
-          long long total = (long long)rb.a[k].rows * rb.a[k].cols;
-          int X = 256 / rb.a[k].ylanes * rb.a[k].vec;
-          nblocks += (total + X - 1) / X;
-          bytes += 4.0 * total * (rb.a[k].nsplit + 2);
+    for (int ph = 0; ph < 2; ph++) {
+      std::vector<ReduceArgs>& pending = pend[bi][ph];
+      for (size_t i = 0; i < pending.size(); i += REDUCE_BATCH) {
+        ReduceBatch rb;
+        rb.n = (int)std::min((size_t)REDUCE_BATCH, pending.size() - i);
+        long long nblocks = 0;
+        double bytes = 0;
+        for (int k = 0; k < REDUCE_BATCH; k++) {
+          rb.a[k] = pending[i + (k < rb.n ? k : 0)];
+          rb.first[k] = (int)nblocks;
+          if (k < rb.n) {
+            long long total = (long long)rb.a[k].rows * rb.a[k].cols;
+            int X = 256 / rb.a[k].ylanes * rb.a[k].vec;
+            nblocks += (total + X - 1) / X;
+            bytes += 4.0 * total * (rb.a[k].nsplit + 2);
+          }
         }
+        rb.first[REDUCE_BATCH] = (int)nblocks;
+        PE_LAUNCH("reduce_partials", 0, bytes, st, reduce_partials_kernel, dim3((unsigned)nblocks), dim3(256), 0, rb);
       }
-      rb.first[REDUCE_BATCH] = (int)nblocks;
-      PE_LAUNCH("reduce_partials", 0, bytes, st, reduce_partials_kernel, dim3((unsigned)nblocks), dim3(256), 0, rb);
+      pending.clear();
     }
-    pending.clear();
+    phase[bi] = 0;
     join_side(main_st);
   }
   void k_ln_bwd(hipStream_t st, Arena& ar, const T* dy, const T* x, const float* stats, long long g_off, long long b_off,
@@ -501,7 +518,7 @@ template <typename T> struct Runner {
     const int lpr = ln_lpr(Cc);
     const int rpw = lpr ? 64 / lpr : 1;
     int grid = (int)std::min<long long>((M + 4 * rpw - 1) / (4 * rpw), LN_MAX_WG);
-    float* part = (float*)ar.alloc((size_t)grid * 2 * Cc * sizeof(float));
+    float* part = (float*)part_arena(ar).alloc((size_t)grid * 2 * Cc * sizeof(float));
     if (!dry && !err) {
       join_side(st);   // gout may alias a buffer the side stream is still reading
       const double bytes = (gin ? 4.0 : 3.0) * M * Cc * sizeof(T);
@@ -516,7 +533,7 @@ template <typename T> struct Runner {
         PE_LAUNCH("ln_bwd", 0, bytes, st, ln_bwd_kernel<T>, dim3(grid), dim3(256), 0, dy, x, stats, P(g_off), gin, gout, part, M, Cc);
       }
       ReduceSeg sg[2] = {{0, Cc, g_off, 0}, {Cc, Cc, b_off, 0}};
-      reduce_to(st, part, grid, 2LL * Cc, 1, 2 * Cc, 2, sg);
+      reduce_to(ar, part, grid, 2LL * Cc, 1, 2 * Cc, 2, sg);
     }
   }
   void gemm(hipStream_t st, const Operand& A, bool akc, const Operand& B, bool bkc, int M, int N, int K, int batch,
@@ -570,8 +587,8 @@ template <typename T> struct Runner {
     long long kc = (K + want - 1) / want;
     kc = (kc + BK - 1) / BK * BK;
     int nsplit = (int)((K + kc - 1) / kc);
-    float* part = (float*)ar.alloc((size_t)nsplit * rows * cols * sizeof(float));
-    float* cs_part = ncs ? (float*)ar.alloc((size_t)nsplit * cols * sizeof(float)) : nullptr;
+    float* part = (float*)part_arena(ar).alloc((size_t)nsplit * rows * cols * sizeof(float));
+    float* cs_part = ncs ? (float*)part_arena(ar).alloc((size_t)nsplit * cols * sizeof(float)) : nullptr;
     if (!dry && !err) {
       fork_side(st);
       st = side_of(st);
@@ -586,8 +603,8 @@ template <typename T> struct Runner {
       prof_end(st, what, kn, 2.0 * rows * cols * K, ((double)rows * K + (double)cols * K) * sizeof(T));
       if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = std::string("gemm_dw operand alignment: ") + what; }
       else check(what);
-      reduce_to(st, part, nsplit, (long long)rows * cols, rows, cols, nseg, segs);
-      if (ncs) reduce_to(st, cs_part, nsplit, cols, 1, cols, ncs, cs);
+      reduce_to(ar, part, nsplit, (long long)rows * cols, rows, cols, nseg, segs);
+      if (ncs) reduce_to(ar, cs_part, nsplit, cols, 1, cols, ncs, cs);
     }
   }
 
@@ -739,7 +756,7 @@ template <typename T> struct Runner {
     { EpiGeneric<T> e = epi_plain<T>(dxh, Cc);
       gemm(st, op_plain(dproj, Wg), true, op_plain(W.gcol.wn_proj, Wg), true, (int)Mm, Cc, Wg, 1, e, "gcol dxhat"); }
     k_ln_bwd(st, ar, dxh, x, c.stats, p.ln_g, p.ln_b, g, g, Mm, Cc);
-    flush_reduces(st);
+    end_subop(ar);
     ar.release(mk);
   }
 
@@ -922,7 +939,7 @@ template <typename T> struct Runner {
     { EpiGeneric<T> e = epi_plain<T>(dxh, Cc);
       gemm(st, op_plain(dh, nC), true, op_plain(w.wn_1, nC), true, (int)M, Cc, nC, 1, e, "trans dxhat"); }
     k_ln_bwd(st, ar, dxh, x, c.stats, p.ln_g, p.ln_b, gin, g, M, Cc);
-    flush_reduces(st);
+    end_subop(ar);
     ar.release(mk);
   }
 
@@ -1004,14 +1021,14 @@ template <typename T> struct Runner {
     { EpiGeneric<T> e = epi_plain<T>(dxh, Cc);
       gemm(st, op_heads_rows(dqkvg, gm, dh, M * dh), true, op_plain(w.wn_qkvg, 4 * HD), true, (int)M, Cc, 4 * HD, 1, e, "attn dxhat"); }
     k_ln_bwd(st, ar, dxh, x, c.stats, p.ln_g, p.ln_b, g, g, M, Cc);
-    flush_reduces(st);   // the bias path below adds to the same LayerNorm parameters: separate launch
+    next_phase(ar);   // the bias path below adds to the same LayerNorm parameters: a later launch
     if (c.bias) {
       const int cz = d.c_z;
       const int lpr = (ln_lpr(cz) && ln_lpr(cz) <= 32) ? ln_lpr(cz) : 0;
       const int rpw = lpr ? 64 / lpr : 1;
       int grid = (int)std::min<long long>((Mz + 4 * rpw - 1) / (4 * rpw), 1024);
       int plen = 2 * cz + cz * H;
-      float* part = (float*)ar.alloc((size_t)grid * plen * sizeof(float));
+      float* part = (float*)part_arena(ar).alloc((size_t)grid * plen * sizeof(float));
       // dbias is [h][key][query]; bring it to pair-row order when the bias rows are the queries
       const bool flip = lpr && !gm.bias_transposed;
       float* dbias_rows = flip ? (float*)ar.alloc((size_t)H * Mz * sizeof(float)) : dbias;
@@ -1032,9 +1049,9 @@ template <typename T> struct Runner {
                     P(bias_ln_g), P(bias_ln_b), P(p.w_bias), bias_gin, bias_gout, part, d.r, cz, H, gm.bias_transposed ^ 1);
         }
         ReduceSeg sg[3] = {{0, cz, bias_ln_g, 0}, {cz, cz, bias_ln_b, 0}, {2 * cz, cz * H, p.w_bias, 0}};
-        reduce_to(st, part, grid, plen, 1, plen, 3, sg);
+        reduce_to(ar, part, grid, plen, 1, plen, 3, sg);
       }
-      flush_reduces(st);
+      end_subop(ar);
     }
     ar.release(mk);
   }
@@ -1064,7 +1081,7 @@ template <typename T> struct Runner {
       gemm(st, op_plain(du, cz), true, op_plain(w.wn_o, cz), true, (int)Mz, ct, cz, 1, e, "trimul dxhat_o"); }
     {  // LayerNorm (channel-major input) backward
       int grid = (int)((Mz + 63) / 64);
-      float* part = (float*)ar.alloc((size_t)grid * 2 * ct * sizeof(float));
+      float* part = (float*)part_arena(ar).alloc((size_t)grid * 2 * ct * sizeof(float));
       if (!dry && !err) {
         size_t lds = (size_t)64 * (ct + 1) * sizeof(float);
 #define PE_LNC_BWD(N) PE_LAUNCH("ln_cmajor_bwd", 0, 3.0 * Mz * ct * sizeof(T), st, (ln_cmajor_bwd_fast_kernel<T, N>), dim3(grid), dim3(256), lds, dxh_o, c.x_t, c.stats_out, P(p.ln_out_g), dx_t, part, Mz, ct)
@@ -1077,7 +1094,7 @@ template <typename T> struct Runner {
           PE_LAUNCH("ln_cmajor_bwd", 0, 3.0 * Mz * ct * sizeof(T), st, ln_cmajor_bwd_kernel<T>, dim3(grid), dim3(256), lds, dxh_o, c.x_t, c.stats_out,
                     P(p.ln_out_g), dx_t, part, Mz, ct);
         ReduceSeg sg[2] = {{0, ct, p.ln_out_g, 0}, {ct, ct, p.ln_out_b, 0}};
-        reduce_to(st, part, grid, 2LL * ct, 1, 2 * ct, 2, sg);
+        reduce_to(ar, part, grid, 2LL * ct, 1, 2 * ct, 2, sg);
       }
     }
     {  // contraction backward, per channel
@@ -1113,7 +1130,7 @@ template <typename T> struct Runner {
       e.accumulate = 1;
       gemm(st, op_plain(dgraw, cz), true, op_plain(w.wn_g, cz), true, (int)Mz, cz, cz, 1, e, "trimul dzhat g"); }
     k_ln_bwd(st, ar, dzh, z, c.stats, p.ln_in_g, p.ln_in_b, g, g, Mz, cz);
-    flush_reduces(st);
+    end_subop(ar);
     ar.release(mk);
   }
 
@@ -1174,7 +1191,7 @@ template <typename T> struct Runner {
         gemm(sm, A, true, op_plain(W.opm.wn_ab, 2 * co), true, (int)Mm, cm, 2 * co, 1, e, "opm dmhat");
       }
       k_ln_bwd(sm, am, dmh, x, C.opm.stats, PL.opm.ln_g, PL.opm.ln_b, gin, gout, Mm, cm);
-      flush_reduces(sm);
+      end_subop(am);
       am.release(mk);
     }
   }
@@ -1236,9 +1253,10 @@ template <typename T> struct Runner {
 // forward's ctx does not convert the parameters again
 // ---------------------------------------------------------------------------
 struct Plan {
-  size_t prep_bytes, arena_m, arena_p, ctx_bytes;
+  size_t prep_bytes, arena_m, arena_p, part_m, part_p, ctx_bytes;
   size_t ctx_total() const { return ctx_bytes + prep_bytes; }
-  size_t total(bool with_ctx) const { return arena_m + arena_p + (with_ctx ? ctx_total() : 0) + 1024; }
+  size_t arenas() const { return arena_m + arena_p + part_m + part_p; }
+  size_t total(bool with_ctx) const { return arenas() + (with_ctx ? ctx_total() : 0) + 1024; }
 };
 
 template <typename T> static Plan make_plan(const pe_dims& d) {
@@ -1260,6 +1278,8 @@ template <typename T> static Plan make_plan(const pe_dims& d) {
   R.bwd_pair(nullptr, gz);
   pl.arena_m = (R.am.high + 255) & ~(size_t)255;
   pl.arena_p = (R.ap.high + 255) & ~(size_t)255;
+  pl.part_m = (R.pm.high + 255) & ~(size_t)255;
+  pl.part_p = (R.pp.high + 255) & ~(size_t)255;
   return pl;
 }
 static Plan plan_for(const pe_dims& d) { return d.dtype == PE_BF16 ? make_plan<bf16>(d) : make_plan<float>(d); }
@@ -1272,7 +1292,9 @@ template <typename T> static void setup_runner(Runner<T>& R, pe_handle* h, const
   R.sp = sp;
   R.am.base = ws;
   R.ap.base = ws + pl.arena_m;
-  char* cbase = ctx ? ctx : ws + pl.arena_m + pl.arena_p;
+  R.pm.base = ws + pl.arena_m + pl.arena_p;
+  R.pp.base = R.pm.base + pl.part_m;
+  char* cbase = ctx ? ctx : ws + pl.arenas();
   carve_ctx<T>(cbase, d, R.C, nullptr);
   R.carve_prep(cbase + pl.ctx_bytes);
 }
@@ -1397,7 +1419,12 @@ static int block_bwd_impl(pe_handle* h, const pe_dims& d, const void* msa_in, co
         if (!hip_ok(h, hipMemcpyAsync(d_pair_in, dzb, (size_t)n * sizeof(T), hipMemcpyDeviceToDevice, sp), "copy")) return PE_ERR_HIP;
       }
     }
+    // the queued parameter-gradient reductions of both branches, each on its own stream; then both streams wait
+    // for each other
+    R.flush_all(R.ap, sp);
+    R.flush_all(R.am, sm);
     if (!ev_link(h, 2, sp, sm)) return PE_ERR_HIP;
+    if (!ev_link(h, 3, sm, sp)) return PE_ERR_HIP;
     return R.err;
   }
   if (d.variant == PE_VARIANT_AF2) {
@@ -1423,6 +1450,9 @@ static int block_bwd_impl(pe_handle* h, const pe_dims& d, const void* msa_in, co
     }
     R.bwd_opm((const T*)d_pair_in, R.msa_in, gm, gm);
   }
+  R.flush_all(R.ap, sp);
+  R.flush_all(R.am, sm);
+  if (!ev_link(h, 3, sp, sm)) return PE_ERR_HIP;
   if (!ev_link(h, 2, sm, sp)) return PE_ERR_HIP;
   return R.err;
 }

@@ -860,7 +860,7 @@ struct ReduceArgs {
 // 256 threads = X outputs x Y split lanes (Y = a.ylanes in {1, 4, 16}, X = 256 / Y); fixed
 // summation order (deterministic).  Up to REDUCE_BATCH independent reductions per launch
 // (blockIdx.y selects one); their destinations must not overlap.
-constexpr int REDUCE_BATCH = 8;
+constexpr int REDUCE_BATCH = 16;   // 16 descriptors of 176 bytes: within the 4 KB of kernel arguments
 // first[k] = first workgroup of reduction k (first[n] = grid size): every workgroup has work
 struct ReduceBatch { ReduceArgs a[REDUCE_BATCH]; int first[REDUCE_BATCH + 1]; int n; };
 __global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceBatch rb) {
