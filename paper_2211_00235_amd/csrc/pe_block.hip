@@ -480,37 +480,47 @@ template <typename T> struct Runner {
     ra.vec = v4 ? 4 : 1;
     pend[bidx(ar)][phase[bidx(ar)]].push_back(ra);
   }
-  // launches every queued reduction of the branch that works in `ar` on that branch's stream and
-  // releases the branch's partial buffers
-  void flush_all(const Arena& ar, hipStream_t main_st) {
+  void launch_reductions(const std::vector<ReduceArgs>& pending, size_t begin, size_t end, hipStream_t st) {
+    for (size_t i = begin; i < end; i += REDUCE_BATCH) {
+      ReduceBatch rb;
+      rb.n = (int)std::min((size_t)REDUCE_BATCH, end - i);
+      long long nblocks = 0;
+      double bytes = 0;
+      for (int k = 0; k < REDUCE_BATCH; k++) {
+        rb.a[k] = pending[i + (k < rb.n ? k : 0)];
+        rb.first[k] = (int)nblocks;
+        if (k < rb.n) {
+          long long total = (long long)rb.a[k].rows * rb.a[k].cols;
+          int X = 256 / rb.a[k].ylanes * rb.a[k].vec;
+          nblocks += (total + X - 1) / X;
+          bytes += 4.0 * total * (rb.a[k].nsplit + 2);
+        }
+      }
+      rb.first[REDUCE_BATCH] = (int)nblocks;
+      PE_LAUNCH("reduce_partials", 0, bytes, st, reduce_partials_kernel, dim3((unsigned)nblocks), dim3(256), 0, rb);
+    }
+  }
+  // launches every queued reduction of the branch that works in `ar` on that branch's stream and releases the
+  // branch's partial buffers.  early_st != nullptr: the reductions queued before mark_early(ar) was called go to
+  // early_st instead (the caller has made early_st wait for the kernels that wrote their partials).
+  size_t early_n[2][2] = {{0, 0}, {0, 0}};
+  void mark_early(const Arena& ar) { const int bi = bidx(ar); early_n[bi][0] = pend[bi][0].size(); early_n[bi][1] = pend[bi][1].size(); }
+  void flush_all(const Arena& ar, hipStream_t main_st, hipStream_t early_st = nullptr) {
     const int bi = bidx(ar);
     part_arena(ar).release(0);
-    if (dry || err) { pend[bi][0].clear(); pend[bi][1].clear(); phase[bi] = 0; return; }
+    if (dry || err) { pend[bi][0].clear(); pend[bi][1].clear(); phase[bi] = 0; early_n[bi][0] = early_n[bi][1] = 0; return; }
+    if (early_st) {
+      for (int ph = 0; ph < 2; ph++) launch_reductions(pend[bi][ph], 0, std::min(early_n[bi][ph], pend[bi][ph].size()), early_st);
+    }
     fork_side(main_st);
     hipStream_t st = side_of(main_st);
     for (int ph = 0; ph < 2; ph++) {
-      std::vector<ReduceArgs>& pending = pend[bi][ph];
-      for (size_t i = 0; i < pending.size(); i += REDUCE_BATCH) {
-        ReduceBatch rb;
-        rb.n = (int)std::min((size_t)REDUCE_BATCH, pending.size() - i);
-        long long nblocks = 0;
-        double bytes = 0;
-        for (int k = 0; k < REDUCE_BATCH; k++) {
-          rb.a[k] = pending[i + (k < rb.n ? k : 0)];
-          rb.first[k] = (int)nblocks;
-          if (k < rb.n) {
-            long long total = (long long)rb.a[k].rows * rb.a[k].cols;
-            int X = 256 / rb.a[k].ylanes * rb.a[k].vec;
-            nblocks += (total + X - 1) / X;
-            bytes += 4.0 * total * (rb.a[k].nsplit + 2);
-          }
-        }
-        rb.first[REDUCE_BATCH] = (int)nblocks;
-        PE_LAUNCH("reduce_partials", 0, bytes, st, reduce_partials_kernel, dim3((unsigned)nblocks), dim3(256), 0, rb);
-      }
-      pending.clear();
+      const size_t from = early_st ? std::min(early_n[bi][ph], pend[bi][ph].size()) : 0;
+      launch_reductions(pend[bi][ph], from, pend[bi][ph].size(), st);
+      pend[bi][ph].clear();
     }
     phase[bi] = 0;
+    early_n[bi][0] = early_n[bi][1] = 0;
     join_side(main_st);
   }
   void k_ln_bwd(hipStream_t st, Arena& ar, const T* dy, const T* x, const float* stats, long long g_off, long long b_off,
@@ -1404,8 +1414,16 @@ static int block_bwd_impl(pe_handle* h, const pe_dims& d, const void* msa_in, co
   if (d.variant == PE_VARIANT_PARALLEL) {
     if (do_p) R.bwd_pair_step(0, (const T*)d_pair_out, gz, R.pair_in);
     if (do_m) R.bwd_opm((const T*)d_pair_out, R.C.m3, (const T*)d_msa_out, gm);
+    // The MSA branch finishes first.  The reductions of all pair sub-operations but the last are therefore handed
+    // to stream_msa (after its own), which waits for the event recorded here: they then run beside the pair
+    // branch's last sub-operation instead of after it.
+    const bool hand_over = do_m && do_p && sm != sp && !h->side_streams;
     for (int i = 1; i < Runner<T>::PAIR_STEPS; i++) {
       if (do_p) R.bwd_pair_step(i, (const T*)d_pair_out, gz, R.pair_in);
+      if (hand_over && i == Runner<T>::PAIR_STEPS - 2) {
+        R.mark_early(R.ap);
+        if (!R.err && !hip_ok(h, hipEventRecord(h->ev[4], sp), "event record")) return PE_ERR_HIP;
+      }
       if (do_m && i - 1 < Runner<T>::MSA_STEPS) R.bwd_msa_step(i - 1, gm, R.pair_in, dzb);
     }
     if (do_m && !ev_link(h, 1, sm, sp)) return PE_ERR_HIP;
@@ -1421,8 +1439,9 @@ static int block_bwd_impl(pe_handle* h, const pe_dims& d, const void* msa_in, co
     }
     // the queued parameter-gradient reductions of both branches, each on its own stream; then both streams wait
     // for each other
-    R.flush_all(R.ap, sp);
     R.flush_all(R.am, sm);
+    if (hand_over && !R.err && !hip_ok(h, hipStreamWaitEvent(sm, h->ev[4], 0), "stream wait")) return PE_ERR_HIP;
+    R.flush_all(R.ap, sp, hand_over ? sm : nullptr);
     if (!ev_link(h, 2, sp, sm)) return PE_ERR_HIP;
     if (!ev_link(h, 3, sm, sp)) return PE_ERR_HIP;
     return R.err;
