@@ -167,8 +167,11 @@ long long pe_param_count(const pe_dims* d);                            /* fp32 e
 int pe_param_table(const pe_dims* d, pe_param_entry* out, int cap);    /* returns #entries      */
 int pe_ctx_table(const pe_dims* d, pe_ctx_entry* out, int cap);        /* returns #entries      */
 size_t pe_ctx_bytes(const pe_dims* d);                                 /* saved activations + prepared weights */
-/* Scratch needed by pe_block_fwd / pe_block_bwd.  with_ctx != 0 adds room for
- * an internal ctx (needed when ctx == NULL is passed to pe_block_bwd).       */
+/* Scratch needed by pe_block_fwd / pe_block_bwd: the two branches' work
+ * arenas plus, for the backward pass, the fp32 partial sums of every
+ * parameter gradient of the block (they are reduced into d_params at the end
+ * of the call).  with_ctx != 0 adds room for an internal ctx (needed when
+ * ctx == NULL is passed to pe_block_bwd).                                   */
 size_t pe_workspace_bytes(const pe_dims* d, int with_ctx);
 /* Scratch needed by pe_stack_fwd_bwd (saved block inputs + one block's needs). */
 size_t pe_stack_workspace_bytes(int n_extra, const pe_dims* extra, int n_main, const pe_dims* main_);
