@@ -201,6 +201,29 @@ int pe_block_fwd(pe_handle* h, const pe_dims* dims,
                  void* workspace, size_t workspace_bytes,
                  void* stream_msa, void* stream_pair);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): pe_block_fwd without ctx and without a workspace
+ * argument.  The scratch that pe_block_fwd carves from `workspace` (work arenas, internal saved
+ * activations, prepared weights) comes from one array that the library holds in device memory on
+ * every device it is loaded on, pe_static_scratch_bytes() = 32 MiB, from load until the process
+ * ends; its address on the handle's device is looked up once in pe_create.  The call allocates
+ * nothing (no hipMalloc / hipFree, no allocating library routine) and only enqueues.
+ *   Arguments as pe_block_fwd; the caller still passes inputs and outputs.
+ *   Returns PE_ERR_WORKSPACE (sizes in pe_last_error) when pe_workspace_bytes(dims, 1) exceeds
+ *   pe_static_scratch_bytes(): e.g. s=24, r=48 at the tiny channel widths fits, s=128, r=256 does
+ *   not.  PE_ERR_ARG when the current device is not the one the handle was created on.
+ *   Every call on a device shares that device's array, which keeps the last call's contents
+ *   (nothing in it has to start at zero: every kernel writes what it later reads).  Calls that
+ *   overlap on one device — two handles, two host threads, or a second call enqueued on other
+ *   streams before the first has finished — race on it; order them (same streams, or an event). */
+size_t pe_static_scratch_bytes(void);
+int pe_block_fwd_static(pe_handle* h, const pe_dims* dims,
+                        const void* msa_in, const void* pair_in,
+                        const float* msa_mask, const float* pair_mask,
+                        const float* params,
+                        void* msa_out, void* pair_out,
+                        void* stream_msa, void* stream_pair);
+
 /* Backward of one block (data flow of Section "Branch Parallelism": the
  * cotangent of the pair output feeds the pair branch AND the outer product
  * mean; d_pair_in = pair-branch term + row-attention-bias term).

@@ -68,6 +68,9 @@ def lib():
     L.pe_stack_workspace_bytes_keep.argtypes = [C.c_int, dp, C.c_int, dp]
     L.pe_stack_workspace_bytes_keep.restype = C.c_size_t
     L.pe_block_fwd.argtypes = [vp, dp, vp, vp, fp, fp, fp, vp, vp, vp, vp, C.c_size_t, vp, vp]
+    L.pe_static_scratch_bytes.argtypes = []
+    L.pe_static_scratch_bytes.restype = C.c_size_t
+    L.pe_block_fwd_static.argtypes = [vp, dp, vp, vp, fp, fp, fp, vp, vp, vp, vp]
     L.pe_block_bwd.argtypes = [vp, dp, vp, vp, fp, fp, fp, vp, vp, vp, vp, fp, vp, vp, C.c_size_t, vp, vp]
     L.pe_stack_fwd_bwd.argtypes = [vp, C.c_int, dp, C.c_int, dp, vp, vp, vp, fp, fp, fp, fp, vp, vp,
                                    vp, vp, vp, vp, vp, fp, vp, C.c_size_t, vp, vp]
@@ -198,6 +201,17 @@ def block_fwd(h, dims, msa_in, pair_in, msa_mask, pair_mask, params, msa_out, pa
                             _p(params), _p(msa_out), _p(pair_out), _p(ctx), _p(workspace),
                             workspace.numel() * workspace.element_size(), _s(stream_msa), _s(stream_pair))
     _raise(h, rc, "pe_block_fwd")
+
+
+def static_scratch_bytes():
+    return int(lib().pe_static_scratch_bytes())
+
+
+def block_fwd_static(h, dims, msa_in, pair_in, msa_mask, pair_mask, params, msa_out, pair_out,
+                     stream_msa=None, stream_pair=None):
+    rc = lib().pe_block_fwd_static(h._h, C.byref(_dims(dims)), _p(msa_in), _p(pair_in), _p(msa_mask), _p(pair_mask),
+                                   _p(params), _p(msa_out), _p(pair_out), _s(stream_msa), _s(stream_pair))
+    _raise(h, rc, "pe_block_fwd_static")
 
 
 def block_bwd(h, dims, msa_in, pair_in, msa_mask, pair_mask, params, d_msa_out, d_pair_out, d_msa_in, d_pair_in,

@@ -7,6 +7,7 @@
 // output cotangent (an input) and the row-attention-bias gradient is added to the pair
 // branch's gradient of the input pair representation at the very end.
 #include <stdio.h>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -16,8 +17,22 @@
 #include "pe_gemm.h"
 #include "pe_layout.h"
 
+// Scratch of pe_block_fwd_static: one array per device, held from the load of the library's code object
+// until the process ends.  Host code never uses the array's name as an address: pe_create looks the
+// device address up once per device and every later use goes through that pointer.
+#define PE_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+// No kernel names the array (kernels get its address as an argument).  It stays in the code object, under a symbol
+// the loader can find, because host code names it in hipGetSymbolAddress; an explicit `used` attribute would
+// keep it as a local symbol instead, which the runtime cannot look up.
+static __device__ __align__(256) unsigned char scratch[PE_STATIC_SCRATCH_BYTES];
+#define PE_MAX_DEVICES 64
+static void* g_scratch_ptr[PE_MAX_DEVICES];
+static std::mutex g_scratch_mutex;
+
 struct ProfRec { const char* label; std::string kern; double flops, bytes; hipEvent_t e0, e1; };
 struct pe_handle {
+  int device;                       // device that was current in pe_create
+  void* static_scratch;             // that device's copy of `scratch`
   hipEvent_t ev[6];
   int branches;
   int sync_debug;
@@ -1598,6 +1613,27 @@ int pe_destroy(pe_handle* h);
 int pe_create(pe_handle** out) {
   if (!out) return PE_ERR_NULL;
   pe_handle* h = new pe_handle();
+  {
+    // Device address of `scratch` on the current device, looked up on the first pe_create per device.
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess && (dev < 0 || dev >= PE_MAX_DEVICES)) e = hipErrorInvalidDevice;
+    if (e == hipSuccess) {
+      std::lock_guard<std::mutex> lock(g_scratch_mutex);
+      if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e == hipSuccess && !p) e = hipErrorInvalidSymbol;
+        if (e == hipSuccess) g_scratch_ptr[dev] = p;
+      }
+      if (e == hipSuccess) { h->device = dev; h->static_scratch = g_scratch_ptr[dev]; }
+    }
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      delete h;
+      return PE_ERR_HIP;
+    }
+  }
   h->branches = 3;
   h->sync_debug = 0;
   h->timing = 0;
@@ -1710,6 +1746,32 @@ int pe_block_fwd(pe_handle* h, const pe_dims* dims, const void* msa_in, const vo
                                 workspace_bytes, (hipStream_t)stream_msa, (hipStream_t)stream_pair);
   return block_fwd_impl<float>(h, *dims, msa_in, pair_in, msa_mask, pair_mask, params, msa_out, pair_out, ctx, workspace,
                                workspace_bytes, (hipStream_t)stream_msa, (hipStream_t)stream_pair);
+}
+
+size_t pe_static_scratch_bytes(void) { return PE_STATIC_SCRATCH_BYTES; }
+
+int pe_block_fwd_static(pe_handle* h, const pe_dims* dims, const void* msa_in, const void* pair_in, const float* msa_mask,
+                        const float* pair_mask, const float* params, void* msa_out, void* pair_out, void* stream_msa,
+                        void* stream_pair) {
+  if (!h || !dims) return PE_ERR_NULL;
+  int rc = pe_check_dims(dims);
+  if (rc) return rc;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != h->device) {
+    h->last_error = "pe_block_fwd_static: the handle belongs to another device than the current one";
+    return PE_ERR_ARG;
+  }
+  const size_t need = plan_for(*dims).total(true);
+  if (need > PE_STATIC_SCRATCH_BYTES) {
+    char msg[160];
+    snprintf(msg, sizeof(msg), "pe_block_fwd_static: these dims need %zu bytes of scratch, the static array holds %zu",
+             need, (size_t)PE_STATIC_SCRATCH_BYTES);
+    h->last_error = msg;
+    return PE_ERR_WORKSPACE;
+  }
+  // nothing in the scratch has to start at zero: every kernel writes what it later reads
+  return pe_block_fwd(h, dims, msa_in, pair_in, msa_mask, pair_mask, params, msa_out, pair_out, nullptr, h->static_scratch,
+                      PE_STATIC_SCRATCH_BYTES, stream_msa, stream_pair);
 }
 
 int pe_block_bwd(pe_handle* h, const pe_dims* dims, const void* msa_in, const void* pair_in, const float* msa_mask,
