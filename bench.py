@@ -43,7 +43,7 @@ def block_fwd_flops(d):
 def bench_trunk(args, torch, pe):
     """Config 5: 4 extra-MSA blocks then 48 main blocks, per-block recompute, two streams."""
     from pe_inputs import dims_for, make_inputs
-    from tests.gpu_util import to_dev
+    from paper_2211_00235_amd.harness import to_dev
     de, me, _ = dims_for("extra_msa")
     dm, mmk, _ = dims_for("af2_initial")
     ne, nm = 4, 48
@@ -147,7 +147,7 @@ def main():
     import torch
     import paper_2211_00235_amd as pe
     from pe_inputs import dims_for, make_inputs
-    from tests.gpu_util import BlockRun     # argument marshalling helper (no oracle import)
+    from paper_2211_00235_amd.harness import BlockRun     # argument marshalling helper (no oracle import)
 
     pe.lib()                                  # fails loudly when the HIP library is not built
     if not torch.cuda.is_available():

@@ -65,15 +65,20 @@ enum {
   PE_ERR_NULL = -1,      /* a required pointer is NULL                               */
   PE_ERR_DIMS = -2,      /* unsupported dims (see pe_check_dims)                     */
   PE_ERR_WORKSPACE = -3, /* workspace smaller than pe_workspace_bytes / stack bytes  */
-  PE_ERR_ALIAS = -4,     /* an output aliases an input or another output             */
+  PE_ERR_ALIAS = -4,     /* a buffer the call writes (outputs, ctx of the forward, d_params, workspace)
+                            overlaps another buffer of the call                       */
   PE_ERR_HIP = -5,       /* a HIP call failed; text in pe_last_error                 */
   PE_ERR_ARG = -6        /* bad option / count / capacity                            */
 };
 
-/* Shape of one block.  Requirements checked by pe_check_dims:
- *   s,r >= 1; c_m, c_z, h*d, c_tri, c_opm, n_trans*c multiples of 8;
- *   d_msa, d_pair in [2, 32] and even; every channel count <= 1024;
- *   variant one of PE_VARIANT_*.                                            */
+/* Shape of one block.  Requirements checked by pe_check_dims (pe_dims_error names the one that
+ * failed):
+ *   s, r >= 1 with s*r < 2^31 and r*r < 2^31; n_trans >= 1;
+ *   c_m, c_z, h_msa*d_msa, h_pair*d_pair, c_tri, c_opm: multiples of 8 in [8, 1024], and
+ *     c_z <= 256, c_tri <= 192, n_trans*c_m <= 4096, n_trans*c_z <= 4096;
+ *   h_msa, h_pair in [1, 8]; d_msa, d_pair in {8, 16, 24, 32};
+ *   col_global in {0, 1}; with col_global = 1 additionally d_msa <= 8;
+ *   dtype PE_F32 or PE_BF16; variant one of PE_VARIANT_*; ln_eps, opm_eps > 0.                    */
 typedef struct pe_dims {
   int s, r, c_m, c_z;    /* msa[s,r,c_m], pair[r,r,c_z]                              */
   int h_msa, d_msa;      /* MSA attention heads x head dim                           */
@@ -163,6 +168,7 @@ int pe_timing_collect(pe_handle* h, pe_timing_entry* out, int cap);
 
 /* Host-side shape queries (no GPU needed). */
 int pe_check_dims(const pe_dims* d);                                   /* PE_OK or PE_ERR_DIMS */
+const char* pe_dims_error(const pe_dims* d);   /* which requirement pe_check_dims found violated ("" if none); static text */
 long long pe_param_count(const pe_dims* d);                            /* fp32 elements / block */
 int pe_param_table(const pe_dims* d, pe_param_entry* out, int cap);    /* returns #entries      */
 int pe_ctx_table(const pe_dims* d, pe_ctx_entry* out, int cap);        /* returns #entries      */

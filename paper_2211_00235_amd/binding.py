@@ -55,6 +55,8 @@ def lib():
     L.pe_destroy.argtypes = [vp]
     L.pe_set_option.argtypes = [vp, C.c_int, C.c_int]
     L.pe_check_dims.argtypes = [dp]
+    L.pe_dims_error.argtypes = [dp]
+    L.pe_dims_error.restype = C.c_char_p
     L.pe_param_count.argtypes = [dp]
     L.pe_param_count.restype = C.c_longlong
     L.pe_param_table.argtypes = [dp, C.POINTER(_ParamEntry), C.c_int]
@@ -93,6 +95,11 @@ def _dims(d):
 
 def check_dims(d):
     return lib().pe_check_dims(C.byref(_dims(d)))
+
+
+def dims_error(d):
+    """Text of the requirement that check_dims found violated ('' if the dims are supported)."""
+    return lib().pe_dims_error(C.byref(_dims(d))).decode()
 
 
 def param_count(d):
@@ -190,9 +197,10 @@ def _s(stream):
     return C.c_void_p(getattr(stream, "cuda_stream", stream))
 
 
-def _raise(h, rc, what):
+def _raise(h, rc, what, dims=None):
     if rc:
-        raise PEError("%s: %s %s" % (what, strerror(rc), h.last_error()))
+        why = dims_error(dims) if (rc == -2 and dims is not None) else h.last_error()
+        raise PEError("%s: %s %s" % (what, strerror(rc), why))
 
 
 def block_fwd(h, dims, msa_in, pair_in, msa_mask, pair_mask, params, msa_out, pair_out, ctx, workspace,
@@ -200,7 +208,7 @@ def block_fwd(h, dims, msa_in, pair_in, msa_mask, pair_mask, params, msa_out, pa
     rc = lib().pe_block_fwd(h._h, C.byref(_dims(dims)), _p(msa_in), _p(pair_in), _p(msa_mask), _p(pair_mask),
                             _p(params), _p(msa_out), _p(pair_out), _p(ctx), _p(workspace),
                             workspace.numel() * workspace.element_size(), _s(stream_msa), _s(stream_pair))
-    _raise(h, rc, "pe_block_fwd")
+    _raise(h, rc, "pe_block_fwd", dims)
 
 
 def static_scratch_bytes():
@@ -211,7 +219,7 @@ def block_fwd_static(h, dims, msa_in, pair_in, msa_mask, pair_mask, params, msa_
                      stream_msa=None, stream_pair=None):
     rc = lib().pe_block_fwd_static(h._h, C.byref(_dims(dims)), _p(msa_in), _p(pair_in), _p(msa_mask), _p(pair_mask),
                                    _p(params), _p(msa_out), _p(pair_out), _s(stream_msa), _s(stream_pair))
-    _raise(h, rc, "pe_block_fwd_static")
+    _raise(h, rc, "pe_block_fwd_static", dims)
 
 
 def block_bwd(h, dims, msa_in, pair_in, msa_mask, pair_mask, params, d_msa_out, d_pair_out, d_msa_in, d_pair_in,
@@ -220,7 +228,7 @@ def block_bwd(h, dims, msa_in, pair_in, msa_mask, pair_mask, params, d_msa_out, 
                             _p(params), _p(d_msa_out), _p(d_pair_out), _p(d_msa_in), _p(d_pair_in), _p(d_params),
                             _p(ctx), _p(workspace), workspace.numel() * workspace.element_size(),
                             _s(stream_msa), _s(stream_pair))
-    _raise(h, rc, "pe_block_bwd")
+    _raise(h, rc, "pe_block_bwd", dims)
 
 
 def stack_fwd_bwd(h, n_extra, extra, n_main, main, extra_msa_in, msa_in, pair_in, extra_mask, msa_mask, pair_mask,

@@ -297,18 +297,21 @@ template <typename T> struct Runner {
     HDm = d.h_msa * d.d_msa;
     HDz = d.h_pair * d.d_pair;
   }
-  void fail(const char* what) {
+  // e: the failing call's code when the caller has it (hipGetLastError clears the error it returns)
+  void fail(const char* what, hipError_t e = hipSuccess) {
     if (!err) {
       err = PE_ERR_HIP;
-      hipError_t e = hipGetLastError();
+      if (e == hipSuccess) e = hipGetLastError();
       if (h) h->last_error = std::string(what) + ": " + hipGetErrorString(e);
     }
   }
   void check(const char* what) {
     if (dry || err) return;
-    if (hipGetLastError() != hipSuccess) { fail(what); return; }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { fail(what, e); return; }
     if (h && h->sync_debug) {
-      if (hipDeviceSynchronize() != hipSuccess) fail(what);
+      e = hipDeviceSynchronize();
+      if (e != hipSuccess) fail(what, e);
     }
   }
 
@@ -393,9 +396,10 @@ template <typename T> struct Runner {
       pb.n = (int)std::min((size_t)PREP_MAX, v.size() - i);
       for (int k = 0; k < pb.n; k++) pb.d[k] = v[i + k];
       dim3 grid(64, pb.n);
-      if (is_f) hipLaunchKernelGGL(prep_params_kernel<float>, grid, dim3(256), 0, st, params, fbase, pb);
-      else hipLaunchKernelGGL(prep_params_kernel<T>, grid, dim3(256), 0, st, params, tbase, pb);
-      check("prep_params");
+      double bytes = 0;
+      for (int k = 0; k < pb.n; k++) bytes += (double)pb.d[k].rows * pb.d[k].cols * (4 + (is_f ? 4 : sizeof(T)));
+      if (is_f) PE_LAUNCH("prep_params", 0, bytes, st, prep_params_kernel<float>, grid, dim3(256), 0, params, fbase, pb);
+      else PE_LAUNCH("prep_params", 0, bytes, st, prep_params_kernel<T>, grid, dim3(256), 0, params, tbase, pb);
     }
   }
   void run_prep(bool msa_side) {
@@ -578,9 +582,11 @@ template <typename T> struct Runner {
       EpiPartial ep{part, (long long)M * N, N};
       prof_begin(st);
       bool al = false, dwx = false;
-      int rc = launch_gemm<T, EpiPartial>(st, A, akc, B, bkc, sh, ep, &al, &dwx, dw_groups());
+      int depth = 0;
+      int rc = launch_gemm<T, EpiPartial>(st, A, akc, B, bkc, sh, ep, &al, &dwx, dw_groups(), &depth);
       char kn[64];
-      if (dwx) snprintf(kn, sizeof(kn), "gemm_dwx_kernel<%d>", dw_groups());
+      if (dwx && depth) snprintf(kn, sizeof(kn), "gemm_dwp_kernel<%d>", depth);
+      else if (dwx) snprintf(kn, sizeof(kn), "gemm_dwx_kernel<%d>", dw_groups());
       else snprintf(kn, sizeof(kn), "gemm_kernel<%s,%s,%s,EpiPartial>", akc ? "kc" : "xc", bkc ? "kc" : "xc", al ? "vec" : "elem");
       prof_end(st, what, kn, 2.0 * M * N * K, ((double)M * K + (double)N * K) * sizeof(T));
       if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = std::string("gemm operand alignment: ") + what; return; }
@@ -621,9 +627,11 @@ template <typename T> struct Runner {
       EpiPartial ep{part, (long long)rows * cols, cols, cs_part};
       prof_begin(st);
       bool al = false, dwx = false;
-      int rc = launch_gemm<T, EpiPartial>(st, X, xkc, Y, ykc, sh, ep, &al, &dwx, dw_groups());
+      int depth = 0;
+      int rc = launch_gemm<T, EpiPartial>(st, X, xkc, Y, ykc, sh, ep, &al, &dwx, dw_groups(), &depth);
       char kn[64];
-      if (dwx) snprintf(kn, sizeof(kn), "gemm_dwx_kernel<%d>", dw_groups());
+      if (dwx && depth) snprintf(kn, sizeof(kn), "gemm_dwp_kernel<%d>", depth);
+      else if (dwx) snprintf(kn, sizeof(kn), "gemm_dwx_kernel<%d>", dw_groups());
       else snprintf(kn, sizeof(kn), "gemm_kernel<%s,%s,%s,EpiPartial>", xkc ? "kc" : "xc", ykc ? "kc" : "xc", al ? "vec" : "elem");
       prof_end(st, what, kn, 2.0 * rows * cols * K, ((double)rows * K + (double)cols * K) * sizeof(T));
       if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = std::string("gemm_dw operand alignment: ") + what; }
@@ -1576,10 +1584,12 @@ static int stack_impl(pe_handle* h, int n_extra, const pe_dims* ex, int n_main, 
   const void* de = nullptr;
   if (n_extra) {
     // a fill kernel, not hipMemsetAsync: the call may be captured into a HIP graph by the caller
+    // the slot that the last extra block does NOT write (it writes de_pp[(n_extra - 1) & 1], or d_extra_msa_in)
+    char* zero_slot = de_pp[n_extra & 1];
     hipLaunchKernelGGL(zero_bytes16_kernel, dim3((unsigned)((sp.n_extra / 16 + 255) / 256)), dim3(256), 0, sm,
-                       (uint4*)de_pp[1], (long long)(sp.n_extra / 16));
+                       (uint4*)zero_slot, (long long)(sp.n_extra / 16));
     if (!hip_ok(h, hipGetLastError(), "zero fill")) return PE_ERR_HIP;
-    de = de_pp[1];
+    de = zero_slot;
   }
   for (int b = nb - 1; b >= 0; b--) {
     const bool is_e = b < n_extra;
@@ -1604,6 +1614,16 @@ static int stack_impl(pe_handle* h, int n_extra, const pe_dims* ex, int n_main, 
 static bool overlap(const void* a, size_t na, const void* b, size_t nb) {
   const char* x = (const char*)a; const char* y = (const char*)b;
   return x < y + nb && y < x + na;
+}
+// a buffer of a call: written = the call writes it (outputs, ctx of the forward, workspace)
+struct Region { const void* p; size_t n; bool written; };
+// true when two buffers overlap of which at least one is written (null and empty buffers are skipped)
+static bool any_alias(const Region* r, int n) {
+  for (int i = 0; i < n; i++)
+    for (int j = i + 1; j < n; j++)
+      if ((r[i].written || r[j].written) && r[i].p && r[j].p && r[i].n && r[j].n && overlap(r[i].p, r[i].n, r[j].p, r[j].n))
+        return true;
+  return false;
 }
 
 extern "C" {
@@ -1682,11 +1702,23 @@ int pe_set_option(pe_handle* h, int option, int value) {
   }
   return PE_ERR_ARG;
 }
-int pe_check_dims(const pe_dims* d) {
-  int rc = pe_check_dims_impl(d);
+static int check_dims_why(const pe_dims* d, const char** why) {
+  int rc = pe_check_dims_impl(d, why);
   if (rc) return rc;
-  if (d->col_global && (d->d_msa > GC_MAXD || d->h_msa > GC_MAXH)) return PE_ERR_DIMS;   // global variant: d <= 8, H <= 8
+  if (d->col_global && (d->d_msa > GC_MAXD || d->h_msa > GC_MAXH)) {
+    *why = "global column attention needs d_msa <= 8 and h_msa <= 8";
+    return PE_ERR_DIMS;
+  }
   return PE_OK;
+}
+int pe_check_dims(const pe_dims* d) {
+  const char* why;
+  return check_dims_why(d, &why);
+}
+const char* pe_dims_error(const pe_dims* d) {
+  const char* why = "";
+  (void)check_dims_why(d, &why);
+  return why;
 }
 long long pe_param_count(const pe_dims* d) {
   if (pe_check_dims_impl(d)) return -1;
@@ -1737,9 +1769,14 @@ int pe_block_fwd(pe_handle* h, const pe_dims* dims, const void* msa_in, const vo
   if (rc) return rc;
   size_t E = dims->dtype == PE_BF16 ? 2 : 4;
   size_t nm = (size_t)dims->s * dims->r * dims->c_m * E, nz = (size_t)dims->r * dims->r * dims->c_z * E;
-  if (overlap(msa_out, nm, msa_in, nm) || overlap(pair_out, nz, pair_in, nz) || overlap(msa_out, nm, pair_in, nz) ||
-      overlap(pair_out, nz, msa_in, nm) || overlap(msa_out, nm, pair_out, nz))
-    return PE_ERR_ALIAS;
+  {
+    const Plan pl = plan_for(*dims);
+    const Region rg[] = {{msa_in, nm, false}, {pair_in, nz, false}, {msa_mask, (size_t)dims->s * dims->r * 4, false},
+                         {pair_mask, (size_t)dims->r * dims->r * 4, false}, {params, (size_t)pe_param_count(dims) * 4, false},
+                         {msa_out, nm, true}, {pair_out, nz, true}, {ctx, ctx ? pl.ctx_total() : 0, true},
+                         {workspace, pl.total(ctx == nullptr), true}};
+    if (any_alias(rg, (int)(sizeof(rg) / sizeof(rg[0])))) return PE_ERR_ALIAS;
+  }
   if (((uintptr_t)workspace) % 256 || (ctx && ((uintptr_t)ctx) % 256)) return PE_ERR_ARG;
   if (dims->dtype == PE_BF16)
     return block_fwd_impl<bf16>(h, *dims, msa_in, pair_in, msa_mask, pair_mask, params, msa_out, pair_out, ctx, workspace,
@@ -1785,9 +1822,16 @@ int pe_block_bwd(pe_handle* h, const pe_dims* dims, const void* msa_in, const vo
   if (rc) return rc;
   size_t E = dims->dtype == PE_BF16 ? 2 : 4;
   size_t nm = (size_t)dims->s * dims->r * dims->c_m * E, nz = (size_t)dims->r * dims->r * dims->c_z * E;
-  if (overlap(d_msa_in, nm, msa_in, nm) || overlap(d_pair_in, nz, pair_in, nz) || overlap(d_msa_in, nm, d_msa_out, nm) ||
-      overlap(d_pair_in, nz, d_pair_out, nz) || overlap(d_msa_in, nm, d_pair_in, nz))
-    return PE_ERR_ALIAS;
+  {
+    const Plan pl = plan_for(*dims);
+    const size_t np = (size_t)pe_param_count(dims) * 4;
+    const Region rg[] = {{msa_in, nm, false}, {pair_in, nz, false}, {msa_mask, (size_t)dims->s * dims->r * 4, false},
+                         {pair_mask, (size_t)dims->r * dims->r * 4, false}, {params, np, false},
+                         {d_msa_out, nm, false}, {d_pair_out, nz, false}, {ctx, ctx ? pl.ctx_total() : 0, false},
+                         {d_msa_in, nm, true}, {d_pair_in, nz, true}, {d_params, np, true},
+                         {workspace, pl.total(ctx == nullptr), true}};
+    if (any_alias(rg, (int)(sizeof(rg) / sizeof(rg[0])))) return PE_ERR_ALIAS;
+  }
   if (((uintptr_t)workspace) % 256 || (ctx && ((uintptr_t)ctx) % 256)) return PE_ERR_ARG;
   if (dims->dtype == PE_BF16)
     return block_bwd_impl<bf16>(h, *dims, msa_in, pair_in, msa_mask, pair_mask, params, d_msa_out, d_pair_out, d_msa_in,
@@ -1817,6 +1861,10 @@ int pe_stack_fwd_bwd(pe_handle* h, int n_extra, const pe_dims* extra, int n_main
                      void* stream_pair) {
   if (!h || !pair_in || !pair_mask || !params || !d_pair_out || !pair_out || !d_pair_in || !d_params || !workspace)
     return PE_ERR_NULL;
+  if (h->branches != 3) {   // a block with one branch switched off leaves an output unwritten that the next block reads
+    h->last_error = "pe_stack_fwd_bwd needs both branches (PE_OPT_BRANCHES = 3)";
+    return PE_ERR_ARG;
+  }
   StackPlan sp;
   int rc = make_stack_plan(n_extra, extra, n_main, main_, h->stack_keep != 0, sp);
   if (rc) return rc;
@@ -1824,12 +1872,22 @@ int pe_stack_fwd_bwd(pe_handle* h, int n_extra, const pe_dims* extra, int n_main
   if (n_main && (!msa_in || !msa_mask || !d_msa_out || !msa_out || !d_msa_in)) return PE_ERR_NULL;
   if (((uintptr_t)workspace) % 256) return PE_ERR_ARG;
   if (workspace_bytes < sp.total) return PE_ERR_WORKSPACE;
-  if (overlap(pair_out, sp.n_pair, pair_in, sp.n_pair) || overlap(d_pair_in, sp.n_pair, d_pair_out, sp.n_pair) ||
-      overlap(d_pair_in, sp.n_pair, pair_in, sp.n_pair))
-    return PE_ERR_ALIAS;
-  if (n_main && (overlap(msa_out, sp.n_msa, msa_in, sp.n_msa) || overlap(d_msa_in, sp.n_msa, d_msa_out, sp.n_msa) ||
-                 overlap(d_msa_in, sp.n_msa, msa_in, sp.n_msa)))
-    return PE_ERR_ALIAS;
+  {
+    const size_t np = (size_t)((n_extra ? pe_param_count(extra) * n_extra : 0) + (n_main ? pe_param_count(main_) * n_main : 0)) * 4;
+    const size_t nem = n_extra ? (size_t)extra->s * extra->r * 4 : 0, nmm = n_main ? (size_t)main_->s * main_->r * 4 : 0;
+    const pe_dims* any = n_main ? main_ : extra;
+    // exact tensor sizes (the plan's are rounded up to its 256-byte slots)
+    const size_t ze = n_extra ? (size_t)extra->s * extra->r * extra->c_m * sp.E : 0;
+    const size_t zm = n_main ? (size_t)main_->s * main_->r * main_->c_m * sp.E : 0;
+    const size_t zz = (size_t)any->r * any->r * any->c_z * sp.E;
+    const Region rg[] = {{extra_msa_in, ze, false}, {msa_in, zm, false}, {pair_in, zz, false},
+                         {extra_msa_mask, nem, false}, {msa_mask, nmm, false}, {pair_mask, (size_t)any->r * any->r * 4, false},
+                         {params, np, false}, {d_msa_out, zm, false}, {d_pair_out, zz, false},
+                         {msa_out, zm, true}, {pair_out, zz, true}, {d_extra_msa_in, ze, true},
+                         {d_msa_in, zm, true}, {d_pair_in, zz, true}, {d_params, np, true},
+                         {workspace, sp.total, true}};
+    if (any_alias(rg, (int)(sizeof(rg) / sizeof(rg[0])))) return PE_ERR_ALIAS;
+  }
   const int dt = n_main ? main_->dtype : extra->dtype;
   if (dt == PE_BF16)
     return stack_impl<bf16>(h, n_extra, extra, n_main, main_, sp, extra_msa_in, msa_in, pair_in, extra_msa_mask, msa_mask,

@@ -17,6 +17,7 @@
 // owns 64x64 = 2x2 MFMA tiles (64 accumulator VGPRs).  Next k-tile is prefetched
 // into registers while the current one is consumed from LDS.
 #pragma once
+#include <stdlib.h>
 #include <string.h>
 #include <type_traits>
 #include "pe_common.h"
@@ -982,6 +983,179 @@ __global__ __launch_bounds__(256 * KG) void gemm_dwx_kernel(Operand A, Operand B
     }
 }
 
+// ---------------------------------------------------------------------------
+// Pipelined parameter-gradient kernel: the arithmetic, LDS layout, fragment gather and accumulator mapping of
+// gemm_dwx_kernel<1>, with S k-tiles in flight per workgroup instead of one.  Every thread keeps a ring of S
+// register tiles (S x 8 loads of 16 bytes): in step t it stores ring slot t % S to the LDS buffer t % 2, re-issues
+// the slot's loads for tile t + S, passes ONE barrier and multiplies from that buffer; the next store to the
+// same buffer comes two steps later, behind the barrier in between, so it cannot overtake a reader.  All
+// loads are unconditional (the host sends only shapes made of full tiles whose k-tiles do not straddle a group
+// of the two-level k map), so nothing but the consuming LDS store waits for them.  A workgroup owns a CU's
+// registers here anyway (256 workgroups on 256 CUs), and a k-step costs its memory latency, not its 16 MFMAs:
+// more bytes in flight is what shortens it.
+// ---------------------------------------------------------------------------
+PE_DEV void dwp_load(bf16x8 (&regs)[4], const bf16* base, const Operand& op, long long xa, int k) {
+  long long ka;
+  if (op.k_in >= (1 << 30)) ka = (long long)k * op.k_stride;
+  else ka = (long long)((unsigned)k / (unsigned)op.k_in) * op.k_outer + (long long)((unsigned)k % (unsigned)op.k_in) * op.k_stride;
+  const bf16* p = base + xa + ka;
+#pragma unroll
+  for (int j = 0; j < 4; j++) regs[j] = *reinterpret_cast<const bf16x8*>(p + (long long)j * op.k_stride);
+}
+
+template <int S>
+__global__ __launch_bounds__(256) void gemm_dwp_kernel(Operand A, Operand B, GemmShape sh, EpiPartial epi) {
+  static_assert(S == 2 || S == 4, "ring depth: even (the LDS buffer of a ring slot must not change between rounds)");
+  constexpr int BM = 128, BK = 64;
+  constexpr int TILE = BK * 128;                       // elements of one operand tile (16 KB)
+  extern __shared__ __attribute__((aligned(16))) bf16 lds_all[];   // 2 buffers x (A tile, B tile) = 64 KB
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  // same XCD-aware workgroup -> (batch, m-tile, n-tile) mapping as gemm_kernel
+  const int NTm = sh.M / BM, NTn = sh.N / BM;
+  const int xcd = blockIdx.x & 7, jq = blockIdx.x >> 3;
+  const int NTu = sh.unit_n ? NTn : NTm, NTi = sh.unit_n ? NTm : NTn;
+  const int unit = xcd + 8 * (jq / NTi);
+  if (unit >= NTu * sh.batch) return;
+  const int b = unit / NTu;
+  const int tu = (unit % NTu) * BM, ti = (jq % NTi) * BM;
+  const int m0 = sh.unit_n ? ti : tu, n0 = sh.unit_n ? tu : ti;
+  const int kbeg = b * sh.k_chunk, kend = min(sh.K, kbeg + sh.k_chunk);
+  const bf16* pa = (const bf16*)A.ptr;
+  const bf16* pb = (const bf16*)B.ptr;
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; i++)
+#pragma unroll
+    for (int j = 0; j < 2; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.0f;
+
+  // loader role: 8 x (chunk xb) at k rows 4 kb .. 4 kb + 3 of the tile
+  const int xb = tid & 15, kb = tid >> 4;
+  XAddr xa, xbb;
+  xa.init(A, m0, sh.M, xb);
+  xbb.init(B, n0, sh.N, xb);
+  const int st_off = kb * 4 * 128 + ((xb ^ (((kb >> 1) & 1) << 3)) * 8);
+  const bool do_cs = epi.colsum != nullptr && (m0 / BM) == (n0 / BM + b) % NTm;
+  float cs[8];
+#pragma unroll
+  for (int e = 0; e < 8; e++) cs[e] = 0.0f;
+  // fragment role (word offsets inside an operand tile): rows 2 l32, 2 l32 + 1 of the wave's strip at k = 16 kk + 8 g + e
+  const int fa_off = (((wm * 64 + 2 * l32) ^ (g * 64)) >> 1) + g * 8 * 64;
+  const int fb_off = (((wn * 64 + 2 * l32) ^ (g * 64)) >> 1) + g * 8 * 64;
+
+  bf16x8 ra[S][4], rb[S][4];
+  const int nt = (kend - kbeg) / BK;                   // a multiple of S
+#pragma unroll
+  for (int j = 0; j < S; j++) {
+    dwp_load(ra[j], pa, A, xa.a, kbeg + j * BK + kb * 4);
+    dwp_load(rb[j], pb, B, xbb.a, kbeg + j * BK + kb * 4);
+  }
+  auto step = [&](auto jc, int t, bool reload) {
+    constexpr int j = decltype(jc)::value;
+    bf16* la = lds_all + (j & 1) * 2 * TILE;
+    bf16* lb = la + TILE;
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      *reinterpret_cast<bf16x8*>(la + st_off + q * 128) = ra[j][q];
+      *reinterpret_cast<bf16x8*>(lb + st_off + q * 128) = rb[j][q];
+    }
+    if (do_cs) {
+#pragma unroll
+      for (int q = 0; q < 4; q++)
+#pragma unroll
+        for (int e = 0; e < 8; e++) cs[e] += (float)rb[j][q][e];
+    }
+    if (reload) {   // uniform over the workgroup
+      dwp_load(ra[j], pa, A, xa.a, kbeg + (t + S) * BK + kb * 4);
+      dwp_load(rb[j], pb, B, xbb.a, kbeg + (t + S) * BK + kb * 4);
+    }
+    __syncthreads();
+    const uint32_t* fa = reinterpret_cast<const uint32_t*>(la) + fa_off;
+    const uint32_t* fb = reinterpret_cast<const uint32_t*>(lb) + fb_off;
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; kk++) {
+      uint32_t wa[8], wb[8];
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        wa[e] = fa[(kk * 16 + e) * 64];
+        wb[e] = fb[(kk * 16 + e) * 64];
+      }
+      union { uint32_t u[4]; bf16x8 v; } a0, a1, b0, b1;
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        a0.u[q] = __builtin_amdgcn_perm(wa[2 * q + 1], wa[2 * q], 0x05040100u);
+        a1.u[q] = __builtin_amdgcn_perm(wa[2 * q + 1], wa[2 * q], 0x07060302u);
+        b0.u[q] = __builtin_amdgcn_perm(wb[2 * q + 1], wb[2 * q], 0x05040100u);
+        b1.u[q] = __builtin_amdgcn_perm(wb[2 * q + 1], wb[2 * q], 0x07060302u);
+      }
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0.v, b0.v, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0.v, b1.v, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1.v, b0.v, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1.v, b1.v, acc[1][1], 0, 0, 0);
+    }
+  };
+  int t = 0;
+  for (; t + S < nt; t += S) {     // rounds whose reloads stay inside the k range
+    step(std::integral_constant<int, 0>{}, t, true);
+    step(std::integral_constant<int, 1>{}, t + 1, true);
+    if constexpr (S == 4) {
+      step(std::integral_constant<int, 2>{}, t + 2, true);
+      step(std::integral_constant<int, 3>{}, t + 3, true);
+    }
+  }
+  // last round: nothing left to load
+  step(std::integral_constant<int, 0>{}, t, false);
+  step(std::integral_constant<int, 1>{}, t + 1, false);
+  if constexpr (S == 4) {
+    step(std::integral_constant<int, 2>{}, t + 2, false);
+    step(std::integral_constant<int, 3>{}, t + 3, false);
+  }
+
+  if (epi.colsum != nullptr) {   // uniform over the workgroup
+    float* lds_f = reinterpret_cast<float*>(lds_all);
+    __syncthreads();
+    if (do_cs) {
+#pragma unroll
+      for (int e = 0; e < 8; e++) lds_f[kb * 128 + xb * 8 + e] = cs[e];
+    }
+    __syncthreads();
+    if (do_cs && tid < 128) {
+      float s = 0.0f;
+      for (int r = 0; r < 16; r++) s += lds_f[r * 128 + tid];
+      epi.colsum[(long long)b * sh.N + n0 + tid] = s;
+    }
+  }
+  // accumulator element (i, j, a) of lane (l32, g): row 2 acc_row(g, a) + i, column 2 l32 + j of the wave's 64 x 64
+  const int n = n0 + wn * 64 + 2 * l32;
+#pragma unroll
+  for (int i = 0; i < 2; i++)
+#pragma unroll
+    for (int a = 0; a < 16; a++) {
+      const int m = m0 + wm * 64 + 2 * acc_row(g, a) + i;
+      f32x2 v; v[0] = acc[i][0][a]; v[1] = acc[i][1][a];
+      *reinterpret_cast<f32x2*>(epi.out + (long long)b * epi.mn + (long long)m * epi.ldn + n) = v;
+    }
+}
+
+// ring depth of the pipelined kernel for a shape (0: the shape is not made of full tiles, take another kernel).
+// What bounds these kernels is the rate at which a CU takes in tile bytes (about 25 GB/s per CU, L2 hits
+// included: 256 x 1024 x 32768 loads 256 MiB of tiles for 80 MiB of operands and takes 40 us, 128 MiB take 23 us,
+// 64 MiB 14 us, whatever the prefetch depth or the number of wave groups), so more depth buys nothing.
+static inline int dwp_depth(const Operand& A, const Operand& B, const GemmShape& sh) {
+  if (sh.k_chunk <= 0 || sh.M % 128 || sh.N % 128 || sh.K % 64 || sh.k_chunk % 64) return 0;
+  auto kmap_ok = [](const Operand& o) { return o.k_in >= (1 << 30) || o.k_in % 64 == 0; };
+  if (!kmap_ok(A) || !kmap_ok(B)) return 0;
+  const int last = sh.K - (sh.batch - 1) * sh.k_chunk;       // length of the last split
+  if (last <= 0 || last > sh.k_chunk) return 0;
+  if (sh.k_chunk % 128 == 0 && last % 128 == 0) return 2;   // a ring of 4 measured no faster (same 40 us at 256 x 1024 x 32768)
+  return 0;
+}
+
 // Two wave groups: measured 15 - 27 % faster than one on the block's parameter-gradient shapes when the
 // kernel has the chip to itself; three are no faster (and need more than 64 KB of LDS), four spill at
 // 128 registers.  Next to another branch's kernels on a second stream the extra resident waves cost
@@ -989,8 +1163,16 @@ __global__ __launch_bounds__(256 * KG) void gemm_dwx_kernel(Operand A, Operand B
 // else runs beside the call and for one group otherwise (0.4 % faster there than the register-transposing
 // kernel: no bank conflicts, fewer instructions).
 constexpr int DWX_GROUPS = 2;
-static inline int launch_dwx(hipStream_t st, dim3 grid, int groups, const Operand& A, const Operand& B, const GemmShape& sh, const EpiPartial& epi) {
+static inline int launch_dwx(hipStream_t st, dim3 grid, int groups, const Operand& A, const Operand& B, const GemmShape& sh, const EpiPartial& epi,
+                             int* depth_used = nullptr) {
   constexpr unsigned bytes = DWX_GROUPS * 32768u;
+  // A call that has the chip to itself takes the pipelined kernel where the shape allows it (one wave group, two
+  // k-tiles in flight: as fast there as two wave groups, 1.3 % on the one-stream step, and it sums the k-tiles in
+  // the order of gemm_dwx_kernel<1>, so its results are bit-identical to a two-stream call's).  Beside another
+  // branch's kernels it does not pay (two-stream step 2.685 -> 2.695 ms): the one-group kernel stays there.
+  const int depth = groups == 2 ? dwp_depth(A, B, sh) : 0;
+  if (depth_used) *depth_used = depth;
+  if (depth == 2) { hipLaunchKernelGGL((gemm_dwp_kernel<2>), grid, dim3(256), 65536u, st, A, B, sh, epi); return hipGetLastError() == hipSuccess ? 0 : -2; }
   static_assert(bytes <= 65536u, "more dynamic LDS than the default limit: raise hipFuncAttributeMaxDynamicSharedMemorySize first");
   if (groups == 1) hipLaunchKernelGGL((gemm_dwx_kernel<1>), grid, dim3(256), 32768u, st, A, B, sh, epi);
   else hipLaunchKernelGGL((gemm_dwx_kernel<DWX_GROUPS>), grid, dim3(256 * DWX_GROUPS), bytes, st, A, B, sh, epi);
@@ -1085,7 +1267,7 @@ static inline void launch_gemm_al(hipStream_t st, dim3 grid, const Operand& A, b
 template <typename T, class Epi>
 static inline int launch_gemm(hipStream_t st, const Operand& A, bool a_kc, const Operand& B, bool b_kc,
                               const GemmShape& shape, const Epi& epi, bool* used_vec = nullptr, bool* used_narrow = nullptr,
-                              int wave_groups = 0) {
+                              int wave_groups = 0, int* dwp_depth_used = nullptr) {
   GemmShape sh = shape;
   if (sh.M <= 0 || sh.N <= 0 || sh.batch <= 0) return 0;
   if (a_kc ? A.k_stride != 1 : A.x_stride != 1) return -1;
@@ -1112,7 +1294,7 @@ static inline int launch_gemm(hipStream_t st, const Operand& A, bool a_kc, const
     // with wave_groups (1 or 2) wave groups (*used_narrow reports that it was taken)
     if (wave_groups && ve && !a_kc && !b_kc) {
       if (used_narrow) *used_narrow = true;
-      return launch_dwx(st, grid, wave_groups, A, B, sh, epi);
+      return launch_dwx(st, grid, wave_groups, A, B, sh, epi, dwp_depth_used);
     }
   }
   if (ve) launch_gemm_al<T, true, true, Epi>(st, grid, A, a_kc, B, b_kc, sh, epi);

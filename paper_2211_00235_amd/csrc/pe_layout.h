@@ -19,23 +19,35 @@ struct ParamLayout {
   std::vector<pe_param_entry> entries;
 };
 
-inline int pe_check_dims_impl(const pe_dims* d) {
-  if (!d) return PE_ERR_NULL;
-  if (d->s < 1 || d->r < 1) return PE_ERR_DIMS;
-  if (d->dtype != PE_F32 && d->dtype != PE_BF16) return PE_ERR_DIMS;
-  if (d->n_trans < 1 || d->h_msa < 1 || d->h_pair < 1) return PE_ERR_DIMS;
-  if (d->h_msa > 8 || d->h_pair > 8) return PE_ERR_DIMS;                 // bias projection keeps <= 8 heads in registers
+// why != nullptr receives a static string that names the violated limit
+inline int pe_check_dims_impl(const pe_dims* d, const char** why = nullptr) {
+  const char* dummy;
+  if (!why) why = &dummy;
+  *why = "";
+  if (!d) { *why = "dims is NULL"; return PE_ERR_NULL; }
+#define PE_DIM_REQUIRE(cond, text) do { if (!(cond)) { *why = text; return PE_ERR_DIMS; } } while (0)
+  PE_DIM_REQUIRE(d->s >= 1 && d->r >= 1, "s and r must be >= 1");
+  PE_DIM_REQUIRE(d->dtype == PE_F32 || d->dtype == PE_BF16, "dtype must be PE_F32 or PE_BF16");
+  PE_DIM_REQUIRE(d->n_trans >= 1 && d->h_msa >= 1 && d->h_pair >= 1, "n_trans, h_msa and h_pair must be >= 1");
+  // the fused LayerNorm + bias projection keeps at most 8 heads in registers
+  PE_DIM_REQUIRE(d->h_msa <= 8 && d->h_pair <= 8, "h_msa and h_pair must be <= 8");
   int ch[] = {d->c_m, d->c_z, d->h_msa * d->d_msa, d->h_pair * d->d_pair, d->c_tri, d->c_opm};
   for (int c : ch)
-    if (c < 8 || c % 8 || c > 1024) return PE_ERR_DIMS;
-  if (d->c_z > 256) return PE_ERR_DIMS;                                  // fused LayerNorm + bias projection: one chunk per lane
-  if (d->c_tri > 192) return PE_ERR_DIMS;                                // channel-major LayerNorm tile in 64 KB of LDS
-  if ((long long)d->n_trans * d->c_m > 4096 || (long long)d->n_trans * d->c_z > 4096) return PE_ERR_DIMS;
-  if (d->d_msa % 8 || d->d_msa > 32 || d->d_pair % 8 || d->d_pair > 32) return PE_ERR_DIMS;
-  if (d->col_global != 0 && d->col_global != 1) return PE_ERR_DIMS;
-  if (d->variant < PE_VARIANT_PARALLEL || d->variant > PE_VARIANT_MULTIMER) return PE_ERR_DIMS;
-  if (!(d->ln_eps > 0.0f) || !(d->opm_eps > 0.0f)) return PE_ERR_DIMS;
-  if ((long long)d->r * d->r * 4 * d->h_pair * d->d_pair >= (1LL << 40)) return PE_ERR_DIMS;
+    PE_DIM_REQUIRE(c >= 8 && c % 8 == 0 && c <= 1024,
+                   "c_m, c_z, h_msa*d_msa, h_pair*d_pair, c_tri and c_opm must be multiples of 8 in [8, 1024]");
+  PE_DIM_REQUIRE(d->c_z <= 256, "c_z must be <= 256");        // fused LayerNorm + bias projection: one chunk per lane
+  PE_DIM_REQUIRE(d->c_tri <= 192, "c_tri must be <= 192");    // channel-major LayerNorm tile in 64 KB of LDS
+  PE_DIM_REQUIRE((long long)d->n_trans * d->c_m <= 4096 && (long long)d->n_trans * d->c_z <= 4096,
+                 "n_trans*c_m and n_trans*c_z must be <= 4096");
+  PE_DIM_REQUIRE(d->d_msa % 8 == 0 && d->d_msa <= 32 && d->d_pair % 8 == 0 && d->d_pair <= 32,
+                 "d_msa and d_pair must be 8, 16, 24 or 32");
+  PE_DIM_REQUIRE(d->col_global == 0 || d->col_global == 1, "col_global must be 0 or 1");
+  PE_DIM_REQUIRE(d->variant >= PE_VARIANT_PARALLEL && d->variant <= PE_VARIANT_MULTIMER, "variant must be one of PE_VARIANT_*");
+  PE_DIM_REQUIRE(d->ln_eps > 0.0f && d->opm_eps > 0.0f, "ln_eps and opm_eps must be > 0");
+  // GEMM row counts and the attention planes are 32-bit in the kernels
+  PE_DIM_REQUIRE((long long)d->s * d->r < (1LL << 31) && (long long)d->r * d->r < (1LL << 31), "s*r and r*r must be < 2^31");
+  PE_DIM_REQUIRE((long long)d->r * d->r * 4 * d->h_pair * d->d_pair < (1LL << 40), "r*r*4*h_pair*d_pair must be < 2^40");
+#undef PE_DIM_REQUIRE
   return PE_OK;
 }
 

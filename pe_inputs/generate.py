@@ -26,6 +26,10 @@ def res_mask_for(recipe, s, r, rng):
         if arg > 0:
             res[-int(arg):] = 0.0
         return np.tile(res, (s, 1)), np.outer(res, res)
+    if kind == "first_residues":
+        res = np.ones(r)
+        res[:int(arg)] = 0.0
+        return np.tile(res, (s, 1)), np.outer(res, res)
     if kind == "random_residues":
         n = int(round(arg * r))
         res = np.ones(r)

@@ -1,14 +1,23 @@
 """Parity check of the HIP path against the float64 oracle for one seeded case.
 
-ReLU decisions.  The transition's ReLU turns a floating-point pre-activation into an
-on/off decision.  A pre-activation whose magnitude is below the implementation's own
-rounding error of it (bf16 operands in the contraction, bf16 residual stream upstream)
-has no unique decision at that precision: both are correct, and a flipped decision
-changes the gradient by O(1) at that element.  The check therefore (1) requires the HIP
-path's decisions to equal sign(a_oracle) wherever |a_oracle| exceeds a band, (2) takes the
-HIP path's decision inside the band as one of the valid choices, and (3) compares every
-output and gradient with the oracle evaluated under exactly those decisions.  The band
-and the fraction of elements inside it are reported and bounded.
+Three comparisons, all element by element:
+
+  A. Forward against the PLAIN oracle (its own ReLU decisions, nothing taken from the HIP path): block
+     outputs and every saved residual-stream value, at the tolerance.
+  B. The transition's hidden activation: the HIP path's saved `h` against relu(a_oracle) wherever both are
+     on, at the tolerance.  The error of the pre-activation itself, E, is measured where it decides
+     something: over the elements that are on in both with |a_oracle| <= 0.25 rms(a) (there the bf16
+     rounding of the stored h is below 5e-4 rms(a), so h - a_oracle is the pre-activation's error).
+  C. Backward against the oracle evaluated under the HIP path's ReLU decisions, after those decisions have
+     been shown valid: a decision may differ from sign(a_oracle) only where |a_oracle| <= 1.5 E (for an
+     element that is on in the HIP path and off in the oracle the stored h gives the error directly:
+     h - a_oracle <= 1.5 E).  E itself must stay below PREACT_ERR_MAX x rms(a), the size that a CPU
+     emulation of the bf16 storage points gives (tests/test_bf16_relu_band.py, which also shows why the
+     comparison cannot be made across different decisions: a flipped element changes its gradient by O(1)).
+     With `plain_backward=True` the gradients are also compared with the plain oracle and reported
+     (`plain.*` entries); callers bound them separately.
+
+Everything the check takes from the HIP path is the boolean `h > 0` at elements inside the measured band.
 """
 import numpy as np
 
@@ -17,59 +26,103 @@ from oracle import evoformer as ev
 from tests.gpu_util import BlockRun, to_np, rel_err, param_errors
 
 TOL = {pe.PE_F32: 1e-4, pe.PE_BF16: 2e-2}
-# band for ambiguous ReLU decisions, as a fraction of the rms pre-activation
-BAND = {pe.PE_F32: 2e-5, pe.PE_BF16: 6e-2}
+# upper bound of the pre-activation error max|a_path - a_oracle| in units of rms(a)
+PREACT_ERR_MAX = {pe.PE_F32: 1e-4, pe.PE_BF16: 4e-2}
+BAND_SAFETY = 1.5
+SMALL = 0.25
+# The metric divides a tensor's largest error by its largest reference magnitude.  For a tensor of few entries that
+# normaliser is itself a small-sample maximum: at the same per-element error the 1-in-100 worst ratio over tensors of
+# 16 entries is 1.77 times that of tensors of 65536 entries, 1.5 times at 33 entries, 1.23 times at 257
+# (tests/test_bf16_relu_band.py::test_max_normalised_metric_by_tensor_size pins these by Monte Carlo).  A block has
+# about a hundred parameter tensors, so that tail is what a test sees.  The benchmark configurations are held to TOL
+# for every tensor; test shapes with 16..64 channels, whose vectors have 16..64 entries, use TOL x size_factor(entries).
+SIZE_FACTORS = ((32, 1.85), (256, 1.5), (4096, 1.25))
+
+
+def size_factor(n):
+    for limit, f in SIZE_FACTORS:
+        if n <= limit:
+            return f
+    return 1.0
+
+
+def worst_scaled(errs, sizes):
+    """Largest error after division by its tensor's size factor, and the entry that has it."""
+    scaled = {k: v / size_factor(sizes.get(k, 1 << 40)) for k, v in errs.items()}
+    worst = max(scaled, key=scaled.get)
+    return worst, scaled[worst]
 
 
 def relu_decisions(dims, run, inter):
-    """Merge oracle decisions (outside the band) with the HIP path's (inside)."""
-    out, stats = {}, {}
+    """Validates the HIP path's ReLU decisions against the oracle's pre-activations; returns the
+    decisions to evaluate the oracle under, per-transition statistics and the h errors."""
+    out, stats, errs = {}, {}, {}
     for key, name in (("mtrans", "mtrans.h"), ("ptrans", "ptrans.h")):
         a = inter[key + "_pre"]
         h = run.ctx_entry(name).reshape(a.shape)
-        band = BAND[dims["dtype"]] * np.sqrt(np.mean(a * a))
-        inside = np.abs(a) <= band
-        gpu_on = h > 0
-        wrong = (~inside) & (gpu_on != (a > 0))
-        stats[key] = dict(frac_inside=float(inside.mean()), wrong_outside=int(wrong.sum()),
-                          flips_inside=int((inside & (gpu_on != (a > 0))).sum()))
-        out[key] = np.where(inside, gpu_on, a > 0)
-    return out, stats
+        rms = float(np.sqrt(np.mean(a * a)))
+        gpu_on, or_on = h > 0, a > 0
+        both = gpu_on & or_on
+        d = np.abs(h - a)
+        errs["ctx." + name] = float(d[both].max() / np.max(np.abs(a))) if both.any() else 0.0
+        small = both & (np.abs(a) <= SMALL * rms)
+        E = float(d[small].max()) if small.any() else 0.0
+        # floor: a tenth of the bound, for tensors too small to hold a sample of small pre-activations
+        band = max(BAND_SAFETY * E, 0.1 * PREACT_ERR_MAX[dims["dtype"]] * rms)
+        flips = gpu_on != or_on
+        # a flip is explained by the pre-activation's error only inside the band
+        viol = flips & (np.where(gpu_on, h - a, a) > band)
+        stats[key] = dict(preact_err=E / rms if rms > 0 else 0.0, frac_inside=float((np.abs(a) <= band).mean()),
+                          flips_inside=int((flips & ~viol).sum()), flips_outside=int(viol.sum()))
+        out[key] = gpu_on
+    return out, stats, errs
 
 
-def check_case(dims, table, inp, two_streams=True, use_ctx=True, verbose=False):
+def check_case(dims, table, inp, two_streams=True, use_ctx=True, verbose=False, plain_backward=False):
     tol = TOL[dims["dtype"]]
     args = (dims, inp["params"], inp["msa"], inp["pair"], inp["msa_mask"], inp["pair_mask"])
-    _, _, _, inter0 = ev.block_fwd(*args, want_cache=False)
+    m0, z0, cache0, inter0 = ev.block_fwd(*args, want_cache=plain_backward)
     run = BlockRun(dims, inp, two_streams=two_streams)
     run.fwd(use_ctx=True)
     run.sync()
-    on, stats = relu_decisions(dims, run, inter0)
-    for k, st in stats.items():
-        assert st["wrong_outside"] == 0, (k, st)
-        assert st["frac_inside"] < 0.08, (k, st)
-    m, z, cache, inter = ev.block_fwd(*args, relu_on=on)
-    dm, dz, g, _ = ev.block_bwd(dims, cache, inp["d_msa_out"], inp["d_pair_out"])
     errs = {}
-    # saved residual-stream values; with the outer product mean in front of the pair stack (orderings
-    # (a) and (b) of Figure 1) z0 = pair input + outer product mean is saved and z5 is the output itself
+    # A. forward, plain oracle.  With the outer product mean in front of the pair stack (orderings (a) and
+    # (b) of Figure 1) z0 = pair input + outer product mean is saved and z5 is the output itself
     keys = ("m1", "m2", "m3", "z1", "z2", "z3", "z4") + (("z0",) if dims.get("variant", 0) else ("z5",))
     for k in keys:
-        errs["ctx." + k] = rel_err(run.ctx_entry(k).reshape(inter[k].shape), inter[k])
-    errs["msa_out"] = rel_err(to_np(run.msa_out), m)
-    errs["pair_out"] = rel_err(to_np(run.pair_out), z)
+        errs["ctx." + k] = rel_err(run.ctx_entry(k).reshape(inter0[k].shape), inter0[k])
+    errs["msa_out"] = rel_err(to_np(run.msa_out), m0)
+    errs["pair_out"] = rel_err(to_np(run.pair_out), z0)
+    # B. hidden activations and the validity of the decisions
+    on, stats, herrs = relu_decisions(dims, run, inter0)
+    errs.update(herrs)
+    for k, st in list(stats.items()):
+        assert st["flips_outside"] == 0, (k, st)
+        assert st["preact_err"] <= PREACT_ERR_MAX[dims["dtype"]], (k, st)
+        assert st["frac_inside"] < 0.05, (k, st)
+    # C. backward under the validated decisions
+    _, _, cache, _ = ev.block_fwd(*args, relu_on=on)
+    dm, dz, g, _ = ev.block_bwd(dims, cache, inp["d_msa_out"], inp["d_pair_out"])
     if not use_ctx:
         run.ctx.zero_()
         run.sync()
     run.bwd(use_ctx=use_ctx)
     run.sync()
-    errs["d_msa_in"] = rel_err(to_np(run.d_msa_in), dm)
-    errs["d_pair_in"] = rel_err(to_np(run.d_pair_in), dz)
-    perr = param_errors(to_np(run.d_params), g, table)
-    errs.update({"d_params." + k: v for k, v in perr.items()})
+    got = dict(d_msa_in=to_np(run.d_msa_in), d_pair_in=to_np(run.d_pair_in), d_params=to_np(run.d_params))
+    errs["d_msa_in"] = rel_err(got["d_msa_in"], dm)
+    errs["d_pair_in"] = rel_err(got["d_pair_in"], dz)
+    errs.update({"d_params." + k: v for k, v in param_errors(got["d_params"], g, table).items()})
+    stats["sizes"] = {"d_params." + e["name"]: int(np.prod(e["shape"])) for e in table}
     worst = max(errs, key=errs.get)
+    plain = {}
+    if plain_backward:
+        dm0, dz0, g0, _ = ev.block_bwd(dims, cache0, inp["d_msa_out"], inp["d_pair_out"])
+        plain["plain.d_msa_in"] = rel_err(got["d_msa_in"], dm0)
+        plain["plain.d_pair_in"] = rel_err(got["d_pair_in"], dz0)
+        plain.update({"plain.d_params." + k: v for k, v in param_errors(got["d_params"], g0, table).items()})
+        stats["plain"] = plain
     if verbose:
-        for k, v in errs.items():
-            print("  %-26s %.3e" % (k, v))
-        print("  relu:", stats)
+        for k, v in list(errs.items()) + list(plain.items()):
+            print("  %-32s %.3e" % (k, v))
+        print("  relu:", {k: v for k, v in stats.items() if k not in ("plain", "sizes")})
     return errs, worst, tol, stats

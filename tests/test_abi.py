@@ -78,3 +78,28 @@ def test_null_and_error_strings(L):
     for code in range(0, -7, -1):
         assert len(pe.strerror(code)) > 0
     assert pe.strerror(-3) == "workspace too small"
+
+
+def test_dims_error_names_the_violated_limit(L):
+    """Every limit that pe_check_dims enforces is reported in words (the header lists the same limits)."""
+    d = dict(CONFIGS["af2_initial"][0])
+    assert pe.dims_error(d) == ""
+    for key, bad, word in (("c_m", 250, "multiples of 8"), ("d_msa", 64, "d_msa"), ("d_pair", 4, "d_pair"),
+                           ("c_z", 512, "c_z must be <= 256"), ("c_tri", 200, "c_tri"), ("h_msa", 16, "h_msa"),
+                           ("n_trans", 32, "n_trans"), ("variant", 3, "variant"), ("dtype", 7, "dtype"),
+                           ("s", 0, "s and r")):
+        dd = dict(d)
+        dd[key] = bad
+        assert pe.check_dims(dd) == -2, key
+        assert word in pe.dims_error(dd), (key, pe.dims_error(dd))
+    big = dict(d, s=70000, r=40000)          # s*r beyond the 32-bit row counts of the kernels
+    assert pe.check_dims(big) == -2 and "2^31" in pe.dims_error(big)
+    g = dict(CONFIGS["extra_msa"][0])
+    assert pe.check_dims(dict(g, d_msa=16)) == -2 and "global column attention" in pe.dims_error(dict(g, d_msa=16))
+    hdr = open(os.path.join(ROOT, "include", "pe.h")).read()
+    for text in ("c_z <= 256", "c_tri <= 192", "n_trans*c_m <= 4096", "{8, 16, 24, 32}", "s*r < 2^31"):
+        assert text in hdr, text
+
+
+def test_static_scratch_size_is_exported(L):
+    assert pe.static_scratch_bytes() == 32 << 20

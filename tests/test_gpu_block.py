@@ -4,7 +4,7 @@ import pytest
 
 from oracle.params import param_table
 from pe_inputs import make_inputs, dims_for
-from tests.parity import check_case
+from tests.parity import check_case, worst_scaled
 
 pytestmark = pytest.mark.gpu
 
@@ -28,16 +28,18 @@ def test_tiny_fp32():
     _assert(*check_case(dims, table, inp)[:3])
 
 
-# bf16 runs of the small test shapes (16..64 channels, 16..150 residues): every reduction is one to
-# two orders of magnitude shorter than at the benchmark shapes, so the bf16 rounding noise of the
-# chain averages out less; they get 3e-2 instead of the 2e-2 that binds the benchmark configs.
-SMALL_BF16_TOL = 3e-2
+def _assert_small(errs, tol, stats):
+    """Small test shapes (16..64 channels): the tolerance of the path, times the size factor of the metric for
+    tensors of few entries (tests/parity.py: SIZE_FACTORS; 1.0 above 4096 entries, so outputs, cotangents and the
+    larger weights are held to the plain tolerance here too).  The benchmark configurations use _assert."""
+    worst, val = worst_scaled(errs, stats["sizes"])
+    assert val <= tol, "worst %s = %.3e (after its size factor %.3e) > %.1e" % (worst, errs[worst], val, tol)
 
 
 def test_tiny_bf16():
     dims, table, inp = _case("tiny", dtype=1)
-    errs, worst, tol, _ = check_case(dims, table, inp)
-    _assert(errs, worst, SMALL_BF16_TOL)
+    errs, worst, tol, stats = check_case(dims, table, inp)
+    _assert_small(errs, tol, stats)
 
 
 @pytest.mark.parametrize("dtype", [0, 1])
@@ -48,8 +50,11 @@ def test_ragged_shapes(dtype):
                              d_pair=8, c_tri=24, c_opm=16, n_trans=2)
     table, n = param_table(dims)
     inp = make_inputs(dims, table, n, ("random_residues", 0.07), 5)
-    errs, worst, tol, _ = check_case(dims, table, inp)
-    _assert(errs, worst, SMALL_BF16_TOL if dtype == 1 else tol)
+    errs, worst, tol, stats = check_case(dims, table, inp)
+    if dtype == 1:
+        _assert_small(errs, tol, stats)
+    else:
+        _assert(errs, worst, tol)
 
 
 @pytest.mark.parametrize("dtype", [0, 1])
@@ -60,8 +65,11 @@ def test_head_dim_24(dtype):
                              d_pair=24, c_tri=16, c_opm=8, n_trans=2)
     table, n = param_table(dims)
     inp = make_inputs(dims, table, n, ("random_residues", 0.1), 9)
-    errs, worst, tol, _ = check_case(dims, table, inp)
-    _assert(errs, worst, SMALL_BF16_TOL if dtype == 1 else tol)
+    errs, worst, tol, stats = check_case(dims, table, inp)
+    if dtype == 1:
+        _assert_small(errs, tol, stats)
+    else:
+        _assert(errs, worst, tol)
 
 
 @pytest.mark.parametrize("use_ctx", [True, False])
@@ -74,8 +82,11 @@ def test_block_orderings_small(variant, dtype, use_ctx):
                              d_pair=8, c_tri=24, c_opm=16, n_trans=2, variant=variant)
     table, n = param_table(dims)
     inp = make_inputs(dims, table, n, ("random_residues", 0.07), 5)
-    errs, worst, tol, _ = check_case(dims, table, inp, use_ctx=use_ctx)
-    _assert(errs, worst, SMALL_BF16_TOL if dtype == 1 else tol)
+    errs, worst, tol, stats = check_case(dims, table, inp, use_ctx=use_ctx)
+    if dtype == 1:
+        _assert_small(errs, tol, stats)
+    else:
+        _assert(errs, worst, tol)
 
 
 @pytest.mark.parametrize("variant", [1, 2])
@@ -85,10 +96,27 @@ def test_block_orderings_af2_initial_bf16(variant):
     _assert(*check_case(dims, table, inp)[:3])
 
 
+# Gradients against the PLAIN oracle (its own ReLU decisions everywhere): the few decisions that differ inside
+# the pre-activation's error band change their elements' gradients by O(1), so this comparison is outside the
+# tolerance by construction (tests/test_bf16_relu_band.py shows 1e-1 on a transition's input cotangent from the
+# flips alone).  It is bounded all the same, so that the unmatched figure is pinned: measured 4e-2..1.1e-1.
+PLAIN_BF16_BOUND = 0.2
+
+
+def _assert_plain(stats):
+    plain = stats["plain"]
+    worst = max(plain, key=plain.get)
+    print("unmatched ReLU decisions: worst %s = %.3e" % (worst, plain[worst]))
+    assert plain[worst] <= PLAIN_BF16_BOUND, (worst, plain[worst])
+
+
 def test_af2_initial_bf16():
-    """Config 2: the benchmark workload at full size, bf16 path, every output element."""
+    """Config 2: the benchmark workload at full size, bf16 path, every output element: forward against the
+    plain oracle, backward under validated ReLU decisions, and the plain-oracle backward bounded."""
     dims, table, inp = _case("af2_initial")
-    _assert(*check_case(dims, table, inp)[:3])
+    errs, worst, tol, stats = check_case(dims, table, inp, plain_backward=True)
+    _assert(errs, worst, tol)
+    _assert_plain(stats)
 
 
 def test_af2_initial_bf16_one_stream():
@@ -104,8 +132,8 @@ def test_ragged_shapes_one_stream_bf16():
                              d_pair=8, c_tri=24, c_opm=16, n_trans=2)
     table, n = param_table(dims)
     inp = make_inputs(dims, table, n, ("random_residues", 0.07), 5)
-    errs, worst, tol, _ = check_case(dims, table, inp, two_streams=False)
-    _assert(errs, worst, SMALL_BF16_TOL)
+    errs, worst, tol, stats = check_case(dims, table, inp, two_streams=False)
+    _assert_small(errs, tol, stats)
 
 
 @pytest.mark.parametrize("two_streams", [True, False])
@@ -169,20 +197,76 @@ def test_recompute_and_single_stream_match():
 
 
 @pytest.mark.slow
-def test_af2_finetune_bf16():
-    """Config 4: fine-tuning shape (s=512, r=384), bf16 path, every output element."""
+@pytest.mark.parametrize("use_ctx", [True, False])
+def test_af2_finetune_bf16(use_ctx):
+    """Config 4: fine-tuning shape (s=512, r=384), bf16 path, every output element; with the saved
+    activations and with ctx == NULL (the backward call recomputes the forward: the block at full recompute)."""
     dims, table, inp = _case("af2_finetune")
-    _assert(*check_case(dims, table, inp)[:3])
+    _assert(*check_case(dims, table, inp, use_ctx=use_ctx)[:3])
 
 
-def test_masked_edge_cases():
-    """All MSA rows of one residue column masked except one, a fully masked residue (column
-    attention sees no valid key there), and an all-ones mask."""
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_masked_edge_cases(dtype):
+    """An all-ones mask, and all residues masked but one (column attention sees no valid key at a masked
+    residue; row and triangle attention have a single valid key)."""
     for recipe in (("none", 0), ("last_residues", 15)):
-        dims, table, inp = _case("tiny", dtype=0)
+        dims, table, inp = _case("tiny", dtype=dtype)
         table, n = param_table(dims)
         inp = make_inputs(dims, table, n, recipe, 21)
-        _assert(*check_case(dims, table, inp)[:3])
+        errs, worst, tol, stats = check_case(dims, table, inp)
+        if dtype == 1:
+            _assert_small(errs, tol, stats)
+        else:
+            _assert(errs, worst, tol)
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_first_key_tile_fully_masked(dtype):
+    """The first 70 of 150 residues masked: the first 64-key tile of every row / triangle attention holds no
+    valid key (the online softmax starts from an empty tile and meets its first finite logit later), queries
+    at masked residues included; column attention has whole columns without a valid key."""
+    dims, table, inp = _case("tiny", dtype=dtype, s=37, r=150, c_m=64, c_z=32, h_msa=2, d_msa=16, h_pair=4,
+                             d_pair=8, c_tri=24, c_opm=16, n_trans=2)
+    table, n = param_table(dims)
+    inp = make_inputs(dims, table, n, ("first_residues", 70), 61)
+    errs, worst, tol, stats = check_case(dims, table, inp)
+    if dtype == 1:
+        _assert_small(errs, tol, stats)
+    else:
+        _assert(errs, worst, tol)
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_large_magnitude_inputs(dtype):
+    """Inputs drawn 8 times wider (N(0, 64)): LayerNorm inputs of large magnitude and, through the un-normalised
+    residual paths, logits whose running maximum moves by tens between key tiles (the online-softmax rescale);
+    s = 70 and r = 150 give two and three key tiles."""
+    dims, table, inp = _case("tiny", dtype=dtype, s=70, r=150, c_m=64, c_z=32, h_msa=2, d_msa=16, h_pair=4,
+                             d_pair=8, c_tri=24, c_opm=16, n_trans=2)
+    table, n = param_table(dims)
+    inp = make_inputs(dims, table, n, ("random_residues", 0.07), 62, scale=8.0)
+    errs, worst, tol, stats = check_case(dims, table, inp)
+    if dtype == 1:
+        _assert_small(errs, tol, stats)
+    else:
+        _assert(errs, worst, tol)
+
+
+def test_peaked_softmax_fp32():
+    """Query / key weights scaled by 3: logits nine times wider (tens in the base-2 domain) with a different
+    winner per key tile, so the running maximum of the online softmax jumps by many units from tile to tile and
+    the rescale factor of the earlier tiles gets tiny (fp32 path: the comparison is sharp there)."""
+    dims, table, inp = _case("tiny", dtype=0, s=70, r=150, c_m=64, c_z=32, h_msa=2, d_msa=16, h_pair=4,
+                             d_pair=8, c_tri=24, c_opm=16, n_trans=2)
+    table, n = param_table(dims)
+    inp = make_inputs(dims, table, n, ("random_residues", 0.07), 63)
+    for e in table:
+        if e["name"].endswith((".w_q", ".w_k")):
+            k = int(np.prod(e["shape"]))
+            inp["params"][e["offset"]:e["offset"] + k] *= 3.0
+    inp["params"] = inp["params"].astype(np.float32).astype(np.float64)
+    errs, worst, tol, _ = check_case(dims, table, inp)
+    _assert(errs, worst, tol)
 
 
 @pytest.mark.parametrize("s,r", [(1, 1), (1, 9), (9, 1), (2, 130)])
@@ -204,12 +288,22 @@ def test_bad_arguments_return_errors():
     with pytest.raises(pe.PEError, match="aliases"):
         pe.block_fwd(run.h, dims, run.msa, run.pair, run.msa_mask, run.pair_mask, run.params, run.msa, run.pair_out,
                      run.ctx, run.ws)
+    # buffers the call writes may not overlap any other buffer: d_params on params, ctx inside the workspace
+    with pytest.raises(pe.PEError, match="aliases"):
+        pe.block_bwd(run.h, dims, run.msa, run.pair, run.msa_mask, run.pair_mask, run.params, run.d_msa_out,
+                     run.d_pair_out, run.d_msa_in, run.d_pair_in, run.params, run.ctx, run.ws)
+    with pytest.raises(pe.PEError, match="aliases"):
+        pe.block_fwd(run.h, dims, run.msa, run.pair, run.msa_mask, run.pair_mask, run.params, run.msa_out,
+                     run.pair_out, run.ws, run.ws)
+    with pytest.raises(pe.PEError, match="aliases"):
+        pe.block_bwd(run.h, dims, run.msa, run.pair, run.msa_mask, run.pair_mask, run.params, run.d_msa_out,
+                     run.d_pair_out, run.d_msa_in, run.d_pair_in, run.d_params, run.ctx, run.ctx)
     small = torch.empty(4096, dtype=torch.uint8, device="cuda")
     with pytest.raises(pe.PEError, match="workspace too small"):
         pe.block_fwd(run.h, dims, run.msa, run.pair, run.msa_mask, run.pair_mask, run.params, run.msa_out,
                      run.pair_out, run.ctx, small)
     bad = dict(dims, c_m=30)
-    with pytest.raises(pe.PEError, match="unsupported dims"):
+    with pytest.raises(pe.PEError, match="unsupported dims.*multiples of 8"):
         pe.block_fwd(run.h, bad, run.msa, run.pair, run.msa_mask, run.pair_mask, run.params, run.msa_out,
                      run.pair_out, run.ctx, run.ws)
 
@@ -220,8 +314,11 @@ def test_global_column_attention_small(dtype):
     dims, table, inp = _case("tiny", dtype=dtype, s=70, r=45, c_m=32, h_msa=4, d_msa=8, col_global=1)
     table, n = param_table(dims)
     inp = make_inputs(dims, table, n, ("random_rows", 0.1), 31)
-    errs, worst, tol, _ = check_case(dims, table, inp)
-    _assert(errs, worst, SMALL_BF16_TOL if dtype == 1 else tol)
+    errs, worst, tol, stats = check_case(dims, table, inp)
+    if dtype == 1:
+        _assert_small(errs, tol, stats)
+    else:
+        _assert(errs, worst, tol)
 
 
 @pytest.mark.slow
@@ -229,6 +326,20 @@ def test_extra_msa_bf16():
     """Config 3: extra-MSA-stack block (s=1024, r=256, c_m=64, global column attention), bf16."""
     dims, table, inp = _case("extra_msa")
     _assert(*check_case(dims, table, inp)[:3])
+
+
+@pytest.mark.slow
+@pytest.mark.parametrize("use_ctx", [True, False])
+def test_extra_msa_finetune_depth_against_oracle(use_ctx):
+    """Extra-MSA block at the fine-tuning depth of Table 1 (N_extra_seq = 5120) against the float64 oracle,
+    element by element, at a residue count the oracle can hold (r = 64): every reduction over the sequence
+    axis (outer product mean over 5120 rows, the mean query, keys and values of global column attention, the
+    d = 8 row attention at a batch of 5120) runs at its full length; 5 % of the rows masked."""
+    dims, mask, _ = dims_for("extra_msa_finetune")
+    dims.update(r=64)
+    table, n = param_table(dims)
+    inp = make_inputs(dims, table, n, mask, 64)
+    _assert(*check_case(dims, table, inp, use_ctx=use_ctx)[:3])
 
 
 @pytest.mark.slow

@@ -54,7 +54,9 @@ def test_stack_fp32_matches_oracle():
         for e in table:
             k = int(np.prod(e["shape"]))
             sl = slice(b * n + e["offset"], b * n + e["offset"] + k)
-            den = max(np.max(np.abs(g[sl])), 1e-3 * np.max(np.abs(g)))
+            den = np.max(np.abs(g[sl]))
+            if e["name"] == "row.ln_z.b":      # exactly zero gradient (a per-head constant cancels in the softmax)
+                den = np.max(np.abs(g))
             assert np.max(np.abs(gg[sl] - g[sl])) / den < 1e-4, (b, e["name"])
 
 
@@ -260,15 +262,18 @@ def test_stack_argument_errors():
                          torch.zeros(n, device="cuda"), small)
 
 
-def test_stack_extra_then_main_fp32_matches_oracle():
-    """One extra-MSA block (global column attention, its own s and c_m) followed by one main block:
-    the pair representation chains through both, the extra-MSA representation is dropped."""
+@pytest.mark.parametrize("n_extra,n_main", [(1, 1), (2, 2), (3, 1)])
+def test_stack_extra_then_main_fp32_matches_oracle(n_extra, n_main):
+    """Extra-MSA blocks (global column attention, their own s and c_m) followed by main blocks: the pair
+    representation chains through all of them, the extra-MSA representation is dropped.  Odd and even counts
+    of extra blocks (the cotangent of the dropped representation starts as zero in the ping-pong slot that the
+    last extra block does not write).  Every output, input cotangent and parameter-gradient entry at 1e-4."""
     dims_m, mask, seed = dims_for("tiny")
     dims_e = dict(dims_m, s=24, c_m=16, col_global=1)
     te, ne = param_table(dims_e)
     tm, nm = param_table(dims_m)
-    ie = make_inputs(dims_e, te, ne, ("random_rows", 0.1), 41)
-    im = make_inputs(dims_m, tm, nm, mask, 42)
+    ie = make_inputs(dims_e, te, ne, ("random_rows", 0.1), 41, n_blocks=n_extra)
+    im = make_inputs(dims_m, tm, nm, mask, 42, n_blocks=n_main)
     params = np.concatenate([ie["params"], im["params"]])
     f32 = torch.float32
     h = pe.Handle()
@@ -279,21 +284,41 @@ def test_stack_extra_then_main_fp32_matches_oracle():
     dmo, dzo = dev(im["d_msa_out"]), dev(im["d_pair_out"])
     mo, zo, dex, dmi, dzi = (torch.empty_like(t) for t in (msa, pair, ex, msa, pair))
     dpar = torch.zeros_like(par)
-    ws = torch.empty(pe.stack_workspace_bytes(1, dims_e, 1, dims_m), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(pe.stack_workspace_bytes(n_extra, dims_e, n_main, dims_m), dtype=torch.uint8, device="cuda")
+    ws.fill_(0x7F)     # stale bytes (large finite values) wherever the call reads something it has not written
     sm, sp = torch.cuda.Stream(), torch.cuda.Stream()
     torch.cuda.synchronize()
-    pe.stack_fwd_bwd(h, 1, dims_e, 1, dims_m, ex, msa, pair, exm, mm, pm, par, dmo, dzo, mo, zo, dex, dmi, dzi, dpar,
-                     ws, sm, sp)
+    pe.stack_fwd_bwd(h, n_extra, dims_e, n_main, dims_m, ex, msa, pair, exm, mm, pm, par, dmo, dzo, mo, zo, dex, dmi,
+                     dzi, dpar, ws, sm, sp)
     torch.cuda.synchronize()
-    r = ev.stack_fwd_bwd(1, dims_e, 1, dims_m, params, ie["msa"], im["msa"], im["pair"], ie["msa_mask"],
+    r = ev.stack_fwd_bwd(n_extra, dims_e, n_main, dims_m, params, ie["msa"], im["msa"], im["pair"], ie["msa_mask"],
                          im["msa_mask"], im["pair_mask"], im["d_msa_out"], im["d_pair_out"])
     msa_o, pair_o, de, dm, dz, g = r
     for got, ref in ((mo, msa_o), (zo, pair_o), (dex, de), (dmi, dm), (dzi, dz)):
         assert rel_err(to_np(got), ref) < 1e-4
     gg = to_np(dpar)
-    for off, table in ((0, te), (ne, tm)):
+    blocks = [(b * ne, te) for b in range(n_extra)] + [(n_extra * ne + b * nm, tm) for b in range(n_main)]
+    for off, table in blocks:
         for e in table:
             k = int(np.prod(e["shape"]))
             sl = slice(off + e["offset"], off + e["offset"] + k)
-            den = max(np.max(np.abs(g[sl])), 1e-3 * np.max(np.abs(g)))
-            assert np.max(np.abs(gg[sl] - g[sl])) / den < 1e-4, e["name"]
+            den = np.max(np.abs(g[sl]))
+            if e["name"] == "row.ln_z.b":      # exactly zero gradient (a per-head constant cancels in the softmax)
+                den = np.max(np.abs(g))
+            assert np.max(np.abs(gg[sl] - g[sl])) / den < 1e-4, (off, e["name"])
+
+
+def test_stack_needs_both_branches():
+    """A block with one branch switched off leaves an output unwritten that the next block would read."""
+    dims, mask, seed = dims_for("tiny")
+    table, n, inp = _stack_inputs(dims, 1, 1, mask)
+    h = pe.Handle()
+    h.set_option(1, 1)
+    f32 = torch.float32
+    m, t = to_dev(inp["msa"], f32), to_dev(inp["pair"], f32)
+    ws = torch.empty(pe.stack_workspace_bytes(0, None, 1, dims), dtype=torch.uint8, device="cuda")
+    with pytest.raises(pe.PEError, match="both branches"):
+        pe.stack_fwd_bwd(h, 0, None, 1, dims, None, m, t, None, to_dev(inp["msa_mask"], f32),
+                         to_dev(inp["pair_mask"], f32), to_dev(inp["params"], f32), m.clone(), t.clone(),
+                         torch.empty_like(m), torch.empty_like(t), None, torch.empty_like(m), torch.empty_like(t),
+                         torch.zeros(n, device="cuda"), ws)
