@@ -62,11 +62,24 @@ def bench_trunk(args, torch, pe):
     h = pe.Handle()
     if keep:
         h.set_option(5, 1)      # PE_OPT_STACK_KEEP_CTX: 288 GB hold every block's activations
+    if args.no_overlap:
+        h.set_option(6, 0)      # PE_OPT_STACK_OVERLAP off: no kernels of the next block before the current one's join
     sm, sp = torch.cuda.Stream(), torch.cuda.Stream()
 
-    def step():
+    def eager():
         pe.stack_fwd_bwd(h, ne, de, nm, dm, ex, msa, pair, exm, mm, pm, par, dmo, dzo, mo, zo, dex, dmi, dzi, dpar,
                          ws, sm, sp)
+    step = eager
+    if args.graph:              # the whole trunk (about 9000 launches on two streams) as one HIP graph
+        eager()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=sm):
+            eager()
+
+        def step():
+            with torch.cuda.stream(sm):
+                graph.replay()
     steps, warm = max(1, min(args.steps, 5)), max(1, min(args.warmup, 2))
     for _ in range(warm):
         step()
@@ -96,6 +109,8 @@ def bench_trunk(args, torch, pe):
         "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": ms, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "trunk", "n_extra": ne, "n_main": nm, "streams": 2,
+                   "launch": "hip graph replay" if args.graph else "eager",
+                   "cross_block_overlap": bool(keep and not args.no_overlap),
                    "recompute": "none (every block's activations kept)" if keep else "per block",
                    "workspace_gib": round(ws.numel() / 2 ** 30, 1)},
         "counted_tflops": flops / (ms * 1e-3) / 1e12,
@@ -104,12 +119,13 @@ def bench_trunk(args, torch, pe):
         "cpu_baseline": cpu}))
 
 
-def profiled_traffic(kernel):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE and
-    WRITE_SIZE runs, scaled by what a plain copy reads on the same counters); None when the
-    summary is not shipped with the tree or does not list the kernel."""
+def profiled_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload
+    (FETCH_SIZE and WRITE_SIZE runs, scaled by what a plain copy reads on the same counters).  None
+    when there is no summary for the workload or it does not list exactly this kernel: a summary
+    taken before a kernel was renamed or replaced yields no figure instead of a stale one."""
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
-                        "block_fwd_bwd_af2_initial_hbm_traffic.md")
+                        "block_fwd_bwd_%s_hbm_traffic.md" % workload)
     try:
         for line in open(path):
             f = line.split()
@@ -133,6 +149,9 @@ def main():
                          "pass (the paper's memory-saving setting) instead of keeping every block's activations")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (both streams) into a HIP graph once and time graph replays")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="trunk workload: do not start the next block's row-attention LayerNorm and projections "
+                         "before the current block's pair branch has finished")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="also print the per-launch-label timing table to stderr")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -271,6 +290,8 @@ def main():
         k["launches"] += e["launches"] // 5
         k["flops"] += e["flops"] / 5
         k["bytes"] += e["bytes"] / 5
+    # The roofline entry is ONE kernel symbol (for the GEMMs: one instantiation, feature mask included): the
+    # one with the largest total time in the timed configuration (two streams).
     dom_name = max(two, key=lambda k: two[k]["ms"])
     dom = two[dom_name]
     # roofline model: the kernel's algorithmic intensity against the ridge (peak flops / peak bandwidth)
@@ -280,24 +301,37 @@ def main():
     tflops = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
     gbs = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
     if dom["flops"] > 0 and intensity >= ridge:
-        roof = dict(bound="mfma", achieved=tflops, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=tflops / PEAK_BF16_TFLOPS,
-                    traffic=None)
+        roof = dict(bound="mfma", achieved=tflops, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=tflops / PEAK_BF16_TFLOPS)
     else:
-        roof = dict(bound="hbm", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s", frac=gbs / PEAK_HBM_GBS, traffic=None)
-    roof.update(flop_per_byte=intensity, ridge_flop_per_byte=ridge, tflops=tflops, mfma_peak_frac=tflops / PEAK_BF16_TFLOPS)
-    roof["traffic"] = profiled_traffic(dom_name) if args.workload == "af2_initial" else None
-    if dom_name in by_kernel and by_kernel[dom_name]["launches"]:
-        roof["avg_launch_us_alone"] = 1e3 * by_kernel[dom_name]["ms"] / by_kernel[dom_name]["launches"]
-    roof.update(kernel=dom_name, launches_per_step=dom["launches"], avg_launch_us=1e3 * dom["ms"] / max(dom["launches"], 1),
-                kernel_ms_per_step=dom["ms"])
+        roof = dict(bound="hbm", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s", frac=gbs / PEAK_HBM_GBS)
+    roof["traffic"] = profiled_traffic(dom_name, args.workload)
+    roof.update(kernel=dom_name, launches_per_step=dom["launches"],
+                algorithmic_bytes_per_launch=dom["bytes"] / max(dom["launches"], 1),
+                algorithmic_flops_per_launch=dom["flops"] / max(dom["launches"], 1),
+                flop_per_byte=intensity, ridge_flop_per_byte=ridge,
+                two_streams={"avg_launch_us": 1e3 * dom["ms"] / max(dom["launches"], 1), "ms_per_step": dom["ms"],
+                             "gbs": gbs, "tflops": tflops, "mfma_peak_frac": tflops / PEAK_BF16_TFLOPS})
+    # the same launches (matched by launch label: a call that has the chip to itself may take another kernel for
+    # them) with both branches on one stream, i.e. every kernel alone on the chip
+    labels = {e["name"] for e in ent2 if e["kernel"] == dom_name}
+    a_ms = sum(e["total_ms"] for e in ent if e["name"] in labels) / 3
+    a_n = sum(e["launches"] for e in ent if e["name"] in labels) // 3
+    if a_n:
+        roof["one_stream"] = {"avg_launch_us": 1e3 * a_ms / a_n, "ms_per_step": a_ms, "launches_per_step": a_n,
+                              "gbs": dom["bytes"] / max(dom["launches"], 1) * a_n / (a_ms * 1e-3) / 1e9,
+                              "kernels": sorted({e["kernel"] for e in ent if e["name"] in labels})}
     kernels = {k: dict(ms=round(v["ms"], 4), launches=v["launches"],
                        tflops=round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["ms"] > 0 else 0.0,
                        gbs=round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["ms"] > 0 else 0.0)
                for k, v in sorted(by_kernel.items(), key=lambda kv: -kv[1]["ms"])}
+    kernels2 = {k: dict(ms=round(v["ms"], 4), launches=v["launches"],
+                        tflops=round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["ms"] > 0 else 0.0,
+                        gbs=round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["ms"] > 0 else 0.0)
+                for k, v in sorted(two.items(), key=lambda kv: -kv[1]["ms"])}
 
     flops = 3.0 * block_fwd_flops(dims)
     out = {
-        "metric": "Parallel Evoformer block fwd+bwd ms (s=%d,r=%d)" % (dims["s"], dims["r"]),
+        "metric": "Parallel Evoformer block fwd+bwd ms (s=%d,r=%d) + %% bf16 MFMA peak" % (dims["s"], dims["r"]),
         "value": ms, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "ms_median": ms_median, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": ms / PAPER_MS_PER_LAYER if args.workload == "af2_initial" and args.variant == 0 else None,
@@ -313,7 +347,8 @@ def main():
         "overlap": {"t_msa_only_ms": t_msa, "t_pair_only_ms": t_pair, "t_two_streams_ms": ms,
                     "t_one_stream_ms": t_serial, "ratio": overlap},
         "roofline": roof,
-        "kernels_ms_per_step": kernels,
+        "kernels_two_streams_ms_per_step": kernels2,
+        "kernels_one_stream_ms_per_step": kernels,
     }
 
     if args.workload == "extra_msa_finetune":

@@ -28,8 +28,9 @@
 struct AttnArgs {
   const void* qkvg; long long plane;    // plane = B*L*d elements
   int B, L, H, d;
-  const float* bias;                 // [H][L][L] (query, key) or nullptr
-  const float* biasT;                // the same values as [H][key][query] (read by the query-per-lane kernels)
+  // pair bias, multiplied by log2 e, storage type, in the two layouts that bias_tile_kernel writes (nullptr: no bias):
+  const void* biasQ;                 // [H][key tile][chunk][g][query][CH]: read by the query-per-lane kernels
+  const void* biasK;                 // [H][query tile][chunk][g][key][CH]: read by the key-per-lane kernel
   const float* mask; long long mask_bs, mask_ks;   // key mask value at mask[b*mask_bs + j*mask_ks]
   void* o; void* og;                 // forward outputs (o ungated, og = sigmoid(g) * o)
   float* lse;                        // [B][H][L]
@@ -39,7 +40,7 @@ struct AttnArgs {
   void* dO;                          // scratch: cotangent of o (written by pre kernel)
   float* D;                          // [B][H][L] rowsum(dO * o)
   void* dqkvg;                       // same layout as qkvg
-  void* dS;                          // [B][H][key][query] storage type, written when bias != nullptr
+  void* dS;                          // [ceil(B/2)][H] planes in the layout of biasQ (storage type), biased attention only
 };
 
 // XCD-aware decode of the 1-D grid of the three tile kernels: workgroup w runs on XCD w % 8, and all
@@ -171,40 +172,56 @@ template <typename T> PE_DEV typename Mma<T>::frag gl_frag(const T* p, int kk, i
 }
 
 // Softmax is evaluated in the base-2 domain: t = s * (scale * log2 e) + bias * log2 e, p = 2^(t - m).
-// biasT is stored pre-multiplied by log2 e.  Key masks are applied as an additive 0 / -inf
-// term read from LDS four keys at a time.  All 16 bias loads of a tile are issued before the
-// score MFMAs (clamped addresses, no branches), so their latency overlaps the matrix work.
+// The tiled bias copies are stored pre-multiplied by log2 e.  Key masks are applied as an additive 0 / -inf
+// term read from LDS four keys at a time.  The four bias loads of a tile are issued before the
+// score MFMAs (clamped position, no branches), so their latency overlaps the matrix work.
 #define PE_LOG2E 1.4426950408889634f
 #define PE_LN2 0.6931471805599453f
 // raw v_exp_f32 (2^x; results below the normal range flush to zero, which is what softmax wants)
 PE_DEV float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// bias values of one 32x32 tile for this lane's column `col` (clamped to L-1 by the caller) of the plane
-// `ub` (uniform over the wave): element e <-> row t0 + acc_row(g, e).
-// Clamped form: rows beyond L-1 read row L-1, no branches.
-PE_DEV void attn_load_bias16(const float* ub, int L, int t0, int g, int col, float (&bv)[16]) {
-  const float* bcol = ub + col;
+// bias values of one 32x32 tile for the lane that owns position `col` (clamped to L-1 by the caller), from the
+// chunk-ordered plane `plane` of its head (see bias_tile_kernel): element e <-> position 32 tile + acc_row(g, e)
+// of the other axis.  16-byte loads; a half wave's 32 lanes read 512 contiguous bytes per load.
+template <typename T> PE_DEV void attn_load_bias_tile(const T* plane, int L, int tile, int col, int g, float (&bv)[16]);
+template <> PE_DEV void attn_load_bias_tile<float>(const float* plane, int L, int tile, int col, int g, float (&bv)[16]) {
 #pragma unroll
-  for (int e = 0; e < 16; e++) {
-    int row = min(t0 + 4 * g + 8 * (e >> 2) + (e & 3), L - 1);
-    bv[e] = bcol[row * L];
+  for (int c = 0; c < 4; c++) {
+    const f32x4 v = *reinterpret_cast<const f32x4*>(plane + bias_chunk_off<float>(tile, c, g, col, L));
+#pragma unroll
+    for (int r = 0; r < 4; r++) bv[c * 4 + r] = v[r];
   }
 }
-// Split form: for a full tile the address is a wave-uniform row base (scalar arithmetic) plus one per-lane
-// byte offset that is the same for every tile.  Measured faster in the dq kernel only (where the dS stores
-// use the same split), slower in the forward and dkv kernels, which keep the clamped form.
-PE_DEV void attn_load_bias16_split(const float* ub, int L, int t0, int g, int col, float (&bv)[16]) {
-  if (t0 + 32 <= L) {
-    const unsigned boff = (unsigned)(4 * g * L + col) * 4u;
+template <> PE_DEV void attn_load_bias_tile<bf16>(const bf16* plane, int L, int tile, int col, int g, float (&bv)[16]) {
 #pragma unroll
-    for (int e = 0; e < 16; e++) {
-      const char* urow = (const char*)(ub + (long long)(t0 + 8 * (e >> 2) + (e & 3)) * L);
-      bv[e] = *(const float*)(urow + boff);
-    }
-  } else {
-    attn_load_bias16(ub, L, t0, g, col, bv);
+  for (int c = 0; c < 2; c++) {
+    const bf16x8 v = *reinterpret_cast<const bf16x8*>(plane + bias_chunk_off<bf16>(tile, c, g, col, L));
+#pragma unroll
+    for (int r = 0; r < 8; r++) bv[c * 8 + r] = (float)v[r];
   }
 }
+// a lane's 16 elements of a score tile (dS) stored in the same chunk order
+template <typename T> PE_DEV void attn_store_tile16(T* plane, int L, int tile, int col, int g, const float (&v)[16]);
+template <> PE_DEV void attn_store_tile16<float>(float* plane, int L, int tile, int col, int g, const float (&v)[16]) {
+#pragma unroll
+  for (int c = 0; c < 4; c++) {
+    float t[4];
+#pragma unroll
+    for (int r = 0; r < 4; r++) t[r] = v[c * 4 + r];
+    store4<float>(plane + bias_chunk_off<float>(tile, c, g, col, L), t);
+  }
+}
+template <> PE_DEV void attn_store_tile16<bf16>(bf16* plane, int L, int tile, int col, int g, const float (&v)[16]) {
+#pragma unroll
+  for (int c = 0; c < 2; c++) {
+    float t[8];
+#pragma unroll
+    for (int r = 0; r < 8; r++) t[r] = v[c * 8 + r];
+    st8<bf16>(plane + bias_chunk_off<bf16>(tile, c, g, col, L), t);
+  }
+}
+// number of 32-position tiles of an axis of length L
+PE_DEV int attn_tiles32(int L) { return (L + 31) >> 5; }
 
 // ---------------------------------------------------------------------------
 // Forward
@@ -242,7 +259,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
   for (int e = 0; e < 16; e++) oacc[e] = 0.0f;
   float m_run = -INFINITY, l_run = 0.0f;
   constexpr bool has_bias = HAS_BIAS;
-  const float* bplane = has_bias ? a.biasT + (long long)h * L * L : nullptr;   // [key][query]
+  const T* bplane = has_bias ? (const T*)a.biasQ + (long long)h * attn_tiles32(L) * L * 32 : nullptr;
   const int bcolq = min(qi, L - 1);
   const float c1 = a.scale * PE_LOG2E;
 
@@ -266,7 +283,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
     for (int jt = 0; jt < C::KT / 32; jt++) {
       if (j0 + jt * 32 >= L) break;
       float bv[16];
-      if (has_bias) attn_load_bias16(bplane, L, j0 + jt * 32, g, bcolq, bv);
+      if (has_bias) attn_load_bias_tile<T>(bplane, L, (j0 >> 5) + jt, bcolq, g, bv);
       // issued after the first tile's bias loads, so that waiting for those does not wait for these
       if (jt == 0 && j0 + C::KT < L) prefetch(j0 + C::KT);
       f32x16 sacc;
@@ -427,11 +444,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   const float lse2 = qok ? a.lse[sidx] * PE_LOG2E : 0.0f;
   const float Di = qok ? a.D[sidx] : 0.0f;
   constexpr bool has_bias = HAS_BIAS;
-  const float* bplane = has_bias ? a.biasT + (long long)h * L * L : nullptr;   // [key][query]
+  const T* bplane = has_bias ? (const T*)a.biasQ + (long long)h * attn_tiles32(L) * L * 32 : nullptr;
   const int bcolq = min(qi, L - 1);
-  // dS^T plane [key][query] of this (b, h); a lane's element offset within a tile row group is tile-invariant
-  T* dsplane = a.dS ? (T*)a.dS + ((long long)b * a.H + h) * L * L : nullptr;
-  const unsigned dsoff = (unsigned)(4 * g * L + qi) * (unsigned)sizeof(T);
+  // dS plane of this (b, h) in the layout of biasQ
+  T* dsplane = a.dS ? (T*)a.dS + ((long long)b * a.H + h) * attn_tiles32(L) * L * 32 : nullptr;
   const float c1 = a.scale * PE_LOG2E;
 
   f32x16 dq;
@@ -453,7 +469,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
       const int kt0 = j0 + jt * 32;
       if (kt0 >= L) break;
       float bv[16];
-      if (has_bias) attn_load_bias16_split(bplane, L, kt0, g, bcolq, bv);
+      if (has_bias) attn_load_bias_tile<T>(bplane, L, kt0 >> 5, bcolq, g, bv);
       f32x16 sacc, pacc;
 #pragma unroll
       for (int e = 0; e < 16; e++) { sacc[e] = 0.0f; pacc[e] = 0.0f; }
@@ -476,19 +492,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         }
       }
       if (dsplane && qok) {
-        if (kt0 + 32 <= L) {
+        float v16[16];
 #pragma unroll
-          for (int e = 0; e < 16; e++) {
-            char* urow = (char*)(dsplane + (long long)(kt0 + 8 * (e >> 2) + (e & 3)) * L);   // wave-uniform
-            *(T*)(urow + dsoff) = from_f<T>(sacc[e]);
-          }
-        } else {
-#pragma unroll
-          for (int e = 0; e < 16; e++) {
-            int key = kt0 + acc_row(g, e);
-            if (key < L) dsplane[(long long)key * L + qi] = from_f<T>(sacc[e]);
-          }
-        }
+        for (int e = 0; e < 16; e++) v16[e] = sacc[e];
+        attn_store_tile16<T>(dsplane, L, kt0 >> 5, qi, g, v16);
       }
       const T* krow = lds_kt + l32 * C::TS + jt * 32;
 #pragma unroll
@@ -565,10 +572,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   const long long sidx = ((long long)b * a.H + h) * L + qi;
   const float lse2 = qok ? a.lse[sidx] * PE_LOG2E : 0.0f;
   const float Di = qok ? a.D[sidx] : 0.0f;
-  const float* bplane = a.biasT + (long long)h * L * L;   // [key][query]
+  const T* bplane = (const T*)a.biasQ + (long long)h * attn_tiles32(L) * L * 32;
   const int bcolq = min(qi, L - 1);
-  T* dsplane = (T*)a.dS + ((long long)bp * a.H + h) * L * L;   // summed pair of rows
-  const unsigned dsoff = (unsigned)(4 * g * L + qi) * (unsigned)sizeof(T);
+  T* dsplane = (T*)a.dS + ((long long)bp * a.H + h) * attn_tiles32(L) * L * 32;   // summed pair of rows, laid out like biasQ
   const float c1 = a.scale * PE_LOG2E;
 
   f32x16 dq;
@@ -591,7 +597,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
       const int kt0 = j0 + jt * 32;
       if (kt0 >= L) break;   // uniform over the workgroup
       float bv[16];
-      attn_load_bias16_split(bplane, L, kt0, g, bcolq, bv);
+      attn_load_bias_tile<T>(bplane, L, kt0 >> 5, bcolq, g, bv);
       f32x16 sacc, pacc;
 #pragma unroll
       for (int e = 0; e < 16; e++) { sacc[e] = 0.0f; pacc[e] = 0.0f; }
@@ -619,20 +625,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         for (int e = 0; e < 16; e++) lds_x[xb][wave][e][lane] = bvalid ? sacc[e] : 0.0f;
       }
       __syncthreads();
-      if (grp == 0 && qok) {
-        if (kt0 + 32 <= L) {
+      if (grp == 0 && qok) {   // 16-byte stores; a half wave's lanes write 512 contiguous bytes each
+        float v16[16];
 #pragma unroll
-          for (int e = 0; e < 16; e++) {
-            char* urow = (char*)(dsplane + (long long)(kt0 + 8 * (e >> 2) + (e & 3)) * L);   // wave-uniform
-            *(T*)(urow + dsoff) = from_f<T>(sacc[e] + lds_x[xb][wave][e][lane]);
-          }
-        } else {
-#pragma unroll
-          for (int e = 0; e < 16; e++) {
-            int key = kt0 + acc_row(g, e);
-            if (key < L) dsplane[(long long)key * L + qi] = from_f<T>(sacc[e] + lds_x[xb][wave][e][lane]);
-          }
-        }
+        for (int e = 0; e < 16; e++) v16[e] = sacc[e] + lds_x[xb][wave][e][lane];
+        attn_store_tile16<T>(dsplane, L, kt0 >> 5, qi, g, v16);
       }
       xb ^= 1;
       const T* krow = lds_kt + l32 * C::TS + jt * 32;
@@ -695,7 +692,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
   const float mk = kok ? a.mask[(long long)b * a.mask_bs + (long long)kj * a.mask_ks] : 0.0f;
   const float madd = (mk > 0.0f) ? 0.0f : -INFINITY;
   constexpr bool has_bias = HAS_BIAS;
-  const float* bplane = has_bias ? a.bias + (long long)h * L * L : nullptr;   // [query][key]
+  const T* bplane = has_bias ? (const T*)a.biasK + (long long)h * attn_tiles32(L) * L * 32 : nullptr;
   const int bcolk = min(kj, L - 1);
   const float c1 = a.scale * PE_LOG2E;
 
@@ -718,7 +715,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
     for (int it = 0; it < C::KT / 32; it++) {
       if (i0 + it * 32 >= L) break;
       float bv[16];
-      if (has_bias) attn_load_bias16(bplane, L, i0 + it * 32, g, bcolk, bv);
+      if (has_bias) attn_load_bias_tile<T>(bplane, L, (i0 >> 5) + it, bcolk, g, bv);
       f32x16 sacc, pacc;
 #pragma unroll
       for (int e = 0; e < 16; e++) { sacc[e] = 0.0f; pacc[e] = 0.0f; }
@@ -737,8 +734,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; r++) {
           int e = q4 * 4 + r;
-          float t = sacc[e] * c1;
-          if (has_bias) t = fmaf(bv[e], PE_LOG2E, t);
+          float t = has_bias ? fmaf(sacc[e], c1, bv[e]) : sacc[e] * c1;
           float p = fast_exp2(t + madd - ls[r]);
           pv[e] = p;
           sacc[e] = p * (pacc[e] - Dr[r]);

@@ -7,6 +7,7 @@
 // output cotangent (an input) and the row-attention-bias gradient is added to the pair
 // branch's gradient of the input pair representation at the very end.
 #include <stdio.h>
+#include <functional>
 #include <mutex>
 #include <string>
 #include <vector>
@@ -39,6 +40,7 @@ struct pe_handle {
   int timing;                       // PE_OPT_KERNEL_TIMING
   int side_streams;                 // PE_OPT_SIDE_STREAMS
   int stack_keep;                   // PE_OPT_STACK_KEEP_CTX
+  int stack_overlap;                // PE_OPT_STACK_OVERLAP
   hipStream_t side[2];              // side stream of the MSA branch / of the pair branch
   hipEvent_t side_ev[32];           // ring of fork/join events
   int side_ev_next;
@@ -83,7 +85,7 @@ struct Carver {   // fixed layouts (ctx, prepared weights); optionally records e
   }
 };
 
-template <typename T> struct AttnCtx { T* xhat; float* stats; T* qkvg; float* bias; float* biasT; float* zstats; float* lse; T* o; T* og; };
+template <typename T> struct AttnCtx { T* xhat; float* stats; T* qkvg; T* bias; T* biasT; float* zstats; float* lse; T* o; T* og; };
 template <typename T> struct TransCtx { T* xhat; float* stats; T* h; };
 template <typename T> struct TriMulCtx { T* zhat; float* stats; T* proj_t; T* a_t; T* b_t; T* g; T* x_t; float* stats_out; T* xhat; T* u; };
 template <typename T> struct OpmCtx { T* mhat; float* stats; T* a; T* b; float* inv_norm; T* O; };
@@ -119,8 +121,11 @@ template <typename T> static void carve_attn_ctx(Carver& cv, AttnCtx<T>& a, cons
   a.xhat = cv.take<T>(N("xhat"), M * C, dtype_tag<T>());
   a.stats = cv.take<float>(N("stats"), M * 2, PE_F32);
   a.qkvg = cv.take<T>(N("qkvg"), M * 4 * HD, dtype_tag<T>());
-  a.bias = has_bias ? cv.take<float>(N("bias"), (long long)H * L * L, PE_F32) : nullptr;
-  a.biasT = has_bias ? cv.take<float>(N("biasT"), (long long)H * L * L, PE_F32) : nullptr;
+  // pair bias x log2 e, storage type, in the two lane-chunk layouts the attention kernels read (bias_tile_kernel):
+  // a key per lane ("bias") and a query per lane ("biasT"); the tile axis is padded to a multiple of 32
+  const long long btile = (long long)H * ((L + 31) / 32) * L * 32;
+  a.bias = has_bias ? cv.take<T>(N("bias"), btile, dtype_tag<T>()) : nullptr;
+  a.biasT = has_bias ? cv.take<T>(N("biasT"), btile, dtype_tag<T>()) : nullptr;
   a.zstats = has_bias ? cv.take<float>(N("zstats"), Mz * 2, PE_F32) : nullptr;
   a.lse = cv.take<float>(N("lse"), B * H * L, PE_F32);
   a.o = cv.take<T>(N("o"), M * HD, dtype_tag<T>());
@@ -601,9 +606,11 @@ template <typename T> struct Runner {
     prof_begin(st);
     bool al = false, narrow = false;
     int rc = launch_gemm<T, EpiGeneric<T>>(st, A, akc, B, bkc, sh, e, &al, &narrow);
+    // the exact instantiation (operand layouts, epilogue path, feature mask F; F = 8191 is the general kernel)
     char kn[64];
-    if (narrow) snprintf(kn, sizeof(kn), "gemm64_kernel<EpiGeneric>");
-    else snprintf(kn, sizeof(kn), "gemm_kernel<%s,%s,%s,EpiGeneric>", akc ? "kc" : "xc", bkc ? "kc" : "xc", al ? "vec" : "elem");
+    if (narrow) snprintf(kn, sizeof(kn), "gemm64_kernel<EpiGeneric,F=%d>", g_gemm_last_features);
+    else snprintf(kn, sizeof(kn), "gemm_kernel<%s,%s,%s,EpiGeneric,F=%d>", akc ? "kc" : "xc", bkc ? "kc" : "xc", al ? "vec" : "elem",
+                  g_gemm_last_features);
     prof_end(st, what, kn, 2.0 * M * N * K * batch, ((double)M * K + (double)N * K + (double)M * N) * batch * sizeof(T));
     if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = std::string("gemm operand alignment: ") + what; return; }
     check(what);
@@ -669,50 +676,66 @@ template <typename T> struct Runner {
     e.on_in = dh; e.on_outer = plane; e.on_stride = 1;
   }
 
-  void attn_sub_fwd(hipStream_t st, Arena& ar, const AttnP& p, const AttnW<T>& w, AttnCtx<T>& c, const T* x, T* xout,
-                    long long M, int Cc, int H, int dh, const AttnGeom& g, const T* bias_src, long long bias_ln_g,
-                    long long bias_ln_b) {
+  // first part of an attention sub-operation: LayerNorm of its input and the fused q / k / v / gate projection.
+  // It reads nothing but x, so the trunk can enqueue it for the NEXT block's row attention as soon as this
+  // block's MSA representation is final (see stack_impl).
+  void attn_sub_fwd_pre(hipStream_t st, const AttnP& p, const AttnW<T>& w, AttnCtx<T>& c, const T* x, long long M, int Cc,
+                        int H, int dh, const AttnGeom& g) {
     const int HD = H * dh;
     k_ln_fwd(st, x, p.ln_g, p.ln_b, c.xhat, c.stats, M, Cc);
-    if (c.bias && !dry && !err) {
+    EpiGeneric<T> e = epi_plain<T>(c.qkvg, 4 * HD);
+    epi_heads(e, g, dh, M * dh);
+    e.bias_n = P(p.b_g) - 3 * HD;   // only columns >= 3HD carry a bias (see bn_begin)
+    e.bn_begin = 3 * HD;
+    gemm(st, op_plain(c.xhat, Cc), true, op_plain(w.wt_qkvg, Cc), true, (int)M, 4 * HD, Cc, 1, e, "attn qkvg");
+  }
+  void attn_sub_fwd(hipStream_t st, Arena& ar, const AttnP& p, const AttnW<T>& w, AttnCtx<T>& c, const T* x, T* xout,
+                    long long M, int Cc, int H, int dh, const AttnGeom& g, const T* bias_src, long long bias_ln_g,
+                    long long bias_ln_b, bool pre_done = false) {
+    const int HD = H * dh;
+    if (!pre_done) attn_sub_fwd_pre(st, p, w, c, x, M, Cc, H, dh, g);
+    if (c.bias) {
+      // bias projection fused with its LayerNorm into a plain [h][pair row] plane (scratch), then the two tiled
+      // copies that the attention kernels read
+      size_t mkb = ar.mark();
+      float* direct = (float*)ar.alloc((size_t)H * Mz * sizeof(float));
+      float* unused = nullptr;
       const int lpr = ln_lpr(d.c_z);
-      const double fl = 2.0 * Mz * d.c_z * H, by = 1.0 * Mz * d.c_z * sizeof(T) + 8.0 * Mz * H;
-      if (lpr && lpr <= 32) {
-        const int rpw = 64 / lpr;
-        int grid = (int)std::min<long long>((Mz + 4 * rpw - 1) / (4 * rpw), 8192);
-        // direct (row-order) orientation first, the other one by a tiled transpose
-        float* direct = g.bias_transposed ? c.biasT : c.bias;
-        float* other = g.bias_transposed ? c.bias : c.biasT;
-        const float dscale = g.bias_transposed ? 1.4426950408889634f : 1.0f;
-        const float oscale = g.bias_transposed ? 0.6931471805599453f : 1.4426950408889634f;
-#define PE_LNB_FWD(L, HH) PE_LAUNCH("ln_bias_fwd", fl, by, st, (ln_bias_fwd_fast_kernel<T, L, HH>), dim3(grid), dim3(256), 0, bias_src, P(bias_ln_g), P(bias_ln_b), P(p.w_bias), direct, dscale, c.zstats, d.r, H, d.ln_eps)
+      const bool fast = lpr && lpr <= 32;
+      if (!fast) unused = (float*)ar.alloc((size_t)H * Mz * sizeof(float));
+      if (!dry && !err) {
+        const double fl = 2.0 * Mz * d.c_z * H, by = 1.0 * Mz * d.c_z * sizeof(T) + 4.0 * Mz * H;
+        int transposed = g.bias_transposed;
+        if (fast) {
+          const int rpw = 64 / lpr;
+          int grid = (int)std::min<long long>((Mz + 4 * rpw - 1) / (4 * rpw), 8192);
+#define PE_LNB_FWD(L, HH) PE_LAUNCH("ln_bias_fwd", fl, by, st, (ln_bias_fwd_fast_kernel<T, L, HH>), dim3(grid), dim3(256), 0, bias_src, P(bias_ln_g), P(bias_ln_b), P(p.w_bias), direct, 1.0f, c.zstats, d.r, H, d.ln_eps)
 #define PE_LNB_FWD_H(L) do { if (H <= 4) PE_LNB_FWD(L, 4); else PE_LNB_FWD(L, 8); } while (0)
-        switch (lpr) {
-          case 2: PE_LNB_FWD_H(2); break; case 4: PE_LNB_FWD_H(4); break; case 8: PE_LNB_FWD_H(8); break;
-          case 16: PE_LNB_FWD_H(16); break; default: PE_LNB_FWD_H(32); break;
-        }
-        PE_LAUNCH("bias_transpose", 0, 8.0 * H * Mz, st, bias_transpose_kernel, dim3((d.r + 31) / 32, (d.r + 31) / 32, H), dim3(256), 0, direct, other, d.r, oscale);
+          switch (lpr) {
+            case 2: PE_LNB_FWD_H(2); break; case 4: PE_LNB_FWD_H(4); break; case 8: PE_LNB_FWD_H(8); break;
+            case 16: PE_LNB_FWD_H(16); break; default: PE_LNB_FWD_H(32); break;
+          }
 #undef PE_LNB_FWD_H
 #undef PE_LNB_FWD
-      } else {
-        int grid = (int)std::min<long long>((Mz + 3) / 4, 4096);
-        PE_LAUNCH("ln_bias_fwd", fl, by, st, ln_bias_fwd_kernel<T>, dim3(grid), dim3(256), 0, bias_src, P(bias_ln_g), P(bias_ln_b),
-                  P(p.w_bias), c.bias, c.biasT, c.zstats, d.r, d.c_z, H, d.ln_eps, g.bias_transposed);
+        } else {
+          // the general kernel writes [h][query][key] itself (and a second orientation that is not used here)
+          int grid = (int)std::min<long long>((Mz + 3) / 4, 4096);
+          PE_LAUNCH("ln_bias_fwd", fl, by, st, ln_bias_fwd_kernel<T>, dim3(grid), dim3(256), 0, bias_src, P(bias_ln_g), P(bias_ln_b),
+                    P(p.w_bias), direct, unused, c.zstats, d.r, d.c_z, H, d.ln_eps, g.bias_transposed);
+          transposed = 0;
+        }
+        const int NT = (d.r + 31) / 32;
+        PE_LAUNCH("bias_tile", 0, (4.0 + 2.0 * sizeof(T)) * H * Mz, st, bias_tile_kernel<T>, dim3(NT, NT, H), dim3(256), 0, direct, c.biasT,
+                  c.bias, d.r, transposed, 1.4426950408889634f);
       }
-    }
-    {
-      EpiGeneric<T> e = epi_plain<T>(c.qkvg, 4 * HD);
-      epi_heads(e, g, dh, M * dh);
-      e.bias_n = P(p.b_g) - 3 * HD;   // only columns >= 3HD carry a bias (see bn_begin)
-      e.bn_begin = 3 * HD;
-      gemm(st, op_plain(c.xhat, Cc), true, op_plain(w.wt_qkvg, Cc), true, (int)M, 4 * HD, Cc, 1, e, "attn qkvg");
+      ar.release(mkb);
     }
     if (!dry && !err) {
       AttnArgs a;
       memset(&a, 0, sizeof(a));
       a.qkvg = c.qkvg; a.plane = M * dh;
       a.B = (int)g.B; a.L = (int)g.L; a.H = H; a.d = dh;
-      a.bias = c.bias; a.biasT = c.biasT; a.mask = g.mask; a.mask_bs = g.mask_bs; a.mask_ks = g.mask_ks;
+      a.biasK = c.bias; a.biasQ = c.biasT; a.mask = g.mask; a.mask_bs = g.mask_bs; a.mask_ks = g.mask_ks;
       a.o = c.o; a.og = c.og; a.lse = c.lse; a.scale = 1.0f / sqrtf((float)dh);
       dim3 grid(attn_grid_size(g.B, H, g.L));
       if (c.bias) PE_LAUNCH(g.l_fwd, 4.0 * g.B * H * g.L * g.L * dh, (5.0 * M * HD + 1.0 * M * HD) * sizeof(T) + (c.bias ? 4.0 * H * g.L * g.L : 0.0), st, (attn_fwd_kernel<T, true>), grid, dim3(256), 0, a);
@@ -873,10 +896,17 @@ template <typename T> struct Runner {
   // be enqueued one at a time so that the host alternates between the two streams (a stream whose
   // kernels are enqueued late starts late: the host needs ~10 us per launch).
   static constexpr int MSA_STEPS = 3, PAIR_STEPS = 5;
+  // set by the trunk when the previous block's call has already enqueued this block's MSA-side weight preparation
+  // and the first part of its row attention (fwd_row_pre) on stream_msa
+  bool row_pre_done = false;
+  void fwd_row_pre() {
+    run_prep(true);
+    attn_sub_fwd_pre(sm, PL.row, W.row, C.row, msa_in, Mm, d.c_m, d.h_msa, d.d_msa, geom_row());
+  }
   void fwd_msa_step(int i, const T* bias_pair, T* msa_out) {
     if (i == 0) {
       attn_sub_fwd(sm, am, PL.row, W.row, C.row, msa_in, C.m1, Mm, d.c_m, d.h_msa, d.d_msa, geom_row(), bias_pair,
-                   PL.row.ln_z_g, PL.row.ln_z_b);
+                   PL.row.ln_z_g, PL.row.ln_z_b, row_pre_done);
     } else if (i == 1) {
       if (d.col_global) gcol_sub_fwd(sm, C.m1, C.m2);
       else attn_sub_fwd(sm, am, PL.col, W.col, C.col, C.m1, C.m2, Mm, d.c_m, d.h_msa, d.d_msa, geom_col(), nullptr, 0, 0);
@@ -989,9 +1019,10 @@ template <typename T> struct Runner {
     T* dxh = (T*)ar.alloc((size_t)M * Cc * sizeof(T));
     T* dS = nullptr;
     float* dbias = nullptr;
+    const long long btile = (long long)H * ((gm.L + 31) / 32) * gm.L * 32;   // elements of one [H] set of chunk-ordered planes
     if (c.bias) {
-      dS = (T*)ar.alloc((size_t)gm.B * H * gm.L * gm.L * sizeof(T));
-      dbias = (float*)ar.alloc((size_t)H * gm.L * gm.L * sizeof(float));
+      dS = (T*)ar.alloc((size_t)((gm.B + 1) / 2) * btile * sizeof(T));
+      dbias = (float*)ar.alloc((size_t)btile * sizeof(float));
     }
     { ReduceSeg sg[1] = {{0, Cc, p.w_o, Cc}}, cb = {0, Cc, p.b_o, 0};
       gemm_dw(st, ar, op_heads_cols(c.og, gm, dh, M * dh), false, op_trans(g, Cc), false, HD, Cc, M, 1, sg, "attn dWo", 1, &cb); }
@@ -1025,7 +1056,7 @@ template <typename T> struct Runner {
       memset(&a, 0, sizeof(a));
       a.qkvg = c.qkvg; a.plane = M * dh;
       a.B = (int)gm.B; a.L = (int)gm.L; a.H = H; a.d = dh;
-      a.bias = c.bias; a.biasT = c.biasT; a.mask = gm.mask; a.mask_bs = gm.mask_bs; a.mask_ks = gm.mask_ks;
+      a.biasK = c.bias; a.biasQ = c.biasT; a.mask = gm.mask; a.mask_bs = gm.mask_bs; a.mask_ks = gm.mask_ks;
       a.o = c.o; a.og = c.og; a.lse = c.lse; a.scale = 1.0f / sqrtf((float)dh);
       a.dog = dog; a.dO = dO; a.D = Dv; a.dqkvg = dqkvg; a.dS = dS;
       long long tot = gm.B * gm.L * H;
@@ -1039,7 +1070,7 @@ template <typename T> struct Runner {
       if (c.bias) PE_LAUNCH(gm.l_dkv, 8.0 * gm.B * H * gm.L * gm.L * dh, 6.0 * M * HD * sizeof(T), st, (attn_bwd_dkv_kernel<T, true>), grid, dim3(256), 0, a);
       else PE_LAUNCH(gm.l_dkv, 8.0 * gm.B * H * gm.L * gm.L * dh, 6.0 * M * HD * sizeof(T), st, (attn_bwd_dkv_kernel<T, false>), grid, dim3(256), 0, a);
       if (c.bias) {
-        long long hll = (long long)H * gm.L * gm.L;
+        const long long hll = btile;
         if (hll % 8 == 0 && al16(dS) && al16(dbias))
           PE_LAUNCH("attn_dbias_reduce", 0, 1.0 * Bds * hll * sizeof(T) + 4.0 * hll, st, attn_dbias_reduce8_kernel<T>, dim3((unsigned)((hll / 8 + 63) / 64)), dim3(256), 0,
                     dS, dbias, (int)Bds, hll);
@@ -1062,13 +1093,14 @@ template <typename T> struct Runner {
       int grid = (int)std::min<long long>((Mz + 4 * rpw - 1) / (4 * rpw), 1024);
       int plen = 2 * cz + cz * H;
       float* part = (float*)part_arena(ar).alloc((size_t)grid * plen * sizeof(float));
-      // dbias is [h][key][query]; bring it to pair-row order when the bias rows are the queries
-      const bool flip = lpr && !gm.bias_transposed;
-      float* dbias_rows = flip ? (float*)ar.alloc((size_t)H * Mz * sizeof(float)) : dbias;
+      // dbias is in the chunk order of the query-per-lane bias copy; bring it to pair-row order
+      float* dbias_rows = (float*)ar.alloc((size_t)H * Mz * sizeof(float));
       if (!dry && !err) {
         const double fl = 4.0 * Mz * cz * H, by = (bias_gin ? 3.0 : 2.0) * Mz * cz * sizeof(T) + 4.0 * Mz * H;
+        const int NT = (d.r + 31) / 32;
+        PE_LAUNCH("bias_untile", 0, 8.0 * H * Mz, st, bias_untile_kernel<T>, dim3(NT, NT, H), dim3(256), 0, dbias, dbias_rows, d.r,
+                  gm.bias_transposed);
         if (lpr) {
-          if (flip) PE_LAUNCH("bias_transpose", 0, 8.0 * H * Mz, st, bias_transpose_kernel, dim3((d.r + 31) / 32, (d.r + 31) / 32, H), dim3(256), 0, dbias, dbias_rows, d.r, 1.0f);
 #define PE_LNB_BWD(L, HH) PE_LAUNCH("ln_bias_bwd", fl, by, st, (ln_bias_bwd_fast_kernel<T, L, HH>), dim3(grid), dim3(256), 0, dbias_rows, bias_src, c.zstats, P(bias_ln_g), P(bias_ln_b), P(p.w_bias), bias_gin, bias_gout, part, d.r, H)
 #define PE_LNB_BWD_H(L) do { if (H <= 4) PE_LNB_BWD(L, 4); else PE_LNB_BWD(L, 8); } while (0)
           switch (lpr) {
@@ -1078,8 +1110,8 @@ template <typename T> struct Runner {
 #undef PE_LNB_BWD_H
 #undef PE_LNB_BWD
         } else {
-          PE_LAUNCH("ln_bias_bwd", fl, by, st, ln_bias_bwd_kernel<T>, dim3(grid), dim3(256), 0, dbias, bias_src, c.zstats,
-                    P(bias_ln_g), P(bias_ln_b), P(p.w_bias), bias_gin, bias_gout, part, d.r, cz, H, gm.bias_transposed ^ 1);
+          PE_LAUNCH("ln_bias_bwd", fl, by, st, ln_bias_bwd_kernel<T>, dim3(grid), dim3(256), 0, dbias_rows, bias_src, c.zstats,
+                    P(bias_ln_g), P(bias_ln_b), P(p.w_bias), bias_gin, bias_gout, part, d.r, cz, H, 0);
         }
         ReduceSeg sg[3] = {{0, cz, bias_ln_g, 0}, {cz, cz, bias_ln_b, 0}, {2 * cz, cz * H, p.w_bias, 0}};
         reduce_to(ar, part, grid, plen, 1, plen, 3, sg);
@@ -1347,14 +1379,18 @@ static bool ev_link(pe_handle* h, int e, hipStream_t from, hipStream_t to) {
 // Forward schedule of one block (Figure 1).  At entry stream_pair has been forked from stream_msa.
 // msa_out / pair_out may be null (recompute inside the backward pass: only ctx is needed).  On
 // return every forward kernel is ordered before later work on BOTH streams.
+// early_next (nullable): called when everything of this block that stream_msa can do before it has to wait for
+// the pair branch is enqueued; the trunk uses it to enqueue the first kernels of the next block there
 template <typename T>
-static int run_forward(Runner<T>& R, pe_handle* h, const pe_dims& d, T* msa_out, T* pair_out) {
+static int run_forward(Runner<T>& R, pe_handle* h, const pe_dims& d, T* msa_out, T* pair_out,
+                       const std::function<int()>* early_next = nullptr) {
   hipStream_t sm = R.sm, sp = R.sp;
   const bool do_m = h->branches & 1, do_p = h->branches & 2;
   if (d.variant == PE_VARIANT_PARALLEL) {
     if (do_p) R.run_prep(false);
-    if (do_m) R.run_prep(true);
+    if (do_m && !R.row_pre_done) R.run_prep(true);
     R.fwd_stacks(do_m, do_p, R.pair_in, R.pair_in, msa_out, R.C.z5, true);
+    if (early_next && *early_next) { int rc = (*early_next)(); if (rc) return rc; }
     if (do_p && !ev_link(h, 1, sp, sm)) return PE_ERR_HIP;
     if (pair_out) {
       if (do_m && do_p) R.fwd_opm_project(pair_out, R.C.z5);
@@ -1392,7 +1428,8 @@ static int run_forward(Runner<T>& R, pe_handle* h, const pe_dims& d, T* msa_out,
 template <typename T>
 static int block_fwd_impl(pe_handle* h, const pe_dims& d, const void* msa_in, const void* pair_in, const float* msa_mask,
                           const float* pair_mask, const float* params, void* msa_out, void* pair_out, void* ctx,
-                          void* workspace, size_t wbytes, hipStream_t sm, hipStream_t sp) {
+                          void* workspace, size_t wbytes, hipStream_t sm, hipStream_t sp, bool row_pre_done = false,
+                          const std::function<int()>* early_next = nullptr) {
   Plan pl = plan_for(d);
   if (wbytes < pl.total(ctx == nullptr)) return PE_ERR_WORKSPACE;
   if (d.variant != PE_VARIANT_PARALLEL && h->branches != 3) return PE_ERR_ARG;
@@ -1401,8 +1438,25 @@ static int block_fwd_impl(pe_handle* h, const pe_dims& d, const void* msa_in, co
   R.params = params;
   R.msa_in = (const T*)msa_in; R.pair_in = (const T*)pair_in;
   R.msa_mask = msa_mask; R.pair_mask = pair_mask;
+  R.row_pre_done = row_pre_done;
   if (!ev_link(h, 0, sm, sp)) return PE_ERR_HIP;
-  return run_forward<T>(R, h, d, (T*)msa_out, (T*)pair_out);
+  return run_forward<T>(R, h, d, (T*)msa_out, (T*)pair_out, early_next);
+}
+
+// The part of a block's forward that depends on its MSA input alone (weights of the MSA branch into their
+// storage form, LayerNorm and q / k / v / gate projection of the row attention), enqueued on stream_msa.  ctx
+// is the block's own (kept) ctx: nothing of it is shared with the block that is still running.
+template <typename T>
+static int block_fwd_row_pre(pe_handle* h, const pe_dims& d, const void* msa_in, const float* msa_mask, const float* params,
+                             void* ctx, void* workspace, hipStream_t sm, hipStream_t sp) {
+  Plan pl = plan_for(d);
+  Runner<T> R;
+  setup_runner<T>(R, h, d, pl, (char*)workspace, (char*)ctx, sm, sp);
+  R.params = params;
+  R.msa_in = (const T*)msa_in;
+  R.msa_mask = msa_mask;
+  R.fwd_row_pre();
+  return R.err;
 }
 
 template <typename T>
@@ -1562,7 +1616,14 @@ static int stack_impl(pe_handle* h, int n_extra, const pe_dims* ex, int n_main, 
     if (!sp.keep) return nullptr;
     return ws + sp.off_ctx + (b < n_extra ? sp.ctx_e * (size_t)b : sp.ctx_e * (size_t)n_extra + sp.ctx_m * (size_t)(b - n_extra));
   };
-  // forward
+  // forward.  Cross-block overlap: a block's MSA representation is final before its outer product mean and before
+  // the pair branch has finished, and the next block's row attention needs the new pair representation only for
+  // its bias.  So, when every block has a ctx of its own (PE_OPT_STACK_KEEP_CTX) and the branches run on two
+  // streams, the next block's MSA-side weight preparation, LayerNorm and q / k / v / gate projection are enqueued
+  // on stream_msa right after this block's outer product, in the time that stream would otherwise spend waiting
+  // for the pair branch.  The same kernels run on the same data, so results are bit-identical.
+  const bool overlap_blocks = sp.keep && h->stack_overlap && sm != sp_;
+  bool pre_done = false;
   for (int b = 0; b < nb; b++) {
     const bool is_e = b < n_extra;
     const pe_dims& d = is_e ? *ex : *mn;
@@ -1570,9 +1631,17 @@ static int stack_impl(pe_handle* h, int n_extra, const pe_dims* ex, int n_main, 
     if (is_e) xo = ws + sp.off_extra_saved + sp.n_extra * (size_t)b;
     else xo = (b == nb - 1) ? msa_out : (void*)(ws + sp.off_msa_saved + sp.n_msa * (size_t)(b - n_extra));
     void* zo = (b == nb - 1) ? pair_out : (void*)pair_slot(b + 1);
+    const bool chain = overlap_blocks && b + 1 < nb && d.variant == PE_VARIANT_PARALLEL &&
+                       (b + 1 < n_extra ? ex : mn)->variant == PE_VARIANT_PARALLEL;
+    std::function<int()> early = [&, b]() -> int {
+      const bool ne = b + 1 < n_extra;
+      return block_fwd_row_pre<T>(h, ne ? *ex : *mn, x_in(b + 1), ne ? extra_mask : msa_mask, params + poff(b + 1),
+                                  ctx_of(b + 1), blockws, sm, sp_);
+    };
     int rc = block_fwd_impl<T>(h, d, x_in(b), z_in(b), is_e ? extra_mask : msa_mask, pair_mask, params + poff(b), xo, zo,
-                               ctx_of(b), blockws, sp.block_bytes, sm, sp_);
+                               ctx_of(b), blockws, sp.block_bytes, sm, sp_, pre_done, chain ? &early : nullptr);
     if (rc) return rc;
+    pre_done = chain;
   }
   // backward
   char* pp = ws + sp.off_pp;
@@ -1659,6 +1728,7 @@ int pe_create(pe_handle** out) {
   h->timing = 0;
   h->side_streams = 0;
   h->stack_keep = 0;
+  h->stack_overlap = 0;
   h->side[0] = h->side[1] = nullptr;
   h->side_ev_next = 0;
   for (int i = 0; i < 32; i++) h->side_ev[i] = nullptr;
@@ -1688,6 +1758,7 @@ int pe_set_option(pe_handle* h, int option, int value) {
   if (option == PE_OPT_SYNC_DEBUG) { h->sync_debug = value ? 1 : 0; return PE_OK; }
   if (option == PE_OPT_KERNEL_TIMING) { h->timing = value ? 1 : 0; return PE_OK; }
   if (option == PE_OPT_STACK_KEEP_CTX) { h->stack_keep = value ? 1 : 0; return PE_OK; }
+  if (option == PE_OPT_STACK_OVERLAP) { h->stack_overlap = value ? 1 : 0; return PE_OK; }
   if (option == PE_OPT_SIDE_STREAMS) {
     // Created on first use only: every extra stream competes for the process's few hardware
     // queues (4 by default), and two streams that share a queue serialise.

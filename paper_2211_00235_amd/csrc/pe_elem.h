@@ -736,20 +736,94 @@ __global__ __launch_bounds__(256) void ln_bias_fwd_fast_kernel(const T* z, const
   }
 }
 
-// dst[h][j][i] = src[h][i][j] * f for H matrices of r x r (32 x 32 tiles through LDS)
-__global__ __launch_bounds__(256) void bias_transpose_kernel(const float* src, float* dst, int r, float f) {
-  __shared__ float tile[32][33];
-  const int h = blockIdx.z, i0 = blockIdx.y * 32, j0 = blockIdx.x * 32;
+// Copies of the pair bias for the attention kernels, in the storage type and in "lane chunk" order.
+// direct[h][.][.] (r x r per head, fp32) holds value(query q, key k) at [q][k] (transposed == 0) or at [k][q]
+// (transposed == 1).  Lane (position p, g) of a 32 x 32 score tile holds the 16 elements whose other-axis
+// offsets are acc_row(g, e) = 8 (e / 4) + 4 g + e % 4.  With CH = 16 bytes / sizeof(T) elements per chunk
+// (4 fp32, 8 bf16) the copies are stored as
+//   biasQ[h][key tile][chunk c][g][query][CH]   element i of chunk c: e = c CH + i   (kernels with a query per lane)
+//   biasK[h][query tile][chunk c][g][key][CH]                                          (the kernel with a key per lane)
+// both multiplied by f.  A lane then reads its 16 values with 16 / CH loads of 16 bytes, and the 32 lanes of a
+// half wave read 512 contiguous bytes per load - instead of sixteen 4-byte loads with a row multiplication each
+// (whose address arithmetic was about a sixth of the attention kernels' vector instructions) - and, in bf16, half
+// the bytes: every workgroup of an attention kernel reads its whole 128 x L bias slab, 268 MB per launch in fp32
+// at the row-attention shape, which is what the forward kernel was waiting for.  The tile axis is padded to a
+// multiple of 32 positions with zeros (padded keys are masked, padded queries never stored).
+// grid (NT, NT, H) with NT = ceil(r / 32): blockIdx.x = key tile, blockIdx.y = query tile.
+template <typename T> struct BiasChunk { static constexpr int CH = 16 / sizeof(T), NC = 16 / CH; };
+// offset (in elements) of chunk c of lane (position p of L, g) of tile t inside one head's plane
+template <typename T> PE_DEV long long bias_chunk_off(int t, int c, int g, int p, int L) {
+  return ((((long long)t * BiasChunk<T>::NC + c) * 2 + g) * L + p) * BiasChunk<T>::CH;
+}
+template <typename T>
+__global__ __launch_bounds__(256) void bias_tile_kernel(const float* direct, T* biasQ, T* biasK, int r, int transposed, float f) {
+  constexpr int CH = BiasChunk<T>::CH, NC = BiasChunk<T>::NC;
+  __shared__ float tile[32][33];   // tile[query - q0][key - k0]
+  const int h = blockIdx.z, q0 = blockIdx.y * 32, k0 = blockIdx.x * 32, NT = gridDim.x;
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-  const long long base = (long long)h * r * r;
-  for (int k = ty; k < 32; k += 8) {
-    int i = i0 + k, j = j0 + tx;
-    tile[k][tx] = (i < r && j < r) ? src[base + (long long)i * r + j] : 0.0f;
+  const long long base = (long long)h * r * r, plane = (long long)NT * 32 * r;
+  for (int a = ty; a < 32; a += 8) {   // coalesced along the fast axis of the direct plane
+    if (!transposed) {
+      const int q = q0 + a, k = k0 + tx;
+      tile[a][tx] = (q < r && k < r) ? direct[base + (long long)q * r + k] * f : 0.0f;
+    } else {
+      const int k = k0 + a, q = q0 + tx;
+      tile[tx][a] = (q < r && k < r) ? direct[base + (long long)k * r + q] * f : 0.0f;
+    }
   }
   __syncthreads();
-  for (int k = ty; k < 32; k += 8) {
-    int j = j0 + k, i = i0 + tx;
-    if (i < r && j < r) dst[base + (long long)j * r + i] = tile[tx][k] * f;
+  // thread (tx, ty): position tx of the lane axis; (c, g) = the ty-th chunk
+  if (ty < 2 * NC) {
+    const int c = ty >> 1, g = ty & 1;
+    float vq[CH], vk[CH];
+#pragma unroll
+    for (int i = 0; i < CH; i++) {
+      const int e = c * CH + i, o = 8 * (e >> 2) + 4 * g + (e & 3);
+      vq[i] = tile[tx][o];
+      vk[i] = tile[o][tx];
+    }
+    if (q0 + tx < r) {
+      T* p = biasQ + h * plane + bias_chunk_off<T>(blockIdx.x, c, g, q0 + tx, r);
+#pragma unroll
+      for (int i = 0; i < CH; i++) p[i] = from_f<T>(vq[i]);
+    }
+    if (k0 + tx < r) {
+      T* p = biasK + h * plane + bias_chunk_off<T>(blockIdx.y, c, g, k0 + tx, r);
+#pragma unroll
+      for (int i = 0; i < CH; i++) p[i] = from_f<T>(vk[i]);
+    }
+  }
+}
+
+// Bias gradient (fp32 sums in the query-per-lane chunk order of storage type T) back to pair-row order:
+//   d bias(q, k) -> rows[h][q r + k]  (transposed == 0: the bias of (q, k) was read from pair position (q, k)) or
+//   rows[h][k r + q] (transposed == 1).  Same grid as above.
+template <typename T>
+__global__ __launch_bounds__(256) void bias_untile_kernel(const float* tiled, float* rows, int r, int transposed) {
+  constexpr int CH = BiasChunk<T>::CH, NC = BiasChunk<T>::NC;
+  __shared__ float tile[32][33];   // tile[query - q0][key - k0]
+  const int h = blockIdx.z, q0 = blockIdx.y * 32, k0 = blockIdx.x * 32, NT = gridDim.x;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const long long plane = (long long)NT * 32 * r;
+  if (ty < 2 * NC) {
+    const int c = ty >> 1, g = ty & 1;
+    const float* p = tiled + h * plane + bias_chunk_off<T>(blockIdx.x, c, g, min(q0 + tx, r - 1), r);
+#pragma unroll
+    for (int i = 0; i < CH; i++) {
+      const int e = c * CH + i, o = 8 * (e >> 2) + 4 * g + (e & 3);
+      tile[tx][o] = (q0 + tx < r) ? p[i] : 0.0f;
+    }
+  }
+  __syncthreads();
+  const long long base = (long long)h * r * r;
+  for (int a = ty; a < 32; a += 8) {
+    if (!transposed) {
+      const int q = q0 + a, k = k0 + tx;
+      if (q < r && k < r) rows[base + (long long)q * r + k] = tile[a][tx];
+    } else {
+      const int k = k0 + a, q = q0 + tx;
+      if (q < r && k < r) rows[base + (long long)k * r + q] = tile[tx][a];
+    }
   }
 }
 

@@ -1179,6 +1179,10 @@ static inline int launch_dwx(hipStream_t st, dim3 grid, int groups, const Operan
   return hipGetLastError() == hipSuccess ? 0 : -2;
 }
 
+// feature mask of the kernel instantiation that the last launch_gemm call of this host thread took (EF_ALL = the
+// general kernel); read by the caller to label the launch with the exact kernel symbol
+static thread_local int g_gemm_last_features = EF_ALL;
+
 // the narrow-output kernel for the feature sets that occur with N <= 128 (else: not taken)
 template <typename T, class Epi>
 static inline bool launch_gemm64(hipStream_t st, const Operand& A, const Operand& B, const GemmShape& sh, const Epi& epi) {
@@ -1190,6 +1194,7 @@ static inline bool launch_gemm64(hipStream_t st, const Operand& A, const Operand
 #define PE_GEMM64_SPEC(S)                                                                         \
   if ((f & ~(S)) == 0) {                                                                          \
     hipLaunchKernelGGL((gemm64_kernel<T, Epi, (S)>), grid, block, 0, st, A, B, sh, epi);           \
+    g_gemm_last_features = (S);                                                                   \
     return true;                                                                                  \
   }
   PE_GEMM64_SPEC(0)
@@ -1217,6 +1222,7 @@ static inline bool launch_gemm_spec(hipStream_t st, dim3 grid, const Operand& A,
 #define PE_GEMM_SPEC(S)                                                                                     \
   if ((f & ~(S)) == 0) {                                                                                    \
     hipLaunchKernelGGL((gemm_kernel<T, true, true, true, true, Epi, (S)>), grid, block, 0, st, A, B, sh, epi); \
+    g_gemm_last_features = (S);                                                                             \
     return true;                                                                                            \
   }
   PE_GEMM_SPEC(0)
@@ -1248,6 +1254,7 @@ static inline void launch_gemm_al(hipStream_t st, dim3 grid, const Operand& A, b
       if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_kernel<T, true, false, true, true, Epi, (S)>), grid, block, 0, st, A, B, sh, epi);       \
       else if (!a_kc && b_kc) hipLaunchKernelGGL((gemm_kernel<T, false, true, true, true, Epi, (S)>), grid, block, 0, st, A, B, sh, epi);  \
       else hipLaunchKernelGGL((gemm_kernel<T, false, false, true, true, Epi, (S)>), grid, block, 0, st, A, B, sh, epi);                    \
+      g_gemm_last_features = (S);                                                                                      \
       return;                                                                                                          \
     }
     if (!(a_kc && b_kc)) {
@@ -1269,6 +1276,7 @@ static inline int launch_gemm(hipStream_t st, const Operand& A, bool a_kc, const
                               const GemmShape& shape, const Epi& epi, bool* used_vec = nullptr, bool* used_narrow = nullptr,
                               int wave_groups = 0, int* dwp_depth_used = nullptr) {
   GemmShape sh = shape;
+  g_gemm_last_features = EF_ALL;
   if (sh.M <= 0 || sh.N <= 0 || sh.batch <= 0) return 0;
   if (a_kc ? A.k_stride != 1 : A.x_stride != 1) return -1;
   if (b_kc ? B.k_stride != 1 : B.x_stride != 1) return -1;

@@ -322,3 +322,44 @@ def test_stack_needs_both_branches():
                          to_dev(inp["pair_mask"], f32), to_dev(inp["params"], f32), m.clone(), t.clone(),
                          torch.empty_like(m), torch.empty_like(t), None, torch.empty_like(m), torch.empty_like(t),
                          torch.zeros(n, device="cuda"), ws)
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_stack_cross_block_overlap_is_bit_identical(dtype):
+    """Trunk-level scheduling: with every block's activations kept, the next block's row-attention LayerNorm and
+    q / k / v / gate projection (and its MSA-side weight preparation) are enqueued on stream_msa before the current
+    block's outer product mean waits for the pair branch.  2 extra-MSA + 3 main blocks (the overlap crosses the
+    extra -> main boundary, where the next block reads the caller's MSA input): every output, input cotangent and
+    parameter gradient is bit-identical with the overlap switched off (PE_OPT_STACK_OVERLAP = 0)."""
+    dims_m, mask, seed = dims_for("tiny")
+    dims_m.update(dtype=dtype, s=16, r=40)
+    dims_e = dict(dims_m, s=24, c_m=16, col_global=1)
+    n_extra, n_main = 2, 3
+    te, ne = param_table(dims_e)
+    tm, nm = param_table(dims_m)
+    ie = make_inputs(dims_e, te, ne, ("random_rows", 0.1), 71, n_blocks=n_extra)
+    im = make_inputs(dims_m, tm, nm, ("last_residues", 4), 72, n_blocks=n_main)
+    dt, f32 = tdtype(dims_m), torch.float32
+    ex, msa, pair = to_dev(ie["msa"], dt), to_dev(im["msa"], dt), to_dev(im["pair"], dt)
+    exm, mm, pm = to_dev(ie["msa_mask"], f32), to_dev(im["msa_mask"], f32), to_dev(im["pair_mask"], f32)
+    par = to_dev(np.concatenate([ie["params"], im["params"]]), f32)
+    dmo, dzo = to_dev(im["d_msa_out"], dt), to_dev(im["d_pair_out"], dt)
+    results = []
+    for overlap in (1, 0):
+        h = pe.Handle()
+        h.set_option(5, 1)          # PE_OPT_STACK_KEEP_CTX
+        h.set_option(6, overlap)    # PE_OPT_STACK_OVERLAP
+        outs = [torch.empty_like(t) for t in (msa, pair, ex, msa, pair)]
+        dpar = torch.zeros_like(par)
+        ws = torch.empty(pe.stack_workspace_bytes(n_extra, dims_e, n_main, dims_m, keep=True), dtype=torch.uint8,
+                         device="cuda")
+        ws.fill_(0x7F)
+        sm, sp = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        pe.stack_fwd_bwd(h, n_extra, dims_e, n_main, dims_m, ex, msa, pair, exm, mm, pm, par, dmo, dzo, outs[0], outs[1],
+                         outs[2], outs[3], outs[4], dpar, ws, sm, sp)
+        torch.cuda.synchronize()
+        results.append(outs + [dpar])
+    for a, b in zip(*results):
+        assert torch.isfinite(a.float()).all()
+        assert torch.equal(a, b)
