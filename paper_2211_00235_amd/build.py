@@ -24,5 +24,24 @@ def build(verbose=False):
     return LIB
 
 
+def build_host_check(out, verbose=False):
+    """Host-only exercise of the C ABI (tests/host_checks/abi_host_check.cpp) linked with the library's source, the
+    HOST code instrumented with AddressSanitizer and UndefinedBehaviorSanitizer (the device code is compiled as
+    usual and never run: the program calls nothing that needs a GPU)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    root = os.path.dirname(HERE)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined"]
+    flags = [f for f in FLAGS if f not in ("-shared", "-fPIC", "-O3")] + ["-O1", "-g"]
+    cmd = ([hipcc] + flags + san + [os.path.join(CSRC, s) for s in SOURCES] +
+           [os.path.join(root, "tests", "host_checks", "abi_host_check.cpp"), "-o", out])
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if verbose or res.returncode:
+        print("\n".join(l for l in (res.stdout + res.stderr).splitlines() if "packed-fp32-ops" not in l))
+    if res.returncode:
+        raise RuntimeError("hipcc failed building %s" % out)
+    return out
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

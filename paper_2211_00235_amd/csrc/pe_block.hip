@@ -52,6 +52,10 @@ struct pe_handle {
 // ---------------------------------------------------------------------------
 // bump allocators
 // ---------------------------------------------------------------------------
+// Base "address" of the dry runs that size the workspace and list the ctx entries: the same carving code runs
+// there without memory behind it.  Not null (offsets added to a null pointer are undefined behaviour, which the
+// sanitizer build of the host code reports), far from anything mapped, never dereferenced.
+static char* const kDryBase = reinterpret_cast<char*>((uintptr_t)1 << 44);
 struct Arena {
   char* base = nullptr;
   size_t off = 0, high = 0;
@@ -1330,8 +1334,14 @@ template <typename T> static Plan make_plan(const pe_dims& d) {
   R.init(d);
   R.dry = true;
   Plan pl;
-  pl.ctx_bytes = carve_ctx<T>(nullptr, d, R.C, nullptr);
-  pl.prep_bytes = R.carve_prep(nullptr);
+  R.am.base = R.ap.base = R.pm.base = R.pp.base = kDryBase;
+  R.params = reinterpret_cast<const float*>(kDryBase);
+  R.dparams = reinterpret_cast<float*>(kDryBase);
+  R.msa_in = reinterpret_cast<const T*>(kDryBase);
+  R.pair_in = reinterpret_cast<const T*>(kDryBase);
+  R.msa_mask = R.pair_mask = reinterpret_cast<const float*>(kDryBase);
+  pl.ctx_bytes = carve_ctx<T>(kDryBase, d, R.C, nullptr);
+  pl.prep_bytes = R.carve_prep(kDryBase);
   // forward needs z5-independent scratch only from ctx; backward uses the arenas
   R.fwd_msa(nullptr);
   R.fwd_opm_project(nullptr, nullptr);
@@ -1813,8 +1823,8 @@ int pe_ctx_table(const pe_dims* d, pe_ctx_entry* out, int cap) {
   int rc = pe_check_dims(d);
   if (rc) return rc;
   std::vector<pe_ctx_entry> rec;
-  if (d->dtype == PE_BF16) { Ctx<bf16> c; carve_ctx<bf16>(nullptr, *d, c, &rec); }
-  else { Ctx<float> c; carve_ctx<float>(nullptr, *d, c, &rec); }
+  if (d->dtype == PE_BF16) { Ctx<bf16> c; carve_ctx<bf16>(kDryBase, *d, c, &rec); }
+  else { Ctx<float> c; carve_ctx<float>(kDryBase, *d, c, &rec); }
   int n = (int)rec.size();
   if (out) {
     if (cap < n) return PE_ERR_ARG;

@@ -103,3 +103,17 @@ def test_dims_error_names_the_violated_limit(L):
 
 def test_static_scratch_size_is_exported(L):
     assert pe.static_scratch_bytes() == 32 << 20
+
+
+def test_host_paths_under_sanitizers(tmp_path):
+    """The host-only paths (dims validation, parameter and ctx tables, the dry-run plans behind every size query,
+    argument validation of the compute calls) run in a build whose host code is instrumented with AddressSanitizer
+    and UndefinedBehaviorSanitizer: tests/host_checks/abi_host_check.cpp walks them over the workload shapes,
+    ragged and degenerate shapes and every limit of pe_dims; any report ends the program with a failure."""
+    import subprocess
+    from paper_2211_00235_amd import build
+    exe = build.build_host_check(str(tmp_path / "abi_host_check"))
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert res.stdout.startswith("ok "), res.stdout + res.stderr
+    assert "runtime error" not in res.stderr and "AddressSanitizer" not in res.stderr, res.stderr
