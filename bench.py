@@ -119,6 +119,14 @@ def bench_trunk(args, torch, pe):
         "cpu_baseline": cpu}))
 
 
+def kernel_symbol(name, dims):
+    """Launch labels carry the kernel as written at the launch site, e.g. "(attn_fwd_kernel<T, true>)"; bring them to
+    the form of the kernel symbol in a rocprofv3 trace ("attn_fwd_kernel<bf16,true>")."""
+    t = "bf16" if dims["dtype"] == 1 else "f32"
+    name = name.strip("()").replace(" ", "")
+    return name.replace("<T,", "<%s," % t).replace("<T>", "<%s>" % t)
+
+
 def profiled_traffic(kernel, workload):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload
     (FETCH_SIZE and WRITE_SIZE runs, scaled by what a plain copy reads on the same counters).  None
@@ -252,6 +260,8 @@ def main():
             print("%-22s %-44s n=%3d  %8.1f us/launch  %7.1f TFLOP/s  %7.1f GB/s" % (
                 e["name"], e["kernel"], e["launches"] // 3, 1e3 * e["total_ms"] / e["launches"],
                 e["flops"] / (e["total_ms"] * 1e-3) / 1e12, e["bytes"] / (e["total_ms"] * 1e-3) / 1e9), file=sys.stderr)
+    for e in ent:
+        e["kernel"] = kernel_symbol(e["kernel"], dims)
     by_kernel = {}
     for e in ent:
         k = by_kernel.setdefault(e["kernel"], dict(ms=0.0, launches=0, flops=0.0, bytes=0.0))
@@ -267,6 +277,8 @@ def main():
         eager_step()
     ent2 = run.h.timing_collect()
     run.h.set_option(3, 0)
+    for e in ent2:
+        e["kernel"] = kernel_symbol(e["kernel"], dims)
     if args.detail:
         alone = {(e["name"], e["kernel"]): e["total_ms"] / max(e["launches"], 1) for e in ent}
         # a launch that takes another kernel when it runs alone (parameter gradients): match by label only
