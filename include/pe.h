@@ -146,13 +146,14 @@ int pe_destroy(pe_handle* h);
  * 1.3 GiB per main block at s=128, r=256, which 288 GB of HBM hold for the whole
  * trunk) and recomputes nothing; results are bit-identical to the default,
  * which saves block inputs only and recomputes each block's forward.
- * PE_OPT_STACK_OVERLAP (default 1): with PE_OPT_STACK_KEEP_CTX and two distinct streams,
+ * PE_OPT_STACK_OVERLAP (default 0): 1 = with PE_OPT_STACK_KEEP_CTX and two distinct streams,
  * pe_stack_fwd_bwd enqueues the part of the NEXT block's forward that needs the new MSA
  * representation only (weight preparation of the MSA branch, LayerNorm and q / k / v / gate
  * projection of the row attention) on stream_msa before the current block's outer product
  * mean waits for the pair branch (Section "Branch Parallelism": the MSA representation is final
  * before the outer product mean; the next row attention needs the new pair representation for
- * its bias only).  Results are bit-identical; 0 switches it off (for measurement).            */
+ * its bias only).  Results are bit-identical.  Measured without gain on one MI355X (the chip
+ * is already full beside the pair branch's tail), hence off.                                 */
 enum { PE_OPT_BRANCHES = 1, PE_OPT_SYNC_DEBUG = 2, PE_OPT_KERNEL_TIMING = 3, PE_OPT_SIDE_STREAMS = 4,
        PE_OPT_STACK_KEEP_CTX = 5, PE_OPT_STACK_OVERLAP = 6 };
 int pe_set_option(pe_handle* h, int option, int value);
