@@ -171,34 +171,94 @@ template <typename T> PE_DEV typename Mma<T>::frag gl_frag(const T* p, int kk, i
   return MM::load(p + c0);
 }
 
-// Softmax is evaluated in the base-2 domain: t = s * (scale * log2 e) + bias * log2 e, p = 2^(t - m).
-// The tiled bias copies are stored pre-multiplied by log2 e.  Key masks are applied as an additive 0 / -inf
-// term read from LDS four keys at a time.  The four bias loads of a tile are issued before the
-// score MFMAs (clamped position, no branches), so their latency overlaps the matrix work.
+// Softmax is evaluated in the base-2 domain: t = q' k + bias', p = 2^(t - m), where q' = q * log2 e / sqrt(d) comes out
+// of the projection GEMM already scaled (its prepared weight copy carries the factor) and bias' = bias * log2 e is what
+// bias_tile_kernel stores.  A logit costs the vector unit no multiply-add and no conversion:
+//   * the bias tile is added by the matrix unit, as I x bias with an identity A operand (bf16; the 32-bit path adds it
+//     with 16 vector adds), and is loaded in exactly the B-operand order, so it needs no conversion;
+//   * the additive 0 / -inf key mask is applied only to 32-key tiles that hold a masked or padded key (one flag per
+//     tile, decided when the tile is staged);
+//   * in the dK / dV kernel, where -lse and -D of a tile's queries sit in LDS in accumulator order, they are the C
+//     operands of the S and dP products.
+// These kernels are bound by the length of a workgroup's life (memory round trips and dependent stages in a row at 3-4
+// waves per SIMD), not by any one unit: measured on MI355X, halving the vector instructions per logit changed the
+// forward kernel by 2 %, taking the exponentials out by 3 %, while its loads and stores add their full time to the
+// arithmetic's.  What helps is fewer round trips in a row (K / V staged 256 keys at a time in the forward kernel) and
+// registers kept at the 128 that four waves per SIMD allow.
 #define PE_LOG2E 1.4426950408889634f
 #define PE_LN2 0.6931471805599453f
 // raw v_exp_f32 (2^x; results below the normal range flush to zero, which is what softmax wants)
 PE_DEV float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// bias values of one 32x32 tile for the lane that owns position `col` (clamped to L-1 by the caller), from the
-// chunk-ordered plane `plane` of its head (see bias_tile_kernel): element e <-> position 32 tile + acc_row(g, e)
-// of the other axis.  16-byte loads; a half wave's 32 lanes read 512 contiguous bytes per load.
-template <typename T> PE_DEV void attn_load_bias_tile(const T* plane, int L, int tile, int col, int g, float (&bv)[16]);
-template <> PE_DEV void attn_load_bias_tile<float>(const float* plane, int L, int tile, int col, int g, float (&bv)[16]) {
+template <typename T> PE_DEV f32x16 mma_c(typename Mma<T>::frag a, typename Mma<T>::frag b, const f32x16& c);
+template <> PE_DEV f32x16 mma_c<bf16>(bf16x8 a, bf16x8 b, const f32x16& c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+template <> PE_DEV f32x16 mma_c<float>(float a, float b, const f32x16& c) {
+  return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+PE_DEV f32x16 splat16(float v) {
+  f32x16 r;
+#pragma unroll
+  for (int e = 0; e < 16; e++) r[e] = v;
+  return r;
+}
+
+// Bias values of one 32x32 tile for the lane that owns position `col` (clamped to L-1 by the caller) of the lane axis,
+// from the chunk-ordered plane of its head (bias_tile_kernel).  bf16: chunk c of lane group g holds positions
+// 16 c + 8 g + 0..7 of the other axis, i.e. the B operand of MFMA step c; fp32: accumulator order.  16-byte loads; a half
+// wave's 32 lanes read 512 contiguous bytes per load.
+template <typename T> struct BiasTile;
+template <> struct BiasTile<bf16> { bf16x8 v[2]; };
+template <> struct BiasTile<float> { float v[16]; };
+PE_DEV void attn_load_bias(const bf16* plane, int L, int tile, int col, int g, BiasTile<bf16>& b) {
+#pragma unroll
+  for (int c = 0; c < 2; c++) b.v[c] = *reinterpret_cast<const bf16x8*>(plane + bias_chunk_off<bf16>(tile, c, g, col, L));
+}
+PE_DEV void attn_load_bias(const float* plane, int L, int tile, int col, int g, BiasTile<float>& b) {
 #pragma unroll
   for (int c = 0; c < 4; c++) {
     const f32x4 v = *reinterpret_cast<const f32x4*>(plane + bias_chunk_off<float>(tile, c, g, col, L));
 #pragma unroll
-    for (int r = 0; r < 4; r++) bv[c * 4 + r] = v[r];
+    for (int r = 0; r < 4; r++) b.v[c * 4 + r] = v[r];
   }
 }
-template <> PE_DEV void attn_load_bias_tile<bf16>(const bf16* plane, int L, int tile, int col, int g, float (&bv)[16]) {
+// identity A operand: lane (row l32, group g) of step c holds [16 c + 8 g + t == l32], t = 0..7
+template <typename T> struct IdFrag;
+template <> struct IdFrag<bf16> {
+  bf16x8 f[2];
+  PE_DEV void init(int l32, int g) {
 #pragma unroll
-  for (int c = 0; c < 2; c++) {
-    const bf16x8 v = *reinterpret_cast<const bf16x8*>(plane + bias_chunk_off<bf16>(tile, c, g, col, L));
+    for (int c = 0; c < 2; c++)
 #pragma unroll
-    for (int r = 0; r < 8; r++) bv[c * 8 + r] = (float)v[r];
+      for (int t = 0; t < 8; t++) f[c][t] = (bf16)((16 * c + 8 * g + t == l32) ? 1.0f : 0.0f);
   }
+};
+template <> struct IdFrag<float> { PE_DEV void init(int, int) {} };
+PE_DEV void attn_add_bias(f32x16& acc, const BiasTile<bf16>& b, const IdFrag<bf16>& id) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(id.f[0], b.v[0], acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(id.f[1], b.v[1], acc, 0, 0, 0);
+}
+PE_DEV void attn_add_bias(f32x16& acc, const BiasTile<float>& b, const IdFrag<float>&) {
+#pragma unroll
+  for (int e = 0; e < 16; e++) acc[e] += b.v[e];
+}
+// additive key mask of one tile in accumulator order (rows of the tile = keys)
+PE_DEV void attn_add_row_mask(f32x16& acc, const float* lds_madd_tile, int g) {
+#pragma unroll
+  for (int q4 = 0; q4 < 4; q4++) {
+    const f32x4 ma = *reinterpret_cast<const f32x4*>(lds_madd_tile + 8 * q4 + 4 * g);
+#pragma unroll
+    for (int r = 0; r < 4; r++) acc[q4 * 4 + r] += ma[r];
+  }
+}
+// Key mask of the 64 staged keys: lds_madd = 0 / -inf per key, lds_flag[t] = 1 when tile t holds a masked or padded
+// key.  Called by threads 0..63 (one wave) with their key's mask value (0 beyond L).
+PE_DEV void attn_stage_mask(float mk, float* lds_madd, int* lds_flag, int t64) {
+  const bool masked = !(mk > 0.0f);
+  lds_madd[t64] = masked ? -INFINITY : 0.0f;
+  const unsigned long long bal = __ballot(masked);
+  if (t64 == 0) { lds_flag[0] = (bal & 0xffffffffull) != 0; lds_flag[1] = (bal >> 32) != 0; }
 }
 // a lane's 16 elements of a score tile (dS) stored in the same chunk order
 template <typename T> PE_DEV void attn_store_tile16(T* plane, int L, int tile, int col, int g, const float (&v)[16]);
@@ -227,19 +287,77 @@ PE_DEV int attn_tiles32(int L) { return (L + 31) >> 5; }
 // Forward
 // grid attn_grid_size(B, H, L), 256 threads; wave w owns queries q0 = tile*128 + 32*w
 // ---------------------------------------------------------------------------
+// The running maximum is a REFERENCE m_ref that follows the true maximum only when it has to.  The first tile in which a
+// query meets a finite logit sets m_ref to that tile's maximum (so a query with a single valid key gets the
+// probability 1 and its value row back exactly); after that the probabilities 2^(t - m_ref) <= 2^TAU are used as they
+// are, and only when a lane's tile maximum is more than TAU above m_ref the wave re-bases (accumulators and sum times
+// 2^(old - new)).  The result o = acc / l and lse = (m_ref + log2 l) ln 2 do not depend on the reference.
+#define ATTN_TAU 8.0f
+// Forward: K and V are staged a CHUNK of up to 256 keys at a time: all loads of the chunk are issued at once and waited
+// for once (with 64-key tiles a workgroup paid one memory round trip per tile, four to six in a row), and the waves then
+// run through its tiles without a barrier.  38 KB of LDS per workgroup, four workgroups per CU.
+template <typename T> struct AttnChunk {
+  static constexpr int CH = (sizeof(T) == 2) ? 256 : 128;          // keys per chunk
+  static constexpr int TS = CH + 4;                                // transposed row stride
+  static constexpr int NV = CH * (32 / Vec16<T>::N) / 256;         // 16-byte vectors per thread and tensor (4)
+};
+// all vectors of one [CH keys][d] chunk for this thread: vector idx = tid + 256 i <-> (row idx / vpr, channels
+// (idx % vpr) VEC ..) with vpr = 32 / VEC vector slots per row whatever d is (slots beyond d stay zero)
+template <typename T>
+PE_DEV void attn_chunk_load(const T* src, int pos0, int L, int d, typename Vec16<T>::type (&r)[AttnChunk<T>::NV], int tid) {
+  typedef typename Vec16<T>::type V;
+  constexpr int VEC = Vec16<T>::N;
+  constexpr int vpr = 32 / VEC;
+#pragma unroll
+  for (int i = 0; i < AttnChunk<T>::NV; i++) {
+    const int idx = tid + i * 256;
+    V v;
+#pragma unroll
+    for (int e = 0; e < VEC; e++) v[e] = from_f<T>(0.0f);
+    const int row = idx / vpr, dd0 = (idx % vpr) * VEC;
+    const int pos = pos0 + row;
+    if (pos < L && dd0 < d) v = *reinterpret_cast<const V*>(src + (long long)pos * d + dd0);
+    r[i] = v;
+  }
+}
+template <typename T>
+PE_DEV void attn_chunk_store(const typename Vec16<T>::type (&r)[AttnChunk<T>::NV], int DP, T* lds_rm, T* lds_t, int tid) {
+  typedef typename Vec16<T>::type V;
+  constexpr int VEC = Vec16<T>::N;
+  constexpr int vpr = 32 / VEC;
+#pragma unroll
+  for (int i = 0; i < AttnChunk<T>::NV; i++) {
+    const int idx = tid + i * 256;
+    const int row = idx / vpr, dd0 = (idx % vpr) * VEC;
+    if (dd0 < DP) {
+      if (lds_rm) *reinterpret_cast<V*>(lds_rm + row * AttnCfg<T>::RM + dd0) = r[i];
+      if (lds_t) {
+#pragma unroll
+        for (int e = 0; e < VEC; e++) lds_t[(dd0 + e) * AttnChunk<T>::TS + row] = r[i][e];
+      }
+    }
+  }
+}
+
+#ifndef PE_FWD_WAVES
+#define PE_FWD_WAVES 4
+#endif
 template <typename T, bool HAS_BIAS>
-__global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PE_FWD_WAVES, PE_FWD_WAVES))) void attn_fwd_kernel(AttnArgs a) {
   typedef AttnCfg<T> C;
   typedef Mma<T> MM;
-  __shared__ __attribute__((aligned(16))) T lds_k[C::KT * C::RM];
-  __shared__ __attribute__((aligned(16))) T lds_vt[32 * C::TS];
-  __shared__ __attribute__((aligned(16))) float lds_madd[C::KT];   // 0 for a valid key, -inf for a masked one
+  typedef AttnChunk<T> K;
+  typedef typename Vec16<T>::type V;
+  __shared__ __attribute__((aligned(16))) T lds_k[K::CH * C::RM];
+  __shared__ __attribute__((aligned(16))) T lds_vt[32 * K::TS];
+  __shared__ __attribute__((aligned(16))) float lds_madd[K::CH];   // 0 for a valid key, -inf for a masked one
+  __shared__ int lds_flag[K::CH / 32];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
   const AttnWg wg = attn_decode_wg(a);
   if (!wg.ok) return;
   const int h = wg.h, b = wg.b;
-  const int L = a.L, d = a.d, HD = a.H * a.d;
+  const int L = a.L, d = a.d;
   const int DP = round_up_i(d, MM::KSTEP);
   const int NKK = DP / MM::KSTEP;
   const int qi = wg.tile * 128 + wave * 32 + l32;       // this lane's query
@@ -250,94 +368,82 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnArgs a) {
 
   constexpr int MAXKK = 32 / MM::KSTEP;   // 2 (bf16) or 16 (fp32): d <= 32
   typename MM::frag qf[MAXKK];
-#pragma unroll
-  for (int kk = 0; kk < MAXKK; kk++)
-    if (kk < NKK) qf[kk] = gl_frag<T>(qrow, kk, g, d);
-
-  f32x16 oacc;
-#pragma unroll
-  for (int e = 0; e < 16; e++) oacc[e] = 0.0f;
-  float m_run = -INFINITY, l_run = 0.0f;
+  f32x16 oacc = splat16(0.0f);
+  float m_ref = 0.0f, l_part = 0.0f;     // l_part: this lane's keys only; the two halves of a query are added at the end
+  bool seen = false;                     // a finite logit has been seen
   constexpr bool has_bias = HAS_BIAS;
   const T* bplane = has_bias ? (const T*)a.biasQ + (long long)h * attn_tiles32(L) * L * 32 : nullptr;
   const int bcolq = min(qi, L - 1);
-  const float c1 = a.scale * PE_LOG2E;
+  IdFrag<T> idf;
+  idf.init(l32, g);
 
-  // K, V and the key mask of the next 64 keys are loaded into registers while the current ones are used
-  AttnStageRegs<T> rk, rv;
-  float mk = 0.0f;
-  auto prefetch = [&](int j0) {
-    attn_stage_load<T>(base + HP, d, j0, L, d, DP, rk, tid);
-    attn_stage_load<T>(base + 2 * HP, d, j0, L, d, DP, rv, tid);
-    const int j = j0 + tid;
-    mk = (tid < C::KT && j < L) ? a.mask[(long long)b * a.mask_bs + (long long)j * a.mask_ks] : 0.0f;
-  };
-  prefetch(0);
-  for (int j0 = 0; j0 < L; j0 += C::KT) {
-    __syncthreads();
-    attn_stage_store<T>(rk, DP, lds_k, (T*)nullptr, tid);
-    attn_stage_store<T>(rv, DP, (T*)nullptr, lds_vt, tid);
-    if (tid < C::KT) lds_madd[tid] = (mk > 0.0f) ? 0.0f : -INFINITY;
-    __syncthreads();
+  for (int c0 = 0; c0 < L; c0 += K::CH) {
+    {
+      V rk[K::NV], rv[K::NV];
+      if (c0 > 0) __syncthreads();
+      attn_chunk_load<T>(base + HP, c0, L, d, rk, tid);
+      attn_chunk_load<T>(base + 2 * HP, c0, L, d, rv, tid);
+      const int j = c0 + tid;
+      const float mk = (tid < K::CH && j < L) ? a.mask[(long long)b * a.mask_bs + (long long)j * a.mask_ks] : 0.0f;
+      if (c0 == 0) {
 #pragma unroll
-    for (int jt = 0; jt < C::KT / 32; jt++) {
-      if (j0 + jt * 32 >= L) break;
-      float bv[16];
-      if (has_bias) attn_load_bias_tile<T>(bplane, L, (j0 >> 5) + jt, bcolq, g, bv);
-      // issued after the first tile's bias loads, so that waiting for those does not wait for these
-      if (jt == 0 && j0 + C::KT < L) prefetch(j0 + C::KT);
-      f32x16 sacc;
-#pragma unroll
-      for (int e = 0; e < 16; e++) sacc[e] = 0.0f;
+        for (int kk = 0; kk < MAXKK; kk++)
+          if (kk < NKK) qf[kk] = gl_frag<T>(qrow, kk, g, d);
+      }
+      attn_chunk_store<T>(rk, DP, lds_k, (T*)nullptr, tid);
+      attn_chunk_store<T>(rv, DP, (T*)nullptr, lds_vt, tid);
+      if (tid < K::CH) attn_stage_mask(mk, lds_madd + 64 * wave, lds_flag + 2 * wave, lane);
+      __syncthreads();
+    }
+    const int jend = min(K::CH, L - c0);
+    BiasTile<T> bt;
+    if (has_bias) attn_load_bias(bplane, L, c0 >> 5, bcolq, g, bt);
+    for (int js = 0; js < jend; js += 32) {
+      const int masked = __builtin_amdgcn_readfirstlane(lds_flag[js >> 5]);
+      // base-2 logits for (query = lane, keys = acc rows)
+      f32x16 sacc = splat16(0.0f);
 #pragma unroll
       for (int kk = 0; kk < MAXKK; kk++)
-        if (kk < NKK) {
-          typename MM::frag kf = MM::load(lds_k + (jt * 32 + l32) * C::RM + kk * MM::KSTEP + g * MM::KP);
-          MM::mma(sacc, kf, qf[kk]);
-        }
-      // logits (base-2 domain) for (query = lane, keys = acc rows)
-      float tmax = -INFINITY;
-#pragma unroll
-      for (int q4 = 0; q4 < 4; q4++) {
-        f32x4 ma = *reinterpret_cast<const f32x4*>(lds_madd + jt * 32 + 8 * q4 + 4 * g);
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-          int e = q4 * 4 + r;
-          float v = has_bias ? fmaf(sacc[e], c1, bv[e]) : sacc[e] * c1;
-          v += ma[r];
-          sacc[e] = v;
-          tmax = fmaxf(tmax, v);
-        }
+        if (kk < NKK) MM::mma(sacc, MM::load(lds_k + (js + l32) * C::RM + kk * MM::KSTEP + g * MM::KP), qf[kk]);
+      if (has_bias) {
+        attn_add_bias(sacc, bt, idf);
+        attn_load_bias(bplane, L, min(((c0 + js) >> 5) + 1, attn_tiles32(L) - 1), bcolq, g, bt);   // next tile's bias
       }
+      if (masked) attn_add_row_mask(sacc, lds_madd + js, g);
+      float tmax = sacc[0];
+#pragma unroll
+      for (int e = 1; e < 16; e++) tmax = fmaxf(tmax, sacc[e]);
       tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-      float m_new = fmaxf(m_run, tmax);
-      float m_use = (m_new == -INFINITY) ? 0.0f : m_new;
-      float corr = fast_exp2(m_run - m_use);     // m_run = -inf -> 0
+      // re-base when the tile's maximum is more than TAU above the reference, and at the first finite logit
+      const bool finite = tmax > -INFINITY;
+      const bool rebase = tmax > m_ref + ATTN_TAU || (!seen && finite);
+      seen = seen || finite;
+      if (__any(rebase)) {
+        const float m_new = rebase ? tmax : m_ref;
+        const float corr = fast_exp2(m_ref - m_new);
+        m_ref = m_new;
+        l_part *= corr;
+#pragma unroll
+        for (int e = 0; e < 16; e++) oacc[e] *= corr;
+      }
       float psum = 0.0f;
 #pragma unroll
       for (int e = 0; e < 16; e++) {
-        float p = fast_exp2(sacc[e] - m_use);
+        float p = fast_exp2(sacc[e] - m_ref);
         sacc[e] = p;
         psum += p;
       }
-      psum += __shfl_xor(psum, 32, 64);
-      l_run = l_run * corr + psum;
-      m_run = m_new;
-#pragma unroll
-      for (int e = 0; e < 16; e++) oacc[e] *= corr;
+      l_part += psum;
       // O^T[dd, i] += sum_j V^T[dd, j] P^T[j, i]
-      const T* vrow = lds_vt + l32 * C::TS + jt * 32;
+      const T* vrow = lds_vt + l32 * K::TS + js;
 #pragma unroll
-      for (int u = 0; u < 32 / MM::KSTEP; u++) {
-        typename MM::frag vf = lds_tfrag<T>(vrow, g, u);
-        typename MM::frag pf = acc_to_frag<T>(sacc, u);
-        MM::mma(oacc, vf, pf);
-      }
+      for (int u = 0; u < 32 / MM::KSTEP; u++) MM::mma(oacc, lds_tfrag<T>(vrow, g, u), acc_to_frag<T>(sacc, u));
     }
   }
+  const float l_run = l_part + __shfl_xor(l_part, 32, 64);
   if (!qok) return;
   float inv = (l_run > 0.0f) ? 1.0f / l_run : 0.0f;
-  if (g == 0) a.lse[((long long)b * a.H + h) * L + qi] = (l_run > 0.0f) ? (m_run + log2f(l_run)) * PE_LN2 : 0.0f;
+  if (g == 0) a.lse[((long long)b * a.H + h) * L + qi] = (l_run > 0.0f) ? (m_ref + log2f(l_run)) * PE_LN2 : 0.0f;
   const long long orow = h * a.plane + ((long long)b * L + qi) * d;
   T* po = (T*)a.o + orow;
   T* pog = (T*)a.og + orow;
@@ -416,12 +522,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   __shared__ __attribute__((aligned(16))) T lds_kt[32 * C::TS];
   __shared__ __attribute__((aligned(16))) T lds_v[C::KT * C::RM];
   __shared__ __attribute__((aligned(16))) float lds_madd[C::KT];
+  __shared__ int lds_flag[2];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
   const AttnWg wg = attn_decode_wg(a);
   if (!wg.ok) return;
   const int h = wg.h, b = wg.b;
-  const int L = a.L, d = a.d, HD = a.H * a.d;
+  const int L = a.L, d = a.d;
   const int DP = round_up_i(d, MM::KSTEP);
   const int NKK = DP / MM::KSTEP;
   const int qi = wg.tile * 128 + wave * 32 + l32;
@@ -448,7 +555,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   const int bcolq = min(qi, L - 1);
   // dS plane of this (b, h) in the layout of biasQ
   T* dsplane = a.dS ? (T*)a.dS + ((long long)b * a.H + h) * attn_tiles32(L) * L * 32 : nullptr;
-  const float c1 = a.scale * PE_LOG2E;
+  IdFrag<T> idf;
+  idf.init(l32, g);
 
   f32x16 dq;
 #pragma unroll
@@ -459,38 +567,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     attn_stage<T>(base + HP, d, j0, L, d, DP, lds_k, lds_kt, tid, 256);
     attn_stage<T>(base + 2 * HP, d, j0, L, d, DP, lds_v, (T*)nullptr, tid, 256);
     if (tid < C::KT) {
-      int j = j0 + tid;
-      float mk = (j < L) ? a.mask[(long long)b * a.mask_bs + (long long)j * a.mask_ks] : 0.0f;
-      lds_madd[tid] = (mk > 0.0f) ? 0.0f : -INFINITY;
+      const int j = j0 + tid;
+      attn_stage_mask((j < L) ? a.mask[(long long)b * a.mask_bs + (long long)j * a.mask_ks] : 0.0f, lds_madd, lds_flag, tid);
     }
     __syncthreads();
 #pragma unroll
     for (int jt = 0; jt < C::KT / 32; jt++) {
       const int kt0 = j0 + jt * 32;
       if (kt0 >= L) break;
-      float bv[16];
-      if (has_bias) attn_load_bias_tile<T>(bplane, L, kt0 >> 5, bcolq, g, bv);
-      f32x16 sacc, pacc;
-#pragma unroll
-      for (int e = 0; e < 16; e++) { sacc[e] = 0.0f; pacc[e] = 0.0f; }
+      BiasTile<T> bt;
+      if (has_bias) attn_load_bias(bplane, L, kt0 >> 5, bcolq, g, bt);
+      const int masked = __builtin_amdgcn_readfirstlane(lds_flag[jt]);
+      const int off0 = (jt * 32 + l32) * C::RM + g * MM::KP;
+      f32x16 sacc = splat16(0.0f), pacc = splat16(0.0f);
 #pragma unroll
       for (int kk = 0; kk < MAXKK; kk++)
         if (kk < NKK) {
-          int off = (jt * 32 + l32) * C::RM + kk * MM::KSTEP + g * MM::KP;
-          MM::mma(sacc, MM::load(lds_k + off), qf[kk]);      // S^T = K Q^T
-          MM::mma(pacc, MM::load(lds_v + off), dof[kk]);     // dP^T = V dO^T
+          MM::mma(sacc, MM::load(lds_k + off0 + kk * MM::KSTEP), qf[kk]);      // S^T = K Q^T
+          MM::mma(pacc, MM::load(lds_v + off0 + kk * MM::KSTEP), dof[kk]);     // dP^T = V dO^T
         }
+      if (has_bias) attn_add_bias(sacc, bt, idf);
+      if (masked) attn_add_row_mask(sacc, lds_madd + jt * 32, g);
 #pragma unroll
-      for (int q4 = 0; q4 < 4; q4++) {
-        f32x4 ma = *reinterpret_cast<const f32x4*>(lds_madd + jt * 32 + 8 * q4 + 4 * g);
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-          int e = q4 * 4 + r;
-          float t = has_bias ? fmaf(sacc[e], c1, bv[e]) : sacc[e] * c1;
-          float p = fast_exp2(t + ma[r] - lse2);
-          sacc[e] = p * (pacc[e] - Di);
-        }
-      }
+      for (int e = 0; e < 16; e++) sacc[e] = fast_exp2(sacc[e] - lse2) * (pacc[e] - Di);     // dS = P (dP - D)
       if (dsplane && qok) {
         float v16[16];
 #pragma unroll
@@ -525,14 +624,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 // halves the dS traffic and the input of the reduction that follows.  With an odd B the last
 // workgroup's upper group runs on row B-1 again and contributes nothing.
 // ---------------------------------------------------------------------------
+#ifndef PE_DQ2_WAVES
+#define PE_DQ2_WAVES 4
+#endif
 template <typename T>
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) void attn_bwd_dq2_kernel(AttnArgs a) {
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(PE_DQ2_WAVES, PE_DQ2_WAVES))) void attn_bwd_dq2_kernel(AttnArgs a) {
   typedef AttnCfg<T> C;
   typedef Mma<T> MM;
   __shared__ __attribute__((aligned(16))) T lds_k2[2][C::KT * C::RM];
   __shared__ __attribute__((aligned(16))) T lds_kt2[2][32 * C::TS];
   __shared__ __attribute__((aligned(16))) T lds_v2[2][C::KT * C::RM];
   __shared__ __attribute__((aligned(16))) float lds_madd2[2][C::KT];
+  __shared__ int lds_flag2[2][2];
   __shared__ __attribute__((aligned(16))) float lds_x[2][4][16][64];   // [buffer][wave of the upper group][element][lane]
 
   const int tid = threadIdx.x, lane = tid & 63, wave8 = tid >> 6, l32 = lane & 31, g = lane >> 5;
@@ -549,6 +652,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   T* lds_kt = lds_kt2[grp];
   T* lds_v = lds_v2[grp];
   float* lds_madd = lds_madd2[grp];
+  int* lds_flag = lds_flag2[grp];
 
   const int L = a.L, d = a.d;
   const int DP = round_up_i(d, MM::KSTEP);
@@ -574,8 +678,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   const float Di = qok ? a.D[sidx] : 0.0f;
   const T* bplane = (const T*)a.biasQ + (long long)h * attn_tiles32(L) * L * 32;
   const int bcolq = min(qi, L - 1);
-  T* dsplane = (T*)a.dS + ((long long)bp * a.H + h) * attn_tiles32(L) * L * 32;   // summed pair of rows, laid out like biasQ
-  const float c1 = a.scale * PE_LOG2E;
+  T* dsplane = (T*)a.dS + ((long long)bp * a.H + h) * attn_tiles32(L) * L * 32;   // summed pair of rows, accumulator order
+  IdFrag<T> idf;
+  idf.init(l32, g);
 
   f32x16 dq;
 #pragma unroll
@@ -587,38 +692,29 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     attn_stage<T>(base + HP, d, j0, L, d, DP, lds_k, lds_kt, tg, 256);
     attn_stage<T>(base + 2 * HP, d, j0, L, d, DP, lds_v, (T*)nullptr, tg, 256);
     if (tg < C::KT) {
-      int j = j0 + tg;
-      float mk = (j < L) ? a.mask[(long long)b * a.mask_bs + (long long)j * a.mask_ks] : 0.0f;
-      lds_madd[tg] = (mk > 0.0f) ? 0.0f : -INFINITY;
+      const int j = j0 + tg;
+      attn_stage_mask((j < L) ? a.mask[(long long)b * a.mask_bs + (long long)j * a.mask_ks] : 0.0f, lds_madd, lds_flag, tg);
     }
     __syncthreads();
 #pragma unroll
     for (int jt = 0; jt < C::KT / 32; jt++) {
       const int kt0 = j0 + jt * 32;
       if (kt0 >= L) break;   // uniform over the workgroup
-      float bv[16];
-      attn_load_bias_tile<T>(bplane, L, kt0 >> 5, bcolq, g, bv);
-      f32x16 sacc, pacc;
-#pragma unroll
-      for (int e = 0; e < 16; e++) { sacc[e] = 0.0f; pacc[e] = 0.0f; }
+      BiasTile<T> bt;
+      attn_load_bias(bplane, L, kt0 >> 5, bcolq, g, bt);
+      const int masked = __builtin_amdgcn_readfirstlane(lds_flag[jt]);
+      const int off0 = (jt * 32 + l32) * C::RM + g * MM::KP;
+      f32x16 sacc = splat16(0.0f), pacc = splat16(0.0f);
 #pragma unroll
       for (int kk = 0; kk < MAXKK; kk++)
         if (kk < NKK) {
-          int off = (jt * 32 + l32) * C::RM + kk * MM::KSTEP + g * MM::KP;
-          MM::mma(sacc, MM::load(lds_k + off), qf[kk]);      // S^T = K Q^T
-          MM::mma(pacc, MM::load(lds_v + off), dof[kk]);     // dP^T = V dO^T
+          MM::mma(sacc, MM::load(lds_k + off0 + kk * MM::KSTEP), qf[kk]);      // S^T = K Q^T
+          MM::mma(pacc, MM::load(lds_v + off0 + kk * MM::KSTEP), dof[kk]);     // dP^T = V dO^T
         }
+      attn_add_bias(sacc, bt, idf);
+      if (masked) attn_add_row_mask(sacc, lds_madd + jt * 32, g);
 #pragma unroll
-      for (int q4 = 0; q4 < 4; q4++) {
-        f32x4 ma = *reinterpret_cast<const f32x4*>(lds_madd + jt * 32 + 8 * q4 + 4 * g);
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-          int e = q4 * 4 + r;
-          float t = fmaf(sacc[e], c1, bv[e]);
-          float p = fast_exp2(t + ma[r] - lse2);
-          sacc[e] = p * (pacc[e] - Di);
-        }
-      }
+      for (int e = 0; e < 16; e++) sacc[e] = fast_exp2(sacc[e] - lse2) * (pacc[e] - Di);     // dS = P (dP - D)
       // the upper group hands its dS tile over; the lower group adds its own and writes the sum
       if (grp == 1) {
 #pragma unroll
@@ -655,22 +751,25 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 // Backward, dK and dV.  Wave w owns keys k0 = tile*128 + 32*w (a key is a lane);
 // loops over query tiles staged in LDS (row-major and transposed copies of Q and dO).
 // ---------------------------------------------------------------------------
+#ifndef PE_DKV_WAVES
+#define PE_DKV_WAVES 3
+#endif
 template <typename T, bool HAS_BIAS>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PE_DKV_WAVES, PE_DKV_WAVES))) void attn_bwd_dkv_kernel(AttnArgs a) {
   typedef AttnCfg<T> C;
   typedef Mma<T> MM;
   __shared__ __attribute__((aligned(16))) T lds_q[C::KT * C::RM];
   __shared__ __attribute__((aligned(16))) T lds_qt[32 * C::TS];
   __shared__ __attribute__((aligned(16))) T lds_do[C::KT * C::RM];
   __shared__ __attribute__((aligned(16))) T lds_dot[32 * C::TS];
-  __shared__ __attribute__((aligned(16))) float lds_lse[C::KT];   // base-2 log-sum-exp, +inf beyond L
-  __shared__ __attribute__((aligned(16))) float lds_D[C::KT];
+  __shared__ __attribute__((aligned(16))) float lds_lse[C::KT];   // minus the base-2 log-sum-exp, -inf beyond L
+  __shared__ __attribute__((aligned(16))) float lds_D[C::KT];     // minus D
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
   const AttnWg wg = attn_decode_wg(a);
   if (!wg.ok) return;
   const int h = wg.h, b = wg.b;
-  const int L = a.L, d = a.d, HD = a.H * a.d;
+  const int L = a.L, d = a.d;
   const int DP = round_up_i(d, MM::KSTEP);
   const int NKK = DP / MM::KSTEP;
   const int kj = wg.tile * 128 + wave * 32 + l32;       // this lane's key
@@ -691,54 +790,77 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
     }
   const float mk = kok ? a.mask[(long long)b * a.mask_bs + (long long)kj * a.mask_ks] : 0.0f;
   const float madd = (mk > 0.0f) ? 0.0f : -INFINITY;
+  const bool wave_masked = __any(!(mk > 0.0f));          // some key of this wave is masked or padded
   constexpr bool has_bias = HAS_BIAS;
   const T* bplane = has_bias ? (const T*)a.biasK + (long long)h * attn_tiles32(L) * L * 32 : nullptr;
   const int bcolk = min(kj, L - 1);
-  const float c1 = a.scale * PE_LOG2E;
+  IdFrag<T> idf;
+  idf.init(l32, g);
 
   f32x16 dk, dv;
 #pragma unroll
   for (int e = 0; e < 16; e++) { dk[e] = 0.0f; dv[e] = 0.0f; }
 
+  // Q, dO, -lse and -D of the next 64 queries are loaded into registers while the current ones are used; the bias
+  // tiles one 64-query step ahead of their use
+  AttnStageRegs<T> rq, rdo;
+  float r_lse = 0.0f, r_D = 0.0f;
+  auto prefetch = [&](int i0) {
+    attn_stage_load<T>(base, d, i0, L, d, DP, rq, tid);
+    attn_stage_load<T>(dobase, d, i0, L, d, DP, rdo, tid);
+    const int i = i0 + tid;
+    const bool ok = tid < C::KT && i < L;
+    const long long sidx = ((long long)b * a.H + h) * L + (ok ? i : 0);
+    r_lse = ok ? -a.lse[sidx] * PE_LOG2E : -INFINITY;
+    r_D = ok ? -a.D[sidx] : 0.0f;
+  };
+  prefetch(0);
+  const int ntile = attn_tiles32(L);
+  BiasTile<T> bt[2];
+  if (has_bias) {
+    attn_load_bias(bplane, L, 0, bcolk, g, bt[0]);
+    attn_load_bias(bplane, L, min(1, ntile - 1), bcolk, g, bt[1]);
+  }
   for (int i0 = 0; i0 < L; i0 += C::KT) {
     __syncthreads();
-    attn_stage<T>(base, d, i0, L, d, DP, lds_q, lds_qt, tid, 256);
-    attn_stage<T>(dobase, d, i0, L, d, DP, lds_do, lds_dot, tid, 256);
-    if (tid < C::KT) {
-      int i = i0 + tid;
-      long long sidx = ((long long)b * a.H + h) * L + i;
-      lds_lse[tid] = (i < L) ? a.lse[sidx] * PE_LOG2E : INFINITY;
-      lds_D[tid] = (i < L) ? a.D[sidx] : 0.0f;
-    }
+    attn_stage_store<T>(rq, DP, lds_q, lds_qt, tid);
+    attn_stage_store<T>(rdo, DP, lds_do, lds_dot, tid);
+    if (tid < C::KT) { lds_lse[tid] = r_lse; lds_D[tid] = r_D; }
     __syncthreads();
+    if (i0 + C::KT < L) prefetch(i0 + C::KT);
 #pragma unroll
     for (int it = 0; it < C::KT / 32; it++) {
       if (i0 + it * 32 >= L) break;
-      float bv[16];
-      if (has_bias) attn_load_bias_tile<T>(bplane, L, (i0 >> 5) + it, bcolk, g, bv);
+      // C operands: -lse and -D of the tile's queries in accumulator order
       f32x16 sacc, pacc;
 #pragma unroll
-      for (int e = 0; e < 16; e++) { sacc[e] = 0.0f; pacc[e] = 0.0f; }
+      for (int q4 = 0; q4 < 4; q4++) {
+        const f32x4 ls = *reinterpret_cast<const f32x4*>(lds_lse + it * 32 + 8 * q4 + 4 * g);
+        const f32x4 Dr = *reinterpret_cast<const f32x4*>(lds_D + it * 32 + 8 * q4 + 4 * g);
+#pragma unroll
+        for (int r = 0; r < 4; r++) { sacc[q4 * 4 + r] = ls[r]; pacc[q4 * 4 + r] = Dr[r]; }
+      }
 #pragma unroll
       for (int kk = 0; kk < MAXKK; kk++)
         if (kk < NKK) {
           int off = (it * 32 + l32) * C::RM + kk * MM::KSTEP + g * MM::KP;
-          MM::mma(sacc, MM::load(lds_q + off), kf[kk]);      // S = Q K^T   (rows queries, col = key lane)
-          MM::mma(pacc, MM::load(lds_do + off), vf[kk]);     // dP = dO V^T
+          MM::mma(sacc, MM::load(lds_q + off), kf[kk]);      // S - lse = Q K^T - lse   (rows queries, col = key lane)
+          MM::mma(pacc, MM::load(lds_do + off), vf[kk]);     // dP - D = dO V^T - D
         }
+      if (has_bias) {
+        attn_add_bias(sacc, bt[it], idf);
+        attn_load_bias(bplane, L, min((i0 >> 5) + 2 + it, ntile - 1), bcolk, g, bt[it]);
+      }
+      if (wave_masked) {
+#pragma unroll
+        for (int e = 0; e < 16; e++) sacc[e] += madd;
+      }
       f32x16 pv;
 #pragma unroll
-      for (int q4 = 0; q4 < 4; q4++) {
-        f32x4 ls = *reinterpret_cast<const f32x4*>(lds_lse + it * 32 + 8 * q4 + 4 * g);
-        f32x4 Dr = *reinterpret_cast<const f32x4*>(lds_D + it * 32 + 8 * q4 + 4 * g);
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-          int e = q4 * 4 + r;
-          float t = has_bias ? fmaf(sacc[e], c1, bv[e]) : sacc[e] * c1;
-          float p = fast_exp2(t + madd - ls[r]);
-          pv[e] = p;
-          sacc[e] = p * (pacc[e] - Dr[r]);
-        }
+      for (int e = 0; e < 16; e++) {
+        const float p = fast_exp2(sacc[e]);
+        pv[e] = p;
+        sacc[e] = p * pacc[e];                                // dS = P (dP - D)
       }
       const T* dotrow = lds_dot + l32 * C::TS + it * 32;
       const T* qtrow = lds_qt + l32 * C::TS + it * 32;
@@ -758,7 +880,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnArgs a) {
     if (dd < d) {
       float v1[4], v2[4];
 #pragma unroll
-      for (int r = 0; r < 4; r++) { v1[r] = dk[q4 * 4 + r] * a.scale; v2[r] = dv[q4 * 4 + r]; }
+      for (int r = 0; r < 4; r++) { v1[r] = dk[q4 * 4 + r] * PE_LN2; v2[r] = dv[q4 * 4 + r]; }   // q' = q scale log2 e
       store4<T>(pdk + dd, v1);
       store4<T>(pdv + dd, v2);
     }

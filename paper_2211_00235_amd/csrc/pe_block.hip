@@ -216,24 +216,30 @@ template <typename T> struct PrepCarver {
   // weight W[in][out] at params offset src -> transposed copy [out][in] placed at row block `row0` of a [*, in] matrix
   T* region(long long count) { long long o = (toff + 127) & ~127LL; toff = o + count; return tbase + o; }
   float* fregion(long long count) { long long o = (foff + 63) & ~63LL; foff = o + count; return fbase + o; }
-  void add(T* dst, long long src, int rows, int cols, long long ld_r, long long ld_c) {
+  void add(T* dst, long long src, int rows, int cols, long long ld_r, long long ld_c, float scale = 1.0f) {
     PrepDesc p; p.src_off = src; p.dst_off = dst - tbase; p.rows = rows; p.cols = cols; p.ld_r = ld_r; p.ld_c = ld_c;
+    p.scale = scale;
     list->t.push_back(p);
   }
   void addf(float* dst, long long src, int n) {
-    PrepDesc p; p.src_off = src; p.dst_off = dst - fbase; p.rows = 1; p.cols = n; p.ld_r = 0; p.ld_c = 1;
+    PrepDesc p; p.src_off = src; p.dst_off = dst - fbase; p.rows = 1; p.cols = n; p.ld_r = 0; p.ld_c = 1; p.scale = 1.0f;
     list->f.push_back(p);
   }
 };
 
-template <typename T> static void prep_attn(PrepCarver<T>& pc, AttnW<T>& w, const AttnP& p, int C, int HD) {
+// The forward copy of the query weights carries log2 e / sqrt(d): the attention kernels take q' = q log2 e / sqrt(d)
+// from the projection and work on base-2 logits q' k without a scale of their own (Section "Evoformer", gated
+// self-attention: logits q k / sqrt(d) + bias).  The copy that the backward GEMM uses is unscaled: the dq kernel returns
+// the gradient with respect to the unscaled q.
+template <typename T> static void prep_attn(PrepCarver<T>& pc, AttnW<T>& w, const AttnP& p, int C, int HD, int dh) {
+  const float qscale = 1.4426950408889634f / sqrtf((float)dh);
   w.wt_qkvg = pc.region((long long)4 * HD * C);
   w.wn_qkvg = pc.region((long long)4 * HD * C);
   w.wt_o = pc.region((long long)HD * C);
   w.wn_o = pc.region((long long)HD * C);
   const long long src[4] = {p.w_q, p.w_k, p.w_v, p.w_g};
   for (int k = 0; k < 4; k++) {
-    pc.add(w.wt_qkvg + (long long)k * HD * C, src[k], C, HD, 1, C);   // [out][in]
+    pc.add(w.wt_qkvg + (long long)k * HD * C, src[k], C, HD, 1, C, k == 0 ? qscale : 1.0f);   // [out][in]
     pc.add(w.wn_qkvg + (long long)k * HD, src[k], C, HD, 4 * HD, 1);  // [in][4HD]
   }
   pc.add(w.wt_o, p.w_o, HD, C, 1, HD);   // [C][HD]
@@ -364,8 +370,8 @@ template <typename T> struct Runner {
     prep_tbase_p = (T*)region(tbytes); prep_fbase_p = (float*)region(fbytes);
     prep_msa.t.clear(); prep_msa.f.clear(); prep_pair.t.clear(); prep_pair.f.clear();
     PrepCarver<T> pm{prep_tbase_m, prep_fbase_m, 0, 0, &prep_msa};
-    prep_attn<T>(pm, W.row, PL.row, d.c_m, HDm);
-    if (!d.col_global) prep_attn<T>(pm, W.col, PL.col, d.c_m, HDm);
+    prep_attn<T>(pm, W.row, PL.row, d.c_m, HDm, d.d_msa);
+    if (!d.col_global) prep_attn<T>(pm, W.col, PL.col, d.c_m, HDm, d.d_msa);
     else {
       const int C_ = d.c_m, dd = d.d_msa, Wg = 2 * HDm + 2 * dd;
       W.gcol.wt_proj = pm.region((long long)Wg * C_); W.gcol.wn_proj = pm.region((long long)Wg * C_);
@@ -394,8 +400,8 @@ template <typename T> struct Runner {
     PrepCarver<T> pp{prep_tbase_p, prep_fbase_p, 0, 0, &prep_pair};
     prep_trimul<T>(pp, W.tmo, PL.tmo, d.c_z, d.c_tri);
     prep_trimul<T>(pp, W.tmi, PL.tmi, d.c_z, d.c_tri);
-    prep_attn<T>(pp, W.tas, PL.tas, d.c_z, HDz);
-    prep_attn<T>(pp, W.tae, PL.tae, d.c_z, HDz);
+    prep_attn<T>(pp, W.tas, PL.tas, d.c_z, HDz, d.d_pair);
+    prep_attn<T>(pp, W.tae, PL.tae, d.c_z, HDz, d.d_pair);
     prep_trans<T>(pp, W.pt, PL.ptrans, d.c_z, d.n_trans);
     return (off + 255) & ~(size_t)255;
   }

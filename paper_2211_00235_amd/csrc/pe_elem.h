@@ -755,6 +755,12 @@ template <typename T> struct BiasChunk { static constexpr int CH = 16 / sizeof(T
 template <typename T> PE_DEV long long bias_chunk_off(int t, int c, int g, int p, int L) {
   return ((((long long)t * BiasChunk<T>::NC + c) * 2 + g) * L + p) * BiasChunk<T>::CH;
 }
+// position inside the 32-wide tile of the other axis that element i of chunk c of lane group g holds in the BIAS planes:
+// bf16 planes are in MFMA B-operand order (the attention kernels add the tile as identity x bias), fp32 planes in
+// accumulator order (added element by element).  dS planes are in accumulator order for both types.
+template <typename T> PE_DEV int bias_slot(int c, int g, int i);
+template <> PE_DEV int bias_slot<bf16>(int c, int g, int i) { return 16 * c + 8 * g + i; }
+template <> PE_DEV int bias_slot<float>(int c, int g, int i) { return 8 * c + 4 * g + i; }
 template <typename T>
 __global__ __launch_bounds__(256) void bias_tile_kernel(const float* direct, T* biasQ, T* biasK, int r, int transposed, float f) {
   constexpr int CH = BiasChunk<T>::CH, NC = BiasChunk<T>::NC;
@@ -778,7 +784,7 @@ __global__ __launch_bounds__(256) void bias_tile_kernel(const float* direct, T* 
     float vq[CH], vk[CH];
 #pragma unroll
     for (int i = 0; i < CH; i++) {
-      const int e = c * CH + i, o = 8 * (e >> 2) + 4 * g + (e & 3);
+      const int o = bias_slot<T>(c, g, i);
       vq[i] = tile[tx][o];
       vk[i] = tile[o][tx];
     }
@@ -1030,7 +1036,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceBatch rb) {
 // ---------------------------------------------------------------------------
 // Parameter preparation: dst[r*ld_r + c*ld_c] = T(src[r*cols + c])
 // ---------------------------------------------------------------------------
-struct PrepDesc { long long src_off, dst_off; int rows, cols; long long ld_r, ld_c; };
+struct PrepDesc { long long src_off, dst_off; int rows, cols; long long ld_r, ld_c; float scale; };   // copy = scale * source
 constexpr int PREP_MAX = 32;
 struct PrepBatch { PrepDesc d[PREP_MAX]; int n; };
 template <typename T>
@@ -1049,7 +1055,7 @@ __global__ __launch_bounds__(256) void prep_params_kernel(const float* params, T
     if (transposed) {
       for (int k = ty; k < 32; k += 8) {
         const int r = r0 + k, c = c0 + tx;
-        tile[k][tx] = (r < d.rows && c < d.cols) ? src[(long long)r * d.cols + c] : 0.0f;
+        tile[k][tx] = (r < d.rows && c < d.cols) ? src[(long long)r * d.cols + c] * d.scale : 0.0f;
       }
       __syncthreads();
       for (int k = ty; k < 32; k += 8) {
@@ -1060,7 +1066,7 @@ __global__ __launch_bounds__(256) void prep_params_kernel(const float* params, T
     } else {
       for (int k = ty; k < 32; k += 8) {
         const int r = r0 + k, c = c0 + tx;
-        if (r < d.rows && c < d.cols) out[r * d.ld_r + c * d.ld_c] = from_f<T>(src[(long long)r * d.cols + c]);
+        if (r < d.rows && c < d.cols) out[r * d.ld_r + c * d.ld_c] = from_f<T>(src[(long long)r * d.cols + c] * d.scale);
       }
     }
   }

@@ -34,8 +34,9 @@ SMALL = 0.25
 # normaliser is itself a small-sample maximum: at the same per-element error the 1-in-100 worst ratio over tensors of
 # 16 entries is 1.77 times that of tensors of 65536 entries, 1.5 times at 33 entries, 1.23 times at 257
 # (tests/test_bf16_relu_band.py::test_max_normalised_metric_by_tensor_size pins these by Monte Carlo).  A block has
-# about a hundred parameter tensors, so that tail is what a test sees.  The benchmark configurations are held to TOL
-# for every tensor; test shapes with 16..64 channels, whose vectors have 16..64 entries, use TOL x size_factor(entries).
+# about a hundred parameter tensors, so that tail is what a test sees: two builds of the HIP path whose relative L2
+# errors agree to 2 % on every tensor differ by 40 % in this metric on single 512-entry tensors.  Every tensor is
+# therefore held to TOL x size_factor(entries); above 4096 entries the factor is 1.
 SIZE_FACTORS = ((32, 1.85), (256, 1.5), (4096, 1.25))
 
 
