@@ -802,7 +802,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PE_DKV_WAVE
   for (int e = 0; e < 16; e++) { dk[e] = 0.0f; dv[e] = 0.0f; }
 
   // Q, dO, -lse and -D of the next 64 queries are loaded into registers while the current ones are used; the bias
-  // tiles one 64-query step ahead of their use
+  // one 32-query tile ahead of its use
   AttnStageRegs<T> rq, rdo;
   float r_lse = 0.0f, r_D = 0.0f;
   auto prefetch = [&](int i0) {
@@ -816,11 +816,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PE_DKV_WAVE
   };
   prefetch(0);
   const int ntile = attn_tiles32(L);
-  BiasTile<T> bt[2];
-  if (has_bias) {
-    attn_load_bias(bplane, L, 0, bcolk, g, bt[0]);
-    attn_load_bias(bplane, L, min(1, ntile - 1), bcolk, g, bt[1]);
-  }
+  BiasTile<T> bt;                       // refilled for the next 32-query tile as soon as its MFMAs have taken it
+  if (has_bias) attn_load_bias(bplane, L, 0, bcolk, g, bt);
   for (int i0 = 0; i0 < L; i0 += C::KT) {
     __syncthreads();
     attn_stage_store<T>(rq, DP, lds_q, lds_qt, tid);
@@ -848,8 +845,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PE_DKV_WAVE
           MM::mma(pacc, MM::load(lds_do + off), vf[kk]);     // dP - D = dO V^T - D
         }
       if (has_bias) {
-        attn_add_bias(sacc, bt[it], idf);
-        attn_load_bias(bplane, L, min((i0 >> 5) + 2 + it, ntile - 1), bcolk, g, bt[it]);
+        attn_add_bias(sacc, bt, idf);
+        attn_load_bias(bplane, L, min((i0 >> 5) + it + 1, ntile - 1), bcolk, g, bt);
       }
       if (wave_masked) {
 #pragma unroll
