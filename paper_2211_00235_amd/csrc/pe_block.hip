@@ -767,7 +767,7 @@ template <typename T> struct Runner {
     a.s = d.s; a.r = d.r; a.H = d.h_msa; a.d = d.d_msa; a.scale = 1.0f / sqrtf((float)d.d_msa);
     return a;
   }
-  void gcol_sub_fwd(hipStream_t st, const T* x, T* xout) {
+  void gcol_sub_fwd(hipStream_t st, Arena& ar, const T* x, T* xout) {
     const AttnP& p = PL.col;
     GlobCtx<T>& c = C.gcol;
     const int Cc = d.c_m, HD = HDm, dd = d.d_msa, Wg = 2 * HD + 2 * dd;
@@ -778,15 +778,20 @@ template <typename T> struct Runner {
       e.bn_begin = HD + 2 * dd;
       gemm(st, op_plain(c.xhat, Cc), true, op_plain(W.gcol.wt_proj, Cc), true, (int)Mm, Wg, Cc, 1, e, "gcol proj");
     }
+    size_t mk = ar.mark();
+    const int chunks = (d.s + gc_chunk_len(HD) - 1) / gc_chunk_len(HD);
+    float* part = (float*)ar.alloc((size_t)chunks * d.r * HD * sizeof(float));
+    float* partm = (float*)ar.alloc((size_t)chunks * d.r * sizeof(float));
     if (!dry && !err) {
       GcolArgs a = gcol_args(c);
-      const double pb = (double)Mm * Wg * sizeof(T);
-      PE_LAUNCH("gcol_qmean", 0, (double)Mm * HD * sizeof(T), st, gcol_qmean_kernel<T>, dim3(d.r), dim3(256), 0, a);
+      a.part = part; a.partm = partm; a.chunks = chunks;
+      PE_LAUNCH("gcol_qmean", 0, (double)Mm * HD * sizeof(T), st, gcol_qmean_kernel<T>, dim3(d.r, chunks), dim3(256), 0, a);
+      PE_LAUNCH("gcol_qmean_fin", 0, 4.0 * chunks * d.r * HD, st, gcol_qmean_fin_kernel, dim3((unsigned)(((long long)d.r * HD + 255) / 256)), dim3(256), 0, a);
       PE_LAUNCH("gcol_attn_fwd", 6.0 * Mm * HD, 3.0 * Mm * 2 * dd * sizeof(T), st, gcol_attn_fwd_kernel<T>, dim3(d.r), dim3(256), 0, a);
       long long n = Mm * HD;
       PE_LAUNCH("gcol_gate_fwd", 0, 2.0 * n * sizeof(T), st, gcol_gate_fwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, a);
-      (void)pb;
     }
+    ar.release(mk);
     {
       EpiGeneric<T> e = epi_plain<T>(xout, Cc);
       e.bias_n = P(p.b_o);
@@ -804,6 +809,8 @@ template <typename T> struct Runner {
     float* dO = (float*)ar.alloc((size_t)d.r * HD * sizeof(float));
     float* dqbar = (float*)ar.alloc((size_t)d.r * HD * sizeof(float));
     T* dxh = (T*)ar.alloc((size_t)Mm * Cc * sizeof(T));
+    const int chunks = (d.s + gc_chunk_len(HD) - 1) / gc_chunk_len(HD);
+    float* part = (float*)ar.alloc((size_t)chunks * d.r * HD * sizeof(float));
     { ReduceSeg sg[1] = {{0, Cc, p.w_o, Cc}}, cb = {0, Cc, p.b_o, 0};
       gemm_dw(st, ar, op_trans(c.og, HD), false, op_trans(g, Cc), false, HD, Cc, Mm, 1, sg, "gcol dWo", 1, &cb); }
     { EpiGeneric<T> e = epi_plain<T>(dog, HD);
@@ -812,7 +819,10 @@ template <typename T> struct Runner {
       GcolArgs a = gcol_args(c);
       a.dproj = dproj; a.dog = dog; a.dO = dO; a.dqbar = dqbar;
       long long n = Mm * HD;
-      PE_LAUNCH("gcol_gate_bwd", 0, 3.0 * n * sizeof(T), st, gcol_gate_bwd_kernel<T>, dim3(d.r), dim3(256), 0, a);
+      a.part = part; a.chunks = chunks;
+      PE_LAUNCH("gcol_gate_bwd", 0, 3.0 * n * sizeof(T), st, gcol_gate_bwd_kernel<T>, dim3(d.r, chunks), dim3(256), 0, a);
+      PE_LAUNCH("gcol_sum_chunks", 0, 4.0 * chunks * d.r * HD, st, gcol_sum_chunks_kernel, dim3((unsigned)(((long long)d.r * HD + 255) / 256)), dim3(256), 0,
+                (const float*)part, dO, chunks, (long long)d.r * HD);
       PE_LAUNCH("gcol_attn_bwd", 12.0 * Mm * HD, 4.0 * Mm * 2 * dd * sizeof(T), st, gcol_attn_bwd_kernel<T>, dim3(d.r), dim3(256), 0, a);
       PE_LAUNCH("gcol_dq", 0, 1.0 * n * sizeof(T), st, gcol_dq_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, a);
     }
@@ -918,7 +928,7 @@ template <typename T> struct Runner {
       attn_sub_fwd(sm, am, PL.row, W.row, C.row, msa_in, C.m1, Mm, d.c_m, d.h_msa, d.d_msa, geom_row(), bias_pair,
                    PL.row.ln_z_g, PL.row.ln_z_b, row_pre_done);
     } else if (i == 1) {
-      if (d.col_global) gcol_sub_fwd(sm, C.m1, C.m2);
+      if (d.col_global) gcol_sub_fwd(sm, am, C.m1, C.m2);
       else attn_sub_fwd(sm, am, PL.col, W.col, C.col, C.m1, C.m2, Mm, d.c_m, d.h_msa, d.d_msa, geom_col(), nullptr, 0, 0);
     } else {
       trans_sub_fwd(sm, PL.mtrans, W.mt, C.mt, C.m2, C.m3, Mm, d.c_m);

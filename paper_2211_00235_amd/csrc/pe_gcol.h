@@ -26,7 +26,12 @@ struct GcolArgs {
   float* dqbar;                     // [r][H*d]
   int s, r, H, d;
   float scale;
+  float* part;                      // [chunks][r][H*d] partial sums over sequence chunks (qmean: numerators; gate_bwd: dO)
+  float* partm;                     // [chunks][r] partial mask sums (qmean)
+  int chunks;                       // sequence chunks of gc_chunk_len(H*d) positions
 };
+// sequence positions per workgroup of the two reductions over s: one batch of GC_UR loads per sequence lane
+static inline int gc_chunk_len(int HD) { return 32 * (256 / HD); }
 
 // d (<= 8) consecutive channels of one (sequence, residue) row -> float[8] (zero beyond d)
 template <typename T> PE_DEV void gc_load_row(const T* p, int d, float (&v)[GC_MAXD]) {
@@ -50,36 +55,53 @@ PE_DEV float block_reduce_max(float v, float* red) {
   return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 
-// qbar[i][hd] = sum_s mask[s][i] q[s][i][hd] / den[i];  grid = r, block = 256 = HD x (256/HD) sequence lanes
+// qbar[i][hd] = sum_s mask[s][i] q[s][i][hd] / den[i], in two stages: grid (r, chunks), block = 256 = HD x (256/HD)
+// sequence lanes; a workgroup sums one chunk of gc_chunk_len(HD) sequence positions of one residue (GC_UR independent
+// loads in flight per thread) into part / partm, gcol_qmean_fin_kernel adds the chunks in order.  (One workgroup per
+// residue walking the whole sequence axis ran at 0.2 TB/s: 256 workgroups, each a chain of dependent load rounds.)
 template <typename T>
 __global__ __launch_bounds__(256) void gcol_qmean_kernel(GcolArgs a) {
   __shared__ float red[256], redm[256];
-  const int i = blockIdx.x, HD = a.H * a.d, Wg = 2 * HD + 2 * a.d;
+  const int i = blockIdx.x, ch = blockIdx.y, HD = a.H * a.d, Wg = 2 * HD + 2 * a.d;
   const int SL = 256 / HD, hd = threadIdx.x % HD, sl = threadIdx.x / HD;
   const T* q = (const T*)a.proj + (long long)i * Wg + hd;
   float acc = 0.0f, msum = 0.0f;
-  if (sl < SL)
-    for (int t0 = sl; t0 < a.s; t0 += GC_UR * SL) {   // GC_UR independent loads in flight per thread
-      float mk[GC_UR], qv[GC_UR];
+  if (sl < SL) {
+    const int t0 = ch * (GC_UR * SL) + sl;
+    float mk[GC_UR], qv[GC_UR];
 #pragma unroll
-      for (int u = 0; u < GC_UR; u++) {
-        const int t = t0 + u * SL;
-        const bool ok = t < a.s;
-        mk[u] = ok ? a.mask[(long long)t * a.r + i] : 0.0f;
-        qv[u] = ok ? to_f(q[(long long)t * a.r * Wg]) : 0.0f;
-      }
-#pragma unroll
-      for (int u = 0; u < GC_UR; u++) { acc += mk[u] * qv[u]; msum += mk[u]; }
+    for (int u = 0; u < GC_UR; u++) {
+      const int t = t0 + u * SL;
+      const bool ok = t < a.s;
+      mk[u] = ok ? a.mask[(long long)t * a.r + i] : 0.0f;
+      qv[u] = ok ? to_f(q[(long long)t * a.r * Wg]) : 0.0f;
     }
+#pragma unroll
+    for (int u = 0; u < GC_UR; u++) { acc += mk[u] * qv[u]; msum += mk[u]; }
+  }
   red[threadIdx.x] = acc;
   redm[threadIdx.x] = msum;
   __syncthreads();
   if (sl == 0) {
     for (int k = 1; k < SL; k++) { acc += red[k * HD + hd]; msum += redm[k * HD + hd]; }
-    float den = msum + 1e-10f;
-    a.qbar[(long long)i * HD + hd] = acc / den;
-    if (hd == 0) a.den[i] = den;
+    a.part[((long long)ch * a.r + i) * HD + hd] = acc;
+    if (hd == 0) a.partm[(long long)ch * a.r + i] = msum;
   }
+}
+// grid = ceil(r * HD / 256)
+__global__ __launch_bounds__(256) void gcol_qmean_fin_kernel(GcolArgs a) {
+  const int HD = a.H * a.d;
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long long)a.r * HD) return;
+  const int i = (int)(idx / HD);
+  float acc = 0.0f, msum = 0.0f;
+  for (int c = 0; c < a.chunks; c++) {
+    acc += a.part[(long long)c * a.r * HD + idx];
+    msum += a.partm[(long long)c * a.r + i];
+  }
+  const float den = msum + 1e-10f;
+  a.qbar[idx] = acc / den;
+  if (idx % HD == 0) a.den[i] = den;
 }
 
 // softmax over the sequence axis and weighted value sum; grid = r, block = 256.
@@ -222,42 +244,51 @@ __global__ void gcol_gate_fwd_kernel(GcolArgs a) {
   ((T*)a.og)[idx] = from_f<T>(sigmoidf_(g) * a.o[(long long)i * HD + hd]);
 }
 
-// dO[i][hd] = sum_t dog * sigmoid(g);  dgate = dog * o * s(1-s) -> dproj gate slot.  grid = r
+// dO[i][hd] = sum_t dog * sigmoid(g);  dgate = dog * o * s(1-s) -> dproj gate slot.  Two stages like the mean query:
+// grid (r, chunks) writes the chunk sums to part, gcol_sum_chunks_kernel adds them in order.
 template <typename T>
 __global__ __launch_bounds__(256) void gcol_gate_bwd_kernel(GcolArgs a) {
   __shared__ float red[256];
-  const int i = blockIdx.x, HD = a.H * a.d, Wg = 2 * HD + 2 * a.d;
+  const int i = blockIdx.x, ch = blockIdx.y, HD = a.H * a.d, Wg = 2 * HD + 2 * a.d;
   const int SL = 256 / HD, hd = threadIdx.x % HD, sl = threadIdx.x / HD;
   const float ov = a.o[(long long)i * HD + hd];
   float acc = 0.0f;
-  if (sl < SL)
-    for (int t0 = sl; t0 < a.s; t0 += GC_UR * SL) {   // loads of GC_UR sequence positions first, then the arithmetic
-      float gv[GC_UR], dv[GC_UR];
+  if (sl < SL) {
+    const int t0 = ch * (GC_UR * SL) + sl;
+    float gv[GC_UR], dv[GC_UR];   // loads of GC_UR sequence positions first, then the arithmetic
 #pragma unroll
-      for (int u = 0; u < GC_UR; u++) {
-        const int t = t0 + u * SL;
-        const bool ok = t < a.s;
-        const long long pos = (long long)(ok ? t : 0) * a.r + i;
-        gv[u] = to_f(((const T*)a.proj)[pos * Wg + HD + 2 * a.d + hd]);
-        dv[u] = ok ? to_f(((const T*)a.dog)[pos * HD + hd]) : 0.0f;
-      }
+    for (int u = 0; u < GC_UR; u++) {
+      const int t = t0 + u * SL;
+      const bool ok = t < a.s;
+      const long long pos = (long long)(ok ? t : 0) * a.r + i;
+      gv[u] = to_f(((const T*)a.proj)[pos * Wg + HD + 2 * a.d + hd]);
+      dv[u] = ok ? to_f(((const T*)a.dog)[pos * HD + hd]) : 0.0f;
+    }
 #pragma unroll
-      for (int u = 0; u < GC_UR; u++) {
-        const int t = t0 + u * SL;
-        if (t < a.s) {
-          const long long pos = (long long)t * a.r + i;
-          float sg = sigmoidf_(gv[u]);
-          acc += dv[u] * sg;
-          ((T*)a.dproj)[pos * Wg + HD + 2 * a.d + hd] = from_f<T>(dv[u] * ov * sg * (1.0f - sg));
-        }
+    for (int u = 0; u < GC_UR; u++) {
+      const int t = t0 + u * SL;
+      if (t < a.s) {
+        const long long pos = (long long)t * a.r + i;
+        float sg = sigmoidf_(gv[u]);
+        acc += dv[u] * sg;
+        ((T*)a.dproj)[pos * Wg + HD + 2 * a.d + hd] = from_f<T>(dv[u] * ov * sg * (1.0f - sg));
       }
     }
+  }
   red[threadIdx.x] = acc;
   __syncthreads();
   if (sl == 0) {
     for (int k = 1; k < SL; k++) acc += red[k * HD + hd];
-    a.dO[(long long)i * HD + hd] = acc;
+    a.part[((long long)ch * a.r + i) * HD + hd] = acc;
   }
+}
+// out[idx] = sum_c part[c][idx], idx < n;  grid = ceil(n / 256)
+__global__ __launch_bounds__(256) void gcol_sum_chunks_kernel(const float* part, float* out, int chunks, long long n) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= n) return;
+  float acc = 0.0f;
+  for (int c = 0; c < chunks; c++) acc += part[(long long)c * n + idx];
+  out[idx] = acc;
 }
 
 // softmax backward per residue: dk, dv -> dproj; dqbar.  grid = r, block = 256; same batching
