@@ -43,5 +43,20 @@ def build_host_check(out, verbose=False):
     return out
 
 
+def build_attn_bench(out=None, verbose=False):
+    """Stand-alone timing program of the attention kernels (csrc/bench/attn_bench.hip); returns its path."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = out or os.path.join(HERE, "attn_bench")
+    flags = [f for f in FLAGS if f not in ("-shared", "-fPIC")] + ["-Wno-implicit-const-int-float-conversion"]
+    cmd = [hipcc] + flags + [os.path.join(CSRC, "bench", "attn_bench.hip"), "-o", out]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if verbose or res.returncode:
+        print("\n".join(l for l in (res.stdout + res.stderr).splitlines() if "packed-fp32-ops" not in l))
+    if res.returncode:
+        raise RuntimeError("hipcc failed building %s" % out)
+    return out
+
+
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    print(build_attn_bench(verbose=True) if "attn_bench" in sys.argv[1:] else build(verbose=True))
