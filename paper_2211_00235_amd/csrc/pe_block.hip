@@ -876,7 +876,21 @@ template <typename T> struct Runner {
       if (outgoing) gemm(st, op_plain(c.a_t, r, Mz), true, op_plain(c.b_t, r, Mz), true, r, r, r, ct, e, "trimul out");
       else gemm(st, op_trans(c.a_t, r, Mz), false, op_trans(c.b_t, r, Mz), false, r, r, r, ct, e, "trimul in");
     }
-    if (!dry && !err) {
+    bool lnc_t = false;   // bf16, 64 or 128 channels: the kernels that move 256-byte runs
+    if constexpr (std::is_same<T, bf16>::value)
+      lnc_t = (ct == 64 || ct == 128) && Mz % 8 == 0 && al16(c.x_t) && al16(c.xhat);
+    if (!dry && !err && lnc_t) {
+      if constexpr (std::is_same<T, bf16>::value) {
+        const unsigned g128 = (unsigned)((Mz + 127) / 128);
+        if (ct == 128)
+          PE_LAUNCH("ln_cmajor_fwd", 0, 2.0 * Mz * ct * sizeof(T), st, ln_cmajor_fwd_t_kernel<16>, dim3(g128), dim3(256), 0, c.x_t, P(p.ln_out_g),
+                    P(p.ln_out_b), c.xhat, c.stats_out, Mz, d.ln_eps);
+        else
+          PE_LAUNCH("ln_cmajor_fwd", 0, 2.0 * Mz * ct * sizeof(T), st, ln_cmajor_fwd_t_kernel<8>, dim3(g128), dim3(256), 0, c.x_t, P(p.ln_out_g),
+                    P(p.ln_out_b), c.xhat, c.stats_out, Mz, d.ln_eps);
+      }
+    }
+    if (!dry && !err && !lnc_t) {
       size_t lds = (size_t)64 * (ct + 1) * sizeof(float);
 #define PE_LNC_FWD(N) PE_LAUNCH("ln_cmajor_fwd", 0, 2.0 * Mz * ct * sizeof(T), st, (ln_cmajor_fwd_fast_kernel<T, N>), dim3((unsigned)((Mz + 63) / 64)), dim3(256), lds, c.x_t, P(p.ln_out_g), P(p.ln_out_b), c.xhat, c.stats_out, Mz, ct, d.ln_eps)
       if (Mz % 4 == 0 && ct % 8 == 0) {
@@ -1165,9 +1179,24 @@ template <typename T> struct Runner {
     { EpiGeneric<T> e = epi_plain<T>(dxh_o, ct);
       gemm(st, op_plain(du, cz), true, op_plain(w.wn_o, cz), true, (int)Mz, ct, cz, 1, e, "trimul dxhat_o"); }
     {  // LayerNorm (channel-major input) backward
-      int grid = (int)((Mz + 63) / 64);
+      bool lnc_t = false;   // bf16, 64 or 128 channels: the kernel that moves 256-byte runs (128 positions per workgroup)
+      if constexpr (std::is_same<T, bf16>::value)
+        lnc_t = (ct == 64 || ct == 128) && Mz % 8 == 0 && al16(c.x_t) && al16(dxh_o) && al16(dx_t);
+      int grid = lnc_t ? (int)((Mz + 127) / 128) : (int)((Mz + 63) / 64);
       float* part = (float*)part_arena(ar).alloc((size_t)grid * 2 * ct * sizeof(float));
-      if (!dry && !err) {
+      if (!dry && !err && lnc_t) {
+        if constexpr (std::is_same<T, bf16>::value) {
+          if (ct == 128)
+            PE_LAUNCH("ln_cmajor_bwd", 0, 3.0 * Mz * ct * sizeof(T), st, ln_cmajor_bwd_t_kernel<16>, dim3(grid), dim3(256), 0, dxh_o, c.x_t, c.stats_out,
+                      P(p.ln_out_g), dx_t, part, Mz);
+          else
+            PE_LAUNCH("ln_cmajor_bwd", 0, 3.0 * Mz * ct * sizeof(T), st, ln_cmajor_bwd_t_kernel<8>, dim3(grid), dim3(256), 0, dxh_o, c.x_t, c.stats_out,
+                      P(p.ln_out_g), dx_t, part, Mz);
+          ReduceSeg sg[2] = {{0, ct, p.ln_out_g, 0}, {ct, ct, p.ln_out_b, 0}};
+          reduce_to(ar, part, grid, 2LL * ct, 1, 2 * ct, 2, sg);
+        }
+      }
+      if (!dry && !err && !lnc_t) {
         size_t lds = (size_t)64 * (ct + 1) * sizeof(float);
 #define PE_LNC_BWD(N) PE_LAUNCH("ln_cmajor_bwd", 0, 3.0 * Mz * ct * sizeof(T), st, (ln_cmajor_bwd_fast_kernel<T, N>), dim3(grid), dim3(256), lds, dxh_o, c.x_t, c.stats_out, P(p.ln_out_g), dx_t, part, Mz, ct)
         if (Mz % 4 == 0 && ct % 8 == 0) {

@@ -550,6 +550,162 @@ __global__ __launch_bounds__(256) void ln_cmajor_bwd_fast_kernel(const T* dy, co
 }
 
 // ---------------------------------------------------------------------------
+// Channel-major LayerNorm, bf16, C = 8 * LPR channels (64 or 128): the variants that move 256-byte runs.
+// A workgroup handles 128 consecutive positions.  The channel-major side is read / written in 16-byte vectors of 8
+// positions (16 lanes cover one channel's 256-byte run; the 64-position kernels above move 128-byte runs and reach
+// 1.6 - 2.5 TB/s) and transposed through an LDS tile [position][channel] whose 8-channel groups are XOR-swizzled
+// with (position / 8): the scalar transposing accesses of a wave and the 16-byte row accesses are both free of
+// bank conflicts.  Per position the arithmetic is that of the channel-last kernels (LPR lanes per position, 8
+// channels each).  All loads of a workgroup are issued before the first wait.  Needs M % 8 == 0.
+// ---------------------------------------------------------------------------
+template <int LPR> struct LnCmT {
+  static constexpr int C = 8 * LPR, PT = 128, PV = PT / 8, NV = C * PV / 256, RPI = 256 / LPR, NIT = PT / RPI;
+  // element offset of (position p, channel c) in the tile
+  static PE_DEV int off(int p, int c) { return p * C + ((((c >> 3) ^ (p >> 3)) & (LPR - 1)) << 3) + (c & 7); }
+};
+template <int LPR>
+PE_DEV void lncm_load_tile(const bf16* xt, long long M, long long m0, bf16x8 (&xr)[LnCmT<LPR>::NV]) {
+  typedef LnCmT<LPR> K;
+#pragma unroll
+  for (int i = 0; i < K::NV; i++) {
+    const int idx = threadIdx.x + 256 * i, pv = idx % K::PV, ch = idx / K::PV;
+    const long long pos = m0 + 8 * pv;
+    bf16x8 v;
+#pragma unroll
+    for (int k = 0; k < 8; k++) v[k] = (bf16)0.0f;
+    if (pos < M) v = *reinterpret_cast<const bf16x8*>(xt + (long long)ch * M + pos);
+    xr[i] = v;
+  }
+}
+template <int LPR>
+PE_DEV void lncm_store_tile(const bf16x8 (&xr)[LnCmT<LPR>::NV], bf16* tile) {
+  typedef LnCmT<LPR> K;
+#pragma unroll
+  for (int i = 0; i < K::NV; i++) {
+    const int idx = threadIdx.x + 256 * i, pv = idx % K::PV, ch = idx / K::PV;
+#pragma unroll
+    for (int k = 0; k < 8; k++) tile[K::off(8 * pv + k, ch)] = xr[i][k];
+  }
+}
+
+template <int LPR>
+__global__ __launch_bounds__(256) void ln_cmajor_fwd_t_kernel(const bf16* xt, const float* gamma, const float* beta,
+                                                              bf16* y, float* stats, long long M, float eps) {
+  typedef LnCmT<LPR> K;
+  constexpr int C = K::C;
+  __shared__ __attribute__((aligned(16))) bf16 tile[K::PT * C];
+  const long long m0 = (long long)blockIdx.x * K::PT;
+  const int sub = threadIdx.x % LPR, rr = threadIdx.x / LPR, c0 = sub * 8;
+  bf16x8 xr[K::NV];
+  lncm_load_tile<LPR>(xt, M, m0, xr);
+  float gm[8], bt[8];
+#pragma unroll
+  for (int e = 0; e < 8; e++) { gm[e] = gamma[c0 + e]; bt[e] = beta[c0 + e]; }
+  lncm_store_tile<LPR>(xr, tile);
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < K::NIT; it++) {
+    const int p = it * K::RPI + rr;
+    const long long row = m0 + p;
+    const bf16x8 xb = *reinterpret_cast<const bf16x8*>(tile + K::off(p, c0));
+    float xv[8], s = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; e++) { xv[e] = (float)xb[e]; s += xv[e]; }
+    const float mu = group_sum<LPR>(s) * (1.0f / C);
+    float q = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; e++) { const float t = xv[e] - mu; q += t * t; }
+    const float rstd = rsqrtf(group_sum<LPR>(q) * (1.0f / C) + eps);
+    if (row < M) {
+      float o[8];
+#pragma unroll
+      for (int e = 0; e < 8; e++) o[e] = (xv[e] - mu) * rstd * gm[e] + bt[e];
+      st8<bf16>(y + row * C + c0, o);
+      if (sub == 0) { stats[row * 2] = mu; stats[row * 2 + 1] = rstd; }
+    }
+  }
+}
+
+template <int LPR>
+__global__ __launch_bounds__(256) void ln_cmajor_bwd_t_kernel(const bf16* dy, const bf16* xt, const float* stats,
+                                                              const float* gamma, bf16* dxt, float* partial, long long M) {
+  typedef LnCmT<LPR> K;
+  constexpr int C = K::C;
+  __shared__ __attribute__((aligned(16))) bf16 tile[K::PT * C];
+  __shared__ float red[4][2 * C];
+  const long long m0 = (long long)blockIdx.x * K::PT;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = threadIdx.x % LPR, rr = threadIdx.x / LPR, c0 = sub * 8;
+  bf16x8 xr[K::NV];
+  lncm_load_tile<LPR>(xt, M, m0, xr);
+  // cotangent rows and statistics of this thread's positions: requested before the tile is waited for
+  bf16x8 dyr[K::NIT];
+  float mu[K::NIT], rstd[K::NIT];
+#pragma unroll
+  for (int it = 0; it < K::NIT; it++) {
+    const long long row = m0 + it * K::RPI + rr;
+    const bool ok = row < M;
+#pragma unroll
+    for (int k = 0; k < 8; k++) dyr[it][k] = (bf16)0.0f;
+    if (ok) dyr[it] = *reinterpret_cast<const bf16x8*>(dy + row * C + c0);
+    mu[it] = ok ? stats[row * 2] : 0.0f;
+    rstd[it] = ok ? stats[row * 2 + 1] : 0.0f;
+  }
+  float gm[8], dgs[8], dbs[8];
+#pragma unroll
+  for (int e = 0; e < 8; e++) { gm[e] = gamma[c0 + e]; dgs[e] = 0.0f; dbs[e] = 0.0f; }
+  lncm_store_tile<LPR>(xr, tile);
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < K::NIT; it++) {
+    const int p = it * K::RPI + rr;
+    bf16* slot = tile + K::off(p, c0);
+    const bf16x8 xb = *reinterpret_cast<const bf16x8*>(slot);
+    float xh[8], dxh[8], s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      const float dv = (float)dyr[it][e];
+      xh[e] = ((float)xb[e] - mu[it]) * rstd[it];
+      dxh[e] = dv * gm[e];
+      dgs[e] += dv * xh[e];
+      dbs[e] += dv;
+      s1 += dxh[e];
+      s2 += dxh[e] * xh[e];
+    }
+    s1 = group_sum<LPR>(s1) * (1.0f / C);
+    s2 = group_sum<LPR>(s2) * (1.0f / C);
+    bf16x8 ob;
+#pragma unroll
+    for (int e = 0; e < 8; e++) ob[e] = (bf16)((dxh[e] - s1 - xh[e] * s2) * rstd[it]);
+    *reinterpret_cast<bf16x8*>(slot) = ob;     // the slot belongs to this thread alone
+  }
+  __syncthreads();
+  // transposed copy out: 8 positions of one channel per 16-byte store
+#pragma unroll
+  for (int i = 0; i < K::NV; i++) {
+    const int idx = threadIdx.x + 256 * i, pv = idx % K::PV, ch = idx / K::PV;
+    const long long pos = m0 + 8 * pv;
+    bf16x8 v;
+#pragma unroll
+    for (int k = 0; k < 8; k++) v[k] = tile[K::off(8 * pv + k, ch)];
+    if (pos < M) *reinterpret_cast<bf16x8*>(dxt + (long long)ch * M + pos) = v;
+  }
+  // gain / offset partials of the workgroup: positions of a wave hold the same channels in lanes sub, sub + LPR, ...
+#pragma unroll
+  for (int e = 0; e < 8; e++) {
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1) { dgs[e] += __shfl_xor(dgs[e], o, 64); dbs[e] += __shfl_xor(dbs[e], o, 64); }
+  }
+  if (lane < LPR) {
+#pragma unroll
+    for (int e = 0; e < 8; e++) { red[wave][c0 + e] = dgs[e]; red[wave][C + c0 + e] = dbs[e]; }
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < 2 * C; c += 256)
+    partial[(long long)blockIdx.x * 2 * C + c] = red[0][c] + red[1][c] + red[2][c] + red[3][c];
+}
+
+// ---------------------------------------------------------------------------
 // Pair-bias projection fused with its LayerNorm: bias[h][i][j] = (LN(z_ij) W)_h
 // (transposed: bias[h][j][i]); biasT holds the other orientation multiplied by log2(e),
 // the form the base-2 softmax of the query-per-lane attention kernels reads.  C <= 256 (one 4-channel chunk per lane).
