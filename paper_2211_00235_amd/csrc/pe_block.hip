@@ -718,7 +718,7 @@ template <typename T> struct Runner {
         int transposed = g.bias_transposed;
         if (fast) {
           const int rpw = 64 / lpr;
-          int grid = (int)std::min<long long>((Mz + 4 * rpw - 1) / (4 * rpw), 8192);
+          int grid = (int)std::min<long long>((Mz + 4 * rpw * LNB_UN - 1) / (4 * rpw * LNB_UN), 2048);
 #define PE_LNB_FWD(L, HH) PE_LAUNCH("ln_bias_fwd", fl, by, st, (ln_bias_fwd_fast_kernel<T, L, HH>), dim3(grid), dim3(256), 0, bias_src, P(bias_ln_g), P(bias_ln_b), P(p.w_bias), direct, 1.0f, c.zstats, d.r, H, d.ln_eps)
 #define PE_LNB_FWD_H(L) do { if (H <= 4) PE_LNB_FWD(L, 4); else PE_LNB_FWD(L, 8); } while (0)
           switch (lpr) {

@@ -845,6 +845,7 @@ PE_DEV void bias_stage_w(const float* w, int H, float (*sw)[8 * HH + 4], int sub
     for (int h = 0; h < HH; h++) wv[e][h] = sw[sub][e * HH + h];
 }
 
+constexpr int LNB_UN = 4;   // rows per lane group and step (the 16-byte stores below assume 4)
 template <typename T, int LPR, int HH>
 __global__ __launch_bounds__(256) void ln_bias_fwd_fast_kernel(const T* z, const float* gamma, const float* beta,
                                                                const float* w, float* direct, float direct_scale,
@@ -860,35 +861,65 @@ __global__ __launch_bounds__(256) void ln_bias_fwd_fast_kernel(const T* z, const
   for (int e = 0; e < 8; e++) { gm[e] = gamma[c0 + e]; bt[e] = beta[c0 + e]; }
   bias_stage_w<LPR, HH>(w, H, sw, sub, wv);
   const long long M = (long long)r * r;
-  const long long stride = (long long)gridDim.x * 4 * RPW;
-  for (long long row = ((long long)blockIdx.x * 4 + wave) * RPW + rw; row < M + rw; row += stride) {
-    const bool ok = row < M;
-    float v[8];
-    if (ok) ld8<T>(z + row * C + c0, v);
-    else {
+  // A lane group handles LNB_UN = 4 CONSECUTIVE rows per step (loads of all four issued before the first is used), so
+  // that its lane 0 writes the four rows' value of a head with one 16-byte store and their statistics with two: with
+  // one row per step the outputs left as 4-byte stores, one per row and head, and those bounded the kernel.
+  const long long wg_rows = 4LL * RPW * LNB_UN, stride = (long long)gridDim.x * wg_rows;
+  for (long long base = (long long)blockIdx.x * wg_rows + (wave * RPW + rw) * LNB_UN; base < M + (wave * RPW + rw) * LNB_UN; base += stride) {
+    typename Vec16<T>::type raw[LNB_UN][sizeof(T) == 2 ? 1 : 2];
 #pragma unroll
-      for (int e = 0; e < 8; e++) v[e] = 0.0f;
+    for (int u = 0; u < LNB_UN; u++) {
+      const long long row = base + u;
+      const T* src = z + (row < M ? row : 0) * C + c0;
+#pragma unroll
+      for (int q = 0; q < (sizeof(T) == 2 ? 1 : 2); q++) raw[u][q] = *reinterpret_cast<const typename Vec16<T>::type*>(src + q * Vec16<T>::N);
     }
-    float s = 0.0f;
+    float outv[HH][LNB_UN], st[2 * LNB_UN];
 #pragma unroll
-    for (int e = 0; e < 8; e++) s += v[e];
-    float mu = group_sum<LPR>(s) * (1.0f / C);
-    float q = 0.0f;
+    for (int u = 0; u < LNB_UN; u++) {
+      const bool ok = base + u < M;
+      float v[8];
 #pragma unroll
-    for (int e = 0; e < 8; e++) { float t = v[e] - mu; q += t * t; }
-    float rstd = rsqrtf(group_sum<LPR>(q) * (1.0f / C) + eps);
-    float y[8];
+      for (int e = 0; e < 8; e++) v[e] = ok ? to_f<T>(raw[u][e / Vec16<T>::N][e % Vec16<T>::N]) : 0.0f;
+      float s = 0.0f;
 #pragma unroll
-    for (int e = 0; e < 8; e++) y[e] = (v[e] - mu) * rstd * gm[e] + bt[e];
+      for (int e = 0; e < 8; e++) s += v[e];
+      float mu = group_sum<LPR>(s) * (1.0f / C);
+      float q = 0.0f;
 #pragma unroll
-    for (int h = 0; h < HH; h++) {
-      float t = 0.0f;
+      for (int e = 0; e < 8; e++) { float t = v[e] - mu; q += t * t; }
+      float rstd = rsqrtf(group_sum<LPR>(q) * (1.0f / C) + eps);
+      float y[8];
 #pragma unroll
-      for (int e = 0; e < 8; e++) t += y[e] * wv[e][h];
-      t = group_sum<LPR>(t);
-      if (ok && sub == 0 && h < H) direct[(long long)h * M + row] = t * direct_scale;
+      for (int e = 0; e < 8; e++) y[e] = (v[e] - mu) * rstd * gm[e] + bt[e];
+#pragma unroll
+      for (int h = 0; h < HH; h++) {
+        float t = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; e++) t += y[e] * wv[e][h];
+        outv[h][u] = group_sum<LPR>(t) * direct_scale;
+      }
+      st[2 * u] = mu; st[2 * u + 1] = rstd;
     }
-    if (ok && sub == 0) { stats[row * 2] = mu; stats[row * 2 + 1] = rstd; }
+    if (sub == 0 && base < M) {
+      if (base + LNB_UN <= M && (M & 3) == 0) {      // rows base .. base+3 exist and the stores are 16-byte aligned
+#pragma unroll
+        for (int h = 0; h < HH; h++)
+          if (h < H) store4<float>(direct + (long long)h * M + base, outv[h]);
+        float s0[4] = {st[0], st[1], st[2], st[3]}, s1[4] = {st[4], st[5], st[6], st[7]};
+        store4<float>(stats + base * 2, s0);
+        store4<float>(stats + base * 2 + 4, s1);
+      } else {
+#pragma unroll
+        for (int u = 0; u < LNB_UN; u++)
+          if (base + u < M) {
+#pragma unroll
+            for (int h = 0; h < HH; h++)
+              if (h < H) direct[(long long)h * M + base + u] = outv[h][u];
+            stats[(base + u) * 2] = st[2 * u]; stats[(base + u) * 2 + 1] = st[2 * u + 1];
+          }
+      }
+    }
   }
 }
 
