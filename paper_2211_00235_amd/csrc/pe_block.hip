@@ -789,7 +789,10 @@ template <typename T> struct Runner {
       PE_LAUNCH("gcol_qmean_fin", 0, 4.0 * chunks * d.r * HD, st, gcol_qmean_fin_kernel, dim3((unsigned)(((long long)d.r * HD + 255) / 256)), dim3(256), 0, a);
       PE_LAUNCH("gcol_attn_fwd", 6.0 * Mm * HD, 3.0 * Mm * 2 * dd * sizeof(T), st, gcol_attn_fwd_kernel<T>, dim3(d.r), dim3(256), 0, a);
       long long n = Mm * HD;
-      PE_LAUNCH("gcol_gate_fwd", 0, 2.0 * n * sizeof(T), st, gcol_gate_fwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, a);
+      if (HD % 8 == 0 && dd % 4 == 0)
+        PE_LAUNCH("gcol_gate_fwd", 0, 2.0 * n * sizeof(T), st, gcol_gate_fwd8_kernel<T>, dim3((unsigned)((n / 8 + 255) / 256)), dim3(256), 0, a);
+      else
+        PE_LAUNCH("gcol_gate_fwd", 0, 2.0 * n * sizeof(T), st, gcol_gate_fwd_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, a);
     }
     ar.release(mk);
     {
@@ -824,7 +827,10 @@ template <typename T> struct Runner {
       PE_LAUNCH("gcol_sum_chunks", 0, 4.0 * chunks * d.r * HD, st, gcol_sum_chunks_kernel, dim3((unsigned)(((long long)d.r * HD + 255) / 256)), dim3(256), 0,
                 (const float*)part, dO, chunks, (long long)d.r * HD);
       PE_LAUNCH("gcol_attn_bwd", 12.0 * Mm * HD, 4.0 * Mm * 2 * dd * sizeof(T), st, gcol_attn_bwd_kernel<T>, dim3(d.r), dim3(256), 0, a);
-      PE_LAUNCH("gcol_dq", 0, 1.0 * n * sizeof(T), st, gcol_dq_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, a);
+      if (HD % 8 == 0 && dd % 4 == 0)
+        PE_LAUNCH("gcol_dq", 0, 1.0 * n * sizeof(T), st, gcol_dq8_kernel<T>, dim3((unsigned)((n / 8 + 255) / 256)), dim3(256), 0, a);
+      else
+        PE_LAUNCH("gcol_dq", 0, 1.0 * n * sizeof(T), st, gcol_dq_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, a);
     }
     { ReduceSeg sg[4] = {{0, HD, p.w_q, HD}, {HD, dd, p.w_k, dd}, {HD + dd, dd, p.w_v, dd}, {HD + 2 * dd, HD, p.w_g, HD}};
       ReduceSeg cb = {HD + 2 * dd, HD, p.b_g, 0};

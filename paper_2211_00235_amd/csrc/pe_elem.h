@@ -1224,7 +1224,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceBatch rb) {
 // Parameter preparation: dst[r*ld_r + c*ld_c] = T(src[r*cols + c])
 // ---------------------------------------------------------------------------
 struct PrepDesc { long long src_off, dst_off; int rows, cols; long long ld_r, ld_c; float scale; };   // copy = scale * source
-constexpr int PREP_MAX = 32;
+constexpr int PREP_MAX = 64;   // descriptors per launch (3 KB of kernel arguments)
 struct PrepBatch { PrepDesc d[PREP_MAX]; int n; };
 template <typename T>
 __global__ __launch_bounds__(256) void prep_params_kernel(const float* params, T* dst, PrepBatch pb) {
@@ -1390,12 +1390,12 @@ __global__ void opm_norm_kernel(const float* mask, float* inv_norm, int s, int r
   int i = idx / r, j = idx % r;
   float acc = 0.0f;   // 0/1 products: any summation order gives the same (exact) count
   int t = 0;
-  for (; t + 8 <= s; t += 8) {
-    float a[8], b[8];
+  for (; t + 32 <= s; t += 32) {   // 64 independent loads in flight per thread: the loop is a chain of memory round trips
+    float a[32], b[32];
 #pragma unroll
-    for (int u = 0; u < 8; u++) { a[u] = mask[(long long)(t + u) * r + i]; b[u] = mask[(long long)(t + u) * r + j]; }
+    for (int u = 0; u < 32; u++) { a[u] = mask[(long long)(t + u) * r + i]; b[u] = mask[(long long)(t + u) * r + j]; }
 #pragma unroll
-    for (int u = 0; u < 8; u++) acc += a[u] * b[u];
+    for (int u = 0; u < 32; u++) acc += a[u] * b[u];
   }
   for (; t < s; t++) acc += mask[(long long)t * r + i] * mask[(long long)t * r + j];
   inv_norm[idx] = 1.0f / (eps + acc);

@@ -244,6 +244,23 @@ __global__ void gcol_gate_fwd_kernel(GcolArgs a) {
   ((T*)a.og)[idx] = from_f<T>(sigmoidf_(g) * a.o[(long long)i * HD + hd]);
 }
 
+// the same with 8 consecutive channels per thread (16-byte accesses): needs (H*d) % 8 == 0 and d % 4 == 0
+template <typename T>
+__global__ __launch_bounds__(256) void gcol_gate_fwd8_kernel(GcolArgs a) {
+  const int HD = a.H * a.d, Wg = 2 * HD + 2 * a.d, HD8 = HD >> 3;
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long long)a.s * a.r * HD8) return;
+  const int hd0 = (int)(idx % HD8) * 8;
+  const long long pos = idx / HD8;
+  const int i = (int)(pos % a.r);
+  float g[8], o[8];
+  ld8<T>((const T*)a.proj + pos * Wg + HD + 2 * a.d + hd0, g);
+  ld8<float>(a.o + (long long)i * HD + hd0, o);
+#pragma unroll
+  for (int e = 0; e < 8; e++) o[e] *= sigmoidf_(g[e]);
+  st8<T>((T*)a.og + pos * HD + hd0, o);
+}
+
 // dO[i][hd] = sum_t dog * sigmoid(g);  dgate = dog * o * s(1-s) -> dproj gate slot.  Two stages like the mean query:
 // grid (r, chunks) writes the chunk sums to part, gcol_sum_chunks_kernel adds them in order.
 template <typename T>
@@ -415,4 +432,21 @@ __global__ void gcol_dq_kernel(GcolArgs a) {
   long long pos = idx / HD;
   int i = pos % a.r;
   ((T*)a.dproj)[pos * Wg + hd] = from_f<T>(a.mask[pos] * a.dqbar[(long long)i * HD + hd] / a.den[i]);
+}
+
+// the same with 8 consecutive channels per thread (16-byte stores): needs (H*d) % 8 == 0 and d % 4 == 0
+template <typename T>
+__global__ __launch_bounds__(256) void gcol_dq8_kernel(GcolArgs a) {
+  const int HD = a.H * a.d, Wg = 2 * HD + 2 * a.d, HD8 = HD >> 3;
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long long)a.s * a.r * HD8) return;
+  const int hd0 = (int)(idx % HD8) * 8;
+  const long long pos = idx / HD8;
+  const int i = (int)(pos % a.r);
+  float v[8];
+  ld8<float>(a.dqbar + (long long)i * HD + hd0, v);
+  const float f = a.mask[pos], den = a.den[i];
+#pragma unroll
+  for (int e = 0; e < 8; e++) v[e] = f * v[e] / den;
+  st8<T>((T*)a.dproj + pos * Wg + hd0, v);
 }
