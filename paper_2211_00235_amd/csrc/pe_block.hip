@@ -90,7 +90,7 @@ struct Carver {   // fixed layouts (ctx, prepared weights); optionally records e
 };
 
 template <typename T> struct AttnCtx { T* xhat; float* stats; T* qkvg; T* bias; T* biasT; float* zstats; float* lse; T* o; T* og; };
-template <typename T> struct TransCtx { T* xhat; float* stats; T* h; };
+template <typename T> struct TransCtx { T* xhat; float* stats; T* h; unsigned char* hbits; };   // hbits: [M][nC / 8], bit = (h > 0)
 template <typename T> struct TriMulCtx { T* zhat; float* stats; T* proj_t; T* a_t; T* b_t; T* g; T* x_t; float* stats_out; T* xhat; T* u; };
 template <typename T> struct OpmCtx { T* mhat; float* stats; T* a; T* b; float* inv_norm; T* O; };
 template <typename T> struct GlobCtx { T* xhat; float* stats; T* proj; float* qbar; float* den; float* p; float* o; T* og; };
@@ -135,12 +135,16 @@ template <typename T> static void carve_attn_ctx(Carver& cv, AttnCtx<T>& a, cons
   a.o = cv.take<T>(N("o"), M * HD, dtype_tag<T>());
   a.og = cv.take<T>(N("og"), M * HD, dtype_tag<T>());
 }
+// The ReLU decisions of a transition are also kept as bits when the first GEMM is sure to take the vector epilogue
+// (8 consecutive columns per lane): channel counts that are multiples of 8 (ctx and arenas are 256-byte aligned)
+static bool trans_bits_ok(int C, int n) { return C % 8 == 0 && (n * C) % 8 == 0; }
 template <typename T> static void carve_trans_ctx(Carver& cv, TransCtx<T>& a, const char* pre, long long M, int C, int n) {
   char nm[32];
   auto N = [&](const char* s) { snprintf(nm, sizeof(nm), "%s.%s", pre, s); return nm; };
   a.xhat = cv.take<T>(N("xhat"), M * C, dtype_tag<T>());
   a.stats = cv.take<float>(N("stats"), M * 2, PE_F32);
   a.h = cv.take<T>(N("h"), M * n * C, dtype_tag<T>());
+  a.hbits = trans_bits_ok(C, n) ? cv.take<unsigned char>(nullptr, M * ((n * C) / 8), 0) : nullptr;   // not listed in the ctx table
 }
 template <typename T> static void carve_trimul_ctx(Carver& cv, TriMulCtx<T>& a, const char* pre, long long Mz, int cz, int ct) {
   char nm[32];
@@ -616,6 +620,10 @@ template <typename T> struct Runner {
     prof_begin(st);
     bool al = false, narrow = false;
     int rc = launch_gemm<T, EpiGeneric<T>>(st, A, akc, B, bkc, sh, e, &al, &narrow);
+    if (e.bits_out && !al && rc == 0) {   // the per-element epilogue cannot write the bit mask
+      err = PE_ERR_DIMS;
+      if (h) h->last_error = std::string("ReLU bit mask without the vector epilogue: ") + what;
+    }
     // the exact instantiation (operand layouts, epilogue path, feature mask F; F = 8191 is the general kernel)
     char kn[64];
     if (narrow) snprintf(kn, sizeof(kn), "gemm64_kernel<EpiGeneric,F=%d>", g_gemm_last_features);
@@ -849,6 +857,7 @@ template <typename T> struct Runner {
     {
       EpiGeneric<T> e = epi_plain<T>(c.h, nC);
       e.bias_n = P(p.b1); e.act = 1;
+      if (c.hbits) { e.bits_out = c.hbits; e.ld_bits = nC / 8; }
       gemm(st, op_plain(c.xhat, Cc), true, op_plain(w.wt_1, Cc), true, (int)M, nC, Cc, 1, e, "trans 1");
     }
     {
@@ -1035,7 +1044,8 @@ template <typename T> struct Runner {
     { ReduceSeg sg[1] = {{0, Cc, p.w2, Cc}}, cb = {0, Cc, p.b2, 0};
       gemm_dw(st, ar, op_trans(c.h, nC), false, op_trans(gin, Cc), false, nC, Cc, M, 1, sg, "trans dW2", 1, &cb); }
     { EpiGeneric<T> e = epi_plain<T>(dh, nC);
-      e.relu_mask = c.h; e.ld_rm = nC;
+      if (c.hbits) { e.bits_in = c.hbits; e.ld_bits = nC / 8; }     // 1 bit instead of 16 per hidden unit
+      else { e.relu_mask = c.h; e.ld_rm = nC; }
       gemm(st, op_plain(gin, Cc), true, op_plain(w.wn_2, Cc), true, (int)M, nC, Cc, 1, e, "trans dh"); }
     { ReduceSeg sg[1] = {{0, nC, p.w1, nC}}, cb = {0, nC, p.b1, 0};
       gemm_dw(st, ar, op_trans(c.xhat, Cc), false, op_trans(dh, nC), false, Cc, nC, M, 1, sg, "trans dW1", 1, &cb); }

@@ -95,6 +95,10 @@ template <typename T> struct EpiGeneric {
   float alpha;
   int act;                       // 0 none, 1 relu, 2 sigmoid
   const T* relu_mask; long long ld_rm;   // v *= (relu_mask[m][n] > 0)
+  // The same decisions as one bit per element, 8 columns per byte (bit e of byte [m][n / 8] <-> column n + e):
+  // bits_out is written by a ReLU epilogue (act == 1; vector epilogue only, the host makes sure it is taken),
+  // bits_in replaces relu_mask where the activation itself is not needed - an eighth of a byte instead of an element
+  unsigned char* bits_out; const unsigned char* bits_in; long long ld_bits;   // ld_bits: bytes per row
   T* aux; long long ld_aux;              // aux[m][n] = v (after bias/act, before mul)
   const T* mul; long long ld_mul;        // v *= mul[m][n]
   const float* rowscale;                 // v *= rowscale[m]
@@ -126,7 +130,8 @@ template <typename T> struct EpiGeneric {
     if (bias_m) v += bias_m[m];
     if (act == 1) v = fmaxf(v, 0.0f);
     else if (act == 2) v = sigmoidf_(v);
-    if (relu_mask) v = (to_f(relu_mask[(long long)m * ld_rm + n]) > 0.0f) ? v : 0.0f;
+    if (bits_in) v = ((bits_in[(long long)m * ld_bits + (n >> 3)] >> (n & 7)) & 1) ? v : 0.0f;
+    else if (relu_mask) v = (to_f(relu_mask[(long long)m * ld_rm + n]) > 0.0f) ? v : 0.0f;
     if (aux) aux[(long long)m * ld_aux + n] = from_f<T>(v);
     if (mul) v *= to_f(mul[(long long)m * ld_mul + n]);
     if (rowscale) v *= rowscale[m];
@@ -143,7 +148,7 @@ template <typename T> struct EpiGeneric {
     if (bias_n) f |= EF_BIASN;
     if (bias_m) f |= EF_BIASM;
     if (act) f |= EF_ACT;
-    if (relu_mask) f |= EF_RELUMASK;
+    if (relu_mask || bits_in) f |= EF_RELUMASK;
     if (aux) f |= EF_AUX;
     if (mul) f |= EF_MUL;
     if (rowscale) f |= EF_ROWSCALE;
@@ -188,13 +193,23 @@ template <typename T> struct EpiGeneric {
       if (act == 1) {
 #pragma unroll
         for (int e = 0; e < 8; e++) v[e] = fmaxf(v[e], 0.0f);
+        if (bits_out) {
+          unsigned bb = 0;
+#pragma unroll
+          for (int e = 0; e < 8; e++) bb |= (to_f(from_f<T>(v[e])) > 0.0f ? 1u : 0u) << e;   // the decision of the STORED value
+          bits_out[(long long)m * ld_bits + (n >> 3)] = (unsigned char)bb;
+        }
       } else if (act == 2) {
 #pragma unroll
         for (int e = 0; e < 8; e++) v[e] = sigmoidf_(v[e]);
       }
     }
     float t[8];
-    if ((F & EF_RELUMASK) && relu_mask) {
+    if ((F & EF_RELUMASK) && bits_in) {
+      const unsigned bb = bits_in[(long long)m * ld_bits + (n >> 3)];
+#pragma unroll
+      for (int e = 0; e < 8; e++) v[e] = ((bb >> e) & 1u) ? v[e] : 0.0f;
+    } else if ((F & EF_RELUMASK) && relu_mask) {
       load8<T>(relu_mask + (long long)m * ld_rm + n, t);
 #pragma unroll
       for (int e = 0; e < 8; e++) v[e] = (t[e] > 0.0f) ? v[e] : 0.0f;
