@@ -73,6 +73,19 @@ def test_head_dim_24(dtype):
         _assert(errs, worst, tol, stats)
 
 
+@pytest.mark.parametrize("c_tri,r", [(64, 36), (128, 20)])
+def test_triangle_channel_major_layernorm_bf16(c_tri, r):
+    """bf16 with 64 and 128 triangle channels and r * r a multiple of 8 but not of 128: the channel-major LayerNorm
+    kernels that move 256-byte runs through a swizzled LDS tile (both lane-group widths), with a ragged last
+    workgroup; the transition's ReLU decisions travel as bits (channel counts are multiples of 8)."""
+    dims, table, inp = _case("tiny", dtype=1, s=12, r=r, c_m=32, c_z=32, h_msa=2, d_msa=16, h_pair=2, d_pair=16,
+                             c_tri=c_tri, c_opm=8, n_trans=2)
+    table, n = param_table(dims)
+    inp = make_inputs(dims, table, n, ("random_residues", 0.1), 17)
+    errs, worst, tol, stats = check_case(dims, table, inp)
+    _assert_small(errs, tol, stats)
+
+
 @pytest.mark.parametrize("use_ctx", [True, False])
 @pytest.mark.parametrize("dtype", [0, 1])
 @pytest.mark.parametrize("variant", [1, 2])
