@@ -440,8 +440,19 @@ template <typename T> struct Runner {
       if (Cc == 8 * l) return l;
     return 0;
   }
+  // LayerNorm of the NEXT sub-operation, done by the row-complete epilogue of this sub-operation's last GEMM
+  // (gemm_out): nxt is set by the caller of a sub-operation, ln_done_y names the LayerNorm output that a fused
+  // launch has already written, and k_ln_fwd skips the launch for exactly that output.
+  struct NextLn { long long g_off, b_off; T* y; float* stats; bool on; };
+  NextLn nxt{0, 0, nullptr, nullptr, false};
+  const T* ln_done_y = nullptr;
+  void prof_cancel() {
+    if (prof_e0 && h) h->ev_pool.push_back(prof_e0);
+    prof_e0 = nullptr;
+  }
   void k_ln_fwd(hipStream_t st, const T* x, long long g_off, long long b_off, T* y, float* stats, long long M, int Cc) {
     if (dry || err) return;
+    if (y == ln_done_y) { ln_done_y = nullptr; return; }
     const int lpr = ln_lpr(Cc);
     const double bytes = 2.0 * M * Cc * sizeof(T);
     if (lpr) {
@@ -633,6 +644,70 @@ template <typename T> struct Runner {
     if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = std::string("gemm operand alignment: ") + what; return; }
     check(what);
   }
+  // last GEMM of a sub-operation (output projection + residual): where the row-complete kernel applies it also
+  // writes the next sub-operation's LayerNorm (nxt), else the plain GEMM
+  void gemm_out(hipStream_t st, const Operand& A, const Operand& B, int M, int N, int K, const EpiGeneric<T>& e, const char* what) {
+    const bool want = nxt.on;
+    nxt.on = false;
+    if (want && !dry && !err) {
+      RowLn<T> ln;
+      memset(&ln, 0, sizeof(ln));
+      ln.gamma = P(nxt.g_off); ln.beta = P(nxt.b_off); ln.y = nxt.y; ln.stats = nxt.stats; ln.eps = d.ln_eps;
+      GemmShape sh{M, N, K, 1, 0, 0};
+      prof_begin(st);
+      if (launch_gemm64r<T, 1>(st, A, B, sh, e, ln)) {
+        char kn[64];
+        snprintf(kn, sizeof(kn), "gemm64r_kernel<F=%d,MODE=1>", g_gemm_last_features);
+        prof_end(st, what, kn, 2.0 * M * N * K, ((double)M * K + (double)N * K + 2.0 * M * N) * sizeof(T));
+        check(what);
+        ln_done_y = nxt.y;
+        return;
+      }
+      prof_cancel();
+    }
+    gemm(st, A, true, B, true, M, N, K, 1, e, what);
+  }
+  // dy = A . B^T (+ the earlier share already in dxh when acc) is the cotangent of a LayerNorm output:
+  //   gout = gin + LayerNorm-backward(dy; x, stats, gain),  gain / offset gradients queued for reduction.
+  // Where the row-complete kernel applies this is the GEMM's epilogue (dy never reaches memory), else the GEMM
+  // into dxh followed by the LayerNorm backward kernel.
+  // bias_db != nullptr: the same LayerNorm output also feeds a pair-bias projection with weight w_bias [Cc][bias_H]
+  // whose cotangent is bias_db [bias_H][M] (triangle attention); the fused launch then covers that path as well
+  // (returns true), otherwise the caller runs the bias path's own kernel (returns false).
+  bool gemm_ln_bwd(hipStream_t st, Arena& ar, const Operand& A, const Operand& B, long long M, int Cc, int K, T* dxh, bool acc,
+                   const T* x, const float* stats, long long g_off, long long b_off, const T* gin, T* gout, const char* what,
+                   const float* bias_db = nullptr, long long w_bias_off = 0, int bias_H = 0) {
+    const long long gridf = (M + 63) / 64;
+    const int plen = 2 * Cc + (bias_db ? Cc * bias_H : 0);
+    // sized by bias_H whether or not the bias path is taken: the planning pass must not depend on pointer values
+    float* part = (Cc == 128) ? (float*)part_arena(ar).alloc((size_t)gridf * (2 * Cc + Cc * bias_H) * sizeof(float)) : nullptr;
+    if (part && !dry && !err) {
+      RowLn<T> ln;
+      memset(&ln, 0, sizeof(ln));
+      ln.gamma = P(g_off); ln.prev = acc ? dxh : nullptr; ln.x = x; ln.stats_in = stats; ln.gin = gin; ln.gout = gout; ln.partial = part;
+      if (bias_db) { ln.beta = P(b_off); ln.db = bias_db; ln.db_ld = M; ln.w_bias = P(w_bias_off); ln.H = bias_H; }
+      EpiGeneric<T> e = epi_plain<T>(dxh, Cc);
+      GemmShape sh{(int)M, Cc, K, 1, 0, 0};
+      join_side(st);   // gout may alias a buffer the side stream is still reading
+      prof_begin(st);
+      if (launch_gemm64r<T, 2>(st, A, B, sh, e, ln)) {
+        char kn[64];
+        snprintf(kn, sizeof(kn), "gemm64r_kernel<F=0,MODE=2,HB=%d>", bias_db ? (bias_H <= 4 ? 4 : 8) : 0);
+        prof_end(st, what, kn, 2.0 * M * Cc * K,
+                 ((double)M * K + (double)Cc * K + (gin ? 3.0 : 2.0) * M * Cc + (acc ? 1.0 : 0.0) * M * Cc) * sizeof(T));
+        check(what);
+        ReduceSeg sg[3] = {{0, Cc, g_off, 0}, {Cc, Cc, b_off, 0}, {2 * Cc, Cc * bias_H, w_bias_off, 0}};
+        reduce_to(ar, part, (int)gridf, plen, 1, plen, bias_db ? 3 : 2, sg);
+        return bias_db != nullptr;
+      }
+      prof_cancel();
+    }
+    EpiGeneric<T> e = epi_plain<T>(dxh, Cc);
+    e.accumulate = acc ? 1 : 0;
+    gemm(st, A, true, B, true, (int)M, Cc, K, 1, e, what);
+    k_ln_bwd(st, ar, dxh, x, stats, g_off, b_off, gin, gout, M, Cc);
+    return false;
+  }
   // dW[rows][cols] += sum_k X(row,k) * Y(col,k), K huge: split-K partials + ordered reduce into dparams
   // ncs > 0: additionally dparams[cs[i].dst_off + j] += sum_k Y(cs[i].n_begin + j, k) (bias gradients)
   void gemm_dw(hipStream_t st, Arena& ar, const Operand& X, bool xkc, const Operand& Y, bool ykc, int rows, int cols,
@@ -763,7 +838,7 @@ template <typename T> struct Runner {
       EpiGeneric<T> e = epi_plain<T>(xout, Cc);
       e.bias_n = P(p.b_o);
       e.res = x; e.ld_res = Cc;
-      gemm(st, op_heads_rows(c.og, g, dh, M * dh), true, op_plain(w.wt_o, HD), true, (int)M, Cc, HD, 1, e, "attn out");
+      gemm_out(st, op_heads_rows(c.og, g, dh, M * dh), op_plain(w.wt_o, HD), (int)M, Cc, HD, e, "attn out");
     }
   }
 
@@ -863,7 +938,7 @@ template <typename T> struct Runner {
     {
       EpiGeneric<T> e = epi_plain<T>(xout, Cc);
       e.bias_n = P(p.b2); e.res = x; e.ld_res = Cc;
-      gemm(st, op_plain(c.h, nC), true, op_plain(w.wt_2, nC), true, (int)M, Cc, nC, 1, e, "trans 2");
+      gemm_out(st, op_plain(c.h, nC), op_plain(w.wt_2, nC), (int)M, Cc, nC, e, "trans 2");
     }
   }
 
@@ -928,7 +1003,7 @@ template <typename T> struct Runner {
       e.aux = c.u; e.ld_aux = cz;
       e.mul = c.g; e.ld_mul = cz;
       e.res = z; e.ld_res = cz;
-      gemm(st, op_plain(c.xhat, ct), true, op_plain(w.wt_o, ct), true, (int)Mz, cz, ct, 1, e, "trimul outproj");
+      gemm_out(st, op_plain(c.xhat, ct), op_plain(w.wt_o, ct), (int)Mz, cz, ct, e, "trimul outproj");
     }
   }
 
@@ -1017,6 +1092,14 @@ template <typename T> struct Runner {
     fwd_pair_stack(pair_in, C.z5);
   }
   void fwd_pair_step(int i, const T* z_in, T* z_out) {
+    // the LayerNorm that opens the next pair sub-operation rides on this one's output projection
+    switch (i) {
+      case 0: nxt = NextLn{PL.tmi.ln_in_g, PL.tmi.ln_in_b, C.tmi.zhat, C.tmi.stats, true}; break;
+      case 1: nxt = NextLn{PL.tas.ln_g, PL.tas.ln_b, C.tas.xhat, C.tas.stats, true}; break;
+      case 2: nxt = NextLn{PL.tae.ln_g, PL.tae.ln_b, C.tae.xhat, C.tae.stats, true}; break;
+      case 3: nxt = NextLn{PL.ptrans.ln_g, PL.ptrans.ln_b, C.pt.xhat, C.pt.stats, true}; break;
+      default: nxt.on = false; break;
+    }
     switch (i) {
       case 0: trimul_sub_fwd(sp, PL.tmo, W.tmo, C.tmo, z_in, C.z1, true); break;
       case 1: trimul_sub_fwd(sp, PL.tmi, W.tmi, C.tmi, C.z1, C.z2, false); break;
@@ -1026,6 +1109,7 @@ template <typename T> struct Runner {
                            PL.tae.ln_g, PL.tae.ln_b); break;
       default: trans_sub_fwd(sp, PL.ptrans, W.pt, C.pt, C.z4, z_out, Mz, d.c_z); break;
     }
+    nxt.on = false;
   }
   void fwd_pair_stack(const T* z_in, T* z_out) {
     for (int i = 0; i < PAIR_STEPS; i++) fwd_pair_step(i, z_in, z_out);
@@ -1049,9 +1133,7 @@ template <typename T> struct Runner {
       gemm(st, op_plain(gin, Cc), true, op_plain(w.wn_2, Cc), true, (int)M, nC, Cc, 1, e, "trans dh"); }
     { ReduceSeg sg[1] = {{0, nC, p.w1, nC}}, cb = {0, nC, p.b1, 0};
       gemm_dw(st, ar, op_trans(c.xhat, Cc), false, op_trans(dh, nC), false, Cc, nC, M, 1, sg, "trans dW1", 1, &cb); }
-    { EpiGeneric<T> e = epi_plain<T>(dxh, Cc);
-      gemm(st, op_plain(dh, nC), true, op_plain(w.wn_1, nC), true, (int)M, Cc, nC, 1, e, "trans dxhat"); }
-    k_ln_bwd(st, ar, dxh, x, c.stats, p.ln_g, p.ln_b, gin, g, M, Cc);
+    gemm_ln_bwd(st, ar, op_plain(dh, nC), op_plain(w.wn_1, nC), M, Cc, nC, dxh, false, x, c.stats, p.ln_g, p.ln_b, gin, g, "trans dxhat");
     end_subop(ar);
     ar.release(mk);
   }
@@ -1069,11 +1151,17 @@ template <typename T> struct Runner {
     T* dxh = (T*)ar.alloc((size_t)M * Cc * sizeof(T));
     T* dS = nullptr;
     float* dbias = nullptr;
+    float* dbias_rows = nullptr;
     const long long btile = (long long)H * ((gm.L + 31) / 32) * gm.L * 32;   // elements of one [H] set of chunk-ordered planes
     if (c.bias) {
       dS = (T*)ar.alloc((size_t)((gm.B + 1) / 2) * btile * sizeof(T));
       dbias = (float*)ar.alloc((size_t)btile * sizeof(float));
+      dbias_rows = (float*)ar.alloc((size_t)H * Mz * sizeof(float));   // dbias in pair-row order
     }
+    // triangle attention: the bias is projected from the same LayerNorm output as q / k / v / gate and its gradient
+    // goes into the same running gradient, so the two LayerNorm backward passes are one (on the sum of the cotangents)
+    const bool bias_same_ln = c.bias && bias_src == x && bias_ln_g == p.ln_g && bias_ln_b == p.ln_b && bias_gin == g && bias_gout == g &&
+                              M == Mz && Cc == d.c_z;
     { ReduceSeg sg[1] = {{0, Cc, p.w_o, Cc}}, cb = {0, Cc, p.b_o, 0};
       gemm_dw(st, ar, op_heads_cols(c.og, gm, dh, M * dh), false, op_trans(g, Cc), false, HD, Cc, M, 1, sg, "attn dWo", 1, &cb); }
     // dog = g W_o^T; its epilogue turns dog into dO, the gate gradient and D (no dog tensor, no pass of its
@@ -1127,29 +1215,28 @@ template <typename T> struct Runner {
         else
           PE_LAUNCH("attn_dbias_reduce", 0, 1.0 * Bds * hll * sizeof(T) + 4.0 * hll, st, attn_dbias_reduce_kernel<T>, dim3((unsigned)((hll + 255) / 256)), dim3(256), 0, dS, dbias,
                     (int)Bds, hll);
+        // dbias is in the chunk order of the query-per-lane bias copy; bring it to pair-row order
+        const int NT = (d.r + 31) / 32;
+        PE_LAUNCH("bias_untile", 0, 8.0 * H * Mz, st, bias_untile_kernel<T>, dim3(NT, NT, H), dim3(256), 0, dbias, dbias_rows, d.r,
+                  gm.bias_transposed);
       }
     }
     { ReduceSeg sg[4] = {{0, HD, p.w_q, HD}, {HD, HD, p.w_k, HD}, {2 * HD, HD, p.w_v, HD}, {3 * HD, HD, p.w_g, HD}};
       ReduceSeg cb = {3 * HD, HD, p.b_g, 0};
       gemm_dw(st, ar, op_trans(c.xhat, Cc), false, op_heads_cols(dqkvg, gm, dh, M * dh), false, Cc, 4 * HD, M, 4, sg, "attn dWqkvg", 1, &cb); }
-    { EpiGeneric<T> e = epi_plain<T>(dxh, Cc);
-      gemm(st, op_heads_rows(dqkvg, gm, dh, M * dh), true, op_plain(w.wn_qkvg, 4 * HD), true, (int)M, Cc, 4 * HD, 1, e, "attn dxhat"); }
-    k_ln_bwd(st, ar, dxh, x, c.stats, p.ln_g, p.ln_b, g, g, M, Cc);
+    const bool bias_done = gemm_ln_bwd(st, ar, op_heads_rows(dqkvg, gm, dh, M * dh), op_plain(w.wn_qkvg, 4 * HD), M, Cc, 4 * HD, dxh, false, x,
+                                       c.stats, p.ln_g, p.ln_b, g, g, "attn dxhat", bias_same_ln ? dbias_rows : nullptr, p.w_bias, c.bias ? H : 0);
     next_phase(ar);   // the bias path below adds to the same LayerNorm parameters: a later launch
-    if (c.bias) {
+    if (c.bias && bias_done) end_subop(ar);
+    if (c.bias && !bias_done) {
       const int cz = d.c_z;
       const int lpr = (ln_lpr(cz) && ln_lpr(cz) <= 32) ? ln_lpr(cz) : 0;
       const int rpw = lpr ? 64 / lpr : 1;
       int grid = (int)std::min<long long>((Mz + 4 * rpw - 1) / (4 * rpw), 1024);
       int plen = 2 * cz + cz * H;
       float* part = (float*)part_arena(ar).alloc((size_t)grid * plen * sizeof(float));
-      // dbias is in the chunk order of the query-per-lane bias copy; bring it to pair-row order
-      float* dbias_rows = (float*)ar.alloc((size_t)H * Mz * sizeof(float));
       if (!dry && !err) {
         const double fl = 4.0 * Mz * cz * H, by = (bias_gin ? 3.0 : 2.0) * Mz * cz * sizeof(T) + 4.0 * Mz * H;
-        const int NT = (d.r + 31) / 32;
-        PE_LAUNCH("bias_untile", 0, 8.0 * H * Mz, st, bias_untile_kernel<T>, dim3(NT, NT, H), dim3(256), 0, dbias, dbias_rows, d.r,
-                  gm.bias_transposed);
         if (lpr) {
 #define PE_LNB_BWD(L, HH) PE_LAUNCH("ln_bias_bwd", fl, by, st, (ln_bias_bwd_fast_kernel<T, L, HH>), dim3(grid), dim3(256), 0, dbias_rows, bias_src, c.zstats, P(bias_ln_g), P(bias_ln_b), P(p.w_bias), bias_gin, bias_gout, part, d.r, H)
 #define PE_LNB_BWD_H(L) do { if (H <= 4) PE_LNB_BWD(L, 4); else PE_LNB_BWD(L, 8); } while (0)
@@ -1256,10 +1343,8 @@ template <typename T> struct Runner {
       gemm_dw(st, ar, op_trans(c.zhat, cz), false, op_trans(dgraw, cz), false, cz, cz, Mz, 1, sg, "trimul dWg", 1, &cb); }
     { EpiGeneric<T> e = epi_plain<T>(dzh, cz);
       gemm(st, op_trans(dproj_t, Mz), false, op_plain(w.wn_p, 4 * ct), true, (int)Mz, cz, 4 * ct, 1, e, "trimul dzhat p"); }
-    { EpiGeneric<T> e = epi_plain<T>(dzh, cz);
-      e.accumulate = 1;
-      gemm(st, op_plain(dgraw, cz), true, op_plain(w.wn_g, cz), true, (int)Mz, cz, cz, 1, e, "trimul dzhat g"); }
-    k_ln_bwd(st, ar, dzh, z, c.stats, p.ln_in_g, p.ln_in_b, g, g, Mz, cz);
+    gemm_ln_bwd(st, ar, op_plain(dgraw, cz), op_plain(w.wn_g, cz), Mz, cz, cz, dzh, true, z, c.stats, p.ln_in_g, p.ln_in_b, g, g,
+                "trimul dzhat g");
     end_subop(ar);
     ar.release(mk);
   }

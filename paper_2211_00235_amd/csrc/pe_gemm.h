@@ -76,6 +76,31 @@ template <> PE_DEV void store8<float>(float* p, const float (&v)[8]) {
   *reinterpret_cast<f32x4*>(p + 4) = b;
 }
 
+// 8 consecutive storage elements as loaded (one or two 16-byte registers groups), converted when they are used:
+// a load issued early costs 4 registers (bf16) until then instead of 8
+template <typename T> struct Raw8;
+template <> struct Raw8<bf16> {
+  bf16x8 v;
+  PE_DEV void ld(const bf16* p) { v = *reinterpret_cast<const bf16x8*>(p); }
+  PE_DEV void zero() {
+#pragma unroll
+    for (int e = 0; e < 8; e++) v[e] = (bf16)0.0f;
+  }
+  PE_DEV void get(float (&f)[8]) const {
+#pragma unroll
+    for (int e = 0; e < 8; e++) f[e] = (float)v[e];
+  }
+};
+template <> struct Raw8<float> {
+  f32x4 lo, hi;
+  PE_DEV void ld(const float* p) { lo = *reinterpret_cast<const f32x4*>(p); hi = *reinterpret_cast<const f32x4*>(p + 4); }
+  PE_DEV void zero() { lo = f32x4{0.0f, 0.0f, 0.0f, 0.0f}; hi = lo; }
+  PE_DEV void get(float (&f)[8]) const {
+#pragma unroll
+    for (int e = 0; e < 4; e++) { f[e] = lo[e]; f[4 + e] = hi[e]; }
+  }
+};
+
 // ---------------------------------------------------------------------------
 // Epilogues
 // ---------------------------------------------------------------------------
@@ -170,12 +195,33 @@ template <typename T> struct EpiGeneric {
 #pragma unroll
     for (int e = 0; e < 8; e++) c.bn[e] = hb ? bias_n[n + e] : 0.0f;
   }
-  template <int F> PE_DEV void vec8(int b, int m, int n, const ColV& c, float (&v)[8]) const {
+  // The epilogue of one (row, 8 columns) group in two steps: pre8 issues every load the feature set needs (raw, not
+  // converted), apply8 does the arithmetic and the stores.  A kernel that calls pre8 for several rows before the
+  // first apply8 has all their loads in flight at once; behind a store the compiler cannot move a later row's
+  // loads up by itself (the pointers may alias).  vec8 = pre8 + apply8.
+  struct Pre8 { Raw8<T> rm, mu, rs, ac; unsigned bits; float bm, sc; };
+  template <int F> PE_DEV long long out_off(int b, int m, const ColV& c) const {
     long long ro = (long long)b * out_batch;
     if ((F & EF_OM2) && om_in < (1 << 30))
       ro += (long long)((unsigned)m / (unsigned)om_in) * om_outer + (long long)((unsigned)m % (unsigned)om_in) * om_stride;
     else
       ro += (long long)m * om_stride;
+    return ro + c.o;
+  }
+  template <int F> PE_DEV void pre8(int b, int m, int n, const ColV& c, Pre8& p) const {
+    if ((F & EF_BIASM) && bias_m) p.bm = bias_m[m];
+    if ((F & EF_RELUMASK) && bits_in) p.bits = bits_in[(long long)m * ld_bits + (n >> 3)];
+    else if ((F & EF_RELUMASK) && relu_mask) p.rm.ld(relu_mask + (long long)m * ld_rm + n);
+    if ((F & EF_MUL) && mul) p.mu.ld(mul + (long long)m * ld_mul + n);
+    if (F & (EF_ROWSCALE | EF_SCALE2D)) {
+      float sc = ((F & EF_ROWSCALE) && rowscale) ? rowscale[m] : 1.0f;
+      if ((F & EF_SCALE2D) && scale2d) sc *= scale2d[(long long)(m / s2_mdiv) * s2_ld + c.s2];
+      p.sc = sc;
+    }
+    if ((F & EF_RES) && res) p.rs.ld(res + (long long)m * ld_res + n);
+    if ((F & EF_ACC) && accumulate) p.ac.ld(out + out_off<F>(b, m, c));
+  }
+  template <int F> PE_DEV void apply8(int b, int m, int n, const ColV& c, float (&v)[8], const Pre8& p) const {
     if ((F & EF_ALPHA) && alpha != 1.0f) {
 #pragma unroll
       for (int e = 0; e < 8; e++) v[e] *= alpha;
@@ -185,9 +231,8 @@ template <typename T> struct EpiGeneric {
       for (int e = 0; e < 8; e++) v[e] += c.bn[e];
     }
     if ((F & EF_BIASM) && bias_m) {
-      float bm = bias_m[m];
 #pragma unroll
-      for (int e = 0; e < 8; e++) v[e] += bm;
+      for (int e = 0; e < 8; e++) v[e] += p.bm;
     }
     if (F & EF_ACT) {
       if (act == 1) {
@@ -206,38 +251,39 @@ template <typename T> struct EpiGeneric {
     }
     float t[8];
     if ((F & EF_RELUMASK) && bits_in) {
-      const unsigned bb = bits_in[(long long)m * ld_bits + (n >> 3)];
 #pragma unroll
-      for (int e = 0; e < 8; e++) v[e] = ((bb >> e) & 1u) ? v[e] : 0.0f;
+      for (int e = 0; e < 8; e++) v[e] = ((p.bits >> e) & 1u) ? v[e] : 0.0f;
     } else if ((F & EF_RELUMASK) && relu_mask) {
-      load8<T>(relu_mask + (long long)m * ld_rm + n, t);
+      p.rm.get(t);
 #pragma unroll
       for (int e = 0; e < 8; e++) v[e] = (t[e] > 0.0f) ? v[e] : 0.0f;
     }
     if ((F & EF_AUX) && aux) store8<T>(aux + (long long)m * ld_aux + n, v);
     if ((F & EF_MUL) && mul) {
-      load8<T>(mul + (long long)m * ld_mul + n, t);
+      p.mu.get(t);
 #pragma unroll
       for (int e = 0; e < 8; e++) v[e] *= t[e];
     }
     if (F & (EF_ROWSCALE | EF_SCALE2D)) {
-      float sc = ((F & EF_ROWSCALE) && rowscale) ? rowscale[m] : 1.0f;
-      if ((F & EF_SCALE2D) && scale2d) sc *= scale2d[(long long)(m / s2_mdiv) * s2_ld + c.s2];
 #pragma unroll
-      for (int e = 0; e < 8; e++) v[e] *= sc;
+      for (int e = 0; e < 8; e++) v[e] *= p.sc;
     }
     if ((F & EF_RES) && res) {
-      load8<T>(res + (long long)m * ld_res + n, t);
+      p.rs.get(t);
 #pragma unroll
       for (int e = 0; e < 8; e++) v[e] += t[e];
     }
-    T* po = out + ro + c.o;
     if ((F & EF_ACC) && accumulate) {
-      load8<T>(po, t);
+      p.ac.get(t);
 #pragma unroll
       for (int e = 0; e < 8; e++) v[e] += t[e];
     }
-    store8<T>(po, v);
+    store8<T>(out + out_off<F>(b, m, c), v);
+  }
+  template <int F> PE_DEV void vec8(int b, int m, int n, const ColV& c, float (&v)[8]) const {
+    Pre8 p;
+    pre8<F>(b, m, n, c, p);
+    apply8<F>(b, m, n, c, v, p);
   }
   bool vec_ok(int N) const {
     auto a8 = [](long long x) { return x % 8 == 0; };
@@ -281,6 +327,9 @@ struct EpiPartial {
   template <int F> PE_DEV void vec8(int b, int m, int n, const ColV&, float (&v)[8]) const {
     store8<float>(out + (long long)b * mn + (long long)m * ldn + n, v);
   }
+  struct Pre8 {};
+  template <int F> PE_DEV void pre8(int, int, int, const ColV&, Pre8&) const {}
+  template <int F> PE_DEV void apply8(int b, int m, int n, const ColV& c, float (&v)[8], const Pre8&) const { vec8<F>(b, m, n, c, v); }
   bool vec_ok(int N) const { return N % 8 == 0 && ldn % 8 == 0 && mn % 8 == 0 && ((uintptr_t)out) % 16 == 0; }
 };
 
@@ -318,11 +367,21 @@ template <typename T> struct EpiAttnPre {
     cv.h = (int)((unsigned)n / (unsigned)dh);
     cv.c = (int)((unsigned)n % (unsigned)dh);
   }
-  template <int F> PE_DEV void vec8(int, int m, int, const ColV& cv, float (&v)[8]) const {
-    int b, pp;
-    if (tr) { pp = (int)((unsigned)m / (unsigned)inner); b = (int)((unsigned)m % (unsigned)inner); }
-    else { b = (int)((unsigned)m / (unsigned)L); pp = (int)((unsigned)m % (unsigned)L); }
-    const long long idx = (long long)cv.h * plane + ((long long)b * L + pp) * dh + cv.c;
+  // (loading gate and o in pre8, ahead of the LDS staging, measured slower here: +10 us over a step's four launches)
+  struct Pre8 { long long idx; int b, pp; };
+  template <int F> PE_DEV void pre8(int, int m, int, const ColV& cv, Pre8& p) const {
+    if (tr) { p.pp = (int)((unsigned)m / (unsigned)inner); p.b = (int)((unsigned)m % (unsigned)inner); }
+    else { p.b = (int)((unsigned)m / (unsigned)L); p.pp = (int)((unsigned)m % (unsigned)L); }
+    p.idx = (long long)cv.h * plane + ((long long)p.b * L + p.pp) * dh + cv.c;
+  }
+  template <int F> PE_DEV void vec8(int b_, int m, int n, const ColV& cv, float (&v)[8]) const {
+    Pre8 p;
+    pre8<F>(b_, m, n, cv, p);
+    apply8<F>(b_, m, n, cv, v, p);
+  }
+  template <int F> PE_DEV void apply8(int, int, int, const ColV& cv, float (&v)[8], const Pre8& p) const {
+    const int b = p.b, pp = p.pp;
+    const long long idx = p.idx;
     float gv[8], ov[8], dov[8], dgv[8];
     load8<T>(gate + idx, gv);
     load8<T>(o + idx, ov);
@@ -594,6 +653,15 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
     __syncthreads();   // all waves are done with the operand tiles
 #pragma unroll
     for (int i = 0; i < 2; i++) {
+      // the loads of the group's four rows are issued before its accumulators go through LDS, all in flight together
+      // (not in the general kernel, which would go beyond 168 registers: three workgroups per CU)
+      constexpr bool PF = F != EF_ALL;
+      typename Epi::Pre8 pre[4];
+#pragma unroll
+      for (int it = 0; it < 4; it++) {
+        const int m = m0 + wm * 64 + i * 32 + (lane >> 3) + it * 8;
+        if (PF && m < sh.M && n < sh.N) epi.template pre8<F>(b, m, n, cv, pre[it]);
+      }
 #pragma unroll
       for (int j = 0; j < 2; j++)
 #pragma unroll
@@ -611,7 +679,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
           f32x4 hi = *reinterpret_cast<const f32x4*>(stage + row * WS + c8 + 4);
 #pragma unroll
           for (int e = 0; e < 4; e++) { vals[e] = lo[e]; vals[4 + e] = hi[e]; }
-          epi.template vec8<F>(b, m, n, cv, vals);
+          if constexpr (PF) epi.template apply8<F>(b, m, n, cv, vals, pre[it]);
+          else epi.template vec8<F>(b, m, n, cv, vals);
         }
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -771,6 +840,13 @@ __global__ __launch_bounds__(256) void gemm64_kernel(Operand A, Operand B, GemmS
   const int c8 = (lane & 3) * 8, n = wave * 32 + c8;
   typename Epi::ColV cv;
   if (n < sh.N) epi.template colv<F>(n, cv);
+  // every load of the epilogue is issued before the accumulators go through LDS, all rows in flight together
+  typename Epi::Pre8 pre[4];
+#pragma unroll
+  for (int q = 0; q < 4; q++) {
+    const int m = m0 + (q >> 1) * 32 + (q & 1) * 16 + (lane >> 2);
+    if (m < sh.M && n < sh.N) epi.template pre8<F>(0, m, n, cv, pre[q]);
+  }
   __syncthreads();   // all waves are done with the operand tiles
 #pragma unroll
   for (int i = 0; i < 2; i++) {
@@ -789,12 +865,365 @@ __global__ __launch_bounds__(256) void gemm64_kernel(Operand A, Operand B, GemmS
         f32x4 hi = *reinterpret_cast<const f32x4*>(stage + row * WS + c8 + 4);
 #pragma unroll
         for (int e = 0; e < 4; e++) { vals[e] = lo[e]; vals[4 + e] = hi[e]; }
-        epi.template vec8<F>(0, m, n, cv, vals);
+        epi.template apply8<F>(0, m, n, cv, vals, pre[i * 2 + it]);
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Row-complete variant of the narrow-output kernel: N == 128 == the channel count of a LayerNorm, so the 64 x 128
+// tile of a workgroup holds whole rows and the LayerNorm work that would follow the GEMM as a pass of its own is
+// done on the tile (row sums: four lanes of a wave by shuffles, the four waves through LDS).
+//   MODE 1 (forward): the generic epilogue finishes and stores the output row (the new residual stream), then
+//     y = LayerNorm(stored row) with the NEXT sub-operation's gain / offset, and the row's (mean, 1/std).
+//   MODE 2 (backward): the GEMM value (+ prev) is the cotangent dy of a LayerNorm output; the kernel stores
+//     gout = gin + LayerNorm-backward(dy; x, stats, gain) and the workgroup's column sums of dy * xhat and dy
+//     (partial[blockIdx.x][2 * 128 (+ 128 H)], summed over the workgroups by the ordered partial reduction).
+//     HB = 4 or 8 (heads, padded): the pair-bias path of a triangle attention rides along (see RowLn).
+// ---------------------------------------------------------------------------
+template <typename T> struct RowLn {
+  const float* gamma; const float* beta;   // MODE 1: gain and offset; MODE 2: gain only
+  T* y; float* stats; float eps;           // MODE 1 outputs: y[M][128], stats[M][2]
+  const T* prev;                           // MODE 2: nullable, added to the GEMM value (an earlier GEMM's share of dy)
+  const T* x; const float* stats_in;       // MODE 2: LayerNorm input and its saved (mean, 1/std)
+  const T* gin; T* gout; float* partial;   // MODE 2: gin nullable; gout may alias gin
+  // MODE 2 with HB > 0: the LayerNorm output also feeds a pair-bias projection b[h][row] = sum_c y[row][c] w_bias[c][h]
+  // (triangle attention); its cotangent db[h][row] (fp32, [H][db_ld]) adds sum_h db[h][row] w_bias[c][h] to dy, and
+  // the workgroup's partial gets 128 * H more entries: sum over its rows of y[row][c] db[h][row] at 2 * 128 + c * H + h
+  const float* db; long long db_ld; const float* w_bias; int H;
+};
+
+template <typename T, int F, int MODE, int HB = 0>
+__global__ __launch_bounds__(256) void gemm64r_kernel(Operand A, Operand B, GemmShape sh, EpiGeneric<T> epi, RowLn<T> ln) {
+  typedef GemmCfg<T> C;
+  typedef Mma<T> MM;
+  typedef typename Vec16<T>::type V;
+  constexpr int BM = 64, CH = 128;
+  __shared__ __attribute__((aligned(16))) T lds_all[(BM + C::BN) * C::LDSS];   // 27 KB
+  __shared__ __attribute__((aligned(16))) float wbl[HB > 0 ? HB * CH : 4];      // w_bias as [h][c], zero beyond H
+  if constexpr (HB > 0) {
+    for (int i = threadIdx.x; i < HB * CH; i += 256) {
+      const int hh = i / CH, c = i % CH;
+      wbl[i] = hh < ln.H ? ln.w_bias[c * ln.H + hh] : 0.0f;
+    }
+  }
+  T* lds_a = lds_all;
+  T* lds_b = lds_all + BM * C::LDSS;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int m0 = blockIdx.x * BM;
+  const T* pa = (const T*)A.ptr;
+  const T* pb = (const T*)B.ptr;
+
+  f32x16 acc[2];
+#pragma unroll
+  for (int i = 0; i < 2; i++)
+#pragma unroll
+    for (int e = 0; e < 16; e++) acc[i][e] = 0.0f;
+
+  const int kv = tid & 7;
+  long long aa[2];
+  bool aok[2];
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+    const int m = m0 + (tid >> 3) + 32 * i;
+    aok[i] = m < sh.M;
+    const int mc = aok[i] ? m : 0;
+    aa[i] = (A.x_in >= (1 << 30)) ? (long long)mc * A.x_stride
+                                  : (long long)((unsigned)mc / (unsigned)A.x_in) * A.x_outer +
+                                        (long long)((unsigned)mc % (unsigned)A.x_in) * A.x_stride;
+  }
+  RowAddr<T, true> rowb;
+  rowb.init(B, 0, sh.N, tid);
+  V ra[2], rb[4];
+  auto load_a = [&](int k0) {
+    const int k = k0 + kv * C::VEC;
+    const long long ka = gemm_kaddr(A, k);
+#pragma unroll
+    for (int i = 0; i < 2; i++) {
+      V v;
+#pragma unroll
+      for (int e = 0; e < C::VEC; e++) v[e] = from_f<T>(0.0f);
+      if (k < sh.K && aok[i]) v = *reinterpret_cast<const V*>(pa + aa[i] + ka);
+      ra[i] = v;
+    }
+  };
+  load_a(0);
+  gemm_load_tile<T, true, true>(rb, pb, B, rowb, sh.N, 0, sh.K, tid);
+  for (int k0 = 0; k0 < sh.K; k0 += C::BK) {
+    __syncthreads();  // previous tile fully consumed
+#pragma unroll
+    for (int i = 0; i < 2; i++) *reinterpret_cast<V*>(lds_a + C::template off<false>((tid >> 3) + 32 * i, kv, 0)) = ra[i];
+    gemm_store_tile<T, true>(rb, lds_b, tid);
+    __syncthreads();
+    if (k0 + C::BK < sh.K) {
+      load_a(k0 + C::BK);
+      gemm_load_tile<T, true, true>(rb, pb, B, rowb, sh.N, k0 + C::BK, sh.K, tid);
+    }
+#pragma unroll
+    for (int kk = 0; kk < C::BK / MM::KSTEP; kk++) {
+      const int eo = kk * MM::KSTEP + g * MM::KP;
+      typename MM::frag bf = MM::load(lds_b + C::template off<false>(wave * 32 + l32, eo / C::VEC, eo % C::VEC));
+#pragma unroll
+      for (int t = 0; t < 2; t++)
+        MM::mma(acc[t], MM::load(lds_a + C::template off<false>(t * 32 + l32, eo / C::VEC, eo % C::VEC)), bf);
+    }
+  }
+
+  // wave-private staging of the 32 x 32 sub-tiles; lane -> 8 consecutive columns of the rows
+  // rloc(q) = 32 (q / 2) + 16 (q % 2) + lane / 4, q = 0..3
+  constexpr int WS = 32 + 4;
+  static_assert((4 * 32 * WS + 4 * BM * 2) * sizeof(float) <= (BM + C::BN) * C::LDSS * sizeof(T), "stage tiles and row sums must fit");
+  float* stage = reinterpret_cast<float*>(lds_all) + wave * 32 * WS;
+  float* rowred = reinterpret_cast<float*>(lds_all) + 4 * 32 * WS;   // [wave][row][2]
+  const int c8 = (lane & 3) * 8, n = wave * 32 + c8;
+  float vals[4][8];
+  // every global load of the epilogue is issued here, before the accumulators go through LDS (raw registers)
+  float gm[8];
+#pragma unroll
+  for (int e = 0; e < 8; e++) gm[e] = ln.gamma[n + e];
+  typename EpiGeneric<T>::ColV cv;
+  typename EpiGeneric<T>::Pre8 pre[MODE == 1 ? 4 : 1];
+  Raw8<T> xr[MODE == 2 ? 4 : 1], pr[MODE == 2 ? 4 : 1], gr[MODE == 2 ? 4 : 1];
+  float mean[MODE == 2 ? 4 : 1], rstd[MODE == 2 ? 4 : 1];
+  float dbv[HB > 0 ? 4 : 1][HB > 0 ? HB : 1];
+  if constexpr (MODE == 1) {
+    epi.template colv<F>(n, cv);
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const int m = m0 + (q >> 1) * 32 + (q & 1) * 16 + (lane >> 2);
+      if (m < sh.M) epi.template pre8<F>(0, m, n, cv, pre[q]);
+    }
+  } else {
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const int m = m0 + (q >> 1) * 32 + (q & 1) * 16 + (lane >> 2);
+      xr[q].zero(); pr[q].zero(); gr[q].zero();
+      mean[q] = 0.0f; rstd[q] = 0.0f;
+      if constexpr (HB > 0) {
+#pragma unroll
+        for (int hh = 0; hh < HB; hh++) dbv[q][hh] = (m < sh.M && hh < ln.H) ? ln.db[(long long)hh * ln.db_ld + m] : 0.0f;
+      }
+      if (m < sh.M) {
+        xr[q].ld(ln.x + (long long)m * CH + n);
+        if (ln.prev) pr[q].ld(ln.prev + (long long)m * CH + n);
+        if (ln.gin) gr[q].ld(ln.gin + (long long)m * CH + n);
+        mean[q] = ln.stats_in[(long long)m * 2];
+        rstd[q] = ln.stats_in[(long long)m * 2 + 1];
+      }
+    }
+  }
+  __syncthreads();   // all waves are done with the operand tiles
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+#pragma unroll
+    for (int a = 0; a < 16; a++) stage[acc_row(g, a) * WS + l32] = acc[i][a];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int it = 0; it < 2; it++) {
+      const int row = (lane >> 2) + it * 16;
+      f32x4 lo = *reinterpret_cast<const f32x4*>(stage + row * WS + c8);
+      f32x4 hi = *reinterpret_cast<const f32x4*>(stage + row * WS + c8 + 4);
+#pragma unroll
+      for (int e = 0; e < 4; e++) { vals[i * 2 + it][e] = lo[e]; vals[i * 2 + it][4 + e] = hi[e]; }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+  auto quad_sum = [](float v) { v += __shfl_xor(v, 1, 64); v += __shfl_xor(v, 2, 64); return v; };
+  auto row_total = [&](int rloc, int j) {
+    return (rowred[(0 * BM + rloc) * 2 + j] + rowred[(1 * BM + rloc) * 2 + j]) + (rowred[(2 * BM + rloc) * 2 + j] + rowred[(3 * BM + rloc) * 2 + j]);
+  };
+  if constexpr (MODE == 1) {
+    float mu[4];
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const int rloc = (q >> 1) * 32 + (q & 1) * 16 + (lane >> 2), m = m0 + rloc;
+      float s = 0.0f;
+      if (m < sh.M) {
+        epi.template apply8<F>(0, m, n, cv, vals[q], pre[q]);
+#pragma unroll
+        for (int e = 0; e < 8; e++) { vals[q][e] = to_f(from_f<T>(vals[q][e])); s += vals[q][e]; }   // the stored row
+      }
+      s = quad_sum(s);
+      if ((lane & 3) == 0) rowred[(wave * BM + rloc) * 2] = s;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const int rloc = (q >> 1) * 32 + (q & 1) * 16 + (lane >> 2);
+      mu[q] = row_total(rloc, 0) * (1.0f / CH);
+      float s = 0.0f;
+#pragma unroll
+      for (int e = 0; e < 8; e++) { const float t = vals[q][e] - mu[q]; s += t * t; }
+      s = quad_sum(s);
+      if ((lane & 3) == 0) rowred[(wave * BM + rloc) * 2 + 1] = s;
+    }
+    __syncthreads();
+    float bt[8];
+#pragma unroll
+    for (int e = 0; e < 8; e++) bt[e] = ln.beta[n + e];
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const int rloc = (q >> 1) * 32 + (q & 1) * 16 + (lane >> 2), m = m0 + rloc;
+      if (m < sh.M) {
+        const float rstd = rsqrtf(row_total(rloc, 1) * (1.0f / CH) + ln.eps);
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 8; e++) o[e] = (vals[q][e] - mu[q]) * rstd * gm[e] + bt[e];
+        store8<T>(ln.y + (long long)m * CH + n, o);
+        if (wave == 0 && (lane & 3) == 0) { ln.stats[(long long)m * 2] = mu[q]; ln.stats[(long long)m * 2 + 1] = rstd; }
+      }
+    }
+  } else {
+    float dgs[8], dbs[8];   // xhat is recomputed from the raw row in the second step instead of kept (32 registers)
+#pragma unroll
+    for (int e = 0; e < 8; e++) { dgs[e] = 0.0f; dbs[e] = 0.0f; }
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const int rloc = (q >> 1) * 32 + (q & 1) * 16 + (lane >> 2), m = m0 + rloc;
+      float s1 = 0.0f, s2 = 0.0f;
+      if (m < sh.M) {
+        float xv[8], pv[8];
+        xr[q].get(xv);
+        pr[q].get(pv);
+        if constexpr (HB > 0) {
+#pragma unroll
+          for (int hh = 0; hh < HB; hh++) {
+            const f32x4 w0 = *reinterpret_cast<const f32x4*>(wbl + hh * CH + n);
+            const f32x4 w1 = *reinterpret_cast<const f32x4*>(wbl + hh * CH + n + 4);
+#pragma unroll
+            for (int e = 0; e < 4; e++) { pv[e] += dbv[q][hh] * w0[e]; pv[4 + e] += dbv[q][hh] * w1[e]; }
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+          const float dv = vals[q][e] + pv[e];
+          const float xh = (xv[e] - mean[q]) * rstd[q];
+          const float dx = dv * gm[e];
+          dgs[e] += dv * xh;
+          dbs[e] += dv;
+          s1 += dx;
+          s2 += dx * xh;
+          vals[q][e] = dx;
+        }
+      }
+      s1 = quad_sum(s1);
+      s2 = quad_sum(s2);
+      if ((lane & 3) == 0) { rowred[(wave * BM + rloc) * 2] = s1; rowred[(wave * BM + rloc) * 2 + 1] = s2; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const int rloc = (q >> 1) * 32 + (q & 1) * 16 + (lane >> 2), m = m0 + rloc;
+      if (m < sh.M) {
+        const float s1 = row_total(rloc, 0) * (1.0f / CH), s2 = row_total(rloc, 1) * (1.0f / CH);
+        float o[8], xv[8];
+        gr[q].get(o);
+        xr[q].get(xv);
+#pragma unroll
+        for (int e = 0; e < 8; e++) o[e] += (vals[q][e] - s1 - (xv[e] - mean[q]) * rstd[q] * s2) * rstd[q];
+        store8<T>(ln.gout + (long long)m * CH + n, o);
+      }
+    }
+    // column sums over the workgroup's 64 rows: the 16 lanes of a wave with the same columns, rows in a fixed order
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+#pragma unroll
+      for (int o = 4; o < 64; o <<= 1) { dgs[e] += __shfl_xor(dgs[e], o, 64); dbs[e] += __shfl_xor(dbs[e], o, 64); }
+    }
+    const int plen = 2 * CH + (HB > 0 ? CH * ln.H : 0);
+    float* pp = ln.partial + (long long)blockIdx.x * plen;
+    if (lane < 4) {
+      store8<float>(pp + n, dgs);
+      store8<float>(pp + CH + n, dbs);
+    }
+    if constexpr (HB > 0) {
+      // bias weight: sum over the 64 rows of y[row][c] db[h][row], 32 rows at a time through LDS (y in fp32 where the
+      // accumulator staging was): thread -> channel c = tid % 128 and HB / 2 heads, rows in order
+      constexpr int YL = CH + 4, HH2 = HB / 2;
+      static_assert(32 * YL + 32 * HB <= 4 * 32 * WS, "y tile and db rows must fit in the staging area");
+      float* ytile = reinterpret_cast<float*>(lds_all);
+      float* dbl = ytile + 32 * YL;
+      float bt[8], accw[HH2];
+#pragma unroll
+      for (int e = 0; e < 8; e++) bt[e] = ln.beta[n + e];
+#pragma unroll
+      for (int j = 0; j < HH2; j++) accw[j] = 0.0f;
+      const int cc = tid & 127, h0 = (tid >> 7) * HH2;
+#pragma unroll
+      for (int half = 0; half < 2; half++) {
+        __syncthreads();   // half 0: every wave is past its row-sum reads; half 1: the first half's tile has been read
+#pragma unroll
+        for (int qq = 0; qq < 2; qq++) {
+          const int q = half * 2 + qq, lr = qq * 16 + (lane >> 2), m = m0 + half * 32 + lr;
+          float xv[8], yv[8];
+          xr[q].get(xv);
+#pragma unroll
+          for (int e = 0; e < 8; e++) yv[e] = (m < sh.M) ? (xv[e] - mean[q]) * rstd[q] * gm[e] + bt[e] : 0.0f;
+          *reinterpret_cast<f32x4*>(ytile + lr * YL + n) = f32x4{yv[0], yv[1], yv[2], yv[3]};
+          *reinterpret_cast<f32x4*>(ytile + lr * YL + n + 4) = f32x4{yv[4], yv[5], yv[6], yv[7]};
+          if (wave == 0 && (lane & 3) == 0) {
+#pragma unroll
+            for (int hh = 0; hh < HB; hh++) dbl[lr * HB + hh] = dbv[q][hh];
+          }
+        }
+        __syncthreads();
+        for (int row = 0; row < 32; row++) {
+          const float yv = ytile[row * YL + cc];
+#pragma unroll
+          for (int j = 0; j < HH2; j++) accw[j] += yv * dbl[row * HB + h0 + j];
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < HH2; j++)
+        if (h0 + j < ln.H) pp[2 * CH + cc * ln.H + h0 + j] = accw[j];
+    }
+  }
+}
+
+// feature mask of the kernel instantiation that the last launch_gemm call of this host thread took (EF_ALL = the
+// general kernel); read by the caller to label the launch with the exact kernel symbol
+static thread_local int g_gemm_last_features = EF_ALL;
+
+// launches the row-complete kernel when its conditions hold (N == 128, k-contiguous aligned operands, the vector
+// epilogue, one of the feature sets below); false: nothing was launched and the caller takes the separate kernels
+template <typename T, int MODE>
+static inline bool launch_gemm64r(hipStream_t st, const Operand& A, const Operand& B, const GemmShape& sh, const EpiGeneric<T>& epi,
+                                  const RowLn<T>& ln) {
+  if (sh.N != 128 || sh.M <= 0 || sh.batch != 1 || sh.k_chunk != 0) return false;
+  if (A.k_stride != 1 || B.k_stride != 1) return false;
+  if (!gemm_operand_ok<T>(A, true, sh.M, sh) || !gemm_operand_ok<T>(B, true, sh.N, sh)) return false;
+  auto p16 = [](const void* p) { return ((uintptr_t)p) % 16 == 0; };
+  dim3 grid((unsigned)((sh.M + 63) / 64)), block(256);
+  if constexpr (MODE == 1) {
+    if (!epi.vec_ok(sh.N) || !p16(ln.y)) return false;
+    const int f = epi.features();
+#define PE_GEMM64R_SPEC(S)                                                                          \
+    if ((f & ~(S)) == 0) {                                                                          \
+      hipLaunchKernelGGL((gemm64r_kernel<T, (S), 1>), grid, block, 0, st, A, B, sh, epi, ln);       \
+      g_gemm_last_features = (S);                                                                   \
+      return true;                                                                                  \
+    }
+    PE_GEMM64R_SPEC(EF_BIASN | EF_RES)
+    PE_GEMM64R_SPEC(EF_BIASN | EF_AUX | EF_MUL | EF_RES)
+#undef PE_GEMM64R_SPEC
+    return false;
+  } else {
+    if (!p16(ln.x) || !p16(ln.gout) || (ln.gin && !p16(ln.gin)) || (ln.prev && !p16(ln.prev)) || !p16(ln.partial)) return false;
+    if (ln.db && (ln.H < 1 || ln.H > 8 || !ln.w_bias || !ln.beta)) return false;
+    if (!ln.db) hipLaunchKernelGGL((gemm64r_kernel<T, 0, 2, 0>), grid, block, 0, st, A, B, sh, epi, ln);
+    else if (ln.H <= 4) hipLaunchKernelGGL((gemm64r_kernel<T, 0, 2, 4>), grid, block, 0, st, A, B, sh, epi, ln);
+    else hipLaunchKernelGGL((gemm64r_kernel<T, 0, 2, 8>), grid, block, 0, st, A, B, sh, epi, ln);
+    g_gemm_last_features = 0;
+    return true;
   }
 }
 
@@ -1193,10 +1622,6 @@ static inline int launch_dwx(hipStream_t st, dim3 grid, int groups, const Operan
   else hipLaunchKernelGGL((gemm_dwx_kernel<DWX_GROUPS>), grid, dim3(256 * DWX_GROUPS), bytes, st, A, B, sh, epi);
   return hipGetLastError() == hipSuccess ? 0 : -2;
 }
-
-// feature mask of the kernel instantiation that the last launch_gemm call of this host thread took (EF_ALL = the
-// general kernel); read by the caller to label the launch with the exact kernel symbol
-static thread_local int g_gemm_last_features = EF_ALL;
 
 // the narrow-output kernel for the feature sets that occur with N <= 128 (else: not taken)
 template <typename T, class Epi>
