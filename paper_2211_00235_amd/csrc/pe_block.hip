@@ -89,7 +89,9 @@ struct Carver {   // fixed layouts (ctx, prepared weights); optionally records e
   }
 };
 
-template <typename T> struct AttnCtx { T* xhat; float* stats; T* qkvg; T* bias; T* biasT; float* zstats; float* lse; T* o; T* og; };
+// direct: the pair bias as projected, fp32 [H][r * r] in pair-row order (scratch between the projection and the two
+// tiled copies; in the ctx so that the previous sub-operation's epilogue can write it)
+template <typename T> struct AttnCtx { T* xhat; float* stats; T* qkvg; T* bias; T* biasT; float* zstats; float* lse; T* o; T* og; float* direct; };
 template <typename T> struct TransCtx { T* xhat; float* stats; T* h; unsigned char* hbits; };   // hbits: [M][nC / 8], bit = (h > 0)
 template <typename T> struct TriMulCtx { T* zhat; float* stats; T* proj_t; T* a_t; T* b_t; T* g; T* x_t; float* stats_out; T* xhat; T* u; };
 template <typename T> struct OpmCtx { T* mhat; float* stats; T* a; T* b; float* inv_norm; T* O; };
@@ -131,6 +133,7 @@ template <typename T> static void carve_attn_ctx(Carver& cv, AttnCtx<T>& a, cons
   a.bias = has_bias ? cv.take<T>(N("bias"), btile, dtype_tag<T>()) : nullptr;
   a.biasT = has_bias ? cv.take<T>(N("biasT"), btile, dtype_tag<T>()) : nullptr;
   a.zstats = has_bias ? cv.take<float>(N("zstats"), Mz * 2, PE_F32) : nullptr;
+  a.direct = has_bias ? cv.take<float>(nullptr, (long long)H * Mz, 0) : nullptr;   // not listed in the ctx table
   a.lse = cv.take<float>(N("lse"), B * H * L, PE_F32);
   a.o = cv.take<T>(N("o"), M * HD, dtype_tag<T>());
   a.og = cv.take<T>(N("og"), M * HD, dtype_tag<T>());
@@ -443,9 +446,12 @@ template <typename T> struct Runner {
   // LayerNorm of the NEXT sub-operation, done by the row-complete epilogue of this sub-operation's last GEMM
   // (gemm_out): nxt is set by the caller of a sub-operation, ln_done_y names the LayerNorm output that a fused
   // launch has already written, and k_ln_fwd skips the launch for exactly that output.
-  struct NextLn { long long g_off, b_off; T* y; float* stats; bool on; };
-  NextLn nxt{0, 0, nullptr, nullptr, false};
+  // w_bias_off / H / direct / zstats: the next sub-operation is a triangle attention whose pair bias is projected
+  // from that LayerNorm output (direct == nullptr: no such projection)
+  struct NextLn { long long g_off, b_off; T* y; float* stats; bool on; long long w_bias_off; int H; float* direct; float* zstats; };
+  NextLn nxt{0, 0, nullptr, nullptr, false, 0, 0, nullptr, nullptr};
   const T* ln_done_y = nullptr;
+  const float* bias_done_direct = nullptr;
   void prof_cancel() {
     if (prof_e0 && h) h->ev_pool.push_back(prof_e0);
     prof_e0 = nullptr;
@@ -653,14 +659,16 @@ template <typename T> struct Runner {
       RowLn<T> ln;
       memset(&ln, 0, sizeof(ln));
       ln.gamma = P(nxt.g_off); ln.beta = P(nxt.b_off); ln.y = nxt.y; ln.stats = nxt.stats; ln.eps = d.ln_eps;
+      if (nxt.direct) { ln.bias_out = nxt.direct; ln.stats2 = nxt.zstats; ln.w_bias = P(nxt.w_bias_off); ln.H = nxt.H; }
       GemmShape sh{M, N, K, 1, 0, 0};
       prof_begin(st);
       if (launch_gemm64r<T, 1>(st, A, B, sh, e, ln)) {
         char kn[64];
-        snprintf(kn, sizeof(kn), "gemm64r_kernel<F=%d,MODE=1>", g_gemm_last_features);
+        snprintf(kn, sizeof(kn), "gemm64r_kernel<F=%d,MODE=1,HB=%d>", g_gemm_last_features, nxt.direct ? (nxt.H <= 4 ? 4 : 8) : 0);
         prof_end(st, what, kn, 2.0 * M * N * K, ((double)M * K + (double)N * K + 2.0 * M * N) * sizeof(T));
         check(what);
         ln_done_y = nxt.y;
+        bias_done_direct = nxt.direct;
         return;
       }
       prof_cancel();
@@ -791,7 +799,7 @@ template <typename T> struct Runner {
       // bias projection fused with its LayerNorm into a plain [h][pair row] plane (scratch), then the two tiled
       // copies that the attention kernels read
       size_t mkb = ar.mark();
-      float* direct = (float*)ar.alloc((size_t)H * Mz * sizeof(float));
+      float* direct = c.direct;
       float* unused = nullptr;
       const int lpr = ln_lpr(d.c_z);
       const bool fast = lpr && lpr <= 32;
@@ -799,7 +807,9 @@ template <typename T> struct Runner {
       if (!dry && !err) {
         const double fl = 2.0 * Mz * d.c_z * H, by = 1.0 * Mz * d.c_z * sizeof(T) + 4.0 * Mz * H;
         int transposed = g.bias_transposed;
-        if (fast) {
+        if (bias_done_direct == direct) {
+          bias_done_direct = nullptr;   // projected (in pair-row order) by the previous sub-operation's last GEMM
+        } else if (fast) {
           const int rpw = 64 / lpr;
           int grid = (int)std::min<long long>((Mz + 4 * rpw * LNB_UN - 1) / (4 * rpw * LNB_UN), 2048);
 #define PE_LNB_FWD(L, HH) PE_LAUNCH("ln_bias_fwd", fl, by, st, (ln_bias_fwd_fast_kernel<T, L, HH>), dim3(grid), dim3(256), 0, bias_src, P(bias_ln_g), P(bias_ln_b), P(p.w_bias), direct, 1.0f, c.zstats, d.r, H, d.ln_eps)
@@ -1094,10 +1104,10 @@ template <typename T> struct Runner {
   void fwd_pair_step(int i, const T* z_in, T* z_out) {
     // the LayerNorm that opens the next pair sub-operation rides on this one's output projection
     switch (i) {
-      case 0: nxt = NextLn{PL.tmi.ln_in_g, PL.tmi.ln_in_b, C.tmi.zhat, C.tmi.stats, true}; break;
-      case 1: nxt = NextLn{PL.tas.ln_g, PL.tas.ln_b, C.tas.xhat, C.tas.stats, true}; break;
-      case 2: nxt = NextLn{PL.tae.ln_g, PL.tae.ln_b, C.tae.xhat, C.tae.stats, true}; break;
-      case 3: nxt = NextLn{PL.ptrans.ln_g, PL.ptrans.ln_b, C.pt.xhat, C.pt.stats, true}; break;
+      case 0: nxt = NextLn{PL.tmi.ln_in_g, PL.tmi.ln_in_b, C.tmi.zhat, C.tmi.stats, true, 0, 0, nullptr, nullptr}; break;
+      case 1: nxt = NextLn{PL.tas.ln_g, PL.tas.ln_b, C.tas.xhat, C.tas.stats, true, PL.tas.w_bias, d.h_pair, C.tas.direct, C.tas.zstats}; break;
+      case 2: nxt = NextLn{PL.tae.ln_g, PL.tae.ln_b, C.tae.xhat, C.tae.stats, true, PL.tae.w_bias, d.h_pair, C.tae.direct, C.tae.zstats}; break;
+      case 3: nxt = NextLn{PL.ptrans.ln_g, PL.ptrans.ln_b, C.pt.xhat, C.pt.stats, true, 0, 0, nullptr, nullptr}; break;
       default: nxt.on = false; break;
     }
     switch (i) {

@@ -895,6 +895,9 @@ template <typename T> struct RowLn {
   // (triangle attention); its cotangent db[h][row] (fp32, [H][db_ld]) adds sum_h db[h][row] w_bias[c][h] to dy, and
   // the workgroup's partial gets 128 * H more entries: sum over its rows of y[row][c] db[h][row] at 2 * 128 + c * H + h
   const float* db; long long db_ld; const float* w_bias; int H;
+  // MODE 1 with HB > 0: that projection itself, bias_out[h][row] = sum_c y[row][c] w_bias[c][h] (fp32, [H][M]), and a
+  // second copy of the row statistics (nullable) where the bias path's backward kernel looks for them
+  float* bias_out; float* stats2;
 };
 
 template <typename T, int F, int MODE, int HB = 0>
@@ -1079,7 +1082,36 @@ __global__ __launch_bounds__(256) void gemm64r_kernel(Operand A, Operand B, Gemm
 #pragma unroll
         for (int e = 0; e < 8; e++) o[e] = (vals[q][e] - mu[q]) * rstd * gm[e] + bt[e];
         store8<T>(ln.y + (long long)m * CH + n, o);
-        if (wave == 0 && (lane & 3) == 0) { ln.stats[(long long)m * 2] = mu[q]; ln.stats[(long long)m * 2 + 1] = rstd; }
+        if (wave == 0 && (lane & 3) == 0) {
+          ln.stats[(long long)m * 2] = mu[q]; ln.stats[(long long)m * 2 + 1] = rstd;
+          if (HB > 0 && ln.stats2) { ln.stats2[(long long)m * 2] = mu[q]; ln.stats2[(long long)m * 2 + 1] = rstd; }
+        }
+        if constexpr (HB > 0) {   // this lane's share of the row's bias projection (the staging area is free by now)
+          float* brd = reinterpret_cast<float*>(lds_all);   // [wave][row][HB]
+#pragma unroll
+          for (int hh = 0; hh < HB; hh++) {
+            const f32x4 w0 = *reinterpret_cast<const f32x4*>(wbl + hh * CH + n);
+            const f32x4 w1 = *reinterpret_cast<const f32x4*>(wbl + hh * CH + n + 4);
+            float t = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 4; e++) t += o[e] * w0[e] + o[4 + e] * w1[e];
+            t = quad_sum(t);
+            if ((lane & 3) == 0) brd[(wave * BM + rloc) * HB + hh] = t;
+          }
+        }
+      }
+    }
+    if constexpr (HB > 0) {
+      static_assert(4 * BM * HB <= 4 * 32 * WS, "bias row sums must fit in the staging area");
+      const float* brd = reinterpret_cast<const float*>(lds_all);
+      __syncthreads();
+      const int row = tid & 63, m = m0 + row;
+      if (m < sh.M) {
+#pragma unroll
+        for (int hh = tid >> 6; hh < HB; hh += 4)
+          if (hh < ln.H)
+            ln.bias_out[(long long)hh * sh.M + m] = (brd[(0 * BM + row) * HB + hh] + brd[(1 * BM + row) * HB + hh]) +
+                                                    (brd[(2 * BM + row) * HB + hh] + brd[(3 * BM + row) * HB + hh]);
       }
     }
   } else {
@@ -1206,11 +1238,14 @@ static inline bool launch_gemm64r(hipStream_t st, const Operand& A, const Operan
   if constexpr (MODE == 1) {
     if (!epi.vec_ok(sh.N) || !p16(ln.y)) return false;
     const int f = epi.features();
-#define PE_GEMM64R_SPEC(S)                                                                          \
-    if ((f & ~(S)) == 0) {                                                                          \
-      hipLaunchKernelGGL((gemm64r_kernel<T, (S), 1>), grid, block, 0, st, A, B, sh, epi, ln);       \
-      g_gemm_last_features = (S);                                                                   \
-      return true;                                                                                  \
+    if (ln.bias_out && (ln.H < 1 || ln.H > 8 || !ln.w_bias)) return false;
+#define PE_GEMM64R_SPEC(S)                                                                                             \
+    if ((f & ~(S)) == 0) {                                                                                             \
+      if (!ln.bias_out) hipLaunchKernelGGL((gemm64r_kernel<T, (S), 1, 0>), grid, block, 0, st, A, B, sh, epi, ln);     \
+      else if (ln.H <= 4) hipLaunchKernelGGL((gemm64r_kernel<T, (S), 1, 4>), grid, block, 0, st, A, B, sh, epi, ln);   \
+      else hipLaunchKernelGGL((gemm64r_kernel<T, (S), 1, 8>), grid, block, 0, st, A, B, sh, epi, ln);                  \
+      g_gemm_last_features = (S);                                                                                      \
+      return true;                                                                                                     \
     }
     PE_GEMM64R_SPEC(EF_BIASN | EF_RES)
     PE_GEMM64R_SPEC(EF_BIASN | EF_AUX | EF_MUL | EF_RES)
