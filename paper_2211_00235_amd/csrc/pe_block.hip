@@ -108,7 +108,9 @@ template <typename T> struct Ctx {
 template <typename T> struct AttnW { T *wt_qkvg, *wn_qkvg, *wt_o, *wn_o; };
 template <typename T> struct TransW { T *wt_1, *wn_1, *wt_2, *wn_2; };
 template <typename T> struct OpmW { T *wt_ab, *wn_ab, *wt_o, *wn_o; };
-template <typename T> struct TriMulW { T *wt_p, *wn_p, *wt_g, *wn_g, *wt_o, *wn_o; float* bias_p; };
+// wt_pi: the rows of wt_p in 64-row strips of 32 projection rows followed by the 32 gate rows of the same channels
+// (a-side strips, then b-side), nullptr unless c_tri is a multiple of 32
+template <typename T> struct TriMulW { T *wt_p, *wn_p, *wt_g, *wn_g, *wt_o, *wn_o; float* bias_p; T* wt_pi; };
 template <typename T> struct GlobW { T *wt_proj, *wn_proj, *wt_o, *wn_o; };
 template <typename T> struct PrepW {
   AttnW<T> row, col, tas, tae;
@@ -223,13 +225,14 @@ template <typename T> struct PrepCarver {
   // weight W[in][out] at params offset src -> transposed copy [out][in] placed at row block `row0` of a [*, in] matrix
   T* region(long long count) { long long o = (toff + 127) & ~127LL; toff = o + count; return tbase + o; }
   float* fregion(long long count) { long long o = (foff + 63) & ~63LL; foff = o + count; return fbase + o; }
-  void add(T* dst, long long src, int rows, int cols, long long ld_r, long long ld_c, float scale = 1.0f) {
+  void add(T* dst, long long src, int rows, int cols, long long ld_r, long long ld_c, float scale = 1.0f, int c_blk = 0, int c_blk_to = 0) {
     PrepDesc p; p.src_off = src; p.dst_off = dst - tbase; p.rows = rows; p.cols = cols; p.ld_r = ld_r; p.ld_c = ld_c;
-    p.scale = scale;
+    p.scale = scale; p.c_blk = c_blk; p.c_blk_to = c_blk_to;
     list->t.push_back(p);
   }
   void addf(float* dst, long long src, int n) {
     PrepDesc p; p.src_off = src; p.dst_off = dst - fbase; p.rows = 1; p.cols = n; p.ld_r = 0; p.ld_c = 1; p.scale = 1.0f;
+    p.c_blk = 0; p.c_blk_to = 0;
     list->f.push_back(p);
   }
 };
@@ -271,6 +274,12 @@ template <typename T> static void prep_trimul(PrepCarver<T>& pc, TriMulW<T>& w, 
     pc.add(w.wt_p + (long long)k * ct * cz, src[k], cz, ct, 1, cz);   // [4ct][cz]
     pc.add(w.wn_p + (long long)k * ct, src[k], cz, ct, 4 * ct, 1);    // [cz][4ct]
     pc.addf(w.bias_p + k * ct, bsrc[k], ct);
+  }
+  w.wt_pi = nullptr;
+  if (ct % 32 == 0) {
+    w.wt_pi = pc.region((long long)4 * ct * cz);
+    for (int k = 0; k < 4; k++)   // group k = 2 side + i: strip (side, block j) holds rows [i * 32, i * 32 + 32) of block j
+      pc.add(w.wt_pi + ((long long)(k >> 1) * (ct / 32) * 64 + (k & 1) * 32) * cz, src[k], cz, ct, 1, cz, 1.0f, 32, 64);
   }
   pc.add(w.wt_g, p.w_g, cz, cz, 1, cz);
   pc.add(w.wn_g, p.w_g, cz, cz, cz, 1);
@@ -371,7 +380,7 @@ template <typename T> struct Runner {
     size_t off = 0;
     auto region = [&](size_t bytes) { size_t o = (off + 255) & ~(size_t)255; off = o + bytes; return base + o; };
     // sizes: generous upper bounds (2 copies of every weight + padding)
-    size_t tbytes = (size_t)(2 * PL.total + 128 * 64) * sizeof(T);
+    size_t tbytes = (size_t)(2 * PL.total + 128 * 64 + 2LL * 4 * d.c_tri * d.c_z) * sizeof(T);   // + the interleaved projection weights
     size_t fbytes = (size_t)(16 * d.c_tri + 1024) * sizeof(float);
     prep_tbase_m = (T*)region(tbytes); prep_fbase_m = (float*)region(fbytes);
     prep_tbase_p = (T*)region(tbytes); prep_fbase_p = (float*)region(fbytes);
@@ -410,6 +419,11 @@ template <typename T> struct Runner {
     prep_attn<T>(pp, W.tas, PL.tas, d.c_z, HDz, d.d_pair);
     prep_attn<T>(pp, W.tae, PL.tae, d.c_z, HDz, d.d_pair);
     prep_trans<T>(pp, W.pt, PL.ptrans, d.c_z, d.n_trans);
+    if ((size_t)pm.toff * sizeof(T) > tbytes || (size_t)pp.toff * sizeof(T) > tbytes || (size_t)pm.foff * sizeof(float) > fbytes ||
+        (size_t)pp.foff * sizeof(float) > fbytes) {
+      err = PE_ERR_DIMS;
+      if (h) h->last_error = "prepared weights exceed their region";
+    }
     return (off + 255) & ~(size_t)255;
   }
   void run_prep_list(hipStream_t st, const std::vector<PrepDesc>& v, bool is_f, T* tbase, float* fbase) {
@@ -956,12 +970,28 @@ template <typename T> struct Runner {
                       bool outgoing) {
     const int cz = d.c_z, ct = d.c_tri, r = d.r;
     k_ln_fwd(st, z, p.ln_in_g, p.ln_in_b, c.zhat, c.stats, Mz, cz);
-    {  // channel-major projections: proj_t[4ct][Mz] = W_p^T[4ct][cz] . zhat^T
+    bool gated = false;   // projection, gate pre-activation and gated operands from one kernel
+    if (!dry && !err && w.wt_pi) {
+      EpiTmGate<T> eg;
+      eg.proj_t = c.proj_t; eg.a_t = c.a_t; eg.b_t = c.b_t; eg.bias = w.bias_p; eg.mask = pair_mask; eg.ct = ct; eg.Mz = Mz;
+      const Operand A = op_plain(w.wt_pi, cz), B = op_plain(c.zhat, cz);
+      GemmShape sh{4 * ct, (int)Mz, cz, 1, 0, 0};
+      if (eg.vec_ok((int)Mz) && gemm_operand_ok<T>(A, true, 4 * ct, sh) && gemm_operand_ok<T>(B, true, (int)Mz, sh)) {
+        prof_begin(st);
+        int rc = launch_gemm<T, EpiTmGate<T>>(st, A, true, B, true, sh, eg);
+        prof_end(st, "trimul proj+gate", "gemm_kernel<kc,kc,vec,EpiTmGate>", 2.0 * 4 * ct * Mz * cz,
+                 ((double)4 * ct * cz + (double)Mz * cz + 6.0 * ct * Mz) * sizeof(T));
+        if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = "gemm operand alignment: trimul proj+gate"; }
+        else check("trimul proj+gate");
+        gated = true;
+      }
+    }
+    if (!gated) {  // channel-major projections: proj_t[4ct][Mz] = W_p^T[4ct][cz] . zhat^T
       EpiGeneric<T> e = epi_plain<T>(c.proj_t, Mz);
       e.bias_m = w.bias_p;
       gemm(st, op_plain(w.wt_p, cz), true, op_plain(c.zhat, cz), true, 4 * ct, (int)Mz, cz, 1, e, "trimul proj");
     }
-    if (!dry && !err) {
+    if (!dry && !err && !gated) {
       long long n = (long long)ct * Mz;
       if (Mz % 8 == 0 && al16(c.proj_t) && al16(pair_mask) && al16(c.a_t) && al16(c.b_t))
         PE_LAUNCH("tm_gate_fwd", 0, 6.0 * n * sizeof(T), st, tm_gate_fwd8_kernel<T>, dim3((unsigned)((n / 8 + 255) / 256)), dim3(256), 0, c.proj_t,

@@ -1223,7 +1223,9 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceBatch rb) {
 // ---------------------------------------------------------------------------
 // Parameter preparation: dst[r*ld_r + c*ld_c] = T(src[r*cols + c])
 // ---------------------------------------------------------------------------
-struct PrepDesc { long long src_off, dst_off; int rows, cols; long long ld_r, ld_c; float scale; };   // copy = scale * source
+// copy = scale * source; c_blk > 0: column c of the source goes to destination column (c / c_blk) * c_blk_to + c % c_blk
+// (blocks of c_blk columns spread c_blk_to apart: the interleaved projection / gate rows of the triangle multiplication)
+struct PrepDesc { long long src_off, dst_off; int rows, cols; long long ld_r, ld_c; float scale; int c_blk, c_blk_to; };
 constexpr int PREP_MAX = 64;   // descriptors per launch (3 KB of kernel arguments)
 struct PrepBatch { PrepDesc d[PREP_MAX]; int n; };
 template <typename T>
@@ -1247,13 +1249,15 @@ __global__ __launch_bounds__(256) void prep_params_kernel(const float* params, T
       __syncthreads();
       for (int k = ty; k < 32; k += 8) {
         const int c = c0 + k, r = r0 + tx;
-        if (r < d.rows && c < d.cols) out[r + c * d.ld_c] = from_f<T>(tile[tx][k]);
+        const int cd = d.c_blk > 0 ? (c / d.c_blk) * d.c_blk_to + c % d.c_blk : c;
+        if (r < d.rows && c < d.cols) out[r + cd * d.ld_c] = from_f<T>(tile[tx][k]);
       }
       __syncthreads();
     } else {
       for (int k = ty; k < 32; k += 8) {
         const int r = r0 + k, c = c0 + tx;
-        if (r < d.rows && c < d.cols) out[r * d.ld_r + c * d.ld_c] = from_f<T>(src[(long long)r * d.cols + c] * d.scale);
+        const int cd = d.c_blk > 0 ? (c / d.c_blk) * d.c_blk_to + c % d.c_blk : c;
+        if (r < d.rows && c < d.cols) out[r * d.ld_r + cd * d.ld_c] = from_f<T>(src[(long long)r * d.cols + c] * d.scale);
       }
     }
   }

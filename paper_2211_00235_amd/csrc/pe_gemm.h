@@ -112,6 +112,7 @@ enum : int { EF_BIASN = 1, EF_BIASM = 2, EF_ACT = 4, EF_RELUMASK = 8, EF_AUX = 1
 
 template <typename T> struct EpiGeneric {
   static constexpr bool HAS_COLSUM = false;
+  static constexpr bool TM_GATE = false;
   T* out; long long out_batch;
   int om_in; long long om_outer, om_stride;
   int on_in; long long on_outer, on_stride;
@@ -314,6 +315,7 @@ template <typename T> static inline EpiGeneric<T> epi_plain(void* out, long long
 // fp32 partial sums of a split-K GEMM: part[b][m][n]
 struct EpiPartial {
   static constexpr bool HAS_COLSUM = true;
+  static constexpr bool TM_GATE = false;
   float* out; long long mn; int ldn;
   float* colsum;   // nullable: [batch][N] sums over k of the B operand (bias gradients ride on the dW GEMM)
   struct Row { long long o; };
@@ -344,6 +346,7 @@ struct EpiPartial {
 // neighbours and always active together); the host falls back to a plain GEMM + a pass of its own otherwise.
 template <typename T> struct EpiAttnPre {
   static constexpr bool HAS_COLSUM = false;
+  static constexpr bool TM_GATE = false;
   const T* gate;       // gate pre-activation plane group: qkvg + 3*H*plane
   const T* o;
   T* dO;
@@ -398,6 +401,41 @@ template <typename T> struct EpiAttnPre {
     if (dh >= 16) Dsum += __shfl_xor(Dsum, 1, 64);
     if (dh >= 32) Dsum += __shfl_xor(Dsum, 2, 64);
     if (cv.c == 0) D[((long long)b * H + cv.h) * L + pp] = Dsum;
+  }
+};
+
+// Epilogue of the triangle multiplication's projection GEMM with the gating folded in (Section "Evoformer",
+// triangle multiplicative update: a = mask * sigmoid(gate a) * projection a, b likewise).  The GEMM computes the
+// channel-major projections out[row][position] from a weight copy whose rows come in 64-row strips: 32 projection
+// rows, then the 32 gate rows of the same channels (a-side strips first, then the b-side).  A wave's 64 x 64
+// accumulator block is one strip, so projection and gate of a (channel, position) sit in the same lane and register
+// index of its two row halves: the gated value is formed in registers from the two values as they are stored
+// (rounded to the storage type, so the result equals that of a separate gating pass over the stored tensor), and
+// three 32 x 64 tiles leave the wave: projection and gate pre-activation (proj_t, rows in the order
+// [a proj | a gate | b proj | b gate] that the backward pass reads) and the gated operand (a_t or b_t).
+// Only the vector path of gemm_kernel (k-contiguous aligned operands) has this epilogue; the host checks.
+template <typename T> struct EpiTmGate {
+  static constexpr bool HAS_COLSUM = false;
+  static constexpr bool TM_GATE = true;
+  T* proj_t; T* a_t; T* b_t;
+  const float* bias;     // [4 ct] in the order of proj_t's rows
+  const float* mask;     // [Mz]
+  int ct; long long Mz;
+  struct Row { long long o; };
+  struct Col { long long o; };
+  PE_DEV Row row(int, int) const { return Row{0}; }
+  PE_DEV Col col(int) const { return Col{0}; }
+  PE_DEV void operator()(int, int, const Row&, const Col&, float) const {}   // element-wise path: never launched
+  struct ColV {};
+  struct Pre8 {};
+  int features() const { return 0; }
+  template <int F> PE_DEV void colv(int, ColV&) const {}
+  template <int F> PE_DEV void pre8(int, int, int, const ColV&, Pre8&) const {}
+  template <int F> PE_DEV void apply8(int, int, int, const ColV&, float (&)[8], const Pre8&) const {}
+  template <int F> PE_DEV void vec8(int, int, int, const ColV&, float (&)[8]) const {}
+  bool vec_ok(int N) const {
+    auto p16 = [](const void* p) { return ((uintptr_t)p) % 16 == 0; };
+    return N % 8 == 0 && Mz % 8 == 0 && ct % 32 == 0 && p16(proj_t) && p16(a_t) && p16(b_t);
   }
 };
 
@@ -648,6 +686,61 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
     static_assert(4 * 32 * WS * sizeof(float) <= (C::BM + C::BN) * C::LDSS * sizeof(T), "stage tiles must fit");
     float* stage = reinterpret_cast<float*>(lds_all) + wave * 32 * WS;
     const int c8 = (lane & 7) * 8, n = n0 + wn * 64 + c8;
+    if constexpr (Epi::TM_GATE) {
+      // the wave's 64 rows are one strip: rows 0..31 projection, 32..63 gate of channels ch0..ch0+31 of one side
+      const int strip = (m0 >> 6) + wm, nside = epi.ct >> 5;
+      const int side = strip / nside, ch0 = (strip % nside) * 32;
+      float mk[2];
+#pragma unroll
+      for (int j = 0; j < 2; j++) {
+        const int col = n0 + wn * 64 + j * 32 + l32;
+        mk[j] = col < sh.N ? epi.mask[col] : 0.0f;
+      }
+#pragma unroll
+      for (int a = 0; a < 16; a++) {
+        const int ch = ch0 + acc_row(g, a);
+        const float bp = epi.bias[(side * 2) * epi.ct + ch], bg = epi.bias[(side * 2 + 1) * epi.ct + ch];
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+          acc[0][j][a] = to_f(from_f<T>(acc[0][j][a] + bp));   // as stored
+          acc[1][j][a] = to_f(from_f<T>(acc[1][j][a] + bg));
+        }
+      }
+      __syncthreads();   // all waves are done with the operand tiles
+#pragma unroll
+      for (int rnd = 0; rnd < 3; rnd++) {
+        if (rnd == 2) {
+#pragma unroll
+          for (int j = 0; j < 2; j++)
+#pragma unroll
+            for (int a = 0; a < 16; a++) acc[0][j][a] = mk[j] * sigmoidf_(acc[1][j][a]) * acc[0][j][a];
+        }
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+#pragma unroll
+          for (int a = 0; a < 16; a++) stage[acc_row(g, a) * WS + j * 32 + l32] = (rnd == 1) ? acc[1][j][a] : acc[0][j][a];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        T* dst = rnd == 2 ? (side ? epi.b_t : epi.a_t) : epi.proj_t + (long long)(side * 2 + rnd) * epi.ct * epi.Mz;
+#pragma unroll
+        for (int it = 0; it < 4; it++) {
+          const int row = (lane >> 3) + it * 8;
+          if (n < sh.N) {
+            float vals[8];
+            f32x4 lo = *reinterpret_cast<const f32x4*>(stage + row * WS + c8);
+            f32x4 hi = *reinterpret_cast<const f32x4*>(stage + row * WS + c8 + 4);
+#pragma unroll
+            for (int e = 0; e < 4; e++) { vals[e] = lo[e]; vals[4 + e] = hi[e]; }
+            store8<T>(dst + (long long)(ch0 + row) * epi.Mz + n, vals);
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      }
+      return;
+    }
     typename Epi::ColV cv;
     if (n < sh.N) epi.template colv<F>(n, cv);
     __syncthreads();   // all waves are done with the operand tiles
@@ -1661,8 +1754,8 @@ static inline int launch_dwx(hipStream_t st, dim3 grid, int groups, const Operan
 // the narrow-output kernel for the feature sets that occur with N <= 128 (else: not taken)
 template <typename T, class Epi>
 static inline bool launch_gemm64(hipStream_t st, const Operand& A, const Operand& B, const GemmShape& sh, const Epi& epi) {
-  if constexpr (Epi::HAS_COLSUM) {
-    return false;   // split-K partials: not for this kernel (and no instantiations for that epilogue)
+  if constexpr (Epi::HAS_COLSUM || Epi::TM_GATE) {
+    return false;   // split-K partials, gated projection: not for this kernel (and no instantiations for those epilogues)
   } else {
   const int f = epi.features();
   dim3 grid((unsigned)((sh.M + 63) / 64)), block(256);
@@ -1691,6 +1784,10 @@ static inline bool launch_gemm_spec(hipStream_t st, dim3 grid, const Operand& A,
                                     const Epi& epi) {
   if constexpr (Epi::HAS_COLSUM) {
     return false;   // split-K partials: one kernel
+  } else if constexpr (Epi::TM_GATE) {
+    hipLaunchKernelGGL((gemm_kernel<T, true, true, true, true, Epi, 0>), grid, dim3(256), 0, st, A, B, sh, epi);
+    g_gemm_last_features = 0;
+    return true;
   } else {
   const int f = epi.features();
   dim3 block(256);
