@@ -1354,7 +1354,43 @@ template <typename T> struct Runner {
         reduce_to(ar, part, grid, 2LL * ct, 1, 2 * ct, 2, sg);
       }
     }
-    {  // contraction backward, per channel
+    // contraction backward, per channel; where the vector path applies the gating backward is the epilogue of these
+    // GEMMs (da_t / db_t are never stored), else they are followed by the gating kernel
+    bool gate_fused = false;
+    {
+      Operand A1, B1, A2, B2;
+      bool a1k, b1k, a2k, b2k;
+      if (outgoing) {
+        A1 = op_plain(dx_t, r, Mz); a1k = true; B1 = op_trans(c.b_t, r, Mz); b1k = false;
+        A2 = op_trans(dx_t, r, Mz); a2k = false; B2 = op_trans(c.a_t, r, Mz); b2k = false;
+      } else {
+        A1 = op_plain(c.b_t, r, Mz); a1k = true; B1 = op_plain(dx_t, r, Mz); b1k = true;
+        A2 = op_plain(c.a_t, r, Mz); a2k = true; B2 = op_trans(dx_t, r, Mz); b2k = false;
+      }
+      EpiTmGateBwd<T> ga;
+      ga.proj_t = c.proj_t; ga.mask = pair_mask; ga.dproj_t = dproj_t; ga.ct = ct; ga.r = r; ga.side = 0; ga.Mz = Mz;
+      EpiTmGateBwd<T> gb = ga;
+      gb.side = 1;
+      GemmShape sh{r, r, r, ct, 0, 0};
+      if (!dry && !err && ga.vec_ok(r) && gemm_operand_ok<T>(A1, a1k, r, sh) && gemm_operand_ok<T>(B1, b1k, r, sh) &&
+          gemm_operand_ok<T>(A2, a2k, r, sh) && gemm_operand_ok<T>(B2, b2k, r, sh)) {
+        gate_fused = true;
+        const double fl = 2.0 * r * r * r * ct, by = (2.0 * r * r + 5.0 * r * r) * ct * sizeof(T);
+        prof_begin(st);
+        int rc = launch_gemm<T, EpiTmGateBwd<T>>(st, A1, a1k, B1, b1k, sh, ga);
+        prof_end(st, "trimul da+gate", a1k && b1k ? "gemm_kernel<kc,kc,vec,EpiTmGateBwd>" : "gemm_kernel<kc,xc,vec,EpiTmGateBwd>", fl, by);
+        if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = "gemm operand alignment: trimul da+gate"; }
+        else check("trimul da+gate");
+        if (!err) {
+          prof_begin(st);
+          rc = launch_gemm<T, EpiTmGateBwd<T>>(st, A2, a2k, B2, b2k, sh, gb);
+          prof_end(st, "trimul db+gate", a2k ? "gemm_kernel<kc,xc,vec,EpiTmGateBwd>" : "gemm_kernel<xc,xc,vec,EpiTmGateBwd>", fl, by);
+          if (rc == -1) { err = PE_ERR_DIMS; if (h) h->last_error = "gemm operand alignment: trimul db+gate"; }
+          else check("trimul db+gate");
+        }
+      }
+    }
+    if (!gate_fused) {
       EpiGeneric<T> ea = epi_plain<T>(da_t, r); ea.out_batch = Mz;
       EpiGeneric<T> eb = epi_plain<T>(db_t, r); eb.out_batch = Mz;
       if (outgoing) {
@@ -1367,7 +1403,7 @@ template <typename T> struct Runner {
         gemm(st, op_plain(c.a_t, r, Mz), true, op_trans(dx_t, r, Mz), false, r, r, r, ct, eb, "trimul db");
       }
     }
-    if (!dry && !err) {
+    if (!dry && !err && !gate_fused) {
       long long n = (long long)ct * Mz;
       if (Mz % 8 == 0 && al16(c.proj_t) && al16(pair_mask) && al16(da_t) && al16(db_t) && al16(dproj_t))
         PE_LAUNCH("tm_gate_bwd", 0, 10.0 * n * sizeof(T), st, tm_gate_bwd8_kernel<T>, dim3((unsigned)((n / 8 + 255) / 256)), dim3(256), 0, c.proj_t,

@@ -439,6 +439,57 @@ template <typename T> struct EpiTmGate {
   }
 };
 
+// Epilogue of the triangle multiplication's backward contractions with the gating backward folded in.  The batched
+// GEMM (batch index = channel) produces the cotangent d of the gated operand a (side 0) or b (side 1) at pair
+// position m * r + n; with p and g the stored projection and gate pre-activation at that (channel, position),
+//   d' = round(d) * mask,   dproj = d' * sigmoid(g),   dgate = d' * p * sigmoid(g) * (1 - sigmoid(g)),
+// written to the projection and gate rows of dproj_t ([a proj | a gate | b proj | b gate] x ct rows of Mz).  d is
+// rounded to the storage type first, so the results equal those of a separate pass over a stored d.
+template <typename T> struct EpiTmGateBwd {
+  static constexpr bool HAS_COLSUM = false;
+  static constexpr bool TM_GATE = false;
+  const T* proj_t; const float* mask; T* dproj_t;
+  int ct, r, side; long long Mz;
+  struct Row { long long o; };
+  struct Col { long long o; };
+  PE_DEV Row row(int, int) const { return Row{0}; }
+  PE_DEV Col col(int) const { return Col{0}; }
+  PE_DEV void operator()(int, int, const Row&, const Col&, float) const {}   // element-wise path: never launched
+  struct ColV {};
+  int features() const { return 0; }
+  template <int F> PE_DEV void colv(int, ColV&) const {}
+  struct Pre8 { Raw8<T> p, g; Raw8<float> mk; };
+  template <int F> PE_DEV void pre8(int b, int m, int n, const ColV&, Pre8& q) const {
+    const long long pos = (long long)m * r + n;
+    q.p.ld(proj_t + ((long long)(side * 2) * ct + b) * Mz + pos);
+    q.g.ld(proj_t + ((long long)(side * 2 + 1) * ct + b) * Mz + pos);
+    q.mk.ld(mask + pos);
+  }
+  template <int F> PE_DEV void apply8(int b, int m, int n, const ColV&, float (&v)[8], const Pre8& q) const {
+    const long long pos = (long long)m * r + n;
+    float pv[8], gv[8], mk[8], o0[8], o1[8];
+    q.p.get(pv); q.g.get(gv); q.mk.get(mk);
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      const float s = sigmoidf_(gv[e]);
+      const float dd = to_f(from_f<T>(v[e])) * mk[e];
+      o0[e] = dd * s;
+      o1[e] = dd * pv[e] * s * (1.0f - s);
+    }
+    store8<T>(dproj_t + ((long long)(side * 2) * ct + b) * Mz + pos, o0);
+    store8<T>(dproj_t + ((long long)(side * 2 + 1) * ct + b) * Mz + pos, o1);
+  }
+  template <int F> PE_DEV void vec8(int b, int m, int n, const ColV& c, float (&v)[8]) const {
+    Pre8 q;
+    pre8<F>(b, m, n, c, q);
+    apply8<F>(b, m, n, c, v, q);
+  }
+  bool vec_ok(int N) const {
+    auto p16 = [](const void* p) { return ((uintptr_t)p) % 16 == 0; };
+    return N % 8 == 0 && r % 8 == 0 && Mz % 8 == 0 && p16(proj_t) && p16(dproj_t) && p16(mask);
+  }
+};
+
 template <typename T> struct GemmCfg {
   static constexpr int VEC = Vec16<T>::N;
   static constexpr int BM = 128, BN = 128;
@@ -748,7 +799,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(Operand A, Operand B, GemmSha
     for (int i = 0; i < 2; i++) {
       // the loads of the group's four rows are issued before its accumulators go through LDS, all in flight together
       // (not in the general kernel, which would go beyond 168 registers: three workgroups per CU)
-      constexpr bool PF = F != EF_ALL;
+      constexpr bool PF = F != EF_ALL || !std::is_same<Epi, EpiGeneric<T>>::value;
       typename Epi::Pre8 pre[4];
 #pragma unroll
       for (int it = 0; it < 4; it++) {
@@ -1759,6 +1810,11 @@ static inline bool launch_gemm64(hipStream_t st, const Operand& A, const Operand
   } else {
   const int f = epi.features();
   dim3 grid((unsigned)((sh.M + 63) / 64)), block(256);
+  if constexpr (!std::is_same<Epi, EpiGeneric<T>>::value) {   // no feature sets: one instantiation
+    hipLaunchKernelGGL((gemm64_kernel<T, Epi, 0>), grid, block, 0, st, A, B, sh, epi);
+    g_gemm_last_features = 0;
+    return true;
+  }
 #define PE_GEMM64_SPEC(S)                                                                         \
   if ((f & ~(S)) == 0) {                                                                          \
     hipLaunchKernelGGL((gemm64_kernel<T, Epi, (S)>), grid, block, 0, st, A, B, sh, epi);           \
@@ -1784,7 +1840,8 @@ static inline bool launch_gemm_spec(hipStream_t st, dim3 grid, const Operand& A,
                                     const Epi& epi) {
   if constexpr (Epi::HAS_COLSUM) {
     return false;   // split-K partials: one kernel
-  } else if constexpr (Epi::TM_GATE) {
+  } else if constexpr (!std::is_same<Epi, EpiGeneric<T>>::value) {
+    // the special-purpose epilogues have no feature sets: one instantiation
     hipLaunchKernelGGL((gemm_kernel<T, true, true, true, true, Epi, 0>), grid, dim3(256), 0, st, A, B, sh, epi);
     g_gemm_last_features = 0;
     return true;
