@@ -464,7 +464,18 @@ template <typename T> struct Runner {
   // from that LayerNorm output (direct == nullptr: no such projection)
   struct NextLn { long long g_off, b_off; T* y; float* stats; bool on; long long w_bias_off; int H; float* direct; float* zstats; };
   NextLn nxt{0, 0, nullptr, nullptr, false, 0, 0, nullptr, nullptr};
-  const T* ln_done_y = nullptr;
+  // (one slot per branch is pending at most: the host alternates between the two branches' sub-operations)
+  const T* ln_done_y[4] = {nullptr, nullptr, nullptr, nullptr};
+  void ln_done_set(const T* y) {
+    for (int i = 0; i < 4; i++)
+      if (!ln_done_y[i]) { ln_done_y[i] = y; return; }
+    ln_done_y[0] = y;
+  }
+  bool ln_done_take(const T* y) {
+    for (int i = 0; i < 4; i++)
+      if (ln_done_y[i] == y && y) { ln_done_y[i] = nullptr; return true; }
+    return false;
+  }
   const float* bias_done_direct = nullptr;
   void prof_cancel() {
     if (prof_e0 && h) h->ev_pool.push_back(prof_e0);
@@ -472,7 +483,7 @@ template <typename T> struct Runner {
   }
   void k_ln_fwd(hipStream_t st, const T* x, long long g_off, long long b_off, T* y, float* stats, long long M, int Cc) {
     if (dry || err) return;
-    if (y == ln_done_y) { ln_done_y = nullptr; return; }
+    if (ln_done_take(y)) return;
     const int lpr = ln_lpr(Cc);
     const double bytes = 2.0 * M * Cc * sizeof(T);
     if (lpr) {
@@ -681,8 +692,8 @@ template <typename T> struct Runner {
         snprintf(kn, sizeof(kn), "gemm64r_kernel<F=%d,MODE=1,HB=%d>", g_gemm_last_features, nxt.direct ? (nxt.H <= 4 ? 4 : 8) : 0);
         prof_end(st, what, kn, 2.0 * M * N * K, ((double)M * K + (double)N * K + 2.0 * M * N) * sizeof(T));
         check(what);
-        ln_done_y = nxt.y;
-        bias_done_direct = nxt.direct;
+        ln_done_set(nxt.y);
+        if (nxt.direct) bias_done_direct = nxt.direct;
         return;
       }
       prof_cancel();
@@ -696,30 +707,46 @@ template <typename T> struct Runner {
   // bias_db != nullptr: the same LayerNorm output also feeds a pair-bias projection with weight w_bias [Cc][bias_H]
   // whose cotangent is bias_db [bias_H][M] (triangle attention); the fused launch then covers that path as well
   // (returns true), otherwise the caller runs the bias path's own kernel (returns false).
+  // fin_add != nullptr (set by the block's backward around the LAST sub-operation of the pair stack): the fused
+  // launch writes fin_out = gin + fin_add + (gradient through the LayerNorm) instead of gout and sets fin_done; the
+  // stream first waits for fin_from (the stream that produced fin_add).
+  const T* fin_add = nullptr;
+  T* fin_out = nullptr;
+  bool fin_done = false;
+  hipStream_t fin_from = nullptr;
+  hipEvent_t fin_ev = nullptr;
   bool gemm_ln_bwd(hipStream_t st, Arena& ar, const Operand& A, const Operand& B, long long M, int Cc, int K, T* dxh, bool acc,
                    const T* x, const float* stats, long long g_off, long long b_off, const T* gin, T* gout, const char* what,
                    const float* bias_db = nullptr, long long w_bias_off = 0, int bias_H = 0) {
     const long long gridf = (M + 63) / 64;
     const int plen = 2 * Cc + (bias_db ? Cc * bias_H : 0);
     // sized by bias_H whether or not the bias path is taken: the planning pass must not depend on pointer values
-    float* part = (Cc == 128) ? (float*)part_arena(ar).alloc((size_t)gridf * (2 * Cc + Cc * bias_H) * sizeof(float)) : nullptr;
+    float* part = (Cc == 128 || Cc == 256) ? (float*)part_arena(ar).alloc((size_t)gridf * (2 * Cc + Cc * bias_H) * sizeof(float)) : nullptr;
     if (part && !dry && !err) {
       RowLn<T> ln;
       memset(&ln, 0, sizeof(ln));
       ln.gamma = P(g_off); ln.prev = acc ? dxh : nullptr; ln.x = x; ln.stats_in = stats; ln.gin = gin; ln.gout = gout; ln.partial = part;
       if (bias_db) { ln.beta = P(b_off); ln.db = bias_db; ln.db_ld = M; ln.w_bias = P(w_bias_off); ln.H = bias_H; }
+      const bool fin = fin_add != nullptr && fin_out != nullptr && ((uintptr_t)fin_add) % 16 == 0 && ((uintptr_t)fin_out) % 16 == 0;
+      if (fin) {
+        if (fin_ev && fin_from != st &&
+            (hipEventRecord(fin_ev, fin_from) != hipSuccess || hipStreamWaitEvent(st, fin_ev, 0) != hipSuccess)) fail("final add: stream wait");
+        ln.gin2 = fin_add; ln.gout = fin_out;
+      }
       EpiGeneric<T> e = epi_plain<T>(dxh, Cc);
       GemmShape sh{(int)M, Cc, K, 1, 0, 0};
       join_side(st);   // gout may alias a buffer the side stream is still reading
       prof_begin(st);
       if (launch_gemm64r<T, 2>(st, A, B, sh, e, ln)) {
         char kn[64];
-        snprintf(kn, sizeof(kn), "gemm64r_kernel<F=0,MODE=2,HB=%d>", bias_db ? (bias_H <= 4 ? 4 : 8) : 0);
+        if (Cc == 256) snprintf(kn, sizeof(kn), "gemm64w_kernel<F=0,MODE=2>");
+        else snprintf(kn, sizeof(kn), "gemm64r_kernel<F=0,MODE=2,HB=%d,G2=%d>", bias_db ? (bias_H <= 4 ? 4 : 8) : 0, fin ? 1 : 0);
         prof_end(st, what, kn, 2.0 * M * Cc * K,
                  ((double)M * K + (double)Cc * K + (gin ? 3.0 : 2.0) * M * Cc + (acc ? 1.0 : 0.0) * M * Cc) * sizeof(T));
         check(what);
         ReduceSeg sg[3] = {{0, Cc, g_off, 0}, {Cc, Cc, b_off, 0}, {2 * Cc, Cc * bias_H, w_bias_off, 0}};
         reduce_to(ar, part, (int)gridf, plen, 1, plen, bias_db ? 3 : 2, sg);
+        if (fin) fin_done = true;
         return bias_db != nullptr;
       }
       prof_cancel();
@@ -1060,6 +1087,7 @@ template <typename T> struct Runner {
   // be enqueued one at a time so that the host alternates between the two streams (a stream whose
   // kernels are enqueued late starts late: the host needs ~10 us per launch).
   static constexpr int MSA_STEPS = 3, PAIR_STEPS = 5;
+  static_assert(MSA_STEPS <= PAIR_STEPS - 2, "the backward pass enqueues every MSA step before the last pair step");
   // set by the trunk when the previous block's call has already enqueued this block's MSA-side weight preparation
   // and the first part of its row attention (fwd_row_pre) on stream_msa
   bool row_pre_done = false;
@@ -1478,10 +1506,9 @@ template <typename T> struct Runner {
         A.ptr = dab; A.batch_stride = 0;
         A.x_in = 1 << 30; A.x_outer = 0; A.x_stride = co;
         A.k_in = co; A.k_outer = Mm * co; A.k_stride = 1;
-        EpiGeneric<T> e = epi_plain<T>(dmh, cm);
-        gemm(sm, A, true, op_plain(W.opm.wn_ab, 2 * co), true, (int)Mm, cm, 2 * co, 1, e, "opm dmhat");
+        gemm_ln_bwd(sm, am, A, op_plain(W.opm.wn_ab, 2 * co), Mm, cm, 2 * co, dmh, false, x, C.opm.stats, PL.opm.ln_g, PL.opm.ln_b, gin,
+                    gout, "opm dmhat");
       }
-      k_ln_bwd(sm, am, dmh, x, C.opm.stats, PL.opm.ln_g, PL.opm.ln_b, gin, gout, Mm, cm);
       end_subop(am);
       am.release(mk);
     }
@@ -1728,18 +1755,26 @@ static int block_bwd_impl(pe_handle* h, const pe_dims& d, const void* msa_in, co
     // branch's last sub-operation instead of after it.
     const bool hand_over = do_m && do_p && sm != sp && !h->side_streams;
     for (int i = 1; i < Runner<T>::PAIR_STEPS; i++) {
+      // the last pair sub-operation's last kernel also adds the row-attention-bias term and writes d_pair_in
+      // (every MSA-side step is enqueued by then: the MSA stack has fewer steps)
+      if (do_p && do_m && i == Runner<T>::PAIR_STEPS - 1) {
+        R.fin_add = dzb; R.fin_out = (T*)d_pair_in; R.fin_from = sm; R.fin_ev = h->ev[1];
+      }
       if (do_p) R.bwd_pair_step(i, (const T*)d_pair_out, gz, R.pair_in);
+      R.fin_add = nullptr;
       if (hand_over && i == Runner<T>::PAIR_STEPS - 2) {
         R.mark_early(R.ap);
         if (!R.err && !hip_ok(h, hipEventRecord(h->ev[4], sp), "event record")) return PE_ERR_HIP;
       }
       if (do_m && i - 1 < Runner<T>::MSA_STEPS) R.bwd_msa_step(i - 1, gm, R.pair_in, dzb);
     }
-    if (do_m && !ev_link(h, 1, sm, sp)) return PE_ERR_HIP;
+    if (do_m && !R.fin_done && !ev_link(h, 1, sm, sp)) return PE_ERR_HIP;
     if (!R.err) {
       if (do_m && do_p) {
-        launch_add2<T>(sp, gz, dzb, (T*)d_pair_in, n);
-        R.check("add d_pair_in");
+        if (!R.fin_done) {
+          launch_add2<T>(sp, gz, dzb, (T*)d_pair_in, n);
+          R.check("add d_pair_in");
+        }
       } else if (do_p) {
         if (!hip_ok(h, hipMemcpyAsync(d_pair_in, gz, (size_t)n * sizeof(T), hipMemcpyDeviceToDevice, sp), "copy")) return PE_ERR_HIP;
       } else if (do_m) {

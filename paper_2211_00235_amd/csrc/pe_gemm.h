@@ -1035,6 +1035,7 @@ template <typename T> struct RowLn {
   const T* prev;                           // MODE 2: nullable, added to the GEMM value (an earlier GEMM's share of dy)
   const T* x; const float* stats_in;       // MODE 2: LayerNorm input and its saved (mean, 1/std)
   const T* gin; T* gout; float* partial;   // MODE 2: gin nullable; gout may alias gin
+  const T* gin2;                           // MODE 2: nullable second addend of gout (same shape as gin)
   // MODE 2 with HB > 0: the LayerNorm output also feeds a pair-bias projection b[h][row] = sum_c y[row][c] w_bias[c][h]
   // (triangle attention); its cotangent db[h][row] (fp32, [H][db_ld]) adds sum_h db[h][row] w_bias[c][h] to dy, and
   // the workgroup's partial gets 128 * H more entries: sum over its rows of y[row][c] db[h][row] at 2 * 128 + c * H + h
@@ -1044,7 +1045,9 @@ template <typename T> struct RowLn {
   float* bias_out; float* stats2;
 };
 
-template <typename T, int F, int MODE, int HB = 0>
+// (asking for three waves per SIMD, which the variant with the bias path misses at 174 registers, makes the pair
+// stack 0.7 % faster alone and the two-stream step 0.4 % slower: not asked for)
+template <typename T, int F, int MODE, int HB = 0, bool G2 = false>
 __global__ __launch_bounds__(256) void gemm64r_kernel(Operand A, Operand B, GemmShape sh, EpiGeneric<T> epi, RowLn<T> ln) {
   typedef GemmCfg<T> C;
   typedef Mma<T> MM;
@@ -1135,7 +1138,7 @@ __global__ __launch_bounds__(256) void gemm64r_kernel(Operand A, Operand B, Gemm
   for (int e = 0; e < 8; e++) gm[e] = ln.gamma[n + e];
   typename EpiGeneric<T>::ColV cv;
   typename EpiGeneric<T>::Pre8 pre[MODE == 1 ? 4 : 1];
-  Raw8<T> xr[MODE == 2 ? 4 : 1], pr[MODE == 2 ? 4 : 1], gr[MODE == 2 ? 4 : 1];
+  Raw8<T> xr[MODE == 2 ? 4 : 1], pr[MODE == 2 ? 4 : 1], gr[MODE == 2 ? 4 : 1], g2[G2 ? 4 : 1];   // G2: the kernel takes gin2
   float mean[MODE == 2 ? 4 : 1], rstd[MODE == 2 ? 4 : 1];
   float dbv[HB > 0 ? 4 : 1][HB > 0 ? HB : 1];
   if constexpr (MODE == 1) {
@@ -1150,6 +1153,7 @@ __global__ __launch_bounds__(256) void gemm64r_kernel(Operand A, Operand B, Gemm
     for (int q = 0; q < 4; q++) {
       const int m = m0 + (q >> 1) * 32 + (q & 1) * 16 + (lane >> 2);
       xr[q].zero(); pr[q].zero(); gr[q].zero();
+      if constexpr (G2) g2[q].zero();
       mean[q] = 0.0f; rstd[q] = 0.0f;
       if constexpr (HB > 0) {
 #pragma unroll
@@ -1159,6 +1163,7 @@ __global__ __launch_bounds__(256) void gemm64r_kernel(Operand A, Operand B, Gemm
         xr[q].ld(ln.x + (long long)m * CH + n);
         if (ln.prev) pr[q].ld(ln.prev + (long long)m * CH + n);
         if (ln.gin) gr[q].ld(ln.gin + (long long)m * CH + n);
+        if constexpr (G2) g2[q].ld(ln.gin2 + (long long)m * CH + n);
         mean[q] = ln.stats_in[(long long)m * 2];
         rstd[q] = ln.stats_in[(long long)m * 2 + 1];
       }
@@ -1303,6 +1308,12 @@ __global__ __launch_bounds__(256) void gemm64r_kernel(Operand A, Operand B, Gemm
         const float s1 = row_total(rloc, 0) * (1.0f / CH), s2 = row_total(rloc, 1) * (1.0f / CH);
         float o[8], xv[8];
         gr[q].get(o);
+        if constexpr (G2) {
+          float o2[8];
+          g2[q].get(o2);
+#pragma unroll
+          for (int e = 0; e < 8; e++) o[e] += o2[e];
+        }
         xr[q].get(xv);
 #pragma unroll
         for (int e = 0; e < 8; e++) o[e] += (vals[q][e] - s1 - (xv[e] - mean[q]) * rstd[q] * s2) * rstd[q];
@@ -1365,6 +1376,207 @@ __global__ __launch_bounds__(256) void gemm64r_kernel(Operand A, Operand B, Gemm
   }
 }
 
+// ---------------------------------------------------------------------------
+// The LayerNorm-backward epilogue (MODE 2 of gemm64r_kernel) for 256 channels (the MSA representation): 64 x 256
+// tile, wave w owns all 64 rows of columns [64 w, 64 w + 64) as 2 x 2 MFMA tiles.  The epilogue goes through the two
+// 32-row halves one after the other (rows are independent), so that only one half's values, raw loads and row
+// statistics are live at a time; a lane holds 8 consecutive columns of four rows per half, a row's sums come from
+// eight lanes and four waves.  Without the earlier share of dy, the bias path and the second addend.
+// The forward counterpart (output projection + next LayerNorm on such tiles) was built and measured: the MSA stack
+// alone 9 us faster, the two-stream step 18 us slower (64-row tiles take in 25 % more operand bytes per flop than
+// the 128 x 128 kernel they replace, and the forward GEMMs are the ones that run at its full rate): not kept.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void gemm64w_kernel(Operand A, Operand B, GemmShape sh, RowLn<T> ln) {
+  typedef GemmCfg<T> C;
+  typedef Mma<T> MM;
+  typedef typename Vec16<T>::type V;
+  constexpr int BM = 64, CH = 256;
+  __shared__ __attribute__((aligned(16))) T lds_all[(BM + CH) * C::LDSS];   // 45 KB
+  T* lds_a = lds_all;
+  T* lds_b = lds_all + BM * C::LDSS;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int m0 = blockIdx.x * BM;
+  const T* pa = (const T*)A.ptr;
+  const T* pb = (const T*)B.ptr;
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; i++)
+#pragma unroll
+    for (int j = 0; j < 2; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.0f;
+
+  const int kv = tid & 7;
+  long long aa[2];
+  bool aok[2];
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+    const int m = m0 + (tid >> 3) + 32 * i;
+    aok[i] = m < sh.M;
+    const int mc = aok[i] ? m : 0;
+    aa[i] = (A.x_in >= (1 << 30)) ? (long long)mc * A.x_stride
+                                  : (long long)((unsigned)mc / (unsigned)A.x_in) * A.x_outer +
+                                        (long long)((unsigned)mc % (unsigned)A.x_in) * A.x_stride;
+  }
+  RowAddr<T, true> rowb0, rowb1;
+  rowb0.init(B, 0, sh.N, tid);
+  rowb1.init(B, 128, sh.N, tid);
+  V ra[2], rb0[4], rb1[4];
+  auto load_a = [&](int k0) {
+    const int k = k0 + kv * C::VEC;
+    const long long ka = gemm_kaddr(A, k);
+#pragma unroll
+    for (int i = 0; i < 2; i++) {
+      V v;
+#pragma unroll
+      for (int e = 0; e < C::VEC; e++) v[e] = from_f<T>(0.0f);
+      if (k < sh.K && aok[i]) v = *reinterpret_cast<const V*>(pa + aa[i] + ka);
+      ra[i] = v;
+    }
+  };
+  load_a(0);
+  gemm_load_tile<T, true, true>(rb0, pb, B, rowb0, sh.N, 0, sh.K, tid);
+  gemm_load_tile<T, true, true>(rb1, pb, B, rowb1, sh.N, 0, sh.K, tid);
+  for (int k0 = 0; k0 < sh.K; k0 += C::BK) {
+    __syncthreads();  // previous tile fully consumed
+#pragma unroll
+    for (int i = 0; i < 2; i++) *reinterpret_cast<V*>(lds_a + C::template off<false>((tid >> 3) + 32 * i, kv, 0)) = ra[i];
+    gemm_store_tile<T, true>(rb0, lds_b, tid);
+    gemm_store_tile<T, true>(rb1, lds_b + 128 * C::LDSS, tid);
+    __syncthreads();
+    if (k0 + C::BK < sh.K) {
+      load_a(k0 + C::BK);
+      gemm_load_tile<T, true, true>(rb0, pb, B, rowb0, sh.N, k0 + C::BK, sh.K, tid);
+      gemm_load_tile<T, true, true>(rb1, pb, B, rowb1, sh.N, k0 + C::BK, sh.K, tid);
+    }
+#pragma unroll
+    for (int kk = 0; kk < C::BK / MM::KSTEP; kk++) {
+      const int eo = kk * MM::KSTEP + g * MM::KP;
+      typename MM::frag af[2], bf[2];
+#pragma unroll
+      for (int t = 0; t < 2; t++) {
+        af[t] = MM::load(lds_a + C::template off<false>(t * 32 + l32, eo / C::VEC, eo % C::VEC));
+        bf[t] = MM::load(lds_b + C::template off<false>(wave * 64 + t * 32 + l32, eo / C::VEC, eo % C::VEC));
+      }
+#pragma unroll
+      for (int i = 0; i < 2; i++)
+#pragma unroll
+        for (int j = 0; j < 2; j++) MM::mma(acc[i][j], af[i], bf[j]);
+    }
+  }
+
+  constexpr int WS = 64 + 4;
+  static_assert((4 * 32 * WS + 2 * 4 * 32 * 2) * sizeof(float) <= (BM + CH) * C::LDSS * sizeof(T), "stage tiles and row sums must fit");
+  float* stage = reinterpret_cast<float*>(lds_all) + wave * 32 * WS;
+  float* rowred_all = reinterpret_cast<float*>(lds_all) + 4 * 32 * WS;   // [half][wave][row][2]
+  const int c8 = (lane & 7) * 8, n = wave * 64 + c8;
+  auto oct_sum = [](float v) { v += __shfl_xor(v, 1, 64); v += __shfl_xor(v, 2, 64); v += __shfl_xor(v, 4, 64); return v; };
+  float gm[8];
+#pragma unroll
+  for (int e = 0; e < 8; e++) gm[e] = ln.gamma[n + e];
+  float dgs[8], dbs[8];
+#pragma unroll
+  for (int e = 0; e < 8; e++) { dgs[e] = 0.0f; dbs[e] = 0.0f; }
+  __syncthreads();   // all waves are done with the operand tiles
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+    float* rowred = rowred_all + i * 4 * 32 * 2;
+    auto row_total = [&](int r, int j) {
+      return (rowred[(0 * 32 + r) * 2 + j] + rowred[(1 * 32 + r) * 2 + j]) + (rowred[(2 * 32 + r) * 2 + j] + rowred[(3 * 32 + r) * 2 + j]);
+    };
+    // the half's global loads first, then its accumulators through LDS
+    Raw8<T> xr[4], gr[4];
+    float mean[4], rstd[4];
+#pragma unroll
+    for (int it = 0; it < 4; it++) {
+      const int m = m0 + i * 32 + (lane >> 3) + it * 8;
+      xr[it].zero(); gr[it].zero();
+      mean[it] = 0.0f; rstd[it] = 0.0f;
+      if (m < sh.M) {
+        xr[it].ld(ln.x + (long long)m * CH + n);
+        if (ln.gin) gr[it].ld(ln.gin + (long long)m * CH + n);
+        mean[it] = ln.stats_in[(long long)m * 2];
+        rstd[it] = ln.stats_in[(long long)m * 2 + 1];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 2; j++)
+#pragma unroll
+      for (int a = 0; a < 16; a++) stage[acc_row(g, a) * WS + j * 32 + l32] = acc[i][j][a];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    float vals[4][8];
+#pragma unroll
+    for (int it = 0; it < 4; it++) {
+      const int row = (lane >> 3) + it * 8;
+      f32x4 lo = *reinterpret_cast<const f32x4*>(stage + row * WS + c8);
+      f32x4 hi = *reinterpret_cast<const f32x4*>(stage + row * WS + c8 + 4);
+#pragma unroll
+      for (int e = 0; e < 4; e++) { vals[it][e] = lo[e]; vals[it][4 + e] = hi[e]; }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    {
+#pragma unroll
+      for (int it = 0; it < 4; it++) {
+        const int r = (lane >> 3) + it * 8, m = m0 + i * 32 + r;
+        float s1 = 0.0f, s2 = 0.0f;
+        if (m < sh.M) {
+          float xv[8];
+          xr[it].get(xv);
+#pragma unroll
+          for (int e = 0; e < 8; e++) {
+            const float dv = vals[it][e];
+            const float xh = (xv[e] - mean[it]) * rstd[it];
+            const float dx = dv * gm[e];
+            dgs[e] += dv * xh;
+            dbs[e] += dv;
+            s1 += dx;
+            s2 += dx * xh;
+            vals[it][e] = dx;
+          }
+        }
+        s1 = oct_sum(s1);
+        s2 = oct_sum(s2);
+        if ((lane & 7) == 0) { rowred[(wave * 32 + r) * 2] = s1; rowred[(wave * 32 + r) * 2 + 1] = s2; }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int it = 0; it < 4; it++) {
+        const int r = (lane >> 3) + it * 8, m = m0 + i * 32 + r;
+        if (m < sh.M) {
+          const float s1 = row_total(r, 0) * (1.0f / CH), s2 = row_total(r, 1) * (1.0f / CH);
+          float o[8], xv[8];
+          gr[it].get(o);
+          xr[it].get(xv);
+#pragma unroll
+          for (int e = 0; e < 8; e++) o[e] += (vals[it][e] - s1 - (xv[e] - mean[it]) * rstd[it] * s2) * rstd[it];
+          store8<T>(ln.gout + (long long)m * CH + n, o);
+        }
+      }
+    }
+  }
+  {
+    // column sums over the workgroup's 64 rows: the 8 lanes of a wave with the same columns
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+#pragma unroll
+      for (int o = 8; o < 64; o <<= 1) { dgs[e] += __shfl_xor(dgs[e], o, 64); dbs[e] += __shfl_xor(dbs[e], o, 64); }
+    }
+    if (lane < 8) {
+      float* pp = ln.partial + (long long)blockIdx.x * 2 * CH;
+      store8<float>(pp + n, dgs);
+      store8<float>(pp + CH + n, dbs);
+    }
+  }
+}
+
 // feature mask of the kernel instantiation that the last launch_gemm call of this host thread took (EF_ALL = the
 // general kernel); read by the caller to label the launch with the exact kernel symbol
 static thread_local int g_gemm_last_features = EF_ALL;
@@ -1374,11 +1586,22 @@ static thread_local int g_gemm_last_features = EF_ALL;
 template <typename T, int MODE>
 static inline bool launch_gemm64r(hipStream_t st, const Operand& A, const Operand& B, const GemmShape& sh, const EpiGeneric<T>& epi,
                                   const RowLn<T>& ln) {
-  if (sh.N != 128 || sh.M <= 0 || sh.batch != 1 || sh.k_chunk != 0) return false;
+  if ((sh.N != 128 && sh.N != 256) || sh.M <= 0 || sh.batch != 1 || sh.k_chunk != 0) return false;
   if (A.k_stride != 1 || B.k_stride != 1) return false;
   if (!gemm_operand_ok<T>(A, true, sh.M, sh) || !gemm_operand_ok<T>(B, true, sh.N, sh)) return false;
   auto p16 = [](const void* p) { return ((uintptr_t)p) % 16 == 0; };
   dim3 grid((unsigned)((sh.M + 63) / 64)), block(256);
+  if (sh.N == 256) {   // the 256-channel kernel: LayerNorm backward only, without the options
+    if constexpr (MODE == 1) {
+      return false;
+    } else {
+      if (ln.prev || ln.db || ln.gin2) return false;
+      if (!p16(ln.x) || !p16(ln.gout) || (ln.gin && !p16(ln.gin)) || !p16(ln.partial)) return false;
+      hipLaunchKernelGGL((gemm64w_kernel<T>), grid, block, 0, st, A, B, sh, ln);
+      g_gemm_last_features = 0;
+      return true;
+    }
+  }
   if constexpr (MODE == 1) {
     if (!epi.vec_ok(sh.N) || !p16(ln.y)) return false;
     const int f = epi.features();
@@ -1396,9 +1619,11 @@ static inline bool launch_gemm64r(hipStream_t st, const Operand& A, const Operan
 #undef PE_GEMM64R_SPEC
     return false;
   } else {
-    if (!p16(ln.x) || !p16(ln.gout) || (ln.gin && !p16(ln.gin)) || (ln.prev && !p16(ln.prev)) || !p16(ln.partial)) return false;
+    if (!p16(ln.x) || !p16(ln.gout) || (ln.gin && !p16(ln.gin)) || (ln.gin2 && !p16(ln.gin2)) || (ln.prev && !p16(ln.prev)) || !p16(ln.partial)) return false;
     if (ln.db && (ln.H < 1 || ln.H > 8 || !ln.w_bias || !ln.beta)) return false;
-    if (!ln.db) hipLaunchKernelGGL((gemm64r_kernel<T, 0, 2, 0>), grid, block, 0, st, A, B, sh, epi, ln);
+    if (ln.gin2 && ln.db) return false;   // no instantiation with both
+    if (ln.gin2) hipLaunchKernelGGL((gemm64r_kernel<T, 0, 2, 0, true>), grid, block, 0, st, A, B, sh, epi, ln);
+    else if (!ln.db) hipLaunchKernelGGL((gemm64r_kernel<T, 0, 2, 0>), grid, block, 0, st, A, B, sh, epi, ln);
     else if (ln.H <= 4) hipLaunchKernelGGL((gemm64r_kernel<T, 0, 2, 4>), grid, block, 0, st, A, B, sh, epi, ln);
     else hipLaunchKernelGGL((gemm64r_kernel<T, 0, 2, 8>), grid, block, 0, st, A, B, sh, epi, ln);
     g_gemm_last_features = 0;
@@ -1814,7 +2039,7 @@ static inline bool launch_gemm64(hipStream_t st, const Operand& A, const Operand
     hipLaunchKernelGGL((gemm64_kernel<T, Epi, 0>), grid, block, 0, st, A, B, sh, epi);
     g_gemm_last_features = 0;
     return true;
-  }
+  } else {
 #define PE_GEMM64_SPEC(S)                                                                         \
   if ((f & ~(S)) == 0) {                                                                          \
     hipLaunchKernelGGL((gemm64_kernel<T, Epi, (S)>), grid, block, 0, st, A, B, sh, epi);           \
@@ -1830,6 +2055,7 @@ static inline bool launch_gemm64(hipStream_t st, const Operand& A, const Operand
   PE_GEMM64_SPEC(EF_BIASN | EF_ROWSCALE)
 #undef PE_GEMM64_SPEC
   return false;
+  }
   }
 }
 

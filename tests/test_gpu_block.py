@@ -104,6 +104,23 @@ def test_row_complete_layernorm_epilogues(dtype, r, use_ctx):
         _assert(errs, worst, tol, stats)
 
 
+@pytest.mark.parametrize("variant,use_ctx", [(0, True), (0, False), (2, True)])
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_row_complete_layernorm_epilogues_msa(dtype, variant, use_ctx):
+    """256 MSA channels: the GEMMs that produce the cotangent of a LayerNorm output in the MSA stack and in the outer
+    product mean finish the LayerNorm backward on 64 x 256 tiles.  s * r = 171 rows: two full tiles and a ragged one of
+    43 rows; the Multimer ordering's outer product mean normalises the block's input instead of the stack's output."""
+    dims, table, inp = _case("tiny", dtype=dtype, s=9, r=19, c_m=256, c_z=32, h_msa=8, d_msa=32, h_pair=2, d_pair=16,
+                             c_tri=16, c_opm=8, n_trans=2, variant=variant)
+    table, n = param_table(dims)
+    inp = make_inputs(dims, table, n, ("random_residues", 0.1), 29)
+    errs, worst, tol, stats = check_case(dims, table, inp, use_ctx=use_ctx)
+    if dtype == 1:
+        _assert_small(errs, tol, stats)
+    else:
+        _assert(errs, worst, tol, stats)
+
+
 @pytest.mark.parametrize("use_ctx", [True, False])
 @pytest.mark.parametrize("dtype", [0, 1])
 @pytest.mark.parametrize("variant", [1, 2])
