@@ -710,6 +710,10 @@ template <typename T> struct Runner {
   // fin_add != nullptr (set by the block's backward around the LAST sub-operation of the pair stack): the fused
   // launch writes fin_out = gin + fin_add + (gradient through the LayerNorm) instead of gout and sets fin_done; the
   // stream first waits for fin_from (the stream that produced fin_add).
+  // bias_tiled_r > 0 (set by the attention backward around its call): bias_db is the tiled sum as the reduction over the
+  // batch axis left it (plane = elements per head), not the row-order copy
+  int bias_tiled_r = 0, bias_tiled_transposed = 0;
+  long long bias_tiled_plane = 0;
   const T* fin_add = nullptr;
   T* fin_out = nullptr;
   bool fin_done = false;
@@ -717,7 +721,16 @@ template <typename T> struct Runner {
   hipEvent_t fin_ev = nullptr;
   bool gemm_ln_bwd(hipStream_t st, Arena& ar, const Operand& A, const Operand& B, long long M, int Cc, int K, T* dxh, bool acc,
                    const T* x, const float* stats, long long g_off, long long b_off, const T* gin, T* gout, const char* what,
-                   const float* bias_db = nullptr, long long w_bias_off = 0, int bias_H = 0) {
+                   const float* bias_db = nullptr, long long w_bias_off = 0, int bias_H = 0, bool probe = false) {
+    if (probe) {   // would the fused launch (with the bias path) be taken?  nothing is allocated or launched
+      if (dry || err || Cc != 128 || !bias_db) return false;
+      RowLn<T> ln;
+      memset(&ln, 0, sizeof(ln));
+      ln.gamma = P(g_off); ln.beta = P(b_off); ln.prev = acc ? dxh : nullptr; ln.x = x; ln.stats_in = stats; ln.gin = gin; ln.gout = gout;
+      ln.partial = reinterpret_cast<float*>((uintptr_t)256); ln.db = bias_db; ln.db_ld = M; ln.w_bias = P(w_bias_off); ln.H = bias_H;
+      GemmShape sh{(int)M, Cc, K, 1, 0, 0};
+      return launch_gemm64r<T, 2>(st, A, B, sh, epi_plain<T>(dxh, Cc), ln, false);
+    }
     const long long gridf = (M + 63) / 64;
     const int plen = 2 * Cc + (bias_db ? Cc * bias_H : 0);
     // sized by bias_H whether or not the bias path is taken: the planning pass must not depend on pointer values
@@ -726,7 +739,10 @@ template <typename T> struct Runner {
       RowLn<T> ln;
       memset(&ln, 0, sizeof(ln));
       ln.gamma = P(g_off); ln.prev = acc ? dxh : nullptr; ln.x = x; ln.stats_in = stats; ln.gin = gin; ln.gout = gout; ln.partial = part;
-      if (bias_db) { ln.beta = P(b_off); ln.db = bias_db; ln.db_ld = M; ln.w_bias = P(w_bias_off); ln.H = bias_H; }
+      if (bias_db) {
+        ln.beta = P(b_off); ln.db = bias_db; ln.db_ld = M; ln.w_bias = P(w_bias_off); ln.H = bias_H;
+        if (bias_tiled_r > 0) { ln.db_r = bias_tiled_r; ln.db_transposed = bias_tiled_transposed; ln.db_ld = bias_tiled_plane; }
+      }
       const bool fin = fin_add != nullptr && fin_out != nullptr && ((uintptr_t)fin_add) % 16 == 0 && ((uintptr_t)fin_out) % 16 == 0;
       if (fin) {
         if (fin_ev && fin_from != st &&
@@ -1228,6 +1244,7 @@ template <typename T> struct Runner {
     }
     // triangle attention: the bias is projected from the same LayerNorm output as q / k / v / gate and its gradient
     // goes into the same running gradient, so the two LayerNorm backward passes are one (on the sum of the cotangents)
+    bool bias_gather = false;
     const bool bias_same_ln = c.bias && bias_src == x && bias_ln_g == p.ln_g && bias_ln_b == p.ln_b && bias_gin == g && bias_gout == g &&
                               M == Mz && Cc == d.c_z;
     { ReduceSeg sg[1] = {{0, Cc, p.w_o, Cc}}, cb = {0, Cc, p.b_o, 0};
@@ -1283,17 +1300,26 @@ template <typename T> struct Runner {
         else
           PE_LAUNCH("attn_dbias_reduce", 0, 1.0 * Bds * hll * sizeof(T) + 4.0 * hll, st, attn_dbias_reduce_kernel<T>, dim3((unsigned)((hll + 255) / 256)), dim3(256), 0, dS, dbias,
                     (int)Bds, hll);
-        // dbias is in the chunk order of the query-per-lane bias copy; bring it to pair-row order
-        const int NT = (d.r + 31) / 32;
-        PE_LAUNCH("bias_untile", 0, 8.0 * H * Mz, st, bias_untile_kernel<T>, dim3(NT, NT, H), dim3(256), 0, dbias, dbias_rows, d.r,
-                  gm.bias_transposed);
+        // dbias is in the chunk order of the query-per-lane bias copy; the fused LayerNorm-backward epilogue gathers from
+        // it directly, the kernel of the bias path wants it in pair-row order
+        bias_gather = bias_same_ln && gemm_ln_bwd(st, ar, op_heads_rows(dqkvg, gm, dh, M * dh), op_plain(w.wn_qkvg, 4 * HD), M, Cc, 4 * HD, dxh,
+                                                  false, x, c.stats, p.ln_g, p.ln_b, g, g, "attn dxhat", dbias, p.w_bias, H, true);
+        if (!bias_gather) {
+          const int NT = (d.r + 31) / 32;
+          PE_LAUNCH("bias_untile", 0, 8.0 * H * Mz, st, bias_untile_kernel<T>, dim3(NT, NT, H), dim3(256), 0, dbias, dbias_rows, d.r,
+                    gm.bias_transposed);
+        }
       }
     }
     { ReduceSeg sg[4] = {{0, HD, p.w_q, HD}, {HD, HD, p.w_k, HD}, {2 * HD, HD, p.w_v, HD}, {3 * HD, HD, p.w_g, HD}};
       ReduceSeg cb = {3 * HD, HD, p.b_g, 0};
       gemm_dw(st, ar, op_trans(c.xhat, Cc), false, op_heads_cols(dqkvg, gm, dh, M * dh), false, Cc, 4 * HD, M, 4, sg, "attn dWqkvg", 1, &cb); }
+    if (bias_gather) { bias_tiled_r = d.r; bias_tiled_transposed = gm.bias_transposed; bias_tiled_plane = btile / H; }
     const bool bias_done = gemm_ln_bwd(st, ar, op_heads_rows(dqkvg, gm, dh, M * dh), op_plain(w.wn_qkvg, 4 * HD), M, Cc, 4 * HD, dxh, false, x,
-                                       c.stats, p.ln_g, p.ln_b, g, g, "attn dxhat", bias_same_ln ? dbias_rows : nullptr, p.w_bias, c.bias ? H : 0);
+                                       c.stats, p.ln_g, p.ln_b, g, g, "attn dxhat",
+                                       bias_same_ln ? (bias_gather ? dbias : dbias_rows) : nullptr, p.w_bias, c.bias ? H : 0);
+    bias_tiled_r = 0;
+    if (bias_gather && !bias_done && !err) fail("attn dxhat: the fused launch was announced but not taken");
     next_phase(ar);   // the bias path below adds to the same LayerNorm parameters: a later launch
     if (c.bias && bias_done) end_subop(ar);
     if (c.bias && !bias_done) {

@@ -1040,6 +1040,10 @@ template <typename T> struct RowLn {
   // (triangle attention); its cotangent db[h][row] (fp32, [H][db_ld]) adds sum_h db[h][row] w_bias[c][h] to dy, and
   // the workgroup's partial gets 128 * H more entries: sum over its rows of y[row][c] db[h][row] at 2 * 128 + c * H + h
   const float* db; long long db_ld; const float* w_bias; int H;
+  // db_r > 0: db is not [H][db_ld] in row order but the attention kernels' tiled sum (fp32 values in the query-per-lane
+  // chunk order of T, db_ld elements per head): row m is pair position (q, k) = (m / db_r, m % db_r), or (k, q) when
+  // db_transposed
+  int db_r, db_transposed;
   // MODE 1 with HB > 0: that projection itself, bias_out[h][row] = sum_c y[row][c] w_bias[c][h] (fp32, [H][M]), and a
   // second copy of the row statistics (nullable) where the bias path's backward kernel looks for them
   float* bias_out; float* stats2;
@@ -1157,7 +1161,19 @@ __global__ __launch_bounds__(256) void gemm64r_kernel(Operand A, Operand B, Gemm
       mean[q] = 0.0f; rstd[q] = 0.0f;
       if constexpr (HB > 0) {
 #pragma unroll
-        for (int hh = 0; hh < HB; hh++) dbv[q][hh] = (m < sh.M && hh < ln.H) ? ln.db[(long long)hh * ln.db_ld + m] : 0.0f;
+        for (int hh = 0; hh < HB; hh++) dbv[q][hh] = 0.0f;
+        if (m < sh.M) {
+          long long off = m;
+          if (ln.db_r > 0) {   // gather from the tiled sum: element e of lane (query, g) of key tile kq >> 5 holds key offset 8 (e / 4) + 4 g + e % 4
+            const int a0 = (int)((unsigned)m / (unsigned)ln.db_r), a1 = (int)((unsigned)m % (unsigned)ln.db_r);
+            const int qq = ln.db_transposed ? a1 : a0, kq = ln.db_transposed ? a0 : a1;
+            const int o = kq & 31, gg = (o >> 2) & 1, ee = ((o >> 3) << 2) | (o & 3);
+            off = bias_chunk_off<T>(kq >> 5, ee / BiasChunk<T>::CH, gg, qq, ln.db_r) + ee % BiasChunk<T>::CH;
+          }
+#pragma unroll
+          for (int hh = 0; hh < HB; hh++)
+            if (hh < ln.H) dbv[q][hh] = ln.db[(long long)hh * ln.db_ld + off];
+        }
       }
       if (m < sh.M) {
         xr[q].ld(ln.x + (long long)m * CH + n);
@@ -1585,7 +1601,7 @@ static thread_local int g_gemm_last_features = EF_ALL;
 // epilogue, one of the feature sets below); false: nothing was launched and the caller takes the separate kernels
 template <typename T, int MODE>
 static inline bool launch_gemm64r(hipStream_t st, const Operand& A, const Operand& B, const GemmShape& sh, const EpiGeneric<T>& epi,
-                                  const RowLn<T>& ln) {
+                                  const RowLn<T>& ln, bool launch = true) {
   if ((sh.N != 128 && sh.N != 256) || sh.M <= 0 || sh.batch != 1 || sh.k_chunk != 0) return false;
   if (A.k_stride != 1 || B.k_stride != 1) return false;
   if (!gemm_operand_ok<T>(A, true, sh.M, sh) || !gemm_operand_ok<T>(B, true, sh.N, sh)) return false;
@@ -1597,6 +1613,7 @@ static inline bool launch_gemm64r(hipStream_t st, const Operand& A, const Operan
     } else {
       if (ln.prev || ln.db || ln.gin2) return false;
       if (!p16(ln.x) || !p16(ln.gout) || (ln.gin && !p16(ln.gin)) || !p16(ln.partial)) return false;
+      if (!launch) return true;
       hipLaunchKernelGGL((gemm64w_kernel<T>), grid, block, 0, st, A, B, sh, ln);
       g_gemm_last_features = 0;
       return true;
@@ -1606,6 +1623,7 @@ static inline bool launch_gemm64r(hipStream_t st, const Operand& A, const Operan
     if (!epi.vec_ok(sh.N) || !p16(ln.y)) return false;
     const int f = epi.features();
     if (ln.bias_out && (ln.H < 1 || ln.H > 8 || !ln.w_bias)) return false;
+    if (!launch) return (f & ~(EF_BIASN | EF_AUX | EF_MUL | EF_RES)) == 0;
 #define PE_GEMM64R_SPEC(S)                                                                                             \
     if ((f & ~(S)) == 0) {                                                                                             \
       if (!ln.bias_out) hipLaunchKernelGGL((gemm64r_kernel<T, (S), 1, 0>), grid, block, 0, st, A, B, sh, epi, ln);     \
@@ -1622,6 +1640,7 @@ static inline bool launch_gemm64r(hipStream_t st, const Operand& A, const Operan
     if (!p16(ln.x) || !p16(ln.gout) || (ln.gin && !p16(ln.gin)) || (ln.gin2 && !p16(ln.gin2)) || (ln.prev && !p16(ln.prev)) || !p16(ln.partial)) return false;
     if (ln.db && (ln.H < 1 || ln.H > 8 || !ln.w_bias || !ln.beta)) return false;
     if (ln.gin2 && ln.db) return false;   // no instantiation with both
+    if (!launch) return true;
     if (ln.gin2) hipLaunchKernelGGL((gemm64r_kernel<T, 0, 2, 0, true>), grid, block, 0, st, A, B, sh, epi, ln);
     else if (!ln.db) hipLaunchKernelGGL((gemm64r_kernel<T, 0, 2, 0>), grid, block, 0, st, A, B, sh, epi, ln);
     else if (ln.H <= 4) hipLaunchKernelGGL((gemm64r_kernel<T, 0, 2, 4>), grid, block, 0, st, A, B, sh, epi, ln);

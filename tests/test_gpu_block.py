@@ -87,12 +87,14 @@ def test_triangle_channel_major_layernorm_bf16(c_tri, r):
 
 
 @pytest.mark.parametrize("use_ctx", [True, False])
-@pytest.mark.parametrize("dtype,r", [(0, 19), (1, 19), (1, 40)])
+@pytest.mark.parametrize("dtype,r", [(0, 19), (1, 19), (1, 40), (0, 32), (1, 32)])
 def test_row_complete_layernorm_epilogues(dtype, r, use_ctx):
     """128 pair channels: the pair stack's output projections write the next sub-operation's LayerNorm and its
     cotangent GEMMs finish the LayerNorm backward on their 64 x 128 tiles.  r * r = 361 leaves a ragged last tile of
-    41 rows (and rows beyond the matrix in both 32-row halves); r * r = 1600 is made of full tiles.  With and without
-    a saved ctx (the recomputed forward takes the same kernels)."""
+    41 rows (and rows beyond the matrix in both 32-row halves); r * r = 1600 is made of full tiles; with r = 32 (a
+    multiple of the attention kernels' 32-position tiles) no tile of the bias gradient is padded; the fused backward
+    epilogue gathers that gradient from the tiled sum at every r.  With and without a saved ctx (the recomputed forward
+    takes the same kernels)."""
     dims, table, inp = _case("tiny", dtype=dtype, s=9, r=r, c_m=32, c_z=128, h_msa=2, d_msa=16, h_pair=4, d_pair=32,
                              c_tri=32, c_opm=8, n_trans=2)
     table, n = param_table(dims)
