@@ -106,6 +106,56 @@ def test_row_complete_layernorm_epilogues(dtype, r, use_ctx):
         _assert(errs, worst, tol, stats)
 
 
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_row_complete_layernorm_epilogues_eight_pair_heads(dtype):
+    """The same with eight pair heads: the bias path of the fused epilogues is built for up to four and for up to
+    eight heads."""
+    dims, table, inp = _case("tiny", dtype=dtype, s=6, r=24, c_m=32, c_z=128, h_msa=2, d_msa=16, h_pair=8, d_pair=16,
+                             c_tri=32, c_opm=8, n_trans=2)
+    table, n = param_table(dims)
+    inp = make_inputs(dims, table, n, ("random_residues", 0.1), 31)
+    errs, worst, tol, stats = check_case(dims, table, inp)
+    if dtype == 1:
+        _assert_small(errs, tol, stats)
+    else:
+        _assert(errs, worst, tol, stats)
+
+
+@pytest.mark.parametrize("c_z", [16, 128])
+def test_single_branch_option_matches_the_full_block(c_z):
+    """PE_OPT_BRANCHES: a call that runs one branch only leaves that branch's saved activations and input cotangent as
+    the full block computes them (Section "Parallel Evoformer": the branches are independent inside a block).  fp32;
+    c_z = 128 takes the fused epilogues, whose last launch adds the MSA branch's term only when that branch runs.
+    Pair branch alone: z1..z5 bit-identical to the full block's; d_pair_in = the full block's d_pair_in minus the
+    row-attention-bias term, which the MSA branch alone delivers as its d_pair_in."""
+    import torch
+    import paper_2211_00235_amd as pe
+    from paper_2211_00235_amd.harness import BlockRun
+    dims, table, inp = _case("tiny", dtype=0, s=7, r=24, c_m=32, c_z=c_z, h_msa=2, d_msa=16, h_pair=2, d_pair=16, c_tri=16,
+                             c_opm=8, n_trans=2)
+    table, n = param_table(dims)
+    inp = make_inputs(dims, table, n, ("random_residues", 0.1), 37)
+    runs = {}
+    for br in (3, 2, 1):
+        run = BlockRun(dims, inp)
+        run.h.set_option(1, br)   # PE_OPT_BRANCHES
+        run.d_pair_in.zero_()
+        run.d_msa_in.zero_()
+        run.fwd()
+        run.bwd()
+        run.sync()
+        runs[br] = run
+    full, pair_only, msa_only = runs[3], runs[2], runs[1]
+    for k in ("z1", "z2", "z3", "z4", "z5"):
+        assert np.array_equal(pair_only.ctx_entry(k), full.ctx_entry(k)), k
+    for k in ("m1", "m2", "m3"):
+        assert np.array_equal(msa_only.ctx_entry(k), full.ctx_entry(k)), k
+    assert torch.equal(msa_only.d_msa_in, full.d_msa_in)
+    dz_full = full.d_pair_in.double().cpu().numpy()
+    dz_sum = pair_only.d_pair_in.double().cpu().numpy() + msa_only.d_pair_in.double().cpu().numpy()
+    assert np.max(np.abs(dz_full - dz_sum)) <= 2e-6 * np.max(np.abs(dz_full))
+
+
 @pytest.mark.parametrize("variant,use_ctx", [(0, True), (0, False), (2, True)])
 @pytest.mark.parametrize("dtype", [0, 1])
 def test_row_complete_layernorm_epilogues_msa(dtype, variant, use_ctx):
