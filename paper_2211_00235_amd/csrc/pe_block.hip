@@ -231,7 +231,7 @@ template <typename T> struct PrepCarver {
     list->t.push_back(p);
   }
   void addf(float* dst, long long src, int n) {
-    PrepDesc p; p.src_off = src; p.dst_off = dst - fbase; p.rows = 1; p.cols = n; p.ld_r = 0; p.ld_c = 1; p.scale = 1.0f;
+    PrepDesc p; p.src_off = src; p.dst_off = dst - fbase; p.rows = 1; p.cols = n; p.ld_r = -1; p.ld_c = 1; p.scale = 1.0f;
     p.c_blk = 0; p.c_blk_to = 0;
     list->f.push_back(p);
   }
@@ -426,27 +426,24 @@ template <typename T> struct Runner {
     }
     return (off + 255) & ~(size_t)255;
   }
-  void run_prep_list(hipStream_t st, const std::vector<PrepDesc>& v, bool is_f, T* tbase, float* fbase) {
+  // one launch per PREP_MAX descriptors; the storage-type copies and the fp32 copies of a branch go together
+  void run_prep_list(hipStream_t st, const std::vector<PrepDesc>& vt, const std::vector<PrepDesc>& vf, T* tbase, float* fbase) {
+    std::vector<PrepDesc> v(vt);
+    v.insert(v.end(), vf.begin(), vf.end());
     for (size_t i = 0; i < v.size(); i += PREP_MAX) {
       PrepBatch pb;
       pb.n = (int)std::min((size_t)PREP_MAX, v.size() - i);
       for (int k = 0; k < pb.n; k++) pb.d[k] = v[i + k];
       dim3 grid(64, pb.n);
       double bytes = 0;
-      for (int k = 0; k < pb.n; k++) bytes += (double)pb.d[k].rows * pb.d[k].cols * (4 + (is_f ? 4 : sizeof(T)));
-      if (is_f) PE_LAUNCH("prep_params", 0, bytes, st, prep_params_kernel<float>, grid, dim3(256), 0, params, fbase, pb);
-      else PE_LAUNCH("prep_params", 0, bytes, st, prep_params_kernel<T>, grid, dim3(256), 0, params, tbase, pb);
+      for (int k = 0; k < pb.n; k++) bytes += (double)pb.d[k].rows * pb.d[k].cols * (4 + (pb.d[k].ld_r < 0 ? 4 : sizeof(T)));
+      PE_LAUNCH("prep_params", 0, bytes, st, prep_params_kernel<T>, grid, dim3(256), 0, params, tbase, fbase, pb);
     }
   }
   void run_prep(bool msa_side) {
     if (dry) return;
-    if (msa_side) {
-      run_prep_list(sm, prep_msa.t, false, prep_tbase_m, prep_fbase_m);
-      run_prep_list(sm, prep_msa.f, true, prep_tbase_m, prep_fbase_m);
-    } else {
-      run_prep_list(sp, prep_pair.t, false, prep_tbase_p, prep_fbase_p);
-      run_prep_list(sp, prep_pair.f, true, prep_tbase_p, prep_fbase_p);
-    }
+    if (msa_side) run_prep_list(sm, prep_msa.t, prep_msa.f, prep_tbase_m, prep_fbase_m);
+    else run_prep_list(sp, prep_pair.t, prep_pair.f, prep_tbase_p, prep_fbase_p);
   }
 
   // ---- kernel wrappers -----------------------------------------------------

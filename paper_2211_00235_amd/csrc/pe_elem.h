@@ -1225,15 +1225,20 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceBatch rb) {
 // ---------------------------------------------------------------------------
 // copy = scale * source; c_blk > 0: column c of the source goes to destination column (c / c_blk) * c_blk_to + c % c_blk
 // (blocks of c_blk columns spread c_blk_to apart: the interleaved projection / gate rows of the triangle multiplication)
+// ld_r < 0: a plain fp32 copy of `cols` values into the fp32 region (dst_off counts floats there) instead of the storage-type region
 struct PrepDesc { long long src_off, dst_off; int rows, cols; long long ld_r, ld_c; float scale; int c_blk, c_blk_to; };
 constexpr int PREP_MAX = 64;   // descriptors per launch (3 KB of kernel arguments)
 struct PrepBatch { PrepDesc d[PREP_MAX]; int n; };
 template <typename T>
-__global__ __launch_bounds__(256) void prep_params_kernel(const float* params, T* dst, PrepBatch pb) {
+__global__ __launch_bounds__(256) void prep_params_kernel(const float* params, T* dst, float* fdst, PrepBatch pb) {
   // 32 x 32 tiles; a transposed destination (ld_r == 1) goes through LDS so that reads and
   // writes both run along the contiguous index
   __shared__ float tile[32][33];
   const PrepDesc& d = pb.d[blockIdx.y];
+  if (d.ld_r < 0) {   // fp32 copy (biases that a GEMM epilogue reads as one vector)
+    for (int c = blockIdx.x * 256 + threadIdx.x; c < d.cols; c += gridDim.x * 256) fdst[d.dst_off + c] = params[d.src_off + c];
+    return;
+  }
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
   const int ntr = (d.rows + 31) / 32, ntc = (d.cols + 31) / 32;
   const bool transposed = d.ld_r == 1 && d.ld_c != 1;
