@@ -900,7 +900,7 @@ __global__ __launch_bounds__(256) void attn_dbias_reduce8_kernel(const T* dS, fl
 #pragma unroll
       for (int u = 0; u < 8; u++) {
         const int bb = b + 4 * u;
-        if (bb < B) ld8<T>(dS + (long long)bb * hll + idx, v[u]);
+        if (bb < B) ld8_once<T>(dS + (long long)bb * hll + idx, v[u]);
         else {
 #pragma unroll
           for (int e = 0; e < 8; e++) v[u][e] = 0.0f;

@@ -173,6 +173,15 @@ template <> PE_DEV void ld8<bf16>(const bf16* p, float (&v)[8]) {
 #pragma unroll
   for (int e = 0; e < 8; e++) v[e] = (float)t[e];
 }
+// the same for data that is read once (the inputs of the reductions over splits and over the batch axis):
+// non-temporal, the lines are not kept in L2 for a second reader that never comes
+template <typename T> PE_DEV void ld8_once(const T* p, float (&v)[8]) { ld8<T>(p, v); }
+template <> PE_DEV void ld8_once<bf16>(const bf16* p, float (&v)[8]) {
+  bf16x8 t = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(p));
+#pragma unroll
+  for (int e = 0; e < 8; e++) v[e] = (float)t[e];
+}
+PE_DEV f32x4 ld4f_once(const float* p) { return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p)); }
 template <typename T> PE_DEV void st8(T* p, const float (&v)[8]) {
   float a[4] = {v[0], v[1], v[2], v[3]}, b[4] = {v[4], v[5], v[6], v[7]};
   store4<T>(p, a);
@@ -1172,7 +1181,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceBatch rb) {
 #pragma unroll
         for (int u = 0; u < 8; u++) {
           int kk = k + u * Y;
-          if (kk < a.nsplit) v[u] = *reinterpret_cast<const f32x4*>(a.part + (long long)kk * a.stride + idx);
+          if (kk < a.nsplit) v[u] = ld4f_once(a.part + (long long)kk * a.stride + idx);
           else v[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
         }
 #pragma unroll
@@ -1183,7 +1192,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceBatch rb) {
 #pragma unroll
         for (int u = 0; u < 4; u++) {
           int kk = k + u * Y;
-          if (kk < a.nsplit) v[u] = *reinterpret_cast<const f32x4*>(a.part + (long long)kk * a.stride + idx);
+          if (kk < a.nsplit) v[u] = ld4f_once(a.part + (long long)kk * a.stride + idx);
           else v[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
         }
 #pragma unroll

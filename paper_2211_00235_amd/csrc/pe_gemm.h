@@ -1664,6 +1664,9 @@ static inline bool launch_gemm64r(hipStream_t st, const Operand& A, const Operan
 // tiles in LDS and its own register prefetch, which doubles the bytes in flight per CU without a
 // second set of partials; the groups' accumulators are added through LDS at the end.
 // ---------------------------------------------------------------------------
+// partial sums are read back by the deferred reduction at the end of the backward pass, long after the L2 has
+// turned over: written non-temporally, they do not displace the lines the neighbouring kernels share
+PE_DEV void dw_store_partial(float* p, f32x2 v) { __builtin_nontemporal_store(v, reinterpret_cast<f32x2*>(p)); }
 struct XAddr {   // per-thread x part of the tile addressing: 8 consecutive x, 4 consecutive k per tile
   long long a; bool ok;
   PE_DEV void init(const Operand& op, int x0, int X, int xb) {
@@ -1846,7 +1849,7 @@ __global__ __launch_bounds__(256 * KG) void gemm_dwx_kernel(Operand A, Operand B
       const int rloc = wm * 64 + 2 * acc_row(g, a) + i;
       const int m = m0 + rloc;
       f32x2 v; v[0] = acc[i][0][a]; v[1] = acc[i][1][a];
-      if (m < sh.M && n < sh.N) *reinterpret_cast<f32x2*>(epi.out + (long long)b * epi.mn + (long long)m * epi.ldn + n) = v;
+      if (m < sh.M && n < sh.N) dw_store_partial(epi.out + (long long)b * epi.mn + (long long)m * epi.ldn + n, v);
     }
 }
 
@@ -2005,7 +2008,7 @@ __global__ __launch_bounds__(256) void gemm_dwp_kernel(Operand A, Operand B, Gem
     for (int a = 0; a < 16; a++) {
       const int m = m0 + wm * 64 + 2 * acc_row(g, a) + i;
       f32x2 v; v[0] = acc[i][0][a]; v[1] = acc[i][1][a];
-      *reinterpret_cast<f32x2*>(epi.out + (long long)b * epi.mn + (long long)m * epi.ldn + n) = v;
+      dw_store_partial(epi.out + (long long)b * epi.mn + (long long)m * epi.ldn + n, v);
     }
 }
 
