@@ -277,7 +277,10 @@ template <> PE_DEV void attn_store_tile16<bf16>(bf16* plane, int L, int tile, in
     float t[8];
 #pragma unroll
     for (int r = 0; r < 8; r++) t[r] = v[c * 8 + r];
-    st8<bf16>(plane + bias_chunk_off<bf16>(tile, c, g, col, L), t);
+    bf16x8 o;   // non-temporal: read once, by the reduction over the batch axis
+#pragma unroll
+    for (int r = 0; r < 8; r++) o[r] = (bf16)t[r];
+    __builtin_nontemporal_store(o, reinterpret_cast<bf16x8*>(plane + bias_chunk_off<bf16>(tile, c, g, col, L)));
   }
 }
 // number of 32-position tiles of an axis of length L
