@@ -57,6 +57,25 @@ def build_attn_bench(out=None, verbose=False):
     return out
 
 
+def build_mem_probe(out=None, verbose=False):
+    """Stand-alone read-bandwidth probe (csrc/bench/mem_probe.hip); returns its path."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = out or os.path.join(HERE, "mem_probe")
+    flags = [f for f in FLAGS if f not in ("-shared", "-fPIC")]
+    cmd = [hipcc] + flags + [os.path.join(CSRC, "bench", "mem_probe.hip"), "-o", out]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if verbose or res.returncode:
+        print("\n".join(l for l in (res.stdout + res.stderr).splitlines() if "packed-fp32-ops" not in l))
+    if res.returncode:
+        raise RuntimeError("hipcc failed building %s" % out)
+    return out
+
+
 if __name__ == "__main__":
     import sys
-    print(build_attn_bench(verbose=True) if "attn_bench" in sys.argv[1:] else build(verbose=True))
+    if "attn_bench" in sys.argv[1:]:
+        print(build_attn_bench(verbose=True))
+    elif "mem_probe" in sys.argv[1:]:
+        print(build_mem_probe(verbose=True))
+    else:
+        print(build(verbose=True))
