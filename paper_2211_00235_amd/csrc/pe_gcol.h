@@ -265,38 +265,49 @@ __global__ __launch_bounds__(256) void gcol_gate_fwd8_kernel(GcolArgs a) {
 // grid (r, chunks) writes the chunk sums to part, gcol_sum_chunks_kernel adds them in order.
 template <typename T>
 __global__ __launch_bounds__(256) void gcol_gate_bwd_kernel(GcolArgs a) {
-  __shared__ float red[256];
+  // a thread owns 8 consecutive (head, channel) columns (16-byte accesses in the storage type; H*d is a multiple of 8)
+  // of up to four sequence positions of the chunk; TPP threads cover a position, SL sequence lanes a workgroup
+  __shared__ float red[256][8];
   const int i = blockIdx.x, ch = blockIdx.y, HD = a.H * a.d, Wg = 2 * HD + 2 * a.d;
-  const int SL = 256 / HD, hd = threadIdx.x % HD, sl = threadIdx.x / HD;
-  const float ov = a.o[(long long)i * HD + hd];
-  float acc = 0.0f;
-  if (sl < SL) {
-    const int t0 = ch * (GC_UR * SL) + sl;
-    float gv[GC_UR], dv[GC_UR];   // loads of GC_UR sequence positions first, then the arithmetic
+  const int TPP = HD / 8, SL = 256 / TPP, hd0 = ((int)threadIdx.x % TPP) * 8, sl = threadIdx.x / TPP;
+  const int len = 32 * (256 / HD), tbeg = ch * len, tend = min(a.s, tbeg + len);   // the chunk of gc_chunk_len(HD) positions
+  float acc[8];
 #pragma unroll
-    for (int u = 0; u < GC_UR; u++) {
-      const int t = t0 + u * SL;
-      const bool ok = t < a.s;
-      const long long pos = (long long)(ok ? t : 0) * a.r + i;
-      gv[u] = to_f(((const T*)a.proj)[pos * Wg + HD + 2 * a.d + hd]);
-      dv[u] = ok ? to_f(((const T*)a.dog)[pos * HD + hd]) : 0.0f;
+  for (int e = 0; e < 8; e++) acc[e] = 0.0f;
+  if (sl < SL) {
+    float ov[8], gv[4][8], dv[4][8];
+    ld8<float>(a.o + (long long)i * HD + hd0, ov);
+#pragma unroll
+    for (int u = 0; u < 4; u++) {   // all loads first (4 SL >= len for every H*d), then the arithmetic
+      const int t = tbeg + sl + u * SL;
+      const long long pos = (long long)(t < tend ? t : tbeg) * a.r + i;
+      ld8<T>((const T*)a.proj + pos * Wg + HD + 2 * a.d + hd0, gv[u]);
+      ld8<T>((const T*)a.dog + pos * HD + hd0, dv[u]);
     }
 #pragma unroll
-    for (int u = 0; u < GC_UR; u++) {
-      const int t = t0 + u * SL;
-      if (t < a.s) {
+    for (int u = 0; u < 4; u++) {
+      const int t = tbeg + sl + u * SL;
+      if (t < tend) {
         const long long pos = (long long)t * a.r + i;
-        float sg = sigmoidf_(gv[u]);
-        acc += dv[u] * sg;
-        ((T*)a.dproj)[pos * Wg + HD + 2 * a.d + hd] = from_f<T>(dv[u] * ov * sg * (1.0f - sg));
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+          const float sg = sigmoidf_(gv[u][e]);
+          acc[e] += dv[u][e] * sg;
+          o[e] = dv[u][e] * ov[e] * sg * (1.0f - sg);
+        }
+        st8<T>((T*)a.dproj + pos * Wg + HD + 2 * a.d + hd0, o);
       }
     }
   }
-  red[threadIdx.x] = acc;
+#pragma unroll
+  for (int e = 0; e < 8; e++) red[threadIdx.x][e] = acc[e];
   __syncthreads();
   if (sl == 0) {
-    for (int k = 1; k < SL; k++) acc += red[k * HD + hd];
-    a.part[((long long)ch * a.r + i) * HD + hd] = acc;
+    for (int k = 1; k < SL; k++)
+#pragma unroll
+      for (int e = 0; e < 8; e++) acc[e] += red[k * TPP + (int)threadIdx.x][e];
+    st8<float>(a.part + ((long long)ch * a.r + i) * HD + hd0, acc);
   }
 }
 // out[idx] = sum_c part[c][idx], idx < n;  grid = ceil(n / 256)
