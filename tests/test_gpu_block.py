@@ -422,6 +422,20 @@ def test_global_column_attention_small(dtype):
         _assert(errs, worst, tol, stats)
 
 
+@pytest.mark.parametrize("h_msa,s,r,dtype", [(3, 700, 20, 0), (8, 300, 24, 0), (1, 1100, 12, 0), (5, 333, 16, 1)])
+def test_global_column_attention_head_counts_and_sequence_chunks(h_msa, s, r, dtype):
+    """Global column attention with head counts that do not divide a workgroup's threads (idle sequence lanes in the
+    reductions over s) and sequence lengths of several chunks with a ragged last one."""
+    dims, table, inp = _case("tiny", dtype=dtype, s=s, r=r, c_m=32, h_msa=h_msa, d_msa=8, col_global=1)
+    table, n = param_table(dims)
+    inp = make_inputs(dims, table, n, ("random_rows", 0.1), 37 + h_msa)
+    errs, worst, tol, stats = check_case(dims, table, inp)
+    if dtype == 1:
+        _assert_small(errs, tol, stats)
+    else:
+        _assert(errs, worst, tol, stats)
+
+
 @pytest.mark.slow
 def test_extra_msa_bf16():
     """Config 3: extra-MSA-stack block (s=1024, r=256, c_m=64, global column attention), bf16."""
