@@ -951,7 +951,8 @@ __global__ __launch_bounds__(256) void gemm64_kernel(Operand A, Operand B, GemmS
       V v;
 #pragma unroll
       for (int e = 0; e < C::VEC; e++) v[e] = from_f<T>(0.0f);
-      if (k < sh.K && aok[i]) v = *reinterpret_cast<const V*>(pa + aa[i] + ka);
+      // the tile spans every output column, so these rows have no second reader: non-temporal
+      if (k < sh.K && aok[i]) v = __builtin_nontemporal_load(reinterpret_cast<const V*>(pa + aa[i] + ka));
       ra[i] = v;
     }
   };
@@ -1102,7 +1103,8 @@ __global__ __launch_bounds__(256) void gemm64r_kernel(Operand A, Operand B, Gemm
       V v;
 #pragma unroll
       for (int e = 0; e < C::VEC; e++) v[e] = from_f<T>(0.0f);
-      if (k < sh.K && aok[i]) v = *reinterpret_cast<const V*>(pa + aa[i] + ka);
+      // the tile spans every output column, so these rows have no second reader: non-temporal
+      if (k < sh.K && aok[i]) v = __builtin_nontemporal_load(reinterpret_cast<const V*>(pa + aa[i] + ka));
       ra[i] = v;
     }
   };
@@ -1449,7 +1451,8 @@ __global__ __launch_bounds__(256) void gemm64w_kernel(Operand A, Operand B, Gemm
       V v;
 #pragma unroll
       for (int e = 0; e < C::VEC; e++) v[e] = from_f<T>(0.0f);
-      if (k < sh.K && aok[i]) v = *reinterpret_cast<const V*>(pa + aa[i] + ka);
+      // the tile spans every output column, so these rows have no second reader: non-temporal
+      if (k < sh.K && aok[i]) v = __builtin_nontemporal_load(reinterpret_cast<const V*>(pa + aa[i] + ka));
       ra[i] = v;
     }
   };
