@@ -1103,8 +1103,7 @@ __global__ __launch_bounds__(256) void gemm64r_kernel(Operand A, Operand B, Gemm
       V v;
 #pragma unroll
       for (int e = 0; e < C::VEC; e++) v[e] = from_f<T>(0.0f);
-      // the tile spans every output column, so these rows have no second reader: non-temporal
-      if (k < sh.K && aok[i]) v = __builtin_nontemporal_load(reinterpret_cast<const V*>(pa + aa[i] + ka));
+      if (k < sh.K && aok[i]) v = *reinterpret_cast<const V*>(pa + aa[i] + ka);
       ra[i] = v;
     }
   };
@@ -1451,8 +1450,7 @@ __global__ __launch_bounds__(256) void gemm64w_kernel(Operand A, Operand B, Gemm
       V v;
 #pragma unroll
       for (int e = 0; e < C::VEC; e++) v[e] = from_f<T>(0.0f);
-      // the tile spans every output column, so these rows have no second reader: non-temporal
-      if (k < sh.K && aok[i]) v = __builtin_nontemporal_load(reinterpret_cast<const V*>(pa + aa[i] + ka));
+      if (k < sh.K && aok[i]) v = *reinterpret_cast<const V*>(pa + aa[i] + ka);
       ra[i] = v;
     }
   };
