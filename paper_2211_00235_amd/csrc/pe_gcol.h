@@ -11,7 +11,6 @@
 #include "pe_elem.h"
 
 constexpr int GC_MAXH = 8, GC_MAXD = 8;
-constexpr int GC_UR = 32;   // sequence positions in flight per thread in the latency-bound reductions over s
 
 struct GcolArgs {
   const void* proj; void* dproj;    // [s][r][Wg] storage type
@@ -30,7 +29,7 @@ struct GcolArgs {
   float* partm;                     // [chunks][r] partial mask sums (qmean)
   int chunks;                       // sequence chunks of gc_chunk_len(H*d) positions
 };
-// sequence positions per workgroup of the two reductions over s: one batch of GC_UR loads per sequence lane
+// sequence positions per workgroup of the two reductions over s (up to four per sequence lane, 16-byte loads)
 static inline int gc_chunk_len(int HD) { return 32 * (256 / HD); }
 
 // d (<= 8) consecutive channels of one (sequence, residue) row -> float[8] (zero beyond d)
@@ -55,37 +54,53 @@ PE_DEV float block_reduce_max(float v, float* red) {
   return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 
-// qbar[i][hd] = sum_s mask[s][i] q[s][i][hd] / den[i], in two stages: grid (r, chunks), block = 256 = HD x (256/HD)
-// sequence lanes; a workgroup sums one chunk of gc_chunk_len(HD) sequence positions of one residue (GC_UR independent
-// loads in flight per thread) into part / partm, gcol_qmean_fin_kernel adds the chunks in order.  (One workgroup per
-// residue walking the whole sequence axis ran at 0.2 TB/s: 256 workgroups, each a chain of dependent load rounds.)
+// qbar[i][hd] = sum_s mask[s][i] q[s][i][hd] / den[i], in two stages: grid (r, chunks), block = 256 = (HD / 8) column
+// groups x sequence lanes; a workgroup sums one chunk of gc_chunk_len(HD) sequence positions of one residue (up to four
+// independent 16-byte loads in flight per thread) into part / partm, gcol_qmean_fin_kernel adds the chunks in order.
+// (One workgroup per residue walking the whole sequence axis ran at 0.2 TB/s: 256 workgroups, each a chain of
+// dependent load rounds; 2-byte loads, one column per thread, at 0.8 TB/s.)
 template <typename T>
 __global__ __launch_bounds__(256) void gcol_qmean_kernel(GcolArgs a) {
-  __shared__ float red[256], redm[256];
+  // a thread owns 8 consecutive (head, channel) columns (one 16-byte load in the storage type) of up to four sequence
+  // positions of the chunk; TPP threads cover a position, SL sequence lanes a workgroup
+  __shared__ float red[256][8], redm[256];
   const int i = blockIdx.x, ch = blockIdx.y, HD = a.H * a.d, Wg = 2 * HD + 2 * a.d;
-  const int SL = 256 / HD, hd = threadIdx.x % HD, sl = threadIdx.x / HD;
-  const T* q = (const T*)a.proj + (long long)i * Wg + hd;
-  float acc = 0.0f, msum = 0.0f;
-  if (sl < SL) {
-    const int t0 = ch * (GC_UR * SL) + sl;
-    float mk[GC_UR], qv[GC_UR];
+  const int TPP = HD / 8, SL = 256 / TPP, hd0 = ((int)threadIdx.x % TPP) * 8, sl = threadIdx.x / TPP;
+  const int len = 32 * (256 / HD), tbeg = ch * len, tend = min(a.s, tbeg + len);   // the chunk of gc_chunk_len(HD) positions
+  float acc[8], msum = 0.0f;
 #pragma unroll
-    for (int u = 0; u < GC_UR; u++) {
-      const int t = t0 + u * SL;
-      const bool ok = t < a.s;
-      mk[u] = ok ? a.mask[(long long)t * a.r + i] : 0.0f;
-      qv[u] = ok ? to_f(q[(long long)t * a.r * Wg]) : 0.0f;
+  for (int e = 0; e < 8; e++) acc[e] = 0.0f;
+  if (sl < SL) {
+    float mk[4], qv[4][8];
+#pragma unroll
+    for (int u = 0; u < 4; u++) {   // all loads first (4 SL >= len for every H*d), then the arithmetic
+      const int t = tbeg + sl + u * SL;
+      const bool ok = t < tend;
+      const long long pos = (long long)(ok ? t : tbeg) * a.r + i;
+      mk[u] = ok ? a.mask[pos] : 0.0f;
+      ld8<T>((const T*)a.proj + pos * Wg + hd0, qv[u]);
     }
 #pragma unroll
-    for (int u = 0; u < GC_UR; u++) { acc += mk[u] * qv[u]; msum += mk[u]; }
+    for (int u = 0; u < 4; u++) {
+      if (tbeg + sl + u * SL < tend) {
+#pragma unroll
+        for (int e = 0; e < 8; e++) acc[e] += mk[u] * qv[u][e];
+        msum += mk[u];
+      }
+    }
   }
-  red[threadIdx.x] = acc;
+#pragma unroll
+  for (int e = 0; e < 8; e++) red[threadIdx.x][e] = acc[e];
   redm[threadIdx.x] = msum;
   __syncthreads();
   if (sl == 0) {
-    for (int k = 1; k < SL; k++) { acc += red[k * HD + hd]; msum += redm[k * HD + hd]; }
-    a.part[((long long)ch * a.r + i) * HD + hd] = acc;
-    if (hd == 0) a.partm[(long long)ch * a.r + i] = msum;
+    for (int k = 1; k < SL; k++) {
+#pragma unroll
+      for (int e = 0; e < 8; e++) acc[e] += red[k * TPP + (int)threadIdx.x][e];
+      msum += redm[k * TPP + (int)threadIdx.x];
+    }
+    st8<float>(a.part + ((long long)ch * a.r + i) * HD + hd0, acc);
+    if (hd0 == 0) a.partm[(long long)ch * a.r + i] = msum;
   }
 }
 // grid = ceil(r * HD / 256)
